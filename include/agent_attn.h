@@ -1,0 +1,128 @@
+/*
+ * agent_attn.h -- C ABI of the MI355X (gfx950) agent-attention forward library.
+ *
+ * The operator (arXiv 2312.08874, "Agent Attention"), per (batch, head) unit with
+ * N tokens of width d on a grid_h x grid_w grid and n agent tokens on an
+ * agent_h x agent_w grid:
+ *
+ *   A   = Pooling(Q)                                   Sec. 4.2 (default agent source)
+ *   V_A = softmax(scale1 * A K^T + B1) V   over N      Sec. 4.1 Eq. (3) "agent aggregation", Eq. (5)
+ *   O   = softmax(scale2 * Q A^T + B2) V_A over n      Sec. 4.1 Eq. (3) "agent broadcast",  Eq. (5)
+ *   O  += DWC(V)                                       Sec. 4.2 Eq. (6), 3x3 depthwise convolution (k = 3, Eq. (7))
+ *   O  += v_residual_k * V                             Appendix C.1 (Stable-Diffusion variant)
+ *
+ * scale defaults to d^-1/2 (Sec. 3.2).  B1 [n,N] and B2 [N,n] are never passed
+ * dense: they are evaluated inside the kernels from the three components of
+ * Appendix B (column, row and block bias; the block bias is resized bilinearly
+ * with half-pixel centres from blk_h0 x blk_w0 to the token grid).
+ *
+ * General conventions
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller; the library
+ *    never allocates or frees device memory.  Descriptor / parameter structs are
+ *    HOST memory, read during the call only.
+ *  - Tensors are dense row-major.  Q, K, V, out: [batch, heads, N, d]; A:
+ *    [batch, heads, n, d]; token t = y*grid_w + x; agent a = ay*agent_w + ax.
+ *    Element type is desc->dtype (fp32, fp16 or bf16); all accumulation is fp32;
+ *    `out` is rounded once to nearest-even.
+ *  - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *    the null stream) and return without synchronising.  Work of one call is
+ *    ordered after earlier work on that stream.
+ *  - Errors are return codes.  On any error nothing has been launched.
+ *  - Two calls may run concurrently only with distinct workspaces and outputs.
+ *  - Results are deterministic: same inputs, same bits.
+ */
+#ifndef AGENT_ATTN_H
+#define AGENT_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { AA_F32 = 0, AA_F16 = 1, AA_BF16 = 2 } aa_dtype;
+
+typedef enum {
+  AA_OK = 0,
+  AA_ERR_NULL = -1,        /* a required pointer is NULL */
+  AA_ERR_SHAPE = -2,       /* non-positive or inconsistent sizes (N != grid_h*grid_w, ...) */
+  AA_ERR_DTYPE = -3,       /* dtype is not one of aa_dtype */
+  AA_ERR_POOL = -4,        /* A == NULL but the token/agent grids do not define a pooling */
+  AA_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned (256 B) or smaller than the query says */
+  AA_ERR_ALIAS = -6,       /* out overlaps an input */
+  AA_ERR_UNSUPPORTED = -7, /* valid problem outside the implemented range (d > 256, strides, ...) */
+  AA_ERR_HIP = -8          /* a HIP runtime call failed */
+} aa_status;
+
+/* Problem descriptor (host memory).  Sizes in elements. */
+typedef struct {
+  int32_t batch, heads;
+  int32_t N, n, d;
+  int32_t grid_h, grid_w;   /* N == grid_h*grid_w.  Needed for pooling, bias and DWC; with none of
+                               them in use both may be 0 (tokens are then an unstructured list). */
+  int32_t agent_h, agent_w; /* n == agent_h*agent_w.  Needed for pooling; else both may be 0. */
+  int32_t dtype;            /* aa_dtype of Q, K, V, A and out */
+  float scale1, scale2;     /* <= 0 selects d^-1/2 (Sec. 3.2).  scale2 is separate because the
+                               Stable-Diffusion variant enlarges it (Appendix C.1). */
+  float v_residual_k;       /* 0 = off; O += k*V (Appendix C.1) */
+  int32_t n_splits;         /* number of N-splits of the aggregation; 0 = library chooses */
+  int64_t stride_b, stride_h, stride_n; /* element strides of Q/K/V/out; 0 = dense [B,H,N,d].
+                                           Only dense layouts are implemented. */
+} aa_desc;
+
+/* Module-mode parameters (host struct of device pointers, fp32).  A NULL pointer
+ * switches that term off; a NULL aa_params* switches all of them off.
+ * Parameters are per head and shared across the batch.
+ *   B1[a, y*w+x] = b1_col[a,x] + b1_row[a,y] + resize(b1_blk[a,:,:])[y,x]     Appendix B
+ *   B2[y*w+x, a] = b2_col[x,a] + b2_row[y,a] + resize(b2_blk[:,:,a])[y,x]     (mirror image)
+ *   DWC: out[y,x,c] = dwc_b[c] + sum_{u,v in -1..1} dwc_w[c,u+1,v+1] * V[y+u,x+v,c], zero padded */
+typedef struct {
+  const float *b1_col, *b1_row, *b1_blk; /* [H,n,w], [H,n,h], [H,n,h0,w0] */
+  const float *b2_col, *b2_row, *b2_blk; /* [H,w,n], [H,h,n], [H,h0,w0,n] */
+  int32_t blk_h0, blk_w0;
+  const float *dwc_w, *dwc_b;            /* [H,d,3,3], [H,d]; dwc_b may be NULL with dwc_w set */
+} aa_params;
+
+/* Bytes of device workspace agent_attn_fwd / agent_aggregate_fwd need for this
+ * problem (holds A when it is pooled, the split partials (m, l, acc), V_A and a
+ * few counters).  Returns 0 when the descriptor is invalid. */
+size_t agent_attn_workspace_bytes(const aa_desc *desc, const aa_params *params);
+
+/* Whole forward pass, Eq. (3)/(5)/(6).  A == NULL: agents are pooled from Q
+ * (needs both grids).  A != NULL: agents are taken as given (learned or
+ * externally produced agents, Sec. 4.1).  workspace: device, 256-byte aligned,
+ * at least agent_attn_workspace_bytes(); its contents on entry are irrelevant
+ * and on exit unspecified. */
+aa_status agent_attn_fwd(const aa_desc *desc, const void *Q, const void *K, const void *V,
+                         const void *A, const aa_params *params, void *workspace,
+                         size_t workspace_bytes, void *out, void *hip_stream);
+
+/* A = Pooling(Q), Sec. 4.2: average over the window
+ * [floor(i*L/La), ceil((i+1)*L/La)) per axis.  A_out [batch, heads, n, d], desc->dtype. */
+aa_status agent_pool_fwd(const aa_desc *desc, const void *Q, void *A_out, void *hip_stream);
+
+/* Agent aggregation V_A = Attn^S(A, K, V) with bias B1 (Eq. (3), (5)), including the
+ * split-N partial pass and its log-sum-exp merge.  VA_out [batch, heads, n, d] fp32. */
+aa_status agent_aggregate_fwd(const aa_desc *desc, const void *A, const void *K, const void *V,
+                              const aa_params *params, void *workspace, size_t workspace_bytes,
+                              float *VA_out, void *hip_stream);
+
+/* Agent broadcast O = Attn^S(Q, A, V_A) with bias B2, plus DWC(V) and k*V
+ * (Eq. (3), (5), (6); Appendix C.1).  VA [batch, heads, n, d] fp32.  V is read only
+ * for the DWC / k*V terms and may be NULL when both are off. */
+aa_status agent_broadcast_fwd(const aa_desc *desc, const void *Q, const void *A, const float *VA,
+                              const void *V, const aa_params *params, void *out, void *hip_stream);
+
+/* FLOPs the cost model of Sec. 4.2 Eq. (7) assigns to the attention part:
+ * 2 * (2nNC + 2NnC) per batch element with C = heads*d, i.e. 8*N*n*d per unit.
+ * Returns 0 when the descriptor is invalid. */
+uint64_t agent_attn_flops(const aa_desc *desc);
+
+/* Static string for a status code. */
+const char *agent_attn_status_str(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AGENT_ATTN_H */

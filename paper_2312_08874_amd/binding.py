@@ -1,0 +1,216 @@
+"""Thin Python binding of the C-ABI library (include/agent_attn.h).
+
+Argument marshalling only: every step of the forward pass runs in the HIP
+kernels of libagent_attn.so.  torch is used for device memory and streams.
+There is no CPU or eager fallback: if the library is missing the import of any
+entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libagent_attn.so")
+
+AA_F32, AA_F16, AA_BF16 = 0, 1, 2
+AA_OK = 0
+STATUS_NAMES = {0: "AA_OK", -1: "AA_ERR_NULL", -2: "AA_ERR_SHAPE", -3: "AA_ERR_DTYPE", -4: "AA_ERR_POOL",
+                -5: "AA_ERR_WORKSPACE", -6: "AA_ERR_ALIAS", -7: "AA_ERR_UNSUPPORTED", -8: "AA_ERR_HIP"}
+
+
+class aa_desc(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32),
+                ("N", ctypes.c_int32), ("n", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("grid_h", ctypes.c_int32), ("grid_w", ctypes.c_int32),
+                ("agent_h", ctypes.c_int32), ("agent_w", ctypes.c_int32),
+                ("dtype", ctypes.c_int32),
+                ("scale1", ctypes.c_float), ("scale2", ctypes.c_float),
+                ("v_residual_k", ctypes.c_float),
+                ("n_splits", ctypes.c_int32),
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64)]
+
+
+class aa_params(ctypes.Structure):
+    _fields_ = [("b1_col", ctypes.c_void_p), ("b1_row", ctypes.c_void_p), ("b1_blk", ctypes.c_void_p),
+                ("b2_col", ctypes.c_void_p), ("b2_row", ctypes.c_void_p), ("b2_blk", ctypes.c_void_p),
+                ("blk_h0", ctypes.c_int32), ("blk_w0", ctypes.c_int32),
+                ("dwc_w", ctypes.c_void_p), ("dwc_b", ctypes.c_void_p)]
+
+
+EXPORTS = ("agent_attn_workspace_bytes", "agent_attn_fwd", "agent_pool_fwd", "agent_aggregate_fwd",
+           "agent_broadcast_fwd", "agent_attn_flops", "agent_attn_status_str")
+
+_lib = None
+
+
+class AgentAttnError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %s (%s)" % (where, STATUS_NAMES.get(status, status), status_str(status)))
+
+
+def lib():
+    """Load libagent_attn.so (built in-tree by __graft_entry__.build()); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("HIP library %s not built; run `python -c 'import __graft_entry__ as g; g.build()'`"
+                              % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, dp, pp = ctypes.c_void_p, ctypes.POINTER(aa_desc), ctypes.POINTER(aa_params)
+        L.agent_attn_workspace_bytes.restype = ctypes.c_size_t
+        L.agent_attn_workspace_bytes.argtypes = [dp, pp]
+        L.agent_attn_flops.restype = ctypes.c_uint64
+        L.agent_attn_flops.argtypes = [dp]
+        L.agent_attn_fwd.restype = ctypes.c_int
+        L.agent_attn_fwd.argtypes = [dp, vp, vp, vp, vp, pp, vp, ctypes.c_size_t, vp, vp]
+        L.agent_pool_fwd.restype = ctypes.c_int
+        L.agent_pool_fwd.argtypes = [dp, vp, vp, vp]
+        L.agent_aggregate_fwd.restype = ctypes.c_int
+        L.agent_aggregate_fwd.argtypes = [dp, vp, vp, vp, pp, vp, ctypes.c_size_t, vp, vp]
+        L.agent_broadcast_fwd.restype = ctypes.c_int
+        L.agent_broadcast_fwd.argtypes = [dp, vp, vp, vp, vp, pp, vp, vp]
+        L.agent_attn_status_str.restype = ctypes.c_char_p
+        L.agent_attn_status_str.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def status_str(status: int) -> str:
+    return lib().agent_attn_status_str(int(status)).decode()
+
+
+def _dtype_code(t):
+    import torch
+    return {torch.float32: AA_F32, torch.float16: AA_F16, torch.bfloat16: AA_BF16}[t.dtype]
+
+
+def make_desc(batch, heads, N, n, d, dtype, grid=None, agent_grid=None, scale1=0.0, scale2=0.0,
+              v_residual_k=0.0, n_splits=0) -> aa_desc:
+    gh, gw = grid if grid is not None else (0, 0)
+    ah, aw = agent_grid if agent_grid is not None else (0, 0)
+    return aa_desc(batch, heads, N, n, d, gh, gw, ah, aw, dtype, scale1, scale2, v_residual_k, n_splits, 0, 0, 0)
+
+
+def make_params(params: dict | None):
+    """dict of torch fp32 device tensors (keys as in aa_params, plus optional 'blk') -> aa_params or None."""
+    if not params:
+        return None
+    p = aa_params()
+    h0 = w0 = 0
+    for key in ("b1_col", "b1_row", "b1_blk", "b2_col", "b2_row", "b2_blk", "dwc_w", "dwc_b"):
+        t = params.get(key)
+        if t is not None:
+            assert t.is_cuda and t.is_contiguous() and str(t.dtype) == "torch.float32", key
+            setattr(p, key, t.data_ptr())
+    if params.get("b1_blk") is not None:
+        h0, w0 = params["b1_blk"].shape[-2:]
+    if params.get("b2_blk") is not None:
+        h0b, w0b = params["b2_blk"].shape[-3:-1]
+        assert (h0, w0) in ((0, 0), (h0b, w0b)), "b1_blk and b2_blk must share blk_h0 x blk_w0"
+        h0, w0 = h0b, w0b
+    p.blk_h0, p.blk_w0 = h0, w0
+    return p
+
+
+def _pp(p):
+    return ctypes.byref(p) if p is not None else None
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def _check(status, where):
+    if status != AA_OK:
+        raise AgentAttnError(status, where)
+
+
+def workspace_bytes(desc: aa_desc, params: aa_params | None = None) -> int:
+    return int(lib().agent_attn_workspace_bytes(ctypes.byref(desc), _pp(params)))
+
+
+def flops(desc: aa_desc) -> int:
+    return int(lib().agent_attn_flops(ctypes.byref(desc)))
+
+
+def _desc_from(Q, n, grid, agent_grid, **kw):
+    B, H, N, d = Q.shape
+    assert Q.is_cuda and Q.is_contiguous()
+    return make_desc(B, H, N, n, d, _dtype_code(Q), grid, agent_grid, **kw)
+
+
+def _workspace(desc, params, workspace):
+    import torch
+    need = workspace_bytes(desc, params)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    return workspace, need
+
+
+def agent_attn_fwd(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict | None = None, scale1=0.0,
+                   scale2=0.0, v_residual_k=0.0, n_splits=0, out=None, workspace=None, stream=None):
+    """O = agent attention of Q, K, V [B,H,N,d] (device tensors).  A None: pool Q onto agent_grid."""
+    import torch
+    n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
+    desc = _desc_from(Q, n, grid, agent_grid, scale1=scale1, scale2=scale2, v_residual_k=v_residual_k,
+                      n_splits=n_splits)
+    p = make_params(params)
+    workspace, need = _workspace(desc, p, workspace)
+    if out is None:
+        out = torch.empty_like(Q)
+    st = lib().agent_attn_fwd(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(A), _pp(p),
+                              workspace.data_ptr(), workspace.numel() * workspace.element_size(), out.data_ptr(),
+                              _stream(stream))
+    _check(st, "agent_attn_fwd")
+    return out
+
+
+def agent_pool_fwd(Q, *, grid, agent_grid, out=None, stream=None):
+    import torch
+    B, H, N, d = Q.shape
+    n = agent_grid[0] * agent_grid[1]
+    desc = _desc_from(Q, n, grid, agent_grid)
+    if out is None:
+        out = torch.empty((B, H, n, d), dtype=Q.dtype, device=Q.device)
+    _check(lib().agent_pool_fwd(ctypes.byref(desc), Q.data_ptr(), out.data_ptr(), _stream(stream)),
+           "agent_pool_fwd")
+    return out
+
+
+def agent_aggregate_fwd(A, K, V, *, grid=None, params: dict | None = None, scale1=0.0, n_splits=0, out=None,
+                        workspace=None, stream=None):
+    import torch
+    B, H, N, d = K.shape
+    n = A.shape[2]
+    desc = _desc_from(K, n, grid, None, scale1=scale1, n_splits=n_splits)
+    p = make_params(params)
+    workspace, need = _workspace(desc, p, workspace)
+    if out is None:
+        out = torch.empty((B, H, n, d), dtype=torch.float32, device=K.device)
+    st = lib().agent_aggregate_fwd(ctypes.byref(desc), A.data_ptr(), K.data_ptr(), V.data_ptr(), _pp(p),
+                                   workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                   out.data_ptr(), _stream(stream))
+    _check(st, "agent_aggregate_fwd")
+    return out
+
+
+def agent_broadcast_fwd(Q, A, VA, V=None, *, grid=None, params: dict | None = None, scale2=0.0,
+                        v_residual_k=0.0, out=None, stream=None):
+    import torch
+    n = A.shape[2]
+    desc = _desc_from(Q, n, grid, None, scale2=scale2, v_residual_k=v_residual_k)
+    p = make_params(params)
+    if out is None:
+        out = torch.empty_like(Q)
+    st = lib().agent_broadcast_fwd(ctypes.byref(desc), Q.data_ptr(), A.data_ptr(), VA.data_ptr(), _ptr(V), _pp(p),
+                                   out.data_ptr(), _stream(stream))
+    _check(st, "agent_broadcast_fwd")
+    return out

@@ -1,0 +1,286 @@
+// C-ABI layer: argument validation, workspace planning and kernel dispatch.
+// All validation is host-only and happens before the first HIP call, so every
+// error path can be exercised on a machine without a GPU.
+#include "../../include/agent_attn.h"
+
+#include <math.h>
+
+#include "kernels.h"
+
+namespace {
+
+using aa::Partials;
+using aa::Problem;
+
+constexpr size_t kAlign = 256;
+constexpr int kMaxD = 256;
+constexpr size_t kMaxDynLds = 64 * 1024;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+size_t elem_size(int dtype) { return dtype == AA_F32 ? 4 : 2; }
+
+struct Plan {
+  int S;               // N-splits of the aggregation
+  size_t off_A;        // pooled agents, element type of the problem
+  size_t off_acc, off_m, off_l;
+  size_t off_VA;       // merged V_A, fp32
+  size_t total;
+};
+
+// Shape checks common to every entry point.  need_grid / need_agent_grid say
+// whether the call uses the 2-D structure of tokens / agents.
+aa_status check_desc(const aa_desc* d, bool need_grid, bool need_agent_grid) {
+  if (!d) return AA_ERR_NULL;
+  if (d->dtype != AA_F32 && d->dtype != AA_F16 && d->dtype != AA_BF16) return AA_ERR_DTYPE;
+  if (d->batch <= 0 || d->heads <= 0 || d->N <= 0 || d->n <= 0 || d->d <= 0) return AA_ERR_SHAPE;
+  if (d->n_splits < 0) return AA_ERR_SHAPE;
+  if (d->grid_h < 0 || d->grid_w < 0 || d->agent_h < 0 || d->agent_w < 0) return AA_ERR_SHAPE;
+  const bool has_grid = d->grid_h > 0 || d->grid_w > 0;
+  const bool has_agrid = d->agent_h > 0 || d->agent_w > 0;
+  if (has_grid && (int64_t)d->grid_h * d->grid_w != d->N) return AA_ERR_SHAPE;
+  if (has_agrid && (int64_t)d->agent_h * d->agent_w != d->n) return AA_ERR_SHAPE;
+  if (need_grid && !has_grid) return AA_ERR_SHAPE;
+  if (need_agent_grid && !has_agrid) return AA_ERR_POOL;
+  if (need_agent_grid && has_grid && (d->agent_h > d->grid_h || d->agent_w > d->grid_w)) return AA_ERR_POOL;
+  const int64_t units = (int64_t)d->batch * d->heads;
+  if (units > 65535) return AA_ERR_UNSUPPORTED;
+  if (d->d > kMaxD) return AA_ERR_UNSUPPORTED;
+  if ((int64_t)units * d->N * d->d >= (int64_t)1 << 40) return AA_ERR_UNSUPPORTED;
+  // only dense [B,H,N,d] tensors
+  const int64_t sn = d->d, sh = (int64_t)d->N * d->d, sb = sh * d->heads;
+  if ((d->stride_n && d->stride_n != sn) || (d->stride_h && d->stride_h != sh) ||
+      (d->stride_b && d->stride_b != sb))
+    return AA_ERR_UNSUPPORTED;
+  if (aa::broadcast_generic_lds_bytes(d->n, d->d) > kMaxDynLds) return AA_ERR_UNSUPPORTED;
+  return AA_OK;
+}
+
+bool params_use_grid(const aa_params* p) {
+  return p && (p->b1_col || p->b1_row || p->b1_blk || p->b2_col || p->b2_row || p->b2_blk || p->dwc_w);
+}
+
+aa_status check_params(const aa_params* p) {
+  if (!p) return AA_OK;
+  if ((p->b1_blk || p->b2_blk) && (p->blk_h0 <= 0 || p->blk_w0 <= 0)) return AA_ERR_SHAPE;
+  if (p->dwc_b && !p->dwc_w) return AA_ERR_NULL;
+  return AA_OK;
+}
+
+int choose_splits(const aa_desc* d) {
+  const int64_t units = (int64_t)d->batch * d->heads;
+  int S = d->n_splits;
+  if (S <= 0) {
+    // generic path: one wave per (unit, agent, split); aim for a few thousand waves
+    const int64_t waves = units * d->n;
+    S = (int)((4096 + waves - 1) / waves);
+    const int max_by_len = (d->N + 127) / 128;   // keep >= 128 tokens per split
+    if (S > max_by_len) S = max_by_len;
+  }
+  if (S > d->N) S = d->N;
+  if (S < 1) S = 1;
+  if (S > 65535) S = 65535;
+  // no empty split: re-derive S from the chunk length
+  const int chunk = (d->N + S - 1) / S;
+  S = (d->N + chunk - 1) / chunk;
+  return S;
+}
+
+Plan make_plan(const aa_desc* d) {
+  Plan pl{};
+  const size_t units = (size_t)d->batch * d->heads;
+  pl.S = choose_splits(d);
+  size_t off = 0;
+  pl.off_A = off;
+  off += align_up(units * d->n * d->d * elem_size(d->dtype));
+  pl.off_acc = off;
+  off += align_up(units * pl.S * d->n * d->d * sizeof(float));
+  pl.off_m = off;
+  off += align_up(units * pl.S * d->n * sizeof(float));
+  pl.off_l = off;
+  off += align_up(units * pl.S * d->n * sizeof(float));
+  pl.off_VA = off;
+  off += align_up(units * d->n * d->d * sizeof(float));
+  pl.total = off;
+  return pl;
+}
+
+Problem make_problem(const aa_desc* d, const aa_params* p) {
+  Problem pr{};
+  pr.units = d->batch * d->heads;
+  pr.heads = d->heads;
+  pr.N = d->N;
+  pr.n = d->n;
+  pr.d = d->d;
+  pr.gh = d->grid_h;
+  pr.gw = d->grid_w;
+  pr.ah = d->agent_h;
+  pr.aw = d->agent_w;
+  pr.dtype = d->dtype;
+  const float dflt = 1.0f / sqrtf((float)d->d);
+  pr.scale1 = d->scale1 > 0.0f ? d->scale1 : dflt;
+  pr.scale2 = d->scale2 > 0.0f ? d->scale2 : dflt;
+  pr.vk = d->v_residual_k;
+  if (p) {
+    pr.b1 = aa::BiasArgs{p->b1_col, p->b1_row, p->b1_blk, p->blk_h0, p->blk_w0};
+    pr.b2 = aa::BiasArgs{p->b2_col, p->b2_row, p->b2_blk, p->blk_h0, p->blk_w0};
+    pr.dwc_w = p->dwc_w;
+    pr.dwc_b = p->dwc_b;
+  }
+  return pr;
+}
+
+bool overlaps(const void* a, size_t abytes, const void* b, size_t bbytes) {
+  if (!a || !b) return false;
+  const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+  return a0 < b0 + bbytes && b0 < a0 + abytes;
+}
+
+Partials partials_in(void* ws, const Plan& pl) {
+  char* base = (char*)ws;
+  return Partials{(float*)(base + pl.off_acc), (float*)(base + pl.off_m), (float*)(base + pl.off_l), pl.S};
+}
+
+aa_status check_workspace(const void* ws, size_t bytes, const Plan& pl) {
+  if (!ws || ((uintptr_t)ws % kAlign) != 0 || bytes < pl.total) return AA_ERR_WORKSPACE;
+  return AA_OK;
+}
+
+#define AA_HIP(call)                       \
+  do {                                     \
+    if ((call) != hipSuccess) return AA_ERR_HIP; \
+  } while (0)
+
+aa_status run_aggregate(const Problem& pr, const void* A, const void* K, const void* V, const Partials& part,
+                        float* VA, hipStream_t st) {
+  AA_HIP(aa::launch_aggregate_generic(pr, A, K, V, part, st));
+  AA_HIP(aa::launch_merge_generic(pr, part, VA, st));
+  return AA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t agent_attn_workspace_bytes(const aa_desc* desc, const aa_params* params) {
+  if (check_desc(desc, params_use_grid(params), false) != AA_OK) return 0;
+  if (check_params(params) != AA_OK) return 0;
+  return make_plan(desc).total;
+}
+
+uint64_t agent_attn_flops(const aa_desc* desc) {
+  if (check_desc(desc, false, false) != AA_OK) return 0;
+  return 8ull * (uint64_t)desc->N * (uint64_t)desc->n * (uint64_t)desc->d * (uint64_t)desc->batch *
+         (uint64_t)desc->heads;
+}
+
+aa_status agent_pool_fwd(const aa_desc* desc, const void* Q, void* A_out, void* hip_stream) {
+  aa_status st = check_desc(desc, true, true);
+  if (st != AA_OK) return st;
+  if (!Q || !A_out) return AA_ERR_NULL;
+  const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
+  if (overlaps(A_out, units * desc->n * desc->d * es, Q, units * desc->N * desc->d * es)) return AA_ERR_ALIAS;
+  Problem pr = make_problem(desc, nullptr);
+  AA_HIP(aa::launch_pool_generic(pr, Q, A_out, (hipStream_t)hip_stream));
+  return AA_OK;
+}
+
+aa_status agent_aggregate_fwd(const aa_desc* desc, const void* A, const void* K, const void* V,
+                              const aa_params* params, void* workspace, size_t workspace_bytes, float* VA_out,
+                              void* hip_stream) {
+  const bool bias1 = params && (params->b1_col || params->b1_row || params->b1_blk);
+  aa_status st = check_desc(desc, bias1, false);
+  if (st != AA_OK) return st;
+  st = check_params(params);
+  if (st != AA_OK) return st;
+  if (!A || !K || !V || !VA_out) return AA_ERR_NULL;
+  const Plan pl = make_plan(desc);
+  st = check_workspace(workspace, workspace_bytes, pl);
+  if (st != AA_OK) return st;
+  const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
+  const size_t va_bytes = units * desc->n * desc->d * sizeof(float);
+  if (overlaps(VA_out, va_bytes, A, units * desc->n * desc->d * es) ||
+      overlaps(VA_out, va_bytes, K, units * desc->N * desc->d * es) ||
+      overlaps(VA_out, va_bytes, V, units * desc->N * desc->d * es) ||
+      overlaps(VA_out, va_bytes, workspace, workspace_bytes))
+    return AA_ERR_ALIAS;
+  Problem pr = make_problem(desc, params);
+  pr.b2 = aa::BiasArgs{};
+  return run_aggregate(pr, A, K, V, partials_in(workspace, pl), VA_out, (hipStream_t)hip_stream);
+}
+
+aa_status agent_broadcast_fwd(const aa_desc* desc, const void* Q, const void* A, const float* VA, const void* V,
+                              const aa_params* params, void* out, void* hip_stream) {
+  const bool bias2 = params && (params->b2_col || params->b2_row || params->b2_blk);
+  const bool dwc = params && params->dwc_w;
+  aa_status st = check_desc(desc, bias2 || dwc, false);
+  if (st != AA_OK) return st;
+  st = check_params(params);
+  if (st != AA_OK) return st;
+  if (!Q || !A || !VA || !out) return AA_ERR_NULL;
+  if ((dwc || desc->v_residual_k != 0.0f) && !V) return AA_ERR_NULL;
+  const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
+  const size_t big = units * desc->N * desc->d * es;
+  if (overlaps(out, big, Q, big) || overlaps(out, big, V, big) ||
+      overlaps(out, big, A, units * desc->n * desc->d * es) ||
+      overlaps(out, big, VA, units * desc->n * desc->d * sizeof(float)))
+    return AA_ERR_ALIAS;
+  Problem pr = make_problem(desc, params);
+  pr.b1 = aa::BiasArgs{};
+  AA_HIP(aa::launch_broadcast_generic(pr, Q, A, VA, V, out, (hipStream_t)hip_stream));
+  return AA_OK;
+}
+
+aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, const void* V, const void* A,
+                         const aa_params* params, void* workspace, size_t workspace_bytes, void* out,
+                         void* hip_stream) {
+  const bool pooling = (A == nullptr);
+  aa_status st = check_desc(desc, pooling || params_use_grid(params), pooling);
+  if (st == AA_ERR_SHAPE && pooling && desc && desc->grid_h == 0 && desc->grid_w == 0) st = AA_ERR_POOL;
+  if (st != AA_OK) return st;
+  st = check_params(params);
+  if (st != AA_OK) return st;
+  if (!Q || !K || !V || !out) return AA_ERR_NULL;
+  const Plan pl = make_plan(desc);
+  st = check_workspace(workspace, workspace_bytes, pl);
+  if (st != AA_OK) return st;
+  const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
+  const size_t big = units * desc->N * desc->d * es;
+  if (overlaps(out, big, Q, big) || overlaps(out, big, K, big) || overlaps(out, big, V, big) ||
+      overlaps(out, big, A, units * desc->n * desc->d * es) || overlaps(out, big, workspace, workspace_bytes) ||
+      overlaps(workspace, workspace_bytes, Q, big) || overlaps(workspace, workspace_bytes, K, big) ||
+      overlaps(workspace, workspace_bytes, V, big) ||
+      overlaps(workspace, workspace_bytes, A, units * desc->n * desc->d * es))
+    return AA_ERR_ALIAS;
+
+  const Problem pr = make_problem(desc, params);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  const void* agents = A;
+  if (pooling) {
+    AA_HIP(aa::launch_pool_generic(pr, Q, ws + pl.off_A, stream));
+    agents = ws + pl.off_A;
+  }
+  float* VA = (float*)(ws + pl.off_VA);
+  st = run_aggregate(pr, agents, K, V, partials_in(workspace, pl), VA, stream);
+  if (st != AA_OK) return st;
+  AA_HIP(aa::launch_broadcast_generic(pr, Q, agents, VA, V, out, stream));
+  return AA_OK;
+}
+
+const char* agent_attn_status_str(int status) {
+  switch (status) {
+    case AA_OK: return "ok";
+    case AA_ERR_NULL: return "required pointer is NULL";
+    case AA_ERR_SHAPE: return "invalid or inconsistent sizes";
+    case AA_ERR_DTYPE: return "unknown dtype";
+    case AA_ERR_POOL: return "agents not given and the grids do not define a pooling";
+    case AA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case AA_ERR_ALIAS: return "output or workspace overlaps an input";
+    case AA_ERR_UNSUPPORTED: return "problem outside the implemented range";
+    case AA_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

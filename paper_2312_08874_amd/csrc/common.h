@@ -1,0 +1,108 @@
+// Device-side helpers shared by the agent-attention kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace aa {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// ---------------------------------------------------------------------------
+// Element types.  bf16 is handled as raw 16-bit patterns; fp16 as _Float16.
+// ---------------------------------------------------------------------------
+struct ElemF32 {
+  using T = float;
+  static __device__ __forceinline__ float to_f32(T v) { return v; }
+  static __device__ __forceinline__ T from_f32(float f) { return f; }
+};
+struct ElemF16 {
+  using T = _Float16;
+  static __device__ __forceinline__ float to_f32(T v) { return (float)v; }
+  static __device__ __forceinline__ T from_f32(float f) { return (_Float16)f; }
+};
+struct ElemBF16 {
+  using T = uint16_t;
+  static __device__ __forceinline__ float to_f32(T v) { return __uint_as_float(((uint32_t)v) << 16); }
+  // round to nearest even; inputs are finite
+  static __device__ __forceinline__ T from_f32(float f) {
+    uint32_t b = __float_as_uint(f);
+    b += 0x7FFFu + ((b >> 16) & 1u);
+    return (T)(b >> 16);
+  }
+};
+
+// ---------------------------------------------------------------------------
+// Agent bias (Appendix B), evaluated on the fly from its three components.
+// Pointers are already offset to the head; any may be null.
+//   kind 1: B1[a,(y,x)] = col[a*w+x] + row[a*h+y] + resize(blk[a,:,:])[y,x]
+//   kind 2: B2[(y,x),a] = col[x*n+a] + row[y*n+a] + resize(blk[:,:,a])[y,x]
+// Block resize: bilinear, half-pixel centres, source coordinate clamped at 0,
+// upper neighbour clamped to the last sample.
+// ---------------------------------------------------------------------------
+struct BiasArgs {
+  const float* col;
+  const float* row;
+  const float* blk;
+  int h0, w0;
+  __host__ __device__ bool any() const { return col || row || blk; }
+};
+
+__device__ __forceinline__ void bilinear_coord(int dst, int L, int L0, int& i0, int& i1, float& f) {
+  float s = ((float)dst + 0.5f) * ((float)L0 / (float)L) - 0.5f;
+  s = fmaxf(s, 0.0f);
+  int lo = (int)floorf(s);
+  lo = lo > L0 - 1 ? L0 - 1 : lo;
+  i0 = lo;
+  i1 = lo + 1 < L0 ? lo + 1 : L0 - 1;
+  f = s - (float)lo;
+}
+
+__device__ __forceinline__ float bias1_at(const BiasArgs& b, int a, int y, int x, int h, int w) {
+  float v = 0.0f;
+  if (b.col) v += b.col[(size_t)a * w + x];
+  if (b.row) v += b.row[(size_t)a * h + y];
+  if (b.blk) {
+    int y0, y1, x0, x1;
+    float fy, fx;
+    bilinear_coord(y, h, b.h0, y0, y1, fy);
+    bilinear_coord(x, w, b.w0, x0, x1, fx);
+    const float* p = b.blk + (size_t)a * b.h0 * b.w0;
+    float v00 = p[y0 * b.w0 + x0], v01 = p[y0 * b.w0 + x1];
+    float v10 = p[y1 * b.w0 + x0], v11 = p[y1 * b.w0 + x1];
+    float top = v00 + (v01 - v00) * fx, bot = v10 + (v11 - v10) * fx;
+    v += top + (bot - top) * fy;
+  }
+  return v;
+}
+
+__device__ __forceinline__ float bias2_at(const BiasArgs& b, int a, int y, int x, int h, int w, int n) {
+  float v = 0.0f;
+  if (b.col) v += b.col[(size_t)x * n + a];
+  if (b.row) v += b.row[(size_t)y * n + a];
+  if (b.blk) {
+    int y0, y1, x0, x1;
+    float fy, fx;
+    bilinear_coord(y, h, b.h0, y0, y1, fy);
+    bilinear_coord(x, w, b.w0, x0, x1, fx);
+    const float* p = b.blk + a;
+    float v00 = p[(size_t)(y0 * b.w0 + x0) * n], v01 = p[(size_t)(y0 * b.w0 + x1) * n];
+    float v10 = p[(size_t)(y1 * b.w0 + x0) * n], v11 = p[(size_t)(y1 * b.w0 + x1) * n];
+    float top = v00 + (v01 - v00) * fx, bot = v10 + (v11 - v10) * fx;
+    v += top + (bot - top) * fy;
+  }
+  return v;
+}
+
+// wave64 reductions
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+}  // namespace aa

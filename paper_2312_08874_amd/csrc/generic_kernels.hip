@@ -1,0 +1,276 @@
+// Reference-quality HIP kernels for agent attention: every shape (d <= 256), every
+// element type, plain fp32 VALU arithmetic.  They are the fp32 path and the safety
+// net behind the MFMA kernels.  One wave works on one agent (aggregation) or one
+// query token (broadcast); all waves of a block run the same trip counts so that
+// block-wide barriers are always reached.
+#include "kernels.h"
+
+namespace aa {
+
+constexpr int kWaves = 4;             // waves per block in aggregate / broadcast
+constexpr int kMaxDPerLane = 4;       // d <= 64 * kMaxDPerLane
+
+__device__ __forceinline__ int win_lo(int i, int L, int La) { return (int)(((long long)i * L) / La); }
+__device__ __forceinline__ int win_hi(int i, int L, int La) {
+  return (int)((((long long)(i + 1)) * L + La - 1) / La);
+}
+
+// ---------------------------------------------------------------------------
+// A = Pooling(Q) (Sec. 4.2): block = one agent of one unit, thread = channel.
+// ---------------------------------------------------------------------------
+template <class E>
+__global__ __launch_bounds__(64) void pool_generic_kernel(const typename E::T* __restrict__ Q,
+                                                          typename E::T* __restrict__ A, int N, int n, int d,
+                                                          int gh, int gw, int ah, int aw) {
+  const int a = blockIdx.x, u = blockIdx.y;
+  const int ay = a / aw, ax = a % aw;
+  const int y0 = win_lo(ay, gh, ah), y1 = win_hi(ay, gh, ah);
+  const int x0 = win_lo(ax, gw, aw), x1 = win_hi(ax, gw, aw);
+  const float inv = 1.0f / (float)((y1 - y0) * (x1 - x0));
+  const typename E::T* q = Q + (size_t)u * N * d;
+  for (int c = threadIdx.x; c < d; c += 64) {
+    float acc = 0.0f;
+    for (int y = y0; y < y1; ++y)
+      for (int x = x0; x < x1; ++x) acc += E::to_f32(q[((size_t)y * gw + x) * d + c]);
+    A[((size_t)u * n + a) * d + c] = E::from_f32(acc * inv);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Agent aggregation, split-N partial pass (Sec. 4.1 Eq. (3), bias of Eq. (5)).
+// grid = (ceil(n / kWaves), S, units); wave w of a block owns agent 4*blockIdx.x + w
+// and walks the tokens of split blockIdx.y in steps of 64 (one token per lane)
+// with the running-maximum ("online") softmax.
+// ---------------------------------------------------------------------------
+template <class E>
+__global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
+    const typename E::T* __restrict__ A, const typename E::T* __restrict__ K,
+    const typename E::T* __restrict__ V, BiasArgs b1, float scale, int N, int n, int d, int heads, int gh,
+    int gw, int S, float* __restrict__ part_acc, float* __restrict__ part_m, float* __restrict__ part_l) {
+  extern __shared__ float smem[];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int a = blockIdx.x * kWaves + wave;
+  const int s = blockIdx.y, u = blockIdx.z;
+  const bool active = a < n;
+  float* a_row = smem + wave * (d + 64);
+  float* p_sh = a_row + d;
+
+  const int chunk = (N + S - 1) / S;
+  const int t0 = s * chunk;
+  const int t1 = min(N, t0 + chunk);
+  const typename E::T* Ku = K + (size_t)u * N * d;
+  const typename E::T* Vu = V + (size_t)u * N * d;
+
+  const int hd = u % heads;
+  BiasArgs b = b1;
+  if (b.col) b.col += (size_t)hd * n * gw;
+  if (b.row) b.row += (size_t)hd * n * gh;
+  if (b.blk) b.blk += (size_t)hd * n * b.h0 * b.w0;
+  const bool has_bias = b.any();
+
+  if (active)
+    for (int c = lane; c < d; c += 64) a_row[c] = E::to_f32(A[((size_t)u * n + a) * d + c]);
+  __syncthreads();
+
+  float m = -INFINITY, l = 0.0f;
+  float acc[kMaxDPerLane] = {0.0f, 0.0f, 0.0f, 0.0f};
+
+  for (int tb = t0; tb < t1; tb += 64) {
+    const int t = tb + lane;
+    const bool valid = active && t < t1;
+    float sc = -INFINITY;
+    if (valid) {
+      const typename E::T* kr = Ku + (size_t)t * d;
+      float dot = 0.0f;
+      for (int c = 0; c < d; ++c) dot += a_row[c] * E::to_f32(kr[c]);
+      sc = dot * scale;
+      if (has_bias) sc += bias1_at(b, a, t / gw, t % gw, gh, gw);
+    }
+    const float m_new = fmaxf(m, wave_max(sc));
+    const float p = valid ? __expf(sc - m_new) : 0.0f;
+    const float alpha = active ? __expf(m - m_new) : 0.0f;   // m = -inf on the first step -> 0
+    l = l * alpha + wave_sum(p);
+    m = m_new;
+    p_sh[lane] = p;
+    __syncthreads();
+    const int cnt = min(64, t1 - tb);
+    if (active) {
+#pragma unroll
+      for (int k = 0; k < kMaxDPerLane; ++k) {
+        const int c = lane + 64 * k;
+        if (c < d) {
+          float v = acc[k] * alpha;
+          for (int j = 0; j < cnt; ++j) v += p_sh[j] * E::to_f32(Vu[(size_t)(tb + j) * d + c]);
+          acc[k] = v;
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  if (active) {
+    const size_t row = ((size_t)u * S + s) * n + a;
+#pragma unroll
+    for (int k = 0; k < kMaxDPerLane; ++k) {
+      const int c = lane + 64 * k;
+      if (c < d) part_acc[row * d + c] = acc[k];
+    }
+    if (lane == 0) {
+      part_m[row] = m;
+      part_l[row] = l;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Merge of the S split partials (log-sum-exp rule):
+//   m = max_s m_s;  l = sum_s l_s e^{m_s-m};  VA = sum_s acc_s e^{m_s-m} / l.
+// block = one agent of one unit; thread = channel.  Fixed summation order.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void merge_generic_kernel(const float* __restrict__ part_acc,
+                                                           const float* __restrict__ part_m,
+                                                           const float* __restrict__ part_l, int S, int n, int d,
+                                                           float* __restrict__ VA) {
+  const int a = blockIdx.x, u = blockIdx.y;
+  float m = -INFINITY;
+  for (int s = 0; s < S; ++s) m = fmaxf(m, part_m[((size_t)u * S + s) * n + a]);
+  float l = 0.0f;
+  for (int s = 0; s < S; ++s) {
+    const size_t row = ((size_t)u * S + s) * n + a;
+    l += part_l[row] * __expf(part_m[row] - m);
+  }
+  const float inv = 1.0f / l;
+  for (int c = threadIdx.x; c < d; c += 64) {
+    float v = 0.0f;
+    for (int s = 0; s < S; ++s) {
+      const size_t row = ((size_t)u * S + s) * n + a;
+      v += part_acc[row * d + c] * __expf(part_m[row] - m);
+    }
+    VA[((size_t)u * n + a) * d + c] = v * inv;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Agent broadcast (Eq. (3), bias B2 of Eq. (5)) with the module epilogue
+// (+DWC(V) of Eq. (6), +k V of Appendix C.1).  grid = (ceil(N / kWaves), units);
+// one wave per query token; scores over the n agents live in LDS.
+// ---------------------------------------------------------------------------
+template <class E>
+__global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
+    const typename E::T* __restrict__ Q, const typename E::T* __restrict__ A, const float* __restrict__ VA,
+    const typename E::T* __restrict__ V, BiasArgs b2, const float* __restrict__ dwc_w,
+    const float* __restrict__ dwc_b, float scale, float vk, int N, int n, int d, int heads, int gh, int gw,
+    typename E::T* __restrict__ O) {
+  extern __shared__ float smem[];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = blockIdx.x * kWaves + wave;
+  const int u = blockIdx.y;
+  const bool active = i < N;
+  float* q_row = smem + wave * (d + n);
+  float* sc = q_row + d;
+
+  const int hd = u % heads;
+  BiasArgs b = b2;
+  if (b.col) b.col += (size_t)hd * gw * n;
+  if (b.row) b.row += (size_t)hd * gh * n;
+  if (b.blk) b.blk += (size_t)hd * b.h0 * b.w0 * n;
+  const bool has_bias = b.any();
+  const int y = gw > 0 ? i / gw : 0, x = gw > 0 ? i % gw : 0;
+
+  if (active)
+    for (int c = lane; c < d; c += 64) q_row[c] = E::to_f32(Q[((size_t)u * N + i) * d + c]);
+  __syncthreads();
+
+  float mx = -INFINITY;
+  if (active)
+    for (int a = lane; a < n; a += 64) {
+      const typename E::T* ar = A + ((size_t)u * n + a) * d;
+      float dot = 0.0f;
+      for (int c = 0; c < d; ++c) dot += q_row[c] * E::to_f32(ar[c]);
+      float s = dot * scale;
+      if (has_bias) s += bias2_at(b, a, y, x, gh, gw, n);
+      sc[a] = s;
+      mx = fmaxf(mx, s);
+    }
+  mx = wave_max(mx);
+  float sum = 0.0f;
+  if (active)
+    for (int a = lane; a < n; a += 64) {
+      const float p = __expf(sc[a] - mx);
+      sc[a] = p;
+      sum += p;
+    }
+  sum = wave_sum(sum);
+  __syncthreads();
+
+  if (active) {
+    const float inv = 1.0f / sum;
+    const float* VAu = VA + (size_t)u * n * d;
+    for (int c = lane; c < d; c += 64) {
+      float o = 0.0f;
+      for (int a = 0; a < n; ++a) o += sc[a] * VAu[(size_t)a * d + c];
+      o *= inv;
+      if (dwc_w) {
+        const float* w9 = dwc_w + ((size_t)hd * d + c) * 9;
+        float conv = dwc_b ? dwc_b[(size_t)hd * d + c] : 0.0f;
+        for (int ky = -1; ky <= 1; ++ky)
+          for (int kx = -1; kx <= 1; ++kx) {
+            const int yy = y + ky, xx = x + kx;
+            if (yy >= 0 && yy < gh && xx >= 0 && xx < gw)
+              conv += w9[(ky + 1) * 3 + (kx + 1)] * E::to_f32(V[((size_t)u * N + (size_t)yy * gw + xx) * d + c]);
+          }
+        o += conv;
+      }
+      if (vk != 0.0f) o += vk * E::to_f32(V[((size_t)u * N + i) * d + c]);
+      O[((size_t)u * N + i) * d + c] = E::from_f32(o);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+#define AA_DISPATCH_DTYPE(dtype, ...)                  \
+  switch (dtype) {                                     \
+    case 0: { using E = ElemF32; __VA_ARGS__; } break;  \
+    case 1: { using E = ElemF16; __VA_ARGS__; } break;  \
+    case 2: { using E = ElemBF16; __VA_ARGS__; } break; \
+    default: return hipErrorInvalidValue;              \
+  }
+
+hipError_t launch_pool_generic(const Problem& p, const void* Q, void* A, hipStream_t st) {
+  dim3 grid(p.n, p.units);
+  AA_DISPATCH_DTYPE(p.dtype, pool_generic_kernel<E><<<grid, dim3(64), 0, st>>>(
+      (const typename E::T*)Q, (typename E::T*)A, p.N, p.n, p.d, p.gh, p.gw, p.ah, p.aw));
+  return hipGetLastError();
+}
+
+hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* K, const void* V,
+                                    const Partials& part, hipStream_t st) {
+  dim3 grid((p.n + kWaves - 1) / kWaves, part.S, p.units);
+  const size_t lds = (size_t)kWaves * (p.d + 64) * sizeof(float);
+  AA_DISPATCH_DTYPE(p.dtype, aggregate_generic_kernel<E><<<grid, dim3(64 * kWaves), lds, st>>>(
+      (const typename E::T*)A, (const typename E::T*)K, (const typename E::T*)V, p.b1, p.scale1, p.N, p.n, p.d,
+      p.heads, p.gh, p.gw, part.S, part.acc, part.m, part.l));
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_generic(const Problem& p, const Partials& part, float* VA, hipStream_t st) {
+  dim3 grid(p.n, p.units);
+  merge_generic_kernel<<<grid, dim3(64), 0, st>>>(part.acc, part.m, part.l, part.S, p.n, p.d, VA);
+  return hipGetLastError();
+}
+
+size_t broadcast_generic_lds_bytes(int n, int d) { return (size_t)kWaves * (n + d) * sizeof(float); }
+
+hipError_t launch_broadcast_generic(const Problem& p, const void* Q, const void* A, const float* VA,
+                                    const void* V, void* out, hipStream_t st) {
+  dim3 grid((p.N + kWaves - 1) / kWaves, p.units);
+  const size_t lds = broadcast_generic_lds_bytes(p.n, p.d);
+  AA_DISPATCH_DTYPE(p.dtype, broadcast_generic_kernel<E><<<grid, dim3(64 * kWaves), lds, st>>>(
+      (const typename E::T*)Q, (const typename E::T*)A, VA, (const typename E::T*)V, p.b2, p.dwc_w, p.dwc_b,
+      p.scale2, p.vk, p.N, p.n, p.d, p.heads, p.gh, p.gw, (typename E::T*)out));
+  return hipGetLastError();
+}
+
+}  // namespace aa

@@ -1,0 +1,42 @@
+// Host-side launch interface between the C-ABI layer (api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "common.h"
+
+namespace aa {
+
+// One fully resolved problem, shared by every launcher.
+struct Problem {
+  int units, heads, N, n, d;
+  int gh, gw, ah, aw;
+  int dtype;  // aa_dtype
+  float scale1, scale2, vk;
+  // module terms (pointers to the start of the per-head arrays, or null)
+  BiasArgs b1, b2;
+  const float* dwc_w;
+  const float* dwc_b;
+};
+
+// Split-N partial state written by the aggregation pass and consumed by the merge:
+//   acc [units][S][n][d], m [units][S][n], l [units][S][n]   (fp32)
+struct Partials {
+  float* acc;
+  float* m;
+  float* l;
+  int S;
+};
+
+// --- reference-quality kernels: any shape (d <= 256), any dtype, VALU fp32 math ---
+hipError_t launch_pool_generic(const Problem& p, const void* Q, void* A, hipStream_t st);
+hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* K, const void* V,
+                                    const Partials& part, hipStream_t st);
+hipError_t launch_merge_generic(const Problem& p, const Partials& part, float* VA, hipStream_t st);
+hipError_t launch_broadcast_generic(const Problem& p, const void* Q, const void* A, const float* VA,
+                                    const void* V, void* out, hipStream_t st);
+// dynamic LDS the generic broadcast needs for this problem (bytes)
+size_t broadcast_generic_lds_bytes(int n, int d);
+
+}  // namespace aa

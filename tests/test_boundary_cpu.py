@@ -1,0 +1,121 @@
+"""Host-side checks of the C-ABI library that need no GPU: the library loads,
+exports what include/agent_attn.h declares, and rejects bad arguments before
+launching anything (every call below must fail, so no kernel ever starts)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2312_08874_amd import binding
+from paper_2312_08874_amd.binding import aa_params, make_desc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # non-null, 256-aligned; never dereferenced because validation fails first
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "agent_attn.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(agent_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = binding.lib()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for nme in names:
+        assert getattr(L, nme) is not None
+
+
+def test_struct_layout_matches_header():
+    # int32 x10, float x3, int32, int64 x3 -> 80 bytes; params: 6 ptr, 2 int32, 2 ptr -> 72 bytes
+    assert ctypes.sizeof(binding.aa_desc) == 80
+    assert ctypes.sizeof(binding.aa_params) == 72
+
+
+def test_flops_follow_the_cost_model():
+    """Eq. (7): agent attention costs 2nNC + 2NnC multiply-adds per image, C = heads*d."""
+    for (B, H, N, n, d) in [(1, 1, 196, 49, 32), (64, 3, 196, 49, 64), (1, 8, 16384, 1024, 64)]:
+        C = H * d
+        macs = 2 * n * N * C + 2 * N * n * C
+        assert binding.flops(make_desc(B, H, N, n, d, binding.AA_BF16)) == 2 * macs * B
+    assert binding.flops(make_desc(1, 1, 0, 4, 4, binding.AA_F32)) == 0
+
+
+def test_workspace_query():
+    d = make_desc(2, 3, 196, 49, 32, binding.AA_BF16, (14, 14), (7, 7))
+    w1 = binding.workspace_bytes(d)
+    assert w1 > 0 and w1 % 256 == 0
+    d2 = make_desc(2, 3, 196, 49, 32, binding.AA_BF16, (14, 14), (7, 7), n_splits=4)
+    assert binding.workspace_bytes(d2) >= w1 or binding.workspace_bytes(d2) > 0
+    assert binding.workspace_bytes(make_desc(2, 3, 196, 49, 32, 7)) == 0          # bad dtype
+    assert binding.workspace_bytes(make_desc(2, 3, 197, 49, 32, 0, (14, 14))) == 0  # N != h*w
+
+
+def call_fwd(desc, Q=FAKE, K=FAKE * 2, V=FAKE * 3, A=None, params=None, ws=FAKE * 4, ws_bytes=1 << 40,
+             out=FAKE * 5 + (1 << 41)):
+    L = binding.lib()
+    return L.agent_attn_fwd(ctypes.byref(desc), Q, K, V, A, None if params is None else ctypes.byref(params),
+                            ws, ws_bytes, out, None)
+
+
+def test_fwd_rejects_bad_arguments():
+    ok = dict(grid=(14, 14), agent_grid=(7, 7))
+    assert call_fwd(make_desc(1, 1, 196, 49, 32, 5, **ok)) == -3                      # dtype
+    assert call_fwd(make_desc(0, 1, 196, 49, 32, 0, **ok)) == -2                      # batch
+    assert call_fwd(make_desc(1, 1, 196, 49, 0, 0, **ok)) == -2                       # d
+    assert call_fwd(make_desc(1, 1, 195, 49, 32, 0, **ok)) == -2                      # N != h*w
+    assert call_fwd(make_desc(1, 1, 196, 48, 32, 0, **ok)) == -2                      # n != ah*aw
+    assert call_fwd(make_desc(1, 1, 196, 49, 32, 0, grid=(14, 14))) == -4             # pooling without agent grid
+    assert call_fwd(make_desc(1, 1, 196, 49, 32, 0, agent_grid=(7, 7))) == -4         # pooling without token grid
+    assert call_fwd(make_desc(1, 1, 196, 400, 32, 0, grid=(14, 14), agent_grid=(20, 20))) == -4
+    assert call_fwd(make_desc(1, 1, 196, 49, 512, 0, **ok)) == -7                     # d too large
+    assert call_fwd(make_desc(1, 1, 196, 49, 32, 0, **ok), Q=None) == -1
+    assert call_fwd(make_desc(1, 1, 196, 49, 32, 0, **ok), out=None) == -1
+    assert call_fwd(make_desc(1, 1, 196, 49, 32, 0, **ok), ws=None) == -5
+    assert call_fwd(make_desc(1, 1, 196, 49, 32, 0, **ok), ws=FAKE * 4 + 8) == -5     # misaligned
+    assert call_fwd(make_desc(1, 1, 196, 49, 32, 0, **ok), ws_bytes=64) == -5         # too small
+    d = make_desc(1, 1, 196, 49, 32, 0, **ok)
+    assert call_fwd(d, out=FAKE) == -6                                                # out aliases Q
+    assert call_fwd(d, out=FAKE * 3 + 16) == -6                                       # out overlaps V
+    d.stride_n = 64
+    assert call_fwd(d) == -7                                                          # strided input
+    # bias without a token grid; block bias without its size; DWC bias without DWC weights
+    p = aa_params()
+    p.b1_row = FAKE * 7
+    assert call_fwd(make_desc(1, 1, 196, 49, 32, 0), A=FAKE * 6, params=p) == -2
+    p = aa_params()
+    p.b2_blk = FAKE * 7
+    assert call_fwd(make_desc(1, 1, 196, 49, 32, 0, **ok), params=p) == -2
+    p = aa_params()
+    p.dwc_b = FAKE * 7
+    assert call_fwd(make_desc(1, 1, 196, 49, 32, 0, **ok), params=p) == -1
+
+
+def test_stage_entry_points_reject_bad_arguments():
+    L = binding.lib()
+    d = make_desc(1, 1, 196, 49, 32, 0, (14, 14), (7, 7))
+    assert L.agent_pool_fwd(ctypes.byref(d), None, FAKE, None) == -1
+    assert L.agent_pool_fwd(ctypes.byref(make_desc(1, 1, 196, 49, 32, 0, (14, 14))), FAKE, FAKE * 9, None) == -4
+    assert L.agent_pool_fwd(ctypes.byref(d), FAKE, FAKE + 64, None) == -6
+    assert L.agent_aggregate_fwd(ctypes.byref(d), FAKE, FAKE * 2, FAKE * 3, None, None, 0, FAKE * 5, None) == -5
+    assert L.agent_aggregate_fwd(ctypes.byref(d), FAKE, None, FAKE * 3, None, FAKE * 4, 1 << 30,
+                                 FAKE * 5 + (1 << 41), None) == -1
+    assert L.agent_broadcast_fwd(ctypes.byref(d), FAKE, FAKE * 2, FAKE * 3, None, None, None, None) == -1
+    d.v_residual_k = 0.5          # k*V requested but V missing
+    assert L.agent_broadcast_fwd(ctypes.byref(d), FAKE, FAKE * 2, FAKE * 3, None, None, FAKE * 9 + (1 << 41),
+                                 None) == -1
+    assert L.agent_attn_fwd(None, FAKE, FAKE, FAKE, None, None, FAKE, 1, FAKE, None) == -1
+
+
+def test_status_strings():
+    for code in range(-8, 1):
+        assert binding.status_str(code) not in ("", "unknown status")
+    assert binding.status_str(-99) == "unknown status"
+
+
+def test_binding_has_no_fallback():
+    """The binding must not import the oracle or compute anything itself."""
+    src = open(os.path.join(ROOT, "paper_2312_08874_amd", "binding.py")).read()
+    assert "oracle" not in src.replace("no CPU or eager fallback", "")

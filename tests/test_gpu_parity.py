@@ -1,0 +1,292 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle
+on the same seeded inputs.  Bar: fp32 max-abs <= 1e-4; bf16/fp16 max-abs <= 1e-2 and
+relative L2 <= 5e-3 (fp32 accumulation); index-free, so no bit-exact part except
+run-to-run determinism.
+"""
+import numpy as np
+import pytest
+
+from paper_2312_08874_amd import inputs
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+WL = inputs.WORKLOADS
+
+
+@pytest.fixture(scope="module")
+def aa():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2312_08874_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev_qkv(wl, t, units=None):
+    u = wl.units if units is None else units
+    B = u // wl.heads
+    return {k: util.to_device(v[:u], wl.dtype, (B, wl.heads, wl.N, wl.d)) for k, v in t.items()}
+
+
+def small(wl, batch):
+    """Same shape per unit, fewer batch elements (keeps the oracle to seconds)."""
+    import dataclasses
+    return dataclasses.replace(wl, batch=min(batch, wl.batch))
+
+
+# --------------------------------------------------------------------------
+# a0  pooling
+# --------------------------------------------------------------------------
+POOL_CASES = [("tiny", (14, 14), (7, 7), 32), ("deit", (14, 14), (7, 7), 64), ("swin", (56, 56), (7, 7), 32),
+              ("sd", (64, 64), (16, 16), 40), ("hires", (128, 128), (32, 32), 64),
+              ("swin9", (56, 56), (3, 3), 32), ("ragged", (13, 17), (4, 5), 24), ("identity", (6, 5), (6, 5), 8),
+              ("one", (9, 9), (1, 1), 72), ("deitb81", (14, 14), (9, 9), 64)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("name,grid,agrid,d", POOL_CASES, ids=[c[0] for c in POOL_CASES])
+def test_pool(aa, oracle, name, grid, agrid, d, dtype):
+    units = (2, 3)
+    N = grid[0] * grid[1]
+    q = inputs.make_tensor((6, N, d), stream=100, dtype=dtype)
+    A = aa.agent_pool_fwd(util.to_device(q, dtype, (*units, N, d)), grid=grid, agent_grid=agrid)
+    ref = oracle.pool(inputs.to_float64(q, dtype), *grid, *agrid)
+    got = util.to_host64(A).reshape(ref.shape)
+    half_ulp = {"f32": 2.0 ** -24, "f16": 2.0 ** -11, "bf16": 2.0 ** -8}[dtype]
+    win = (-(-grid[0] // agrid[0]) + 1) * (-(-grid[1] // agrid[1]) + 1)      # tokens per window, upper bound
+    # one rounding to the storage type plus fp32 accumulation over the window
+    bound = np.abs(ref) * half_ulp * 1.01 + win * 4e-7 + (6e-8 if dtype == "f16" else 0.0)
+    assert np.all(np.abs(got - ref) <= bound), np.abs(got - ref).max()
+
+
+# --------------------------------------------------------------------------
+# a1 + a1b  aggregation and split merge
+# --------------------------------------------------------------------------
+AGG_SHAPES = [(196, 49, 32), (196, 49, 64), (3136, 49, 32), (1000, 256, 40), (777, 130, 64), (1, 1, 8),
+              (15, 9, 8), (197, 16, 72), (200, 81, 128), (2048, 1024, 64)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("N,n,d", AGG_SHAPES)
+def test_aggregate(aa, oracle, N, n, d, dtype):
+    import torch
+    units = 2
+    a = inputs.make_tensor((units, n, d), stream=110, dtype=dtype, std=0.7)
+    k = inputs.make_tensor((units, N, d), stream=111, dtype=dtype)
+    v = inputs.make_tensor((units, N, d), stream=112, dtype=dtype)
+    ref = np.stack([oracle.softmax_attention(inputs.to_float64(a[u], dtype), inputs.to_float64(k[u], dtype),
+                                             inputs.to_float64(v[u], dtype), None, scale=d ** -0.5)
+                    for u in range(units)])
+    dA, dK, dV = (util.to_device(x, dtype, (1, units, x.shape[1], d)) for x in (a, k, v))
+    results = []
+    for S in (0, 1, 2, 3, 7):
+        if S > N:
+            continue
+        VA = aa.agent_aggregate_fwd(dA, dK, dV, n_splits=S)
+        assert VA.dtype == torch.float32
+        got = util.to_host64(VA).reshape(ref.shape)
+        util.assert_parity(got, ref, dtype, "aggregate N=%d n=%d d=%d S=%d" % (N, n, d, S))
+        results.append(got)
+
+
+def test_aggregate_peaky_and_offset(aa, oracle):
+    """Scores with a large spread (running-max rescale), values with a large mean, a near one-hot row."""
+    N, n, d, dtype = 1500, 49, 32, "bf16"
+    a = inputs.make_tensor((1, n, d), stream=120, dtype=dtype, std=3.0)
+    k = inputs.make_tensor((1, N, d), stream=121, dtype=dtype, std=3.0)
+    v = inputs.make_tensor((1, N, d), stream=122, dtype=dtype, mean=10.0)
+    k64 = inputs.to_float64(k, dtype)
+    k64[0, 1234] = 2.0 * inputs.to_float64(a, dtype)[0, 5]
+    k = inputs.to_storage(k64.astype(np.float32), dtype)
+    ref = oracle.softmax_attention(inputs.to_float64(a[0], dtype), inputs.to_float64(k[0], dtype),
+                                   inputs.to_float64(v[0], dtype), None, scale=d ** -0.5)
+    for S in (1, 4, 0):
+        VA = aa.agent_aggregate_fwd(*(util.to_device(x, dtype, (1, 1, x.shape[1], d)) for x in (a, k, v)), n_splits=S)
+        # values are O(10): the absolute bar scales with them, the relative one does not
+        util.assert_parity(util.to_host64(VA)[0, 0], ref, dtype, "peaky S=%d" % S, max_abs=0.1)
+
+
+# --------------------------------------------------------------------------
+# a2  broadcast
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("N,n,d", AGG_SHAPES)
+def test_broadcast(aa, oracle, N, n, d, dtype):
+    units = 2
+    q = inputs.make_tensor((units, N, d), stream=130, dtype=dtype)
+    a = inputs.make_tensor((units, n, d), stream=131, dtype=dtype, std=0.7)
+    va = inputs.make_tensor((units, n, d), stream=132, dtype="f32")
+    ref = np.stack([oracle.softmax_attention(inputs.to_float64(q[u], dtype), inputs.to_float64(a[u], dtype),
+                                             va[u].astype(np.float64), None, scale=d ** -0.5) for u in range(units)])
+    O = aa.agent_broadcast_fwd(util.to_device(q, dtype, (1, units, N, d)), util.to_device(a, dtype, (1, units, n, d)),
+                               util.to_device(va, "f32", (1, units, n, d)))
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, dtype, "broadcast N=%d n=%d d=%d" % (N, n, d))
+
+
+# --------------------------------------------------------------------------
+# whole path, pure mode: the five evaluation workloads
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("name,batch", [("tiny", 1), ("deit_t", 4), ("swin_t_s1", 1), ("sd_latent", 1)])
+def test_forward_pure_elementwise(aa, oracle, name, batch):
+    """Every output element, at the workload's per-unit shape with a reduced batch."""
+    wl = small(WL[name], batch)
+    t = inputs.make_qkv(wl)
+    dv = dev_qkv(wl, t)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid)
+    ref = oracle.agent_attn_fwd(*(inputs.to_float64(t[k], wl.dtype) for k in ("Q", "K", "V")), heads=wl.heads,
+                                grid=wl.grid, agent_grid=wl.agent_grid)
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, wl.dtype, name)
+
+
+@pytest.mark.parametrize("name,n_units,n_rows", [("deit_t", 24, None), ("swin_t_s1", 6, 512), ("sd_latent", 4, 1024),
+                                                 ("highres", 2, 1024)])
+def test_forward_pure_full_size_sampled(aa, oracle, name, n_units, n_rows):
+    """Full workload on the GPU (the launch configuration bench.py times); oracle on sampled units and rows."""
+    wl = WL[name]
+    t = inputs.make_qkv(wl)
+    dv = dev_qkv(wl, t)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid)
+    got = util.to_host64(O).reshape(wl.units, wl.N, wl.d)
+    assert np.all(np.isfinite(got))
+    rng = np.random.default_rng(7)
+    unit_ids = sorted(rng.choice(wl.units, size=n_units, replace=False).tolist())
+    rows = None if n_rows is None else np.sort(rng.choice(wl.N, size=n_rows, replace=False))
+    ref = util.oracle_forward_units(oracle, wl, t, unit_ids, rows=rows)
+    sel = got[unit_ids] if rows is None else got[unit_ids][:, rows]
+    util.assert_parity(sel, ref, wl.dtype, name + " full size")
+    # property that holds at any size (pure mode): outputs are convex combinations of V rows
+    v64 = inputs.to_float64(t["V"], wl.dtype)
+    slack = {"f32": 1e-5, "f16": 2e-3, "bf16": 1e-2}[wl.dtype]
+    assert np.all(got <= v64.max(axis=1, keepdims=True) + slack)
+    assert np.all(got >= v64.min(axis=1, keepdims=True) - slack)
+
+
+def test_forward_is_deterministic(aa):
+    import torch
+    wl = small(WL["swin_t_s1"], 2)
+    dv = dev_qkv(wl, inputs.make_qkv(wl))
+    outs = [aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid) for _ in range(3)]
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+def test_forward_ignores_workspace_contents(aa):
+    import torch
+    wl = small(WL["deit_t"], 2)
+    dv = dev_qkv(wl, inputs.make_qkv(wl))
+    desc = aa.make_desc(wl.batch, wl.heads, wl.N, wl.n, wl.d, aa.AA_BF16, wl.grid, wl.agent_grid)
+    nbytes = aa.workspace_bytes(desc)
+    ws_nan = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda").view(torch.uint8)
+    ws_zero = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    o1 = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid, workspace=ws_nan)
+    o2 = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid, workspace=ws_zero)
+    assert torch.equal(o1, o2) and bool(torch.isfinite(o1.float()).all())
+
+
+# --------------------------------------------------------------------------
+# explicit agents (learned / external agents, Sec. 4.1)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_forward_with_explicit_agents(aa, oracle, dtype):
+    B, H, N, n, d = 2, 2, 300, 20, 48
+    q, k, v = (inputs.make_tensor((B * H, N, d), stream=140 + i, dtype=dtype) for i in range(3))
+    a = inputs.make_tensor((B * H, n, d), stream=143, dtype=dtype)
+    O = aa.agent_attn_fwd(*(util.to_device(x, dtype, (B, H, x.shape[1], d)) for x in (q, k, v, a)))
+    ref = oracle.agent_attn_fwd(*(inputs.to_float64(x, dtype) for x in (q, k, v)), heads=H,
+                                A=inputs.to_float64(a, dtype))
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, dtype, "explicit agents")
+
+
+# --------------------------------------------------------------------------
+# a3 + a4  module mode: agent bias (Appendix B) and DWC (Eq. (6)); SD variant (Appendix C.1)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("name,batch,bias_std", [("tiny", 1, 0.5), ("deit_t", 2, 0.5), ("deit_t", 2, 2.0),
+                                                 ("swin_t_s1", 1, 0.5), ("sd_latent", 1, 0.5)])
+def test_forward_module_mode(aa, oracle, name, batch, bias_std):
+    wl = small(WL[name], batch)
+    t = inputs.make_qkv(wl)
+    params = inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, index=wl.index, bias_std=bias_std)
+    dv = dev_qkv(wl, t)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid,
+                          params=util.params_to_device(params))
+    ref = util.oracle_forward_units(oracle, wl, t, list(range(wl.units)), params=params)
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, wl.dtype, name + " module")
+    pure = util.oracle_forward_units(oracle, wl, t, [0])
+    assert np.abs(pure[0] - ref[0]).max() > 0.05      # the module terms do change the result
+
+
+@pytest.mark.parametrize("which", ["b1_col", "b1_row", "b1_blk", "b2_col", "b2_row", "b2_blk", "dwc_w", "dwc_w+dwc_b"])
+def test_module_terms_one_at_a_time(aa, oracle, which):
+    import dataclasses
+    wl = dataclasses.replace(WL["deit_t"], batch=1, grid=(12, 10), agent_grid=(3, 5), d=24, dtype="f32")
+    t = inputs.make_qkv(wl)
+    full = inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, blk=(4, 3), index=5)
+    params = {k: full[k] for k in which.split("+")}
+    dv = dev_qkv(wl, t)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid,
+                          params=util.params_to_device(params))
+    ref = util.oracle_forward_units(oracle, wl, t, list(range(wl.units)), params=params)
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, "f32", which)
+
+
+def test_highres_module_mode_sampled(aa, oracle):
+    wl = WL["highres"]
+    t = inputs.make_qkv(wl)
+    params = inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, index=wl.index)
+    dv = dev_qkv(wl, t)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid,
+                          params=util.params_to_device(params))
+    rows = np.sort(np.random.default_rng(3).choice(wl.N, size=512, replace=False))
+    ref = util.oracle_forward_units(oracle, wl, t, [5], rows=rows, params=params)
+    util.assert_parity(util.to_host64(O).reshape(wl.units, wl.N, wl.d)[[5]][:, rows], ref, wl.dtype, "highres module")
+
+
+def test_stable_diffusion_variant(aa, oracle):
+    """Appendix C.1: O = sigma(QA^T) sigma(AK^T) V + k V with a larger scale on the second softmax."""
+    wl = small(WL["sd_latent"], 1)
+    t = inputs.make_qkv(wl)
+    dv = dev_qkv(wl, t)
+    kw = dict(scale2=wl.d ** -0.15, v_residual_k=0.075)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid, **kw)
+    ref = oracle.agent_attn_fwd(*(inputs.to_float64(t[k], wl.dtype) for k in ("Q", "K", "V")), heads=wl.heads,
+                                grid=wl.grid, agent_grid=wl.agent_grid, **kw)
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, wl.dtype, "sd variant")
+
+
+# --------------------------------------------------------------------------
+# stress distributions and shapes off the tile grid
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("scale_qk,v_mean", [(4.0, 0.0), (8.0, 0.0), (1.0, 10.0)])
+def test_forward_stress_distributions(aa, oracle, scale_qk, v_mean):
+    """Peaky softmaxes / offset values.  A is pooled and rounded to bf16 on the GPU, which the oracle
+    does not do; with scores this large that rounding alone moves the output by more than the
+    bar for the evaluation workloads, so the comparison feeds the GPU's own pooled A (checked
+    separately by test_pool) to both sides and keeps the standard bar."""
+    wl = small(WL["swin_t_s1"], 1)
+    t = inputs.make_qkv(wl, scale_qk=scale_qk, v_mean=v_mean)
+    dv = dev_qkv(wl, t)
+    A = aa.agent_pool_fwd(dv["Q"], grid=wl.grid, agent_grid=wl.agent_grid)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid)
+    O2 = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], A)
+    import torch
+    assert torch.equal(O, O2)
+    ref = oracle.agent_attn_fwd(*(inputs.to_float64(t[k], wl.dtype) for k in ("Q", "K", "V")), heads=wl.heads,
+                                A=util.to_host64(A).reshape(wl.units, wl.n, wl.d))
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, wl.dtype, "stress x%g mean %g" % (scale_qk, v_mean),
+                       max_abs=1e-2 * max(1.0, v_mean), rel_l2=5e-3 if scale_qk < 8 else 1e-2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("grid,agrid,d", [((1, 1), (1, 1), 8), ((3, 5), (3, 3), 8), ((1, 197), (1, 16), 40),
+                                          ((10, 20), (9, 9), 72), ((25, 8), (4, 4), 128), ((56, 56), (3, 3), 32),
+                                          ((28, 28), (4, 4), 64), ((14, 14), (9, 9), 64)])
+def test_forward_odd_shapes(aa, oracle, grid, agrid, d, dtype):
+    import dataclasses
+    wl = dataclasses.replace(WL["tiny"], batch=1, heads=2, grid=grid, agent_grid=agrid, d=d, dtype=dtype, index=9)
+    t = inputs.make_qkv(wl)
+    dv = dev_qkv(wl, t)
+    A = aa.agent_pool_fwd(dv["Q"], grid=grid, agent_grid=agrid)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=grid, agent_grid=agrid)
+    ref = oracle.agent_attn_fwd(*(inputs.to_float64(t[k], wl.dtype) for k in ("Q", "K", "V")), heads=wl.heads,
+                                A=util.to_host64(A).reshape(wl.units, wl.n, wl.d))
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, dtype, "odd shape %s %s %d" % (grid, agrid, d))
