@@ -89,20 +89,22 @@ class Ring:
             s["VA"] = torch.empty((wl.batch, wl.heads, wl.n, wl.d), dtype=torch.float32, device="cuda")
             self.sets.append(s)
 
+        b, p = binding, self.params
+        self.fwd = [b.prepare_fwd(s["Q"], s["K"], s["V"], grid=wl.grid, agent_grid=wl.agent_grid, params=p,
+                                  out=s["out"], workspace=s["ws"]) for s in self.sets]
+        self.stages = {
+            "pool": [b.prepare_pool(s["Q"], grid=wl.grid, agent_grid=wl.agent_grid, out=s["A"]) for s in self.sets],
+            "aggregate": [b.prepare_aggregate(s["A"], s["K"], s["V"], grid=wl.grid, params=p, out=s["VA"],
+                                              workspace=s["ws"]) for s in self.sets],
+            "broadcast": [b.prepare_broadcast(s["Q"], s["A"], s["VA"], s["V"], grid=wl.grid, params=p, out=s["out"])
+                          for s in self.sets],
+        }
+
     def forward(self, i):
-        s = self.sets[i % self.R]
-        return self.binding.agent_attn_fwd(s["Q"], s["K"], s["V"], grid=self.wl.grid, agent_grid=self.wl.agent_grid,
-                                           params=self.params, out=s["out"], workspace=s["ws"])
+        self.fwd[i % self.R]()
 
     def stage(self, name, i):
-        s, b, wl = self.sets[i % self.R], self.binding, self.wl
-        if name == "pool":
-            b.agent_pool_fwd(s["Q"], grid=wl.grid, agent_grid=wl.agent_grid, out=s["A"])
-        elif name == "aggregate":
-            b.agent_aggregate_fwd(s["A"], s["K"], s["V"], grid=wl.grid, params=self.params, out=s["VA"],
-                                  workspace=s["ws"])
-        else:
-            b.agent_broadcast_fwd(s["Q"], s["A"], s["VA"], s["V"], grid=wl.grid, params=self.params, out=s["out"])
+        self.stages[name][i % self.R]()
 
 
 def timed(fn, steps, warmup):

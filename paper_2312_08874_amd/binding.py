@@ -173,6 +173,62 @@ def agent_attn_fwd(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict 
     return out
 
 
+class PreparedCall:
+    """A C-ABI call with its arguments marshalled once; calling it only crosses the ABI.
+
+    Used by callers that issue the same call many times (serving loops, the benchmark): the
+    descriptor structs and pointer arguments are built up front, so one invocation costs one
+    ctypes call.  Holds references to every tensor involved so the pointers stay valid.
+    """
+
+    def __init__(self, fn, name, args, keep):
+        self._fn, self._name, self._args, self._keep = fn, name, args, keep
+
+    def __call__(self):
+        st = self._fn(*self._args)
+        if st != AA_OK:
+            raise AgentAttnError(st, self._name)
+
+
+def prepare_fwd(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict | None = None, scale1=0.0,
+                scale2=0.0, v_residual_k=0.0, n_splits=0, out, workspace=None, stream=None) -> PreparedCall:
+    n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
+    desc = _desc_from(Q, n, grid, agent_grid, scale1=scale1, scale2=scale2, v_residual_k=v_residual_k,
+                      n_splits=n_splits)
+    p = make_params(params)
+    workspace, need = _workspace(desc, p, workspace)
+    args = (ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(A), _pp(p), workspace.data_ptr(),
+            workspace.numel() * workspace.element_size(), out.data_ptr(), _stream(stream))
+    return PreparedCall(lib().agent_attn_fwd, "agent_attn_fwd", args, (desc, p, Q, K, V, A, params, workspace, out))
+
+
+def prepare_pool(Q, *, grid, agent_grid, out, stream=None) -> PreparedCall:
+    n = agent_grid[0] * agent_grid[1]
+    desc = _desc_from(Q, n, grid, agent_grid)
+    args = (ctypes.byref(desc), Q.data_ptr(), out.data_ptr(), _stream(stream))
+    return PreparedCall(lib().agent_pool_fwd, "agent_pool_fwd", args, (desc, Q, out))
+
+
+def prepare_aggregate(A, K, V, *, grid=None, params: dict | None = None, scale1=0.0, n_splits=0, out,
+                      workspace=None, stream=None) -> PreparedCall:
+    desc = _desc_from(K, A.shape[2], grid, None, scale1=scale1, n_splits=n_splits)
+    p = make_params(params)
+    workspace, need = _workspace(desc, p, workspace)
+    args = (ctypes.byref(desc), A.data_ptr(), K.data_ptr(), V.data_ptr(), _pp(p), workspace.data_ptr(),
+            workspace.numel() * workspace.element_size(), out.data_ptr(), _stream(stream))
+    return PreparedCall(lib().agent_aggregate_fwd, "agent_aggregate_fwd", args,
+                        (desc, p, A, K, V, params, workspace, out))
+
+
+def prepare_broadcast(Q, A, VA, V=None, *, grid=None, params: dict | None = None, scale2=0.0, v_residual_k=0.0,
+                      out, stream=None) -> PreparedCall:
+    desc = _desc_from(Q, A.shape[2], grid, None, scale2=scale2, v_residual_k=v_residual_k)
+    p = make_params(params)
+    args = (ctypes.byref(desc), Q.data_ptr(), A.data_ptr(), VA.data_ptr(), _ptr(V), _pp(p), out.data_ptr(),
+            _stream(stream))
+    return PreparedCall(lib().agent_broadcast_fwd, "agent_broadcast_fwd", args, (desc, p, Q, A, VA, V, params, out))
+
+
 def agent_pool_fwd(Q, *, grid, agent_grid, out=None, stream=None):
     import torch
     B, H, N, d = Q.shape

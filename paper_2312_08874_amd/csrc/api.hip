@@ -5,6 +5,8 @@
 
 #include <math.h>
 
+#include <initializer_list>
+
 #include "kernels.h"
 
 namespace {
@@ -20,8 +22,13 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 size_t elem_size(int dtype) { return dtype == AA_F32 ? 4 : 2; }
 
+enum Path { PATH_GENERIC = 0, PATH_SMALL_FUSED = 1, PATH_SMALL_SPLIT = 2 };
+
 struct Plan {
-  int S;               // N-splits of the aggregation
+  int S;               // N-splits of the generic aggregation
+  int S_small;         // N-splits of the small-agent MFMA aggregation
+  int bcast_chunks;    // token chunks per unit of the small-agent broadcast
+  bool prefer_fused;   // small-agent regime: one block per unit does the whole pass
   size_t off_A;        // pooled agents, element type of the problem
   size_t off_acc, off_m, off_l;
   size_t off_VA;       // merged V_A, fp32
@@ -46,6 +53,7 @@ aa_status check_desc(const aa_desc* d, bool need_grid, bool need_agent_grid) {
   const int64_t units = (int64_t)d->batch * d->heads;
   if (units > 65535) return AA_ERR_UNSUPPORTED;
   if (d->d > kMaxD) return AA_ERR_UNSUPPORTED;
+  if (d->grid_h > 65535 || d->grid_w > 65535) return AA_ERR_UNSUPPORTED;   // 32-bit window arithmetic
   if ((int64_t)units * d->N * d->d >= (int64_t)1 << 40) return AA_ERR_UNSUPPORTED;
   // only dense [B,H,N,d] tensors
   const int64_t sn = d->d, sh = (int64_t)d->N * d->d, sb = sh * d->heads;
@@ -86,19 +94,39 @@ int choose_splits(const aa_desc* d) {
   return S;
 }
 
+// Splits / chunks of the small-agent path.  An explicit n_splits forces the multi-kernel path
+// with that many splits (rounded so that every split is a non-empty multiple of 32 tokens).
+void plan_small(const aa_desc* d, Plan& pl) {
+  const int64_t units = (int64_t)d->batch * d->heads;
+  int S = d->n_splits;
+  pl.prefer_fused = (S <= 0);   // taken when the unit's Q rows fit in LDS, see run time check
+  if (S <= 0) {
+    S = (int)((512 + units - 1) / units);
+    const int max_by_len = (d->N + 127) / 128;
+    if (S > max_by_len) S = max_by_len;
+  }
+  if (S > d->N) S = d->N;
+  if (S < 1) S = 1;
+  const int chunk = aa::small_split_chunk(d->N, S);
+  pl.S_small = (d->N + chunk - 1) / chunk;
+  pl.bcast_chunks = (d->N + 511) / 512;
+}
+
 Plan make_plan(const aa_desc* d) {
   Plan pl{};
   const size_t units = (size_t)d->batch * d->heads;
   pl.S = choose_splits(d);
+  plan_small(d, pl);
+  const int Smax = pl.S > pl.S_small ? pl.S : pl.S_small;
   size_t off = 0;
   pl.off_A = off;
   off += align_up(units * d->n * d->d * elem_size(d->dtype));
   pl.off_acc = off;
-  off += align_up(units * pl.S * d->n * d->d * sizeof(float));
+  off += align_up(units * Smax * d->n * d->d * sizeof(float));
   pl.off_m = off;
-  off += align_up(units * pl.S * d->n * sizeof(float));
+  off += align_up(units * Smax * d->n * sizeof(float));
   pl.off_l = off;
-  off += align_up(units * pl.S * d->n * sizeof(float));
+  off += align_up(units * Smax * d->n * sizeof(float));
   pl.off_VA = off;
   off += align_up(units * d->n * d->d * sizeof(float));
   pl.total = off;
@@ -136,9 +164,19 @@ bool overlaps(const void* a, size_t abytes, const void* b, size_t bbytes) {
   return a0 < b0 + bbytes && b0 < a0 + abytes;
 }
 
-Partials partials_in(void* ws, const Plan& pl) {
+Partials partials_in(void* ws, const Plan& pl, int S) {
   char* base = (char*)ws;
-  return Partials{(float*)(base + pl.off_acc), (float*)(base + pl.off_m), (float*)(base + pl.off_l), pl.S};
+  return Partials{(float*)(base + pl.off_acc), (float*)(base + pl.off_m), (float*)(base + pl.off_l), S};
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+// The MFMA kernels use 16-byte vector accesses on every tensor.
+bool use_small(const Problem& pr, std::initializer_list<const void*> ptrs) {
+  if (!aa::small_supported(pr)) return false;
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return false;
+  return true;
 }
 
 aa_status check_workspace(const void* ws, size_t bytes, const Plan& pl) {
@@ -151,10 +189,34 @@ aa_status check_workspace(const void* ws, size_t bytes, const Plan& pl) {
     if ((call) != hipSuccess) return AA_ERR_HIP; \
   } while (0)
 
-aa_status run_aggregate(const Problem& pr, const void* A, const void* K, const void* V, const Partials& part,
+aa_status run_aggregate(const Problem& pr, const void* A, const void* K, const void* V, void* ws, const Plan& pl,
                         float* VA, hipStream_t st) {
+  if (use_small(pr, {A, K, V})) {
+    const Partials part = partials_in(ws, pl, pl.S_small);
+    AA_HIP(aa::launch_small_aggregate(pr, A, K, V, part, st));
+    AA_HIP(aa::launch_small_merge(pr, part, VA, st));
+    return AA_OK;
+  }
+  const Partials part = partials_in(ws, pl, pl.S);
   AA_HIP(aa::launch_aggregate_generic(pr, A, K, V, part, st));
   AA_HIP(aa::launch_merge_generic(pr, part, VA, st));
+  return AA_OK;
+}
+
+aa_status run_broadcast(const Problem& pr, const void* Q, const void* A, const float* VA, const void* V, void* out,
+                        const Plan& pl, hipStream_t st) {
+  if (use_small(pr, {Q, A, V, out}))
+    AA_HIP(aa::launch_small_broadcast(pr, Q, A, VA, V, out, pl.bcast_chunks, st));
+  else
+    AA_HIP(aa::launch_broadcast_generic(pr, Q, A, VA, V, out, st));
+  return AA_OK;
+}
+
+aa_status run_pool(const Problem& pr, const void* Q, void* A, hipStream_t st) {
+  if (use_small(pr, {Q, A}))
+    AA_HIP(aa::launch_small_pool(pr, Q, A, st));
+  else
+    AA_HIP(aa::launch_pool_generic(pr, Q, A, st));
   return AA_OK;
 }
 
@@ -181,8 +243,7 @@ aa_status agent_pool_fwd(const aa_desc* desc, const void* Q, void* A_out, void* 
   const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
   if (overlaps(A_out, units * desc->n * desc->d * es, Q, units * desc->N * desc->d * es)) return AA_ERR_ALIAS;
   Problem pr = make_problem(desc, nullptr);
-  AA_HIP(aa::launch_pool_generic(pr, Q, A_out, (hipStream_t)hip_stream));
-  return AA_OK;
+  return run_pool(pr, Q, A_out, (hipStream_t)hip_stream);
 }
 
 aa_status agent_aggregate_fwd(const aa_desc* desc, const void* A, const void* K, const void* V,
@@ -206,7 +267,7 @@ aa_status agent_aggregate_fwd(const aa_desc* desc, const void* A, const void* K,
     return AA_ERR_ALIAS;
   Problem pr = make_problem(desc, params);
   pr.b2 = aa::BiasArgs{};
-  return run_aggregate(pr, A, K, V, partials_in(workspace, pl), VA_out, (hipStream_t)hip_stream);
+  return run_aggregate(pr, A, K, V, workspace, pl, VA_out, (hipStream_t)hip_stream);
 }
 
 aa_status agent_broadcast_fwd(const aa_desc* desc, const void* Q, const void* A, const float* VA, const void* V,
@@ -227,8 +288,7 @@ aa_status agent_broadcast_fwd(const aa_desc* desc, const void* Q, const void* A,
     return AA_ERR_ALIAS;
   Problem pr = make_problem(desc, params);
   pr.b1 = aa::BiasArgs{};
-  AA_HIP(aa::launch_broadcast_generic(pr, Q, A, VA, V, out, (hipStream_t)hip_stream));
-  return AA_OK;
+  return run_broadcast(pr, Q, A, VA, V, out, make_plan(desc), (hipStream_t)hip_stream);
 }
 
 aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, const void* V, const void* A,
@@ -256,16 +316,20 @@ aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, cons
   const Problem pr = make_problem(desc, params);
   hipStream_t stream = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
+  if (pl.prefer_fused && aa::small_fused_supported(pr) && use_small(pr, {Q, K, V, A, out})) {
+    AA_HIP(aa::launch_small_fused(pr, Q, K, V, A, out, stream));
+    return AA_OK;
+  }
   const void* agents = A;
   if (pooling) {
-    AA_HIP(aa::launch_pool_generic(pr, Q, ws + pl.off_A, stream));
+    st = run_pool(pr, Q, ws + pl.off_A, stream);
+    if (st != AA_OK) return st;
     agents = ws + pl.off_A;
   }
   float* VA = (float*)(ws + pl.off_VA);
-  st = run_aggregate(pr, agents, K, V, partials_in(workspace, pl), VA, stream);
+  st = run_aggregate(pr, agents, K, V, workspace, pl, VA, stream);
   if (st != AA_OK) return st;
-  AA_HIP(aa::launch_broadcast_generic(pr, Q, agents, VA, V, out, stream));
-  return AA_OK;
+  return run_broadcast(pr, Q, agents, VA, V, out, pl, stream);
 }
 
 const char* agent_attn_status_str(int status) {

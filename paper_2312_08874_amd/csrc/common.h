@@ -93,6 +93,13 @@ __device__ __forceinline__ float bias2_at(const BiasArgs& b, int a, int y, int x
   return v;
 }
 
+// Pooling window of output index i along an axis of length L pooled to La (Sec. 4.2):
+// [floor(i*L/La), ceil((i+1)*L/La)).  32-bit unsigned arithmetic: (i+1)*L < 2^32 for L, La <= 65535.
+__device__ __forceinline__ int pool_win_lo(int i, int L, int La) { return (int)(((unsigned)i * (unsigned)L) / (unsigned)La); }
+__device__ __forceinline__ int pool_win_hi(int i, int L, int La) {
+  return (int)((((unsigned)i + 1u) * (unsigned)L + (unsigned)La - 1u) / (unsigned)La);
+}
+
 // wave64 reductions
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll

@@ -10,10 +10,6 @@ namespace aa {
 constexpr int kWaves = 4;             // waves per block in aggregate / broadcast
 constexpr int kMaxDPerLane = 4;       // d <= 64 * kMaxDPerLane
 
-__device__ __forceinline__ int win_lo(int i, int L, int La) { return (int)(((long long)i * L) / La); }
-__device__ __forceinline__ int win_hi(int i, int L, int La) {
-  return (int)((((long long)(i + 1)) * L + La - 1) / La);
-}
 
 // ---------------------------------------------------------------------------
 // A = Pooling(Q) (Sec. 4.2): block = one agent of one unit, thread = channel.
@@ -24,8 +20,8 @@ __global__ __launch_bounds__(64) void pool_generic_kernel(const typename E::T* _
                                                           int gh, int gw, int ah, int aw) {
   const int a = blockIdx.x, u = blockIdx.y;
   const int ay = a / aw, ax = a % aw;
-  const int y0 = win_lo(ay, gh, ah), y1 = win_hi(ay, gh, ah);
-  const int x0 = win_lo(ax, gw, aw), x1 = win_hi(ax, gw, aw);
+  const int y0 = pool_win_lo(ay, gh, ah), y1 = pool_win_hi(ay, gh, ah);
+  const int x0 = pool_win_lo(ax, gw, aw), x1 = pool_win_hi(ax, gw, aw);
   const float inv = 1.0f / (float)((y1 - y0) * (x1 - x0));
   const typename E::T* q = Q + (size_t)u * N * d;
   for (int c = threadIdx.x; c < d; c += 64) {

@@ -39,4 +39,22 @@ hipError_t launch_broadcast_generic(const Problem& p, const void* Q, const void*
 // dynamic LDS the generic broadcast needs for this problem (bytes)
 size_t broadcast_generic_lds_bytes(int n, int d);
 
+// --- small-agent regime (n <= 64, d in {32, 64}, fp16 / bf16): MFMA kernels that keep A and V_A in
+//     registers and stream tokens straight from global memory ---
+bool small_supported(const Problem& p);
+// true when the one-block-per-unit kernel applies (the unit's Q rows fit in LDS)
+bool small_fused_supported(const Problem& p);
+// whole forward pass, one block per (batch, head) unit; A == nullptr pools Q
+hipError_t launch_small_fused(const Problem& p, const void* Q, const void* K, const void* V, const void* A,
+                              void* out, hipStream_t st);
+hipError_t launch_small_pool(const Problem& p, const void* Q, void* A, hipStream_t st);
+// tokens per split (multiple of 32) the split-N aggregation uses for S requested splits
+int small_split_chunk(int N, int S);
+// part.S must equal ceil(N / small_split_chunk(N, S_requested)); m is stored in the log2 domain
+hipError_t launch_small_aggregate(const Problem& p, const void* A, const void* K, const void* V,
+                                  const Partials& part, hipStream_t st);
+hipError_t launch_small_merge(const Problem& p, const Partials& part, float* VA, hipStream_t st);
+hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A, const float* VA, const void* V,
+                                  void* out, int chunks, hipStream_t st);
+
 }  // namespace aa

@@ -1,0 +1,1041 @@
+// MFMA kernels for the small-agent regime (n <= 64, d in {32, 64}, fp16 / bf16).
+//
+// With at most 64 agents the agent matrix A and the agent features V_A are a few
+// KB: each wave keeps them in registers as stationary MFMA operands and streams its
+// own tokens straight from global memory -- K, V and Q tiles are never staged in
+// LDS.  LDS only carries A, V_A and the cross-wave merge of the online-softmax
+// state.  All products are v_mfma_f32_16x16x32 with fp32 accumulation.
+//
+// Lane conventions (r = lane % 16, g = lane / 16):
+//   A/B operand of a 16x16x32 MFMA: lane holds row/col r and the 8 k-values of
+//   group g; C/D: lane holds column r and rows 4g..4g+3.
+// Because a C tile already has "column r, 4 consecutive rows", two score tiles can
+// be fed back as the 8 k-values of the next product's B operand without leaving
+// the lane; the other operand (V or V_A) is arranged to use the same k order:
+//   k-slot 8g+j  <->  row 4g+j of the first tile (j<4) / row 4g+j-4 of the second.
+//
+// Stages (Sec. 4.1 Eq. (3); bias of Eq. (5); DWC of Eq. (6); k*V of Appendix C.1):
+//   pool      A = Pooling(Q)                       (Sec. 4.2)
+//   aggregate V_A^T += V^T P1^T,  P1^T = exp2(K A^T * c - m)   running max per agent
+//   broadcast O^T = V_A^T P2^T,   P2^T = softmax over agents of (A Q^T * c)
+#include "kernels.h"
+
+namespace aa {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+template <class E>
+struct Mx;
+template <>
+struct Mx<ElemBF16> {
+  static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                   0, 0, 0);
+  }
+  static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+  }
+  static __device__ __forceinline__ void unpack2(uint32_t w, float& lo, float& hi) {
+    lo = __uint_as_float(w << 16);
+    hi = __uint_as_float(w & 0xFFFF0000u);
+  }
+};
+template <>
+struct Mx<ElemF16> {
+  static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0,
+                                                  0, 0);
+  }
+  static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+  }
+  static __device__ __forceinline__ void unpack2(uint32_t w, float& lo, float& hi) {
+    f16x2 h = __builtin_bit_cast(f16x2, w);
+    lo = (float)h[0];
+    hi = (float)h[1];
+  }
+};
+
+constexpr float kNegBig = -1.0e30f;   // finite stand-in for "no maximum yet"
+constexpr int kMaxWaves = 8;          // waves per block (launch bound 512 threads -> up to 256 VGPRs)
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float xor16_32_max(float v) {
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  return fmaxf(v, __shfl_xor(v, 32, 64));
+}
+__device__ __forceinline__ float xor16_32_sum(float v) {
+  v += __shfl_xor(v, 16, 64);
+  return v + __shfl_xor(v, 32, 64);
+}
+
+// Geometry shared by the kernels of one instantiation.
+template <int D, int NAT>
+struct Geo {
+  static constexpr int KC = D / 32;          // k-chunks of the score products (contraction over d)
+  static constexpr int EV = D / 16;          // 16-row tiles along d in the value products
+  static constexpr int KS = (NAT + 1) / 2;   // k-steps (pairs of agent tiles) of the broadcast value product
+  static constexpr int AS = D + 8;           // LDS row stride (elements) of A and V_A
+  static constexpr int NREG = EV * NAT * 4 + 2 * NAT;   // floats per lane of an aggregation state
+};
+
+template <int D, int NAT>
+struct AggState {
+  float m[NAT];                     // running maximum (log2 domain), equal in the 4 lanes sharing r
+  float l[NAT];                     // per-lane partial of the running denominator
+  f32x4 acc[D / 16][NAT];           // V_A^T tiles: acc[e][at][i] <-> agent 16at+r, channel (D/16)*(4g+i)+e
+};
+
+// ---------------------------------------------------------------------------
+// pooling (Sec. 4.2): one wave averages the window of one agent.  Lanes split into D/8 chunks of 8
+// channels times 64/(D/8) token lanes; up to four window tokens per token lane are loaded before any
+// is used, then the token lanes are summed with shuffles.  Returns the 8 pooled channels of this
+// lane's chunk, packed (valid in the lanes with token lane 0).  `src` is global memory or LDS.
+// ---------------------------------------------------------------------------
+template <class E, int D>
+__device__ __forceinline__ u32x4 pool_agent(const uint16_t* src, int row_stride, int a, int gh, int gw, int ah,
+                                            int aw, int lane) {
+  constexpr int CH = D / 8, TL = 64 / CH;
+  const int chunk = lane % CH, tl = lane / CH;
+  const int ay = a / aw, ax = a - ay * aw;
+  const int y0 = pool_win_lo(ay, gh, ah), y1 = pool_win_hi(ay, gh, ah);
+  const int x0 = pool_win_lo(ax, gw, aw), x1 = pool_win_hi(ax, gw, aw);
+  const int ww = x1 - x0, cnt = (y1 - y0) * ww;
+  const float inv_ww = 1.0f / (float)ww;     // idx / ww by reciprocal: exact for idx < 2^20
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int base = 0; base < cnt; base += 4 * TL) {
+    u32x4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int idx = base + k * TL + tl;
+      v[k] = u32x4{0, 0, 0, 0};
+      if (idx < cnt) {
+        const int yy = (int)(((float)idx + 0.5f) * inv_ww);
+        const int t = (y0 + yy) * gw + x0 + (idx - yy * ww);
+        v[k] = *(const u32x4*)(src + (size_t)t * row_stride + 8 * chunk);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float lo, hi;
+        Mx<E>::unpack2(v[k][q], lo, hi);
+        acc[2 * q] += lo;
+        acc[2 * q + 1] += hi;
+      }
+  }
+#pragma unroll
+  for (int o = CH; o < 64; o <<= 1)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[k] += __shfl_xor(acc[k], o, 64);
+  const float inv = 1.0f / (float)cnt;
+  u32x4 w;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) w[k] = Mx<E>::pack2(acc[2 * k] * inv, acc[2 * k + 1] * inv);
+  return w;
+}
+
+// pooled agents of one unit, from the unit's Q rows in LDS, into LDS rows (rounded to the element
+// type), zero padded to 16*NAT rows.  One thread per (agent, 8-channel chunk) walks the window serially:
+// LDS latency is short and the windows of units that fit in LDS are small.
+template <class E, int D, int NAT>
+__device__ __forceinline__ void pool_unit_to_lds(const uint16_t* Q_lds, int row_stride, uint16_t* A_lds, int n, int gh,
+                                                 int gw, int ah, int aw, int tid, int nthreads) {
+  constexpr int CH = D / 8, AS = Geo<D, NAT>::AS;
+  for (int item = tid; item < 16 * NAT * CH; item += nthreads) {
+    const int a = item / CH, chunk = item % CH;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    float inv = 0.0f;
+    if (a < n) {
+      const int ay = a / aw, ax = a - ay * aw;
+      const int y0 = pool_win_lo(ay, gh, ah), y1 = pool_win_hi(ay, gh, ah);
+      const int x0 = pool_win_lo(ax, gw, aw), x1 = pool_win_hi(ax, gw, aw);
+      inv = 1.0f / (float)((y1 - y0) * (x1 - x0));
+      for (int y = y0; y < y1; ++y)
+        for (int x = x0; x < x1; ++x) {
+          const u32x4 v = *(const u32x4*)(Q_lds + (y * gw + x) * row_stride + 8 * chunk);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float lo, hi;
+            Mx<E>::unpack2(v[q], lo, hi);
+            acc[2 * q] += lo;
+            acc[2 * q + 1] += hi;
+          }
+        }
+    }
+    u32x4 w;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) w[k] = Mx<E>::pack2(acc[2 * k] * inv, acc[2 * k + 1] * inv);
+    *(u32x4*)(A_lds + a * AS + 8 * chunk) = w;
+  }
+}
+
+// copy given agents of one unit into LDS rows, zero padded
+template <int D, int NAT>
+__device__ __forceinline__ void load_agents_to_lds(const uint16_t* __restrict__ Au, uint16_t* A_lds, int n, int tid,
+                                                   int nthreads) {
+  constexpr int CH = D / 8, AS = Geo<D, NAT>::AS;
+  for (int q = tid; q < 16 * NAT * CH; q += nthreads) {
+    const int a = q / CH, chunk = q - a * CH;
+    u32x4 w = {0, 0, 0, 0};
+    if (a < n) w = *(const u32x4*)(Au + (size_t)a * D + 8 * chunk);
+    *(u32x4*)(A_lds + a * AS + 8 * chunk) = w;
+  }
+}
+
+// stationary A operand: areg[at][kc] = A[16at + r][32kc + 8g .. +7]
+template <int D, int NAT>
+__device__ __forceinline__ void load_a_regs(const uint16_t* A_lds, u32x4 (&areg)[NAT][D / 32], int lane) {
+  constexpr int AS = Geo<D, NAT>::AS;
+  const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int at = 0; at < NAT; ++at)
+#pragma unroll
+    for (int kc = 0; kc < D / 32; ++kc) areg[at][kc] = *(const u32x4*)(A_lds + (16 * at + r) * AS + 32 * kc + 8 * g);
+}
+
+// ---------------------------------------------------------------------------
+// aggregation: one step = 32 tokens [t0, t0+32) of one unit, all 16*NAT agents
+// ---------------------------------------------------------------------------
+// K / V registers of one step.  kop[rt][kc] = K[t0 + 16rt + r][32kc + 8g .. +7]; vraw[j] = channels
+// [EV*r, EV*r + EV) of the token row of k-slot j (4g+j for j<4, 16+4g+j-4 otherwise).  Rows are clamped
+// to N-1; the tokens beyond N are masked in agg_compute.
+template <int D>
+struct KVRegs {
+  u32x4 kop[2][D / 32];
+  uint32_t vraw[8][D / 32];
+};
+
+template <int D>
+__device__ __forceinline__ void agg_load(const uint16_t* __restrict__ Ku, const uint16_t* __restrict__ Vu, int t0,
+                                         int N, int lane, KVRegs<D>& kv) {
+  constexpr int KC = D / 32, EV = D / 16;
+  const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) {
+    const int row = min(t0 + 16 * rt + r, N - 1);
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) kv.kop[rt][kc] = *(const u32x4*)(Ku + (size_t)row * D + 32 * kc + 8 * g);
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int row = min(t0 + (j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4)), N - 1);
+    const uint16_t* p = Vu + (size_t)row * D + EV * r;
+    if constexpr (EV == 2) {
+      kv.vraw[j][0] = *(const uint32_t*)p;
+    } else {
+      const u32x2 w = *(const u32x2*)p;
+      kv.vraw[j][0] = w[0];
+      kv.vraw[j][1] = w[1];
+    }
+  }
+}
+
+template <class E, int D, int NAT, bool BIAS>
+__device__ __forceinline__ void agg_compute(const KVRegs<D>& kv, int t0, int N, int n,
+                                            const u32x4 (&areg)[NAT][D / 32], AggState<D, NAT>& st, float sc,
+                                            int lane, const BiasArgs& b1, int gh, int gw) {
+  constexpr int KC = D / 32, EV = D / 16;
+  const int r = lane & 15, g = lane >> 4;
+
+  // scores S^T = K A^T : tile (rt, at), element i <-> token t0+16rt+4g+i, agent 16at+r
+  f32x4 s[2][NAT];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int at = 0; at < NAT; ++at) {
+      f32x4 c = {0, 0, 0, 0};
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) c = Mx<E>::mma(kv.kop[rt][kc], areg[at][kc], c);
+      s[rt][at] = c;
+    }
+
+  float mnew[NAT];
+  bool grew = false;
+#pragma unroll
+  for (int at = 0; at < NAT; ++at) {
+    float mx = kNegBig;
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int tok = t0 + 16 * rt + 4 * g + i;
+        float v = s[rt][at][i] * sc;
+        if constexpr (BIAS) {
+          const int tc = min(tok, N - 1);
+          v += kLog2e * bias1_at(b1, min(16 * at + r, n - 1), tc / gw, tc % gw, gh, gw);
+        }
+        v = tok < N ? v : -INFINITY;
+        s[rt][at][i] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = xor16_32_max(mx);
+    mnew[at] = fmaxf(st.m[at], mx);
+    grew |= mnew[at] > st.m[at];
+  }
+  if (__any(grew)) {
+#pragma unroll
+    for (int at = 0; at < NAT; ++at) {
+      const float alpha = fast_exp2(st.m[at] - mnew[at]);
+      st.m[at] = mnew[at];
+      st.l[at] *= alpha;
+#pragma unroll
+      for (int e = 0; e < EV; ++e) st.acc[e][at] *= alpha;
+    }
+  }
+
+  // probabilities, packed as the B operand of the value product
+  u32x4 pk[NAT];
+#pragma unroll
+  for (int at = 0; at < NAT; ++at) {
+    float p[2][4];
+    float sum = 0.0f;
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        p[rt][i] = fast_exp2(s[rt][at][i] - st.m[at]);
+        sum += p[rt][i];
+      }
+    st.l[at] += sum;
+    pk[at][0] = Mx<E>::pack2(p[0][0], p[0][1]);
+    pk[at][1] = Mx<E>::pack2(p[0][2], p[0][3]);
+    pk[at][2] = Mx<E>::pack2(p[1][0], p[1][1]);
+    pk[at][3] = Mx<E>::pack2(p[1][2], p[1][3]);
+  }
+
+  // V_A^T += V^T P^T : operand e holds channel EV*r + e of the 8 k-slot rows
+#pragma unroll
+  for (int e = 0; e < EV; ++e) {
+    u32x4 vop;
+    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) vop[jj] = __builtin_amdgcn_perm(kv.vraw[2 * jj + 1][e / 2], kv.vraw[2 * jj][e / 2], sel);
+#pragma unroll
+    for (int at = 0; at < NAT; ++at) st.acc[e][at] = Mx<E>::mma(vop, pk[at], st.acc[e][at]);
+  }
+}
+
+// Walk the steps t0 = first, first + stride, ... < end with the next step's K/V loads in flight
+// while the current step is computed.  `cur` already holds the loads of step `first` (if first < end).
+template <class E, int D, int NAT, bool BIAS>
+__device__ __forceinline__ void agg_range(const uint16_t* __restrict__ Ku, const uint16_t* __restrict__ Vu,
+                                          KVRegs<D>& cur, int first, int stride, int end, int n,
+                                          const u32x4 (&areg)[NAT][D / 32], AggState<D, NAT>& st, float sc, int lane,
+                                          const BiasArgs& b1, int gh, int gw) {
+  for (int t0 = first; t0 < end; t0 += stride) {
+    KVRegs<D> nxt;
+    const int tn = t0 + stride;
+    if (tn < end) agg_load<D>(Ku, Vu, tn, end, lane, nxt);
+    agg_compute<E, D, NAT, BIAS>(cur, t0, end, n, areg, st, sc, lane, b1, gh, gw);
+    if (tn < end) cur = nxt;
+  }
+}
+
+template <int D, int NAT>
+__device__ __forceinline__ void agg_init(AggState<D, NAT>& st) {
+#pragma unroll
+  for (int at = 0; at < NAT; ++at) {
+    st.m[at] = kNegBig;
+    st.l[at] = 0.0f;
+#pragma unroll
+    for (int e = 0; e < D / 16; ++e) st.acc[e][at] = f32x4{0, 0, 0, 0};
+  }
+}
+
+template <int D, int NAT>
+__device__ __forceinline__ void agg_store_lds(const AggState<D, NAT>& st, float* slot, int lane) {
+  int q = 0;
+#pragma unroll
+  for (int at = 0; at < NAT; ++at) {
+    slot[(q++) * 64 + lane] = st.m[at];
+    slot[(q++) * 64 + lane] = st.l[at];
+#pragma unroll
+    for (int e = 0; e < D / 16; ++e)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) slot[(q++) * 64 + lane] = st.acc[e][at][i];
+  }
+}
+
+template <int D, int NAT>
+__device__ __forceinline__ void agg_merge_lds(AggState<D, NAT>& st, const float* slot, int lane) {
+  int q = 0;
+#pragma unroll
+  for (int at = 0; at < NAT; ++at) {
+    const float mo = slot[(q++) * 64 + lane];
+    const float lo = slot[(q++) * 64 + lane];
+    const float mn = fmaxf(st.m[at], mo);
+    const float a = fast_exp2(st.m[at] - mn), b = fast_exp2(mo - mn);
+    st.m[at] = mn;
+    st.l[at] = st.l[at] * a + lo * b;
+#pragma unroll
+    for (int e = 0; e < D / 16; ++e)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) st.acc[e][at][i] = st.acc[e][at][i] * a + slot[(q++) * 64 + lane] * b;
+  }
+}
+
+// Tree merge of the W wave states of a block through LDS; wave 0 ends with the total.
+// slots: (W/2) * NREG * 64 floats.  Every wave calls this (block-wide barriers inside).
+template <int D, int NAT>
+__device__ __forceinline__ void agg_block_merge(AggState<D, NAT>& st, float* slots, int wave, int W, int lane) {
+  constexpr int NREG = Geo<D, NAT>::NREG;
+  for (int half = W >> 1; half >= 1; half >>= 1) {
+    if (wave >= half && wave < 2 * half) agg_store_lds<D, NAT>(st, slots + (size_t)(wave - half) * NREG * 64, lane);
+    __syncthreads();
+    if (wave < half) agg_merge_lds<D, NAT>(st, slots + (size_t)wave * NREG * 64, lane);
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------
+// broadcast: one step = 32 tokens, two independent 16-token tiles
+// ---------------------------------------------------------------------------
+// stationary V_A operand: vaop[ct][ks]: row r <-> channel (D/4)*(r/4) + 4ct + r%4,
+// k-slot 8g+j <-> agent 16*(2ks) + 4g+j (j<4) / 16*(2ks+1) + 4g+j-4.
+template <int D, int NAT>
+__device__ __forceinline__ void load_va_regs(const uint16_t* VA_lds, u32x4 (&vaop)[D / 16][(NAT + 1) / 2], int lane) {
+  constexpr int AS = Geo<D, NAT>::AS;
+  const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int ct = 0; ct < D / 16; ++ct) {
+    const int ch = (D / 4) * (r >> 2) + 4 * ct + (r & 3);
+#pragma unroll
+    for (int ks = 0; ks < (NAT + 1) / 2; ++ks) {
+      u32x4 w;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int j0 = 2 * jj, j1 = 2 * jj + 1;
+        const int a0 = (j0 < 4 ? 16 * (2 * ks) + 4 * g + j0 : 16 * (2 * ks + 1) + 4 * g + (j0 - 4));
+        const int a1 = (j1 < 4 ? 16 * (2 * ks) + 4 * g + j1 : 16 * (2 * ks + 1) + 4 * g + (j1 - 4));
+        const uint32_t lo = a0 < 16 * NAT ? VA_lds[a0 * AS + ch] : 0u;
+        const uint32_t hi = a1 < 16 * NAT ? VA_lds[a1 * AS + ch] : 0u;
+        w[jj] = lo | (hi << 16);
+      }
+      vaop[ct][ks] = w;
+    }
+  }
+}
+
+// Q registers of one step: qop[tt][kc] = Q[t0 + 16tt + r][32kc + 8g .. +7], rows clamped to N-1.
+// Qsrc may point to global memory (row stride D) or to an LDS copy of the unit's Q rows.
+template <int D>
+struct QRegs {
+  u32x4 qop[2][D / 32];
+};
+
+template <int D>
+__device__ __forceinline__ void bcast_load(const uint16_t* Qsrc, int row_stride, int t0, int N, int lane,
+                                           QRegs<D>& q) {
+  const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt) {
+    const int row = min(t0 + 16 * tt + r, N - 1);
+#pragma unroll
+    for (int kc = 0; kc < D / 32; ++kc) q.qop[tt][kc] = *(const u32x4*)(Qsrc + (size_t)row * row_stride + 32 * kc + 8 * g);
+  }
+}
+
+template <class E, int D, int NAT, bool BIAS, bool EPI>
+__device__ __forceinline__ void bcast_compute(const QRegs<D>& q, const uint16_t* __restrict__ Vu,
+                                              uint16_t* __restrict__ Ou, int t0, int N, int n,
+                                              const u32x4 (&areg)[NAT][D / 32],
+                                              const u32x4 (&vaop)[D / 16][(NAT + 1) / 2], float sc, int lane,
+                                              const BiasArgs& b2, const float* __restrict__ dwc_w,
+                                              const float* __restrict__ dwc_b, float vk, int gh, int gw) {
+  constexpr int KC = D / 32, EV = D / 16, KS = (NAT + 1) / 2;
+  const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt) {
+    const int tok = t0 + 16 * tt + r;
+    const int tokc = min(tok, N - 1);
+    // S2^T = A Q^T : tile at, element i <-> agent 16at+4g+i, token tok
+    f32x4 s[NAT];
+    float mx = -INFINITY;
+    int y = 0, x = 0;
+    if constexpr (BIAS || EPI) {
+      if (gw > 0) {
+        y = tokc / gw;
+        x = tokc - y * gw;
+      }
+    }
+#pragma unroll
+    for (int at = 0; at < NAT; ++at) {
+      f32x4 c = {0, 0, 0, 0};
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) c = Mx<E>::mma(areg[at][kc], q.qop[tt][kc], c);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int a = 16 * at + 4 * g + i;
+        float v = c[i] * sc;
+        if constexpr (BIAS) v += kLog2e * bias2_at(b2, min(a, n - 1), y, x, gh, gw, n);
+        v = a < n ? v : -INFINITY;
+        c[i] = v;
+        mx = fmaxf(mx, v);
+      }
+      s[at] = c;
+    }
+    mx = xor16_32_max(mx);
+    float sum = 0.0f;
+#pragma unroll
+    for (int at = 0; at < NAT; ++at)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float p = fast_exp2(s[at][i] - mx);
+        s[at][i] = p;
+        sum += p;
+      }
+    sum = xor16_32_sum(sum);
+    const float inv = 1.0f / sum;
+    u32x4 pk[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      pk[ks][0] = Mx<E>::pack2(s[2 * ks][0], s[2 * ks][1]);
+      pk[ks][1] = Mx<E>::pack2(s[2 * ks][2], s[2 * ks][3]);
+      if (2 * ks + 1 < NAT) {
+        pk[ks][2] = Mx<E>::pack2(s[(2 * ks + 1) % NAT][0], s[(2 * ks + 1) % NAT][1]);
+        pk[ks][3] = Mx<E>::pack2(s[(2 * ks + 1) % NAT][2], s[(2 * ks + 1) % NAT][3]);
+      } else {
+        pk[ks][2] = 0u;
+        pk[ks][3] = 0u;
+      }
+    }
+    // O^T = V_A^T P2^T : tile ct, element i <-> channel (D/4)*g + 4ct + i, token tok
+    float o[4 * EV];
+#pragma unroll
+    for (int ct = 0; ct < EV; ++ct) {
+      f32x4 c = {0, 0, 0, 0};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) c = Mx<E>::mma(vaop[ct][ks], pk[ks], c);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[4 * ct + i] = c[i] * inv;
+    }
+    const int ch0 = (D / 4) * g;     // this lane's D/4 contiguous output channels
+    if constexpr (EPI) {
+      if (dwc_w) {
+#pragma unroll
+        for (int k = 0; k < 4 * EV; ++k) {
+          const int ch = ch0 + k;
+          float conv = dwc_b ? dwc_b[ch] : 0.0f;
+          for (int ky = -1; ky <= 1; ++ky)
+            for (int kx = -1; kx <= 1; ++kx) {
+              const int yy = y + ky, xx = x + kx;
+              if (yy >= 0 && yy < gh && xx >= 0 && xx < gw)
+                conv += dwc_w[ch * 9 + (ky + 1) * 3 + (kx + 1)] * E::to_f32(Vu[((size_t)yy * gw + xx) * D + ch]);
+            }
+          o[k] += conv;
+        }
+      }
+      if (vk != 0.0f) {
+#pragma unroll
+        for (int k = 0; k < 4 * EV; ++k) o[k] += vk * E::to_f32(Vu[(size_t)tokc * D + ch0 + k]);
+      }
+    }
+    if (tok < N) {
+#pragma unroll
+      for (int q = 0; q < EV / 2; ++q) {     // 8 channels = 16 bytes per store
+        u32x4 w;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) w[k] = Mx<E>::pack2(o[8 * q + 2 * k], o[8 * q + 2 * k + 1]);
+        *(u32x4*)(Ou + (size_t)tok * D + ch0 + 8 * q) = w;
+      }
+    }
+  }
+}
+
+// Walk broadcast steps with the next step's Q loads in flight; `cur` holds the loads of step `first`.
+template <class E, int D, int NAT, bool BIAS, bool EPI>
+__device__ __forceinline__ void bcast_range(QRegs<D>& cur, const uint16_t* Qsrc, int row_stride,
+                                            const uint16_t* __restrict__ Vu,
+                                            uint16_t* __restrict__ Ou, int first, int stride, int end, int N, int n,
+                                            const u32x4 (&areg)[NAT][D / 32],
+                                            const u32x4 (&vaop)[D / 16][(NAT + 1) / 2], float sc, int lane,
+                                            const BiasArgs& b2, const float* __restrict__ dwc_w,
+                                            const float* __restrict__ dwc_b, float vk, int gh, int gw) {
+  for (int t0 = first; t0 < end; t0 += stride) {
+    QRegs<D> nxt;
+    const int tn = t0 + stride;
+    if (tn < end) bcast_load<D>(Qsrc, row_stride, tn, N, lane, nxt);
+    bcast_compute<E, D, NAT, BIAS, EPI>(cur, Vu, Ou, t0, N, n, areg, vaop, sc, lane, b2, dwc_w, dwc_b, vk, gh, gw);
+    if (tn < end) cur = nxt;
+  }
+}
+
+template <class E, int D, int NAT, bool MODULE>
+__device__ __forceinline__ void bcast_dispatch(bool bias2, bool epi, QRegs<D>& cur, const uint16_t* Qsrc,
+                                               int row_stride,
+                                               const uint16_t* __restrict__ Vu, uint16_t* __restrict__ Ou, int first,
+                                               int stride, int end, int N, int n, const u32x4 (&areg)[NAT][D / 32],
+                                               const u32x4 (&vaop)[D / 16][(NAT + 1) / 2], float sc, int lane,
+                                               const BiasArgs& b2, const float* __restrict__ dwc_w,
+                                               const float* __restrict__ dwc_b, float vk, int gh, int gw) {
+  if constexpr (MODULE) {
+    if (bias2 && epi)
+      bcast_range<E, D, NAT, true, true>(cur, Qsrc, row_stride, Vu, Ou, first, stride, end, N, n, areg, vaop, sc, lane, b2,
+                                         dwc_w, dwc_b, vk, gh, gw);
+    else if (bias2)
+      bcast_range<E, D, NAT, true, false>(cur, Qsrc, row_stride, Vu, Ou, first, stride, end, N, n, areg, vaop, sc, lane, b2,
+                                          dwc_w, dwc_b, vk, gh, gw);
+    else
+      bcast_range<E, D, NAT, false, true>(cur, Qsrc, row_stride, Vu, Ou, first, stride, end, N, n, areg, vaop, sc, lane, b2,
+                                          dwc_w, dwc_b, vk, gh, gw);
+  } else {
+    bcast_range<E, D, NAT, false, false>(cur, Qsrc, row_stride, Vu, Ou, first, stride, end, N, n, areg, vaop, sc, lane, b2,
+                                         dwc_w, dwc_b, vk, gh, gw);
+  }
+}
+
+// final V_A of wave 0 -> LDS rows (element type) and, optionally, fp32 global
+template <class E, int D, int NAT>
+__device__ __forceinline__ void agg_finish(AggState<D, NAT>& st, uint16_t* VA_lds, float* __restrict__ VA_glob,
+                                           int n, int lane) {
+  constexpr int EV = D / 16, AS = Geo<D, NAT>::AS;
+  const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int at = 0; at < NAT; ++at) {
+    const float l = xor16_32_sum(st.l[at]);
+    const float inv = 1.0f / l;
+    const int a = 16 * at + r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int e = 0; e < EV; e += 2) {
+        const int ch = EV * (4 * g + i) + e;
+        const float v0 = st.acc[e][at][i] * inv, v1 = st.acc[e + 1][at][i] * inv;
+        *(uint32_t*)(VA_lds + a * AS + ch) = Mx<E>::pack2(v0, v1);
+        if (VA_glob && a < n) {
+          VA_glob[(size_t)a * D + ch] = v0;
+          VA_glob[(size_t)a * D + ch + 1] = v1;
+        }
+      }
+  }
+}
+
+__device__ __forceinline__ BiasArgs head_bias1(BiasArgs b, int hd, int n, int gh, int gw) {
+  if (b.col) b.col += (size_t)hd * n * gw;
+  if (b.row) b.row += (size_t)hd * n * gh;
+  if (b.blk) b.blk += (size_t)hd * n * b.h0 * b.w0;
+  return b;
+}
+__device__ __forceinline__ BiasArgs head_bias2(BiasArgs b, int hd, int n, int gh, int gw) {
+  if (b.col) b.col += (size_t)hd * gw * n;
+  if (b.row) b.row += (size_t)hd * gh * n;
+  if (b.blk) b.blk += (size_t)hd * b.h0 * b.w0 * n;
+  return b;
+}
+
+// ---------------------------------------------------------------------------
+// Kernel 1: the whole forward pass of one unit in one block, for units whose Q rows fit in LDS.
+// Every global load of the block is issued up front (K/V of each wave's first step into registers,
+// Q into LDS), so the cold-HBM latency is paid once; pooling and the broadcast then read Q from LDS.
+// grid = units.  LDS: A rows | V_A rows | Q rows (N x AS) | (W/2) merge slots.
+// ---------------------------------------------------------------------------
+template <class E, int D, int NAT, bool MODULE>
+__global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
+    const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+    const uint16_t* __restrict__ Agiven, uint16_t* __restrict__ O, BiasArgs b1, BiasArgs b2,
+    const float* __restrict__ dwc_w, const float* __restrict__ dwc_b, float sc1, float sc2, float vk, int N, int n,
+    int heads, int gh, int gw, int ah, int aw) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  constexpr int AS = Geo<D, NAT>::AS, CH = D / 8;
+  uint16_t* A_lds = (uint16_t*)smem_raw;
+  uint16_t* VA_lds = A_lds + 16 * NAT * AS;
+  uint16_t* Q_lds = VA_lds + 16 * NAT * AS;
+  float* slots = (float*)(Q_lds + (size_t)((N + 31) / 32 * 32) * AS);
+
+  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
+  const int hd = u % heads;
+  const uint16_t* Qu = Q + (size_t)u * N * D;
+  const uint16_t* Ku = K + (size_t)u * N * D;
+  const uint16_t* Vu = V + (size_t)u * N * D;
+  uint16_t* Ou = O + (size_t)u * N * D;
+
+  KVRegs<D> kv0;
+  if (32 * wave < N) agg_load<D>(Ku, Vu, 32 * wave, N, lane, kv0);
+
+  const int total = N * CH;
+  for (int base = tid; base < total; base += 4 * blockDim.x) {
+    u32x4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int q = base + k * blockDim.x;
+      if (q < total) v[k] = *(const u32x4*)(Qu + (size_t)q * 8);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int q = base + k * blockDim.x;
+      if (q < total) *(u32x4*)(Q_lds + (q / CH) * AS + 8 * (q % CH)) = v[k];
+    }
+  }
+  if (Agiven) load_agents_to_lds<D, NAT>(Agiven + (size_t)u * n * D, A_lds, n, tid, blockDim.x);
+  __syncthreads();
+  if (!Agiven) {
+    pool_unit_to_lds<E, D, NAT>(Q_lds, AS, A_lds, n, gh, gw, ah, aw, tid, blockDim.x);
+    __syncthreads();
+  }
+
+  u32x4 areg[NAT][D / 32];
+  load_a_regs<D, NAT>(A_lds, areg, lane);
+
+  AggState<D, NAT> st;
+  agg_init<D, NAT>(st);
+  const BiasArgs hb1 = head_bias1(b1, hd, n, gh, gw);
+  const bool bias1 = MODULE && hb1.any();
+  bool agg_done = false;
+  if constexpr (MODULE) {
+    if (bias1) {
+      agg_range<E, D, NAT, true>(Ku, Vu, kv0, 32 * wave, 32 * W, N, n, areg, st, sc1, lane, hb1, gh, gw);
+      agg_done = true;
+    }
+  }
+  if (!agg_done) agg_range<E, D, NAT, false>(Ku, Vu, kv0, 32 * wave, 32 * W, N, n, areg, st, sc1, lane, hb1, gh, gw);
+  agg_block_merge<D, NAT>(st, slots, wave, W, lane);
+  if (wave == 0) agg_finish<E, D, NAT>(st, VA_lds, nullptr, n, lane);
+  __syncthreads();
+
+  u32x4 vaop[D / 16][(NAT + 1) / 2];
+  load_va_regs<D, NAT>(VA_lds, vaop, lane);
+  const BiasArgs hb2 = head_bias2(b2, hd, n, gh, gw);
+  const bool bias2 = MODULE && hb2.any();
+  const float* w9 = (MODULE && dwc_w) ? dwc_w + (size_t)hd * D * 9 : nullptr;
+  const float* wb = (MODULE && dwc_b) ? dwc_b + (size_t)hd * D : nullptr;
+  const bool epi = MODULE && (w9 != nullptr || vk != 0.0f);
+  QRegs<D> q0;
+  if (32 * wave < N) bcast_load<D>(Q_lds, AS, 32 * wave, N, lane, q0);
+  bcast_dispatch<E, D, NAT, MODULE>(bias2, epi, q0, Q_lds, AS, Vu, Ou, 32 * wave, 32 * W, N, N, n, areg, vaop, sc2,
+                                    lane, hb2, w9, wb, vk, gh, gw);
+}
+
+// ---------------------------------------------------------------------------
+// Kernel 2: pooling alone.  grid = (ceil(n / 4), units), 4 waves, one agent per wave.
+// ---------------------------------------------------------------------------
+template <class E, int D>
+__global__ __launch_bounds__(256) void small_pool_kernel(const uint16_t* __restrict__ Q, uint16_t* __restrict__ A,
+                                                         int N, int n, int gh, int gw, int ah, int aw) {
+  constexpr int CH = D / 8;
+  const int u = blockIdx.y, lane = threadIdx.x & 63;
+  const int a = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (a >= n) return;
+  const u32x4 w = pool_agent<E, D>(Q + (size_t)u * N * D, D, a, gh, gw, ah, aw, lane);
+  if (lane < CH) *(u32x4*)(A + ((size_t)u * n + a) * D + 8 * lane) = w;
+}
+
+// ---------------------------------------------------------------------------
+// Kernel 3: split-N aggregation.  grid = (S, units); block (s, u) walks the tokens
+// [s*chunk, min(N, (s+1)*chunk)), chunk a multiple of 32, merges its waves and writes
+// the un-normalised partial: acc [u][s][n][D], m and l [u][s][n] (m in log2 domain).
+// ---------------------------------------------------------------------------
+template <class E, int D, int NAT, bool MODULE>
+__global__ __launch_bounds__(64 * kMaxWaves) void small_aggregate_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V, BiasArgs b1,
+    float sc1, int N, int n, int heads, int gh, int gw, int chunk, float* __restrict__ part_acc,
+    float* __restrict__ part_m, float* __restrict__ part_l) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  constexpr int AS = Geo<D, NAT>::AS, EV = D / 16;
+  uint16_t* A_lds = (uint16_t*)smem_raw;
+  float* slots = (float*)(A_lds + 16 * NAT * AS);
+  const int s = blockIdx.x, S = gridDim.x, u = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
+  const uint16_t* Ku = K + (size_t)u * N * D;
+  const uint16_t* Vu = V + (size_t)u * N * D;
+
+  const int tbeg = s * chunk, tend = min(N, tbeg + chunk);
+  KVRegs<D> kv0;
+  if (tbeg + 32 * wave < tend) agg_load<D>(Ku, Vu, tbeg + 32 * wave, tend, lane, kv0);
+  load_agents_to_lds<D, NAT>(A + (size_t)u * n * D, A_lds, n, tid, blockDim.x);
+  __syncthreads();
+  u32x4 areg[NAT][D / 32];
+  load_a_regs<D, NAT>(A_lds, areg, lane);
+
+  AggState<D, NAT> st;
+  agg_init<D, NAT>(st);
+  const BiasArgs hb1 = head_bias1(b1, u % heads, n, gh, gw);
+  const bool bias1 = MODULE && hb1.any();
+  bool agg_done = false;
+  if constexpr (MODULE) {
+    if (bias1) {
+      agg_range<E, D, NAT, true>(Ku, Vu, kv0, tbeg + 32 * wave, 32 * W, tend, n, areg, st, sc1, lane, hb1, gh, gw);
+      agg_done = true;
+    }
+  }
+  if (!agg_done)
+    agg_range<E, D, NAT, false>(Ku, Vu, kv0, tbeg + 32 * wave, 32 * W, tend, n, areg, st, sc1, lane, hb1, gh, gw);
+  agg_block_merge<D, NAT>(st, slots, wave, W, lane);
+  if (wave == 0) {
+    const int r = lane & 15, g = lane >> 4;
+    const size_t base = (size_t)u * S + s;
+#pragma unroll
+    for (int at = 0; at < NAT; ++at) {
+      const int a = 16 * at + r;
+      const float l = xor16_32_sum(st.l[at]);
+      if (a < n) {
+        if (g == 0) {
+          part_m[base * n + a] = st.m[at];
+          part_l[base * n + a] = l;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float* dst = part_acc + (base * n + a) * D + EV * (4 * g + i);
+#pragma unroll
+          for (int e = 0; e < EV; ++e) dst[e] = st.acc[e][at][i];
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Kernel 4: merge of the split partials (m in log2 domain) -> V_A fp32 [u][n][D].
+// grid = (n, units), 64 threads (thread = channel).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void small_merge_kernel(const float* __restrict__ part_acc,
+                                                         const float* __restrict__ part_m,
+                                                         const float* __restrict__ part_l, int S, int n, int D,
+                                                         float* __restrict__ VA) {
+  const int a = blockIdx.x, u = blockIdx.y;
+  float m = kNegBig;
+  for (int s = 0; s < S; ++s) m = fmaxf(m, part_m[((size_t)u * S + s) * n + a]);
+  float l = 0.0f;
+  for (int s = 0; s < S; ++s) {
+    const size_t row = ((size_t)u * S + s) * n + a;
+    l += part_l[row] * fast_exp2(part_m[row] - m);
+  }
+  const float inv = 1.0f / l;
+  for (int c = threadIdx.x; c < D; c += 64) {
+    float v = 0.0f;
+    for (int s = 0; s < S; ++s) {
+      const size_t row = ((size_t)u * S + s) * n + a;
+      v += part_acc[row * D + c] * fast_exp2(part_m[row] - m);
+    }
+    VA[((size_t)u * n + a) * D + c] = v * inv;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Kernel 5: broadcast.  grid = (token chunks, units); A (element type) and V_A
+// (fp32) come from global and are staged once per block.
+// ---------------------------------------------------------------------------
+template <class E, int D, int NAT, bool MODULE>
+__global__ __launch_bounds__(64 * kMaxWaves) void small_broadcast_kernel(
+    const uint16_t* __restrict__ Q, const uint16_t* __restrict__ A, const float* __restrict__ VA,
+    const uint16_t* __restrict__ V, uint16_t* __restrict__ O, BiasArgs b2, const float* __restrict__ dwc_w,
+    const float* __restrict__ dwc_b, float sc2, float vk, int N, int n, int heads, int gh, int gw, int chunk) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  constexpr int AS = Geo<D, NAT>::AS;
+  uint16_t* A_lds = (uint16_t*)smem_raw;
+  uint16_t* VA_lds = A_lds + 16 * NAT * AS;
+  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
+  const int hd = u % heads;
+  const uint16_t* Qu = Q + (size_t)u * N * D;
+  const uint16_t* Vu = V ? V + (size_t)u * N * D : nullptr;
+  uint16_t* Ou = O + (size_t)u * N * D;
+
+  const int tbeg = blockIdx.x * chunk, tend = min(N, tbeg + chunk);
+  QRegs<D> q0;
+  if (tbeg + 32 * wave < tend) bcast_load<D>(Qu, D, tbeg + 32 * wave, N, lane, q0);
+  load_agents_to_lds<D, NAT>(A + (size_t)u * n * D, A_lds, n, tid, blockDim.x);
+  const float* VAu = VA + (size_t)u * n * D;
+  for (int q = tid; q < 16 * NAT * (D / 2); q += blockDim.x) {
+    const int a = q / (D / 2), c2 = q - a * (D / 2);
+    uint32_t w = 0u;
+    if (a < n) {
+      const f32x2 v = *(const f32x2*)(VAu + (size_t)a * D + 2 * c2);
+      w = Mx<E>::pack2(v[0], v[1]);
+    }
+    *(uint32_t*)(VA_lds + a * AS + 2 * c2) = w;
+  }
+  __syncthreads();
+  u32x4 areg[NAT][D / 32];
+  load_a_regs<D, NAT>(A_lds, areg, lane);
+  u32x4 vaop[D / 16][(NAT + 1) / 2];
+  load_va_regs<D, NAT>(VA_lds, vaop, lane);
+
+  const BiasArgs hb2 = head_bias2(b2, hd, n, gh, gw);
+  const bool bias2 = MODULE && hb2.any();
+  const float* w9 = (MODULE && dwc_w) ? dwc_w + (size_t)hd * D * 9 : nullptr;
+  const float* wb = (MODULE && dwc_b) ? dwc_b + (size_t)hd * D : nullptr;
+  const bool epi = MODULE && (w9 != nullptr || vk != 0.0f);
+  bcast_dispatch<E, D, NAT, MODULE>(bias2, epi, q0, Qu, D, Vu, Ou, tbeg + 32 * wave, 32 * W, tend, N, n, areg, vaop,
+                                    sc2, lane, hb2, w9, wb, vk, gh, gw);
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+bool small_supported(const Problem& p) {
+  // N bound: the pooling kernel divides window indices by reciprocal multiplication (exact below 2^20)
+  return (p.dtype == 1 || p.dtype == 2) && (p.d == 32 || p.d == 64) && p.n <= 64 && p.N <= (1 << 20);
+}
+
+// waves per block for a range of `tokens` tokens: one 32-token step per wave if possible
+// (power of two because of the tree merge, at most kMaxWaves)
+static int waves_for(int tokens) {
+  const int steps = (tokens + 31) / 32;
+  int w = 1;
+  while (w < steps && w < kMaxWaves) w *= 2;
+  return w;
+}
+
+template <int D, int NAT>
+static size_t fused_lds_bytes(int W, int N) {
+  return (size_t)2 * 16 * NAT * Geo<D, NAT>::AS * 2 + (size_t)((N + 31) / 32 * 32) * Geo<D, NAT>::AS * 2 +
+         (size_t)max(1, W / 2) * Geo<D, NAT>::NREG * 64 * 4;
+}
+
+// The one-block-per-unit kernel keeps the unit's Q rows in LDS: at most 64 KB of them.
+bool small_fused_supported(const Problem& p) {
+  return small_supported(p) && (size_t)((p.N + 31) / 32 * 32) * (p.d + 8) * 2 <= 64 * 1024;
+}
+
+#define AA_SMALL_DISPATCH(p, ...)                                                  \
+  do {                                                                             \
+    const int nat_ = ((p).n + 15) / 16;                                            \
+    if ((p).dtype == 2) {                                                          \
+      using E = ElemBF16;                                                          \
+      AA_SMALL_DISPATCH_D(p, nat_, __VA_ARGS__)                                    \
+    } else {                                                                       \
+      using E = ElemF16;                                                           \
+      AA_SMALL_DISPATCH_D(p, nat_, __VA_ARGS__)                                    \
+    }                                                                              \
+  } while (0)
+#define AA_SMALL_DISPATCH_D(p, nat_, ...)                                          \
+  if ((p).d == 32) {                                                               \
+    constexpr int D = 32;                                                          \
+    AA_SMALL_DISPATCH_N(nat_, __VA_ARGS__)                                         \
+  } else {                                                                         \
+    constexpr int D = 64;                                                          \
+    AA_SMALL_DISPATCH_N(nat_, __VA_ARGS__)                                         \
+  }
+#define AA_SMALL_DISPATCH_N(nat_, ...)                                             \
+  switch (nat_) {                                                                  \
+    case 1: { constexpr int NAT = 1; __VA_ARGS__; } break;                         \
+    case 2: { constexpr int NAT = 2; __VA_ARGS__; } break;                         \
+    case 3: { constexpr int NAT = 3; __VA_ARGS__; } break;                         \
+    default: { constexpr int NAT = 4; __VA_ARGS__; } break;                        \
+  }
+
+static bool module_mode(const Problem& p) {
+  return p.b1.any() || p.b2.any() || p.dwc_w != nullptr || p.vk != 0.0f;
+}
+
+// Kernels whose dynamic LDS may exceed 64 KB need the opt-in once per kernel (gfx950 has 160 KB per CU).
+template <class KernelT>
+static hipError_t allow_lds(KernelT kernel, size_t bytes) {
+  static bool done = false;      // one flag per kernel instantiation
+  if (bytes <= 64 * 1024 || done) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e == hipSuccess) done = true;
+  return e;
+}
+
+hipError_t launch_small_fused(const Problem& p, const void* Q, const void* K, const void* V, const void* A,
+                              void* out, hipStream_t st) {
+  const int W = waves_for(p.N);
+  const float c1 = p.scale1 * kLog2e, c2 = p.scale2 * kLog2e;
+  const bool mod = module_mode(p);
+  hipError_t err = hipSuccess;
+  AA_SMALL_DISPATCH(p, {
+    const size_t lds = fused_lds_bytes<D, NAT>(W, p.N);
+    auto launch = [&](auto kernel) {
+      err = allow_lds(kernel, lds);
+      if (err == hipSuccess)
+        kernel<<<dim3(p.units), dim3(64 * W), lds, st>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
+                                                          (const uint16_t*)A, (uint16_t*)out, p.b1, p.b2, p.dwc_w,
+                                                          p.dwc_b, c1, c2, p.vk, p.N, p.n, p.heads, p.gh, p.gw,
+                                                          p.ah, p.aw);
+    };
+    if (mod)
+      launch(small_fused_kernel<E, D, NAT, true>);
+    else
+      launch(small_fused_kernel<E, D, NAT, false>);
+  });
+  return err != hipSuccess ? err : hipGetLastError();
+}
+
+hipError_t launch_small_pool(const Problem& p, const void* Q, void* A, hipStream_t st) {
+  const dim3 grid((p.n + 3) / 4, p.units);
+  if (p.dtype == 2) {
+    if (p.d == 32)
+      small_pool_kernel<ElemBF16, 32><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, p.N, p.n, p.gh,
+                                                                  p.gw, p.ah, p.aw);
+    else
+      small_pool_kernel<ElemBF16, 64><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, p.N, p.n, p.gh,
+                                                                  p.gw, p.ah, p.aw);
+  } else {
+    if (p.d == 32)
+      small_pool_kernel<ElemF16, 32><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, p.N, p.n, p.gh,
+                                                                 p.gw, p.ah, p.aw);
+    else
+      small_pool_kernel<ElemF16, 64><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, p.N, p.n, p.gh,
+                                                                 p.gw, p.ah, p.aw);
+  }
+  return hipGetLastError();
+}
+
+int small_split_chunk(int N, int S) {
+  int chunk = (N + S - 1) / S;
+  return (chunk + 31) / 32 * 32;
+}
+
+hipError_t launch_small_aggregate(const Problem& p, const void* A, const void* K, const void* V,
+                                  const Partials& part, hipStream_t st) {
+  const int chunk = small_split_chunk(p.N, part.S);
+  const int W = waves_for(chunk);
+  const float c1 = p.scale1 * kLog2e;
+  const bool mod = p.b1.any();
+  hipError_t err = hipSuccess;
+  AA_SMALL_DISPATCH(p, {
+    const size_t lds = (size_t)16 * NAT * Geo<D, NAT>::AS * 2 + (size_t)max(1, W / 2) * Geo<D, NAT>::NREG * 64 * 4;
+    auto launch = [&](auto kernel) {
+      err = allow_lds(kernel, lds);
+      if (err == hipSuccess)
+        kernel<<<dim3(part.S, p.units), dim3(64 * W), lds, st>>>((const uint16_t*)A, (const uint16_t*)K,
+                                                                  (const uint16_t*)V, p.b1, c1, p.N, p.n, p.heads,
+                                                                  p.gh, p.gw, chunk, part.acc, part.m, part.l);
+    };
+    if (mod)
+      launch(small_aggregate_kernel<E, D, NAT, true>);
+    else
+      launch(small_aggregate_kernel<E, D, NAT, false>);
+  });
+  return err != hipSuccess ? err : hipGetLastError();
+}
+
+hipError_t launch_small_merge(const Problem& p, const Partials& part, float* VA, hipStream_t st) {
+  small_merge_kernel<<<dim3(p.n, p.units), dim3(64), 0, st>>>(part.acc, part.m, part.l, part.S, p.n, p.d, VA);
+  return hipGetLastError();
+}
+
+hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A, const float* VA, const void* V,
+                                  void* out, int chunks, hipStream_t st) {
+  int chunk = (p.N + chunks - 1) / chunks;
+  chunk = (chunk + 31) / 32 * 32;
+  const int nchunks = (p.N + chunk - 1) / chunk;
+  const int W = waves_for(chunk);
+  const float c2 = p.scale2 * kLog2e;
+  const bool mod = p.b2.any() || p.dwc_w != nullptr || p.vk != 0.0f;
+  AA_SMALL_DISPATCH(p, {
+    const size_t lds = (size_t)2 * 16 * NAT * Geo<D, NAT>::AS * 2;
+    if (mod)
+      small_broadcast_kernel<E, D, NAT, true><<<dim3(nchunks, p.units), dim3(64 * W), lds, st>>>(
+          (const uint16_t*)Q, (const uint16_t*)A, VA, (const uint16_t*)V, (uint16_t*)out, p.b2, p.dwc_w, p.dwc_b,
+          c2, p.vk, p.N, p.n, p.heads, p.gh, p.gw, chunk);
+    else
+      small_broadcast_kernel<E, D, NAT, false><<<dim3(nchunks, p.units), dim3(64 * W), lds, st>>>(
+          (const uint16_t*)Q, (const uint16_t*)A, VA, (const uint16_t*)V, (uint16_t*)out, p.b2, p.dwc_w, p.dwc_b,
+          c2, p.vk, p.N, p.n, p.heads, p.gh, p.gw, chunk);
+  });
+  return hipGetLastError();
+}
+
+}  // namespace aa
