@@ -101,7 +101,7 @@ void plan_small(const aa_desc* d, Plan& pl) {
   int S = d->n_splits;
   pl.prefer_fused = (S <= 0);   // taken when the unit's Q rows fit in LDS, see run time check
   if (S <= 0) {
-    S = (int)((512 + units - 1) / units);
+    S = (int)((640 + units - 1) / units);      // about one resident round of blocks on 256 CUs
     const int max_by_len = (d->N + 127) / 128;
     if (S > max_by_len) S = max_by_len;
   }

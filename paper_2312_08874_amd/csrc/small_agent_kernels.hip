@@ -14,11 +14,32 @@
 // the lane; the other operand (V or V_A) is arranged to use the same k order:
 //   k-slot 8g+j  <->  row 4g+j of the first tile (j<4) / row 4g+j-4 of the second.
 //
+// Work split inside a block: in the aggregation a wave owns one tile of 16 agents and one slice of
+// the block's tokens (waves = agent tiles x token slices), so the online-softmax state of a wave is
+// small and only the token slices have to be merged through LDS; in the broadcast every wave owns
+// tokens and needs all agents.  Global loads are issued two steps ahead of their use.
+//
 // Stages (Sec. 4.1 Eq. (3); bias of Eq. (5); DWC of Eq. (6); k*V of Appendix C.1):
 //   pool      A = Pooling(Q)                       (Sec. 4.2)
 //   aggregate V_A^T += V^T P1^T,  P1^T = exp2(K A^T * c - m)   running max per agent
 //   broadcast O^T = V_A^T P2^T,   P2^T = softmax over agents of (A Q^T * c)
 #include "kernels.h"
+
+// Optional in-kernel timeline for development builds (-DAA_TIMELINE): wave 0 of the first blocks
+// stamps the 100 MHz wall clock at phase boundaries.  Compiled out of the product library.
+#ifdef AA_TIMELINE
+__device__ unsigned long long aa_timeline_buf[4096 * 8];
+#define AA_TL(slot)                                                                          \
+  do {                                                                                       \
+    const unsigned bid_ = blockIdx.x + gridDim.x * blockIdx.y;                               \
+    if (threadIdx.x == 0 && bid_ < 4096) aa_timeline_buf[bid_ * 8 + (slot)] = wall_clock64(); \
+  } while (0)
+extern "C" int aa_debug_timeline(unsigned long long* host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(aa_timeline_buf), sizeof(aa_timeline_buf));
+}
+#else
+#define AA_TL(slot) do { } while (0)
+#endif
 
 namespace aa {
 
@@ -69,13 +90,22 @@ constexpr float kNegBig = -1.0e30f;   // finite stand-in for "no maximum yet"
 constexpr int kMaxWaves = 8;          // waves per block (launch bound 512 threads -> up to 256 VGPRs)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// Reductions over the four lanes r, r+16, r+32, r+48 (same MFMA column, the four row groups) with the
+// gfx950 row-swap instructions: permlane32_swap(v, v) yields (lower half twice, upper half twice),
+// permlane16_swap(v, v) yields (rows 0,0,2,2) and (rows 1,1,3,3).
 __device__ __forceinline__ float xor16_32_max(float v) {
-  v = fmaxf(v, __shfl_xor(v, 16, 64));
-  return fmaxf(v, __shfl_xor(v, 32, 64));
+  const uint32_t b = __float_as_uint(v);
+  const auto h = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+  const uint32_t c = __float_as_uint(fmaxf(__uint_as_float(h[0]), __uint_as_float(h[1])));
+  const auto q = __builtin_amdgcn_permlane16_swap(c, c, false, false);
+  return fmaxf(__uint_as_float(q[0]), __uint_as_float(q[1]));
 }
 __device__ __forceinline__ float xor16_32_sum(float v) {
-  v += __shfl_xor(v, 16, 64);
-  return v + __shfl_xor(v, 32, 64);
+  const uint32_t b = __float_as_uint(v);
+  const auto h = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+  const uint32_t c = __float_as_uint(__uint_as_float(h[0]) + __uint_as_float(h[1]));
+  const auto q = __builtin_amdgcn_permlane16_swap(c, c, false, false);
+  return __uint_as_float(q[0]) + __uint_as_float(q[1]);
 }
 
 // Geometry shared by the kernels of one instantiation.
@@ -84,15 +114,16 @@ struct Geo {
   static constexpr int KC = D / 32;          // k-chunks of the score products (contraction over d)
   static constexpr int EV = D / 16;          // 16-row tiles along d in the value products
   static constexpr int KS = (NAT + 1) / 2;   // k-steps (pairs of agent tiles) of the broadcast value product
-  static constexpr int AS = D + 8;           // LDS row stride (elements) of A and V_A
-  static constexpr int NREG = EV * NAT * 4 + 2 * NAT;   // floats per lane of an aggregation state
+  static constexpr int AS = D + 8;           // LDS row stride (elements) of A, V_A and Q rows
+  static constexpr int NREG = EV * 4 + 2;    // floats per lane of one wave's aggregation state
 };
 
-template <int D, int NAT>
+// Online-softmax state of one wave: 16 agents (tile at0), channels in MFMA C layout.
+template <int D>
 struct AggState {
-  float m[NAT];                     // running maximum (log2 domain), equal in the 4 lanes sharing r
-  float l[NAT];                     // per-lane partial of the running denominator
-  f32x4 acc[D / 16][NAT];           // V_A^T tiles: acc[e][at][i] <-> agent 16at+r, channel (D/16)*(4g+i)+e
+  float m;                 // running maximum (log2 domain), equal in the 4 lanes sharing r
+  float l;                 // per-lane partial of the running denominator
+  f32x4 acc[D / 16];       // V_A^T tiles: acc[e][i] <-> agent 16*at0 + r, channel (D/16)*(4g+i) + e
 };
 
 // ---------------------------------------------------------------------------
@@ -204,6 +235,15 @@ __device__ __forceinline__ void load_a_regs(const uint16_t* A_lds, u32x4 (&areg)
     for (int kc = 0; kc < D / 32; ++kc) areg[at][kc] = *(const u32x4*)(A_lds + (16 * at + r) * AS + 32 * kc + 8 * g);
 }
 
+// A operand of one agent tile: areg1[kc] = A[16*at0 + r][32kc + 8g .. +7]
+template <int D, int NAT>
+__device__ __forceinline__ void load_a_tile(const uint16_t* A_lds, int at0, u32x4 (&areg1)[D / 32], int lane) {
+  constexpr int AS = Geo<D, NAT>::AS;
+  const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int kc = 0; kc < D / 32; ++kc) areg1[kc] = *(const u32x4*)(A_lds + (16 * at0 + r) * AS + 32 * kc + 8 * g);
+}
+
 // ---------------------------------------------------------------------------
 // aggregation: one step = 32 tokens [t0, t0+32) of one unit, all 16*NAT agents
 // ---------------------------------------------------------------------------
@@ -221,15 +261,18 @@ __device__ __forceinline__ void agg_load(const uint16_t* __restrict__ Ku, const 
                                          int N, int lane, KVRegs<D>& kv) {
   constexpr int KC = D / 32, EV = D / 16;
   const int r = lane & 15, g = lane >> 4;
+  const bool tail = t0 + 32 > N;     // wave-uniform: only the last step of a range clamps its rows
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt) {
-    const int row = min(t0 + 16 * rt + r, N - 1);
+    int row = t0 + 16 * rt + r;
+    if (tail) row = min(row, N - 1);
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc) kv.kop[rt][kc] = *(const u32x4*)(Ku + (size_t)row * D + 32 * kc + 8 * g);
   }
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const int row = min(t0 + (j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4)), N - 1);
+    int row = t0 + (j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4));
+    if (tail) row = min(row, N - 1);
     const uint16_t* p = Vu + (size_t)row * D + EV * r;
     if constexpr (EV == 2) {
       kv.vraw[j][0] = *(const uint32_t*)p;
@@ -241,78 +284,65 @@ __device__ __forceinline__ void agg_load(const uint16_t* __restrict__ Ku, const 
   }
 }
 
-template <class E, int D, int NAT, bool BIAS>
-__device__ __forceinline__ void agg_compute(const KVRegs<D>& kv, int t0, int N, int n,
-                                            const u32x4 (&areg)[NAT][D / 32], AggState<D, NAT>& st, float sc,
-                                            int lane, const BiasArgs& b1, int gh, int gw) {
+// TAIL: the step may reach beyond N (mask those tokens).  Scores stay unscaled ("raw") until the exponent:
+// p = exp2(raw * f - m) with f = scale * log2(e) folded into one fma; with a bias the transform
+// raw <- raw * f + bias * log2(e) is applied first and f becomes 1.
+template <class E, int D, bool BIAS, bool TAIL>
+__device__ __forceinline__ void agg_compute(const KVRegs<D>& kv, int t0, int N, int n, int at0,
+                                            const u32x4 (&areg1)[D / 32], AggState<D>& st, float sc, int lane,
+                                            const BiasArgs& b1, int gh, int gw) {
   constexpr int KC = D / 32, EV = D / 16;
   const int r = lane & 15, g = lane >> 4;
 
-  // scores S^T = K A^T : tile (rt, at), element i <-> token t0+16rt+4g+i, agent 16at+r
-  f32x4 s[2][NAT];
+  // scores S^T = K A^T : tile rt, element i <-> token t0+16rt+4g+i, agent 16*at0+r
+  f32x4 s[2];
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt)
+  for (int rt = 0; rt < 2; ++rt) {
+    f32x4 c = {0, 0, 0, 0};
 #pragma unroll
-    for (int at = 0; at < NAT; ++at) {
-      f32x4 c = {0, 0, 0, 0};
-#pragma unroll
-      for (int kc = 0; kc < KC; ++kc) c = Mx<E>::mma(kv.kop[rt][kc], areg[at][kc], c);
-      s[rt][at] = c;
-    }
-
-  float mnew[NAT];
-  bool grew = false;
-#pragma unroll
-  for (int at = 0; at < NAT; ++at) {
-    float mx = kNegBig;
+    for (int kc = 0; kc < KC; ++kc) c = Mx<E>::mma(kv.kop[rt][kc], areg1[kc], c);
+    s[rt] = c;
+  }
+  const float f = BIAS ? 1.0f : sc;
+  if constexpr (BIAS || TAIL) {
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int tok = t0 + 16 * rt + 4 * g + i;
-        float v = s[rt][at][i] * sc;
+        float v = s[rt][i];
         if constexpr (BIAS) {
           const int tc = min(tok, N - 1);
-          v += kLog2e * bias1_at(b1, min(16 * at + r, n - 1), tc / gw, tc % gw, gh, gw);
+          v = v * sc + kLog2e * bias1_at(b1, min(16 * at0 + r, n - 1), tc / gw, tc % gw, gh, gw);
         }
-        v = tok < N ? v : -INFINITY;
-        s[rt][at][i] = v;
-        mx = fmaxf(mx, v);
+        if constexpr (TAIL) v = tok < N ? v : -INFINITY;
+        s[rt][i] = v;
       }
-    mx = xor16_32_max(mx);
-    mnew[at] = fmaxf(st.m[at], mx);
-    grew |= mnew[at] > st.m[at];
   }
-  if (__any(grew)) {
+  float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                   fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+  mx = xor16_32_max(mx);
+  const float mnew = fmaxf(st.m, mx * f);
+  if (__any(mnew > st.m)) {
+    const float alpha = fast_exp2(st.m - mnew);
+    st.m = mnew;
+    st.l *= alpha;
 #pragma unroll
-    for (int at = 0; at < NAT; ++at) {
-      const float alpha = fast_exp2(st.m[at] - mnew[at]);
-      st.m[at] = mnew[at];
-      st.l[at] *= alpha;
-#pragma unroll
-      for (int e = 0; e < EV; ++e) st.acc[e][at] *= alpha;
-    }
+    for (int e = 0; e < EV; ++e) st.acc[e] *= alpha;
   }
-
   // probabilities, packed as the B operand of the value product
-  u32x4 pk[NAT];
+  float p[2][4];
+  const float nm = -st.m;
 #pragma unroll
-  for (int at = 0; at < NAT; ++at) {
-    float p[2][4];
-    float sum = 0.0f;
+  for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        p[rt][i] = fast_exp2(s[rt][at][i] - st.m[at]);
-        sum += p[rt][i];
-      }
-    st.l[at] += sum;
-    pk[at][0] = Mx<E>::pack2(p[0][0], p[0][1]);
-    pk[at][1] = Mx<E>::pack2(p[0][2], p[0][3]);
-    pk[at][2] = Mx<E>::pack2(p[1][0], p[1][1]);
-    pk[at][3] = Mx<E>::pack2(p[1][2], p[1][3]);
-  }
+    for (int i = 0; i < 4; ++i) p[rt][i] = fast_exp2(__builtin_fmaf(s[rt][i], f, nm));
+  st.l += ((p[0][0] + p[0][1]) + (p[0][2] + p[0][3])) + ((p[1][0] + p[1][1]) + (p[1][2] + p[1][3]));
+  u32x4 pk;
+  pk[0] = Mx<E>::pack2(p[0][0], p[0][1]);
+  pk[1] = Mx<E>::pack2(p[0][2], p[0][3]);
+  pk[2] = Mx<E>::pack2(p[1][0], p[1][1]);
+  pk[3] = Mx<E>::pack2(p[1][2], p[1][3]);
 
   // V_A^T += V^T P^T : operand e holds channel EV*r + e of the 8 k-slot rows
 #pragma unroll
@@ -321,80 +351,80 @@ __device__ __forceinline__ void agg_compute(const KVRegs<D>& kv, int t0, int N, 
     const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) vop[jj] = __builtin_amdgcn_perm(kv.vraw[2 * jj + 1][e / 2], kv.vraw[2 * jj][e / 2], sel);
-#pragma unroll
-    for (int at = 0; at < NAT; ++at) st.acc[e][at] = Mx<E>::mma(vop, pk[at], st.acc[e][at]);
+    st.acc[e] = Mx<E>::mma(vop, pk, st.acc[e]);
   }
 }
 
-// Walk the steps t0 = first, first + stride, ... < end with the next step's K/V loads in flight
-// while the current step is computed.  `cur` already holds the loads of step `first` (if first < end).
-template <class E, int D, int NAT, bool BIAS>
+template <class E, int D, bool BIAS>
+__device__ __forceinline__ void agg_compute_any(const KVRegs<D>& kv, int t0, int N, int n, int at0,
+                                                const u32x4 (&areg1)[D / 32], AggState<D>& st, float sc, int lane,
+                                                const BiasArgs& b1, int gh, int gw) {
+  if constexpr (BIAS) {
+    agg_compute<E, D, true, true>(kv, t0, N, n, at0, areg1, st, sc, lane, b1, gh, gw);
+  } else {
+    if (t0 + 32 > N)
+      agg_compute<E, D, false, true>(kv, t0, N, n, at0, areg1, st, sc, lane, b1, gh, gw);
+    else
+      agg_compute<E, D, false, false>(kv, t0, N, n, at0, areg1, st, sc, lane, b1, gh, gw);
+  }
+}
+
+// Walk the steps t0 = first, first + stride, ... < end.  The loads of the next two steps are in
+// flight while a step is computed; `k0` / `k1` already hold the loads of steps `first` and
+// `first + stride` (when those exist).
+template <class E, int D, bool BIAS>
 __device__ __forceinline__ void agg_range(const uint16_t* __restrict__ Ku, const uint16_t* __restrict__ Vu,
-                                          KVRegs<D>& cur, int first, int stride, int end, int n,
-                                          const u32x4 (&areg)[NAT][D / 32], AggState<D, NAT>& st, float sc, int lane,
+                                          KVRegs<D>& k0, KVRegs<D>& k1, int first, int stride, int end, int n,
+                                          int at0, const u32x4 (&areg1)[D / 32], AggState<D>& st, float sc, int lane,
                                           const BiasArgs& b1, int gh, int gw) {
-  for (int t0 = first; t0 < end; t0 += stride) {
-    KVRegs<D> nxt;
-    const int tn = t0 + stride;
-    if (tn < end) agg_load<D>(Ku, Vu, tn, end, lane, nxt);
-    agg_compute<E, D, NAT, BIAS>(cur, t0, end, n, areg, st, sc, lane, b1, gh, gw);
-    if (tn < end) cur = nxt;
+  for (int t0 = first; t0 < end; t0 += 2 * stride) {
+    agg_compute_any<E, D, BIAS>(k0, t0, end, n, at0, areg1, st, sc, lane, b1, gh, gw);
+    if (t0 + 2 * stride < end) agg_load<D>(Ku, Vu, t0 + 2 * stride, end, lane, k0);
+    if (t0 + stride < end) {
+      agg_compute_any<E, D, BIAS>(k1, t0 + stride, end, n, at0, areg1, st, sc, lane, b1, gh, gw);
+      if (t0 + 3 * stride < end) agg_load<D>(Ku, Vu, t0 + 3 * stride, end, lane, k1);
+    }
   }
 }
 
-template <int D, int NAT>
-__device__ __forceinline__ void agg_init(AggState<D, NAT>& st) {
+template <int D>
+__device__ __forceinline__ void agg_init(AggState<D>& st) {
+  st.m = kNegBig;
+  st.l = 0.0f;
 #pragma unroll
-  for (int at = 0; at < NAT; ++at) {
-    st.m[at] = kNegBig;
-    st.l[at] = 0.0f;
-#pragma unroll
-    for (int e = 0; e < D / 16; ++e) st.acc[e][at] = f32x4{0, 0, 0, 0};
-  }
+  for (int e = 0; e < D / 16; ++e) st.acc[e] = f32x4{0, 0, 0, 0};
 }
 
+// Merge of the token slices of a block: the waves of slices 1.. store their state, the waves of
+// slice 0 fold them in (fixed order).  slots: (TS-1) * NAT * NREG * 64 floats.  Every wave calls
+// this (one block-wide barrier inside when TS > 1).
 template <int D, int NAT>
-__device__ __forceinline__ void agg_store_lds(const AggState<D, NAT>& st, float* slot, int lane) {
-  int q = 0;
+__device__ __forceinline__ void agg_slice_merge(AggState<D>& st, float* slots, int at0, int ts, int TS, int lane) {
+  constexpr int NREG = Geo<D, NAT>::NREG, EV = D / 16;
+  if (TS == 1) return;
+  if (ts > 0) {
+    float* slot = slots + ((size_t)(ts - 1) * NAT + at0) * NREG * 64;
+    slot[lane] = st.m;
+    slot[64 + lane] = st.l;
 #pragma unroll
-  for (int at = 0; at < NAT; ++at) {
-    slot[(q++) * 64 + lane] = st.m[at];
-    slot[(q++) * 64 + lane] = st.l[at];
+    for (int e = 0; e < EV; ++e)
 #pragma unroll
-    for (int e = 0; e < D / 16; ++e)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) slot[(q++) * 64 + lane] = st.acc[e][at][i];
+      for (int i = 0; i < 4; ++i) slot[(2 + 4 * e + i) * 64 + lane] = st.acc[e][i];
   }
-}
-
-template <int D, int NAT>
-__device__ __forceinline__ void agg_merge_lds(AggState<D, NAT>& st, const float* slot, int lane) {
-  int q = 0;
+  __syncthreads();
+  if (ts == 0) {
+    for (int o = 1; o < TS; ++o) {
+      const float* slot = slots + ((size_t)(o - 1) * NAT + at0) * NREG * 64;
+      const float mo = slot[lane], lo = slot[64 + lane];
+      const float mn = fmaxf(st.m, mo);
+      const float a = fast_exp2(st.m - mn), b = fast_exp2(mo - mn);
+      st.m = mn;
+      st.l = st.l * a + lo * b;
 #pragma unroll
-  for (int at = 0; at < NAT; ++at) {
-    const float mo = slot[(q++) * 64 + lane];
-    const float lo = slot[(q++) * 64 + lane];
-    const float mn = fmaxf(st.m[at], mo);
-    const float a = fast_exp2(st.m[at] - mn), b = fast_exp2(mo - mn);
-    st.m[at] = mn;
-    st.l[at] = st.l[at] * a + lo * b;
+      for (int e = 0; e < EV; ++e)
 #pragma unroll
-    for (int e = 0; e < D / 16; ++e)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) st.acc[e][at][i] = st.acc[e][at][i] * a + slot[(q++) * 64 + lane] * b;
-  }
-}
-
-// Tree merge of the W wave states of a block through LDS; wave 0 ends with the total.
-// slots: (W/2) * NREG * 64 floats.  Every wave calls this (block-wide barriers inside).
-template <int D, int NAT>
-__device__ __forceinline__ void agg_block_merge(AggState<D, NAT>& st, float* slots, int wave, int W, int lane) {
-  constexpr int NREG = Geo<D, NAT>::NREG;
-  for (int half = W >> 1; half >= 1; half >>= 1) {
-    if (wave >= half && wave < 2 * half) agg_store_lds<D, NAT>(st, slots + (size_t)(wave - half) * NREG * 64, lane);
-    __syncthreads();
-    if (wave < half) agg_merge_lds<D, NAT>(st, slots + (size_t)wave * NREG * 64, lane);
-    __syncthreads();
+        for (int i = 0; i < 4; ++i) st.acc[e][i] = st.acc[e][i] * a + slot[(2 + 4 * e + i) * 64 + lane] * b;
+    }
   }
 }
 
@@ -469,32 +499,35 @@ __device__ __forceinline__ void bcast_compute(const QRegs<D>& q, const uint16_t*
         x = tokc - y * gw;
       }
     }
+    // scores stay unscaled until the exponent (one fma per element); with a bias they are
+    // transformed to raw * f + bias * log2(e) first and the factor becomes 1
+    const float f = BIAS ? 1.0f : sc;
 #pragma unroll
     for (int at = 0; at < NAT; ++at) {
       f32x4 c = {0, 0, 0, 0};
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) c = Mx<E>::mma(areg[at][kc], q.qop[tt][kc], c);
+      if (BIAS || at == NAT - 1) {      // only the last agent tile can hold padded agents
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int a = 16 * at + 4 * g + i;
-        float v = c[i] * sc;
-        if constexpr (BIAS) v += kLog2e * bias2_at(b2, min(a, n - 1), y, x, gh, gw, n);
-        v = a < n ? v : -INFINITY;
-        c[i] = v;
-        mx = fmaxf(mx, v);
+        for (int i = 0; i < 4; ++i) {
+          const int a = 16 * at + 4 * g + i;
+          float v = c[i];
+          if constexpr (BIAS) v = v * sc + kLog2e * bias2_at(b2, min(a, n - 1), y, x, gh, gw, n);
+          c[i] = a < n ? v : -INFINITY;
+        }
       }
+      mx = fmaxf(mx, fmaxf(fmaxf(c[0], c[1]), fmaxf(c[2], c[3])));
       s[at] = c;
     }
     mx = xor16_32_max(mx);
+    const float nm = -mx * f;
     float sum = 0.0f;
 #pragma unroll
-    for (int at = 0; at < NAT; ++at)
+    for (int at = 0; at < NAT; ++at) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float p = fast_exp2(s[at][i] - mx);
-        s[at][i] = p;
-        sum += p;
-      }
+      for (int i = 0; i < 4; ++i) s[at][i] = fast_exp2(__builtin_fmaf(s[at][i], f, nm));
+      sum += (s[at][0] + s[at][1]) + (s[at][2] + s[at][3]);
+    }
     sum = xor16_32_sum(sum);
     const float inv = 1.0f / sum;
     u32x4 pk[KS];
@@ -595,30 +628,20 @@ __device__ __forceinline__ void bcast_dispatch(bool bias2, bool epi, QRegs<D>& c
   }
 }
 
-// final V_A of wave 0 -> LDS rows (element type) and, optionally, fp32 global
+// final V_A rows of one agent tile -> LDS rows (element type)
 template <class E, int D, int NAT>
-__device__ __forceinline__ void agg_finish(AggState<D, NAT>& st, uint16_t* VA_lds, float* __restrict__ VA_glob,
-                                           int n, int lane) {
+__device__ __forceinline__ void agg_finish(AggState<D>& st, uint16_t* VA_lds, int at0, int lane) {
   constexpr int EV = D / 16, AS = Geo<D, NAT>::AS;
   const int r = lane & 15, g = lane >> 4;
+  const float inv = 1.0f / xor16_32_sum(st.l);
+  const int a = 16 * at0 + r;
 #pragma unroll
-  for (int at = 0; at < NAT; ++at) {
-    const float l = xor16_32_sum(st.l[at]);
-    const float inv = 1.0f / l;
-    const int a = 16 * at + r;
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int e = 0; e < EV; e += 2) {
-        const int ch = EV * (4 * g + i) + e;
-        const float v0 = st.acc[e][at][i] * inv, v1 = st.acc[e + 1][at][i] * inv;
-        *(uint32_t*)(VA_lds + a * AS + ch) = Mx<E>::pack2(v0, v1);
-        if (VA_glob && a < n) {
-          VA_glob[(size_t)a * D + ch] = v0;
-          VA_glob[(size_t)a * D + ch + 1] = v1;
-        }
-      }
-  }
+    for (int e = 0; e < EV; e += 2) {
+      const int ch = EV * (4 * g + i) + e;
+      *(uint32_t*)(VA_lds + a * AS + ch) = Mx<E>::pack2(st.acc[e][i] * inv, st.acc[e + 1][i] * inv);
+    }
 }
 
 __device__ __forceinline__ BiasArgs head_bias1(BiasArgs b, int hd, int n, int gh, int gw) {
@@ -636,9 +659,11 @@ __device__ __forceinline__ BiasArgs head_bias2(BiasArgs b, int hd, int n, int gh
 
 // ---------------------------------------------------------------------------
 // Kernel 1: the whole forward pass of one unit in one block, for units whose Q rows fit in LDS.
-// Every global load of the block is issued up front (K/V of each wave's first step into registers,
-// Q into LDS), so the cold-HBM latency is paid once; pooling and the broadcast then read Q from LDS.
-// grid = units.  LDS: A rows | V_A rows | Q rows (N x AS) | (W/2) merge slots.
+// Every global load of the block is issued up front (K/V of each wave's first two steps into
+// registers, Q into LDS), so the cold-HBM latency is paid once; pooling and the broadcast then read
+// Q from LDS.  grid = units, block = NAT * TS waves (wave = agent tile x token slice in the
+// aggregation, token slice in the broadcast).
+// LDS: A rows | V_A rows | Q rows (N x AS) | (TS-1) * NAT merge slots.
 // ---------------------------------------------------------------------------
 template <class E, int D, int NAT, bool MODULE>
 __global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
@@ -654,14 +679,17 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
   float* slots = (float*)(Q_lds + (size_t)((N + 31) / 32 * 32) * AS);
 
   const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
+  const int TS = W / NAT, at0 = wave % NAT, ts = wave / NAT;
   const int hd = u % heads;
   const uint16_t* Qu = Q + (size_t)u * N * D;
   const uint16_t* Ku = K + (size_t)u * N * D;
   const uint16_t* Vu = V + (size_t)u * N * D;
   uint16_t* Ou = O + (size_t)u * N * D;
 
-  KVRegs<D> kv0;
-  if (32 * wave < N) agg_load<D>(Ku, Vu, 32 * wave, N, lane, kv0);
+  AA_TL(0);
+  KVRegs<D> k0, k1;
+  if (32 * ts < N) agg_load<D>(Ku, Vu, 32 * ts, N, lane, k0);
+  if (32 * (ts + TS) < N) agg_load<D>(Ku, Vu, 32 * (ts + TS), N, lane, k1);
 
   const int total = N * CH;
   for (int base = tid; base < total; base += 4 * blockDim.x) {
@@ -679,30 +707,37 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
   }
   if (Agiven) load_agents_to_lds<D, NAT>(Agiven + (size_t)u * n * D, A_lds, n, tid, blockDim.x);
   __syncthreads();
+  AA_TL(1);
   if (!Agiven) {
     pool_unit_to_lds<E, D, NAT>(Q_lds, AS, A_lds, n, gh, gw, ah, aw, tid, blockDim.x);
     __syncthreads();
   }
+  AA_TL(2);
+
+  {
+    u32x4 areg1[D / 32];
+    load_a_tile<D, NAT>(A_lds, at0, areg1, lane);
+    AggState<D> st;
+    agg_init<D>(st);
+    const BiasArgs hb1 = head_bias1(b1, hd, n, gh, gw);
+    bool agg_done = false;
+    if constexpr (MODULE) {
+      if (hb1.any()) {
+        agg_range<E, D, true>(Ku, Vu, k0, k1, 32 * ts, 32 * TS, N, n, at0, areg1, st, sc1, lane, hb1, gh, gw);
+        agg_done = true;
+      }
+    }
+    if (!agg_done) agg_range<E, D, false>(Ku, Vu, k0, k1, 32 * ts, 32 * TS, N, n, at0, areg1, st, sc1, lane, hb1, gh, gw);
+    AA_TL(3);
+    agg_slice_merge<D, NAT>(st, slots, at0, ts, TS, lane);
+    AA_TL(4);
+    if (ts == 0) agg_finish<E, D, NAT>(st, VA_lds, at0, lane);
+  }
+  __syncthreads();
+  AA_TL(5);
 
   u32x4 areg[NAT][D / 32];
   load_a_regs<D, NAT>(A_lds, areg, lane);
-
-  AggState<D, NAT> st;
-  agg_init<D, NAT>(st);
-  const BiasArgs hb1 = head_bias1(b1, hd, n, gh, gw);
-  const bool bias1 = MODULE && hb1.any();
-  bool agg_done = false;
-  if constexpr (MODULE) {
-    if (bias1) {
-      agg_range<E, D, NAT, true>(Ku, Vu, kv0, 32 * wave, 32 * W, N, n, areg, st, sc1, lane, hb1, gh, gw);
-      agg_done = true;
-    }
-  }
-  if (!agg_done) agg_range<E, D, NAT, false>(Ku, Vu, kv0, 32 * wave, 32 * W, N, n, areg, st, sc1, lane, hb1, gh, gw);
-  agg_block_merge<D, NAT>(st, slots, wave, W, lane);
-  if (wave == 0) agg_finish<E, D, NAT>(st, VA_lds, nullptr, n, lane);
-  __syncthreads();
-
   u32x4 vaop[D / 16][(NAT + 1) / 2];
   load_va_regs<D, NAT>(VA_lds, vaop, lane);
   const BiasArgs hb2 = head_bias2(b2, hd, n, gh, gw);
@@ -712,8 +747,10 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
   const bool epi = MODULE && (w9 != nullptr || vk != 0.0f);
   QRegs<D> q0;
   if (32 * wave < N) bcast_load<D>(Q_lds, AS, 32 * wave, N, lane, q0);
+  AA_TL(6);
   bcast_dispatch<E, D, NAT, MODULE>(bias2, epi, q0, Q_lds, AS, Vu, Ou, 32 * wave, 32 * W, N, N, n, areg, vaop, sc2,
                                     lane, hb2, w9, wb, vk, gh, gw);
+  AA_TL(7);
 }
 
 // ---------------------------------------------------------------------------
@@ -731,9 +768,9 @@ __global__ __launch_bounds__(256) void small_pool_kernel(const uint16_t* __restr
 }
 
 // ---------------------------------------------------------------------------
-// Kernel 3: split-N aggregation.  grid = (S, units); block (s, u) walks the tokens
-// [s*chunk, min(N, (s+1)*chunk)), chunk a multiple of 32, merges its waves and writes
-// the un-normalised partial: acc [u][s][n][D], m and l [u][s][n] (m in log2 domain).
+// Kernel 3: split-N aggregation.  grid = (S, units), block = NAT * TS waves; block (s, u) walks the
+// tokens [s*chunk, min(N, (s+1)*chunk)), chunk a multiple of 32; wave = (agent tile, token slice).
+// Writes the un-normalised partial: acc [u][s][n][D], m and l [u][s][n] (m in the log2 domain).
 // ---------------------------------------------------------------------------
 template <class E, int D, int NAT, bool MODULE>
 __global__ __launch_bounds__(64 * kMaxWaves) void small_aggregate_kernel(
@@ -746,49 +783,51 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_aggregate_kernel(
   float* slots = (float*)(A_lds + 16 * NAT * AS);
   const int s = blockIdx.x, S = gridDim.x, u = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
+  const int TS = W / NAT, at0 = wave % NAT, ts = wave / NAT;
   const uint16_t* Ku = K + (size_t)u * N * D;
   const uint16_t* Vu = V + (size_t)u * N * D;
 
+  AA_TL(0);
   const int tbeg = s * chunk, tend = min(N, tbeg + chunk);
-  KVRegs<D> kv0;
-  if (tbeg + 32 * wave < tend) agg_load<D>(Ku, Vu, tbeg + 32 * wave, tend, lane, kv0);
+  const int first = tbeg + 32 * ts, stride = 32 * TS;
+  KVRegs<D> k0, k1;
+  if (first < tend) agg_load<D>(Ku, Vu, first, tend, lane, k0);
+  if (first + stride < tend) agg_load<D>(Ku, Vu, first + stride, tend, lane, k1);
   load_agents_to_lds<D, NAT>(A + (size_t)u * n * D, A_lds, n, tid, blockDim.x);
   __syncthreads();
-  u32x4 areg[NAT][D / 32];
-  load_a_regs<D, NAT>(A_lds, areg, lane);
+  AA_TL(1);
+  u32x4 areg1[D / 32];
+  load_a_tile<D, NAT>(A_lds, at0, areg1, lane);
 
-  AggState<D, NAT> st;
-  agg_init<D, NAT>(st);
+  AggState<D> st;
+  agg_init<D>(st);
   const BiasArgs hb1 = head_bias1(b1, u % heads, n, gh, gw);
-  const bool bias1 = MODULE && hb1.any();
   bool agg_done = false;
   if constexpr (MODULE) {
-    if (bias1) {
-      agg_range<E, D, NAT, true>(Ku, Vu, kv0, tbeg + 32 * wave, 32 * W, tend, n, areg, st, sc1, lane, hb1, gh, gw);
+    if (hb1.any()) {
+      agg_range<E, D, true>(Ku, Vu, k0, k1, first, stride, tend, n, at0, areg1, st, sc1, lane, hb1, gh, gw);
       agg_done = true;
     }
   }
-  if (!agg_done)
-    agg_range<E, D, NAT, false>(Ku, Vu, kv0, tbeg + 32 * wave, 32 * W, tend, n, areg, st, sc1, lane, hb1, gh, gw);
-  agg_block_merge<D, NAT>(st, slots, wave, W, lane);
-  if (wave == 0) {
+  if (!agg_done) agg_range<E, D, false>(Ku, Vu, k0, k1, first, stride, tend, n, at0, areg1, st, sc1, lane, hb1, gh, gw);
+  AA_TL(2);
+  agg_slice_merge<D, NAT>(st, slots, at0, ts, TS, lane);
+  AA_TL(3);
+  if (ts == 0) {
     const int r = lane & 15, g = lane >> 4;
     const size_t base = (size_t)u * S + s;
+    const int a = 16 * at0 + r;
+    const float l = xor16_32_sum(st.l);
+    if (a < n) {
+      if (g == 0) {
+        part_m[base * n + a] = st.m;
+        part_l[base * n + a] = l;
+      }
 #pragma unroll
-    for (int at = 0; at < NAT; ++at) {
-      const int a = 16 * at + r;
-      const float l = xor16_32_sum(st.l[at]);
-      if (a < n) {
-        if (g == 0) {
-          part_m[base * n + a] = st.m[at];
-          part_l[base * n + a] = l;
-        }
+      for (int i = 0; i < 4; ++i) {
+        float* dst = part_acc + (base * n + a) * D + EV * (4 * g + i);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float* dst = part_acc + (base * n + a) * D + EV * (4 * g + i);
-#pragma unroll
-          for (int e = 0; e < EV; ++e) dst[e] = st.acc[e][at][i];
-        }
+        for (int e = 0; e < EV; ++e) dst[e] = st.acc[e][i];
       }
     }
   }
@@ -840,6 +879,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_broadcast_kernel(
   const uint16_t* Vu = V ? V + (size_t)u * N * D : nullptr;
   uint16_t* Ou = O + (size_t)u * N * D;
 
+  AA_TL(0);
   const int tbeg = blockIdx.x * chunk, tend = min(N, tbeg + chunk);
   QRegs<D> q0;
   if (tbeg + 32 * wave < tend) bcast_load<D>(Qu, D, tbeg + 32 * wave, N, lane, q0);
@@ -855,10 +895,12 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_broadcast_kernel(
     *(uint32_t*)(VA_lds + a * AS + 2 * c2) = w;
   }
   __syncthreads();
+  AA_TL(1);
   u32x4 areg[NAT][D / 32];
   load_a_regs<D, NAT>(A_lds, areg, lane);
   u32x4 vaop[D / 16][(NAT + 1) / 2];
   load_va_regs<D, NAT>(VA_lds, vaop, lane);
+  AA_TL(2);
 
   const BiasArgs hb2 = head_bias2(b2, hd, n, gh, gw);
   const bool bias2 = MODULE && hb2.any();
@@ -867,6 +909,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_broadcast_kernel(
   const bool epi = MODULE && (w9 != nullptr || vk != 0.0f);
   bcast_dispatch<E, D, NAT, MODULE>(bias2, epi, q0, Qu, D, Vu, Ou, tbeg + 32 * wave, 32 * W, tend, N, n, areg, vaop,
                                     sc2, lane, hb2, w9, wb, vk, gh, gw);
+  AA_TL(3);
 }
 
 // ---------------------------------------------------------------------------
@@ -877,8 +920,16 @@ bool small_supported(const Problem& p) {
   return (p.dtype == 1 || p.dtype == 2) && (p.d == 32 || p.d == 64) && p.n <= 64 && p.N <= (1 << 20);
 }
 
-// waves per block for a range of `tokens` tokens: one 32-token step per wave if possible
-// (power of two because of the tree merge, at most kMaxWaves)
+// Token slices per block for a range of `tokens` tokens and NAT agent tiles: as many as there are
+// pairs of 32-token steps, while NAT * TS stays within kMaxWaves.
+static int slices_for(int tokens, int nat) {
+  const int steps = (tokens + 31) / 32;
+  int ts = 1;
+  while (2 * ts * nat <= kMaxWaves && 2 * ts <= steps) ts *= 2;
+  return ts;
+}
+
+// waves per block of the broadcast kernel for a range of `tokens` tokens
 static int waves_for(int tokens) {
   const int steps = (tokens + 31) / 32;
   int w = 1;
@@ -887,9 +938,9 @@ static int waves_for(int tokens) {
 }
 
 template <int D, int NAT>
-static size_t fused_lds_bytes(int W, int N) {
+static size_t fused_lds_bytes(int TS, int N) {
   return (size_t)2 * 16 * NAT * Geo<D, NAT>::AS * 2 + (size_t)((N + 31) / 32 * 32) * Geo<D, NAT>::AS * 2 +
-         (size_t)max(1, W / 2) * Geo<D, NAT>::NREG * 64 * 4;
+         (size_t)max(1, TS - 1) * NAT * Geo<D, NAT>::NREG * 64 * 4;
 }
 
 // The one-block-per-unit kernel keeps the unit's Q rows in LDS: at most 64 KB of them.
@@ -940,12 +991,12 @@ static hipError_t allow_lds(KernelT kernel, size_t bytes) {
 
 hipError_t launch_small_fused(const Problem& p, const void* Q, const void* K, const void* V, const void* A,
                               void* out, hipStream_t st) {
-  const int W = waves_for(p.N);
   const float c1 = p.scale1 * kLog2e, c2 = p.scale2 * kLog2e;
   const bool mod = module_mode(p);
   hipError_t err = hipSuccess;
   AA_SMALL_DISPATCH(p, {
-    const size_t lds = fused_lds_bytes<D, NAT>(W, p.N);
+    const int TS = slices_for(p.N, NAT), W = NAT * TS;
+    const size_t lds = fused_lds_bytes<D, NAT>(TS, p.N);
     auto launch = [&](auto kernel) {
       err = allow_lds(kernel, lds);
       if (err == hipSuccess)
@@ -990,12 +1041,12 @@ int small_split_chunk(int N, int S) {
 hipError_t launch_small_aggregate(const Problem& p, const void* A, const void* K, const void* V,
                                   const Partials& part, hipStream_t st) {
   const int chunk = small_split_chunk(p.N, part.S);
-  const int W = waves_for(chunk);
   const float c1 = p.scale1 * kLog2e;
   const bool mod = p.b1.any();
   hipError_t err = hipSuccess;
   AA_SMALL_DISPATCH(p, {
-    const size_t lds = (size_t)16 * NAT * Geo<D, NAT>::AS * 2 + (size_t)max(1, W / 2) * Geo<D, NAT>::NREG * 64 * 4;
+    const int TS = slices_for(chunk, NAT), W = NAT * TS;
+    const size_t lds = (size_t)16 * NAT * Geo<D, NAT>::AS * 2 + (size_t)max(1, TS - 1) * NAT * Geo<D, NAT>::NREG * 64 * 4;
     auto launch = [&](auto kernel) {
       err = allow_lds(kernel, lds);
       if (err == hipSuccess)
