@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="total footprint of the rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short summary of the other workloads")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for the HBM byte counters when profiling)")
     return ap.parse_args()
 
 
@@ -122,17 +124,38 @@ def timed(fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
-def roofline_for(wl, stage_ms):
-    """Roofline entry of the dominant kernel (the stage with the longest average launch)."""
-    name = max(stage_ms, key=stage_ms.get)
-    ms = stage_ms[name]
+def load_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            table = json.load(f)
+        return table[workload][kernel]["hbm_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+def roofline_for(wl, stage_ms, fused_ms=None):
+    """Roofline entry of the dominant kernel.
+
+    When the whole step is one kernel (the one-block-per-unit path) that kernel is the entry, with the
+    algorithmic bytes of the whole path and the step time as its launch duration.  Otherwise it is the
+    stage with the longest average launch (aggregate = split pass + merge, timed together)."""
+    if fused_ms is not None:
+        name, ms = "path", fused_ms
+        label = "small_fused"
+    else:
+        name = max(stage_ms, key=stage_ms.get)
+        ms = stage_ms[name]
+        label = name
+    traffic = load_traffic(wl.name, label)
     if wl.n >= 1024:
         ach = stage_flops(wl)[name] / (ms * 1e-3) / 1e12
-        return {"kernel": name, "bound": "mfma", "achieved": ach, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / MFMA_PEAK_TFLOPS, "traffic": None, "avg_launch_us": ms * 1e3}
+        return {"kernel": label, "bound": "mfma", "achieved": ach, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / MFMA_PEAK_TFLOPS, "traffic": traffic, "avg_launch_us": ms * 1e3}
     ach = stage_bytes(wl)[name] / (ms * 1e-3) / 1e9
-    return {"kernel": name, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": ach / HBM_PEAK_GBS, "traffic": None, "avg_launch_us": ms * 1e3}
+    return {"kernel": label, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": ach / HBM_PEAK_GBS, "traffic": traffic, "avg_launch_us": ms * 1e3}
 
 
 def measure(wl, binding, args, steps, warmup, module):
@@ -145,13 +168,17 @@ def measure(wl, binding, args, steps, warmup, module):
     stage_ms = {st: timed(lambda i, st=st: ring.stage(st, i), steps, max(3, warmup // 3))
                 for st in ("pool", "aggregate", "broadcast")}
     tokens = wl.batch * wl.N
+    desc = binding.make_desc(wl.batch, wl.heads, wl.N, wl.n, wl.d, {"f32": 0, "f16": 1, "bf16": 2}[wl.dtype],
+                             wl.grid, wl.agent_grid)
+    plan = binding.plan_str(desc)
     res = {
         "ms_per_step": ms,
         "tokens_per_s": tokens / (ms * 1e-3),
         "tflops": stage_flops(wl)["path"] / (ms * 1e-3) / 1e12,
         "path_gbs": stage_bytes(wl)["path"] / (ms * 1e-3) / 1e9,
         "stage_us": {k: v * 1e3 for k, v in stage_ms.items()},
-        "roofline": roofline_for(wl, stage_ms),
+        "roofline": roofline_for(wl, stage_ms, ms if plan == "small_fused" else None),
+        "plan": plan,
         "ring_sets": ring.R,
     }
     res["path_roofline_frac"] = (res["tflops"] / MFMA_PEAK_TFLOPS) if wl.n >= 1024 else (res["path_gbs"] / HBM_PEAK_GBS)
@@ -198,6 +225,14 @@ def main():
     wl = inputs.WORKLOADS[args.workload]
     module = args.mode == "module"
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     torch.cuda.synchronize()
     res, ring = measure(wl, binding, args, args.steps, args.warmup, module)
     line = {
@@ -206,7 +241,8 @@ def main():
         "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "heads": wl.heads, "N": wl.N, "d": wl.d, "n": wl.n,
-                   "mode": args.mode, "cache": "cold (ring of %d input sets)" % res["ring_sets"]},
+                   "mode": args.mode, "cache": "cold (ring of %d input sets)" % res["ring_sets"],
+                   "kernels": res["plan"]},
         "tflops": res["tflops"], "path_gbs": res["path_gbs"], "path_roofline_frac": res["path_roofline_frac"],
         "stage_us": res["stage_us"],
         "roofline": res["roofline"],
@@ -225,7 +261,7 @@ def main():
             torch.cuda.empty_cache()
             others[name] = {"tokens_per_s": r["tokens_per_s"], "ms_per_step": r["ms_per_step"], "tflops": r["tflops"],
                             "path_gbs": r["path_gbs"], "path_roofline_frac": r["path_roofline_frac"],
-                            "stage_us": r["stage_us"], "dominant": r["roofline"]["kernel"],
+                            "stage_us": r["stage_us"], "kernels": r["plan"], "dominant": r["roofline"]["kernel"],
                             "dominant_frac": r["roofline"]["frac"]}
         line["other_workloads"] = others
     print(json.dumps(line))

@@ -119,6 +119,13 @@ aa_status agent_broadcast_fwd(const aa_desc *desc, const void *Q, const void *A,
  * Returns 0 when the descriptor is invalid. */
 uint64_t agent_attn_flops(const aa_desc *desc);
 
+/* Writes a short, human-readable name of the kernel sequence agent_attn_fwd would run for this
+ * problem (pooling when agents_given == 0), e.g. "small_fused" or
+ * "small_pool + small_aggregate(S=7) + small_merge + small_broadcast", assuming 16-byte aligned
+ * tensors.  Host only.  Returns the length written (excluding the terminator), 0 on an invalid
+ * descriptor or a NULL / zero-length buffer. */
+size_t agent_attn_plan_str(const aa_desc *desc, int agents_given, char *buf, size_t buf_len);
+
 /* Static string for a status code. */
 const char *agent_attn_status_str(int status);
 

@@ -39,7 +39,7 @@ class aa_params(ctypes.Structure):
 
 
 EXPORTS = ("agent_attn_workspace_bytes", "agent_attn_fwd", "agent_pool_fwd", "agent_aggregate_fwd",
-           "agent_broadcast_fwd", "agent_attn_flops", "agent_attn_status_str")
+           "agent_broadcast_fwd", "agent_attn_flops", "agent_attn_status_str", "agent_attn_plan_str")
 
 _lib = None
 
@@ -71,6 +71,8 @@ def lib():
         L.agent_aggregate_fwd.argtypes = [dp, vp, vp, vp, pp, vp, ctypes.c_size_t, vp, vp]
         L.agent_broadcast_fwd.restype = ctypes.c_int
         L.agent_broadcast_fwd.argtypes = [dp, vp, vp, vp, vp, pp, vp, vp]
+        L.agent_attn_plan_str.restype = ctypes.c_size_t
+        L.agent_attn_plan_str.argtypes = [dp, ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
         L.agent_attn_status_str.restype = ctypes.c_char_p
         L.agent_attn_status_str.argtypes = [ctypes.c_int]
         _lib = L
@@ -135,6 +137,12 @@ def _check(status, where):
 
 def workspace_bytes(desc: aa_desc, params: aa_params | None = None) -> int:
     return int(lib().agent_attn_workspace_bytes(ctypes.byref(desc), _pp(params)))
+
+
+def plan_str(desc: aa_desc, agents_given: bool = False) -> str:
+    buf = ctypes.create_string_buffer(256)
+    lib().agent_attn_plan_str(ctypes.byref(desc), int(agents_given), buf, 256)
+    return buf.value.decode()
 
 
 def flops(desc: aa_desc) -> int:

@@ -4,6 +4,7 @@
 #include "../../include/agent_attn.h"
 
 #include <math.h>
+#include <stdio.h>
 
 #include <initializer_list>
 
@@ -330,6 +331,27 @@ aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, cons
   st = run_aggregate(pr, agents, K, V, workspace, pl, VA, stream);
   if (st != AA_OK) return st;
   return run_broadcast(pr, Q, agents, VA, V, out, pl, stream);
+}
+
+size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, size_t buf_len) {
+  if (!buf || buf_len == 0) return 0;
+  buf[0] = 0;
+  if (check_desc(desc, false, false) != AA_OK) return 0;
+  const Plan pl = make_plan(desc);
+  const Problem pr = make_problem(desc, nullptr);
+  int len;
+  if (aa::small_supported(pr)) {
+    if (pl.prefer_fused && aa::small_fused_supported(pr))
+      len = snprintf(buf, buf_len, "small_fused");
+    else
+      len = snprintf(buf, buf_len, "%ssmall_aggregate(S=%d) + small_merge + small_broadcast(chunks=%d)",
+                     agents_given ? "" : "small_pool + ", pl.S_small, pl.bcast_chunks);
+  } else {
+    len = snprintf(buf, buf_len, "%saggregate_generic(S=%d) + merge_generic + broadcast_generic",
+                   agents_given ? "" : "pool_generic + ", pl.S);
+  }
+  if (len < 0) return 0;
+  return (size_t)len < buf_len ? (size_t)len : buf_len - 1;
 }
 
 const char* agent_attn_status_str(int status) {

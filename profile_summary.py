@@ -1,0 +1,131 @@
+#!/usr/bin/env python3
+"""Turns rocprofv3 CSV output of `bench.py` runs into the short summaries kept under profiles/.
+
+Three runs of the same workload are expected in one directory (names are the -o prefixes):
+
+  rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload W --no-others --no-cpu-baseline
+  rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d DIR -o fetch -- python3 bench.py --workload W --no-others --no-cpu-baseline --copy-calibration --steps 40
+  rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d DIR -o write -- python3 bench.py --workload W --no-others --no-cpu-baseline --copy-calibration --steps 40
+
+usage: python profile_summary.py DIR W
+writes profiles/W_kernels.md and updates profiles/traffic.json (read back by bench.py for roofline.traffic).
+
+HBM bytes: FETCH_SIZE / WRITE_SIZE are reported in KiB per dispatch; both are scaled by what the same
+counter reads for the plain 1 GiB device-to-device copy that --copy-calibration runs (it moves exactly
+1 GiB in and 1 GiB out), so a mis-scaled counter cancels out.
+"""
+import csv
+import json
+import os
+import re
+import statistics
+import sys
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+GIB_KIB = float(1 << 20)
+
+
+def short(name):
+    name = re.sub(r"\(.*", "", name)
+    return name.replace("void ", "").replace("aa::", "")
+
+
+def stage_of(kernel):
+    k = kernel.lower()
+    if "fused" in k:
+        return "small_fused"
+    if "pool" in k:
+        return "pool"
+    if "aggregate" in k or "merge" in k:
+        return "aggregate"
+    if "broadcast" in k:
+        return "broadcast"
+    return None
+
+
+def read_stats(path):
+    rows = []
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            rows.append((short(r["Name"]), int(r["Calls"]), float(r["AverageNs"]) / 1e3, float(r["MinNs"]) / 1e3,
+                         float(r["MaxNs"]) / 1e3, float(r["Percentage"])))
+    return rows
+
+
+def read_counter(path, counter):
+    """kernel -> list of per-dispatch values of `counter`."""
+    out = {}
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            if r["Counter_Name"] != counter:
+                continue
+            out.setdefault(short(r["Kernel_Name"]), []).append(float(r["Counter_Value"]))
+    return out
+
+
+def calibration(values_by_kernel):
+    """Counter reading (KiB) of the 1 GiB copy: the largest dispatch among the runtime's copy kernels
+    (the same kernel also serves the small host-to-device copies of the benchmark's set-up)."""
+    best = None
+    for k, v in values_by_kernel.items():
+        if "copy" in k.lower():
+            m = max(v)
+            if best is None or m > best:
+                best = m
+    return best
+
+
+def main():
+    d, wl = sys.argv[1], sys.argv[2]
+    lines = ["# rocprofv3 summary: bench.py --workload %s (one MI355X)" % wl, ""]
+    stats_path = os.path.join(d, "stats_kernel_stats.csv")
+    lines += ["## kernel durations (--kernel-trace --stats)", "",
+              "command: `rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py "
+              "--workload %s --no-others --no-cpu-baseline`" % wl, "",
+              "| kernel | calls | avg us | min us | max us | % of GPU time |", "|---|---|---|---|---|---|"]
+    for name, calls, avg, mn, mx, pct in read_stats(stats_path):
+        if name.startswith(("small_", "pool_", "aggregate_", "merge_", "broadcast_", "large_")):
+            lines.append("| `%s` | %d | %.2f | %.2f | %.2f | %.2f |" % (name, calls, avg, mn, mx, pct))
+    traffic = {}
+    fetch_p, write_p = os.path.join(d, "fetch_counter_collection.csv"), os.path.join(d, "write_counter_collection.csv")
+    if os.path.exists(fetch_p) and os.path.exists(write_p):
+        fetch, write = read_counter(fetch_p, "FETCH_SIZE"), read_counter(write_p, "WRITE_SIZE")
+        cf, cw = calibration(fetch), calibration(write)
+        lines += ["", "## HBM traffic per launch (--pmc FETCH_SIZE, --pmc WRITE_SIZE; separate runs)", "",
+                  "commands: `rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d DIR -o fetch -- python3 "
+                  "bench.py --workload %s --no-others --no-cpu-baseline --copy-calibration --steps 40` and the same with "
+                  "WRITE_SIZE / -o write." % wl, "",
+                  "calibration: the 1 GiB device copy reads FETCH_SIZE = %.0f KiB and WRITE_SIZE = %.0f KiB "
+                  "(expected 1048576 each) -> scale factors %.4f and %.4f." % (cf, cw, GIB_KIB / cf, GIB_KIB / cw), "",
+                  "| kernel | fetch MB | write MB | total MB |", "|---|---|---|---|"]
+        per_stage = {}
+        for k in sorted(set(fetch) | set(write)):
+            st = stage_of(k)
+            if st is None or "copy" in k.lower():
+                continue
+            fb = statistics.median(fetch.get(k, [0.0])) * (GIB_KIB / cf) * 1024.0
+            wb = statistics.median(write.get(k, [0.0])) * (GIB_KIB / cw) * 1024.0
+            lines.append("| `%s` | %.2f | %.2f | %.2f |" % (k, fb / 1e6, wb / 1e6, (fb + wb) / 1e6))
+            e = per_stage.setdefault(st, {"fetch": 0.0, "write": 0.0})
+            e["fetch"] += fb
+            e["write"] += wb
+        for st, e in per_stage.items():
+            traffic[st] = {"hbm_bytes_per_launch": e["fetch"] + e["write"], "fetch_bytes": e["fetch"],
+                           "write_bytes": e["write"]}
+    os.makedirs(os.path.join(ROOT, "profiles"), exist_ok=True)
+    with open(os.path.join(ROOT, "profiles", "%s_kernels.md" % wl), "w") as f:
+        f.write("\n".join(lines) + "\n")
+    if traffic:
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        table = {}
+        if os.path.exists(tpath):
+            with open(tpath) as f:
+                table = json.load(f)
+        table[wl] = traffic
+        with open(tpath, "w") as f:
+            json.dump(table, f, indent=1, sort_keys=True)
+    print("\n".join(lines))
+
+
+if __name__ == "__main__":
+    main()

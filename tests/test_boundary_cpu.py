@@ -109,6 +109,13 @@ def test_stage_entry_points_reject_bad_arguments():
     assert L.agent_attn_fwd(None, FAKE, FAKE, FAKE, None, None, FAKE, 1, FAKE, None) == -1
 
 
+def test_plan_string_is_host_only():
+    assert binding.plan_str(make_desc(64, 3, 196, 49, 64, binding.AA_BF16, (14, 14), (7, 7))) == "small_fused"
+    assert "small_aggregate" in binding.plan_str(make_desc(32, 3, 3136, 49, 32, binding.AA_BF16, (56, 56), (7, 7)))
+    assert "generic" in binding.plan_str(make_desc(1, 1, 196, 49, 32, binding.AA_F32, (14, 14), (7, 7)))
+    assert binding.plan_str(make_desc(1, 1, 0, 49, 32, binding.AA_F32)) == ""
+
+
 def test_status_strings():
     for code in range(-8, 1):
         assert binding.status_str(code) not in ("", "unknown status")
