@@ -27,6 +27,8 @@ enum Path { PATH_GENERIC = 0, PATH_SMALL_FUSED = 1, PATH_SMALL_SPLIT = 2 };
 
 struct Plan {
   int S;               // N-splits of the generic aggregation
+  int S_large, chunk_large, waves_large, nw_large;   // large-agent MFMA aggregation: splits, tokens per split,
+                                                      // waves per block, 16-agent tiles per wave
   int S_small;         // N-splits of the small-agent MFMA aggregation
   int bcast_chunks;    // token chunks per unit of the small-agent broadcast
   bool prefer_fused;   // small-agent regime: one block per unit does the whole pass
@@ -113,12 +115,39 @@ void plan_small(const aa_desc* d, Plan& pl) {
   pl.bcast_chunks = (d->N + 511) / 512;
 }
 
+// Large-agent path: agents per block = waves * nw * 16; splits chosen for about 512 blocks, at least
+// 128 tokens per split, split length a multiple of the 64-token K/V tile.
+void plan_large(const aa_desc* d, Plan& pl) {
+  const int64_t units = (int64_t)d->batch * d->heads;
+  pl.nw_large = d->n >= 128 ? 2 : 1;
+  int waves = (d->n + 16 * pl.nw_large - 1) / (16 * pl.nw_large);
+  if (waves > 8) waves = 8;
+  if (waves < 4) waves = 4;          // the staging copies want at least 256 threads
+  pl.waves_large = waves;
+  const int apb = waves * pl.nw_large * 16;
+  const int64_t nblocks = (d->n + apb - 1) / apb;
+  int S = d->n_splits;
+  if (S <= 0) {
+    S = (int)((512 + units * nblocks - 1) / (units * nblocks));
+    const int max_by_len = (d->N + 127) / 128;
+    if (S > max_by_len) S = max_by_len;
+  }
+  if (S > d->N) S = d->N;
+  if (S < 1) S = 1;
+  int chunk = (d->N + S - 1) / S;
+  chunk = (chunk + 63) / 64 * 64;
+  pl.chunk_large = chunk;
+  pl.S_large = (d->N + chunk - 1) / chunk;
+}
+
 Plan make_plan(const aa_desc* d) {
   Plan pl{};
   const size_t units = (size_t)d->batch * d->heads;
   pl.S = choose_splits(d);
   plan_small(d, pl);
-  const int Smax = pl.S > pl.S_small ? pl.S : pl.S_small;
+  plan_large(d, pl);
+  int Smax = pl.S > pl.S_small ? pl.S : pl.S_small;
+  if (pl.S_large > Smax) Smax = pl.S_large;
   size_t off = 0;
   pl.off_A = off;
   off += align_up(units * d->n * d->d * elem_size(d->dtype));
@@ -180,6 +209,18 @@ bool use_small(const Problem& pr, std::initializer_list<const void*> ptrs) {
   return true;
 }
 
+// Large-agent MFMA kernels: fp16 / bf16, d a multiple of 8 (16-byte chunks) up to 128.
+bool large_supported(const Problem& pr) {
+  return (pr.dtype == AA_F16 || pr.dtype == AA_BF16) && pr.d % 8 == 0 && pr.d <= 128;
+}
+bool use_large(const Problem& pr, std::initializer_list<const void*> ptrs) {
+  if (!large_supported(pr)) return false;
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return false;
+  return true;
+}
+int padded_width(int d) { return d <= 32 ? 32 : (d <= 64 ? 64 : 128); }
+
 aa_status check_workspace(const void* ws, size_t bytes, const Plan& pl) {
   if (!ws || ((uintptr_t)ws % kAlign) != 0 || bytes < pl.total) return AA_ERR_WORKSPACE;
   return AA_OK;
@@ -198,6 +239,24 @@ aa_status run_aggregate(const Problem& pr, const void* A, const void* K, const v
     AA_HIP(aa::launch_small_merge(pr, part, VA, st));
     return AA_OK;
   }
+  if (use_large(pr, {A, K, V})) {
+    const Partials part = partials_in(ws, pl, pl.S_large);
+    switch (padded_width(pr.d)) {
+      case 32:
+        AA_HIP(aa::launch_large_aggregate_dp32(pr, A, K, V, part, pl.chunk_large, pl.waves_large, pl.nw_large, st));
+        AA_HIP(aa::launch_large_merge_dp32(pr, part, VA, st));
+        break;
+      case 64:
+        AA_HIP(aa::launch_large_aggregate_dp64(pr, A, K, V, part, pl.chunk_large, pl.waves_large, pl.nw_large, st));
+        AA_HIP(aa::launch_large_merge_dp64(pr, part, VA, st));
+        break;
+      default:
+        AA_HIP(aa::launch_large_aggregate_dp128(pr, A, K, V, part, pl.chunk_large, pl.waves_large, pl.nw_large, st));
+        AA_HIP(aa::launch_large_merge_dp128(pr, part, VA, st));
+        break;
+    }
+    return AA_OK;
+  }
   const Partials part = partials_in(ws, pl, pl.S);
   AA_HIP(aa::launch_aggregate_generic(pr, A, K, V, part, st));
   AA_HIP(aa::launch_merge_generic(pr, part, VA, st));
@@ -206,10 +265,17 @@ aa_status run_aggregate(const Problem& pr, const void* A, const void* K, const v
 
 aa_status run_broadcast(const Problem& pr, const void* Q, const void* A, const float* VA, const void* V, void* out,
                         const Plan& pl, hipStream_t st) {
-  if (use_small(pr, {Q, A, V, out}))
+  if (use_small(pr, {Q, A, V, out})) {
     AA_HIP(aa::launch_small_broadcast(pr, Q, A, VA, V, out, pl.bcast_chunks, st));
-  else
+  } else if (use_large(pr, {Q, A, VA, V, out})) {
+    switch (padded_width(pr.d)) {
+      case 32: AA_HIP(aa::launch_large_broadcast_dp32(pr, Q, A, VA, V, out, 8, st)); break;
+      case 64: AA_HIP(aa::launch_large_broadcast_dp64(pr, Q, A, VA, V, out, 8, st)); break;
+      default: AA_HIP(aa::launch_large_broadcast_dp128(pr, Q, A, VA, V, out, 8, st)); break;
+    }
+  } else {
     AA_HIP(aa::launch_broadcast_generic(pr, Q, A, VA, V, out, st));
+  }
   return AA_OK;
 }
 
@@ -346,6 +412,10 @@ size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, siz
     else
       len = snprintf(buf, buf_len, "%ssmall_aggregate(S=%d) + small_merge + small_broadcast(chunks=%d)",
                      agents_given ? "" : "small_pool + ", pl.S_small, pl.bcast_chunks);
+  } else if (large_supported(pr)) {
+    len = snprintf(buf, buf_len,
+                   "%slarge_aggregate(S=%d, %d agents/block) + large_merge + large_broadcast(256 tokens/block)",
+                   agents_given ? "" : "pool_generic + ", pl.S_large, pl.waves_large * pl.nw_large * 16);
   } else {
     len = snprintf(buf, buf_len, "%saggregate_generic(S=%d) + merge_generic + broadcast_generic",
                    agents_given ? "" : "pool_generic + ", pl.S);

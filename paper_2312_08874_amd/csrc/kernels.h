@@ -57,4 +57,17 @@ hipError_t launch_small_merge(const Problem& p, const Partials& part, float* VA,
 hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A, const float* VA, const void* V,
                                   void* out, int chunks, hipStream_t st);
 
+// --- large-agent regime (any n; fp16 / bf16; d a multiple of 8, d <= 128): flash-style MFMA kernels that
+//     stage the streamed operand in LDS; one set per padded head width DP in {32, 64, 128} ---
+#define AA_DECLARE_LARGE(DP)                                                                                        \
+  hipError_t launch_large_aggregate_dp##DP(const Problem& p, const void* A, const void* K, const void* V,           \
+                                           const Partials& part, int chunk, int waves, int nw, hipStream_t st);     \
+  hipError_t launch_large_merge_dp##DP(const Problem& p, const Partials& part, float* VA, hipStream_t st);          \
+  hipError_t launch_large_broadcast_dp##DP(const Problem& p, const void* Q, const void* A, const float* VA,         \
+                                           const void* V, void* out, int waves, hipStream_t st);
+AA_DECLARE_LARGE(32)
+AA_DECLARE_LARGE(64)
+AA_DECLARE_LARGE(128)
+#undef AA_DECLARE_LARGE
+
 }  // namespace aa

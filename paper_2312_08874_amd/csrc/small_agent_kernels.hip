@@ -64,6 +64,7 @@ struct Mx<ElemBF16> {
     f32x2 v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
   }
+  static __device__ __forceinline__ float bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
   static __device__ __forceinline__ void unpack2(uint32_t w, float& lo, float& hi) {
     lo = __uint_as_float(w << 16);
     hi = __uint_as_float(w & 0xFFFF0000u);
@@ -79,6 +80,7 @@ struct Mx<ElemF16> {
     f32x2 v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
   }
+  static __device__ __forceinline__ float bits_to_f32(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
   static __device__ __forceinline__ void unpack2(uint32_t w, float& lo, float& hi) {
     f16x2 h = __builtin_bit_cast(f16x2, w);
     lo = (float)h[0];
@@ -564,14 +566,14 @@ __device__ __forceinline__ void bcast_compute(const QRegs<D>& q, const uint16_t*
             for (int kx = -1; kx <= 1; ++kx) {
               const int yy = y + ky, xx = x + kx;
               if (yy >= 0 && yy < gh && xx >= 0 && xx < gw)
-                conv += dwc_w[ch * 9 + (ky + 1) * 3 + (kx + 1)] * E::to_f32(Vu[((size_t)yy * gw + xx) * D + ch]);
+                conv += dwc_w[ch * 9 + (ky + 1) * 3 + (kx + 1)] * Mx<E>::bits_to_f32(Vu[((size_t)yy * gw + xx) * D + ch]);
             }
           o[k] += conv;
         }
       }
       if (vk != 0.0f) {
 #pragma unroll
-        for (int k = 0; k < 4 * EV; ++k) o[k] += vk * E::to_f32(Vu[(size_t)tokc * D + ch0 + k]);
+        for (int k = 0; k < 4 * EV; ++k) o[k] += vk * Mx<E>::bits_to_f32(Vu[(size_t)tokc * D + ch0 + k]);
       }
     }
     if (tok < N) {
