@@ -5,6 +5,7 @@
 
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 
 #include <initializer_list>
 
@@ -27,6 +28,7 @@ enum Path { PATH_GENERIC = 0, PATH_SMALL_FUSED = 1, PATH_SMALL_SPLIT = 2 };
 
 struct Plan {
   int S;               // N-splits of the generic aggregation
+  int bcast_waves_large;                              // waves (32 tokens each) per block of the large broadcast
   int S_large, chunk_large, waves_large, nw_large;   // large-agent MFMA aggregation: splits, tokens per split,
                                                       // waves per block, 16-agent tiles per wave
   int S_small;         // N-splits of the small-agent MFMA aggregation
@@ -117,16 +119,26 @@ void plan_small(const aa_desc* d, Plan& pl) {
 
 // Large-agent path: agents per block = waves * nw * 16; splits chosen for about 512 blocks, at least
 // 128 tokens per split, split length a multiple of the 64-token K/V tile.
+// Tuning override for experiments: integer environment variable, 0 / unset = use the built-in choice.
+int tuning_env(const char* name) {
+  const char* v = getenv(name);
+  return v ? atoi(v) : 0;
+}
+
 void plan_large(const aa_desc* d, Plan& pl) {
   const int64_t units = (int64_t)d->batch * d->heads;
-  pl.nw_large = d->n >= 128 ? 2 : 1;
+  pl.nw_large = 1;     // one 16-agent tile per wave: 117 VGPRs, two blocks of 8 waves per CU (measured best)
+  if (tuning_env("AA_LARGE_NW") == 1 || tuning_env("AA_LARGE_NW") == 2) pl.nw_large = tuning_env("AA_LARGE_NW");
   int waves = (d->n + 16 * pl.nw_large - 1) / (16 * pl.nw_large);
   if (waves > 8) waves = 8;
+  if (tuning_env("AA_LARGE_WAVES") >= 4 && tuning_env("AA_LARGE_WAVES") <= 8 && waves > tuning_env("AA_LARGE_WAVES"))
+    waves = tuning_env("AA_LARGE_WAVES");
   if (waves < 4) waves = 4;          // the staging copies want at least 256 threads
   pl.waves_large = waves;
   const int apb = waves * pl.nw_large * 16;
   const int64_t nblocks = (d->n + apb - 1) / apb;
   int S = d->n_splits;
+  if (S <= 0 && tuning_env("AA_LARGE_S") > 0) S = tuning_env("AA_LARGE_S");
   if (S <= 0) {
     S = (int)((512 + units * nblocks - 1) / (units * nblocks));
     const int max_by_len = (d->N + 127) / 128;
@@ -138,6 +150,9 @@ void plan_large(const aa_desc* d, Plan& pl) {
   chunk = (chunk + 63) / 64 * 64;
   pl.chunk_large = chunk;
   pl.S_large = (d->N + chunk - 1) / chunk;
+  pl.bcast_waves_large = 8;
+  if (tuning_env("AA_LARGE_BWAVES") >= 4 && tuning_env("AA_LARGE_BWAVES") <= 8)
+    pl.bcast_waves_large = tuning_env("AA_LARGE_BWAVES");
 }
 
 Plan make_plan(const aa_desc* d) {
@@ -266,12 +281,12 @@ aa_status run_aggregate(const Problem& pr, const void* A, const void* K, const v
 aa_status run_broadcast(const Problem& pr, const void* Q, const void* A, const float* VA, const void* V, void* out,
                         const Plan& pl, hipStream_t st) {
   if (use_small(pr, {Q, A, V, out})) {
-    AA_HIP(aa::launch_small_broadcast(pr, Q, A, VA, V, out, pl.bcast_chunks, st));
+    AA_HIP(aa::launch_small_broadcast(pr, Q, A, VA, nullptr, V, out, pl.bcast_chunks, st));
   } else if (use_large(pr, {Q, A, VA, V, out})) {
     switch (padded_width(pr.d)) {
-      case 32: AA_HIP(aa::launch_large_broadcast_dp32(pr, Q, A, VA, V, out, 8, st)); break;
-      case 64: AA_HIP(aa::launch_large_broadcast_dp64(pr, Q, A, VA, V, out, 8, st)); break;
-      default: AA_HIP(aa::launch_large_broadcast_dp128(pr, Q, A, VA, V, out, 8, st)); break;
+      case 32: AA_HIP(aa::launch_large_broadcast_dp32(pr, Q, A, VA, V, out, pl.bcast_waves_large, st)); break;
+      case 64: AA_HIP(aa::launch_large_broadcast_dp64(pr, Q, A, VA, V, out, pl.bcast_waves_large, st)); break;
+      default: AA_HIP(aa::launch_large_broadcast_dp128(pr, Q, A, VA, V, out, pl.bcast_waves_large, st)); break;
     }
   } else {
     AA_HIP(aa::launch_broadcast_generic(pr, Q, A, VA, V, out, st));
@@ -394,6 +409,13 @@ aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, cons
     agents = ws + pl.off_A;
   }
   float* VA = (float*)(ws + pl.off_VA);
+  if (use_small(pr, {Q, K, V, agents, out})) {
+    // small-agent regime: the broadcast blocks merge the split partials themselves (no merge launch)
+    const Partials part = partials_in(workspace, pl, pl.S_small);
+    AA_HIP(aa::launch_small_aggregate(pr, agents, K, V, part, stream));
+    AA_HIP(aa::launch_small_broadcast(pr, Q, agents, nullptr, &part, V, out, pl.bcast_chunks, stream));
+    return AA_OK;
+  }
   st = run_aggregate(pr, agents, K, V, workspace, pl, VA, stream);
   if (st != AA_OK) return st;
   return run_broadcast(pr, Q, agents, VA, V, out, pl, stream);
@@ -410,12 +432,13 @@ size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, siz
     if (pl.prefer_fused && aa::small_fused_supported(pr))
       len = snprintf(buf, buf_len, "small_fused");
     else
-      len = snprintf(buf, buf_len, "%ssmall_aggregate(S=%d) + small_merge + small_broadcast(chunks=%d)",
+      len = snprintf(buf, buf_len, "%ssmall_aggregate(S=%d) + small_broadcast(chunks=%d, merges the partials)",
                      agents_given ? "" : "small_pool + ", pl.S_small, pl.bcast_chunks);
   } else if (large_supported(pr)) {
     len = snprintf(buf, buf_len,
-                   "%slarge_aggregate(S=%d, %d agents/block) + large_merge + large_broadcast(256 tokens/block)",
-                   agents_given ? "" : "pool_generic + ", pl.S_large, pl.waves_large * pl.nw_large * 16);
+                   "%slarge_aggregate(S=%d, %d agents/block) + large_merge + large_broadcast(%d tokens/block)",
+                   agents_given ? "" : "pool_generic + ", pl.S_large, pl.waves_large * pl.nw_large * 16,
+                   32 * pl.bcast_waves_large);
   } else {
     len = snprintf(buf, buf_len, "%saggregate_generic(S=%d) + merge_generic + broadcast_generic",
                    agents_given ? "" : "pool_generic + ", pl.S);

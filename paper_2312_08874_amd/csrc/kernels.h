@@ -54,8 +54,10 @@ int small_split_chunk(int N, int S);
 hipError_t launch_small_aggregate(const Problem& p, const void* A, const void* K, const void* V,
                                   const Partials& part, hipStream_t st);
 hipError_t launch_small_merge(const Problem& p, const Partials& part, float* VA, hipStream_t st);
-hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A, const float* VA, const void* V,
-                                  void* out, int chunks, hipStream_t st);
+// V_A either merged (VA, part == nullptr) or as the aggregation's split partials (part, VA unused): the
+// broadcast blocks then do the merge themselves while staging V_A
+hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A, const float* VA,
+                                  const Partials* part, const void* V, void* out, int chunks, hipStream_t st);
 
 // --- large-agent regime (any n; fp16 / bf16; d a multiple of 8, d <= 128): flash-style MFMA kernels that
 //     stage the streamed operand in LDS; one set per padded head width DP in {32, 64, 128} ---

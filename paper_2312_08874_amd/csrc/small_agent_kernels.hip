@@ -863,14 +863,18 @@ __global__ __launch_bounds__(64) void small_merge_kernel(const float* __restrict
 }
 
 // ---------------------------------------------------------------------------
-// Kernel 5: broadcast.  grid = (token chunks, units); A (element type) and V_A
-// (fp32) come from global and are staged once per block.
+// Kernel 5: broadcast.  grid = (token chunks, units); A (element type) and V_A come from global and
+// are staged once per block.  V_A is either given merged (fp32, S_part == 0) or as the S_part split
+// partials of the aggregation kernel, which every block then merges itself while staging (log-sum-exp
+// rule, fixed order; a few KB per block from L2 instead of a separate merge launch).
 // ---------------------------------------------------------------------------
 template <class E, int D, int NAT, bool MODULE>
 __global__ __launch_bounds__(64 * kMaxWaves) void small_broadcast_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ A, const float* __restrict__ VA,
-    const uint16_t* __restrict__ V, uint16_t* __restrict__ O, BiasArgs b2, const float* __restrict__ dwc_w,
-    const float* __restrict__ dwc_b, float sc2, float vk, int N, int n, int heads, int gh, int gw, int chunk) {
+    const float* __restrict__ part_acc, const float* __restrict__ part_m, const float* __restrict__ part_l,
+    int S_part, const uint16_t* __restrict__ V, uint16_t* __restrict__ O, BiasArgs b2,
+    const float* __restrict__ dwc_w, const float* __restrict__ dwc_b, float sc2, float vk, int N, int n, int heads,
+    int gh, int gw, int chunk) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   constexpr int AS = Geo<D, NAT>::AS;
   uint16_t* A_lds = (uint16_t*)smem_raw;
@@ -886,15 +890,29 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_broadcast_kernel(
   QRegs<D> q0;
   if (tbeg + 32 * wave < tend) bcast_load<D>(Qu, D, tbeg + 32 * wave, N, lane, q0);
   load_agents_to_lds<D, NAT>(A + (size_t)u * n * D, A_lds, n, tid, blockDim.x);
-  const float* VAu = VA + (size_t)u * n * D;
-  for (int q = tid; q < 16 * NAT * (D / 2); q += blockDim.x) {
-    const int a = q / (D / 2), c2 = q - a * (D / 2);
-    uint32_t w = 0u;
+  for (int q = tid; q < 16 * NAT * (D / 4); q += blockDim.x) {
+    const int a = q / (D / 4), c4 = q - a * (D / 4);
+    f32x4 out = {0, 0, 0, 0};
     if (a < n) {
-      const f32x2 v = *(const f32x2*)(VAu + (size_t)a * D + 2 * c2);
-      w = Mx<E>::pack2(v[0], v[1]);
+      if (S_part == 0) {
+        out = *(const f32x4*)(VA + ((size_t)u * n + a) * D + 4 * c4);
+      } else {
+        float m = kNegBig;
+#pragma unroll 4
+        for (int sp = 0; sp < S_part; ++sp) m = fmaxf(m, part_m[((size_t)u * S_part + sp) * n + a]);
+        float l = 0.0f;
+#pragma unroll 4
+        for (int sp = 0; sp < S_part; ++sp) {
+          const size_t row = ((size_t)u * S_part + sp) * n + a;
+          const float w = fast_exp2(part_m[row] - m);
+          l += part_l[row] * w;
+          out += *(const f32x4*)(part_acc + row * D + 4 * c4) * w;
+        }
+        out *= 1.0f / l;
+      }
     }
-    *(uint32_t*)(VA_lds + a * AS + 2 * c2) = w;
+    u32x2 w2 = {Mx<E>::pack2(out[0], out[1]), Mx<E>::pack2(out[2], out[3])};
+    *(u32x2*)(VA_lds + a * AS + 4 * c4) = w2;
   }
   __syncthreads();
   AA_TL(1);
@@ -1069,24 +1087,28 @@ hipError_t launch_small_merge(const Problem& p, const Partials& part, float* VA,
   return hipGetLastError();
 }
 
-hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A, const float* VA, const void* V,
-                                  void* out, int chunks, hipStream_t st) {
+hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A, const float* VA,
+                                  const Partials* part, const void* V, void* out, int chunks, hipStream_t st) {
   int chunk = (p.N + chunks - 1) / chunks;
   chunk = (chunk + 31) / 32 * 32;
   const int nchunks = (p.N + chunk - 1) / chunk;
   const int W = waves_for(chunk);
   const float c2 = p.scale2 * kLog2e;
   const bool mod = p.b2.any() || p.dwc_w != nullptr || p.vk != 0.0f;
+  const float* pacc = part ? part->acc : nullptr;
+  const float* pm = part ? part->m : nullptr;
+  const float* plv = part ? part->l : nullptr;
+  const int ps = part ? part->S : 0;
   AA_SMALL_DISPATCH(p, {
     const size_t lds = (size_t)2 * 16 * NAT * Geo<D, NAT>::AS * 2;
     if (mod)
       small_broadcast_kernel<E, D, NAT, true><<<dim3(nchunks, p.units), dim3(64 * W), lds, st>>>(
-          (const uint16_t*)Q, (const uint16_t*)A, VA, (const uint16_t*)V, (uint16_t*)out, p.b2, p.dwc_w, p.dwc_b,
-          c2, p.vk, p.N, p.n, p.heads, p.gh, p.gw, chunk);
+          (const uint16_t*)Q, (const uint16_t*)A, VA, pacc, pm, plv, ps, (const uint16_t*)V, (uint16_t*)out, p.b2,
+          p.dwc_w, p.dwc_b, c2, p.vk, p.N, p.n, p.heads, p.gh, p.gw, chunk);
     else
       small_broadcast_kernel<E, D, NAT, false><<<dim3(nchunks, p.units), dim3(64 * W), lds, st>>>(
-          (const uint16_t*)Q, (const uint16_t*)A, VA, (const uint16_t*)V, (uint16_t*)out, p.b2, p.dwc_w, p.dwc_b,
-          c2, p.vk, p.N, p.n, p.heads, p.gh, p.gw, chunk);
+          (const uint16_t*)Q, (const uint16_t*)A, VA, pacc, pm, plv, ps, (const uint16_t*)V, (uint16_t*)out, p.b2,
+          p.dwc_w, p.dwc_b, c2, p.vk, p.N, p.n, p.heads, p.gh, p.gw, chunk);
   });
   return hipGetLastError();
 }
