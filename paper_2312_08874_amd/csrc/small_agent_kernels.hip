@@ -117,6 +117,7 @@ struct Geo {
   static constexpr int EV = D / 16;          // 16-row tiles along d in the value products
   static constexpr int KS = (NAT + 1) / 2;   // k-steps (pairs of agent tiles) of the broadcast value product
   static constexpr int AS = D + 8;           // LDS row stride (elements) of A, V_A and Q rows
+  static constexpr int RV = 32 * ((NAT + 1) / 2);   // rows of the V_A region (whole k-steps; pad rows are zero)
   static constexpr int NREG = EV * 4 + 2;    // floats per lane of one wave's aggregation state
 };
 
@@ -433,30 +434,30 @@ __device__ __forceinline__ void agg_slice_merge(AggState<D>& st, float* slots, i
 // ---------------------------------------------------------------------------
 // broadcast: one step = 32 tokens, two independent 16-token tiles
 // ---------------------------------------------------------------------------
+// LDS transpose read of 4 x 16 bit (ds_read_b64_tr_b16): within a group of 16 lanes, lane q supplies the
+// address of 4 consecutive elements; lane i receives element i%4 of the chunks addressed by lanes
+// i/4, 4 + i/4, 8 + i/4 and 12 + i/4.
+__device__ __forceinline__ u32x2 lds_read_tr(const uint16_t* p) {
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+  return __builtin_bit_cast(u32x2, v);
+}
+
 // stationary V_A operand: vaop[ct][ks]: row r <-> channel (D/4)*(r/4) + 4ct + r%4,
-// k-slot 8g+j <-> agent 16*(2ks) + 4g+j (j<4) / 16*(2ks+1) + 4g+j-4.
+// k-slot 8g+j <-> agent 16*(2ks) + 4g+j (j<4) / 16*(2ks+1) + 4g+j-4.  Lane q of a 16-lane group points
+// at agent row 4g + q/4 (and 16 rows further for the second half), channel group q%4.
 template <int D, int NAT>
 __device__ __forceinline__ void load_va_regs(const uint16_t* VA_lds, u32x4 (&vaop)[D / 16][(NAT + 1) / 2], int lane) {
   constexpr int AS = Geo<D, NAT>::AS;
-  const int r = lane & 15, g = lane >> 4;
+  const int q = lane & 15, g = lane >> 4;
 #pragma unroll
-  for (int ct = 0; ct < D / 16; ++ct) {
-    const int ch = (D / 4) * (r >> 2) + 4 * ct + (r & 3);
+  for (int ct = 0; ct < D / 16; ++ct)
 #pragma unroll
     for (int ks = 0; ks < (NAT + 1) / 2; ++ks) {
-      u32x4 w;
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int j0 = 2 * jj, j1 = 2 * jj + 1;
-        const int a0 = (j0 < 4 ? 16 * (2 * ks) + 4 * g + j0 : 16 * (2 * ks + 1) + 4 * g + (j0 - 4));
-        const int a1 = (j1 < 4 ? 16 * (2 * ks) + 4 * g + j1 : 16 * (2 * ks + 1) + 4 * g + (j1 - 4));
-        const uint32_t lo = a0 < 16 * NAT ? VA_lds[a0 * AS + ch] : 0u;
-        const uint32_t hi = a1 < 16 * NAT ? VA_lds[a1 * AS + ch] : 0u;
-        w[jj] = lo | (hi << 16);
-      }
-      vaop[ct][ks] = w;
+      const uint16_t* p = VA_lds + (32 * ks + 4 * g + (q >> 2)) * AS + (D / 4) * (q & 3) + 4 * ct;
+      const u32x2 lo = lds_read_tr(p), hi = lds_read_tr(p + 16 * AS);
+      vaop[ct][ks] = u32x4{lo[0], lo[1], hi[0], hi[1]};
     }
-  }
 }
 
 // Q registers of one step: qop[tt][kc] = Q[t0 + 16tt + r][32kc + 8g .. +7], rows clamped to N-1.
@@ -531,7 +532,7 @@ __device__ __forceinline__ void bcast_compute(const QRegs<D>& q, const uint16_t*
       sum += (s[at][0] + s[at][1]) + (s[at][2] + s[at][3]);
     }
     sum = xor16_32_sum(sum);
-    const float inv = 1.0f / sum;
+    const float inv = __builtin_amdgcn_rcpf(sum);    // 1 ulp; the IEEE division costs 11 instructions
     u32x4 pk[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -635,7 +636,7 @@ template <class E, int D, int NAT>
 __device__ __forceinline__ void agg_finish(AggState<D>& st, uint16_t* VA_lds, int at0, int lane) {
   constexpr int EV = D / 16, AS = Geo<D, NAT>::AS;
   const int r = lane & 15, g = lane >> 4;
-  const float inv = 1.0f / xor16_32_sum(st.l);
+  const float inv = __builtin_amdgcn_rcpf(xor16_32_sum(st.l));
   const int a = 16 * at0 + r;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -675,9 +676,10 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
     int heads, int gh, int gw, int ah, int aw) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   constexpr int AS = Geo<D, NAT>::AS, CH = D / 8;
+  constexpr int RV = Geo<D, NAT>::RV;
   uint16_t* A_lds = (uint16_t*)smem_raw;
   uint16_t* VA_lds = A_lds + 16 * NAT * AS;
-  uint16_t* Q_lds = VA_lds + 16 * NAT * AS;
+  uint16_t* Q_lds = VA_lds + RV * AS;
   float* slots = (float*)(Q_lds + (size_t)((N + 31) / 32 * 32) * AS);
 
   const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
@@ -692,6 +694,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
   KVRegs<D> k0, k1;
   if (32 * ts < N) agg_load<D>(Ku, Vu, 32 * ts, N, lane, k0);
   if (32 * (ts + TS) < N) agg_load<D>(Ku, Vu, 32 * (ts + TS), N, lane, k1);
+  for (int q = tid; q < (RV - 16 * NAT) * (AS / 8); q += blockDim.x)     // zero the pad rows of V_A (odd NAT)
+    *(u32x4*)(VA_lds + 16 * NAT * AS + 8 * q) = u32x4{0, 0, 0, 0};
 
   const int total = N * CH;
   for (int base = tid; base < total; base += 4 * blockDim.x) {
@@ -851,7 +855,7 @@ __global__ __launch_bounds__(64) void small_merge_kernel(const float* __restrict
     const size_t row = ((size_t)u * S + s) * n + a;
     l += part_l[row] * fast_exp2(part_m[row] - m);
   }
-  const float inv = 1.0f / l;
+  const float inv = __builtin_amdgcn_rcpf(l);
   for (int c = threadIdx.x; c < D; c += 64) {
     float v = 0.0f;
     for (int s = 0; s < S; ++s) {
@@ -876,7 +880,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_broadcast_kernel(
     const float* __restrict__ dwc_w, const float* __restrict__ dwc_b, float sc2, float vk, int N, int n, int heads,
     int gh, int gw, int chunk) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  constexpr int AS = Geo<D, NAT>::AS;
+  constexpr int AS = Geo<D, NAT>::AS, RV = Geo<D, NAT>::RV;
   uint16_t* A_lds = (uint16_t*)smem_raw;
   uint16_t* VA_lds = A_lds + 16 * NAT * AS;
   const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
@@ -890,7 +894,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_broadcast_kernel(
   QRegs<D> q0;
   if (tbeg + 32 * wave < tend) bcast_load<D>(Qu, D, tbeg + 32 * wave, N, lane, q0);
   load_agents_to_lds<D, NAT>(A + (size_t)u * n * D, A_lds, n, tid, blockDim.x);
-  for (int q = tid; q < 16 * NAT * (D / 4); q += blockDim.x) {
+  for (int q = tid; q < RV * (D / 4); q += blockDim.x) {
     const int a = q / (D / 4), c4 = q - a * (D / 4);
     f32x4 out = {0, 0, 0, 0};
     if (a < n) {
@@ -908,7 +912,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_broadcast_kernel(
           l += part_l[row] * w;
           out += *(const f32x4*)(part_acc + row * D + 4 * c4) * w;
         }
-        out *= 1.0f / l;
+        out *= __builtin_amdgcn_rcpf(l);
       }
     }
     u32x2 w2 = {Mx<E>::pack2(out[0], out[1]), Mx<E>::pack2(out[2], out[3])};
@@ -959,7 +963,7 @@ static int waves_for(int tokens) {
 
 template <int D, int NAT>
 static size_t fused_lds_bytes(int TS, int N) {
-  return (size_t)2 * 16 * NAT * Geo<D, NAT>::AS * 2 + (size_t)((N + 31) / 32 * 32) * Geo<D, NAT>::AS * 2 +
+  return (size_t)(16 * NAT + Geo<D, NAT>::RV) * Geo<D, NAT>::AS * 2 + (size_t)((N + 31) / 32 * 32) * Geo<D, NAT>::AS * 2 +
          (size_t)max(1, TS - 1) * NAT * Geo<D, NAT>::NREG * 64 * 4;
 }
 
@@ -1100,7 +1104,7 @@ hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A
   const float* plv = part ? part->l : nullptr;
   const int ps = part ? part->S : 0;
   AA_SMALL_DISPATCH(p, {
-    const size_t lds = (size_t)2 * 16 * NAT * Geo<D, NAT>::AS * 2;
+    const size_t lds = (size_t)(16 * NAT + Geo<D, NAT>::RV) * Geo<D, NAT>::AS * 2;
     if (mod)
       small_broadcast_kernel<E, D, NAT, true><<<dim3(nchunks, p.units), dim3(64 * W), lds, st>>>(
           (const uint16_t*)Q, (const uint16_t*)A, VA, pacc, pm, plv, ps, (const uint16_t*)V, (uint16_t*)out, p.b2,
