@@ -110,6 +110,15 @@ __device__ __forceinline__ float xor16_32_sum(float v) {
   return __uint_as_float(q[0]) + __uint_as_float(q[1]);
 }
 
+// LDS transpose read of 4 x 16 bit (ds_read_b64_tr_b16): within a group of 16 lanes, lane q supplies the
+// address of 4 consecutive elements; lane i receives element i%4 of the chunks addressed by lanes
+// i/4, 4 + i/4, 8 + i/4 and 12 + i/4.
+__device__ __forceinline__ u32x2 lds_read_tr(const uint16_t* p) {
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+  return __builtin_bit_cast(u32x2, v);
+}
+
 // Geometry shared by the kernels of one instantiation.
 template <int D, int NAT>
 struct Geo {
@@ -186,26 +195,37 @@ template <class E, int D, int NAT>
 __device__ __forceinline__ void pool_unit_to_lds(const uint16_t* Q_lds, int row_stride, uint16_t* A_lds, int n, int gh,
                                                  int gw, int ah, int aw, int tid, int nthreads) {
   constexpr int CH = D / 8, AS = Geo<D, NAT>::AS;
+  const bool uniform = (gh % ah == 0) && (gw % aw == 0);      // block-uniform; the usual case
+  const int wh_u = gh / ah, ww_u = gw / aw;
   for (int item = tid; item < 16 * NAT * CH; item += nthreads) {
     const int a = item / CH, chunk = item % CH;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     float inv = 0.0f;
     if (a < n) {
       const int ay = a / aw, ax = a - ay * aw;
-      const int y0 = pool_win_lo(ay, gh, ah), y1 = pool_win_hi(ay, gh, ah);
-      const int x0 = pool_win_lo(ax, gw, aw), x1 = pool_win_hi(ax, gw, aw);
-      inv = 1.0f / (float)((y1 - y0) * (x1 - x0));
-      for (int y = y0; y < y1; ++y)
-        for (int x = x0; x < x1; ++x) {
-          const u32x4 v = *(const u32x4*)(Q_lds + (y * gw + x) * row_stride + 8 * chunk);
+      int y0, x0, wh, ww;
+      if (uniform) {
+        y0 = ay * wh_u, x0 = ax * ww_u, wh = wh_u, ww = ww_u;
+      } else {
+        y0 = pool_win_lo(ay, gh, ah), x0 = pool_win_lo(ax, gw, aw);
+        wh = pool_win_hi(ay, gh, ah) - y0, ww = pool_win_hi(ax, gw, aw) - x0;
+      }
+      const int cnt = wh * ww;
+      inv = 1.0f / (float)cnt;
+      const float inv_ww = 1.0f / (float)ww;       // idx / ww by reciprocal: exact for idx < 2^20
+      const uint16_t* base = Q_lds + (y0 * gw + x0) * row_stride + 8 * chunk;
+#pragma unroll 4
+      for (int idx = 0; idx < cnt; ++idx) {
+        const int yy = (int)(((float)idx + 0.5f) * inv_ww);
+        const u32x4 v = *(const u32x4*)(base + (yy * gw + (idx - yy * ww)) * row_stride);
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            float lo, hi;
-            Mx<E>::unpack2(v[q], lo, hi);
-            acc[2 * q] += lo;
-            acc[2 * q + 1] += hi;
-          }
+        for (int q = 0; q < 4; ++q) {
+          float lo, hi;
+          Mx<E>::unpack2(v[q], lo, hi);
+          acc[2 * q] += lo;
+          acc[2 * q + 1] += hi;
         }
+      }
     }
     u32x4 w;
 #pragma unroll
@@ -390,6 +410,90 @@ __device__ __forceinline__ void agg_range(const uint16_t* __restrict__ Ku, const
   }
 }
 
+// The same step with the K and V rows of the unit resident in LDS ([token][AS] rows): K operands are
+// 16-byte LDS reads, V operands come from the LDS transpose read (operand row <-> channel 16e + lane%16,
+// so acc[e][i] <-> channel 16e + 4g + i here).
+template <class E, int D, int NAT, bool BIAS, bool TAIL>
+__device__ __forceinline__ void agg_compute_lds(const uint16_t* K_lds, const uint16_t* V_lds, int t0, int N, int n,
+                                                int at0, const u32x4 (&areg1)[D / 32], AggState<D>& st, float sc,
+                                                int lane, const BiasArgs& b1, int gh, int gw) {
+  constexpr int KC = D / 32, EV = D / 16, AS = Geo<D, NAT>::AS;
+  const int r = lane & 15, g = lane >> 4;
+  f32x4 s[2];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) {
+    f32x4 c = {0, 0, 0, 0};
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+      const u32x4 kop = *(const u32x4*)(K_lds + (t0 + 16 * rt + r) * AS + 32 * kc + 8 * g);
+      c = Mx<E>::mma(kop, areg1[kc], c);
+    }
+    s[rt] = c;
+  }
+  const float f = BIAS ? 1.0f : sc;
+  if constexpr (BIAS || TAIL) {
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int tok = t0 + 16 * rt + 4 * g + i;
+        float v = s[rt][i];
+        if constexpr (BIAS) {
+          const int tc = min(tok, N - 1);
+          v = v * sc + kLog2e * bias1_at(b1, min(16 * at0 + r, n - 1), tc / gw, tc % gw, gh, gw);
+        }
+        if constexpr (TAIL) v = tok < N ? v : -INFINITY;
+        s[rt][i] = v;
+      }
+  }
+  float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                   fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+  mx = xor16_32_max(mx);
+  const float mnew = fmaxf(st.m, mx * f);
+  if (__any(mnew > st.m)) {
+    const float alpha = fast_exp2(st.m - mnew);
+    st.m = mnew;
+    st.l *= alpha;
+#pragma unroll
+    for (int e = 0; e < EV; ++e) st.acc[e] *= alpha;
+  }
+  float p[2][4];
+  const float nm = -st.m;
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p[rt][i] = fast_exp2(__builtin_fmaf(s[rt][i], f, nm));
+  st.l += ((p[0][0] + p[0][1]) + (p[0][2] + p[0][3])) + ((p[1][0] + p[1][1]) + (p[1][2] + p[1][3]));
+  u32x4 pk;
+  pk[0] = Mx<E>::pack2(p[0][0], p[0][1]);
+  pk[1] = Mx<E>::pack2(p[0][2], p[0][3]);
+  pk[2] = Mx<E>::pack2(p[1][0], p[1][1]);
+  pk[3] = Mx<E>::pack2(p[1][2], p[1][3]);
+  const int q = lane & 15;
+#pragma unroll
+  for (int e = 0; e < EV; ++e) {
+    const uint16_t* vp = V_lds + (t0 + 4 * g + (q >> 2)) * AS + 16 * e + 4 * (q & 3);
+    const u32x2 lo = lds_read_tr(vp), hi = lds_read_tr(vp + 16 * AS);
+    st.acc[e] = Mx<E>::mma(u32x4{lo[0], lo[1], hi[0], hi[1]}, pk, st.acc[e]);
+  }
+}
+
+template <class E, int D, int NAT, bool BIAS>
+__device__ __forceinline__ void agg_range_lds(const uint16_t* K_lds, const uint16_t* V_lds, int first, int stride,
+                                              int N, int n, int at0, const u32x4 (&areg1)[D / 32], AggState<D>& st,
+                                              float sc, int lane, const BiasArgs& b1, int gh, int gw) {
+  for (int t0 = first; t0 < N; t0 += stride) {
+    if constexpr (BIAS) {
+      agg_compute_lds<E, D, NAT, true, true>(K_lds, V_lds, t0, N, n, at0, areg1, st, sc, lane, b1, gh, gw);
+    } else {
+      if (t0 + 32 > N)
+        agg_compute_lds<E, D, NAT, false, true>(K_lds, V_lds, t0, N, n, at0, areg1, st, sc, lane, b1, gh, gw);
+      else
+        agg_compute_lds<E, D, NAT, false, false>(K_lds, V_lds, t0, N, n, at0, areg1, st, sc, lane, b1, gh, gw);
+    }
+  }
+}
+
 template <int D>
 __device__ __forceinline__ void agg_init(AggState<D>& st) {
   st.m = kNegBig;
@@ -434,15 +538,6 @@ __device__ __forceinline__ void agg_slice_merge(AggState<D>& st, float* slots, i
 // ---------------------------------------------------------------------------
 // broadcast: one step = 32 tokens, two independent 16-token tiles
 // ---------------------------------------------------------------------------
-// LDS transpose read of 4 x 16 bit (ds_read_b64_tr_b16): within a group of 16 lanes, lane q supplies the
-// address of 4 consecutive elements; lane i receives element i%4 of the chunks addressed by lanes
-// i/4, 4 + i/4, 8 + i/4 and 12 + i/4.
-__device__ __forceinline__ u32x2 lds_read_tr(const uint16_t* p) {
-  typedef short s16x4 __attribute__((ext_vector_type(4)));
-  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
-  return __builtin_bit_cast(u32x2, v);
-}
-
 // stationary V_A operand: vaop[ct][ks]: row r <-> channel (D/4)*(r/4) + 4ct + r%4,
 // k-slot 8g+j <-> agent 16*(2ks) + 4g+j (j<4) / 16*(2ks+1) + 4g+j-4.  Lane q of a 16-lane group points
 // at agent row 4g + q/4 (and 16 rows further for the second half), channel group q%4.
@@ -647,6 +742,21 @@ __device__ __forceinline__ void agg_finish(AggState<D>& st, uint16_t* VA_lds, in
     }
 }
 
+// same for the LDS-resident aggregation, whose accumulators hold channel 16e + 4g + i
+template <class E, int D, int NAT>
+__device__ __forceinline__ void agg_finish_natural(AggState<D>& st, uint16_t* VA_lds, int at0, int lane) {
+  constexpr int EV = D / 16, AS = Geo<D, NAT>::AS;
+  const int r = lane & 15, g = lane >> 4;
+  const float inv = __builtin_amdgcn_rcpf(xor16_32_sum(st.l));
+  const int a = 16 * at0 + r;
+#pragma unroll
+  for (int e = 0; e < EV; ++e) {
+    const u32x2 w = {Mx<E>::pack2(st.acc[e][0] * inv, st.acc[e][1] * inv),
+                     Mx<E>::pack2(st.acc[e][2] * inv, st.acc[e][3] * inv)};
+    *(u32x2*)(VA_lds + a * AS + 16 * e + 4 * g) = w;
+  }
+}
+
 __device__ __forceinline__ BiasArgs head_bias1(BiasArgs b, int hd, int n, int gh, int gw) {
   if (b.col) b.col += (size_t)hd * n * gw;
   if (b.row) b.row += (size_t)hd * n * gh;
@@ -661,12 +771,12 @@ __device__ __forceinline__ BiasArgs head_bias2(BiasArgs b, int hd, int n, int gh
 }
 
 // ---------------------------------------------------------------------------
-// Kernel 1: the whole forward pass of one unit in one block, for units whose Q rows fit in LDS.
-// Every global load of the block is issued up front (K/V of each wave's first two steps into
-// registers, Q into LDS), so the cold-HBM latency is paid once; pooling and the broadcast then read
-// Q from LDS.  grid = units, block = NAT * TS waves (wave = agent tile x token slice in the
+// Kernel 1: the whole forward pass of one unit in one block, for units whose Q, K and V rows fit in
+// LDS together.  Every global load of the block is issued at its very start (up to 12 16-byte loads in
+// flight per thread), so the cold-HBM latency is paid exactly once; pooling, aggregation and broadcast
+// then run out of LDS.  grid = units, block = NAT * TS waves (wave = agent tile x token slice in the
 // aggregation, token slice in the broadcast).
-// LDS: A rows | V_A rows | Q rows (N x AS) | (TS-1) * NAT merge slots.
+// LDS: A rows | V_A rows | Q rows | K rows | V rows (each roundup32(N) x AS) | (TS-1) * NAT merge slots.
 // ---------------------------------------------------------------------------
 template <class E, int D, int NAT, bool MODULE>
 __global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
@@ -677,10 +787,13 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   constexpr int AS = Geo<D, NAT>::AS, CH = D / 8;
   constexpr int RV = Geo<D, NAT>::RV;
+  const int rows = (N + 31) / 32 * 32;
   uint16_t* A_lds = (uint16_t*)smem_raw;
   uint16_t* VA_lds = A_lds + 16 * NAT * AS;
   uint16_t* Q_lds = VA_lds + RV * AS;
-  float* slots = (float*)(Q_lds + (size_t)((N + 31) / 32 * 32) * AS);
+  uint16_t* K_lds = Q_lds + (size_t)rows * AS;
+  uint16_t* V_lds = K_lds + (size_t)rows * AS;
+  float* slots = (float*)(V_lds + (size_t)rows * AS);
 
   const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
   const int TS = W / NAT, at0 = wave % NAT, ts = wave / NAT;
@@ -691,26 +804,36 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
   uint16_t* Ou = O + (size_t)u * N * D;
 
   AA_TL(0);
-  KVRegs<D> k0, k1;
-  if (32 * ts < N) agg_load<D>(Ku, Vu, 32 * ts, N, lane, k0);
-  if (32 * (ts + TS) < N) agg_load<D>(Ku, Vu, 32 * (ts + TS), N, lane, k1);
-  for (int q = tid; q < (RV - 16 * NAT) * (AS / 8); q += blockDim.x)     // zero the pad rows of V_A (odd NAT)
-    *(u32x4*)(VA_lds + 16 * NAT * AS + 8 * q) = u32x4{0, 0, 0, 0};
-
-  const int total = N * CH;
-  for (int base = tid; base < total; base += 4 * blockDim.x) {
-    u32x4 v[4];
+  // Q, K, V rows -> LDS: one index space over the 3*N*CH 16-byte chunks
+  const int per = N * CH, total = 3 * per;
+  constexpr int kInFlight = 12;
+  for (int base = tid; base < total; base += kInFlight * blockDim.x) {
+    u32x4 v[kInFlight];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int q = base + k * blockDim.x;
-      if (q < total) v[k] = *(const u32x4*)(Qu + (size_t)q * 8);
+    for (int k = 0; k < kInFlight; ++k) {
+      const int c = base + k * blockDim.x;
+      if (c < total) {
+        const int which = c >= 2 * per ? 2 : (c >= per ? 1 : 0);
+        const uint16_t* src = which == 0 ? Qu : (which == 1 ? Ku : Vu);
+        v[k] = *(const u32x4*)(src + (size_t)(c - which * per) * 8);
+      }
     }
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int q = base + k * blockDim.x;
-      if (q < total) *(u32x4*)(Q_lds + (q / CH) * AS + 8 * (q % CH)) = v[k];
+    for (int k = 0; k < kInFlight; ++k) {
+      const int c = base + k * blockDim.x;
+      if (c < total) {
+        const int which = c >= 2 * per ? 2 : (c >= per ? 1 : 0);
+        const int cc = c - which * per;
+        *(u32x4*)(Q_lds + (size_t)which * rows * AS + (cc / CH) * AS + 8 * (cc % CH)) = v[k];
+      }
     }
   }
+  // zero what the products may touch beyond the data: V rows [N, rows) (their weights are zero, but
+  // 0 * garbage must stay 0) and the pad rows of V_A (odd NAT)
+  for (int q = tid; q < (rows - N) * (AS / 8); q += blockDim.x)
+    *(u32x4*)(V_lds + (size_t)N * AS + 8 * q) = u32x4{0, 0, 0, 0};
+  for (int q = tid; q < (RV - 16 * NAT) * (AS / 8); q += blockDim.x)
+    *(u32x4*)(VA_lds + 16 * NAT * AS + 8 * q) = u32x4{0, 0, 0, 0};
   if (Agiven) load_agents_to_lds<D, NAT>(Agiven + (size_t)u * n * D, A_lds, n, tid, blockDim.x);
   __syncthreads();
   AA_TL(1);
@@ -729,15 +852,16 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
     bool agg_done = false;
     if constexpr (MODULE) {
       if (hb1.any()) {
-        agg_range<E, D, true>(Ku, Vu, k0, k1, 32 * ts, 32 * TS, N, n, at0, areg1, st, sc1, lane, hb1, gh, gw);
+        agg_range_lds<E, D, NAT, true>(K_lds, V_lds, 32 * ts, 32 * TS, N, n, at0, areg1, st, sc1, lane, hb1, gh, gw);
         agg_done = true;
       }
     }
-    if (!agg_done) agg_range<E, D, false>(Ku, Vu, k0, k1, 32 * ts, 32 * TS, N, n, at0, areg1, st, sc1, lane, hb1, gh, gw);
+    if (!agg_done)
+      agg_range_lds<E, D, NAT, false>(K_lds, V_lds, 32 * ts, 32 * TS, N, n, at0, areg1, st, sc1, lane, hb1, gh, gw);
     AA_TL(3);
     agg_slice_merge<D, NAT>(st, slots, at0, ts, TS, lane);
     AA_TL(4);
-    if (ts == 0) agg_finish<E, D, NAT>(st, VA_lds, at0, lane);
+    if (ts == 0) agg_finish_natural<E, D, NAT>(st, VA_lds, at0, lane);
   }
   __syncthreads();
   AA_TL(5);
@@ -963,13 +1087,15 @@ static int waves_for(int tokens) {
 
 template <int D, int NAT>
 static size_t fused_lds_bytes(int TS, int N) {
-  return (size_t)(16 * NAT + Geo<D, NAT>::RV) * Geo<D, NAT>::AS * 2 + (size_t)((N + 31) / 32 * 32) * Geo<D, NAT>::AS * 2 +
+  return (size_t)(16 * NAT + Geo<D, NAT>::RV) * Geo<D, NAT>::AS * 2 +
+         (size_t)3 * ((N + 31) / 32 * 32) * Geo<D, NAT>::AS * 2 +
          (size_t)max(1, TS - 1) * NAT * Geo<D, NAT>::NREG * 64 * 4;
 }
 
-// The one-block-per-unit kernel keeps the unit's Q rows in LDS: at most 64 KB of them.
+// The one-block-per-unit kernel keeps the unit's Q, K and V rows in LDS (160 KB per CU, some of it for
+// A, V_A and the merge slots): at most 120 KB of rows.
 bool small_fused_supported(const Problem& p) {
-  return small_supported(p) && (size_t)((p.N + 31) / 32 * 32) * (p.d + 8) * 2 <= 64 * 1024;
+  return small_supported(p) && (size_t)3 * ((p.N + 31) / 32 * 32) * (p.d + 8) * 2 <= 120 * 1024;
 }
 
 #define AA_SMALL_DISPATCH(p, ...)                                                  \
