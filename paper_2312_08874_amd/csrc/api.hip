@@ -99,14 +99,21 @@ int choose_splits(const aa_desc* d) {
   return S;
 }
 
+// Tuning override for experiments: integer environment variable, 0 / unset = use the built-in choice.
+int tuning_env(const char* name) {
+  const char* v = getenv(name);
+  return v ? atoi(v) : 0;
+}
+
 // Splits / chunks of the small-agent path.  An explicit n_splits forces the multi-kernel path
 // with that many splits (rounded so that every split is a non-empty multiple of 32 tokens).
 void plan_small(const aa_desc* d, Plan& pl) {
   const int64_t units = (int64_t)d->batch * d->heads;
   int S = d->n_splits;
   pl.prefer_fused = (S <= 0);   // taken when the unit's Q rows fit in LDS, see run time check
+  if (S <= 0 && tuning_env("AA_SMALL_S") > 0) S = tuning_env("AA_SMALL_S");
   if (S <= 0) {
-    S = (int)((640 + units - 1) / units);      // about one resident round of blocks on 256 CUs
+    S = (int)((448 + units - 1) / units);      // a few hundred blocks: one resident round on 256 CUs (swept)
     const int max_by_len = (d->N + 127) / 128;
     if (S > max_by_len) S = max_by_len;
   }
@@ -114,17 +121,12 @@ void plan_small(const aa_desc* d, Plan& pl) {
   if (S < 1) S = 1;
   const int chunk = aa::small_split_chunk(d->N, S);
   pl.S_small = (d->N + chunk - 1) / chunk;
-  pl.bcast_chunks = (d->N + 511) / 512;
+  const int btok = tuning_env("AA_SMALL_BTOK") >= 32 ? tuning_env("AA_SMALL_BTOK") : 512;   // tokens per broadcast block
+  pl.bcast_chunks = (d->N + btok - 1) / btok;
 }
 
 // Large-agent path: agents per block = waves * nw * 16; splits chosen for about 512 blocks, at least
 // 128 tokens per split, split length a multiple of the 64-token K/V tile.
-// Tuning override for experiments: integer environment variable, 0 / unset = use the built-in choice.
-int tuning_env(const char* name) {
-  const char* v = getenv(name);
-  return v ? atoi(v) : 0;
-}
-
 void plan_large(const aa_desc* d, Plan& pl) {
   const int64_t units = (int64_t)d->batch * d->heads;
   pl.nw_large = 1;     // one 16-agent tile per wave: 117 VGPRs, two blocks of 8 waves per CU (measured best)

@@ -310,101 +310,113 @@ __device__ __forceinline__ void agg_load(const uint16_t* __restrict__ Ku, const 
 // TAIL: the step may reach beyond N (mask those tokens).  Scores stay unscaled ("raw") until the exponent:
 // p = exp2(raw * f - m) with f = scale * log2(e) folded into one fma; with a bias the transform
 // raw <- raw * f + bias * log2(e) is applied first and f becomes 1.
-template <class E, int D, bool BIAS, bool TAIL>
+template <class E, int D, int NW, bool BIAS, bool TAIL>
 __device__ __forceinline__ void agg_compute(const KVRegs<D>& kv, int t0, int N, int n, int at0,
-                                            const u32x4 (&areg1)[D / 32], AggState<D>& st, float sc, int lane,
-                                            const BiasArgs& b1, int gh, int gw) {
+                                            const u32x4 (&areg)[NW][D / 32], AggState<D> (&st)[NW], float sc,
+                                            int lane, const BiasArgs& b1, int gh, int gw) {
   constexpr int KC = D / 32, EV = D / 16;
   const int r = lane & 15, g = lane >> 4;
-
-  // scores S^T = K A^T : tile rt, element i <-> token t0+16rt+4g+i, agent 16*at0+r
-  f32x4 s[2];
-#pragma unroll
-  for (int rt = 0; rt < 2; ++rt) {
-    f32x4 c = {0, 0, 0, 0};
-#pragma unroll
-    for (int kc = 0; kc < KC; ++kc) c = Mx<E>::mma(kv.kop[rt][kc], areg1[kc], c);
-    s[rt] = c;
-  }
   const float f = BIAS ? 1.0f : sc;
-  if constexpr (BIAS || TAIL) {
+
+  // scores S^T = K A^T : tile (w, rt), element i <-> token t0+16rt+4g+i, agent 16*(at0+w)+r
+  f32x4 s[NW][2];
+  float mnew[NW];
+  bool grew = false;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+      f32x4 c = {0, 0, 0, 0};
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) c = Mx<E>::mma(kv.kop[rt][kc], areg[w][kc], c);
+      s[w][rt] = c;
+    }
+    if constexpr (BIAS || TAIL) {
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int tok = t0 + 16 * rt + 4 * g + i;
+          float v = s[w][rt][i];
+          if constexpr (BIAS) {
+            const int tc = min(tok, N - 1);
+            v = v * sc + kLog2e * bias1_at(b1, min(16 * (at0 + w) + r, n - 1), tc / gw, tc % gw, gh, gw);
+          }
+          if constexpr (TAIL) v = tok < N ? v : -INFINITY;
+          s[w][rt][i] = v;
+        }
+    }
+    float mx = fmaxf(fmaxf(fmaxf(s[w][0][0], s[w][0][1]), fmaxf(s[w][0][2], s[w][0][3])),
+                     fmaxf(fmaxf(s[w][1][0], s[w][1][1]), fmaxf(s[w][1][2], s[w][1][3])));
+    mx = xor16_32_max(mx);
+    mnew[w] = fmaxf(st[w].m, mx * f);
+    grew |= mnew[w] > st[w].m;
+  }
+  if (__any(grew)) {      // one wave-uniform branch for all tiles
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float alpha = fast_exp2(st[w].m - mnew[w]);
+      st[w].m = mnew[w];
+      st[w].l *= alpha;
+#pragma unroll
+      for (int e = 0; e < EV; ++e) st[w].acc[e] *= alpha;
+    }
+  }
+  // probabilities, packed as the B operand of the value product
+  u32x4 pk[NW];
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    float p[2][4];
+    const float nm = -st[w].m;
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int tok = t0 + 16 * rt + 4 * g + i;
-        float v = s[rt][i];
-        if constexpr (BIAS) {
-          const int tc = min(tok, N - 1);
-          v = v * sc + kLog2e * bias1_at(b1, min(16 * at0 + r, n - 1), tc / gw, tc % gw, gh, gw);
-        }
-        if constexpr (TAIL) v = tok < N ? v : -INFINITY;
-        s[rt][i] = v;
-      }
+      for (int i = 0; i < 4; ++i) p[rt][i] = fast_exp2(__builtin_fmaf(s[w][rt][i], f, nm));
+    st[w].l += ((p[0][0] + p[0][1]) + (p[0][2] + p[0][3])) + ((p[1][0] + p[1][1]) + (p[1][2] + p[1][3]));
+    pk[w][0] = Mx<E>::pack2(p[0][0], p[0][1]);
+    pk[w][1] = Mx<E>::pack2(p[0][2], p[0][3]);
+    pk[w][2] = Mx<E>::pack2(p[1][0], p[1][1]);
+    pk[w][3] = Mx<E>::pack2(p[1][2], p[1][3]);
   }
-  float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
-                   fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
-  mx = xor16_32_max(mx);
-  const float mnew = fmaxf(st.m, mx * f);
-  if (__any(mnew > st.m)) {
-    const float alpha = fast_exp2(st.m - mnew);
-    st.m = mnew;
-    st.l *= alpha;
-#pragma unroll
-    for (int e = 0; e < EV; ++e) st.acc[e] *= alpha;
-  }
-  // probabilities, packed as the B operand of the value product
-  float p[2][4];
-  const float nm = -st.m;
-#pragma unroll
-  for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) p[rt][i] = fast_exp2(__builtin_fmaf(s[rt][i], f, nm));
-  st.l += ((p[0][0] + p[0][1]) + (p[0][2] + p[0][3])) + ((p[1][0] + p[1][1]) + (p[1][2] + p[1][3]));
-  u32x4 pk;
-  pk[0] = Mx<E>::pack2(p[0][0], p[0][1]);
-  pk[1] = Mx<E>::pack2(p[0][2], p[0][3]);
-  pk[2] = Mx<E>::pack2(p[1][0], p[1][1]);
-  pk[3] = Mx<E>::pack2(p[1][2], p[1][3]);
-
-  // V_A^T += V^T P^T : operand e holds channel EV*r + e of the 8 k-slot rows
+  // V_A^T += V^T P^T : operand e holds channel EV*r + e of the 8 k-slot rows; shared by the NW tiles
 #pragma unroll
   for (int e = 0; e < EV; ++e) {
     u32x4 vop;
     const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) vop[jj] = __builtin_amdgcn_perm(kv.vraw[2 * jj + 1][e / 2], kv.vraw[2 * jj][e / 2], sel);
-    st.acc[e] = Mx<E>::mma(vop, pk, st.acc[e]);
+#pragma unroll
+    for (int w = 0; w < NW; ++w) st[w].acc[e] = Mx<E>::mma(vop, pk[w], st[w].acc[e]);
   }
 }
 
-template <class E, int D, bool BIAS>
+template <class E, int D, int NW, bool BIAS>
 __device__ __forceinline__ void agg_compute_any(const KVRegs<D>& kv, int t0, int N, int n, int at0,
-                                                const u32x4 (&areg1)[D / 32], AggState<D>& st, float sc, int lane,
-                                                const BiasArgs& b1, int gh, int gw) {
+                                                const u32x4 (&areg)[NW][D / 32], AggState<D> (&st)[NW], float sc,
+                                                int lane, const BiasArgs& b1, int gh, int gw) {
   if constexpr (BIAS) {
-    agg_compute<E, D, true, true>(kv, t0, N, n, at0, areg1, st, sc, lane, b1, gh, gw);
+    agg_compute<E, D, NW, true, true>(kv, t0, N, n, at0, areg, st, sc, lane, b1, gh, gw);
   } else {
     if (t0 + 32 > N)
-      agg_compute<E, D, false, true>(kv, t0, N, n, at0, areg1, st, sc, lane, b1, gh, gw);
+      agg_compute<E, D, NW, false, true>(kv, t0, N, n, at0, areg, st, sc, lane, b1, gh, gw);
     else
-      agg_compute<E, D, false, false>(kv, t0, N, n, at0, areg1, st, sc, lane, b1, gh, gw);
+      agg_compute<E, D, NW, false, false>(kv, t0, N, n, at0, areg, st, sc, lane, b1, gh, gw);
   }
 }
 
 // Walk the steps t0 = first, first + stride, ... < end.  The loads of the next two steps are in
 // flight while a step is computed; `k0` / `k1` already hold the loads of steps `first` and
 // `first + stride` (when those exist).
-template <class E, int D, bool BIAS>
+template <class E, int D, int NW, bool BIAS>
 __device__ __forceinline__ void agg_range(const uint16_t* __restrict__ Ku, const uint16_t* __restrict__ Vu,
                                           KVRegs<D>& k0, KVRegs<D>& k1, int first, int stride, int end, int n,
-                                          int at0, const u32x4 (&areg1)[D / 32], AggState<D>& st, float sc, int lane,
-                                          const BiasArgs& b1, int gh, int gw) {
+                                          int at0, const u32x4 (&areg)[NW][D / 32], AggState<D> (&st)[NW], float sc,
+                                          int lane, const BiasArgs& b1, int gh, int gw) {
   for (int t0 = first; t0 < end; t0 += 2 * stride) {
-    agg_compute_any<E, D, BIAS>(k0, t0, end, n, at0, areg1, st, sc, lane, b1, gh, gw);
+    agg_compute_any<E, D, NW, BIAS>(k0, t0, end, n, at0, areg, st, sc, lane, b1, gh, gw);
     if (t0 + 2 * stride < end) agg_load<D>(Ku, Vu, t0 + 2 * stride, end, lane, k0);
     if (t0 + stride < end) {
-      agg_compute_any<E, D, BIAS>(k1, t0 + stride, end, n, at0, areg1, st, sc, lane, b1, gh, gw);
+      agg_compute_any<E, D, NW, BIAS>(k1, t0 + stride, end, n, at0, areg, st, sc, lane, b1, gh, gw);
       if (t0 + 3 * stride < end) agg_load<D>(Ku, Vu, t0 + 3 * stride, end, lane, k1);
     }
   }
@@ -503,34 +515,43 @@ __device__ __forceinline__ void agg_init(AggState<D>& st) {
 }
 
 // Merge of the token slices of a block: the waves of slices 1.. store their state, the waves of
-// slice 0 fold them in (fixed order).  slots: (TS-1) * NAT * NREG * 64 floats.  Every wave calls
-// this (one block-wide barrier inside when TS > 1).
-template <int D, int NAT>
-__device__ __forceinline__ void agg_slice_merge(AggState<D>& st, float* slots, int at0, int ts, int TS, int lane) {
-  constexpr int NREG = Geo<D, NAT>::NREG, EV = D / 16;
+// slice 0 fold them in (fixed order).  A wave holds NW tiles and belongs to group `grp` of G groups.
+// slots: (TS-1) * G * NW * NREG * 64 floats.  Every wave calls this (one block-wide barrier when TS > 1).
+template <int D, int NW>
+__device__ __forceinline__ void agg_slice_merge(AggState<D> (&st)[NW], float* slots, int grp, int G, int ts, int TS,
+                                                int lane) {
+  constexpr int EV = D / 16, NREG = EV * 4 + 2;
   if (TS == 1) return;
   if (ts > 0) {
-    float* slot = slots + ((size_t)(ts - 1) * NAT + at0) * NREG * 64;
-    slot[lane] = st.m;
-    slot[64 + lane] = st.l;
+    float* slot = slots + ((size_t)(ts - 1) * G + grp) * NW * NREG * 64;
 #pragma unroll
-    for (int e = 0; e < EV; ++e)
+    for (int w = 0; w < NW; ++w) {
+      float* sw = slot + w * NREG * 64;
+      sw[lane] = st[w].m;
+      sw[64 + lane] = st[w].l;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) slot[(2 + 4 * e + i) * 64 + lane] = st.acc[e][i];
+      for (int e = 0; e < EV; ++e)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sw[(2 + 4 * e + i) * 64 + lane] = st[w].acc[e][i];
+    }
   }
   __syncthreads();
   if (ts == 0) {
     for (int o = 1; o < TS; ++o) {
-      const float* slot = slots + ((size_t)(o - 1) * NAT + at0) * NREG * 64;
-      const float mo = slot[lane], lo = slot[64 + lane];
-      const float mn = fmaxf(st.m, mo);
-      const float a = fast_exp2(st.m - mn), b = fast_exp2(mo - mn);
-      st.m = mn;
-      st.l = st.l * a + lo * b;
+      const float* slot = slots + ((size_t)(o - 1) * G + grp) * NW * NREG * 64;
 #pragma unroll
-      for (int e = 0; e < EV; ++e)
+      for (int w = 0; w < NW; ++w) {
+        const float* sw = slot + w * NREG * 64;
+        const float mo = sw[lane], lo = sw[64 + lane];
+        const float mn = fmaxf(st[w].m, mo);
+        const float a = fast_exp2(st[w].m - mn), b = fast_exp2(mo - mn);
+        st[w].m = mn;
+        st[w].l = st[w].l * a + lo * b;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) st.acc[e][i] = st.acc[e][i] * a + slot[(2 + 4 * e + i) * 64 + lane] * b;
+        for (int e = 0; e < EV; ++e)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) st[w].acc[e][i] = st[w].acc[e][i] * a + sw[(2 + 4 * e + i) * 64 + lane] * b;
+      }
     }
   }
 }
@@ -846,22 +867,22 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
   {
     u32x4 areg1[D / 32];
     load_a_tile<D, NAT>(A_lds, at0, areg1, lane);
-    AggState<D> st;
-    agg_init<D>(st);
+    AggState<D> st[1];
+    agg_init<D>(st[0]);
     const BiasArgs hb1 = head_bias1(b1, hd, n, gh, gw);
     bool agg_done = false;
     if constexpr (MODULE) {
       if (hb1.any()) {
-        agg_range_lds<E, D, NAT, true>(K_lds, V_lds, 32 * ts, 32 * TS, N, n, at0, areg1, st, sc1, lane, hb1, gh, gw);
+        agg_range_lds<E, D, NAT, true>(K_lds, V_lds, 32 * ts, 32 * TS, N, n, at0, areg1, st[0], sc1, lane, hb1, gh, gw);
         agg_done = true;
       }
     }
     if (!agg_done)
-      agg_range_lds<E, D, NAT, false>(K_lds, V_lds, 32 * ts, 32 * TS, N, n, at0, areg1, st, sc1, lane, hb1, gh, gw);
+      agg_range_lds<E, D, NAT, false>(K_lds, V_lds, 32 * ts, 32 * TS, N, n, at0, areg1, st[0], sc1, lane, hb1, gh, gw);
     AA_TL(3);
-    agg_slice_merge<D, NAT>(st, slots, at0, ts, TS, lane);
+    agg_slice_merge<D, 1>(st, slots, at0, NAT, ts, TS, lane);
     AA_TL(4);
-    if (ts == 0) agg_finish_natural<E, D, NAT>(st, VA_lds, at0, lane);
+    if (ts == 0) agg_finish_natural<E, D, NAT>(st[0], VA_lds, at0, lane);
   }
   __syncthreads();
   AA_TL(5);
@@ -898,22 +919,25 @@ __global__ __launch_bounds__(256) void small_pool_kernel(const uint16_t* __restr
 }
 
 // ---------------------------------------------------------------------------
-// Kernel 3: split-N aggregation.  grid = (S, units), block = NAT * TS waves; block (s, u) walks the
-// tokens [s*chunk, min(N, (s+1)*chunk)), chunk a multiple of 32; wave = (agent tile, token slice).
-// Writes the un-normalised partial: acc [u][s][n][D], m and l [u][s][n] (m in the log2 domain).
+// Kernel 3: split-N aggregation.  grid = (S, units); block (s, u) walks the tokens
+// [s*chunk, min(N, (s+1)*chunk)), chunk a multiple of 32.  A wave holds NW of the NAT agent tiles (the
+// K / V loads and the V operand preparation are shared by its tiles) and one token slice; block =
+// (NAT / NW) * TS waves.  Writes the un-normalised partial: acc [u][s][n][D], m and l [u][s][n] (m in the
+// log2 domain).
 // ---------------------------------------------------------------------------
-template <class E, int D, int NAT, bool MODULE>
+template <class E, int D, int NAT, int NW, bool MODULE>
 __global__ __launch_bounds__(64 * kMaxWaves) void small_aggregate_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V, BiasArgs b1,
     float sc1, int N, int n, int heads, int gh, int gw, int chunk, float* __restrict__ part_acc,
     float* __restrict__ part_m, float* __restrict__ part_l) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  constexpr int AS = Geo<D, NAT>::AS, EV = D / 16;
+  constexpr int AS = Geo<D, NAT>::AS, EV = D / 16, G = NAT / NW;
+  static_assert(NAT % NW == 0, "tiles per wave must divide the tile count");
   uint16_t* A_lds = (uint16_t*)smem_raw;
   float* slots = (float*)(A_lds + 16 * NAT * AS);
   const int s = blockIdx.x, S = gridDim.x, u = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
-  const int TS = W / NAT, at0 = wave % NAT, ts = wave / NAT;
+  const int TS = W / G, grp = wave % G, ts = wave / G, at0 = grp * NW;
   const uint16_t* Ku = K + (size_t)u * N * D;
   const uint16_t* Vu = V + (size_t)u * N * D;
 
@@ -926,38 +950,44 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_aggregate_kernel(
   load_agents_to_lds<D, NAT>(A + (size_t)u * n * D, A_lds, n, tid, blockDim.x);
   __syncthreads();
   AA_TL(1);
-  u32x4 areg1[D / 32];
-  load_a_tile<D, NAT>(A_lds, at0, areg1, lane);
+  u32x4 areg[NW][D / 32];
+#pragma unroll
+  for (int w = 0; w < NW; ++w) load_a_tile<D, NAT>(A_lds, at0 + w, areg[w], lane);
 
-  AggState<D> st;
-  agg_init<D>(st);
+  AggState<D> st[NW];
+#pragma unroll
+  for (int w = 0; w < NW; ++w) agg_init<D>(st[w]);
   const BiasArgs hb1 = head_bias1(b1, u % heads, n, gh, gw);
   bool agg_done = false;
   if constexpr (MODULE) {
     if (hb1.any()) {
-      agg_range<E, D, true>(Ku, Vu, k0, k1, first, stride, tend, n, at0, areg1, st, sc1, lane, hb1, gh, gw);
+      agg_range<E, D, NW, true>(Ku, Vu, k0, k1, first, stride, tend, n, at0, areg, st, sc1, lane, hb1, gh, gw);
       agg_done = true;
     }
   }
-  if (!agg_done) agg_range<E, D, false>(Ku, Vu, k0, k1, first, stride, tend, n, at0, areg1, st, sc1, lane, hb1, gh, gw);
+  if (!agg_done)
+    agg_range<E, D, NW, false>(Ku, Vu, k0, k1, first, stride, tend, n, at0, areg, st, sc1, lane, hb1, gh, gw);
   AA_TL(2);
-  agg_slice_merge<D, NAT>(st, slots, at0, ts, TS, lane);
+  agg_slice_merge<D, NW>(st, slots, grp, G, ts, TS, lane);
   AA_TL(3);
   if (ts == 0) {
     const int r = lane & 15, g = lane >> 4;
     const size_t base = (size_t)u * S + s;
-    const int a = 16 * at0 + r;
-    const float l = xor16_32_sum(st.l);
-    if (a < n) {
-      if (g == 0) {
-        part_m[base * n + a] = st.m;
-        part_l[base * n + a] = l;
-      }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float* dst = part_acc + (base * n + a) * D + EV * (4 * g + i);
+    for (int w = 0; w < NW; ++w) {
+      const int a = 16 * (at0 + w) + r;
+      const float l = xor16_32_sum(st[w].l);
+      if (a < n) {
+        if (g == 0) {
+          part_m[base * n + a] = st[w].m;
+          part_l[base * n + a] = l;
+        }
 #pragma unroll
-        for (int e = 0; e < EV; ++e) dst[e] = st.acc[e][i];
+        for (int i = 0; i < 4; ++i) {
+          float* dst = part_acc + (base * n + a) * D + EV * (4 * g + i);
+#pragma unroll
+          for (int e = 0; e < EV; ++e) dst[e] = st[w].acc[e][i];
+        }
       }
     }
   }
@@ -1195,7 +1225,9 @@ hipError_t launch_small_aggregate(const Problem& p, const void* A, const void* K
   const bool mod = p.b1.any();
   hipError_t err = hipSuccess;
   AA_SMALL_DISPATCH(p, {
-    const int TS = slices_for(chunk, NAT), W = NAT * TS;
+    constexpr int NW = (NAT % 2 == 0) ? 2 : 1;      // agent tiles per wave
+    constexpr int G = NAT / NW;
+    const int TS = slices_for(chunk, G), W = G * TS;
     const size_t lds = (size_t)16 * NAT * Geo<D, NAT>::AS * 2 + (size_t)max(1, TS - 1) * NAT * Geo<D, NAT>::NREG * 64 * 4;
     auto launch = [&](auto kernel) {
       err = allow_lds(kernel, lds);
@@ -1205,9 +1237,9 @@ hipError_t launch_small_aggregate(const Problem& p, const void* A, const void* K
                                                                   p.gh, p.gw, chunk, part.acc, part.m, part.l);
     };
     if (mod)
-      launch(small_aggregate_kernel<E, D, NAT, true>);
+      launch(small_aggregate_kernel<E, D, NAT, NW, true>);
     else
-      launch(small_aggregate_kernel<E, D, NAT, false>);
+      launch(small_aggregate_kernel<E, D, NAT, NW, false>);
   });
   return err != hipSuccess ? err : hipGetLastError();
 }
