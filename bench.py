@@ -203,12 +203,16 @@ def cpu_baseline(wl, ring):
         kw = {kk: vv[:1] for kk, vv in kw.items()}
     oracle.agent_attn_fwd(q[:1], k[:1], v[:1], heads=1, grid=wl.grid, agent_grid=wl.agent_grid,
                           **({kk: vv[:1] for kk, vv in kw.items()}))      # warm the library
+    reps, dt = 0, 0.0
     t0 = time.perf_counter()
-    oracle.agent_attn_fwd(q, k, v, heads=heads, grid=wl.grid, agent_grid=wl.agent_grid, **kw)
-    dt = time.perf_counter() - t0
-    tokens = units * wl.N / wl.heads
+    while dt < 1.5 and reps < 200:          # about 1.5 s of wall time on all host cores
+        oracle.agent_attn_fwd(q, k, v, heads=heads, grid=wl.grid, agent_grid=wl.agent_grid, **kw)
+        reps += 1
+        dt = time.perf_counter() - t0
+    tokens = reps * units * wl.N / wl.heads
     return {"value": tokens / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "%d of %d (batch*head) units of workload %s, fp64, %.2f s wall" % (units, wl.units, wl.name, dt)}
+            "sample": "%d of %d (batch*head) units of workload %s, fp64, %d repetition(s), %.2f s wall"
+                      % (units, wl.units, wl.name, reps, dt)}
 
 
 def main():
