@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="total footprint of the rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short summary of the other workloads")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the steps from a captured HIP graph (one graph = one pass over the ring)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for the HBM byte counters when profiling)")
     return ap.parse_args()
@@ -158,10 +160,41 @@ def roofline_for(wl, stage_ms, fused_ms=None):
             "frac": ach / HBM_PEAK_GBS, "traffic": traffic, "avg_launch_us": ms * 1e3}
 
 
+def timed_graph(ring, steps, warmup):
+    """Same measurement with the launches replayed from a HIP graph that holds one pass over the ring."""
+    import torch
+    for i in range(max(warmup, ring.R)):
+        ring.forward(i)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        calls = [ring.binding.prepare_fwd(s["Q"], s["K"], s["V"], grid=ring.wl.grid, agent_grid=ring.wl.agent_grid,
+                                          params=ring.params, out=s["out"], workspace=s["ws"], stream=side)
+                 for s in ring.sets]
+        for c in calls:
+            c()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for c in calls:
+                c()
+    torch.cuda.synchronize()
+    reps = max(1, steps // ring.R)
+    graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (reps * ring.R)
+
+
 def measure(wl, binding, args, steps, warmup, module):
     import torch
     ring = Ring(wl, binding, args.ring_bytes, module)
-    ms = timed(ring.forward, steps, warmup)
+    ms = timed_graph(ring, steps, warmup) if args.graph else timed(ring.forward, steps, warmup)
     ring.stage("pool", 0)
     ring.stage("aggregate", 0)
     torch.cuda.synchronize()

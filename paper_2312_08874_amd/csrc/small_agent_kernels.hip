@@ -279,30 +279,54 @@ struct KVRegs {
   uint32_t vraw[8][D / 32];
 };
 
+// Addresses are formed as (wave-uniform step base) + (per-lane 32-bit byte offset): t0 is uniform, so the
+// compiler keeps the base in scalar registers and each load costs no vector address arithmetic.  Only
+// the last, partial step of a range clamps its rows (then the offsets are recomputed per lane).
 template <int D>
 __device__ __forceinline__ void agg_load(const uint16_t* __restrict__ Ku, const uint16_t* __restrict__ Vu, int t0,
                                          int N, int lane, KVRegs<D>& kv) {
   constexpr int KC = D / 32, EV = D / 16;
   const int r = lane & 15, g = lane >> 4;
-  const bool tail = t0 + 32 > N;     // wave-uniform: only the last step of a range clamps its rows
+  const char* kb = (const char*)(Ku + (size_t)t0 * D);
+  const char* vb = (const char*)(Vu + (size_t)t0 * D);
+  if (t0 + 32 <= N) {
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt) {
-    int row = t0 + 16 * rt + r;
-    if (tail) row = min(row, N - 1);
+    for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc) kv.kop[rt][kc] = *(const u32x4*)(Ku + (size_t)row * D + 32 * kc + 8 * g);
-  }
+      for (int kc = 0; kc < KC; ++kc) {
+        const uint32_t off = (uint32_t)(((16 * rt + r) * D + 32 * kc + 8 * g) * 2);
+        kv.kop[rt][kc] = *(const u32x4*)(kb + off);
+      }
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    int row = t0 + (j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4));
-    if (tail) row = min(row, N - 1);
-    const uint16_t* p = Vu + (size_t)row * D + EV * r;
-    if constexpr (EV == 2) {
-      kv.vraw[j][0] = *(const uint32_t*)p;
-    } else {
-      const u32x2 w = *(const u32x2*)p;
-      kv.vraw[j][0] = w[0];
-      kv.vraw[j][1] = w[1];
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t off = (uint32_t)((((j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4))) * D + EV * r) * 2);
+      if constexpr (EV == 2) {
+        kv.vraw[j][0] = *(const uint32_t*)(vb + off);
+      } else {
+        const u32x2 w = *(const u32x2*)(vb + off);
+        kv.vraw[j][0] = w[0];
+        kv.vraw[j][1] = w[1];
+      }
+    }
+  } else {
+    const int last = N - 1 - t0;       // last valid row of this step, relative to t0 (>= 0)
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) {
+        const uint32_t off = (uint32_t)((min(16 * rt + r, last) * D + 32 * kc + 8 * g) * 2);
+        kv.kop[rt][kc] = *(const u32x4*)(kb + off);
+      }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t off = (uint32_t)((min((j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4)), last) * D + EV * r) * 2);
+      if constexpr (EV == 2) {
+        kv.vraw[j][0] = *(const uint32_t*)(vb + off);
+      } else {
+        const u32x2 w = *(const u32x2*)(vb + off);
+        kv.vraw[j][0] = w[0];
+        kv.vraw[j][1] = w[1];
+      }
     }
   }
 }
@@ -587,11 +611,14 @@ template <int D>
 __device__ __forceinline__ void bcast_load(const uint16_t* Qsrc, int row_stride, int t0, int N, int lane,
                                            QRegs<D>& q) {
   const int r = lane & 15, g = lane >> 4;
+  const char* qb = (const char*)(Qsrc + (size_t)t0 * row_stride);     // wave-uniform step base
+  const int last = N - 1 - t0;
 #pragma unroll
   for (int tt = 0; tt < 2; ++tt) {
-    const int row = min(t0 + 16 * tt + r, N - 1);
+    const int row = t0 + 32 <= N ? 16 * tt + r : min(16 * tt + r, last);
 #pragma unroll
-    for (int kc = 0; kc < D / 32; ++kc) q.qop[tt][kc] = *(const u32x4*)(Qsrc + (size_t)row * row_stride + 32 * kc + 8 * g);
+    for (int kc = 0; kc < D / 32; ++kc)
+      q.qop[tt][kc] = *(const u32x4*)(qb + (uint32_t)((row * row_stride + 32 * kc + 8 * g) * 2));
   }
 }
 
@@ -714,12 +741,17 @@ __device__ __forceinline__ void bcast_range(QRegs<D>& cur, const uint16_t* Qsrc,
                                             const u32x4 (&vaop)[D / 16][(NAT + 1) / 2], float sc, int lane,
                                             const BiasArgs& b2, const float* __restrict__ dwc_w,
                                             const float* __restrict__ dwc_b, float vk, int gh, int gw) {
-  for (int t0 = first; t0 < end; t0 += stride) {
-    QRegs<D> nxt;
-    const int tn = t0 + stride;
-    if (tn < end) bcast_load<D>(Qsrc, row_stride, tn, N, lane, nxt);
+  // two steps of Q loads in flight: `cur` holds step `first`, `nxt` is loaded for `first + stride` right away
+  QRegs<D> nxt;
+  if (first + stride < end) bcast_load<D>(Qsrc, row_stride, first + stride, N, lane, nxt);
+  for (int t0 = first; t0 < end; t0 += 2 * stride) {
     bcast_compute<E, D, NAT, BIAS, EPI>(cur, Vu, Ou, t0, N, n, areg, vaop, sc, lane, b2, dwc_w, dwc_b, vk, gh, gw);
-    if (tn < end) cur = nxt;
+    if (t0 + 2 * stride < end) bcast_load<D>(Qsrc, row_stride, t0 + 2 * stride, N, lane, cur);
+    if (t0 + stride < end) {
+      bcast_compute<E, D, NAT, BIAS, EPI>(nxt, Vu, Ou, t0 + stride, N, n, areg, vaop, sc, lane, b2, dwc_w, dwc_b, vk,
+                                          gh, gw);
+      if (t0 + 3 * stride < end) bcast_load<D>(Qsrc, row_stride, t0 + 3 * stride, N, lane, nxt);
+    }
   }
 }
 
@@ -816,7 +848,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_fused_kernel(
   uint16_t* V_lds = K_lds + (size_t)rows * AS;
   float* slots = (float*)(V_lds + (size_t)rows * AS);
 
-  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
+  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6),
+            W = blockDim.x >> 6;
   const int TS = W / NAT, at0 = wave % NAT, ts = wave / NAT;
   const int hd = u % heads;
   const uint16_t* Qu = Q + (size_t)u * N * D;
@@ -936,7 +969,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_aggregate_kernel(
   uint16_t* A_lds = (uint16_t*)smem_raw;
   float* slots = (float*)(A_lds + 16 * NAT * AS);
   const int s = blockIdx.x, S = gridDim.x, u = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6),
+            W = blockDim.x >> 6;
   const int TS = W / G, grp = wave % G, ts = wave / G, at0 = grp * NW;
   const uint16_t* Ku = K + (size_t)u * N * D;
   const uint16_t* Vu = V + (size_t)u * N * D;
@@ -1037,7 +1071,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_broadcast_kernel(
   constexpr int AS = Geo<D, NAT>::AS, RV = Geo<D, NAT>::RV;
   uint16_t* A_lds = (uint16_t*)smem_raw;
   uint16_t* VA_lds = A_lds + 16 * NAT * AS;
-  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, W = blockDim.x >> 6;
+  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6),
+            W = blockDim.x >> 6;
   const int hd = u % heads;
   const uint16_t* Qu = Q + (size_t)u * N * D;
   const uint16_t* Vu = V ? V + (size_t)u * N * D : nullptr;
@@ -1055,18 +1090,42 @@ __global__ __launch_bounds__(64 * kMaxWaves) void small_broadcast_kernel(
       if (S_part == 0) {
         out = *(const f32x4*)(VA + ((size_t)u * n + a) * D + 4 * c4);
       } else {
-        float m = kNegBig;
+        constexpr int kFast = 8;         // up to 8 splits: every load of the merge is issued before the first use
+        if (S_part <= kFast) {
+          float pm[kFast], plv[kFast];
+          f32x4 pa[kFast];
+#pragma unroll
+          for (int sp = 0; sp < kFast; ++sp) {
+            const size_t row = ((size_t)u * S_part + min(sp, S_part - 1)) * n + a;
+            pm[sp] = part_m[row];
+            plv[sp] = part_l[row];
+            pa[sp] = *(const f32x4*)(part_acc + row * D + 4 * c4);
+          }
+          float m = kNegBig;
+#pragma unroll
+          for (int sp = 0; sp < kFast; ++sp) m = fmaxf(m, pm[sp]);
+          float l = 0.0f;
+#pragma unroll
+          for (int sp = 0; sp < kFast; ++sp) {
+            const float w = sp < S_part ? fast_exp2(pm[sp] - m) : 0.0f;
+            l += plv[sp] * w;
+            out += pa[sp] * w;
+          }
+          out *= __builtin_amdgcn_rcpf(l);
+        } else {
+          float m = kNegBig;
 #pragma unroll 4
-        for (int sp = 0; sp < S_part; ++sp) m = fmaxf(m, part_m[((size_t)u * S_part + sp) * n + a]);
-        float l = 0.0f;
+          for (int sp = 0; sp < S_part; ++sp) m = fmaxf(m, part_m[((size_t)u * S_part + sp) * n + a]);
+          float l = 0.0f;
 #pragma unroll 4
-        for (int sp = 0; sp < S_part; ++sp) {
-          const size_t row = ((size_t)u * S_part + sp) * n + a;
-          const float w = fast_exp2(part_m[row] - m);
-          l += part_l[row] * w;
-          out += *(const f32x4*)(part_acc + row * D + 4 * c4) * w;
+          for (int sp = 0; sp < S_part; ++sp) {
+            const size_t row = ((size_t)u * S_part + sp) * n + a;
+            const float w = fast_exp2(part_m[row] - m);
+            l += part_l[row] * w;
+            out += *(const f32x4*)(part_acc + row * D + 4 * c4) * w;
+          }
+          out *= __builtin_amdgcn_rcpf(l);
         }
-        out *= __builtin_amdgcn_rcpf(l);
       }
     }
     u32x2 w2 = {Mx<E>::pack2(out[0], out[1]), Mx<E>::pack2(out[2], out[3])};
