@@ -59,6 +59,21 @@ hipError_t launch_small_merge(const Problem& p, const Partials& part, float* VA,
 hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A, const float* VA,
                                   const Partials* part, const void* V, void* out, int chunks, hipStream_t st);
 
+// per (element type, head width) units behind the launchers above
+#define AA_DECLARE_SMALL(TAG)                                                                                       \
+  hipError_t launch_small_fused_##TAG(const Problem& p, const void* Q, const void* K, const void* V, const void* A, \
+                                      void* out, hipStream_t st);                                                   \
+  hipError_t launch_small_pool_##TAG(const Problem& p, const void* Q, void* A, hipStream_t st);                     \
+  hipError_t launch_small_aggregate_##TAG(const Problem& p, const void* A, const void* K, const void* V,            \
+                                          const Partials& part, hipStream_t st);                                    \
+  hipError_t launch_small_broadcast_##TAG(const Problem& p, const void* Q, const void* A, const float* VA,          \
+                                          const Partials* part, const void* V, void* out, int chunks,               \
+                                          hipStream_t st);
+AA_DECLARE_SMALL(bf16_d32)
+AA_DECLARE_SMALL(bf16_d64)
+AA_DECLARE_SMALL(f16_d32)
+AA_DECLARE_SMALL(f16_d64)
+
 // --- large-agent regime (any n; fp16 / bf16; d a multiple of 8, d <= 128): flash-style MFMA kernels that
 //     stage the streamed operand in LDS; one set per padded head width DP in {32, 64, 128} ---
 #define AA_DECLARE_LARGE(DP)                                                                                        \

@@ -1,0 +1,5 @@
+// Small-agent MFMA kernels for bf16 elements, head width 32.
+#define AA_SMALL_E ElemBF16
+#define AA_SMALL_D 32
+#define AA_SMALL_TAG bf16_d32
+#include "small_agent_kernels.inc"
