@@ -309,3 +309,37 @@ def test_forward_odd_shapes(aa, oracle, grid, agrid, d, dtype):
     ref = oracle.agent_attn_fwd(*(inputs.to_float64(t[k], wl.dtype) for k in ("Q", "K", "V")), heads=wl.heads,
                                 A=util.to_host64(A).reshape(wl.units, wl.n, wl.d))
     util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, dtype, "odd shape %s %s %d" % (grid, agrid, d))
+
+
+# --------------------------------------------------------------------------
+# the one-block-per-unit kernel: every pooling route (window rows fetched by the pooling threads
+# themselves for windows of at most four tokens, pooling out of LDS otherwise, ragged windows), every
+# agent tile count, given agents, and the module terms
+# --------------------------------------------------------------------------
+FUSED_SHAPES = [((8, 8), (4, 4), 64), ((16, 12), (8, 6), 32), ((6, 32), (6, 8), 32), ((9, 3), (3, 3), 64),
+                ((13, 11), (4, 3), 32), ((18, 14), (6, 7), 64), ((14, 14), (7, 7), 32), ((2, 17), (2, 17), 64),
+                ((20, 20), (4, 5), 32)]
+_DT = {"f16": 1, "bf16": 2}
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("grid,agrid,d", FUSED_SHAPES)
+@pytest.mark.parametrize("module", [False, True])
+def test_forward_one_block_per_unit(aa, oracle, grid, agrid, d, dtype, module):
+    import dataclasses
+    wl = dataclasses.replace(WL["tiny"], batch=2, heads=2, grid=grid, agent_grid=agrid, d=d, dtype=dtype, index=11)
+    desc = aa.make_desc(wl.batch, wl.heads, wl.N, wl.n, d, _DT[dtype], grid, agrid)
+    assert aa.plan_str(desc) == "small_fused"
+    t = inputs.make_qkv(wl)
+    dv = dev_qkv(wl, t)
+    params = inputs.make_module_params(wl.heads, wl.n, d, grid, blk=(3, 2), index=11) if module else None
+    A = aa.agent_pool_fwd(dv["Q"], grid=grid, agent_grid=agrid)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=grid, agent_grid=agrid,
+                          params=util.params_to_device(params) if module else None)
+    ref = util.oracle_forward_units(oracle, wl, t, list(range(wl.units)), params=params, A=_stored(A, wl))
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, dtype, "one block per unit %s %s %d" % (grid, agrid, d),
+                       max_abs=1e-2 * max(1.0, float(np.abs(ref).max())))
+    if not module:      # the same agents handed in must give the same bits
+        import torch
+        O2 = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], A)
+        assert torch.equal(O, O2)
