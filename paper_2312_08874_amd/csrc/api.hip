@@ -121,7 +121,14 @@ void plan_small(const aa_desc* d, Plan& pl) {
   if (S < 1) S = 1;
   const int chunk = aa::small_split_chunk(d->N, S);
   pl.S_small = (d->N + chunk - 1) / chunk;
-  const int btok = tuning_env("AA_SMALL_BTOK") >= 32 ? tuning_env("AA_SMALL_BTOK") : 512;   // tokens per broadcast block
+  // tokens per broadcast block: about 448 blocks in all as well, 256 to 1024 tokens each (swept)
+  int btok = tuning_env("AA_SMALL_BTOK");
+  if (btok < 32) {
+    const int64_t want = (448 + units - 1) / units;
+    btok = (int)((d->N + want - 1) / want);
+    btok = (btok + 31) / 32 * 32;
+    btok = btok < 256 ? 256 : (btok > 1024 ? 1024 : btok);
+  }
   pl.bcast_chunks = (d->N + btok - 1) / btok;
 }
 
