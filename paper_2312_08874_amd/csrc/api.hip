@@ -306,6 +306,8 @@ aa_status run_broadcast(const Problem& pr, const void* Q, const void* A, const f
 aa_status run_pool(const Problem& pr, const void* Q, void* A, hipStream_t st) {
   if (use_small(pr, {Q, A}))
     AA_HIP(aa::launch_small_pool(pr, Q, A, st));
+  else if ((pr.dtype == 1 || pr.dtype == 2) && pr.d % 8 == 0 && aligned16(Q) && aligned16(A))
+    AA_HIP(aa::launch_pool_chunk(pr, Q, A, st));
   else
     AA_HIP(aa::launch_pool_generic(pr, Q, A, st));
   return AA_OK;
@@ -446,7 +448,7 @@ size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, siz
   } else if (large_supported(pr)) {
     len = snprintf(buf, buf_len,
                    "%slarge_aggregate(S=%d, %d agents/block) + large_merge + large_broadcast(%d tokens/block)",
-                   agents_given ? "" : "pool_generic + ", pl.S_large, pl.waves_large * pl.nw_large * 16,
+                   agents_given ? "" : "pool_chunk + ", pl.S_large, pl.waves_large * pl.nw_large * 16,
                    32 * pl.bcast_waves_large);
   } else {
     len = snprintf(buf, buf_len, "%saggregate_generic(S=%d) + merge_generic + broadcast_generic",

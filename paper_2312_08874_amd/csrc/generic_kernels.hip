@@ -33,6 +33,57 @@ __global__ __launch_bounds__(64) void pool_generic_kernel(const typename E::T* _
 }
 
 // ---------------------------------------------------------------------------
+// The same for the 16-bit element types with d a multiple of 8 and 16-byte aligned tensors: thread = one
+// (agent, 8-channel chunk) item, 16-byte loads, four window rows in flight.  grid = (ceil(n*d/8 / 256),
+// units).  Accumulation is fp32 in window order (row-major), as in the kernel above.
+// ---------------------------------------------------------------------------
+template <class E>
+__global__ __launch_bounds__(256) void pool_chunk_kernel(const uint16_t* __restrict__ Q, uint16_t* __restrict__ A,
+                                                         int N, int n, int d, int gh, int gw, int ah, int aw) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const int cpr = d >> 3, u = blockIdx.y;
+  const int item = blockIdx.x * 256 + threadIdx.x;
+  if (item >= n * cpr) return;
+  const int a = item / cpr, chunk = item - a * cpr;
+  const int ay = a / aw, ax = a - ay * aw;
+  const int y0 = pool_win_lo(ay, gh, ah), y1 = pool_win_hi(ay, gh, ah);
+  const int x0 = pool_win_lo(ax, gw, aw), x1 = pool_win_hi(ax, gw, aw);
+  const uint16_t* q = Q + (size_t)u * N * d + 8 * chunk;
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  auto add = [&](const u32x4& v) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      union { uint16_t h[2]; uint32_t w; } t;
+      t.w = v[k];
+      acc[2 * k] += E::to_f32(*(const typename E::T*)&t.h[0]);
+      acc[2 * k + 1] += E::to_f32(*(const typename E::T*)&t.h[1]);
+    }
+  };
+  for (int y = y0; y < y1; ++y) {
+    const uint16_t* row = q + (size_t)y * gw * d;
+    int x = x0;
+    for (; x + 4 <= x1; x += 4) {
+      u32x4 v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = *(const u32x4*)(row + (size_t)(x + j) * d);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) add(v[j]);
+    }
+    for (; x < x1; ++x) add(*(const u32x4*)(row + (size_t)x * d));
+  }
+  const float inv = 1.0f / (float)((y1 - y0) * (x1 - x0));
+  u32x4 w;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    union { uint16_t h[2]; uint32_t w; } t;
+    *(typename E::T*)&t.h[0] = E::from_f32(acc[2 * k] * inv);
+    *(typename E::T*)&t.h[1] = E::from_f32(acc[2 * k + 1] * inv);
+    w[k] = t.w;
+  }
+  *(u32x4*)(A + ((size_t)u * n + a) * d + 8 * chunk) = w;
+}
+
+// ---------------------------------------------------------------------------
 // Agent aggregation, split-N partial pass (Sec. 4.1 Eq. (3), bias of Eq. (5)).
 // grid = (ceil(n / kWaves), S, units); wave w of a block owns agent 4*blockIdx.x + w
 // and walks the tokens of split blockIdx.y in steps of 64 (one token per lane)
@@ -238,6 +289,19 @@ hipError_t launch_pool_generic(const Problem& p, const void* Q, void* A, hipStre
   dim3 grid(p.n, p.units);
   AA_DISPATCH_DTYPE(p.dtype, pool_generic_kernel<E><<<grid, dim3(64), 0, st>>>(
       (const typename E::T*)Q, (typename E::T*)A, p.N, p.n, p.d, p.gh, p.gw, p.ah, p.aw));
+  return hipGetLastError();
+}
+
+hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, hipStream_t st) {
+  const dim3 grid((p.n * (p.d >> 3) + 255) / 256, p.units);
+  if (p.dtype == 2)
+    pool_chunk_kernel<ElemBF16><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, p.N, p.n, p.d, p.gh, p.gw,
+                                                            p.ah, p.aw);
+  else if (p.dtype == 1)
+    pool_chunk_kernel<ElemF16><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, p.N, p.n, p.d, p.gh, p.gw,
+                                                           p.ah, p.aw);
+  else
+    return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

@@ -31,6 +31,8 @@ struct Partials {
 
 // --- reference-quality kernels: any shape (d <= 256), any dtype, VALU fp32 math ---
 hipError_t launch_pool_generic(const Problem& p, const void* Q, void* A, hipStream_t st);
+// fp16 / bf16, d a multiple of 8, Q and A 16-byte aligned: 16-byte loads, thread per (agent, 8 channels)
+hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, hipStream_t st);
 hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* K, const void* V,
                                     const Partials& part, hipStream_t st);
 hipError_t launch_merge_generic(const Problem& p, const Partials& part, float* VA, hipStream_t st);
