@@ -1,5 +1,6 @@
 /*
- * CPU oracle for the agent-attention forward pass (arXiv 2312.08874).
+ * CPU oracle for the agent-attention forward pass (arXiv 2312.08874) and its
+ * gradients.
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, fp64 statement of
  * what the GPU library must compute.  It shares no code, header, table or
@@ -346,6 +347,269 @@ void oracle_agent_attn_fwd(const double *Q, const double *K, const double *V,
     free(A);
     free(VA);
     free(conv);
+}
+
+/* ========================================================================
+ * Backward pass.  The paper trains its models end to end (Sec. 5, training
+ * set-up), so every operation above needs its gradient; the paper prints none
+ * of them, they follow from the definitions by the chain rule and are written
+ * out here term by term.  Pins: central finite differences of the forward
+ * oracle and an automatic-differentiation library on the same definition
+ * (tests/test_oracle_bwd_pins.py).
+ * ====================================================================== */
+
+/* ------------------------------------------------------------------------
+ * Gradient of oracle_softmax_attention.  With w the normalised weights and
+ * g = d(loss)/d(out):
+ *   dVm[j,:]  = sum_i w[i,j] g[i,:]
+ *   dW[i,j]   = <g[i,:], Vm[j,:]>
+ *   dS[i,j]   = w[i,j] (dW[i,j] - sum_j' w[i,j'] dW[i,j'])      (softmax rows)
+ *   dBias     = dS
+ *   dQm[i,:]  = scale sum_j dS[i,j] Km[j,:]
+ *   dKm[j,:]  = scale sum_i dS[i,j] Qm[i,:]
+ * dQm [M,d], dKm [L,d], dVm [L,dv] are overwritten; dBias [M,L] (may be NULL)
+ * is ACCUMULATED into (bias parameters are shared across the batch).
+ * ---------------------------------------------------------------------- */
+void oracle_softmax_attention_bwd(const double *Qm, const double *Km,
+                                  const double *Vm, const double *bias,
+                                  double scale, int M, int L, int d, int dv,
+                                  const double *g, double *dQm, double *dKm,
+                                  double *dVm, double *dBias)
+{
+    double *w = (double *)malloc((size_t)M * L * sizeof(double));
+    double *dS = (double *)malloc((size_t)M * L * sizeof(double));
+    double *out = (double *)malloc((size_t)M * dv * sizeof(double));
+    oracle_softmax_attention(Qm, Km, Vm, bias, scale, M, L, d, dv, out, w);
+    for (int i = 0; i < M; ++i) {
+        double inner = 0.0;
+        for (int j = 0; j < L; ++j) {
+            double dW = 0.0;
+            for (int c = 0; c < dv; ++c)
+                dW += g[(size_t)i * dv + c] * Vm[(size_t)j * dv + c];
+            dS[(size_t)i * L + j] = dW;
+            inner += w[(size_t)i * L + j] * dW;
+        }
+        for (int j = 0; j < L; ++j)
+            dS[(size_t)i * L + j] = w[(size_t)i * L + j] * (dS[(size_t)i * L + j] - inner);
+    }
+    for (int j = 0; j < L; ++j)
+        for (int c = 0; c < dv; ++c) {
+            double acc = 0.0;
+            for (int i = 0; i < M; ++i)
+                acc += w[(size_t)i * L + j] * g[(size_t)i * dv + c];
+            dVm[(size_t)j * dv + c] = acc;
+        }
+    for (int i = 0; i < M; ++i)
+        for (int c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int j = 0; j < L; ++j)
+                acc += dS[(size_t)i * L + j] * Km[(size_t)j * d + c];
+            dQm[(size_t)i * d + c] = scale * acc;
+        }
+    for (int j = 0; j < L; ++j)
+        for (int c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int i = 0; i < M; ++i)
+                acc += dS[(size_t)i * L + j] * Qm[(size_t)i * d + c];
+            dKm[(size_t)j * d + c] = scale * acc;
+        }
+    if (dBias)
+        for (size_t e = 0; e < (size_t)M * L; ++e) dBias[e] += dS[e];
+    free(w);
+    free(dS);
+    free(out);
+}
+
+/* ------------------------------------------------------------------------
+ * Gradient of oracle_pool for one unit: every token of agent a's window
+ * receives dA[a,:] / |window|.  dA [n,d]; dQ [N,d] is ACCUMULATED into.
+ * ---------------------------------------------------------------------- */
+void oracle_pool_bwd(const double *dA, int gh, int gw, int ah, int aw, int d,
+                     double *dQ)
+{
+    for (int ay = 0; ay < ah; ++ay)
+        for (int ax = 0; ax < aw; ++ax) {
+            int y0 = win_lo(ay, gh, ah), y1 = win_hi(ay, gh, ah);
+            int x0 = win_lo(ax, gw, aw), x1 = win_hi(ax, gw, aw);
+            double cnt = (double)(y1 - y0) * (double)(x1 - x0);
+            for (int y = y0; y < y1; ++y)
+                for (int x = x0; x < x1; ++x)
+                    for (int c = 0; c < d; ++c)
+                        dQ[((size_t)y * gw + x) * d + c] +=
+                            dA[((size_t)ay * aw + ax) * d + c] / cnt;
+        }
+}
+
+/* ------------------------------------------------------------------------
+ * Gradient of oracle_dwc for one unit, g = d(loss)/d(out) [gh*gw, d]:
+ *   dV[y+u,x+v,c]  += wgt[c,u+1,v+1] g[y,x,c]
+ *   dwgt[c,u+1,v+1] += V[y+u,x+v,c]  g[y,x,c]
+ *   db[c]          += g[y,x,c]
+ * All three outputs are ACCUMULATED into; dwgt / db may be NULL.
+ * ---------------------------------------------------------------------- */
+void oracle_dwc_bwd(const double *V, const double *wgt, const double *g, int gh,
+                    int gw, int d, double *dV, double *dwgt, double *db)
+{
+    for (int y = 0; y < gh; ++y)
+        for (int x = 0; x < gw; ++x)
+            for (int c = 0; c < d; ++c) {
+                double gv = g[((size_t)y * gw + x) * d + c];
+                if (db) db[c] += gv;
+                for (int u = -1; u <= 1; ++u)
+                    for (int v = -1; v <= 1; ++v) {
+                        int yy = y + u, xx = x + v;
+                        if (yy < 0 || yy >= gh || xx < 0 || xx >= gw) continue;
+                        size_t wi = (size_t)c * 9 + (size_t)(u + 1) * 3 + (v + 1);
+                        size_t vi = ((size_t)yy * gw + xx) * d + c;
+                        dV[vi] += wgt[wi] * gv;
+                        if (dwgt) dwgt[wi] += V[vi] * gv;
+                    }
+            }
+}
+
+/* ------------------------------------------------------------------------
+ * Gradient of the bias composition (adjoint of oracle_bias1_dense /
+ * oracle_bias2_dense) for ONE head: the dense gradient is summed along the
+ * axis each component was repeated over, and pushed back through the
+ * bilinear weights for the block component.  Outputs are overwritten; any
+ * may be NULL.
+ * ---------------------------------------------------------------------- */
+static void resize_bilinear_bwd(const double *gdst /* [h*w] */, int h0, int w0,
+                                size_t stride, int h, int w, double *gsrc)
+{
+    for (int y = 0; y < h; ++y) {
+        int y0, y1;
+        double fy;
+        src_coord(y, h, h0, &y0, &y1, &fy);
+        for (int x = 0; x < w; ++x) {
+            int x0, x1;
+            double fx;
+            src_coord(x, w, w0, &x0, &x1, &fx);
+            double gv = gdst[(size_t)y * w + x];
+            gsrc[((size_t)y0 * w0 + x0) * stride] += gv * (1.0 - fy) * (1.0 - fx);
+            gsrc[((size_t)y0 * w0 + x1) * stride] += gv * (1.0 - fy) * fx;
+            gsrc[((size_t)y1 * w0 + x0) * stride] += gv * fy * (1.0 - fx);
+            gsrc[((size_t)y1 * w0 + x1) * stride] += gv * fy * fx;
+        }
+    }
+}
+
+void oracle_bias1_components_bwd(const double *dB1 /* [n,N] */, int n, int h,
+                                 int w, int h0, int w0, double *dcol1,
+                                 double *drow1, double *dblk1)
+{
+    const size_t N = (size_t)h * w;
+    if (dcol1) memset(dcol1, 0, (size_t)n * w * sizeof(double));
+    if (drow1) memset(drow1, 0, (size_t)n * h * sizeof(double));
+    if (dblk1) memset(dblk1, 0, (size_t)n * h0 * w0 * sizeof(double));
+    for (int a = 0; a < n; ++a) {
+        for (int y = 0; y < h; ++y)
+            for (int x = 0; x < w; ++x) {
+                double gv = dB1[(size_t)a * N + (size_t)y * w + x];
+                if (dcol1) dcol1[(size_t)a * w + x] += gv;
+                if (drow1) drow1[(size_t)a * h + y] += gv;
+            }
+        if (dblk1)
+            resize_bilinear_bwd(dB1 + (size_t)a * N, h0, w0, 1, h, w,
+                                dblk1 + (size_t)a * h0 * w0);
+    }
+}
+
+void oracle_bias2_components_bwd(const double *dB2 /* [N,n] */, int n, int h,
+                                 int w, int h0, int w0, double *dcol2,
+                                 double *drow2, double *dblk2)
+{
+    const size_t N = (size_t)h * w;
+    double *plane = (double *)malloc(N * sizeof(double));
+    if (dcol2) memset(dcol2, 0, (size_t)w * n * sizeof(double));
+    if (drow2) memset(drow2, 0, (size_t)h * n * sizeof(double));
+    if (dblk2) memset(dblk2, 0, (size_t)h0 * w0 * n * sizeof(double));
+    for (int a = 0; a < n; ++a) {
+        for (int y = 0; y < h; ++y)
+            for (int x = 0; x < w; ++x) {
+                double gv = dB2[((size_t)y * w + x) * n + a];
+                plane[(size_t)y * w + x] = gv;
+                if (dcol2) dcol2[(size_t)x * n + a] += gv;
+                if (drow2) drow2[(size_t)y * n + a] += gv;
+            }
+        if (dblk2) resize_bilinear_bwd(plane, h0, w0, (size_t)n, h, w, dblk2 + a);
+    }
+    free(plane);
+}
+
+/* ------------------------------------------------------------------------
+ * Gradient of oracle_agent_attn_fwd.  g = d(loss)/dO [units,N,d].
+ *
+ *   O = Attn(Q, A, VA; B2) + DWC(V) + vk V,  VA = Attn(A, K, V; B1),
+ *   A = Pooling(Q) or given.
+ *
+ *   broadcast stage  -> dQ, dA (as keys), dVA, dB2
+ *   aggregation stage-> dA (as queries), dK, dV, dB1        (fed with dVA)
+ *   dV += DWC^T(g) + vk g;   A pooled: dQ += Pooling^T(dA);  A given: dA out.
+ *
+ * dQ, dK, dV [units,N,d] overwritten; dA_out [units,n,d] overwritten (used
+ * only when A_in is given, else ignored / may be NULL); dB1 [heads,n,N],
+ * dB2 [heads,N,n], ddwc_w [heads,d,3,3], ddwc_b [heads,d]: overwritten with
+ * the sum over the batch, each may be NULL.
+ * ---------------------------------------------------------------------- */
+void oracle_agent_attn_bwd(const double *Q, const double *K, const double *V,
+                           const double *A_in, int units, int heads, int gh,
+                           int gw, int ah, int aw, int N, int n, int d,
+                           double scale1, double scale2, const double *B1,
+                           const double *B2, const double *dwc_w,
+                           const double *dwc_b, double vk, const double *g,
+                           double *dQ, double *dK, double *dV, double *dA_out,
+                           double *dB1, double *dB2, double *ddwc_w,
+                           double *ddwc_b)
+{
+    (void)dwc_b;
+    double *A = (double *)malloc((size_t)n * d * sizeof(double));
+    double *VA = (double *)malloc((size_t)n * d * sizeof(double));
+    double *dVA = (double *)malloc((size_t)n * d * sizeof(double));
+    double *dA_keys = (double *)malloc((size_t)n * d * sizeof(double));
+    double *dA_queries = (double *)malloc((size_t)n * d * sizeof(double));
+    if (dB1) memset(dB1, 0, (size_t)heads * n * N * sizeof(double));
+    if (dB2) memset(dB2, 0, (size_t)heads * N * n * sizeof(double));
+    if (ddwc_w) memset(ddwc_w, 0, (size_t)heads * d * 9 * sizeof(double));
+    if (ddwc_b) memset(ddwc_b, 0, (size_t)heads * d * sizeof(double));
+    for (int u = 0; u < units; ++u) {
+        const int hd = u % heads;
+        const size_t off = (size_t)u * N * d;
+        const double *Qu = Q + off, *Ku = K + off, *Vu = V + off, *gu = g + off;
+        const double *B1h = B1 ? B1 + (size_t)hd * n * N : NULL;
+        const double *B2h = B2 ? B2 + (size_t)hd * N * n : NULL;
+        if (A_in)
+            memcpy(A, A_in + (size_t)u * n * d, (size_t)n * d * sizeof(double));
+        else
+            oracle_pool(Qu, 1, gh, gw, ah, aw, d, A);
+        oracle_softmax_attention(A, Ku, Vu, B1h, scale1, n, N, d, d, VA, NULL);
+        /* broadcast stage: queries Q, keys A, values VA */
+        oracle_softmax_attention_bwd(Qu, A, VA, B2h, scale2, N, n, d, d, gu,
+                                     dQ + off, dA_keys, dVA,
+                                     dB2 ? dB2 + (size_t)hd * N * n : NULL);
+        /* aggregation stage: queries A, keys K, values V, upstream dVA */
+        oracle_softmax_attention_bwd(A, Ku, Vu, B1h, scale1, n, N, d, d, dVA,
+                                     dA_queries, dK + off, dV + off,
+                                     dB1 ? dB1 + (size_t)hd * n * N : NULL);
+        for (size_t e = 0; e < (size_t)n * d; ++e) dA_keys[e] += dA_queries[e];
+        if (A_in) {
+            if (dA_out)
+                memcpy(dA_out + (size_t)u * n * d, dA_keys, (size_t)n * d * sizeof(double));
+        } else {
+            oracle_pool_bwd(dA_keys, gh, gw, ah, aw, d, dQ + off);
+        }
+        if (dwc_w)
+            oracle_dwc_bwd(Vu, dwc_w + (size_t)hd * d * 9, gu, gh, gw, d, dV + off,
+                           ddwc_w ? ddwc_w + (size_t)hd * d * 9 : NULL,
+                           ddwc_b ? ddwc_b + (size_t)hd * d : NULL);
+        if (vk != 0.0)
+            for (size_t e = 0; e < (size_t)N * d; ++e) dV[off + e] += vk * gu[e];
+    }
+    free(A);
+    free(VA);
+    free(dVA);
+    free(dA_keys);
+    free(dA_queries);
 }
 
 int oracle_num_threads(void)

@@ -188,3 +188,72 @@ def agent_attn_fwd(Q, K, V, *, heads, grid=None, agent_grid=None, A=None, scale1
     if return_intermediates:
         return O, A_out, VA_out
     return O
+
+
+# --------------------------------------------------------------------------
+# gradients
+# --------------------------------------------------------------------------
+def softmax_attention_bwd(Qm, Km, Vm, g, bias=None, scale=1.0):
+    """Gradient of softmax_attention for upstream g [M, dv]: (dQm, dKm, dVm, dBias)."""
+    Qm, Km, Vm, g, bias = _f64(Qm), _f64(Km), _f64(Vm), _f64(g), _f64(bias)
+    M, d = Qm.shape
+    L, dv = Vm.shape
+    dQ, dK, dV = np.empty((M, d)), np.empty((L, d)), np.empty((L, dv))
+    dB = np.zeros((M, L))
+    _load().oracle_softmax_attention_bwd(_p(Qm), _p(Km), _p(Vm), _p(bias), ctypes.c_double(scale), M, L, d, dv,
+                                         _p(g), _p(dQ), _p(dK), _p(dV), _p(dB))
+    return dQ, dK, dV, dB
+
+
+def bias1_components_bwd(dB1, h, w, h0, w0):
+    """Dense dB1 [n, N] of one head -> (dcol1 [n,w], drow1 [n,h], dblk1 [n,h0,w0])."""
+    dB1 = _f64(dB1)
+    n = dB1.shape[0]
+    dcol, drow, dblk = np.empty((n, w)), np.empty((n, h)), np.empty((n, h0, w0))
+    _load().oracle_bias1_components_bwd(_p(dB1), n, h, w, h0, w0, _p(dcol), _p(drow), _p(dblk))
+    return dcol, drow, dblk
+
+
+def bias2_components_bwd(dB2, h, w, h0, w0):
+    """Dense dB2 [N, n] of one head -> (dcol2 [w,n], drow2 [h,n], dblk2 [h0,w0,n])."""
+    dB2 = _f64(dB2)
+    n = dB2.shape[1]
+    dcol, drow, dblk = np.empty((w, n)), np.empty((h, n)), np.empty((h0, w0, n))
+    _load().oracle_bias2_components_bwd(_p(dB2), n, h, w, h0, w0, _p(dcol), _p(drow), _p(dblk))
+    return dcol, drow, dblk
+
+
+def agent_attn_bwd(Q, K, V, dO, *, heads, grid=None, agent_grid=None, A=None, scale1=None, scale2=None,
+                   B1=None, B2=None, dwc_w=None, dwc_b=None, v_residual_k=0.0):
+    """Gradient of agent_attn_fwd for upstream dO [units, N, d].
+
+    Returns a dict: dQ, dK, dV [units,N,d]; dA [units,n,d] when A is given; dB1 [heads,n,N] /
+    dB2 [heads,N,n] (dense, summed over the batch) when the bias is given; ddwc_w, ddwc_b when
+    dwc_w is given.
+    """
+    Q, K, V, A, dO = _f64(Q), _f64(K), _f64(V), _f64(A), _f64(dO)
+    B1, B2, dwc_w, dwc_b = _f64(B1), _f64(B2), _f64(dwc_w), _f64(dwc_b)
+    units, N, d = Q.shape
+    gh, gw = grid if grid is not None else (1, N)
+    if A is not None:
+        n = A.shape[1]
+        ah, aw = agent_grid if agent_grid is not None else (1, n)
+    else:
+        ah, aw = agent_grid
+        n = ah * aw
+    s1 = d ** -0.5 if scale1 is None else scale1
+    s2 = d ** -0.5 if scale2 is None else scale2
+    out = {"dQ": np.empty((units, N, d)), "dK": np.empty((units, N, d)), "dV": np.empty((units, N, d))}
+    dA = np.empty((units, n, d)) if A is not None else None
+    dB1 = np.empty((heads, n, N)) if B1 is not None else None
+    dB2 = np.empty((heads, N, n)) if B2 is not None else None
+    dw = np.empty((heads, d, 3, 3)) if dwc_w is not None else None
+    db = np.empty((heads, d)) if dwc_w is not None else None
+    _load().oracle_agent_attn_bwd(_p(Q), _p(K), _p(V), _p(A), units, heads, gh, gw, ah, aw, N, n, d,
+                                  ctypes.c_double(s1), ctypes.c_double(s2), _p(B1), _p(B2), _p(dwc_w), _p(dwc_b),
+                                  ctypes.c_double(v_residual_k), _p(dO), _p(out["dQ"]), _p(out["dK"]),
+                                  _p(out["dV"]), _p(dA), _p(dB1), _p(dB2), _p(dw), _p(db))
+    for k, v in (("dA", dA), ("dB1", dB1), ("dB2", dB2), ("ddwc_w", dw), ("ddwc_b", db)):
+        if v is not None:
+            out[k] = v
+    return out
