@@ -114,6 +114,40 @@ aa_status agent_aggregate_fwd(const aa_desc *desc, const void *A, const void *K,
 aa_status agent_broadcast_fwd(const aa_desc *desc, const void *Q, const void *A, const float *VA,
                               const void *V, const aa_params *params, void *out, void *hip_stream);
 
+/* ------------------------------------------------------------------------
+ * Backward pass (the paper trains its models end to end, Sec. 5; the gradients
+ * follow from Eq. (3), (5), (6) and Appendix B / C.1 by the chain rule).
+ * First implementation: reference-quality kernels that materialise both
+ * attention matrices in the workspace (fp32), so the workspace is large:
+ * about 4*n*N + 7*N*d + 4*n*d floats per (batch, head) unit.
+ * ---------------------------------------------------------------------- */
+
+/* Gradients of the module parameters (host struct of device pointers, fp32,
+ * same layouts as aa_params, summed over the batch).  A NULL pointer skips that
+ * gradient; a NULL aa_param_grads* skips all.  A gradient may only be requested
+ * for a parameter that is present in aa_params (else AA_ERR_NULL). */
+typedef struct {
+  float *db1_col, *db1_row, *db1_blk; /* [H,n,w], [H,n,h], [H,n,h0,w0] */
+  float *db2_col, *db2_row, *db2_blk; /* [H,w,n], [H,h,n], [H,h0,w0,n] */
+  float *ddwc_w, *ddwc_b;             /* [H,d,3,3], [H,d] */
+} aa_param_grads;
+
+/* Bytes of device workspace agent_attn_bwd needs.  0 when the descriptor is invalid. */
+size_t agent_attn_bwd_workspace_bytes(const aa_desc *desc, const aa_params *params);
+
+/* Gradients of agent_attn_fwd for the upstream gradient dO [batch, heads, N, d].
+ * A == NULL: agents are pooled from Q and their gradient flows back into dQ
+ * (dA must be NULL).  A != NULL: agents were given; dA [batch, heads, n, d]
+ * receives their gradient (required).  dQ, dK, dV have the shape and type of
+ * Q, K, V and are rounded once from fp32.  The pooled agents are rounded to the
+ * element type exactly as the forward pass does; that rounding is treated as
+ * the identity by the gradient.  Outputs must not overlap inputs or the
+ * workspace.  Same stream, error and determinism conventions as the forward. */
+aa_status agent_attn_bwd(const aa_desc *desc, const void *Q, const void *K, const void *V,
+                         const void *A, const aa_params *params, const void *dO, void *workspace,
+                         size_t workspace_bytes, void *dQ, void *dK, void *dV, void *dA,
+                         const aa_param_grads *param_grads, void *hip_stream);
+
 /* FLOPs the cost model of Sec. 4.2 Eq. (7) assigns to the attention part:
  * 2 * (2nNC + 2NnC) per batch element with C = heads*d, i.e. 8*N*n*d per unit.
  * Returns 0 when the descriptor is invalid. */

@@ -257,3 +257,13 @@ def agent_attn_bwd(Q, K, V, dO, *, heads, grid=None, agent_grid=None, A=None, sc
         if v is not None:
             out[k] = v
     return out
+
+
+def pool_bwd(dA, gh, gw, ah, aw):
+    """Gradient of pool: dA [units, n, d] -> dQ [units, N, d]."""
+    dA = _f64(dA)
+    units, n, d = dA.shape
+    dQ = np.zeros((units, gh * gw, d))
+    for u in range(units):
+        _load().oracle_pool_bwd(_p(dA[u]), gh, gw, ah, aw, d, _p(dQ[u]))
+    return dQ

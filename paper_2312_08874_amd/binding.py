@@ -38,8 +38,15 @@ class aa_params(ctypes.Structure):
                 ("dwc_w", ctypes.c_void_p), ("dwc_b", ctypes.c_void_p)]
 
 
+class aa_param_grads(ctypes.Structure):
+    _fields_ = [("db1_col", ctypes.c_void_p), ("db1_row", ctypes.c_void_p), ("db1_blk", ctypes.c_void_p),
+                ("db2_col", ctypes.c_void_p), ("db2_row", ctypes.c_void_p), ("db2_blk", ctypes.c_void_p),
+                ("ddwc_w", ctypes.c_void_p), ("ddwc_b", ctypes.c_void_p)]
+
+
 EXPORTS = ("agent_attn_workspace_bytes", "agent_attn_fwd", "agent_pool_fwd", "agent_aggregate_fwd",
-           "agent_broadcast_fwd", "agent_attn_flops", "agent_attn_status_str", "agent_attn_plan_str")
+           "agent_broadcast_fwd", "agent_attn_flops", "agent_attn_status_str", "agent_attn_plan_str",
+           "agent_attn_bwd_workspace_bytes", "agent_attn_bwd")
 
 _lib = None
 
@@ -71,6 +78,11 @@ def lib():
         L.agent_aggregate_fwd.argtypes = [dp, vp, vp, vp, pp, vp, ctypes.c_size_t, vp, vp]
         L.agent_broadcast_fwd.restype = ctypes.c_int
         L.agent_broadcast_fwd.argtypes = [dp, vp, vp, vp, vp, pp, vp, vp]
+        L.agent_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.agent_attn_bwd_workspace_bytes.argtypes = [dp, pp]
+        L.agent_attn_bwd.restype = ctypes.c_int
+        L.agent_attn_bwd.argtypes = [dp, vp, vp, vp, vp, pp, vp, vp, ctypes.c_size_t, vp, vp, vp, vp,
+                                     ctypes.POINTER(aa_param_grads), vp]
         L.agent_attn_plan_str.restype = ctypes.c_size_t
         L.agent_attn_plan_str.argtypes = [dp, ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
         L.agent_attn_status_str.restype = ctypes.c_char_p
@@ -178,6 +190,39 @@ def agent_attn_fwd(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict 
                               workspace.data_ptr(), workspace.numel() * workspace.element_size(), out.data_ptr(),
                               _stream(stream))
     _check(st, "agent_attn_fwd")
+    return out
+
+
+def agent_attn_bwd(Q, K, V, dO, A=None, *, grid=None, agent_grid=None, params: dict | None = None, scale1=0.0,
+                   scale2=0.0, v_residual_k=0.0, want_param_grads=True, workspace=None, stream=None):
+    """Gradients of agent_attn_fwd for upstream dO.  Returns a dict: dQ, dK, dV (shape and type of Q),
+    dA when A is given, and, for every module parameter present in `params` (want_param_grads), its
+    fp32 gradient under the parameter's own name prefixed with "d" (db1_col, ..., ddwc_w, ddwc_b)."""
+    import torch
+    n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
+    desc = _desc_from(Q, n, grid, agent_grid, scale1=scale1, scale2=scale2, v_residual_k=v_residual_k)
+    p = make_params(params)
+    need = int(lib().agent_attn_bwd_workspace_bytes(ctypes.byref(desc), _pp(p)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    out = {"dQ": torch.empty_like(Q), "dK": torch.empty_like(K), "dV": torch.empty_like(V)}
+    if A is not None:
+        out["dA"] = torch.empty_like(A)
+    g = aa_param_grads()
+    if params and want_param_grads:
+        for key in ("b1_col", "b1_row", "b1_blk", "b2_col", "b2_row", "b2_blk", "dwc_w", "dwc_b"):
+            t = params.get(key)
+            if t is None and not (key == "dwc_b" and params.get("dwc_w") is not None):
+                continue
+            shape = t.shape if t is not None else params["dwc_w"].shape[:2]
+            gt = torch.empty(tuple(shape), dtype=torch.float32, device="cuda")
+            out["d" + key] = gt
+            setattr(g, "d" + key, gt.data_ptr())
+    st = lib().agent_attn_bwd(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(A), _pp(p),
+                              dO.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                              out["dQ"].data_ptr(), out["dK"].data_ptr(), out["dV"].data_ptr(), _ptr(out.get("dA")),
+                              ctypes.byref(g), _stream(stream))
+    _check(st, "agent_attn_bwd")
     return out
 
 

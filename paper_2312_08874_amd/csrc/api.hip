@@ -432,6 +432,75 @@ aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, cons
   return run_broadcast(pr, Q, agents, VA, V, out, pl, stream);
 }
 
+// Backward workspace: the pooled agents in the element type (256-byte aligned), then the fp32 scratch.
+static size_t bwd_agents_bytes(const aa_desc* d) {
+  return align_up((size_t)d->batch * d->heads * d->n * d->d * elem_size(d->dtype));
+}
+
+size_t agent_attn_bwd_workspace_bytes(const aa_desc* desc, const aa_params* params) {
+  if (check_desc(desc, params_use_grid(params), false) != AA_OK) return 0;
+  if (check_params(params) != AA_OK) return 0;
+  const Problem pr = make_problem(desc, params);
+  return bwd_agents_bytes(desc) + align_up(aa::backward_workspace_floats(pr) * sizeof(float));
+}
+
+aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, const void* V, const void* A,
+                         const aa_params* params, const void* dO, void* workspace, size_t workspace_bytes, void* dQ,
+                         void* dK, void* dV, void* dA, const aa_param_grads* param_grads, void* hip_stream) {
+  const bool pooling = (A == nullptr);
+  aa_status st = check_desc(desc, pooling || params_use_grid(params), pooling);
+  if (st == AA_ERR_SHAPE && pooling && desc && desc->grid_h == 0 && desc->grid_w == 0) st = AA_ERR_POOL;
+  if (st != AA_OK) return st;
+  st = check_params(params);
+  if (st != AA_OK) return st;
+  if (!Q || !K || !V || !dO || !dQ || !dK || !dV) return AA_ERR_NULL;
+  if (pooling ? dA != nullptr : dA == nullptr) return AA_ERR_NULL;
+  aa::BackwardParamGrads pg{};
+  if (param_grads) {
+    // a gradient can only be asked for a parameter that takes part in the forward
+    const aa_param_grads& g = *param_grads;
+    const bool ok = (!g.db1_col || (params && params->b1_col)) && (!g.db1_row || (params && params->b1_row)) &&
+                    (!g.db1_blk || (params && params->b1_blk)) && (!g.db2_col || (params && params->b2_col)) &&
+                    (!g.db2_row || (params && params->b2_row)) && (!g.db2_blk || (params && params->b2_blk)) &&
+                    (!g.ddwc_w || (params && params->dwc_w)) && (!g.ddwc_b || (params && params->dwc_w));
+    if (!ok) return AA_ERR_NULL;
+    pg = aa::BackwardParamGrads{g.db1_col, g.db1_row, g.db1_blk, g.db2_col, g.db2_row, g.db2_blk, g.ddwc_w, g.ddwc_b,
+                                params ? params->blk_h0 : 0, params ? params->blk_w0 : 0};
+  }
+  const size_t need = agent_attn_bwd_workspace_bytes(desc, params);
+  if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < need) return AA_ERR_WORKSPACE;
+  const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
+  const size_t big = units * desc->N * desc->d * es, small = units * desc->n * desc->d * es;
+  const void* ins[] = {Q, K, V, dO};
+  void* outs[] = {dQ, dK, dV};
+  for (void* o : outs) {
+    for (const void* i : ins)
+      if (overlaps(o, big, i, big)) return AA_ERR_ALIAS;
+    if (overlaps(o, big, A, small) || overlaps(o, big, workspace, workspace_bytes) || overlaps(o, big, dA, small))
+      return AA_ERR_ALIAS;
+    for (void* o2 : outs)
+      if (o2 != o && overlaps(o, big, o2, big)) return AA_ERR_ALIAS;
+  }
+  for (const void* i : ins)
+    if (overlaps(workspace, workspace_bytes, i, big) || overlaps(dA, small, i, big)) return AA_ERR_ALIAS;
+  if (overlaps(workspace, workspace_bytes, A, small) || overlaps(dA, small, A, small) ||
+      overlaps(dA, small, workspace, workspace_bytes))
+    return AA_ERR_ALIAS;
+
+  const Problem pr = make_problem(desc, params);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  const void* agents = A;
+  if (pooling) {
+    st = run_pool(pr, Q, ws, stream);
+    if (st != AA_OK) return st;
+    agents = ws;
+  }
+  AA_HIP(aa::launch_backward(pr, Q, K, V, agents, dO, (float*)(ws + bwd_agents_bytes(desc)), dQ, dK, dV, dA, !pooling,
+                             pg, stream));
+  return AA_OK;
+}
+
 size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, size_t buf_len) {
   if (!buf || buf_len == 0) return 0;
   buf[0] = 0;

@@ -1,0 +1,432 @@
+// Backward pass of agent attention: reference-quality kernels, fp32 VALU arithmetic, any shape and
+// element type.  The attention matrices of both stages are materialised in the workspace (fp32,
+// n x N and N x n per unit), which turns the gradient into batched matrix products, row-wise softmax
+// kernels and a few gathers:
+//
+//   forward recompute   S1 = c1 A K^T + B1,  P1 = softmax_rows(S1),  V_A = P1 V        (Sec. 4.1 Eq. (3), (5))
+//                       S2 = c2 Q A^T + B2,  P2 = softmax_rows(S2)
+//   broadcast stage     dV_A = P2^T dO,  dP2 = dO V_A^T,  dS2 = P2 o (dP2 - rowsum(P2 o dP2))
+//                       dQ = c2 dS2 A,  dA = c2 dS2^T Q
+//   aggregation stage   dP1 = dV_A V^T,  dS1 = P1 o (dP1 - rowsum(P1 o dP1))
+//                       dA += c1 dS1 K,  dK = c1 dS1^T A,  dV = P1^T dV_A
+//   module terms        dV += DWC^T(dO) + k dO (Eq. (6), Appendix C.1); bias component gradients are the
+//                       sums of dS1 / dS2 over the batch and over the axis a component is repeated along,
+//                       or through the bilinear weights (Appendix B); DWC weight and bias gradients
+//   pooling             dQ += Pooling^T(dA) (Sec. 4.2), or dA is returned when the agents were given
+//
+// Every reduction runs in a fixed order (no atomics): results are bitwise repeatable.
+#include "kernels.h"
+
+namespace aa {
+
+namespace {
+
+constexpr int kTile = 64;      // C tile of the matrix-product kernel
+constexpr int kTileK = 16;
+
+// ---------------------------------------------------------------------------
+// element type -> fp32 copy, and fp32 -> element type (round to nearest even)
+// ---------------------------------------------------------------------------
+template <class E>
+__global__ __launch_bounds__(256) void to_f32_kernel(const typename E::T* __restrict__ src, float* __restrict__ dst,
+                                                     size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < count) dst[i] = E::to_f32(src[i]);
+}
+template <class E>
+__global__ __launch_bounds__(256) void from_f32_kernel(const float* __restrict__ src, typename E::T* __restrict__ dst,
+                                                       size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < count) dst[i] = E::from_f32(src[i]);
+}
+
+// ---------------------------------------------------------------------------
+// Batched C[u] = alpha * op(A[u]) op(B[u]) (+ C[u] when ACC), all fp32 row-major.
+//   op(A) is M x Kd: A stored [M][Kd] (TA = false) or [Kd][M] (TA = true)
+//   op(B) is Kd x Nc: B stored [Kd][Nc] (TB = false) or [Nc][Kd] (TB = true)
+// grid = (ceil(Nc/64), ceil(M/64), units), 256 threads, thread = 4 x 4 outputs, LDS tiles 64 x 16.
+// ---------------------------------------------------------------------------
+template <bool TA, bool TB, bool ACC>
+__global__ __launch_bounds__(256) void matmul_kernel(const float* __restrict__ A, const float* __restrict__ B,
+                                                     float* __restrict__ C, int M, int Nc, int Kd, size_t strideA,
+                                                     size_t strideB, size_t strideC, float alpha) {
+  __shared__ float As[kTileK][kTile + 1];
+  __shared__ float Bs[kTileK][kTile + 1];
+  const int u = blockIdx.z, tid = threadIdx.x;
+  const int row0 = blockIdx.y * kTile, col0 = blockIdx.x * kTile;
+  const float* Au = A + (size_t)u * strideA;
+  const float* Bu = B + (size_t)u * strideB;
+  float* Cu = C + (size_t)u * strideC;
+  const int tr = tid / 16, tc = tid % 16;      // thread's 4 x 4 block: rows 4*tr.., cols 4*tc..
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < Kd; k0 += kTileK) {
+    for (int e = tid; e < kTile * kTileK; e += 256) {
+      int m, k;
+      if (TA) { m = e % kTile; k = e / kTile; } else { k = e % kTileK; m = e / kTileK; }
+      const int gm = row0 + m, gk = k0 + k;
+      float v = 0.0f;
+      if (gm < M && gk < Kd) v = TA ? Au[(size_t)gk * M + gm] : Au[(size_t)gm * Kd + gk];
+      As[k][m] = v;
+    }
+    for (int e = tid; e < kTile * kTileK; e += 256) {
+      int c, k;
+      if (TB) { k = e % kTileK; c = e / kTileK; } else { c = e % kTile; k = e / kTile; }
+      const int gc = col0 + c, gk = k0 + k;
+      float v = 0.0f;
+      if (gc < Nc && gk < Kd) v = TB ? Bu[(size_t)gc * Kd + gk] : Bu[(size_t)gk * Nc + gc];
+      Bs[k][c] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kTileK; ++k) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = As[k][4 * tr + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = Bs[k][4 * tc + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int gm = row0 + 4 * tr + i;
+    if (gm >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int gc = col0 + 4 * tc + j;
+      if (gc >= Nc) continue;
+      float* out = Cu + (size_t)gm * Nc + gc;
+      *out = ACC ? *out + alpha * acc[i][j] : alpha * acc[i][j];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Row softmax in place with the agent bias added first.  One wave per row.
+//   KIND 1: rows = agents, columns = tokens (S1, bias B1);  KIND 2: rows = tokens, columns = agents (S2, B2).
+// grid = (rows, units), 64 threads.
+// ---------------------------------------------------------------------------
+template <int KIND>
+__global__ __launch_bounds__(64) void softmax_rows_kernel(float* __restrict__ S, int rows, int cols, BiasArgs b,
+                                                          int heads, int n, int gh, int gw) {
+  const int r = blockIdx.x, u = blockIdx.y, lane = threadIdx.x;
+  float* row = S + ((size_t)u * rows + r) * cols;
+  if (b.any()) {
+    const int hd = u % heads;
+    BiasArgs hb = b;
+    if (KIND == 1) {
+      if (hb.col) hb.col += (size_t)hd * n * gw;
+      if (hb.row) hb.row += (size_t)hd * n * gh;
+      if (hb.blk) hb.blk += (size_t)hd * n * hb.h0 * hb.w0;
+      for (int j = lane; j < cols; j += 64) row[j] += bias1_at(hb, r, j / gw, j % gw, gh, gw);
+    } else {
+      if (hb.col) hb.col += (size_t)hd * gw * n;
+      if (hb.row) hb.row += (size_t)hd * gh * n;
+      if (hb.blk) hb.blk += (size_t)hd * hb.h0 * hb.w0 * n;
+      for (int j = lane; j < cols; j += 64) row[j] += bias2_at(hb, j, r / gw, r % gw, gh, gw, n);
+    }
+  }
+  float mx = -INFINITY;
+  for (int j = lane; j < cols; j += 64) mx = fmaxf(mx, row[j]);
+  mx = wave_max(mx);
+  float sum = 0.0f;
+  for (int j = lane; j < cols; j += 64) {
+    const float e = __expf(row[j] - mx);
+    row[j] = e;
+    sum += e;
+  }
+  sum = wave_sum(sum);
+  const float inv = 1.0f / sum;
+  for (int j = lane; j < cols; j += 64) row[j] *= inv;
+}
+
+// dS = P o (dP - rowsum(P o dP)), written over dP.  One wave per row; grid = (rows, units).
+__global__ __launch_bounds__(64) void softmax_grad_rows_kernel(const float* __restrict__ P, float* __restrict__ dP,
+                                                               int rows, int cols) {
+  const size_t off = ((size_t)blockIdx.y * rows + blockIdx.x) * cols;
+  const float* p = P + off;
+  float* g = dP + off;
+  const int lane = threadIdx.x;
+  float dot = 0.0f;
+  for (int j = lane; j < cols; j += 64) dot = __builtin_fmaf(p[j], g[j], dot);
+  dot = wave_sum(dot);
+  for (int j = lane; j < cols; j += 64) g[j] = p[j] * (g[j] - dot);
+}
+
+// ---------------------------------------------------------------------------
+// dV += DWC^T(dO) + k dO  (adjoint of the zero-padded 3x3 depthwise cross-correlation):
+//   dV[y,x,c] += sum_{u,v} w[c,u+1,v+1] dO[y-u, x-v, c].   thread = element; grid covers units*N*d.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void value_extras_kernel(float* __restrict__ dV, const float* __restrict__ dO,
+                                                           const float* __restrict__ dwc_w, float vk, int heads, int N,
+                                                           int d, int gh, int gw, size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  const int c = (int)(i % d);
+  const size_t t_all = i / d;
+  const int t = (int)(t_all % N), u = (int)(t_all / N);
+  float v = dV[i] + vk * dO[i];
+  if (dwc_w) {
+    const int y = t / gw, x = t - y * gw;
+    const float* w9 = dwc_w + ((size_t)(u % heads) * d + c) * 9;
+    for (int a = -1; a <= 1; ++a)
+      for (int b = -1; b <= 1; ++b) {
+        const int yy = y - a, xx = x - b;
+        if (yy < 0 || yy >= gh || xx < 0 || xx >= gw) continue;
+        v += w9[(a + 1) * 3 + (b + 1)] * dO[((size_t)u * N + (size_t)yy * gw + xx) * d + c];
+      }
+  }
+  dV[i] = v;
+}
+
+// DWC parameter gradients, summed over the batch in a fixed order.  thread = (head, channel, tap) for
+// the weights (tap 9 = the bias).  grid = ceil(heads*d*10 / 64), 64 threads.
+__global__ __launch_bounds__(64) void dwc_param_grad_kernel(const float* __restrict__ V, const float* __restrict__ dO,
+                                                            float* __restrict__ dw, float* __restrict__ db, int batch,
+                                                            int heads, int N, int d, int gh, int gw) {
+  const int item = blockIdx.x * 64 + threadIdx.x;
+  if (item >= heads * d * 10) return;
+  const int tap = item % 10, c = (item / 10) % d, hd = item / (10 * d);
+  if (tap == 9 && !db) return;
+  const int a = tap / 3 - 1, b = tap % 3 - 1;
+  float acc = 0.0f;
+  for (int bt = 0; bt < batch; ++bt) {
+    const size_t base = ((size_t)bt * heads + hd) * N;
+    for (int y = 0; y < gh; ++y)
+      for (int x = 0; x < gw; ++x) {
+        const float g = dO[(base + (size_t)y * gw + x) * d + c];
+        if (tap == 9) {
+          acc += g;
+        } else {
+          const int yy = y + a, xx = x + b;
+          if (yy < 0 || yy >= gh || xx < 0 || xx >= gw) continue;
+          acc += g * V[(base + (size_t)yy * gw + xx) * d + c];
+        }
+      }
+  }
+  if (tap == 9)
+    db[(size_t)hd * d + c] = acc;
+  else
+    dw[((size_t)hd * d + c) * 9 + tap] = acc;
+}
+
+// ---------------------------------------------------------------------------
+// Bias component gradients (Appendix B), from the dense dS of every unit of a head.
+//   KIND 1: dS1 [units][n][N];  col [H][n][w], row [H][n][h], blk [H][n][h0][w0]
+//   KIND 2: dS2 [units][N][n];  col [H][w][n], row [H][h][n], blk [H][h0][w0][n]
+// thread = one output element; which = 0 col, 1 row, 2 blk.  Sums run over the batch and over the
+// repeated axis (col: y, row: x) or over all tokens with their bilinear weights (blk), in index order.
+// ---------------------------------------------------------------------------
+template <int KIND>
+__device__ __forceinline__ float ds_at(const float* dS, int u, int a, int t, int n, int N) {
+  return KIND == 1 ? dS[((size_t)u * n + a) * N + t] : dS[((size_t)u * N + t) * n + a];
+}
+
+template <int KIND>
+__global__ __launch_bounds__(64) void bias_grad_kernel(const float* __restrict__ dS, float* __restrict__ out, int which,
+                                                       int batch, int heads, int n, int gh, int gw, int h0, int w0) {
+  const int N = gh * gw;
+  const int per_head = which == 0 ? n * gw : (which == 1 ? n * gh : n * h0 * w0);
+  const int item = blockIdx.x * 64 + threadIdx.x;
+  if (item >= heads * per_head) return;
+  const int hd = item / per_head, e = item % per_head;
+  int a, p, q = 0;      // agent, first and second coordinate of the component
+  if (which == 0) {
+    if (KIND == 1) { a = e / gw; p = e % gw; } else { p = e / n; a = e % n; }
+  } else if (which == 1) {
+    if (KIND == 1) { a = e / gh; p = e % gh; } else { p = e / n; a = e % n; }
+  } else {
+    if (KIND == 1) { a = e / (h0 * w0); p = (e / w0) % h0; q = e % w0; } else { a = e % n; p = e / (w0 * n); q = (e / n) % w0; }
+  }
+  float acc = 0.0f;
+  for (int bt = 0; bt < batch; ++bt) {
+    const int u = bt * heads + hd;
+    if (which == 0) {
+      for (int y = 0; y < gh; ++y) acc += ds_at<KIND>(dS, u, a, y * gw + p, n, N);
+    } else if (which == 1) {
+      for (int x = 0; x < gw; ++x) acc += ds_at<KIND>(dS, u, a, p * gw + x, n, N);
+    } else {
+      for (int y = 0; y < gh; ++y) {
+        int y0, y1;
+        float fy;
+        bilinear_coord(y, gh, h0, y0, y1, fy);
+        const float wy = (y0 == p ? 1.0f - fy : 0.0f) + (y1 == p ? fy : 0.0f);
+        if (wy == 0.0f) continue;
+        for (int x = 0; x < gw; ++x) {
+          int x0, x1;
+          float fx;
+          bilinear_coord(x, gw, w0, x0, x1, fx);
+          const float wx = (x0 == q ? 1.0f - fx : 0.0f) + (x1 == q ? fx : 0.0f);
+          if (wx != 0.0f) acc += wy * wx * ds_at<KIND>(dS, u, a, y * gw + x, n, N);
+        }
+      }
+    }
+  }
+  out[item] = acc;
+}
+
+// ---------------------------------------------------------------------------
+// dQ += Pooling^T(dA): token (y, x) gathers dA[a] / |window(a)| from every agent whose window holds
+// it (adaptive windows may overlap by one row / column).  thread = element of dQ.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pool_grad_kernel(float* __restrict__ dQ, const float* __restrict__ dA, int N,
+                                                        int n, int d, int gh, int gw, int ah, int aw, size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  const int c = (int)(i % d);
+  const size_t t_all = i / d;
+  const int t = (int)(t_all % N), u = (int)(t_all / N);
+  const int y = t / gw, x = t - y * gw;
+  const int ayc = (int)(((unsigned)y * (unsigned)ah) / (unsigned)gh), axc = (int)(((unsigned)x * (unsigned)aw) / (unsigned)gw);
+  float v = dQ[i];
+  for (int ay = max(0, ayc - 1); ay <= min(ah - 1, ayc + 1); ++ay) {
+    const int y0 = pool_win_lo(ay, gh, ah), y1 = pool_win_hi(ay, gh, ah);
+    if (y < y0 || y >= y1) continue;
+    for (int ax = max(0, axc - 1); ax <= min(aw - 1, axc + 1); ++ax) {
+      const int x0 = pool_win_lo(ax, gw, aw), x1 = pool_win_hi(ax, gw, aw);
+      if (x < x0 || x >= x1) continue;
+      v += dA[((size_t)u * n + (size_t)ay * aw + ax) * d + c] / (float)((y1 - y0) * (x1 - x0));
+    }
+  }
+  dQ[i] = v;
+}
+
+template <bool TA, bool TB, bool ACC>
+hipError_t matmul(const float* A, const float* B, float* C, int M, int Nc, int Kd, int units, float alpha,
+                  hipStream_t st) {
+  const dim3 grid((Nc + kTile - 1) / kTile, (M + kTile - 1) / kTile, units);
+  matmul_kernel<TA, TB, ACC><<<grid, dim3(256), 0, st>>>(A, B, C, M, Nc, Kd, (size_t)M * Kd, (size_t)Kd * Nc,
+                                                         (size_t)M * Nc, alpha);
+  return hipGetLastError();
+}
+
+#define AA_BWD_CHECK(expr)             \
+  do {                                 \
+    const hipError_t e_ = (expr);      \
+    if (e_ != hipSuccess) return e_;   \
+  } while (0)
+
+hipError_t to_f32(int dtype, const void* src, float* dst, size_t count, hipStream_t st) {
+  const dim3 grid((unsigned)((count + 255) / 256));
+  switch (dtype) {
+    case 0: to_f32_kernel<ElemF32><<<grid, dim3(256), 0, st>>>((const float*)src, dst, count); break;
+    case 1: to_f32_kernel<ElemF16><<<grid, dim3(256), 0, st>>>((const _Float16*)src, dst, count); break;
+    case 2: to_f32_kernel<ElemBF16><<<grid, dim3(256), 0, st>>>((const uint16_t*)src, dst, count); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+hipError_t from_f32(int dtype, const float* src, void* dst, size_t count, hipStream_t st) {
+  const dim3 grid((unsigned)((count + 255) / 256));
+  switch (dtype) {
+    case 0: from_f32_kernel<ElemF32><<<grid, dim3(256), 0, st>>>(src, (float*)dst, count); break;
+    case 1: from_f32_kernel<ElemF16><<<grid, dim3(256), 0, st>>>(src, (_Float16*)dst, count); break;
+    case 2: from_f32_kernel<ElemBF16><<<grid, dim3(256), 0, st>>>(src, (uint16_t*)dst, count); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t backward_workspace_floats(const Problem& p) {
+  const size_t u = (size_t)p.units, Nd = (size_t)p.N * p.d, nd = (size_t)p.n * p.d, nN = (size_t)p.n * p.N;
+  // Q, K, V, dO, dQ, dK, dV (7 x N*d), A, V_A, dV_A, dA (4 x n*d), P1, dS1, P2, dS2 (4 x n*N)
+  return u * (7 * Nd + 4 * nd + 4 * nN);
+}
+
+hipError_t launch_backward(const Problem& p, const void* Q, const void* K, const void* V, const void* A_elem,
+                           const void* dO, float* ws, void* dQ, void* dK, void* dV, void* dA, bool agents_given,
+                           const BackwardParamGrads& pg, hipStream_t st) {
+  const size_t u = (size_t)p.units, Nd = (size_t)p.N * p.d, nd = (size_t)p.n * p.d, nN = (size_t)p.n * p.N;
+  float* Qf = ws;
+  float* Kf = Qf + u * Nd;
+  float* Vf = Kf + u * Nd;
+  float* dOf = Vf + u * Nd;
+  float* dQf = dOf + u * Nd;
+  float* dKf = dQf + u * Nd;
+  float* dVf = dKf + u * Nd;
+  float* Af = dVf + u * Nd;
+  float* VAf = Af + u * nd;
+  float* dVAf = VAf + u * nd;
+  float* dAf = dVAf + u * nd;
+  float* P1 = dAf + u * nd;
+  float* T1 = P1 + u * nN;
+  float* P2 = T1 + u * nN;
+  float* T2 = P2 + u * nN;
+  const int N = p.N, n = p.n, d = p.d, U = p.units;
+
+  AA_BWD_CHECK(to_f32(p.dtype, Q, Qf, u * Nd, st));
+  AA_BWD_CHECK(to_f32(p.dtype, K, Kf, u * Nd, st));
+  AA_BWD_CHECK(to_f32(p.dtype, V, Vf, u * Nd, st));
+  AA_BWD_CHECK(to_f32(p.dtype, dO, dOf, u * Nd, st));
+  AA_BWD_CHECK(to_f32(p.dtype, A_elem, Af, u * nd, st));
+
+  // forward recompute
+  AA_BWD_CHECK((matmul<false, true, false>(Af, Kf, P1, n, N, d, U, p.scale1, st)));
+  softmax_rows_kernel<1><<<dim3(n, U), dim3(64), 0, st>>>(P1, n, N, p.b1, p.heads, n, p.gh, p.gw);
+  AA_BWD_CHECK((matmul<false, false, false>(P1, Vf, VAf, n, d, N, U, 1.0f, st)));
+  AA_BWD_CHECK((matmul<false, true, false>(Qf, Af, P2, N, n, d, U, p.scale2, st)));
+  softmax_rows_kernel<2><<<dim3(N, U), dim3(64), 0, st>>>(P2, N, n, p.b2, p.heads, n, p.gh, p.gw);
+
+  // broadcast stage
+  AA_BWD_CHECK((matmul<true, false, false>(P2, dOf, dVAf, n, d, N, U, 1.0f, st)));
+  AA_BWD_CHECK((matmul<false, true, false>(dOf, VAf, T2, N, n, d, U, 1.0f, st)));
+  softmax_grad_rows_kernel<<<dim3(N, U), dim3(64), 0, st>>>(P2, T2, N, n);
+  AA_BWD_CHECK((matmul<false, false, false>(T2, Af, dQf, N, d, n, U, p.scale2, st)));
+  AA_BWD_CHECK((matmul<true, false, false>(T2, Qf, dAf, n, d, N, U, p.scale2, st)));
+
+  // aggregation stage
+  AA_BWD_CHECK((matmul<false, true, false>(dVAf, Vf, T1, n, N, d, U, 1.0f, st)));
+  softmax_grad_rows_kernel<<<dim3(n, U), dim3(64), 0, st>>>(P1, T1, n, N);
+  AA_BWD_CHECK((matmul<false, false, true>(T1, Kf, dAf, n, d, N, U, p.scale1, st)));
+  AA_BWD_CHECK((matmul<true, false, false>(T1, Af, dKf, N, d, n, U, p.scale1, st)));
+  AA_BWD_CHECK((matmul<true, false, false>(P1, dVAf, dVf, N, d, n, U, 1.0f, st)));
+
+  // module terms
+  if (p.dwc_w || p.vk != 0.0f) {
+    const size_t count = u * Nd;
+    value_extras_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(dVf, dOf, p.dwc_w, p.vk, p.heads, N,
+                                                                                    d, p.gh, p.gw, count);
+  }
+  if (p.dwc_w && pg.ddwc_w) {
+    const int items = p.heads * d * 10;
+    dwc_param_grad_kernel<<<dim3((items + 63) / 64), dim3(64), 0, st>>>(Vf, dOf, pg.ddwc_w, pg.ddwc_b, U / p.heads,
+                                                                        p.heads, N, d, p.gh, p.gw);
+  }
+  const int batch = U / p.heads;
+  auto bias_grad = [&](int kind, const float* dS, float* out, int which, int h0, int w0) {
+    if (!out) return;
+    const int per_head = which == 0 ? n * p.gw : (which == 1 ? n * p.gh : n * h0 * w0);
+    const dim3 grid((p.heads * per_head + 63) / 64);
+    if (kind == 1)
+      bias_grad_kernel<1><<<grid, dim3(64), 0, st>>>(dS, out, which, batch, p.heads, n, p.gh, p.gw, h0, w0);
+    else
+      bias_grad_kernel<2><<<grid, dim3(64), 0, st>>>(dS, out, which, batch, p.heads, n, p.gh, p.gw, h0, w0);
+  };
+  bias_grad(1, T1, pg.db1_col, 0, pg.h0, pg.w0);
+  bias_grad(1, T1, pg.db1_row, 1, pg.h0, pg.w0);
+  bias_grad(1, T1, pg.db1_blk, 2, pg.h0, pg.w0);
+  bias_grad(2, T2, pg.db2_col, 0, pg.h0, pg.w0);
+  bias_grad(2, T2, pg.db2_row, 1, pg.h0, pg.w0);
+  bias_grad(2, T2, pg.db2_blk, 2, pg.h0, pg.w0);
+
+  // pooling, rounding to the element type
+  if (agents_given) {
+    AA_BWD_CHECK(from_f32(p.dtype, dAf, dA, u * nd, st));
+  } else {
+    const size_t count = u * Nd;
+    pool_grad_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(dQf, dAf, N, n, d, p.gh, p.gw, p.ah,
+                                                                                 p.aw, count);
+  }
+  AA_BWD_CHECK(from_f32(p.dtype, dQf, dQ, u * Nd, st));
+  AA_BWD_CHECK(from_f32(p.dtype, dKf, dK, u * Nd, st));
+  AA_BWD_CHECK(from_f32(p.dtype, dVf, dV, u * Nd, st));
+  return hipGetLastError();
+}
+
+}  // namespace aa

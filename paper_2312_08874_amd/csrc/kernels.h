@@ -41,6 +41,20 @@ hipError_t launch_broadcast_generic(const Problem& p, const void* Q, const void*
 // dynamic LDS the generic broadcast needs for this problem (bytes)
 size_t broadcast_generic_lds_bytes(int n, int d);
 
+// --- backward pass: reference-quality kernels (fp32 VALU, attention matrices materialised in the
+//     workspace), any shape and element type ---
+struct BackwardParamGrads {      // fp32 device outputs, any may be null; layouts as the parameters
+  float *db1_col, *db1_row, *db1_blk, *db2_col, *db2_row, *db2_blk, *ddwc_w, *ddwc_b;
+  int h0, w0;
+};
+// fp32 scratch the backward needs, in floats
+size_t backward_workspace_floats(const Problem& p);
+// A_elem: the agents in the element type (pooled by the forward's pooling kernel, or as given).
+// dA is written only when agents_given.
+hipError_t launch_backward(const Problem& p, const void* Q, const void* K, const void* V, const void* A_elem,
+                           const void* dO, float* ws, void* dQ, void* dK, void* dV, void* dA, bool agents_given,
+                           const BackwardParamGrads& pg, hipStream_t st);
+
 // --- small-agent regime (n <= 64, d in {32, 64}, fp16 / bf16): MFMA kernels that keep A and V_A in
 //     registers and stream tokens straight from global memory ---
 bool small_supported(const Problem& p);

@@ -1,0 +1,152 @@
+"""GPU parity of the backward pass (agent_attn_bwd through the C ABI) against the fp64 oracle's
+gradients on the same seeded inputs.
+
+Bar, per gradient tensor g with reference r: fp32 path max-abs <= 1e-4 * max(1, max|r|); fp16 / bf16
+paths (outputs rounded once to the 16-bit type) max-abs <= 1e-2 * max(1, max|r|) and relative
+L2 <= 5e-3; fp32 parameter gradients relative L2 <= 1e-4 (fp32 inputs) or 2e-3 (16-bit inputs).
+
+With pooled agents the GPU rounds A to the element type as its forward does, and differentiates
+through that rounding as if it were the identity.  For the 16-bit types the reference is therefore
+assembled from oracle pieces fed with the GPU's pooled A: the gradient for given agents, plus the
+pooling gradient of dA.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2312_08874_amd import inputs
+from tests import util
+
+pytestmark = pytest.mark.gpu
+WL = inputs.WORKLOADS
+
+
+@pytest.fixture(scope="module")
+def aa():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2312_08874_amd import binding
+    binding.lib()
+    return binding
+
+
+def _stored(t, dtype, shape):
+    import torch
+    a = t.reshape(shape).cpu()
+    if dtype == "bf16":
+        return a.view(torch.int16).numpy().view(np.uint16)
+    return a.numpy()
+
+
+def _check(got, ref, dtype, what):
+    scale = max(1.0, float(np.abs(ref).max()))
+    util.assert_parity(util.to_host64(got).reshape(ref.shape), ref, dtype, what,
+                       max_abs=util.TOL[dtype]["max_abs"] * scale)
+
+
+def _check_param(got, ref, dtype, what):
+    _, rel = util.errors(util.to_host64(got).reshape(ref.shape), ref)
+    assert rel <= (1e-4 if dtype == "f32" else 2e-3), "%s: rel_l2 %.3e" % (what, rel)
+
+
+def _run_case(aa, oracle, wl, *, given=False, module=False, blk=(3, 2), kw=None):
+    kw = kw or {}
+    t = inputs.make_qkv(wl)
+    dO = inputs.make_tensor((wl.units, wl.N, wl.d), stream=wl.index * 16 + 12, dtype=wl.dtype)
+    shape = (wl.batch, wl.heads, wl.N, wl.d)
+    dv = {k: util.to_device(v, wl.dtype, shape) for k, v in t.items()}
+    dOd = util.to_device(dO, wl.dtype, shape)
+    params = inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, blk=blk, index=wl.index) if module else None
+    pd = util.params_to_device(params) if module else None
+    A_st = None
+    if given:
+        A_st = inputs.make_tensor((wl.units, wl.n, wl.d), stream=wl.index * 16 + 11, dtype=wl.dtype)
+        Ad = util.to_device(A_st, wl.dtype, (wl.batch, wl.heads, wl.n, wl.d))
+        got = aa.agent_attn_bwd(dv["Q"], dv["K"], dv["V"], dOd, Ad, grid=wl.grid if module else None, params=pd, **kw)
+    else:
+        got = aa.agent_attn_bwd(dv["Q"], dv["K"], dv["V"], dOd, grid=wl.grid, agent_grid=wl.agent_grid, params=pd, **kw)
+
+    f64 = {k: inputs.to_float64(v, wl.dtype) for k, v in t.items()}
+    B1 = B2 = None
+    okw = dict(heads=wl.heads, grid=wl.grid, scale1=kw.get("scale1") or None, scale2=kw.get("scale2") or None,
+               v_residual_k=kw.get("v_residual_k", 0.0))
+    if module:
+        B1, B2 = util.dense_biases(oracle, params, wl.heads, wl.n, wl.grid)
+        okw.update(B1=B1, B2=B2, dwc_w=params["dwc_w"], dwc_b=params["dwc_b"])
+    g64 = inputs.to_float64(dO, wl.dtype)
+    if given:
+        ref = oracle.agent_attn_bwd(f64["Q"], f64["K"], f64["V"], g64, A=inputs.to_float64(A_st, wl.dtype), **okw)
+    elif wl.dtype == "f32":
+        ref = oracle.agent_attn_bwd(f64["Q"], f64["K"], f64["V"], g64, agent_grid=wl.agent_grid, **okw)
+    else:
+        A_gpu = aa.agent_pool_fwd(dv["Q"], grid=wl.grid, agent_grid=wl.agent_grid)
+        A64 = inputs.to_float64(_stored(A_gpu, wl.dtype, (wl.units, wl.n, wl.d)), wl.dtype)
+        ref = oracle.agent_attn_bwd(f64["Q"], f64["K"], f64["V"], g64, A=A64, agent_grid=wl.agent_grid, **okw)
+        ref["dQ"] = ref["dQ"] + oracle.pool_bwd(ref.pop("dA"), *wl.grid, *wl.agent_grid)
+    for k in ("dQ", "dK", "dV") + (("dA",) if given else ()):
+        _check(got[k], ref[k], wl.dtype, "%s %s" % (wl.name, k))
+    if module:
+        h0, w0 = blk
+        gh, gw = wl.grid
+        for hd in range(wl.heads):
+            c1, r1, b1 = oracle.bias1_components_bwd(ref["dB1"][hd], gh, gw, h0, w0)
+            c2, r2, b2 = oracle.bias2_components_bwd(ref["dB2"][hd], gh, gw, h0, w0)
+            for key, r in (("db1_col", c1), ("db1_row", r1), ("db1_blk", b1), ("db2_col", c2), ("db2_row", r2),
+                           ("db2_blk", b2)):
+                _check_param(got[key][hd], r, wl.dtype, "%s %s head %d" % (wl.name, key, hd))
+        _check_param(got["ddwc_w"], ref["ddwc_w"], wl.dtype, wl.name + " ddwc_w")
+        _check_param(got["ddwc_b"], ref["ddwc_b"], wl.dtype, wl.name + " ddwc_b")
+    return got
+
+
+def _wl(name, dtype, grid, agrid, d, batch=2, heads=2, index=13):
+    return dataclasses.replace(WL["tiny"], name=name, batch=batch, heads=heads, grid=grid, agent_grid=agrid, d=d,
+                               dtype=dtype, index=index)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("grid,agrid,d", [((14, 14), (7, 7), 32), ((13, 11), (4, 3), 24), ((1, 1), (1, 1), 8),
+                                          ((9, 70), (3, 9), 72), ((20, 20), (5, 5), 64)])
+def test_backward_pure_pooled(aa, oracle, grid, agrid, d, dtype):
+    _run_case(aa, oracle, _wl("pure", dtype, grid, agrid, d))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_given_agents(aa, oracle, dtype):
+    wl = _wl("given", dtype, (10, 13), (1, 20), 40)
+    _run_case(aa, oracle, wl, given=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("grid,agrid,d", [((12, 10), (3, 5), 32), ((7, 9), (3, 3), 16)])
+def test_backward_module_mode(aa, oracle, grid, agrid, d, dtype):
+    _run_case(aa, oracle, _wl("module", dtype, grid, agrid, d), module=True)
+
+
+def test_backward_module_given_agents_and_residual(aa, oracle):
+    wl = _wl("module-given", "f32", (8, 8), (2, 8), 24)
+    _run_case(aa, oracle, wl, given=True, module=True, kw=dict(v_residual_k=0.075, scale2=24 ** -0.15))
+
+
+def test_backward_deit_shape(aa, oracle):
+    """The DeiT-T shape of the benchmark, two batch elements."""
+    wl = dataclasses.replace(WL["deit_t"], batch=2)
+    _run_case(aa, oracle, wl)
+
+
+def test_backward_is_deterministic_and_ignores_workspace(aa):
+    import torch
+    wl = _wl("det", "bf16", (12, 12), (4, 4), 32)
+    t = inputs.make_qkv(wl)
+    shape = (wl.batch, wl.heads, wl.N, wl.d)
+    dv = {k: util.to_device(v, wl.dtype, shape) for k, v in t.items()}
+    dO = util.to_device(inputs.make_tensor((wl.units, wl.N, wl.d), stream=300, dtype=wl.dtype), wl.dtype, shape)
+    a = aa.agent_attn_bwd(dv["Q"], dv["K"], dv["V"], dO, grid=wl.grid, agent_grid=wl.agent_grid)
+    desc = aa.make_desc(wl.batch, wl.heads, wl.N, wl.n, wl.d, 2, wl.grid, wl.agent_grid)
+    import ctypes
+    need = int(aa.lib().agent_attn_bwd_workspace_bytes(ctypes.byref(desc), None))
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda")
+    b = aa.agent_attn_bwd(dv["Q"], dv["K"], dv["V"], dO, grid=wl.grid, agent_grid=wl.agent_grid, workspace=ws)
+    for k in ("dQ", "dK", "dV"):
+        assert torch.equal(a[k], b[k])
