@@ -19,6 +19,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, GB/s
 MFMA_PEAK_TFLOPS = 2500.0      # dense bf16 / fp16 MFMA, TFLOP/s
+VALU_F32_PEAK_TFLOPS = 157.3   # fp32 vector arithmetic, published figure, TFLOP/s
 ELEM = {"f32": 4, "f16": 2, "bf16": 2}
 
 
@@ -29,6 +30,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="deit_t")
     ap.add_argument("--mode", default="pure", choices=["pure", "module"])
+    ap.add_argument("--backward", action="store_true",
+                    help="also time agent_attn_bwd on the workload and add a \"backward\" object to the line")
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="total footprint of the rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short summary of the other workloads")
@@ -218,6 +221,32 @@ def measure(wl, binding, args, steps, warmup, module):
     return res, ring
 
 
+def measure_backward(wl, binding, ring, steps, warmup):
+    """agent_attn_bwd on the first input set (same buffers every call: the dense attention matrices in its
+    workspace dwarf the inputs, so a cold ring would add nothing).  Its ten matrix products run as fp32
+    vector FMAs, hence the ALU roofline: 20*N*n*d FLOPs per unit against the fp32 vector peak."""
+    import torch
+    s = ring.sets[0]
+    dO = torch.randn(s["Q"].shape, device="cuda", dtype=torch.float32).to(s["Q"].dtype)
+    desc = binding.make_desc(wl.batch, wl.heads, wl.N, wl.n, wl.d, {"f32": 0, "f16": 1, "bf16": 2}[wl.dtype],
+                             wl.grid, wl.agent_grid)
+    import ctypes
+    need = int(binding.lib().agent_attn_bwd_workspace_bytes(ctypes.byref(desc), binding._pp(binding.make_params(ring.params))))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+
+    def call(i):
+        binding.agent_attn_bwd(s["Q"], s["K"], s["V"], dO, grid=wl.grid, agent_grid=wl.agent_grid, params=ring.params,
+                               workspace=ws)
+    ms = timed(call, steps, warmup)
+    flops = 20.0 * wl.N * wl.n * wl.d * wl.units
+    tf = flops / (ms * 1e-3) / 1e12
+    return {"ms_per_step": ms, "tokens_per_s": wl.batch * wl.N / (ms * 1e-3), "tflops": tf,
+            "workspace_bytes": need, "cache": "hot (one input set)",
+            "kernels": "reference kernels: 10 batched fp32 matrix products + row softmax / gradient kernels",
+            "roofline": {"kernel": "matmul_kernel", "bound": "alu", "achieved": tf, "peak": VALU_F32_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": tf / VALU_F32_PEAK_TFLOPS, "traffic": None}}
+
+
 def cpu_baseline(wl, ring):
     """The fp64 oracle, as it stands, on the host cores: a bounded sample of the same workload."""
     from oracle import agent_attn_oracle as oracle
@@ -284,6 +313,8 @@ def main():
         "stage_us": res["stage_us"],
         "roofline": res["roofline"],
     }
+    if args.backward:
+        line["backward"] = measure_backward(wl, binding, ring, max(5, args.steps // 15), 3)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, ring)
     del ring

@@ -473,13 +473,14 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
   const size_t big = units * desc->N * desc->d * es, small = units * desc->n * desc->d * es;
   const void* ins[] = {Q, K, V, dO};
   void* outs[] = {dQ, dK, dV};
-  for (void* o : outs) {
+  for (int a = 0; a < 3; ++a) {
+    void* o = outs[a];
     for (const void* i : ins)
       if (overlaps(o, big, i, big)) return AA_ERR_ALIAS;
     if (overlaps(o, big, A, small) || overlaps(o, big, workspace, workspace_bytes) || overlaps(o, big, dA, small))
       return AA_ERR_ALIAS;
-    for (void* o2 : outs)
-      if (o2 != o && overlaps(o, big, o2, big)) return AA_ERR_ALIAS;
+    for (int b = a + 1; b < 3; ++b)
+      if (overlaps(o, big, outs[b], big)) return AA_ERR_ALIAS;
   }
   for (const void* i : ins)
     if (overlaps(workspace, workspace_bytes, i, big) || overlaps(dA, small, i, big)) return AA_ERR_ALIAS;

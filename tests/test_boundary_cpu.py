@@ -126,3 +126,33 @@ def test_binding_has_no_fallback():
     """The binding must not import the oracle or compute anything itself."""
     src = open(os.path.join(ROOT, "paper_2312_08874_amd", "binding.py")).read()
     assert "oracle" not in src.replace("no CPU or eager fallback", "")
+
+
+def test_bwd_rejects_bad_arguments():
+    """agent_attn_bwd validates on the host before anything is launched."""
+    L = binding.lib()
+    G = 1 << 42      # far apart fake addresses: no overlap unless a test makes one
+    desc = make_desc(2, 3, 196, 49, 32, binding.AA_BF16, (14, 14), (7, 7))
+    need = L.agent_attn_bwd_workspace_bytes(ctypes.byref(desc), None)
+    assert need > 0 and need % 256 == 0
+    # about 4*n*N + 7*N*d + 4*n*d floats per unit
+    assert need >= 6 * 4 * (4 * 49 * 196 + 7 * 196 * 32 + 4 * 49 * 32)
+    assert L.agent_attn_bwd_workspace_bytes(ctypes.byref(make_desc(2, 3, 196, 49, 32, 9)), None) == 0
+
+    def call(desc=desc, Q=G, K=2 * G, V=3 * G, A=None, params=None, dO=4 * G, ws=5 * G, ws_bytes=1 << 40, dQ=7 * G,
+             dK=8 * G, dV=9 * G, dA=None, grads=None):
+        return L.agent_attn_bwd(ctypes.byref(desc), Q, K, V, A, None if params is None else ctypes.byref(params), dO,
+                                ws, ws_bytes, dQ, dK, dV, dA, None if grads is None else ctypes.byref(grads), None)
+
+    assert call(dO=None) == -1 and call(dQ=None) == -1 and call(K=None) == -1          # AA_ERR_NULL
+    assert call(dA=10 * G) == -1                      # pooled agents: their gradient goes into dQ
+    assert call(A=10 * G) == -1                       # given agents: dA is required
+    assert call(ws=None) == -5 and call(ws_bytes=need - 1) == -5 and call(ws=5 * G + 8) == -5
+    assert call(dQ=G) == -6 and call(dK=7 * G) == -6 and call(dV=4 * G) == -6           # AA_ERR_ALIAS
+    assert call(desc=make_desc(2, 3, 196, 49, 32, binding.AA_BF16)) == -4               # no grid to pool on
+    g = binding.aa_param_grads()
+    g.db1_col = 11 * G
+    assert call(grads=g) == -1                        # gradient of a parameter that is not there
+    p = aa_params()
+    p.b1_col = 12 * G
+    assert call(params=p, grads=g, ws_bytes=need - 1) == -5     # accepted up to the workspace check
