@@ -497,8 +497,10 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
     if (st != AA_OK) return st;
     agents = ws;
   }
+  const bool use_mfma = (pr.dtype == AA_F16 || pr.dtype == AA_BF16) && pr.d % 8 == 0 && aligned16(Q) && aligned16(K) &&
+                        aligned16(V) && aligned16(dO) && aligned16(agents);
   AA_HIP(aa::launch_backward(pr, Q, K, V, agents, dO, (float*)(ws + bwd_agents_bytes(desc)), dQ, dK, dV, dA, !pooling,
-                             pg, stream));
+                             use_mfma, pg, stream));
   return AA_OK;
 }
 

@@ -157,6 +157,185 @@ __global__ __launch_bounds__(64) void softmax_grad_rows_kernel(const float* __re
   for (int j = lane; j < cols; j += 64) g[j] = p[j] * (g[j] - dot);
 }
 
+// ===========================================================================
+// fp16 / bf16 path: the same chain with the matrix products on the MFMA units.  P and dS are stored in
+// the element type (what the products consume), their rows padded to a multiple of 8 elements.
+// ===========================================================================
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+template <class E>
+struct Half;      // 16-bit storage <-> fp32, and the 16x16x32 MFMA of the type
+template <>
+struct Half<ElemBF16> {
+  static __device__ __forceinline__ float to_f32(uint16_t b) { return ElemBF16::to_f32(b); }
+  static __device__ __forceinline__ uint16_t from_f32(float f) { return ElemBF16::from_f32(f); }
+  static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                   0, 0, 0);
+  }
+};
+template <>
+struct Half<ElemF16> {
+  static __device__ __forceinline__ float to_f32(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+  static __device__ __forceinline__ uint16_t from_f32(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+  static __device__ __forceinline__ f32x4 mma(u32x4 a, u32x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0,
+                                                  0, 0);
+  }
+};
+template <>
+struct Half<ElemF32> {      // never instantiated for real work; lets the fp32 path share the templates
+  static __device__ __forceinline__ float to_f32(uint16_t) { return 0.0f; }
+  static __device__ __forceinline__ uint16_t from_f32(float) { return 0; }
+};
+
+// ---------------------------------------------------------------------------
+// Batched C[u] = alpha * op(A[u]) op(B[u]) with 16-bit operands and fp32 accumulation on MFMA.
+//   op(A) M x Kd: stored [M][lda] (TA = false) or [Kd][lda] (TA = true);
+//   op(B) Kd x Nc: stored [Kd][ldb] (TB = false) or [Nc][ldb] (TB = true);  lda, ldb multiples of 8,
+//   base pointers 16-byte aligned (16-byte loads; elements beyond M / Nc / Kd are masked to zero).
+//   OUT 0: C fp32 = result; 1: C fp32 += result; 2: C element type = round(result).  ldc in elements.
+// grid = (ceil(Nc/64), ceil(M/64), units); 4 waves, wave = 32 x 32 outputs (2 x 2 MFMA tiles); LDS tiles
+// hold 64 rows (columns) x 32 k-values with the k-values contiguous, as the MFMA operands want them.
+// ---------------------------------------------------------------------------
+constexpr int kLdsK = 40;      // 32 k-values + 8 of padding per LDS row
+template <class E, bool TRANS>
+__device__ __forceinline__ void mfma_stage_tile(const uint16_t* __restrict__ src, int ld, int rows_valid, int k_valid,
+                                                int r0, int k0, uint16_t (*tile)[kLdsK], int tid) {
+  // tile[r][k] = op(X)[r0 + r][k0 + k] for r < 64, k < 32 (zero outside the matrix)
+  if constexpr (!TRANS) {      // stored [row][k]: one 16-byte chunk of 8 k-values per thread
+    const int r = tid >> 2, kc = (tid & 3) * 8;
+    u32x4 v = {0, 0, 0, 0};
+    const int gr = r0 + r, gk = k0 + kc;
+    if (gr < rows_valid && gk < k_valid) {
+      v = *(const u32x4*)(src + (size_t)gr * ld + gk);
+      if (gk + 8 > k_valid) {      // ragged end of the k range: clear the elements beyond it
+        uint16_t* e = (uint16_t*)&v;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (gk + j >= k_valid) e[j] = 0;
+      }
+    }
+    *(u32x4*)&tile[r][kc] = v;
+  } else {                     // stored [k][row]: a chunk holds 8 rows of one k; scatter it
+    const int k = tid >> 3, rc = (tid & 7) * 8;
+    u32x4 v = {0, 0, 0, 0};
+    const int gk = k0 + k, gr = r0 + rc;
+    if (gk < k_valid && gr < rows_valid) v = *(const u32x4*)(src + (size_t)gk * ld + gr);
+    const uint16_t* e = (const uint16_t*)&v;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) tile[rc + j][k] = (gr + j < rows_valid) ? e[j] : (uint16_t)0;
+  }
+}
+
+template <class E, bool TA, bool TB, int OUT>
+__global__ __launch_bounds__(256) void mfma_matmul_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
+                                                          void* __restrict__ C, int M, int Nc, int Kd, int lda, int ldb,
+                                                          int ldc, size_t strideA, size_t strideB, size_t strideC,
+                                                          float alpha) {
+  __shared__ __attribute__((aligned(16))) uint16_t As[64][kLdsK];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[64][kLdsK];
+  const int u = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row0 = blockIdx.y * 64, col0 = blockIdx.x * 64;
+  const uint16_t* Au = A + (size_t)u * strideA;
+  const uint16_t* Bu = B + (size_t)u * strideB;
+  const int wm = wave >> 1, wn = wave & 1, r = lane & 15, g = lane >> 4;
+  f32x4 acc[2][2] = {};
+  for (int k0 = 0; k0 < Kd; k0 += 32) {
+    mfma_stage_tile<E, TA>(Au, lda, M, Kd, row0, k0, As, tid);
+    mfma_stage_tile<E, !TB>(Bu, ldb, Nc, Kd, col0, k0, Bs, tid);
+    __syncthreads();
+    u32x4 a[2], b[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) a[i] = *(const u32x4*)&As[32 * wm + 16 * i + r][8 * g];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) b[j] = *(const u32x4*)&Bs[32 * wn + 16 * j + r][8 * g];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = Half<E>::mma(a[i], b[j], acc[i][j]);
+    __syncthreads();
+  }
+  // C layout of a tile: lane holds column r, rows 4g .. 4g+3
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int gc = col0 + 32 * wn + 16 * j + r;
+      if (gc >= Nc) continue;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int gm = row0 + 32 * wm + 16 * i + 4 * g + e;
+        if (gm >= M) continue;
+        const size_t o = (size_t)u * strideC + (size_t)gm * ldc + gc;
+        const float v = alpha * acc[i][j][e];
+        if constexpr (OUT == 0) ((float*)C)[o] = v;
+        if constexpr (OUT == 1) ((float*)C)[o] += v;
+        if constexpr (OUT == 2) ((uint16_t*)C)[o] = Half<E>::from_f32(v);
+      }
+    }
+}
+
+// Row softmax of the fp32 scores S (rows of length ld), bias added first, result rounded to the element
+// type into P (same ld); the padding columns [cols, ld) of P are zeroed.  One wave per row.
+template <class E, int KIND>
+__global__ __launch_bounds__(64) void softmax_rows16_kernel(const float* __restrict__ S, uint16_t* __restrict__ P,
+                                                            int rows, int cols, int ld, BiasArgs b, int heads, int n,
+                                                            int gh, int gw) {
+  const int r = blockIdx.x, u = blockIdx.y, lane = threadIdx.x;
+  const float* row = S + ((size_t)u * rows + r) * ld;
+  uint16_t* prow = P + ((size_t)u * rows + r) * ld;
+  BiasArgs hb = b;
+  const bool biased = b.any();
+  if (biased) {
+    const int hd = u % heads;
+    if (KIND == 1) {
+      if (hb.col) hb.col += (size_t)hd * n * gw;
+      if (hb.row) hb.row += (size_t)hd * n * gh;
+      if (hb.blk) hb.blk += (size_t)hd * n * hb.h0 * hb.w0;
+    } else {
+      if (hb.col) hb.col += (size_t)hd * gw * n;
+      if (hb.row) hb.row += (size_t)hd * gh * n;
+      if (hb.blk) hb.blk += (size_t)hd * hb.h0 * hb.w0 * n;
+    }
+  }
+  auto score = [&](int j) -> float {
+    float v = row[j];
+    if (biased) v += KIND == 1 ? bias1_at(hb, r, j / gw, j % gw, gh, gw) : bias2_at(hb, j, r / gw, r % gw, gh, gw, n);
+    return v;
+  };
+  float mx = -INFINITY;
+  for (int j = lane; j < cols; j += 64) mx = fmaxf(mx, score(j));
+  mx = wave_max(mx);
+  float sum = 0.0f;
+  for (int j = lane; j < cols; j += 64) sum += __expf(score(j) - mx);
+  sum = wave_sum(sum);
+  const float inv = 1.0f / sum;
+  for (int j = lane; j < ld; j += 64) prow[j] = j < cols ? Half<E>::from_f32(__expf(score(j) - mx) * inv) : (uint16_t)0;
+}
+
+// dS = P o (dP - rowsum(P o dP)) with P in the element type, dP fp32, dS rounded to the element type
+// (padding columns zeroed).  With keep_f32 the unrounded dS also replaces dP (the bias-component sums
+// are taken from it).  One wave per row.
+template <class E>
+__global__ __launch_bounds__(64) void softmax_grad_rows16_kernel(const uint16_t* __restrict__ P, float* __restrict__ dP,
+                                                                 uint16_t* __restrict__ dS, int rows, int cols, int ld,
+                                                                 bool keep_f32) {
+  const size_t off = ((size_t)blockIdx.y * rows + blockIdx.x) * ld;
+  const int lane = threadIdx.x;
+  float dot = 0.0f;
+  for (int j = lane; j < cols; j += 64) dot = __builtin_fmaf(Half<E>::to_f32(P[off + j]), dP[off + j], dot);
+  dot = wave_sum(dot);
+  for (int j = lane; j < ld; j += 64) {
+    const float v = j < cols ? Half<E>::to_f32(P[off + j]) * (dP[off + j] - dot) : 0.0f;
+    dS[off + j] = Half<E>::from_f32(v);
+    if (keep_f32 && j < cols) dP[off + j] = v;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // dV += DWC^T(dO) + k dO  (adjoint of the zero-padded 3x3 depthwise cross-correlation):
 //   dV[y,x,c] += sum_{u,v} w[c,u+1,v+1] dO[y-u, x-v, c].   thread = element; grid covers units*N*d.
@@ -221,15 +400,23 @@ __global__ __launch_bounds__(64) void dwc_param_grad_kernel(const float* __restr
 // thread = one output element; which = 0 col, 1 row, 2 blk.  Sums run over the batch and over the
 // repeated axis (col: y, row: x) or over all tokens with their bilinear weights (blk), in index order.
 // ---------------------------------------------------------------------------
-template <int KIND>
-__device__ __forceinline__ float ds_at(const float* dS, int u, int a, int t, int n, int N) {
-  return KIND == 1 ? dS[((size_t)u * n + a) * N + t] : dS[((size_t)u * N + t) * n + a];
+// dS element (u, agent a, token t); ST = float or the 16-bit element storage, ld = padded row length
+template <int KIND, class LD>
+__device__ __forceinline__ float ds_at(const LD& ld, int u, int a, int t, int n, int N) {
+  return KIND == 1 ? ld(((size_t)u * n + a), t) : ld(((size_t)u * N + t), a);
 }
 
-template <int KIND>
-__global__ __launch_bounds__(64) void bias_grad_kernel(const float* __restrict__ dS, float* __restrict__ out, int which,
-                                                       int batch, int heads, int n, int gh, int gw, int h0, int w0) {
+template <int KIND, class E, bool HALF>
+__global__ __launch_bounds__(64) void bias_grad_kernel(const void* __restrict__ dS_raw, int ldS, float* __restrict__ out,
+                                                       int which, int batch, int heads, int n, int gh, int gw, int h0,
+                                                       int w0) {
   const int N = gh * gw;
+  auto dS = [&](size_t row, int col) -> float {
+    if constexpr (HALF)
+      return Half<E>::to_f32(((const uint16_t*)dS_raw)[row * ldS + col]);
+    else
+      return ((const float*)dS_raw)[row * ldS + col];
+  };
   const int per_head = which == 0 ? n * gw : (which == 1 ? n * gh : n * h0 * w0);
   const int item = blockIdx.x * 64 + threadIdx.x;
   if (item >= heads * per_head) return;
@@ -331,17 +518,140 @@ hipError_t from_f32(int dtype, const float* src, void* dst, size_t count, hipStr
   return hipGetLastError();
 }
 
+template <class E, bool TA, bool TB, int OUT>
+hipError_t mfma_matmul(const uint16_t* A, const uint16_t* B, void* C, int M, int Nc, int Kd, int lda, int ldb, int ldc,
+                       size_t strideA, size_t strideB, size_t strideC, int units, float alpha, hipStream_t st) {
+  const dim3 grid((Nc + 63) / 64, (M + 63) / 64, units);
+  mfma_matmul_kernel<E, TA, TB, OUT><<<grid, dim3(256), 0, st>>>(A, B, C, M, Nc, Kd, lda, ldb, ldc, strideA, strideB,
+                                                                strideC, alpha);
+  return hipGetLastError();
+}
+
+inline int round8(int v) { return (v + 7) / 8 * 8; }
+
+// Module terms, pooling adjoint and the final rounding: shared tail of both paths.  dS1 / dS2 are fp32
+// (HALF = false) or element-type (HALF = true) matrices with row lengths ld1 / ld2.
+template <class E, bool HALF>
+hipError_t backward_tail(const Problem& p, const float* Vf, const float* dOf, const void* dS1, int ld1,
+                         const void* dS2, int ld2, float* dQf, float* dKf, float* dVf, float* dAf, void* dQ, void* dK,
+                         void* dV, void* dA, bool agents_given, const BackwardParamGrads& pg, hipStream_t st) {
+  const size_t u = (size_t)p.units, Nd = (size_t)p.N * p.d, nd = (size_t)p.n * p.d;
+  const int N = p.N, n = p.n, d = p.d, U = p.units, batch = U / p.heads;
+  if (p.dwc_w || p.vk != 0.0f) {
+    const size_t count = u * Nd;
+    value_extras_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(dVf, dOf, p.dwc_w, p.vk, p.heads, N,
+                                                                                    d, p.gh, p.gw, count);
+  }
+  if (p.dwc_w && pg.ddwc_w) {
+    const int items = p.heads * d * 10;
+    dwc_param_grad_kernel<<<dim3((items + 63) / 64), dim3(64), 0, st>>>(Vf, dOf, pg.ddwc_w, pg.ddwc_b, batch, p.heads, N,
+                                                                        d, p.gh, p.gw);
+  }
+  auto bias_grad = [&](int kind, float* out, int which) {
+    if (!out) return;
+    const int per_head = which == 0 ? n * p.gw : (which == 1 ? n * p.gh : n * pg.h0 * pg.w0);
+    const dim3 grid((p.heads * per_head + 63) / 64);
+    if (kind == 1)
+      bias_grad_kernel<1, E, HALF><<<grid, dim3(64), 0, st>>>(dS1, ld1, out, which, batch, p.heads, n, p.gh, p.gw, pg.h0,
+                                                              pg.w0);
+    else
+      bias_grad_kernel<2, E, HALF><<<grid, dim3(64), 0, st>>>(dS2, ld2, out, which, batch, p.heads, n, p.gh, p.gw, pg.h0,
+                                                              pg.w0);
+  };
+  bias_grad(1, pg.db1_col, 0);
+  bias_grad(1, pg.db1_row, 1);
+  bias_grad(1, pg.db1_blk, 2);
+  bias_grad(2, pg.db2_col, 0);
+  bias_grad(2, pg.db2_row, 1);
+  bias_grad(2, pg.db2_blk, 2);
+  if (agents_given) {
+    AA_BWD_CHECK(from_f32(p.dtype, dAf, dA, u * nd, st));
+  } else {
+    const size_t count = u * Nd;
+    pool_grad_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(dQf, dAf, N, n, d, p.gh, p.gw, p.ah,
+                                                                                 p.aw, count);
+  }
+  AA_BWD_CHECK(from_f32(p.dtype, dQf, dQ, u * Nd, st));
+  AA_BWD_CHECK(from_f32(p.dtype, dKf, dK, u * Nd, st));
+  AA_BWD_CHECK(from_f32(p.dtype, dVf, dV, u * Nd, st));
+  return hipGetLastError();
+}
+
+// fp16 / bf16 inputs with d a multiple of 8 and 16-byte aligned tensors: matrix products on MFMA.
+template <class E>
+hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, const void* V, const void* A_elem,
+                                const void* dO, float* ws, void* dQ, void* dK, void* dV, void* dA, bool agents_given,
+                                const BackwardParamGrads& pg, hipStream_t st) {
+  const size_t u = (size_t)p.units, Nd = (size_t)p.N * p.d, nd = (size_t)p.n * p.d;
+  const int N = p.N, n = p.n, d = p.d, U = p.units, ldN = round8(N), ldn = round8(n);
+  const size_t s1 = (size_t)n * ldN, s2 = (size_t)N * ldn;      // per-unit sizes of the two attention matrices
+  // fp32 regions first, then the 16-bit ones (each region's size is a multiple of 16 bytes)
+  float* dQf = ws;
+  float* dKf = dQf + u * Nd;
+  float* dVf = dKf + u * Nd;
+  float* Vf = dVf + u * Nd;
+  float* dOf = Vf + u * Nd;
+  float* dAf = dOf + u * Nd;
+  float* F1 = dAf + u * nd;
+  float* F2 = F1 + u * s1;
+  uint16_t* P1h = (uint16_t*)(F2 + u * s2);
+  uint16_t* dS1h = P1h + u * s1;
+  uint16_t* P2h = dS1h + u * s1;
+  uint16_t* dS2h = P2h + u * s2;
+  uint16_t* VAh = dS2h + u * s2;
+  uint16_t* dVAh = VAh + u * nd;
+  const uint16_t *Qh = (const uint16_t*)Q, *Kh = (const uint16_t*)K, *Vh = (const uint16_t*)V,
+                 *Ah = (const uint16_t*)A_elem, *dOh = (const uint16_t*)dO;
+
+  const bool want_db1 = pg.db1_col || pg.db1_row || pg.db1_blk, want_db2 = pg.db2_col || pg.db2_row || pg.db2_blk;
+
+  // forward recompute
+  AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(Ah, Kh, F1, n, N, d, d, d, ldN, nd, Nd, s1, U, p.scale1, st)));
+  softmax_rows16_kernel<E, 1><<<dim3(n, U), dim3(64), 0, st>>>(F1, P1h, n, N, ldN, p.b1, p.heads, n, p.gh, p.gw);
+  AA_BWD_CHECK((mfma_matmul<E, false, false, 2>(P1h, Vh, VAh, n, d, N, ldN, d, d, s1, Nd, nd, U, 1.0f, st)));
+  AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(Qh, Ah, F2, N, n, d, d, d, ldn, Nd, nd, s2, U, p.scale2, st)));
+  softmax_rows16_kernel<E, 2><<<dim3(N, U), dim3(64), 0, st>>>(F2, P2h, N, n, ldn, p.b2, p.heads, n, p.gh, p.gw);
+
+  // broadcast stage
+  AA_BWD_CHECK((mfma_matmul<E, true, false, 2>(P2h, dOh, dVAh, n, d, N, ldn, d, d, s2, Nd, nd, U, 1.0f, st)));
+  AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(dOh, VAh, F2, N, n, d, d, d, ldn, Nd, nd, s2, U, 1.0f, st)));
+  softmax_grad_rows16_kernel<E><<<dim3(N, U), dim3(64), 0, st>>>(P2h, F2, dS2h, N, n, ldn, want_db2);
+  AA_BWD_CHECK((mfma_matmul<E, false, false, 0>(dS2h, Ah, dQf, N, d, n, ldn, d, d, s2, nd, Nd, U, p.scale2, st)));
+  AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(dS2h, Qh, dAf, n, d, N, ldn, d, d, s2, Nd, nd, U, p.scale2, st)));
+
+  // aggregation stage
+  AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(dVAh, Vh, F1, n, N, d, d, d, ldN, nd, Nd, s1, U, 1.0f, st)));
+  softmax_grad_rows16_kernel<E><<<dim3(n, U), dim3(64), 0, st>>>(P1h, F1, dS1h, n, N, ldN, want_db1);
+  AA_BWD_CHECK((mfma_matmul<E, false, false, 1>(dS1h, Kh, dAf, n, d, N, ldN, d, d, s1, Nd, nd, U, p.scale1, st)));
+  AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(dS1h, Ah, dKf, N, d, n, ldN, d, d, s1, nd, Nd, U, p.scale1, st)));
+  AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(P1h, dVAh, dVf, N, d, n, ldN, d, d, s1, nd, Nd, U, 1.0f, st)));
+
+  if (p.dwc_w || p.vk != 0.0f) {      // the gathers of the module terms read fp32 copies
+    AA_BWD_CHECK(to_f32(p.dtype, V, Vf, u * Nd, st));
+    AA_BWD_CHECK(to_f32(p.dtype, dO, dOf, u * Nd, st));
+  }
+  // F1 / F2 now hold the unrounded dS1 / dS2 (when their bias gradients are wanted)
+  return backward_tail<E, false>(p, Vf, dOf, F1, ldN, F2, ldn, dQf, dKf, dVf, dAf, dQ, dK, dV, dA, agents_given, pg, st);
+}
+
 }  // namespace
 
 size_t backward_workspace_floats(const Problem& p) {
-  const size_t u = (size_t)p.units, Nd = (size_t)p.N * p.d, nd = (size_t)p.n * p.d, nN = (size_t)p.n * p.N;
-  // Q, K, V, dO, dQ, dK, dV (7 x N*d), A, V_A, dV_A, dA (4 x n*d), P1, dS1, P2, dS2 (4 x n*N)
-  return u * (7 * Nd + 4 * nd + 4 * nN);
+  const size_t u = (size_t)p.units, Nd = (size_t)p.N * p.d, nd = (size_t)p.n * p.d;
+  // fp32 path: Q, K, V, dO, dQ, dK, dV (7 x N*d), A, V_A, dV_A, dA (4 x n*d), P1, dS1, P2, dS2 (4 x n*N).
+  // 16-bit path: 5 x N*d + n*d fp32, the two score matrices in fp32 and four 16-bit copies (rows padded
+  // to a multiple of 8), V_A and dV_A in 16 bits: never more than the figure below.
+  const size_t nN = (size_t)p.n * ((p.N + 7) / 8 * 8), Nn = (size_t)p.N * ((p.n + 7) / 8 * 8);
+  return u * (7 * Nd + 4 * nd + 2 * nN + 2 * Nn);
 }
 
 hipError_t launch_backward(const Problem& p, const void* Q, const void* K, const void* V, const void* A_elem,
                            const void* dO, float* ws, void* dQ, void* dK, void* dV, void* dA, bool agents_given,
-                           const BackwardParamGrads& pg, hipStream_t st) {
+                           bool use_mfma, const BackwardParamGrads& pg, hipStream_t st) {
+  if (use_mfma && p.dtype == 2)
+    return launch_backward_mfma<ElemBF16>(p, Q, K, V, A_elem, dO, ws, dQ, dK, dV, dA, agents_given, pg, st);
+  if (use_mfma && p.dtype == 1)
+    return launch_backward_mfma<ElemF16>(p, Q, K, V, A_elem, dO, ws, dQ, dK, dV, dA, agents_given, pg, st);
   const size_t u = (size_t)p.units, Nd = (size_t)p.N * p.d, nd = (size_t)p.n * p.d, nN = (size_t)p.n * p.N;
   float* Qf = ws;
   float* Kf = Qf + u * Nd;
@@ -387,46 +697,8 @@ hipError_t launch_backward(const Problem& p, const void* Q, const void* K, const
   AA_BWD_CHECK((matmul<true, false, false>(T1, Af, dKf, N, d, n, U, p.scale1, st)));
   AA_BWD_CHECK((matmul<true, false, false>(P1, dVAf, dVf, N, d, n, U, 1.0f, st)));
 
-  // module terms
-  if (p.dwc_w || p.vk != 0.0f) {
-    const size_t count = u * Nd;
-    value_extras_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(dVf, dOf, p.dwc_w, p.vk, p.heads, N,
-                                                                                    d, p.gh, p.gw, count);
-  }
-  if (p.dwc_w && pg.ddwc_w) {
-    const int items = p.heads * d * 10;
-    dwc_param_grad_kernel<<<dim3((items + 63) / 64), dim3(64), 0, st>>>(Vf, dOf, pg.ddwc_w, pg.ddwc_b, U / p.heads,
-                                                                        p.heads, N, d, p.gh, p.gw);
-  }
-  const int batch = U / p.heads;
-  auto bias_grad = [&](int kind, const float* dS, float* out, int which, int h0, int w0) {
-    if (!out) return;
-    const int per_head = which == 0 ? n * p.gw : (which == 1 ? n * p.gh : n * h0 * w0);
-    const dim3 grid((p.heads * per_head + 63) / 64);
-    if (kind == 1)
-      bias_grad_kernel<1><<<grid, dim3(64), 0, st>>>(dS, out, which, batch, p.heads, n, p.gh, p.gw, h0, w0);
-    else
-      bias_grad_kernel<2><<<grid, dim3(64), 0, st>>>(dS, out, which, batch, p.heads, n, p.gh, p.gw, h0, w0);
-  };
-  bias_grad(1, T1, pg.db1_col, 0, pg.h0, pg.w0);
-  bias_grad(1, T1, pg.db1_row, 1, pg.h0, pg.w0);
-  bias_grad(1, T1, pg.db1_blk, 2, pg.h0, pg.w0);
-  bias_grad(2, T2, pg.db2_col, 0, pg.h0, pg.w0);
-  bias_grad(2, T2, pg.db2_row, 1, pg.h0, pg.w0);
-  bias_grad(2, T2, pg.db2_blk, 2, pg.h0, pg.w0);
-
-  // pooling, rounding to the element type
-  if (agents_given) {
-    AA_BWD_CHECK(from_f32(p.dtype, dAf, dA, u * nd, st));
-  } else {
-    const size_t count = u * Nd;
-    pool_grad_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(dQf, dAf, N, n, d, p.gh, p.gw, p.ah,
-                                                                                 p.aw, count);
-  }
-  AA_BWD_CHECK(from_f32(p.dtype, dQf, dQ, u * Nd, st));
-  AA_BWD_CHECK(from_f32(p.dtype, dKf, dK, u * Nd, st));
-  AA_BWD_CHECK(from_f32(p.dtype, dVf, dV, u * Nd, st));
-  return hipGetLastError();
+  return backward_tail<ElemF32, false>(p, Vf, dOf, T1, N, T2, n, dQf, dKf, dVf, dAf, dQ, dK, dV, dA, agents_given, pg,
+                                       st);
 }
 
 }  // namespace aa

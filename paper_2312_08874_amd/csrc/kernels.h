@@ -50,10 +50,11 @@ struct BackwardParamGrads {      // fp32 device outputs, any may be null; layout
 // fp32 scratch the backward needs, in floats
 size_t backward_workspace_floats(const Problem& p);
 // A_elem: the agents in the element type (pooled by the forward's pooling kernel, or as given).
-// dA is written only when agents_given.
+// dA is written only when agents_given.  use_mfma: fp16 / bf16, d a multiple of 8 and every tensor
+// 16-byte aligned -- the matrix products then run on MFMA with P and dS kept in the element type.
 hipError_t launch_backward(const Problem& p, const void* Q, const void* K, const void* V, const void* A_elem,
                            const void* dO, float* ws, void* dQ, void* dK, void* dV, void* dA, bool agents_given,
-                           const BackwardParamGrads& pg, hipStream_t st);
+                           bool use_mfma, const BackwardParamGrads& pg, hipStream_t st);
 
 // --- small-agent regime (n <= 64, d in {32, 64}, fp16 / bf16): MFMA kernels that keep A and V_A in
 //     registers and stream tokens straight from global memory ---

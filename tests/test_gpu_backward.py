@@ -3,7 +3,8 @@ gradients on the same seeded inputs.
 
 Bar, per gradient tensor g with reference r: fp32 path max-abs <= 1e-4 * max(1, max|r|); fp16 / bf16
 paths (outputs rounded once to the 16-bit type) max-abs <= 1e-2 * max(1, max|r|) and relative
-L2 <= 5e-3; fp32 parameter gradients relative L2 <= 1e-4 (fp32 inputs) or 2e-3 (16-bit inputs).
+L2 <= 5e-3; fp32 parameter gradients relative L2 <= 1e-4 (fp32 inputs) or 5e-3 (16-bit inputs: the
+probabilities, V_A and dV_A that feed the MFMA products are rounded to the element type).
 
 With pooled agents the GPU rounds A to the element type as its forward does, and differentiates
 through that rounding as if it were the identity.  For the 16-bit types the reference is therefore
@@ -47,7 +48,7 @@ def _check(got, ref, dtype, what):
 
 def _check_param(got, ref, dtype, what):
     _, rel = util.errors(util.to_host64(got).reshape(ref.shape), ref)
-    assert rel <= (1e-4 if dtype == "f32" else 2e-3), "%s: rel_l2 %.3e" % (what, rel)
+    assert rel <= (1e-4 if dtype == "f32" else 5e-3), "%s: rel_l2 %.3e" % (what, rel)
 
 
 def _run_case(aa, oracle, wl, *, given=False, module=False, blk=(3, 2), kw=None):
