@@ -35,8 +35,14 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        # AA_ORACLE_LIB: a differently built copy of this library.  Only the mutation test sets it, to check
+        # that the pins notice a planted mistake; nothing else may.
+        alt = os.environ.get("AA_ORACLE_LIB")
+        if alt:
+            _lib = ctypes.CDLL(alt)
+        else:
+            build()
+            _lib = ctypes.CDLL(_LIB)
         _lib.oracle_num_threads.restype = ctypes.c_int
     return _lib
 

@@ -186,11 +186,6 @@ struct Half<ElemF16> {
                                                   0, 0);
   }
 };
-template <>
-struct Half<ElemF32> {      // never instantiated for real work; lets the fp32 path share the templates
-  static __device__ __forceinline__ float to_f32(uint16_t) { return 0.0f; }
-  static __device__ __forceinline__ uint16_t from_f32(float) { return 0; }
-};
 
 // ---------------------------------------------------------------------------
 // Batched C[u] = alpha * op(A[u]) op(B[u]) with 16-bit operands and fp32 accumulation on MFMA.
@@ -400,23 +395,18 @@ __global__ __launch_bounds__(64) void dwc_param_grad_kernel(const float* __restr
 // thread = one output element; which = 0 col, 1 row, 2 blk.  Sums run over the batch and over the
 // repeated axis (col: y, row: x) or over all tokens with their bilinear weights (blk), in index order.
 // ---------------------------------------------------------------------------
-// dS element (u, agent a, token t); ST = float or the 16-bit element storage, ld = padded row length
+// dS element (u, agent a, token t) through an accessor that knows the row length
 template <int KIND, class LD>
 __device__ __forceinline__ float ds_at(const LD& ld, int u, int a, int t, int n, int N) {
   return KIND == 1 ? ld(((size_t)u * n + a), t) : ld(((size_t)u * N + t), a);
 }
 
-template <int KIND, class E, bool HALF>
-__global__ __launch_bounds__(64) void bias_grad_kernel(const void* __restrict__ dS_raw, int ldS, float* __restrict__ out,
+template <int KIND>
+__global__ __launch_bounds__(64) void bias_grad_kernel(const float* __restrict__ dS_raw, int ldS, float* __restrict__ out,
                                                        int which, int batch, int heads, int n, int gh, int gw, int h0,
                                                        int w0) {
   const int N = gh * gw;
-  auto dS = [&](size_t row, int col) -> float {
-    if constexpr (HALF)
-      return Half<E>::to_f32(((const uint16_t*)dS_raw)[row * ldS + col]);
-    else
-      return ((const float*)dS_raw)[row * ldS + col];
-  };
+  auto dS = [&](size_t row, int col) -> float { return dS_raw[row * ldS + col]; };
   const int per_head = which == 0 ? n * gw : (which == 1 ? n * gh : n * h0 * w0);
   const int item = blockIdx.x * 64 + threadIdx.x;
   if (item >= heads * per_head) return;
@@ -529,11 +519,10 @@ hipError_t mfma_matmul(const uint16_t* A, const uint16_t* B, void* C, int M, int
 
 inline int round8(int v) { return (v + 7) / 8 * 8; }
 
-// Module terms, pooling adjoint and the final rounding: shared tail of both paths.  dS1 / dS2 are fp32
-// (HALF = false) or element-type (HALF = true) matrices with row lengths ld1 / ld2.
-template <class E, bool HALF>
-hipError_t backward_tail(const Problem& p, const float* Vf, const float* dOf, const void* dS1, int ld1,
-                         const void* dS2, int ld2, float* dQf, float* dKf, float* dVf, float* dAf, void* dQ, void* dK,
+// Module terms, pooling adjoint and the final rounding: shared tail of both paths.  dS1 / dS2 are the
+// unrounded fp32 gradients of the scores, rows of length ld1 / ld2.
+hipError_t backward_tail(const Problem& p, const float* Vf, const float* dOf, const float* dS1, int ld1,
+                         const float* dS2, int ld2, float* dQf, float* dKf, float* dVf, float* dAf, void* dQ, void* dK,
                          void* dV, void* dA, bool agents_given, const BackwardParamGrads& pg, hipStream_t st) {
   const size_t u = (size_t)p.units, Nd = (size_t)p.N * p.d, nd = (size_t)p.n * p.d;
   const int N = p.N, n = p.n, d = p.d, U = p.units, batch = U / p.heads;
@@ -552,10 +541,10 @@ hipError_t backward_tail(const Problem& p, const float* Vf, const float* dOf, co
     const int per_head = which == 0 ? n * p.gw : (which == 1 ? n * p.gh : n * pg.h0 * pg.w0);
     const dim3 grid((p.heads * per_head + 63) / 64);
     if (kind == 1)
-      bias_grad_kernel<1, E, HALF><<<grid, dim3(64), 0, st>>>(dS1, ld1, out, which, batch, p.heads, n, p.gh, p.gw, pg.h0,
+      bias_grad_kernel<1><<<grid, dim3(64), 0, st>>>(dS1, ld1, out, which, batch, p.heads, n, p.gh, p.gw, pg.h0,
                                                               pg.w0);
     else
-      bias_grad_kernel<2, E, HALF><<<grid, dim3(64), 0, st>>>(dS2, ld2, out, which, batch, p.heads, n, p.gh, p.gw, pg.h0,
+      bias_grad_kernel<2><<<grid, dim3(64), 0, st>>>(dS2, ld2, out, which, batch, p.heads, n, p.gh, p.gw, pg.h0,
                                                               pg.w0);
   };
   bias_grad(1, pg.db1_col, 0);
@@ -631,7 +620,7 @@ hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, 
     AA_BWD_CHECK(to_f32(p.dtype, dO, dOf, u * Nd, st));
   }
   // F1 / F2 now hold the unrounded dS1 / dS2 (when their bias gradients are wanted)
-  return backward_tail<E, false>(p, Vf, dOf, F1, ldN, F2, ldn, dQf, dKf, dVf, dAf, dQ, dK, dV, dA, agents_given, pg, st);
+  return backward_tail(p, Vf, dOf, F1, ldN, F2, ldn, dQf, dKf, dVf, dAf, dQ, dK, dV, dA, agents_given, pg, st);
 }
 
 }  // namespace
@@ -697,7 +686,7 @@ hipError_t launch_backward(const Problem& p, const void* Q, const void* K, const
   AA_BWD_CHECK((matmul<true, false, false>(T1, Af, dKf, N, d, n, U, p.scale1, st)));
   AA_BWD_CHECK((matmul<true, false, false>(P1, dVAf, dVf, N, d, n, U, 1.0f, st)));
 
-  return backward_tail<ElemF32, false>(p, Vf, dOf, T1, N, T2, n, dQf, dKf, dVf, dAf, dQ, dK, dV, dA, agents_given, pg,
+  return backward_tail(p, Vf, dOf, T1, N, T2, n, dQf, dKf, dVf, dAf, dQ, dK, dV, dA, agents_given, pg,
                                        st);
 }
 
