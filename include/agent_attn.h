@@ -20,8 +20,12 @@
  *  - Every tensor pointer is a DEVICE pointer owned by the caller; the library
  *    never allocates or frees device memory.  Descriptor / parameter structs are
  *    HOST memory, read during the call only.
- *  - Tensors are dense row-major.  Q, K, V, out: [batch, heads, N, d]; A:
- *    [batch, heads, n, d]; token t = y*grid_w + x; agent a = ay*agent_w + ax.
+ *  - Q, K, V, out are indexed [batch, heads, N, d] with unit channel stride and the batch / head /
+ *    token strides of the descriptor (dense by default); the MFMA kernels need strides and base
+ *    pointers that are multiples of 16 bytes, anything else takes the reference kernels.  A
+ *    [batch, heads, n, d], V_A and the workspace are dense.  Distinct elements of `out` must not
+ *    alias.  token t = y*grid_w + x; agent a = ay*agent_w + ax.  The backward entry point
+ *    accepts dense tensors only.
  *    Element type is desc->dtype (fp32, fp16 or bf16); all accumulation is fp32;
  *    `out` is rounded once to nearest-even.
  *  - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
@@ -67,8 +71,13 @@ typedef struct {
                                Stable-Diffusion variant enlarges it (Appendix C.1). */
   float v_residual_k;       /* 0 = off; O += k*V (Appendix C.1) */
   int32_t n_splits;         /* number of N-splits of the aggregation; 0 = library chooses */
-  int64_t stride_b, stride_h, stride_n; /* element strides of Q/K/V/out; 0 = dense [B,H,N,d].
-                                           Only dense layouts are implemented. */
+  int64_t stride_b, stride_h, stride_n; /* element strides of Q, K, V (shared by the three): element
+                                           (b,h,t,c) is at b*stride_b + h*stride_h + t*stride_n + c.
+                                           All 0 = dense [B,H,N,d].  Otherwise all three are required,
+                                           stride_n >= d.  A token-major tensor [B,N,H,d] is stride_b =
+                                           N*H*d, stride_h = d, stride_n = H*d; the q / k / v slices of a
+                                           fused projection output [B,N,3,H,d] use stride_n = 3*H*d. */
+  int64_t out_stride_b, out_stride_h, out_stride_n; /* the same for `out`; all 0 = dense [B,H,N,d] */
 } aa_desc;
 
 /* Module-mode parameters (host struct of device pointers, fp32).  A NULL pointer

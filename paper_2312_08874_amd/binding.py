@@ -28,7 +28,8 @@ class aa_desc(ctypes.Structure):
                 ("scale1", ctypes.c_float), ("scale2", ctypes.c_float),
                 ("v_residual_k", ctypes.c_float),
                 ("n_splits", ctypes.c_int32),
-                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64)]
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
+                ("out_stride_b", ctypes.c_int64), ("out_stride_h", ctypes.c_int64), ("out_stride_n", ctypes.c_int64)]
 
 
 class aa_params(ctypes.Structure):
@@ -101,10 +102,12 @@ def _dtype_code(t):
 
 
 def make_desc(batch, heads, N, n, d, dtype, grid=None, agent_grid=None, scale1=0.0, scale2=0.0,
-              v_residual_k=0.0, n_splits=0) -> aa_desc:
+              v_residual_k=0.0, n_splits=0, strides=(0, 0, 0), out_strides=(0, 0, 0)) -> aa_desc:
+    """strides / out_strides: (batch, head, token) element strides of Q, K, V / of out; zeros = dense."""
     gh, gw = grid if grid is not None else (0, 0)
     ah, aw = agent_grid if agent_grid is not None else (0, 0)
-    return aa_desc(batch, heads, N, n, d, gh, gw, ah, aw, dtype, scale1, scale2, v_residual_k, n_splits, 0, 0, 0)
+    return aa_desc(batch, heads, N, n, d, gh, gw, ah, aw, dtype, scale1, scale2, v_residual_k, n_splits,
+                   *[int(x) for x in strides], *[int(x) for x in out_strides])
 
 
 def make_params(params: dict | None):
@@ -161,10 +164,22 @@ def flops(desc: aa_desc) -> int:
     return int(lib().agent_attn_flops(ctypes.byref(desc)))
 
 
-def _desc_from(Q, n, grid, agent_grid, **kw):
+def _strides_of(t):
+    """(batch, head, token) element strides of a [B,H,N,d] tensor (view); zeros when it is dense."""
+    assert t.is_cuda and t.dim() == 4 and (t.stride(3) == 1 or t.shape[3] == 1), "channels must be contiguous"
+    return (0, 0, 0) if t.is_contiguous() else (t.stride(0), t.stride(1), t.stride(2))
+
+
+def _desc_from(Q, n, grid, agent_grid, same=(), out=None, **kw):
+    """Descriptor for token tensors shaped like Q.  `same`: further inputs that must share Q's strides
+    (K, V); `out`: the output tensor, which may have strides of its own."""
     B, H, N, d = Q.shape
-    assert Q.is_cuda and Q.is_contiguous()
-    return make_desc(B, H, N, n, d, _dtype_code(Q), grid, agent_grid, **kw)
+    st = _strides_of(Q)
+    for t in same:
+        assert t is None or (tuple(t.shape) == tuple(Q.shape) and _strides_of(t) == st), \
+            "Q, K, V must share one shape and one set of strides"
+    ost = _strides_of(out) if out is not None else (0, 0, 0)
+    return make_desc(B, H, N, n, d, _dtype_code(Q), grid, agent_grid, strides=st, out_strides=ost, **kw)
 
 
 def _workspace(desc, params, workspace):
@@ -180,12 +195,12 @@ def agent_attn_fwd(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict 
     """O = agent attention of Q, K, V [B,H,N,d] (device tensors).  A None: pool Q onto agent_grid."""
     import torch
     n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
-    desc = _desc_from(Q, n, grid, agent_grid, scale1=scale1, scale2=scale2, v_residual_k=v_residual_k,
-                      n_splits=n_splits)
+    if out is None:
+        out = torch.empty_like(Q)      # keeps Q's (possibly permuted) layout
+    desc = _desc_from(Q, n, grid, agent_grid, same=(K, V), out=out, scale1=scale1, scale2=scale2,
+                      v_residual_k=v_residual_k, n_splits=n_splits)
     p = make_params(params)
     workspace, need = _workspace(desc, p, workspace)
-    if out is None:
-        out = torch.empty_like(Q)
     st = lib().agent_attn_fwd(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(A), _pp(p),
                               workspace.data_ptr(), workspace.numel() * workspace.element_size(), out.data_ptr(),
                               _stream(stream))
@@ -200,6 +215,7 @@ def agent_attn_bwd(Q, K, V, dO, A=None, *, grid=None, agent_grid=None, params: d
     fp32 gradient under the parameter's own name prefixed with "d" (db1_col, ..., ddwc_w, ddwc_b)."""
     import torch
     n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
+    assert all(t.is_contiguous() for t in (Q, K, V, dO)), "agent_attn_bwd takes dense tensors"
     desc = _desc_from(Q, n, grid, agent_grid, scale1=scale1, scale2=scale2, v_residual_k=v_residual_k)
     p = make_params(params)
     need = int(lib().agent_attn_bwd_workspace_bytes(ctypes.byref(desc), _pp(p)))
@@ -246,8 +262,8 @@ class PreparedCall:
 def prepare_fwd(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict | None = None, scale1=0.0,
                 scale2=0.0, v_residual_k=0.0, n_splits=0, out, workspace=None, stream=None) -> PreparedCall:
     n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
-    desc = _desc_from(Q, n, grid, agent_grid, scale1=scale1, scale2=scale2, v_residual_k=v_residual_k,
-                      n_splits=n_splits)
+    desc = _desc_from(Q, n, grid, agent_grid, same=(K, V), out=out, scale1=scale1, scale2=scale2,
+                      v_residual_k=v_residual_k, n_splits=n_splits)
     p = make_params(params)
     workspace, need = _workspace(desc, p, workspace)
     args = (ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(A), _pp(p), workspace.data_ptr(),
@@ -264,7 +280,7 @@ def prepare_pool(Q, *, grid, agent_grid, out, stream=None) -> PreparedCall:
 
 def prepare_aggregate(A, K, V, *, grid=None, params: dict | None = None, scale1=0.0, n_splits=0, out,
                       workspace=None, stream=None) -> PreparedCall:
-    desc = _desc_from(K, A.shape[2], grid, None, scale1=scale1, n_splits=n_splits)
+    desc = _desc_from(K, A.shape[2], grid, None, same=(V,), scale1=scale1, n_splits=n_splits)
     p = make_params(params)
     workspace, need = _workspace(desc, p, workspace)
     args = (ctypes.byref(desc), A.data_ptr(), K.data_ptr(), V.data_ptr(), _pp(p), workspace.data_ptr(),
@@ -275,7 +291,7 @@ def prepare_aggregate(A, K, V, *, grid=None, params: dict | None = None, scale1=
 
 def prepare_broadcast(Q, A, VA, V=None, *, grid=None, params: dict | None = None, scale2=0.0, v_residual_k=0.0,
                       out, stream=None) -> PreparedCall:
-    desc = _desc_from(Q, A.shape[2], grid, None, scale2=scale2, v_residual_k=v_residual_k)
+    desc = _desc_from(Q, A.shape[2], grid, None, same=(V,), out=out, scale2=scale2, v_residual_k=v_residual_k)
     p = make_params(params)
     args = (ctypes.byref(desc), Q.data_ptr(), A.data_ptr(), VA.data_ptr(), _ptr(V), _pp(p), out.data_ptr(),
             _stream(stream))
@@ -299,7 +315,7 @@ def agent_aggregate_fwd(A, K, V, *, grid=None, params: dict | None = None, scale
     import torch
     B, H, N, d = K.shape
     n = A.shape[2]
-    desc = _desc_from(K, n, grid, None, scale1=scale1, n_splits=n_splits)
+    desc = _desc_from(K, n, grid, None, same=(V,), scale1=scale1, n_splits=n_splits)
     p = make_params(params)
     workspace, need = _workspace(desc, p, workspace)
     if out is None:
@@ -315,10 +331,10 @@ def agent_broadcast_fwd(Q, A, VA, V=None, *, grid=None, params: dict | None = No
                         v_residual_k=0.0, out=None, stream=None):
     import torch
     n = A.shape[2]
-    desc = _desc_from(Q, n, grid, None, scale2=scale2, v_residual_k=v_residual_k)
-    p = make_params(params)
     if out is None:
         out = torch.empty_like(Q)
+    desc = _desc_from(Q, n, grid, None, same=(V,), out=out, scale2=scale2, v_residual_k=v_residual_k)
+    p = make_params(params)
     st = lib().agent_broadcast_fwd(ctypes.byref(desc), Q.data_ptr(), A.data_ptr(), VA.data_ptr(), _ptr(V), _pp(p),
                                    out.data_ptr(), _stream(stream))
     _check(st, "agent_broadcast_fwd")

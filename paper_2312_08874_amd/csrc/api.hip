@@ -60,11 +60,15 @@ aa_status check_desc(const aa_desc* d, bool need_grid, bool need_agent_grid) {
   if (d->d > kMaxD) return AA_ERR_UNSUPPORTED;
   if (d->grid_h > 65535 || d->grid_w > 65535) return AA_ERR_UNSUPPORTED;   // 32-bit window arithmetic
   if ((int64_t)units * d->N * d->d >= (int64_t)1 << 40) return AA_ERR_UNSUPPORTED;
-  // only dense [B,H,N,d] tensors
-  const int64_t sn = d->d, sh = (int64_t)d->N * d->d, sb = sh * d->heads;
-  if ((d->stride_n && d->stride_n != sn) || (d->stride_h && d->stride_h != sh) ||
-      (d->stride_b && d->stride_b != sb))
-    return AA_ERR_UNSUPPORTED;
+  // strides: all zero (dense) or all given, rows at least d apart and addressable with 32-bit row strides
+  for (int k = 0; k < 2; ++k) {
+    const int64_t sb = k ? d->out_stride_b : d->stride_b, sh = k ? d->out_stride_h : d->stride_h,
+                  sn = k ? d->out_stride_n : d->stride_n;
+    if (sb == 0 && sh == 0 && sn == 0) continue;
+    if (sb < 0 || sh < 0 || sn < d->d) return AA_ERR_SHAPE;
+    if (sn > (int64_t)1 << 30) return AA_ERR_UNSUPPORTED;
+    if ((d->batch > 1 && sb == 0) || (d->heads > 1 && sh == 0)) return AA_ERR_SHAPE;
+  }
   if (aa::broadcast_generic_lds_bytes(d->n, d->d) > kMaxDynLds) return AA_ERR_UNSUPPORTED;
   return AA_OK;
 }
@@ -187,6 +191,34 @@ Plan make_plan(const aa_desc* d) {
   return pl;
 }
 
+aa::Layout layout_of(const aa_desc* d) {
+  aa::Layout L;
+  const bool dense_in = d->stride_b == 0 && d->stride_h == 0 && d->stride_n == 0;
+  const bool dense_out = d->out_stride_b == 0 && d->out_stride_h == 0 && d->out_stride_n == 0;
+  L.sn = dense_in ? d->d : (int)d->stride_n;
+  L.sh = dense_in ? (long long)d->N * d->d : d->stride_h;
+  L.sb = dense_in ? (long long)d->N * d->d * d->heads : d->stride_b;
+  L.on = dense_out ? d->d : (int)d->out_stride_n;
+  L.oh = dense_out ? (long long)d->N * d->d : d->out_stride_h;
+  L.ob = dense_out ? (long long)d->N * d->d * d->heads : d->out_stride_b;
+  return L;
+}
+bool dense_layout(const aa_desc* d) {
+  return d->stride_b == 0 && d->stride_h == 0 && d->stride_n == 0 && d->out_stride_b == 0 && d->out_stride_h == 0 &&
+         d->out_stride_n == 0;
+}
+// bytes from the base pointer to one past the last element of a token tensor
+size_t extent_bytes(const aa_desc* d, bool out) {
+  const aa::Layout L = layout_of(d);
+  const size_t sb = out ? L.ob : L.sb, sh = out ? L.oh : L.sh, sn = out ? L.on : L.sn;
+  return ((size_t)(d->batch - 1) * sb + (size_t)(d->heads - 1) * sh + (size_t)(d->N - 1) * sn + (size_t)d->d) *
+         elem_size(d->dtype);
+}
+// the 16-byte vector accesses of the MFMA kernels need every stride to be a multiple of 8 elements
+bool layout_vectorizable(const aa::Layout& L) {
+  return L.sb % 8 == 0 && L.sh % 8 == 0 && L.sn % 8 == 0 && L.ob % 8 == 0 && L.oh % 8 == 0 && L.on % 8 == 0;
+}
+
 Problem make_problem(const aa_desc* d, const aa_params* p) {
   Problem pr{};
   pr.units = d->batch * d->heads;
@@ -199,6 +231,7 @@ Problem make_problem(const aa_desc* d, const aa_params* p) {
   pr.ah = d->agent_h;
   pr.aw = d->agent_w;
   pr.dtype = d->dtype;
+  pr.lay = layout_of(d);
   const float dflt = 1.0f / sqrtf((float)d->d);
   pr.scale1 = d->scale1 > 0.0f ? d->scale1 : dflt;
   pr.scale2 = d->scale2 > 0.0f ? d->scale2 : dflt;
@@ -227,7 +260,7 @@ bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 // The MFMA kernels use 16-byte vector accesses on every tensor.
 bool use_small(const Problem& pr, std::initializer_list<const void*> ptrs) {
-  if (!aa::small_supported(pr)) return false;
+  if (!aa::small_supported(pr) || !layout_vectorizable(pr.lay)) return false;
   for (const void* p : ptrs)
     if (!aligned16(p)) return false;
   return true;
@@ -238,7 +271,7 @@ bool large_supported(const Problem& pr) {
   return (pr.dtype == AA_F16 || pr.dtype == AA_BF16) && pr.d % 8 == 0 && pr.d <= 128;
 }
 bool use_large(const Problem& pr, std::initializer_list<const void*> ptrs) {
-  if (!large_supported(pr)) return false;
+  if (!large_supported(pr) || !layout_vectorizable(pr.lay)) return false;
   for (const void* p : ptrs)
     if (!aligned16(p)) return false;
   return true;
@@ -334,7 +367,7 @@ aa_status agent_pool_fwd(const aa_desc* desc, const void* Q, void* A_out, void* 
   if (st != AA_OK) return st;
   if (!Q || !A_out) return AA_ERR_NULL;
   const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
-  if (overlaps(A_out, units * desc->n * desc->d * es, Q, units * desc->N * desc->d * es)) return AA_ERR_ALIAS;
+  if (overlaps(A_out, units * desc->n * desc->d * es, Q, extent_bytes(desc, false))) return AA_ERR_ALIAS;
   Problem pr = make_problem(desc, nullptr);
   return run_pool(pr, Q, A_out, (hipStream_t)hip_stream);
 }
@@ -354,8 +387,8 @@ aa_status agent_aggregate_fwd(const aa_desc* desc, const void* A, const void* K,
   const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
   const size_t va_bytes = units * desc->n * desc->d * sizeof(float);
   if (overlaps(VA_out, va_bytes, A, units * desc->n * desc->d * es) ||
-      overlaps(VA_out, va_bytes, K, units * desc->N * desc->d * es) ||
-      overlaps(VA_out, va_bytes, V, units * desc->N * desc->d * es) ||
+      overlaps(VA_out, va_bytes, K, extent_bytes(desc, false)) ||
+      overlaps(VA_out, va_bytes, V, extent_bytes(desc, false)) ||
       overlaps(VA_out, va_bytes, workspace, workspace_bytes))
     return AA_ERR_ALIAS;
   Problem pr = make_problem(desc, params);
@@ -374,10 +407,10 @@ aa_status agent_broadcast_fwd(const aa_desc* desc, const void* Q, const void* A,
   if (!Q || !A || !VA || !out) return AA_ERR_NULL;
   if ((dwc || desc->v_residual_k != 0.0f) && !V) return AA_ERR_NULL;
   const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
-  const size_t big = units * desc->N * desc->d * es;
-  if (overlaps(out, big, Q, big) || overlaps(out, big, V, big) ||
-      overlaps(out, big, A, units * desc->n * desc->d * es) ||
-      overlaps(out, big, VA, units * desc->n * desc->d * sizeof(float)))
+  const size_t big = extent_bytes(desc, false), obig = extent_bytes(desc, true);
+  if (overlaps(out, obig, Q, big) || overlaps(out, obig, V, big) ||
+      overlaps(out, obig, A, units * desc->n * desc->d * es) ||
+      overlaps(out, obig, VA, units * desc->n * desc->d * sizeof(float)))
     return AA_ERR_ALIAS;
   Problem pr = make_problem(desc, params);
   pr.b1 = aa::BiasArgs{};
@@ -398,9 +431,9 @@ aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, cons
   st = check_workspace(workspace, workspace_bytes, pl);
   if (st != AA_OK) return st;
   const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
-  const size_t big = units * desc->N * desc->d * es;
-  if (overlaps(out, big, Q, big) || overlaps(out, big, K, big) || overlaps(out, big, V, big) ||
-      overlaps(out, big, A, units * desc->n * desc->d * es) || overlaps(out, big, workspace, workspace_bytes) ||
+  const size_t big = extent_bytes(desc, false), obig = extent_bytes(desc, true);
+  if (overlaps(out, obig, Q, big) || overlaps(out, obig, K, big) || overlaps(out, obig, V, big) ||
+      overlaps(out, obig, A, units * desc->n * desc->d * es) || overlaps(out, obig, workspace, workspace_bytes) ||
       overlaps(workspace, workspace_bytes, Q, big) || overlaps(workspace, workspace_bytes, K, big) ||
       overlaps(workspace, workspace_bytes, V, big) ||
       overlaps(workspace, workspace_bytes, A, units * desc->n * desc->d * es))
@@ -453,6 +486,7 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
   if (st != AA_OK) return st;
   st = check_params(params);
   if (st != AA_OK) return st;
+  if (!dense_layout(desc)) return AA_ERR_UNSUPPORTED;      // the backward takes dense tensors only
   if (!Q || !K || !V || !dO || !dQ || !dK || !dV) return AA_ERR_NULL;
   if (pooling ? dA != nullptr : dA == nullptr) return AA_ERR_NULL;
   aa::BackwardParamGrads pg{};

@@ -32,6 +32,24 @@ struct ElemBF16 {
 };
 
 // ---------------------------------------------------------------------------
+// Memory layout of the token tensors.  Element (b, h, t, c) of Q, K, V sits at
+// b*sb + h*sh + t*sn + c (elements) from the tensor's base pointer; `out` has its own three strides.
+// The channel stride is always 1.  A, V_A and the workspace are dense.
+// ---------------------------------------------------------------------------
+struct Layout {
+  long long sb, sh;      // batch and head strides of Q, K, V
+  int sn;                // token (row) stride of Q, K, V
+  long long ob, oh;      // the same for out
+  int on;
+  __host__ __device__ size_t in_unit(int u, int heads) const {
+    return (size_t)(u / heads) * (size_t)sb + (size_t)(u % heads) * (size_t)sh;
+  }
+  __host__ __device__ size_t out_unit(int u, int heads) const {
+    return (size_t)(u / heads) * (size_t)ob + (size_t)(u % heads) * (size_t)oh;
+  }
+};
+
+// ---------------------------------------------------------------------------
 // Agent bias (Appendix B), evaluated on the fly from its three components.
 // Pointers are already offset to the head; any may be null.
 //   kind 1: B1[a,(y,x)] = col[a*w+x] + row[a*h+y] + resize(blk[a,:,:])[y,x]

@@ -17,17 +17,17 @@ constexpr int kMaxDPerLane = 4;       // d <= 64 * kMaxDPerLane
 template <class E>
 __global__ __launch_bounds__(64) void pool_generic_kernel(const typename E::T* __restrict__ Q,
                                                           typename E::T* __restrict__ A, int N, int n, int d,
-                                                          int gh, int gw, int ah, int aw) {
+                                                          int heads, Layout lay, int gh, int gw, int ah, int aw) {
   const int a = blockIdx.x, u = blockIdx.y;
   const int ay = a / aw, ax = a % aw;
   const int y0 = pool_win_lo(ay, gh, ah), y1 = pool_win_hi(ay, gh, ah);
   const int x0 = pool_win_lo(ax, gw, aw), x1 = pool_win_hi(ax, gw, aw);
   const float inv = 1.0f / (float)((y1 - y0) * (x1 - x0));
-  const typename E::T* q = Q + (size_t)u * N * d;
+  const typename E::T* q = Q + lay.in_unit(u, heads);
   for (int c = threadIdx.x; c < d; c += 64) {
     float acc = 0.0f;
     for (int y = y0; y < y1; ++y)
-      for (int x = x0; x < x1; ++x) acc += E::to_f32(q[((size_t)y * gw + x) * d + c]);
+      for (int x = x0; x < x1; ++x) acc += E::to_f32(q[((size_t)y * gw + x) * lay.sn + c]);
     A[((size_t)u * n + a) * d + c] = E::from_f32(acc * inv);
   }
 }
@@ -39,7 +39,8 @@ __global__ __launch_bounds__(64) void pool_generic_kernel(const typename E::T* _
 // ---------------------------------------------------------------------------
 template <class E>
 __global__ __launch_bounds__(256) void pool_chunk_kernel(const uint16_t* __restrict__ Q, uint16_t* __restrict__ A,
-                                                         int N, int n, int d, int gh, int gw, int ah, int aw) {
+                                                         int N, int n, int d, int heads, Layout lay, int gh, int gw,
+                                                         int ah, int aw) {
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   const int cpr = d >> 3, u = blockIdx.y;
   const int item = blockIdx.x * 256 + threadIdx.x;
@@ -48,7 +49,7 @@ __global__ __launch_bounds__(256) void pool_chunk_kernel(const uint16_t* __restr
   const int ay = a / aw, ax = a - ay * aw;
   const int y0 = pool_win_lo(ay, gh, ah), y1 = pool_win_hi(ay, gh, ah);
   const int x0 = pool_win_lo(ax, gw, aw), x1 = pool_win_hi(ax, gw, aw);
-  const uint16_t* q = Q + (size_t)u * N * d + 8 * chunk;
+  const uint16_t* q = Q + lay.in_unit(u, heads) + 8 * chunk;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   auto add = [&](const u32x4& v) {
 #pragma unroll
@@ -60,16 +61,16 @@ __global__ __launch_bounds__(256) void pool_chunk_kernel(const uint16_t* __restr
     }
   };
   for (int y = y0; y < y1; ++y) {
-    const uint16_t* row = q + (size_t)y * gw * d;
+    const uint16_t* row = q + (size_t)y * gw * lay.sn;
     int x = x0;
     for (; x + 4 <= x1; x += 4) {
       u32x4 v[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] = *(const u32x4*)(row + (size_t)(x + j) * d);
+      for (int j = 0; j < 4; ++j) v[j] = *(const u32x4*)(row + (size_t)(x + j) * lay.sn);
 #pragma unroll
       for (int j = 0; j < 4; ++j) add(v[j]);
     }
-    for (; x < x1; ++x) add(*(const u32x4*)(row + (size_t)x * d));
+    for (; x < x1; ++x) add(*(const u32x4*)(row + (size_t)x * lay.sn));
   }
   const float inv = 1.0f / (float)((y1 - y0) * (x1 - x0));
   u32x4 w;
@@ -92,8 +93,8 @@ __global__ __launch_bounds__(256) void pool_chunk_kernel(const uint16_t* __restr
 template <class E>
 __global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
     const typename E::T* __restrict__ A, const typename E::T* __restrict__ K,
-    const typename E::T* __restrict__ V, BiasArgs b1, float scale, int N, int n, int d, int heads, int gh,
-    int gw, int S, float* __restrict__ part_acc, float* __restrict__ part_m, float* __restrict__ part_l) {
+    const typename E::T* __restrict__ V, BiasArgs b1, float scale, int N, int n, int d, int heads, Layout lay,
+    int gh, int gw, int S, float* __restrict__ part_acc, float* __restrict__ part_m, float* __restrict__ part_l) {
   extern __shared__ float smem[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int a = blockIdx.x * kWaves + wave;
@@ -105,8 +106,8 @@ __global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
   const int chunk = (N + S - 1) / S;
   const int t0 = s * chunk;
   const int t1 = min(N, t0 + chunk);
-  const typename E::T* Ku = K + (size_t)u * N * d;
-  const typename E::T* Vu = V + (size_t)u * N * d;
+  const typename E::T* Ku = K + lay.in_unit(u, heads);
+  const typename E::T* Vu = V + lay.in_unit(u, heads);
 
   const int hd = u % heads;
   BiasArgs b = b1;
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
     const bool valid = active && t < t1;
     float sc = -INFINITY;
     if (valid) {
-      const typename E::T* kr = Ku + (size_t)t * d;
+      const typename E::T* kr = Ku + (size_t)t * lay.sn;
       float dot = 0.0f;
       for (int c = 0; c < d; ++c) dot += a_row[c] * E::to_f32(kr[c]);
       sc = dot * scale;
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
         const int c = lane + 64 * k;
         if (c < d) {
           float v = acc[k] * alpha;
-          for (int j = 0; j < cnt; ++j) v += p_sh[j] * E::to_f32(Vu[(size_t)(tb + j) * d + c]);
+          for (int j = 0; j < cnt; ++j) v += p_sh[j] * E::to_f32(Vu[(size_t)(tb + j) * lay.sn + c]);
           acc[k] = v;
         }
       }
@@ -206,8 +207,8 @@ template <class E>
 __global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
     const typename E::T* __restrict__ Q, const typename E::T* __restrict__ A, const float* __restrict__ VA,
     const typename E::T* __restrict__ V, BiasArgs b2, const float* __restrict__ dwc_w,
-    const float* __restrict__ dwc_b, float scale, float vk, int N, int n, int d, int heads, int gh, int gw,
-    typename E::T* __restrict__ O) {
+    const float* __restrict__ dwc_b, float scale, float vk, int N, int n, int d, int heads, Layout lay, int gh,
+    int gw, typename E::T* __restrict__ O) {
   extern __shared__ float smem[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int i = blockIdx.x * kWaves + wave;
@@ -225,7 +226,7 @@ __global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
   const int y = gw > 0 ? i / gw : 0, x = gw > 0 ? i % gw : 0;
 
   if (active)
-    for (int c = lane; c < d; c += 64) q_row[c] = E::to_f32(Q[((size_t)u * N + i) * d + c]);
+    for (int c = lane; c < d; c += 64) q_row[c] = E::to_f32(Q[lay.in_unit(u, heads) + (size_t)i * lay.sn + c]);
   __syncthreads();
 
   float mx = -INFINITY;
@@ -264,12 +265,12 @@ __global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
           for (int kx = -1; kx <= 1; ++kx) {
             const int yy = y + ky, xx = x + kx;
             if (yy >= 0 && yy < gh && xx >= 0 && xx < gw)
-              conv += w9[(ky + 1) * 3 + (kx + 1)] * E::to_f32(V[((size_t)u * N + (size_t)yy * gw + xx) * d + c]);
+              conv += w9[(ky + 1) * 3 + (kx + 1)] * E::to_f32(V[lay.in_unit(u, heads) + ((size_t)yy * gw + xx) * lay.sn + c]);
           }
         o += conv;
       }
-      if (vk != 0.0f) o += vk * E::to_f32(V[((size_t)u * N + i) * d + c]);
-      O[((size_t)u * N + i) * d + c] = E::from_f32(o);
+      if (vk != 0.0f) o += vk * E::to_f32(V[lay.in_unit(u, heads) + (size_t)i * lay.sn + c]);
+      O[lay.out_unit(u, heads) + (size_t)i * lay.on + c] = E::from_f32(o);
     }
   }
 }
@@ -288,18 +289,18 @@ __global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
 hipError_t launch_pool_generic(const Problem& p, const void* Q, void* A, hipStream_t st) {
   dim3 grid(p.n, p.units);
   AA_DISPATCH_DTYPE(p.dtype, pool_generic_kernel<E><<<grid, dim3(64), 0, st>>>(
-      (const typename E::T*)Q, (typename E::T*)A, p.N, p.n, p.d, p.gh, p.gw, p.ah, p.aw));
+      (const typename E::T*)Q, (typename E::T*)A, p.N, p.n, p.d, p.heads, p.lay, p.gh, p.gw, p.ah, p.aw));
   return hipGetLastError();
 }
 
 hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, hipStream_t st) {
   const dim3 grid((p.n * (p.d >> 3) + 255) / 256, p.units);
   if (p.dtype == 2)
-    pool_chunk_kernel<ElemBF16><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, p.N, p.n, p.d, p.gh, p.gw,
-                                                            p.ah, p.aw);
+    pool_chunk_kernel<ElemBF16><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, p.N, p.n, p.d, p.heads,
+                                                            p.lay, p.gh, p.gw, p.ah, p.aw);
   else if (p.dtype == 1)
-    pool_chunk_kernel<ElemF16><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, p.N, p.n, p.d, p.gh, p.gw,
-                                                           p.ah, p.aw);
+    pool_chunk_kernel<ElemF16><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, p.N, p.n, p.d, p.heads,
+                                                           p.lay, p.gh, p.gw, p.ah, p.aw);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
@@ -311,7 +312,7 @@ hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void*
   const size_t lds = (size_t)kWaves * (p.d + 64) * sizeof(float);
   AA_DISPATCH_DTYPE(p.dtype, aggregate_generic_kernel<E><<<grid, dim3(64 * kWaves), lds, st>>>(
       (const typename E::T*)A, (const typename E::T*)K, (const typename E::T*)V, p.b1, p.scale1, p.N, p.n, p.d,
-      p.heads, p.gh, p.gw, part.S, part.acc, part.m, part.l));
+      p.heads, p.lay, p.gh, p.gw, part.S, part.acc, part.m, part.l));
   return hipGetLastError();
 }
 
@@ -329,7 +330,7 @@ hipError_t launch_broadcast_generic(const Problem& p, const void* Q, const void*
   const size_t lds = broadcast_generic_lds_bytes(p.n, p.d);
   AA_DISPATCH_DTYPE(p.dtype, broadcast_generic_kernel<E><<<grid, dim3(64 * kWaves), lds, st>>>(
       (const typename E::T*)Q, (const typename E::T*)A, VA, (const typename E::T*)V, p.b2, p.dwc_w, p.dwc_b,
-      p.scale2, p.vk, p.N, p.n, p.d, p.heads, p.gh, p.gw, (typename E::T*)out));
+      p.scale2, p.vk, p.N, p.n, p.d, p.heads, p.lay, p.gh, p.gw, (typename E::T*)out));
   return hipGetLastError();
 }
 

@@ -13,6 +13,7 @@ struct Problem {
   int units, heads, N, n, d;
   int gh, gw, ah, aw;
   int dtype;  // aa_dtype
+  Layout lay; // strides of Q, K, V and of out (elements)
   float scale1, scale2, vk;
   // module terms (pointers to the start of the per-head arrays, or null)
   BiasArgs b1, b2;

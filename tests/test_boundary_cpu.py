@@ -29,8 +29,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    # int32 x10, float x3, int32, int64 x3 -> 80 bytes; params: 6 ptr, 2 int32, 2 ptr -> 72 bytes
-    assert ctypes.sizeof(binding.aa_desc) == 80
+    # int32 x10, float x3, int32, int64 x6 -> 104 bytes; params: 6 ptr, 2 int32, 2 ptr -> 72 bytes
+    assert ctypes.sizeof(binding.aa_desc) == 104
     assert ctypes.sizeof(binding.aa_params) == 72
 
 
@@ -79,8 +79,13 @@ def test_fwd_rejects_bad_arguments():
     d = make_desc(1, 1, 196, 49, 32, 0, **ok)
     assert call_fwd(d, out=FAKE) == -6                                                # out aliases Q
     assert call_fwd(d, out=FAKE * 3 + 16) == -6                                       # out overlaps V
-    d.stride_n = 64
-    assert call_fwd(d) == -7                                                          # strided input
+    # strides: rows closer than d; some but not all strides of a batched problem; out overlapping a strided input
+    assert call_fwd(make_desc(1, 1, 196, 49, 32, 0, strides=(0, 0, 16), **ok)) == -2
+    assert call_fwd(make_desc(2, 3, 196, 49, 32, 0, strides=(0, 0, 96), **ok)) == -2
+    assert call_fwd(make_desc(2, 3, 196, 49, 32, 0, strides=(-1, 32, 96), **ok)) == -2
+    assert call_fwd(make_desc(2, 3, 196, 49, 32, 0, out_strides=(0, 32, 96), **ok)) == -2
+    wide = make_desc(2, 3, 196, 49, 32, 0, strides=(196 * 288, 32, 288), **ok)        # q of a fused [B,N,3,H,d] tensor
+    assert call_fwd(wide, out=FAKE + 2 * 196 * 288 * 4 - 64) == -6                    # inside Q's strided extent
     # bias without a token grid; block bias without its size; DWC bias without DWC weights
     p = aa_params()
     p.b1_row = FAKE * 7

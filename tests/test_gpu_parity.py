@@ -343,3 +343,54 @@ def test_forward_one_block_per_unit(aa, oracle, grid, agrid, d, dtype, module):
         import torch
         O2 = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], A)
         assert torch.equal(O, O2)
+
+
+# --------------------------------------------------------------------------
+# strided Q, K, V, out: views of token-major [B,N,H,d] tensors and of a fused [B,N,3,H,d] projection
+# output must give exactly the bits of the dense call, on every kernel family
+# --------------------------------------------------------------------------
+STRIDED_CASES = [
+    ("one-block", (14, 14), (7, 7), 64, "bf16", 3),       # one block per unit
+    ("split", (40, 40), (7, 7), 32, "f16", 2),            # pool + split aggregate + broadcast
+    ("large", (24, 24), (9, 9), 40, "bf16", 2),           # large-agent kernels, padded head width
+    ("reference-f32", (9, 11), (3, 4), 24, "f32", 2),     # reference kernels
+    ("reference-odd-stride", (9, 11), (3, 4), 20, "bf16", 3),      # strides not a multiple of 8 elements
+]
+
+
+@pytest.mark.parametrize("layout", ["token-major", "fused-qkv"])
+@pytest.mark.parametrize("module", [False, True])
+@pytest.mark.parametrize("name,grid,agrid,d,dtype,heads", STRIDED_CASES, ids=[c[0] for c in STRIDED_CASES])
+def test_forward_strided_layouts(aa, name, grid, agrid, d, dtype, heads, module, layout):
+    import dataclasses
+    import torch
+    wl = dataclasses.replace(WL["tiny"], batch=2, heads=heads, grid=grid, agent_grid=agrid, d=d, dtype=dtype, index=12)
+    t = inputs.make_qkv(wl)
+    dense = dev_qkv(wl, t)                                  # [B,H,N,d] contiguous
+    B, H, N = wl.batch, wl.heads, wl.N
+    if layout == "token-major":
+        views = {k: v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for k, v in dense.items()}
+    else:
+        qkv = torch.stack([dense[k].permute(0, 2, 1, 3) for k in ("Q", "K", "V")], dim=2).contiguous()   # [B,N,3,H,d]
+        views = {k: qkv[:, :, i].permute(0, 2, 1, 3) for i, k in enumerate(("Q", "K", "V"))}
+    for k in views:
+        assert not views[k].is_contiguous() and torch.equal(views[k], dense[k])
+    params = None
+    if module:
+        params = util.params_to_device(inputs.make_module_params(H, wl.n, d, grid, blk=(3, 2), index=12))
+    kw = dict(grid=grid, agent_grid=agrid, params=params)
+    ref = aa.agent_attn_fwd(dense["Q"], dense["K"], dense["V"], **kw)
+    # dense output from strided inputs, and a token-major output
+    out_dense = torch.empty_like(dense["Q"])
+    got = aa.agent_attn_fwd(views["Q"], views["K"], views["V"], out=out_dense, **kw)
+    assert torch.equal(got, ref)
+    out_tm = torch.full((B, N, H, d), 7.0, dtype=ref.dtype, device="cuda").permute(0, 2, 1, 3)
+    got = aa.agent_attn_fwd(views["Q"], views["K"], views["V"], out=out_tm, **kw)
+    assert torch.equal(got, ref)
+    # stage entry points
+    A = aa.agent_pool_fwd(views["Q"], grid=grid, agent_grid=agrid)
+    assert torch.equal(A, aa.agent_pool_fwd(dense["Q"], grid=grid, agent_grid=agrid))
+    VA = aa.agent_aggregate_fwd(A, views["K"], views["V"], grid=grid, params=params)
+    assert torch.equal(VA, aa.agent_aggregate_fwd(A, dense["K"], dense["V"], grid=grid, params=params))
+    O = aa.agent_broadcast_fwd(views["Q"], A, VA, views["V"], grid=grid, params=params, out=out_tm)
+    assert torch.equal(O, aa.agent_broadcast_fwd(dense["Q"], A, VA, dense["V"], grid=grid, params=params))
