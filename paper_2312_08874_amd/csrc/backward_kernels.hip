@@ -274,13 +274,32 @@ __global__ __launch_bounds__(256) void mfma_matmul_kernel(const uint16_t* __rest
     }
 }
 
+// reductions over groups of LPR consecutive lanes (LPR a power of two)
+template <int LPR>
+__device__ __forceinline__ float group_max(float v) {
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
 // Row softmax of the fp32 scores S (rows of length ld), bias added first, result rounded to the element
-// type into P (same ld); the padding columns [cols, ld) of P are zeroed.  One wave per row.
-template <class E, int KIND>
+// type into P (same ld); the padding columns [cols, ld) of P are zeroed.  LPR lanes per row: a whole wave
+// for long rows, 16 lanes (four rows per wave) for the short rows of the broadcast stage.
+// grid = (ceil(rows * LPR / 64), units), 64 threads.
+template <class E, int KIND, int LPR>
 __global__ __launch_bounds__(64) void softmax_rows16_kernel(const float* __restrict__ S, uint16_t* __restrict__ P,
                                                             int rows, int cols, int ld, BiasArgs b, int heads, int n,
                                                             int gh, int gw) {
-  const int r = blockIdx.x, u = blockIdx.y, lane = threadIdx.x;
+  const int u = blockIdx.y, lane = threadIdx.x % LPR;
+  const int r_raw = blockIdx.x * (64 / LPR) + threadIdx.x / LPR;
+  const bool live = r_raw < rows;
+  const int r = live ? r_raw : rows - 1;      // idle groups shadow the last row and write nothing
   const float* row = S + ((size_t)u * rows + r) * ld;
   uint16_t* prow = P + ((size_t)u * rows + r) * ld;
   BiasArgs hb = b;
@@ -303,28 +322,32 @@ __global__ __launch_bounds__(64) void softmax_rows16_kernel(const float* __restr
     return v;
   };
   float mx = -INFINITY;
-  for (int j = lane; j < cols; j += 64) mx = fmaxf(mx, score(j));
-  mx = wave_max(mx);
+  for (int j = lane; j < cols; j += LPR) mx = fmaxf(mx, score(j));
+  mx = group_max<LPR>(mx);
   float sum = 0.0f;
-  for (int j = lane; j < cols; j += 64) sum += __expf(score(j) - mx);
-  sum = wave_sum(sum);
+  for (int j = lane; j < cols; j += LPR) sum += __expf(score(j) - mx);
+  sum = group_sum<LPR>(sum);
   const float inv = 1.0f / sum;
-  for (int j = lane; j < ld; j += 64) prow[j] = j < cols ? Half<E>::from_f32(__expf(score(j) - mx) * inv) : (uint16_t)0;
+  if (live)
+    for (int j = lane; j < ld; j += LPR) prow[j] = j < cols ? Half<E>::from_f32(__expf(score(j) - mx) * inv) : (uint16_t)0;
 }
 
 // dS = P o (dP - rowsum(P o dP)) with P in the element type, dP fp32, dS rounded to the element type
 // (padding columns zeroed).  With keep_f32 the unrounded dS also replaces dP (the bias-component sums
-// are taken from it).  One wave per row.
-template <class E>
+// are taken from it).  LPR lanes per row as above.
+template <class E, int LPR>
 __global__ __launch_bounds__(64) void softmax_grad_rows16_kernel(const uint16_t* __restrict__ P, float* __restrict__ dP,
                                                                  uint16_t* __restrict__ dS, int rows, int cols, int ld,
                                                                  bool keep_f32) {
-  const size_t off = ((size_t)blockIdx.y * rows + blockIdx.x) * ld;
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x % LPR;
+  const int r_raw = blockIdx.x * (64 / LPR) + threadIdx.x / LPR;
+  const bool live = r_raw < rows;
+  const size_t off = ((size_t)blockIdx.y * rows + (live ? r_raw : rows - 1)) * ld;
   float dot = 0.0f;
-  for (int j = lane; j < cols; j += 64) dot = __builtin_fmaf(Half<E>::to_f32(P[off + j]), dP[off + j], dot);
-  dot = wave_sum(dot);
-  for (int j = lane; j < ld; j += 64) {
+  for (int j = lane; j < cols; j += LPR) dot = __builtin_fmaf(Half<E>::to_f32(P[off + j]), dP[off + j], dot);
+  dot = group_sum<LPR>(dot);
+  if (!live) return;
+  for (int j = lane; j < ld; j += LPR) {
     const float v = j < cols ? Half<E>::to_f32(P[off + j]) * (dP[off + j] - dot) : 0.0f;
     dS[off + j] = Half<E>::from_f32(v);
     if (keep_f32 && j < cols) dP[off + j] = v;
@@ -450,26 +473,44 @@ __global__ __launch_bounds__(64) void bias_grad_kernel(const float* __restrict__
 // dQ += Pooling^T(dA): token (y, x) gathers dA[a] / |window(a)| from every agent whose window holds
 // it (adaptive windows may overlap by one row / column).  thread = element of dQ.
 // ---------------------------------------------------------------------------
+// VEC = 4 (d a multiple of 4) or 1 channels per thread; count = units * N * d / VEC.
+template <int VEC>
 __global__ __launch_bounds__(256) void pool_grad_kernel(float* __restrict__ dQ, const float* __restrict__ dA, int N,
                                                         int n, int d, int gh, int gw, int ah, int aw, size_t count) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= count) return;
-  const int c = (int)(i % d);
-  const size_t t_all = i / d;
+  const int dv = d / VEC;
+  const int c = (int)(i % dv) * VEC;
+  const size_t t_all = i / dv;
   const int t = (int)(t_all % N), u = (int)(t_all / N);
   const int y = t / gw, x = t - y * gw;
-  const int ayc = (int)(((unsigned)y * (unsigned)ah) / (unsigned)gh), axc = (int)(((unsigned)x * (unsigned)aw) / (unsigned)gw);
-  float v = dQ[i];
-  for (int ay = max(0, ayc - 1); ay <= min(ah - 1, ayc + 1); ++ay) {
-    const int y0 = pool_win_lo(ay, gh, ah), y1 = pool_win_hi(ay, gh, ah);
-    if (y < y0 || y >= y1) continue;
-    for (int ax = max(0, axc - 1); ax <= min(aw - 1, axc + 1); ++ax) {
-      const int x0 = pool_win_lo(ax, gw, aw), x1 = pool_win_hi(ax, gw, aw);
-      if (x < x0 || x >= x1) continue;
-      v += dA[((size_t)u * n + (size_t)ay * aw + ax) * d + c] / (float)((y1 - y0) * (x1 - x0));
+  float v[VEC];
+  float* q = dQ + t_all * d + c;
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) v[k] = q[k];
+  auto add = [&](int ay, int ax, int cnt) {
+    const float inv = 1.0f / (float)cnt;
+    const float* a = dA + ((size_t)u * n + (size_t)ay * aw + ax) * d + c;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) v[k] += a[k] * inv;
+  };
+  if (gh % ah == 0 && gw % aw == 0) {      // disjoint equal windows: one agent per token
+    const int wh = gh / ah, ww = gw / aw;
+    add(y / wh, x / ww, wh * ww);
+  } else {
+    const int ayc = (int)(((unsigned)y * (unsigned)ah) / (unsigned)gh), axc = (int)(((unsigned)x * (unsigned)aw) / (unsigned)gw);
+    for (int ay = max(0, ayc - 1); ay <= min(ah - 1, ayc + 1); ++ay) {
+      const int y0 = pool_win_lo(ay, gh, ah), y1 = pool_win_hi(ay, gh, ah);
+      if (y < y0 || y >= y1) continue;
+      for (int ax = max(0, axc - 1); ax <= min(aw - 1, axc + 1); ++ax) {
+        const int x0 = pool_win_lo(ax, gw, aw), x1 = pool_win_hi(ax, gw, aw);
+        if (x < x0 || x >= x1) continue;
+        add(ay, ax, (y1 - y0) * (x1 - x0));
+      }
     }
   }
-  dQ[i] = v;
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) q[k] = v[k];
 }
 
 template <bool TA, bool TB, bool ACC>
@@ -556,9 +597,15 @@ hipError_t backward_tail(const Problem& p, const float* Vf, const float* dOf, co
   if (agents_given) {
     AA_BWD_CHECK(from_f32(p.dtype, dAf, dA, u * nd, st));
   } else {
-    const size_t count = u * Nd;
-    pool_grad_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(dQf, dAf, N, n, d, p.gh, p.gw, p.ah,
-                                                                                 p.aw, count);
+    if (d % 4 == 0) {
+      const size_t count = u * Nd / 4;
+      pool_grad_kernel<4><<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(dQf, dAf, N, n, d, p.gh, p.gw,
+                                                                                      p.ah, p.aw, count);
+    } else {
+      const size_t count = u * Nd;
+      pool_grad_kernel<1><<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(dQf, dAf, N, n, d, p.gh, p.gw,
+                                                                                      p.ah, p.aw, count);
+    }
   }
   AA_BWD_CHECK(from_f32(p.dtype, dQf, dQ, u * Nd, st));
   AA_BWD_CHECK(from_f32(p.dtype, dKf, dK, u * Nd, st));
@@ -596,21 +643,35 @@ hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, 
 
   // forward recompute
   AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(Ah, Kh, F1, n, N, d, d, d, ldN, nd, Nd, s1, U, p.scale1, st)));
-  softmax_rows16_kernel<E, 1><<<dim3(n, U), dim3(64), 0, st>>>(F1, P1h, n, N, ldN, p.b1, p.heads, n, p.gh, p.gw);
+  // rows of up to 64 elements get 16 lanes each (four rows per wave)
+  auto rows_grid = [&](int rows, int lpr) { return dim3((unsigned)(((size_t)rows * lpr + 63) / 64), U); };
+  if (N <= 64)
+    softmax_rows16_kernel<E, 1, 16><<<rows_grid(n, 16), dim3(64), 0, st>>>(F1, P1h, n, N, ldN, p.b1, p.heads, n, p.gh, p.gw);
+  else
+    softmax_rows16_kernel<E, 1, 64><<<rows_grid(n, 64), dim3(64), 0, st>>>(F1, P1h, n, N, ldN, p.b1, p.heads, n, p.gh, p.gw);
   AA_BWD_CHECK((mfma_matmul<E, false, false, 2>(P1h, Vh, VAh, n, d, N, ldN, d, d, s1, Nd, nd, U, 1.0f, st)));
   AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(Qh, Ah, F2, N, n, d, d, d, ldn, Nd, nd, s2, U, p.scale2, st)));
-  softmax_rows16_kernel<E, 2><<<dim3(N, U), dim3(64), 0, st>>>(F2, P2h, N, n, ldn, p.b2, p.heads, n, p.gh, p.gw);
+  if (n <= 64)
+    softmax_rows16_kernel<E, 2, 16><<<rows_grid(N, 16), dim3(64), 0, st>>>(F2, P2h, N, n, ldn, p.b2, p.heads, n, p.gh, p.gw);
+  else
+    softmax_rows16_kernel<E, 2, 64><<<rows_grid(N, 64), dim3(64), 0, st>>>(F2, P2h, N, n, ldn, p.b2, p.heads, n, p.gh, p.gw);
 
   // broadcast stage
   AA_BWD_CHECK((mfma_matmul<E, true, false, 2>(P2h, dOh, dVAh, n, d, N, ldn, d, d, s2, Nd, nd, U, 1.0f, st)));
   AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(dOh, VAh, F2, N, n, d, d, d, ldn, Nd, nd, s2, U, 1.0f, st)));
-  softmax_grad_rows16_kernel<E><<<dim3(N, U), dim3(64), 0, st>>>(P2h, F2, dS2h, N, n, ldn, want_db2);
+  if (n <= 64)
+    softmax_grad_rows16_kernel<E, 16><<<rows_grid(N, 16), dim3(64), 0, st>>>(P2h, F2, dS2h, N, n, ldn, want_db2);
+  else
+    softmax_grad_rows16_kernel<E, 64><<<rows_grid(N, 64), dim3(64), 0, st>>>(P2h, F2, dS2h, N, n, ldn, want_db2);
   AA_BWD_CHECK((mfma_matmul<E, false, false, 0>(dS2h, Ah, dQf, N, d, n, ldn, d, d, s2, nd, Nd, U, p.scale2, st)));
   AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(dS2h, Qh, dAf, n, d, N, ldn, d, d, s2, Nd, nd, U, p.scale2, st)));
 
   // aggregation stage
   AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(dVAh, Vh, F1, n, N, d, d, d, ldN, nd, Nd, s1, U, 1.0f, st)));
-  softmax_grad_rows16_kernel<E><<<dim3(n, U), dim3(64), 0, st>>>(P1h, F1, dS1h, n, N, ldN, want_db1);
+  if (N <= 64)
+    softmax_grad_rows16_kernel<E, 16><<<rows_grid(n, 16), dim3(64), 0, st>>>(P1h, F1, dS1h, n, N, ldN, want_db1);
+  else
+    softmax_grad_rows16_kernel<E, 64><<<rows_grid(n, 64), dim3(64), 0, st>>>(P1h, F1, dS1h, n, N, ldN, want_db1);
   AA_BWD_CHECK((mfma_matmul<E, false, false, 1>(dS1h, Kh, dAf, n, d, N, ldN, d, d, s1, Nd, nd, U, p.scale1, st)));
   AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(dS1h, Ah, dKf, N, d, n, ldN, d, d, s1, nd, Nd, U, p.scale1, st)));
   AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(P1h, dVAh, dVf, N, d, n, ldN, d, d, s1, nd, Nd, U, 1.0f, st)));
