@@ -230,18 +230,23 @@ template <class E, bool TA, bool TB, int OUT>
 __global__ __launch_bounds__(256) void mfma_matmul_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
                                                           void* __restrict__ C, int M, int Nc, int Kd, int lda, int ldb,
                                                           int ldc, size_t strideA, size_t strideB, size_t strideC,
-                                                          float alpha) {
+                                                          float alpha, int ksplit, int kchunk) {
   __shared__ __attribute__((aligned(16))) uint16_t As[64][kLdsK];
   __shared__ __attribute__((aligned(16))) uint16_t Bs[64][kLdsK];
-  const int u = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // blockIdx.z = unit * ksplit + k-slice; with ksplit > 1 every slice writes its own partial result
+  // (C then points at a scratch of [units * ksplit] matrices, strideC = M * ldc) and a second kernel adds
+  // the slices up in order
+  const int u = blockIdx.z / ksplit, ks = blockIdx.z - u * ksplit;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int row0 = blockIdx.y * 64, col0 = blockIdx.x * 64;
   const uint16_t* Au = A + (size_t)u * strideA;
   const uint16_t* Bu = B + (size_t)u * strideB;
   const int wm = wave >> 1, wn = wave & 1, r = lane & 15, g = lane >> 4;
   f32x4 acc[2][2] = {};
-  for (int k0 = 0; k0 < Kd; k0 += 32) {
-    mfma_stage_tile<E, TA>(Au, lda, M, Kd, row0, k0, As, tid);
-    mfma_stage_tile<E, !TB>(Bu, ldb, Nc, Kd, col0, k0, Bs, tid);
+  const int kbeg = ks * kchunk, kend = min(Kd, kbeg + kchunk);
+  for (int k0 = kbeg; k0 < kend; k0 += 32) {
+    mfma_stage_tile<E, TA>(Au, lda, M, kend, row0, k0, As, tid);
+    mfma_stage_tile<E, !TB>(Bu, ldb, Nc, kend, col0, k0, Bs, tid);
     __syncthreads();
     u32x4 a[2], b[2];
 #pragma unroll
@@ -265,7 +270,7 @@ __global__ __launch_bounds__(256) void mfma_matmul_kernel(const uint16_t* __rest
       for (int e = 0; e < 4; ++e) {
         const int gm = row0 + 32 * wm + 16 * i + 4 * g + e;
         if (gm >= M) continue;
-        const size_t o = (size_t)u * strideC + (size_t)gm * ldc + gc;
+        const size_t o = (size_t)blockIdx.z * strideC + (size_t)gm * ldc + gc;
         const float v = alpha * acc[i][j][e];
         if constexpr (OUT == 0) ((float*)C)[o] = v;
         if constexpr (OUT == 1) ((float*)C)[o] += v;
@@ -549,12 +554,47 @@ hipError_t from_f32(int dtype, const float* src, void* dst, size_t count, hipStr
   return hipGetLastError();
 }
 
+// Sum of the ksplit partial results of a k-sliced product, in slice order, into C with the product's
+// output mode.  thread = one element; grid covers units * M * Nc.
+template <class E, int OUT>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, void* __restrict__ C, int M,
+                                                            int Nc, int ldc, size_t strideC, int ksplit, size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  const size_t mn = (size_t)M * Nc, u = i / mn, e = i - u * mn;
+  float v = 0.0f;
+  for (int k = 0; k < ksplit; ++k) v += part[(u * ksplit + k) * mn + e];
+  const size_t o = u * strideC + (e / Nc) * ldc + (e % Nc);
+  if constexpr (OUT == 0) ((float*)C)[o] = v;
+  if constexpr (OUT == 1) ((float*)C)[o] += v;
+  if constexpr (OUT == 2) ((uint16_t*)C)[o] = Half<E>::from_f32(v);
+}
+
+// scratch: room for the partial results of a k-sliced product (floats), or null / 0 to forbid slicing.
+// A product with few output tiles and a long k range is cut into slices so that it fills the chip.
 template <class E, bool TA, bool TB, int OUT>
 hipError_t mfma_matmul(const uint16_t* A, const uint16_t* B, void* C, int M, int Nc, int Kd, int lda, int ldb, int ldc,
-                       size_t strideA, size_t strideB, size_t strideC, int units, float alpha, hipStream_t st) {
-  const dim3 grid((Nc + 63) / 64, (M + 63) / 64, units);
-  mfma_matmul_kernel<E, TA, TB, OUT><<<grid, dim3(256), 0, st>>>(A, B, C, M, Nc, Kd, lda, ldb, ldc, strideA, strideB,
-                                                                strideC, alpha);
+                       size_t strideA, size_t strideB, size_t strideC, int units, float alpha, hipStream_t st,
+                       float* scratch = nullptr, size_t scratch_floats = 0) {
+  const int tiles = ((Nc + 63) / 64) * ((M + 63) / 64);
+  int ksplit = 1;
+  if (scratch) {
+    while (ksplit < 32 && (size_t)tiles * units * ksplit < 1024 && Kd / (ksplit * 2) >= 128 &&
+           (size_t)units * (ksplit * 2) * M * Nc <= scratch_floats)
+      ksplit *= 2;
+  }
+  const int kchunk = ((Kd + ksplit - 1) / ksplit + 31) / 32 * 32;
+  const dim3 grid((Nc + 63) / 64, (M + 63) / 64, units * ksplit);
+  if (ksplit == 1) {
+    mfma_matmul_kernel<E, TA, TB, OUT><<<grid, dim3(256), 0, st>>>(A, B, C, M, Nc, Kd, lda, ldb, ldc, strideA, strideB,
+                                                                  strideC, alpha, 1, kchunk);
+    return hipGetLastError();
+  }
+  mfma_matmul_kernel<E, TA, TB, 0><<<grid, dim3(256), 0, st>>>(A, B, scratch, M, Nc, Kd, lda, ldb, Nc, strideA, strideB,
+                                                                (size_t)M * Nc, alpha, ksplit, kchunk);
+  const size_t count = (size_t)units * M * Nc;
+  splitk_reduce_kernel<E, OUT><<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(scratch, C, M, Nc, ldc, strideC,
+                                                                                             ksplit, count);
   return hipGetLastError();
 }
 
@@ -649,7 +689,7 @@ hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, 
     softmax_rows16_kernel<E, 1, 16><<<rows_grid(n, 16), dim3(64), 0, st>>>(F1, P1h, n, N, ldN, p.b1, p.heads, n, p.gh, p.gw);
   else
     softmax_rows16_kernel<E, 1, 64><<<rows_grid(n, 64), dim3(64), 0, st>>>(F1, P1h, n, N, ldN, p.b1, p.heads, n, p.gh, p.gw);
-  AA_BWD_CHECK((mfma_matmul<E, false, false, 2>(P1h, Vh, VAh, n, d, N, ldN, d, d, s1, Nd, nd, U, 1.0f, st)));
+  AA_BWD_CHECK((mfma_matmul<E, false, false, 2>(P1h, Vh, VAh, n, d, N, ldN, d, d, s1, Nd, nd, U, 1.0f, st, dKf, u * Nd)));
   AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(Qh, Ah, F2, N, n, d, d, d, ldn, Nd, nd, s2, U, p.scale2, st)));
   if (n <= 64)
     softmax_rows16_kernel<E, 2, 16><<<rows_grid(N, 16), dim3(64), 0, st>>>(F2, P2h, N, n, ldn, p.b2, p.heads, n, p.gh, p.gw);
@@ -657,14 +697,14 @@ hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, 
     softmax_rows16_kernel<E, 2, 64><<<rows_grid(N, 64), dim3(64), 0, st>>>(F2, P2h, N, n, ldn, p.b2, p.heads, n, p.gh, p.gw);
 
   // broadcast stage
-  AA_BWD_CHECK((mfma_matmul<E, true, false, 2>(P2h, dOh, dVAh, n, d, N, ldn, d, d, s2, Nd, nd, U, 1.0f, st)));
+  AA_BWD_CHECK((mfma_matmul<E, true, false, 2>(P2h, dOh, dVAh, n, d, N, ldn, d, d, s2, Nd, nd, U, 1.0f, st, dKf, u * Nd)));
   AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(dOh, VAh, F2, N, n, d, d, d, ldn, Nd, nd, s2, U, 1.0f, st)));
   if (n <= 64)
     softmax_grad_rows16_kernel<E, 16><<<rows_grid(N, 16), dim3(64), 0, st>>>(P2h, F2, dS2h, N, n, ldn, want_db2);
   else
     softmax_grad_rows16_kernel<E, 64><<<rows_grid(N, 64), dim3(64), 0, st>>>(P2h, F2, dS2h, N, n, ldn, want_db2);
   AA_BWD_CHECK((mfma_matmul<E, false, false, 0>(dS2h, Ah, dQf, N, d, n, ldn, d, d, s2, nd, Nd, U, p.scale2, st)));
-  AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(dS2h, Qh, dAf, n, d, N, ldn, d, d, s2, Nd, nd, U, p.scale2, st)));
+  AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(dS2h, Qh, dAf, n, d, N, ldn, d, d, s2, Nd, nd, U, p.scale2, st, dKf, u * Nd)));
 
   // aggregation stage
   AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(dVAh, Vh, F1, n, N, d, d, d, ldN, nd, Nd, s1, U, 1.0f, st)));
@@ -672,7 +712,7 @@ hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, 
     softmax_grad_rows16_kernel<E, 16><<<rows_grid(n, 16), dim3(64), 0, st>>>(P1h, F1, dS1h, n, N, ldN, want_db1);
   else
     softmax_grad_rows16_kernel<E, 64><<<rows_grid(n, 64), dim3(64), 0, st>>>(P1h, F1, dS1h, n, N, ldN, want_db1);
-  AA_BWD_CHECK((mfma_matmul<E, false, false, 1>(dS1h, Kh, dAf, n, d, N, ldN, d, d, s1, Nd, nd, U, p.scale1, st)));
+  AA_BWD_CHECK((mfma_matmul<E, false, false, 1>(dS1h, Kh, dAf, n, d, N, ldN, d, d, s1, Nd, nd, U, p.scale1, st, dKf, u * Nd)));
   AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(dS1h, Ah, dKf, N, d, n, ldN, d, d, s1, nd, Nd, U, p.scale1, st)));
   AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(P1h, dVAh, dVf, N, d, n, ldN, d, d, s1, nd, Nd, U, 1.0f, st)));
 
