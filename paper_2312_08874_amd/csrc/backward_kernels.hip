@@ -279,6 +279,8 @@ __global__ __launch_bounds__(256) void mfma_matmul_kernel(const uint16_t* __rest
     }
 }
 
+constexpr int kRowCache = 16;      // row elements a lane keeps in registers in the row kernels
+
 // reductions over groups of LPR consecutive lanes (LPR a power of two)
 template <int LPR>
 __device__ __forceinline__ float group_max(float v) {
@@ -326,15 +328,51 @@ __global__ __launch_bounds__(64) void softmax_rows16_kernel(const float* __restr
     if (biased) v += KIND == 1 ? bias1_at(hb, r, j / gw, j % gw, gh, gw) : bias2_at(hb, j, r / gw, r % gw, gh, gw, n);
     return v;
   };
-  float mx = -INFINITY;
-  for (int j = lane; j < cols; j += LPR) mx = fmaxf(mx, score(j));
-  mx = group_max<LPR>(mx);
-  float sum = 0.0f;
-  for (int j = lane; j < cols; j += LPR) sum += __expf(score(j) - mx);
-  sum = group_sum<LPR>(sum);
+  if (cols <= LPR * kRowCache) {
+    // short row: every score is read (and its bias evaluated) once and kept in registers
+    float c[kRowCache];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kRowCache; ++k) {
+      const int j = lane + k * LPR;
+      c[k] = j < cols ? score(j) : -INFINITY;
+      mx = fmaxf(mx, c[k]);
+    }
+    mx = group_max<LPR>(mx);
+    float sum = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kRowCache; ++k) {
+      c[k] = __expf(c[k] - mx);      // 0 beyond the row
+      sum += c[k];
+    }
+    sum = group_sum<LPR>(sum);
+    const float inv = 1.0f / sum;
+    if (live) {
+#pragma unroll
+      for (int k = 0; k < kRowCache; ++k) {
+        const int j = lane + k * LPR;
+        if (j < ld) prow[j] = Half<E>::from_f32(c[k] * inv);
+      }
+    }
+    return;
+  }
+  // long row: one pass for the maximum and the sum together (running maximum per lane, rescaled sum),
+  // a second pass to write
+  float mx = -INFINITY, sum = 0.0f;
+  for (int j = lane; j < cols; j += LPR) {
+    const float v = score(j);
+    if (v > mx) {
+      sum = sum * __expf(mx - v) + 1.0f;      // exp(-inf) = 0 on the first element
+      mx = v;
+    } else {
+      sum += __expf(v - mx);
+    }
+  }
+  const float gmx = group_max<LPR>(mx);
+  sum = group_sum<LPR>(mx == -INFINITY ? 0.0f : sum * __expf(mx - gmx));
   const float inv = 1.0f / sum;
   if (live)
-    for (int j = lane; j < ld; j += LPR) prow[j] = j < cols ? Half<E>::from_f32(__expf(score(j) - mx) * inv) : (uint16_t)0;
+    for (int j = lane; j < ld; j += LPR) prow[j] = j < cols ? Half<E>::from_f32(__expf(score(j) - gmx) * inv) : (uint16_t)0;
 }
 
 // dS = P o (dP - rowsum(P o dP)) with P in the element type, dP fp32, dS rounded to the element type
@@ -348,6 +386,29 @@ __global__ __launch_bounds__(64) void softmax_grad_rows16_kernel(const uint16_t*
   const int r_raw = blockIdx.x * (64 / LPR) + threadIdx.x / LPR;
   const bool live = r_raw < rows;
   const size_t off = ((size_t)blockIdx.y * rows + (live ? r_raw : rows - 1)) * ld;
+  if (cols <= LPR * kRowCache) {      // short row: P and dP are read once
+    float pc[kRowCache], gc[kRowCache];
+    float dot = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kRowCache; ++k) {
+      const int j = lane + k * LPR;
+      pc[k] = j < cols ? Half<E>::to_f32(P[off + j]) : 0.0f;
+      gc[k] = j < cols ? dP[off + j] : 0.0f;
+      dot = __builtin_fmaf(pc[k], gc[k], dot);
+    }
+    dot = group_sum<LPR>(dot);
+    if (!live) return;
+#pragma unroll
+    for (int k = 0; k < kRowCache; ++k) {
+      const int j = lane + k * LPR;
+      if (j < ld) {
+        const float v = pc[k] * (gc[k] - dot);      // 0 in the padding columns
+        dS[off + j] = Half<E>::from_f32(v);
+        if (keep_f32 && j < cols) dP[off + j] = v;
+      }
+    }
+    return;
+  }
   float dot = 0.0f;
   for (int j = lane; j < cols; j += LPR) dot = __builtin_fmaf(Half<E>::to_f32(P[off + j]), dP[off + j], dot);
   dot = group_sum<LPR>(dot);

@@ -10,6 +10,11 @@ Three runs of the same workload are expected in one directory (names are the -o 
 usage: python profile_summary.py DIR W
 writes profiles/W_kernels.md and updates profiles/traffic.json (read back by bench.py for roofline.traffic).
 
+usage: python profile_summary.py DIR W backward
+DIR holds one run with the backward pass timed as well:
+  rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload W --no-others --no-cpu-baseline --backward --steps 30 --warmup 5
+writes profiles/W_backward_kernels.md (durations of the backward pass's kernels only).
+
 HBM bytes: FETCH_SIZE / WRITE_SIZE are reported in KiB per dispatch; both are scaled by what the same
 counter reads for the plain 1 GiB device-to-device copy that --copy-calibration runs (it moves exactly
 1 GiB in and 1 GiB out), so a mis-scaled counter cancels out.
@@ -75,8 +80,45 @@ def calibration(values_by_kernel):
     return best
 
 
+BACKWARD_KERNELS = ("matmul_kernel", "mfma_matmul_kernel", "splitk_reduce_kernel", "softmax_rows", "softmax_grad_rows",
+                    "value_extras_kernel", "dwc_param_grad_kernel", "bias_grad_kernel", "pool_grad_kernel", "to_f32_kernel",
+                    "from_f32_kernel")
+
+
+def backward_summary(d, wl):
+    cmd = ("rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload %s "
+           "--no-others --no-cpu-baseline --backward --steps 30 --warmup 5" % wl)
+    lines = ["# rocprofv3 summary: backward pass, bench.py --workload %s --backward (one MI355X)" % wl, "",
+             "command: `%s`" % cmd, "",
+             "Kernels of `agent_attn_bwd` only (the run also times the forward pass; its kernels are in "
+             "`%s_kernels.md`).  `us per backward` = calls x avg / number of backward calls." % wl, "",
+             "| kernel | calls | avg us | us per backward |", "|---|---|---|---|"]
+    rows = []
+    with open(os.path.join(d, "stats_kernel_stats.csv")) as f:
+        for r in csv.DictReader(f):
+            name = r["Name"].replace("void ", "").replace("aa::(anonymous namespace)::", "").replace("aa::", "")
+            name = re.sub(r"\(.*", "", name)
+            if name.startswith(BACKWARD_KERNELS):
+                rows.append((name, int(r["Calls"]), float(r["AverageNs"]) / 1e3))
+    ncalls = min(c for n, c, a in rows if n.startswith("pool_grad_kernel") or n.startswith("from_f32_kernel")) if rows else 1
+    pg = [c for n, c, a in rows if n.startswith("pool_grad_kernel")]
+    ncalls = pg[0] if pg else ncalls
+    total = 0.0
+    for name, calls, avg in rows:
+        per = calls * avg / ncalls
+        total += per
+        lines.append("| `%s` | %d | %.1f | %.1f |" % (name, calls, avg, per))
+    lines += ["", "sum over the kernels: %.1f us per backward call (%d calls)" % (total, ncalls)]
+    with open(os.path.join(ROOT, "profiles", "%s_backward_kernels.md" % wl), "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print("\n".join(lines))
+
+
 def main():
     d, wl = sys.argv[1], sys.argv[2]
+    if len(sys.argv) > 3 and sys.argv[3] == "backward":
+        backward_summary(d, wl)
+        return
     lines = ["# rocprofv3 summary: bench.py --workload %s (one MI355X)" % wl, ""]
     stats_path = os.path.join(d, "stats_kernel_stats.csv")
     lines += ["## kernel durations (--kernel-trace --stats)", "",
