@@ -37,6 +37,7 @@ struct Plan {
   size_t off_A;        // pooled agents, element type of the problem
   size_t off_acc, off_m, off_l;
   size_t off_VA;       // merged V_A, fp32
+  size_t off_B1d, off_B2d;   // dense agent bias (0 = not built)
   size_t total;
 };
 
@@ -168,7 +169,11 @@ void plan_large(const aa_desc* d, Plan& pl) {
     pl.bcast_waves_large = tuning_env("AA_LARGE_BWAVES");
 }
 
-Plan make_plan(const aa_desc* d) {
+// The dense form of the agent bias is built in the workspace when it stays below this size per kind
+// (it is read once per batch element; beyond the cap the kernels evaluate the components per score).
+constexpr size_t kBiasDenseCapBytes = (size_t)2 << 30;
+
+Plan make_plan(const aa_desc* d, const aa_params* params = nullptr) {
   Plan pl{};
   const size_t units = (size_t)d->batch * d->heads;
   pl.S = choose_splits(d);
@@ -187,6 +192,22 @@ Plan make_plan(const aa_desc* d) {
   off += align_up(units * Smax * d->n * sizeof(float));
   pl.off_VA = off;
   off += align_up(units * d->n * d->d * sizeof(float));
+  pl.off_B1d = pl.off_B2d = 0;
+  const bool dense_ok = d->grid_h > 0 && d->dtype != AA_F32;      // the MFMA kernels are the ones that read it
+  if (params && dense_ok && (params->b1_col || params->b1_row || params->b1_blk)) {
+    const size_t bytes = aa::bias_dense_floats(1, d->heads, d->n, d->N) * sizeof(float);
+    if (bytes <= kBiasDenseCapBytes) {
+      pl.off_B1d = off;
+      off += align_up(bytes);
+    }
+  }
+  if (params && dense_ok && (params->b2_col || params->b2_row || params->b2_blk)) {
+    const size_t bytes = aa::bias_dense_floats(2, d->heads, d->n, d->N) * sizeof(float);
+    if (bytes <= kBiasDenseCapBytes) {
+      pl.off_B2d = off;
+      off += align_up(bytes);
+    }
+  }
   pl.total = off;
   return pl;
 }
@@ -336,6 +357,26 @@ aa_status run_broadcast(const Problem& pr, const void* Q, const void* A, const f
   return AA_OK;
 }
 
+// Build the dense agent bias in the workspace (when the plan reserved room for it and the MFMA kernels
+// will run) and point the problem's bias arguments at it.
+aa_status prepare_dense_bias(Problem& pr, const Plan& pl, void* workspace, bool mfma_path, hipStream_t st) {
+  if (!mfma_path) return AA_OK;
+  char* ws = (char*)workspace;
+  if (pl.off_B1d && pr.b1.any()) {
+    float* d1 = (float*)(ws + pl.off_B1d);
+    AA_HIP(aa::launch_bias_dense(pr, 1, d1, st));
+    pr.b1.dense = d1;
+    pr.b1.ld = aa::round_up64(pr.N);
+  }
+  if (pl.off_B2d && pr.b2.any()) {
+    float* d2 = (float*)(ws + pl.off_B2d);
+    AA_HIP(aa::launch_bias_dense(pr, 2, d2, st));
+    pr.b2.dense = d2;
+    pr.b2.ld = aa::round_up64(pr.n);
+  }
+  return AA_OK;
+}
+
 aa_status run_pool(const Problem& pr, const void* Q, void* A, hipStream_t st) {
   if (use_small(pr, {Q, A}))
     AA_HIP(aa::launch_small_pool(pr, Q, A, st));
@@ -353,7 +394,7 @@ extern "C" {
 size_t agent_attn_workspace_bytes(const aa_desc* desc, const aa_params* params) {
   if (check_desc(desc, params_use_grid(params), false) != AA_OK) return 0;
   if (check_params(params) != AA_OK) return 0;
-  return make_plan(desc).total;
+  return make_plan(desc, params).total;
 }
 
 uint64_t agent_attn_flops(const aa_desc* desc) {
@@ -381,7 +422,7 @@ aa_status agent_aggregate_fwd(const aa_desc* desc, const void* A, const void* K,
   st = check_params(params);
   if (st != AA_OK) return st;
   if (!A || !K || !V || !VA_out) return AA_ERR_NULL;
-  const Plan pl = make_plan(desc);
+  const Plan pl = make_plan(desc, params);
   st = check_workspace(workspace, workspace_bytes, pl);
   if (st != AA_OK) return st;
   const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
@@ -393,6 +434,9 @@ aa_status agent_aggregate_fwd(const aa_desc* desc, const void* A, const void* K,
     return AA_ERR_ALIAS;
   Problem pr = make_problem(desc, params);
   pr.b2 = aa::BiasArgs{};
+  st = prepare_dense_bias(pr, pl, workspace, use_small(pr, {A, K, V}) || use_large(pr, {A, K, V}),
+                          (hipStream_t)hip_stream);
+  if (st != AA_OK) return st;
   return run_aggregate(pr, A, K, V, workspace, pl, VA_out, (hipStream_t)hip_stream);
 }
 
@@ -427,7 +471,7 @@ aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, cons
   st = check_params(params);
   if (st != AA_OK) return st;
   if (!Q || !K || !V || !out) return AA_ERR_NULL;
-  const Plan pl = make_plan(desc);
+  const Plan pl = make_plan(desc, params);
   st = check_workspace(workspace, workspace_bytes, pl);
   if (st != AA_OK) return st;
   const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
@@ -439,9 +483,11 @@ aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, cons
       overlaps(workspace, workspace_bytes, A, units * desc->n * desc->d * es))
     return AA_ERR_ALIAS;
 
-  const Problem pr = make_problem(desc, params);
+  Problem pr = make_problem(desc, params);
   hipStream_t stream = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
+  st = prepare_dense_bias(pr, pl, workspace, use_small(pr, {Q, K, V, A, out}) || use_large(pr, {Q, K, V, A, out}), stream);
+  if (st != AA_OK) return st;
   if (pl.prefer_fused && aa::small_fused_supported(pr) && use_small(pr, {Q, K, V, A, out})) {
     AA_HIP(aa::launch_small_fused(pr, Q, K, V, A, out, stream));
     return AA_OK;

@@ -57,13 +57,21 @@ struct Layout {
 // Block resize: bilinear, half-pixel centres, source coordinate clamped at 0,
 // upper neighbour clamped to the last sample.
 // ---------------------------------------------------------------------------
+// `dense`, when set, is the same bias already evaluated for every (agent, token) pair, multiplied by
+// log2(e) and padded so that the MFMA kernels can read it in 16-byte pieces without masks:
+//   kind 1: dense[a * ld + t], a < roundup64(n), t < ld = roundup64(N); -inf for t >= N, 0 for a >= n
+//   kind 2: dense[t * ld + a], t < N, a < ld = roundup64(n); -inf for a >= n
+// (per head: kind 1 heads are roundup64(n) * ld apart, kind 2 heads N * ld).
 struct BiasArgs {
   const float* col;
   const float* row;
   const float* blk;
   int h0, w0;
+  const float* dense;
+  int ld;
   __host__ __device__ bool any() const { return col || row || blk; }
 };
+__host__ __device__ inline int round_up64(int v) { return (v + 63) / 64 * 64; }
 
 __device__ __forceinline__ void bilinear_coord(int dst, int L, int L0, int& i0, int& i1, float& f) {
   float s = ((float)dst + 0.5f) * ((float)L0 / (float)L) - 0.5f;

@@ -286,6 +286,62 @@ __global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
     default: return hipErrorInvalidValue;              \
   }
 
+// ---------------------------------------------------------------------------
+// Agent bias evaluated once for all (agent, token) pairs of every head (Appendix B), in the padded
+// layouts described at BiasArgs.  thread = one element.
+// ---------------------------------------------------------------------------
+template <int KIND>
+__global__ __launch_bounds__(256) void bias_dense_kernel(BiasArgs b, float* __restrict__ out, int heads, int n, int N,
+                                                         int gh, int gw, size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  const int NA = round_up64(n), NT = round_up64(N);
+  int hd, a, t;
+  if (KIND == 1) {
+    t = (int)(i % NT);
+    a = (int)((i / NT) % NA);
+    hd = (int)(i / ((size_t)NT * NA));
+  } else {
+    a = (int)(i % NA);
+    t = (int)((i / NA) % N);
+    hd = (int)(i / ((size_t)NA * N));
+  }
+  float v;
+  if (t >= N || (KIND == 2 && a >= n)) {
+    v = -INFINITY;
+  } else if (a >= n) {
+    v = 0.0f;
+  } else {
+    BiasArgs hb = b;
+    if (KIND == 1) {
+      if (hb.col) hb.col += (size_t)hd * n * gw;
+      if (hb.row) hb.row += (size_t)hd * n * gh;
+      if (hb.blk) hb.blk += (size_t)hd * n * hb.h0 * hb.w0;
+      v = kLog2e * bias1_at(hb, a, t / gw, t % gw, gh, gw);
+    } else {
+      if (hb.col) hb.col += (size_t)hd * gw * n;
+      if (hb.row) hb.row += (size_t)hd * gh * n;
+      if (hb.blk) hb.blk += (size_t)hd * hb.h0 * hb.w0 * n;
+      v = kLog2e * bias2_at(hb, a, t / gw, t % gw, gh, gw, n);
+    }
+  }
+  out[i] = v;
+}
+
+size_t bias_dense_floats(int kind, int heads, int n, int N) {
+  return kind == 1 ? (size_t)heads * round_up64(n) * round_up64(N) : (size_t)heads * N * round_up64(n);
+}
+
+hipError_t launch_bias_dense(const Problem& p, int kind, float* out, hipStream_t st) {
+  const size_t count = bias_dense_floats(kind, p.heads, p.n, p.N);
+  const dim3 grid((unsigned)((count + 255) / 256));
+  if (kind == 1)
+    bias_dense_kernel<1><<<grid, dim3(256), 0, st>>>(p.b1, out, p.heads, p.n, p.N, p.gh, p.gw, count);
+  else
+    bias_dense_kernel<2><<<grid, dim3(256), 0, st>>>(p.b2, out, p.heads, p.n, p.N, p.gh, p.gw, count);
+  return hipGetLastError();
+}
+
 hipError_t launch_pool_generic(const Problem& p, const void* Q, void* A, hipStream_t st) {
   dim3 grid(p.n, p.units);
   AA_DISPATCH_DTYPE(p.dtype, pool_generic_kernel<E><<<grid, dim3(64), 0, st>>>(

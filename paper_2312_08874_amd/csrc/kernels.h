@@ -34,6 +34,9 @@ struct Partials {
 hipError_t launch_pool_generic(const Problem& p, const void* Q, void* A, hipStream_t st);
 // fp16 / bf16, d a multiple of 8, Q and A 16-byte aligned: 16-byte loads, thread per (agent, 8 channels)
 hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, hipStream_t st);
+// agent bias of kind 1 (p.b1) or 2 (p.b2) evaluated for all pairs into the padded dense layout of BiasArgs
+size_t bias_dense_floats(int kind, int heads, int n, int N);
+hipError_t launch_bias_dense(const Problem& p, int kind, float* out, hipStream_t st);
 hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* K, const void* V,
                                     const Partials& part, hipStream_t st);
 hipError_t launch_merge_generic(const Problem& p, const Partials& part, float* VA, hipStream_t st);
