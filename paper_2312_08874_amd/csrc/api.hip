@@ -362,15 +362,14 @@ aa_status run_broadcast(const Problem& pr, const void* Q, const void* A, const f
 aa_status prepare_dense_bias(Problem& pr, const Plan& pl, void* workspace, bool mfma_path, hipStream_t st) {
   if (!mfma_path) return AA_OK;
   char* ws = (char*)workspace;
-  if (pl.off_B1d && pr.b1.any()) {
-    float* d1 = (float*)(ws + pl.off_B1d);
-    AA_HIP(aa::launch_bias_dense(pr, 1, d1, st));
+  float* d1 = (pl.off_B1d && pr.b1.any()) ? (float*)(ws + pl.off_B1d) : nullptr;
+  float* d2 = (pl.off_B2d && pr.b2.any()) ? (float*)(ws + pl.off_B2d) : nullptr;
+  AA_HIP(aa::launch_bias_dense(pr, d1, d2, st));
+  if (d1) {
     pr.b1.dense = d1;
     pr.b1.ld = aa::round_up64(pr.N);
   }
-  if (pl.off_B2d && pr.b2.any()) {
-    float* d2 = (float*)(ws + pl.off_B2d);
-    AA_HIP(aa::launch_bias_dense(pr, 2, d2, st));
+  if (d2) {
     pr.b2.dense = d2;
     pr.b2.ld = aa::round_up64(pr.n);
   }

@@ -291,10 +291,8 @@ __global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
 // layouts described at BiasArgs.  thread = one element.
 // ---------------------------------------------------------------------------
 template <int KIND>
-__global__ __launch_bounds__(256) void bias_dense_kernel(BiasArgs b, float* __restrict__ out, int heads, int n, int N,
-                                                         int gh, int gw, size_t count) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= count) return;
+__device__ __forceinline__ void bias_dense_element(const BiasArgs& b, float* __restrict__ out, int heads, int n, int N,
+                                                   int gh, int gw, size_t i) {
   const int NA = round_up64(n), NT = round_up64(N);
   int hd, a, t;
   if (KIND == 1) {
@@ -328,17 +326,31 @@ __global__ __launch_bounds__(256) void bias_dense_kernel(BiasArgs b, float* __re
   out[i] = v;
 }
 
+// One launch for both kinds: the first blocks1 blocks fill the kind-1 table (when out1 is set), the rest the
+// kind-2 table.
+__global__ __launch_bounds__(256) void bias_dense_kernel(BiasArgs b1, float* __restrict__ out1, size_t count1,
+                                                         unsigned blocks1, BiasArgs b2, float* __restrict__ out2,
+                                                         size_t count2, int heads, int n, int N, int gh, int gw) {
+  if (blockIdx.x < blocks1) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count1) bias_dense_element<1>(b1, out1, heads, n, N, gh, gw, i);
+  } else {
+    const size_t i = (size_t)(blockIdx.x - blocks1) * 256 + threadIdx.x;
+    if (i < count2) bias_dense_element<2>(b2, out2, heads, n, N, gh, gw, i);
+  }
+}
+
 size_t bias_dense_floats(int kind, int heads, int n, int N) {
   return kind == 1 ? (size_t)heads * round_up64(n) * round_up64(N) : (size_t)heads * N * round_up64(n);
 }
 
-hipError_t launch_bias_dense(const Problem& p, int kind, float* out, hipStream_t st) {
-  const size_t count = bias_dense_floats(kind, p.heads, p.n, p.N);
-  const dim3 grid((unsigned)((count + 255) / 256));
-  if (kind == 1)
-    bias_dense_kernel<1><<<grid, dim3(256), 0, st>>>(p.b1, out, p.heads, p.n, p.N, p.gh, p.gw, count);
-  else
-    bias_dense_kernel<2><<<grid, dim3(256), 0, st>>>(p.b2, out, p.heads, p.n, p.N, p.gh, p.gw, count);
+hipError_t launch_bias_dense(const Problem& p, float* out1, float* out2, hipStream_t st) {
+  const size_t count1 = out1 ? bias_dense_floats(1, p.heads, p.n, p.N) : 0;
+  const size_t count2 = out2 ? bias_dense_floats(2, p.heads, p.n, p.N) : 0;
+  const unsigned blocks1 = (unsigned)((count1 + 255) / 256), blocks2 = (unsigned)((count2 + 255) / 256);
+  if (blocks1 + blocks2 == 0) return hipSuccess;
+  bias_dense_kernel<<<dim3(blocks1 + blocks2), dim3(256), 0, st>>>(p.b1, out1, count1, blocks1, p.b2, out2, count2,
+                                                                   p.heads, p.n, p.N, p.gh, p.gw);
   return hipGetLastError();
 }
 

@@ -34,9 +34,10 @@ struct Partials {
 hipError_t launch_pool_generic(const Problem& p, const void* Q, void* A, hipStream_t st);
 // fp16 / bf16, d a multiple of 8, Q and A 16-byte aligned: 16-byte loads, thread per (agent, 8 channels)
 hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, hipStream_t st);
-// agent bias of kind 1 (p.b1) or 2 (p.b2) evaluated for all pairs into the padded dense layout of BiasArgs
+// agent bias of kind 1 (p.b1 -> out1) and / or 2 (p.b2 -> out2) evaluated for all pairs into the padded dense
+// layout of BiasArgs, in one launch; a null output skips that kind
 size_t bias_dense_floats(int kind, int heads, int n, int N);
-hipError_t launch_bias_dense(const Problem& p, int kind, float* out, hipStream_t st);
+hipError_t launch_bias_dense(const Problem& p, float* out1, float* out2, hipStream_t st);
 hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* K, const void* V,
                                     const Partials& part, hipStream_t st);
 hipError_t launch_merge_generic(const Problem& p, const Partials& part, float* VA, hipStream_t st);
