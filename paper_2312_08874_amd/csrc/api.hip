@@ -367,7 +367,7 @@ aa_status prepare_dense_bias(Problem& pr, const Plan& pl, void* workspace, bool 
   AA_HIP(aa::launch_bias_dense(pr, d1, d2, st));
   if (d1) {
     pr.b1.dense = d1;
-    pr.b1.ld = aa::round_up64(pr.N);
+    pr.b1.ld = aa::round_up64(pr.n);
   }
   if (d2) {
     pr.b2.dense = d2;

@@ -58,10 +58,12 @@ struct Layout {
 // upper neighbour clamped to the last sample.
 // ---------------------------------------------------------------------------
 // `dense`, when set, is the same bias already evaluated for every (agent, token) pair, multiplied by
-// log2(e) and padded so that the MFMA kernels can read it in 16-byte pieces without masks:
-//   kind 1: dense[a * ld + t], a < roundup64(n), t < ld = roundup64(N); -inf for t >= N, 0 for a >= n
-//   kind 2: dense[t * ld + a], t < N, a < ld = roundup64(n); -inf for a >= n
-// (per head: kind 1 heads are roundup64(n) * ld apart, kind 2 heads N * ld).
+// log2(e), padded so that the MFMA kernels can read it in 16-byte pieces without masks, and laid out so
+// that the 16 lanes of a group read consecutive pieces (ld = NA = roundup64(n), NT = roundup64(N)):
+//   kind 1: lanes hold agents, a piece is 4 consecutive tokens:  dense[((t/4) * NA + a) * 4 + t%4],
+//           a < NA, t < NT; -inf for t >= N, 0 for a >= n; heads are NA * NT apart
+//   kind 2: lanes hold tokens, a piece is 4 consecutive agents:  dense[((a/4) * N + t) * 4 + a%4],
+//           t < N, a < NA; -inf for a >= n; heads are NA * N apart
 struct BiasArgs {
   const float* col;
   const float* row;

@@ -295,13 +295,14 @@ __device__ __forceinline__ void bias_dense_element(const BiasArgs& b, float* __r
                                                    int gh, int gw, size_t i) {
   const int NA = round_up64(n), NT = round_up64(N);
   int hd, a, t;
-  if (KIND == 1) {
-    t = (int)(i % NT);
-    a = (int)((i / NT) % NA);
+  const int q = (int)(i & 3);
+  if (KIND == 1) {      // i = ((hd * NT/4 + t/4) * NA + a) * 4 + t%4
+    a = (int)((i >> 2) % NA);
+    t = 4 * (int)((i / (4 * (size_t)NA)) % (NT / 4)) + q;
     hd = (int)(i / ((size_t)NT * NA));
-  } else {
-    a = (int)(i % NA);
-    t = (int)((i / NA) % N);
+  } else {              // i = ((hd * NA/4 + a/4) * N + t) * 4 + a%4
+    t = (int)((i >> 2) % N);
+    a = 4 * (int)((i / (4 * (size_t)N)) % (NA / 4)) + q;
     hd = (int)(i / ((size_t)NA * N));
   }
   float v;
