@@ -38,6 +38,7 @@ struct Plan {
   size_t off_acc, off_m, off_l;
   size_t off_VA;       // merged V_A, fp32
   size_t off_B1d, off_B2d;   // dense agent bias (0 = not built)
+  size_t off_H1, off_R1, off_H2, off_R2;   // half-resized agent bias and its row component (0 = not built)
   size_t total;
 };
 
@@ -192,19 +193,29 @@ Plan make_plan(const aa_desc* d, const aa_params* params = nullptr) {
   off += align_up(units * Smax * d->n * sizeof(float));
   pl.off_VA = off;
   off += align_up(units * d->n * d->d * sizeof(float));
-  pl.off_B1d = pl.off_B2d = 0;
+  pl.off_B1d = pl.off_B2d = pl.off_H1 = pl.off_R1 = pl.off_H2 = pl.off_R2 = 0;
   const bool dense_ok = d->grid_h > 0 && d->dtype != AA_F32;      // the MFMA kernels are the ones that read it
-  if (params && dense_ok && (params->b1_col || params->b1_row || params->b1_blk)) {
-    const size_t bytes = aa::bias_dense_floats(1, d->heads, d->n, d->N) * sizeof(float);
-    if (bytes <= kBiasDenseCapBytes) {
-      pl.off_B1d = off;
-      off += align_up(bytes);
+  // Many agents: n * N bias values per head are too many to write and read back per call, so the
+  // large-agent kernels get the half-resized form (n * blk_h0 * w values) and interpolate along y.
+  const bool half_form = dense_ok && d->n > 64 && d->grid_w % 4 == 0;
+  for (int kind = 1; kind <= 2; ++kind) {
+    const bool any = params && (kind == 1 ? (params->b1_col || params->b1_row || params->b1_blk)
+                                          : (params->b2_col || params->b2_row || params->b2_blk));
+    if (!any || !dense_ok) continue;
+    if (half_form) {
+      const bool blk = kind == 1 ? params->b1_blk != nullptr : params->b2_blk != nullptr;
+      const bool row = kind == 1 ? params->b1_row != nullptr : params->b2_row != nullptr;
+      (kind == 1 ? pl.off_H1 : pl.off_H2) = off;
+      off += align_up(aa::bias_half_floats(d->heads, d->n, d->grid_w, blk ? params->blk_h0 : 1) * sizeof(float));
+      if (row) {
+        (kind == 1 ? pl.off_R1 : pl.off_R2) = off;
+        off += align_up(aa::bias_rows_floats(d->heads, d->n, d->grid_h) * sizeof(float));
+      }
+      continue;
     }
-  }
-  if (params && dense_ok && (params->b2_col || params->b2_row || params->b2_blk)) {
-    const size_t bytes = aa::bias_dense_floats(2, d->heads, d->n, d->N) * sizeof(float);
+    const size_t bytes = aa::bias_dense_floats(kind, d->heads, d->n, d->N) * sizeof(float);
     if (bytes <= kBiasDenseCapBytes) {
-      pl.off_B2d = off;
+      (kind == 1 ? pl.off_B1d : pl.off_B2d) = off;
       off += align_up(bytes);
     }
   }
@@ -365,6 +376,23 @@ aa_status prepare_dense_bias(Problem& pr, const Plan& pl, void* workspace, bool 
   float* d1 = (pl.off_B1d && pr.b1.any()) ? (float*)(ws + pl.off_B1d) : nullptr;
   float* d2 = (pl.off_B2d && pr.b2.any()) ? (float*)(ws + pl.off_B2d) : nullptr;
   AA_HIP(aa::launch_bias_dense(pr, d1, d2, st));
+  float* h1 = (pl.off_H1 && pr.b1.any()) ? (float*)(ws + pl.off_H1) : nullptr;
+  float* h2 = (pl.off_H2 && pr.b2.any()) ? (float*)(ws + pl.off_H2) : nullptr;
+  float* r1 = (h1 && pl.off_R1) ? (float*)(ws + pl.off_R1) : nullptr;
+  float* r2 = (h2 && pl.off_R2) ? (float*)(ws + pl.off_R2) : nullptr;
+  AA_HIP(aa::launch_bias_half(pr, h1, r1, h2, r2, st));
+  if (h1) {
+    pr.b1.half = h1;
+    pr.b1.rows = r1;
+    pr.b1.he = pr.b1.blk ? pr.b1.h0 : 1;
+    pr.b1.ld = aa::round_up64(pr.n);
+  }
+  if (h2) {
+    pr.b2.half = h2;
+    pr.b2.rows = r2;
+    pr.b2.he = pr.b2.blk ? pr.b2.h0 : 1;
+    pr.b2.ld = aa::round_up64(pr.n);
+  }
   if (d1) {
     pr.b1.dense = d1;
     pr.b1.ld = aa::round_up64(pr.n);

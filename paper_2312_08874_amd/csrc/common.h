@@ -64,6 +64,16 @@ struct Layout {
 //           a < NA, t < NT; -inf for t >= N, 0 for a >= n; heads are NA * NT apart
 //   kind 2: lanes hold tokens, a piece is 4 consecutive agents:  dense[((a/4) * N + t) * 4 + a%4],
 //           t < N, a < NA; -inf for a >= n; heads are NA * N apart
+// `half`, when set, is the cheaper form for large n * N: the column component plus the block component
+// already interpolated along x, and the row component, all times log2(e); the interpolation along y (two
+// rows of the table, weights from bilinear_coord) is left to the reader.  he = rows of the table per
+// agent (blk_h0, or 1 without a block component); NA = roundup64(n); w % 4 == 0 is required.  Readers
+// take four neighbours in x (kind 1) or four agents (kind 2) per 16-byte load, neighbouring lanes read
+// neighbouring pieces:
+//   kind 1: half[((i * w/4 + x/4) * NA + a) * 4 + x%4],  rows[y * NA + a]
+//   kind 2: half[((i * NA/4 + a/4) * w + x) * 4 + a%4],  rows[((a/4) * h + y) * 4 + a%4]
+// (per head he * w * NA and h * NA floats).  Padded agents hold 0; no masks are folded in.  rows is null
+// when there is no row component.
 struct BiasArgs {
   const float* col;
   const float* row;
@@ -71,6 +81,9 @@ struct BiasArgs {
   int h0, w0;
   const float* dense;
   int ld;
+  const float* half;
+  const float* rows;
+  int he;
   __host__ __device__ bool any() const { return col || row || blk; }
 };
 __host__ __device__ inline int round_up64(int v) { return (v + 63) / 64 * 64; }

@@ -341,6 +341,80 @@ __global__ __launch_bounds__(256) void bias_dense_kernel(BiasArgs b1, float* __r
   }
 }
 
+// ---------------------------------------------------------------------------
+// The half-resized tables of BiasArgs (both kinds in one launch; a null output skips a kind).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void bias_half_kernel(BiasArgs b1, float* __restrict__ half1, float* __restrict__ rows1,
+                                                        BiasArgs b2, float* __restrict__ half2, float* __restrict__ rows2,
+                                                        int n, int gh, int gw, size_t c_half1, size_t c_half2, size_t c_rows) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const int NA = round_up64(n);
+  const size_t seg[4] = {half1 ? c_half1 : 0, rows1 ? c_rows : 0, half2 ? c_half2 : 0, rows2 ? c_rows : 0};
+  int which = 0;
+  while (which < 4 && i >= seg[which]) i -= seg[which++];
+  if (which == 4) return;
+  const bool first = which < 2;
+  const BiasArgs& b = first ? b1 : b2;
+  const int h0 = b.blk ? b.h0 : 1, w0 = b.blk ? b.w0 : 1, he = h0;
+  const int j = (int)(i & 3);
+  float v = 0.0f;
+  if (which == 0 || which == 2) {
+    const int hd = (int)(i / ((size_t)NA * gw * he)), ii = (int)((i / ((size_t)NA * gw)) % he);
+    int a, x;
+    if (first) {
+      a = (int)((i >> 2) % NA);
+      x = 4 * (int)((i / (4 * (size_t)NA)) % (gw / 4)) + j;
+    } else {
+      x = (int)((i >> 2) % gw);
+      a = 4 * (int)((i / (4 * (size_t)gw)) % (NA / 4)) + j;
+    }
+    if (a < n) {
+      if (b.col) v += first ? b.col[((size_t)hd * n + a) * gw + x] : b.col[((size_t)hd * gw + x) * n + a];
+      if (b.blk) {
+        int x0, x1;
+        float fx;
+        bilinear_coord(x, gw, w0, x0, x1, fx);
+        float v0, v1;
+        if (first) {
+          const float* p = b.blk + (((size_t)hd * n + a) * h0 + ii) * w0;
+          v0 = p[x0];
+          v1 = p[x1];
+        } else {
+          const float* p = b.blk + ((size_t)hd * h0 + ii) * w0 * n + a;
+          v0 = p[(size_t)x0 * n];
+          v1 = p[(size_t)x1 * n];
+        }
+        v += v0 + (v1 - v0) * fx;
+      }
+    }
+    (first ? half1 : half2)[i] = v * kLog2e;
+  } else {
+    const int hd = (int)(i / ((size_t)NA * gh));
+    if (first) {
+      const int a = (int)(i % NA), y = (int)((i / NA) % gh);
+      if (a < n && b.row) v = b.row[((size_t)hd * n + a) * gh + y];
+    } else {
+      const int y = (int)((i >> 2) % gh), a = 4 * (int)((i / (4 * (size_t)gh)) % (NA / 4)) + j;
+      if (a < n && b.row) v = b.row[((size_t)hd * gh + y) * n + a];
+    }
+    (first ? rows1 : rows2)[i] = v * kLog2e;
+  }
+}
+
+size_t bias_half_floats(int heads, int n, int gw, int he) { return (size_t)heads * round_up64(n) * he * gw; }
+size_t bias_rows_floats(int heads, int n, int gh) { return (size_t)heads * round_up64(n) * gh; }
+
+hipError_t launch_bias_half(const Problem& p, float* half1, float* rows1, float* half2, float* rows2, hipStream_t st) {
+  const size_t c_half1 = bias_half_floats(p.heads, p.n, p.gw, p.b1.blk ? p.b1.h0 : 1);
+  const size_t c_half2 = bias_half_floats(p.heads, p.n, p.gw, p.b2.blk ? p.b2.h0 : 1);
+  const size_t c_rows = bias_rows_floats(p.heads, p.n, p.gh);
+  const size_t total = (half1 ? c_half1 : 0) + (rows1 ? c_rows : 0) + (half2 ? c_half2 : 0) + (rows2 ? c_rows : 0);
+  if (total == 0) return hipSuccess;
+  bias_half_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(p.b1, half1, rows1, p.b2, half2, rows2,
+                                                                               p.n, p.gh, p.gw, c_half1, c_half2, c_rows);
+  return hipGetLastError();
+}
+
 size_t bias_dense_floats(int kind, int heads, int n, int N) {
   return kind == 1 ? (size_t)heads * round_up64(n) * round_up64(N) : (size_t)heads * N * round_up64(n);
 }

@@ -38,6 +38,10 @@ hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, hipStream
 // layout of BiasArgs, in one launch; a null output skips that kind
 size_t bias_dense_floats(int kind, int heads, int n, int N);
 hipError_t launch_bias_dense(const Problem& p, float* out1, float* out2, hipStream_t st);
+// the half-resized tables of BiasArgs (he = table rows per agent: blk_h0, or 1 without block components)
+size_t bias_half_floats(int heads, int n, int gw, int he);
+size_t bias_rows_floats(int heads, int n, int gh);
+hipError_t launch_bias_half(const Problem& p, float* half1, float* rows1, float* half2, float* rows2, hipStream_t st);
 hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* K, const void* V,
                                     const Partials& part, hipStream_t st);
 hipError_t launch_merge_generic(const Problem& p, const Partials& part, float* VA, hipStream_t st);

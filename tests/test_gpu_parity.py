@@ -237,6 +237,29 @@ def test_module_terms_one_at_a_time(aa, oracle, which, dtype, d):
                        max_abs=None if dtype == "f32" else 1e-2 * max(1.0, float(np.abs(ref).max())))
 
 
+@pytest.mark.parametrize("dtype,d", [("f16", 32), ("bf16", 64), ("bf16", 40)])
+@pytest.mark.parametrize("grid,agrid,blk", [((13, 12), (9, 9), (4, 3)), ((20, 16), (10, 13), (7, 7)),
+                                            ((9, 24), (5, 13), (1, 1)), ((15, 15), (10, 13), (4, 3))])
+@pytest.mark.parametrize("which", ["b1_col", "b1_row", "b1_blk", "b2_col", "b2_row", "b2_blk", "all"])
+def test_module_terms_many_agents(aa, oracle, which, grid, agrid, blk, dtype, d):
+    """Agent bias with more than 64 agents: the kernels read tables of the column and block components
+    interpolated along x and interpolate along y themselves (grids whose width is a multiple of four;
+    the last grid takes the other route).  Token counts off the 64-token tile, agent counts off the
+    16-agent tile and beyond the last 64-agent boundary, a 1 x 1 block."""
+    import dataclasses
+    wl = dataclasses.replace(WL["deit_t"], batch=1, heads=2, grid=grid, agent_grid=agrid, d=d, dtype=dtype)
+    t = inputs.make_qkv(wl)
+    full = inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, blk=blk, index=6)
+    params = full if which == "all" else {which: full[which]}
+    dv = dev_qkv(wl, t)
+    A = aa.agent_pool_fwd(dv["Q"], grid=wl.grid, agent_grid=wl.agent_grid)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid,
+                          params=util.params_to_device(params))
+    ref = util.oracle_forward_units(oracle, wl, t, list(range(wl.units)), params=params, A=_stored(A, wl))
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, dtype, which,
+                       max_abs=1e-2 * max(1.0, float(np.abs(ref).max())))
+
+
 def _stored(A, wl):
     """GPU tensor of agents -> numpy array in the storage representation of inputs.to_float64."""
     import torch
