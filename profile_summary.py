@@ -15,6 +15,12 @@ DIR holds one run with the backward pass timed as well:
   rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload W --no-others --no-cpu-baseline --backward --steps 30 --warmup 5
 writes profiles/W_backward_kernels.md (durations of the backward pass's kernels only).
 
+usage: python profile_summary.py DIR W counters [MODE]
+DIR holds one run with eight SQ counters (MODE = pure, the default, or module):
+  rocprofv3 --pmc SQ_BUSY_CU_CYCLES SQ_INSTS_VALU SQ_INSTS_MFMA SQ_ACTIVE_INST_VALU SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_LDS SQ_ACTIVE_INST_LDS SQ_LDS_BANK_CONFLICT --kernel-trace --output-format csv -d DIR -o sq -- python3 bench.py --workload W --mode MODE --no-others --no-cpu-baseline --steps 20 --warmup 5
+writes profiles/W_sq_counters.md (profiles/W_module_sq_counters.md): per kernel the launch shape, registers,
+LDS, the median of every counter per dispatch and the ratios used in the design notes.
+
 HBM bytes: FETCH_SIZE / WRITE_SIZE are reported in KiB per dispatch; both are scaled by what the same
 counter reads for the plain 1 GiB device-to-device copy that --copy-calibration runs (it moves exactly
 1 GiB in and 1 GiB out), so a mis-scaled counter cancels out.
@@ -114,10 +120,68 @@ def backward_summary(d, wl):
     print("\n".join(lines))
 
 
+SQ_COUNTERS = ("SQ_BUSY_CU_CYCLES", "SQ_INSTS_VALU", "SQ_INSTS_MFMA", "SQ_ACTIVE_INST_VALU", "SQ_VALU_MFMA_BUSY_CYCLES",
+               "SQ_INSTS_LDS", "SQ_ACTIVE_INST_LDS", "SQ_LDS_BANK_CONFLICT")
+
+
+def counters_summary(d, wl, mode):
+    cmd = ("rocprofv3 --pmc %s --kernel-trace --output-format csv -d DIR -o sq -- python3 bench.py --workload %s "
+           "--mode %s --no-others --no-cpu-baseline --steps 20 --warmup 5" % (" ".join(SQ_COUNTERS), wl, mode))
+    per = {}
+    with open(os.path.join(d, "sq_counter_collection.csv")) as f:
+        for r in csv.DictReader(f):
+            k = short(r["Kernel_Name"])
+            if not k.startswith(("small_", "pool_", "aggregate_", "merge_", "broadcast_", "large_", "bias_")):
+                continue
+            e = per.setdefault(k, {"c": {}, "dur": [], "shape": None})
+            e["c"].setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
+            e["dur"].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+            e["shape"] = (int(r["Grid_Size"]), int(r["Workgroup_Size"]), int(r["VGPR_Count"]), int(r["Accum_VGPR_Count"]),
+                          int(r["LDS_Block_Size"]), int(r["Scratch_Size"]))
+    lines = ["# SQ counters: bench.py --workload %s --mode %s (one MI355X)" % (wl, mode), "", "command: `%s`" % cmd, "",
+             "Medians over the dispatches of each kernel; counter values are sums over the chip as rocprofv3 reports "
+             "them.  Kernel durations under counter collection are longer than in the timing runs.", "",
+             "| kernel | grid threads | block | VGPRs (+acc) | LDS B | scratch B | us under collection |",
+             "|---|---|---|---|---|---|---|"]
+    for k, e in sorted(per.items()):
+        g, w, v, a, l, sc = e["shape"]
+        lines.append("| `%s` | %d | %d | %d (+%d) | %d | %d | %.1f |" % (k, g, w, v, a, l, sc, statistics.median(e["dur"])))
+    lines += ["", "| kernel | " + " | ".join(c.replace("SQ_", "") for c in SQ_COUNTERS) + " |",
+              "|---|" + "---|" * len(SQ_COUNTERS)]
+    med = {}
+    for k, e in sorted(per.items()):
+        med[k] = {c: statistics.median(e["c"].get(c, [0.0])) for c in SQ_COUNTERS}
+        lines.append("| `%s` | " % k + " | ".join("%.3g" % med[k][c] for c in SQ_COUNTERS) + " |")
+    lines += ["", "Ratios.  BUSY_CU_CYCLES and VALU_MFMA_BUSY_CYCLES count cycles (the latter reads 16 per "
+              "16x16x32 MFMA); ACTIVE_INST_VALU reads about 1.1 per VALU instruction, i.e. it counts the four-cycle "
+              "passes of a 64-lane instruction over the 16-lane SIMD, so VALU-active cycles = 4 x ACTIVE_INST_VALU.  "
+              "Both pipes are given as a fraction of the SIMD cycles of the busy CUs (4 x BUSY_CU_CYCLES); the last "
+              "column is bank-conflict cycles per LDS-active count.", "",
+              "| kernel | VALU / MFMA insts | VALU active, fraction of SIMD cycles | MFMA busy, fraction of SIMD cycles | LDS conflict / LDS active |",
+              "|---|---|---|---|---|"]
+
+    def ratio(a, b):
+        return "%.2f" % (a / b) if b > 0 else "-"
+
+    for k, m in sorted(med.items()):
+        busy4 = 4.0 * m["SQ_BUSY_CU_CYCLES"]
+        lines.append("| `%s` | %s | %s | %s | %s |" % (k, ratio(m["SQ_INSTS_VALU"], m["SQ_INSTS_MFMA"]),
+                                                      ratio(4.0 * m["SQ_ACTIVE_INST_VALU"], busy4),
+                                                      ratio(m["SQ_VALU_MFMA_BUSY_CYCLES"], busy4),
+                                                      ratio(m["SQ_LDS_BANK_CONFLICT"], m["SQ_ACTIVE_INST_LDS"])))
+    name = "%s_sq_counters.md" % wl if mode == "pure" else "%s_%s_sq_counters.md" % (wl, mode)
+    with open(os.path.join(ROOT, "profiles", name), "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print("\n".join(lines))
+
+
 def main():
     d, wl = sys.argv[1], sys.argv[2]
     if len(sys.argv) > 3 and sys.argv[3] == "backward":
         backward_summary(d, wl)
+        return
+    if len(sys.argv) > 3 and sys.argv[3] == "counters":
+        counters_summary(d, wl, sys.argv[4] if len(sys.argv) > 4 else "pure")
         return
     lines = ["# rocprofv3 summary: bench.py --workload %s (one MI355X)" % wl, ""]
     stats_path = os.path.join(d, "stats_kernel_stats.csv")
