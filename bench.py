@@ -62,7 +62,7 @@ def stage_flops(wl):
 class Ring:
     """R independent copies of (Q, K, V, out, workspace) on the device."""
 
-    def __init__(self, wl, binding, ring_bytes, module):
+    def __init__(self, wl, binding, ring_bytes, module, prepared=False):
         import numpy as np
         import torch
         from paper_2312_08874_amd import inputs
@@ -82,6 +82,11 @@ class Ring:
         if module:
             self.host_params = inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, index=wl.index)
             self.params = {k: torch.from_numpy(v).cuda() for k, v in self.host_params.items()}
+            if prepared:      # agent-bias tables built once, outside the timed calls (fixed parameters: inference)
+                tables = binding.agent_attn_bias_tables(self.params, heads=wl.heads, N=wl.N, n=wl.n, d=wl.d,
+                                                        dtype=base["Q"].dtype, grid=wl.grid)
+                if tables is not None:
+                    self.params["bias_tables"] = tables
         desc = binding.make_desc(wl.batch, wl.heads, wl.N, wl.n, wl.d, {"f32": 0, "f16": 1, "bf16": 2}[wl.dtype],
                                  wl.grid, wl.agent_grid)
         ws_bytes = binding.workspace_bytes(desc, binding.make_params(self.params))
@@ -192,6 +197,16 @@ def timed_graph(ring, steps, warmup):
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / (reps * ring.R)
+
+
+def step_time(wl, binding, ring_bytes, steps, warmup, module, prepared=False):
+    """Milliseconds per forward pass alone (no stage timings), for the hot and module-mode variants."""
+    import torch
+    ring = Ring(wl, binding, ring_bytes, module, prepared)
+    ms = timed(ring.forward, steps, warmup)
+    del ring
+    torch.cuda.empty_cache()
+    return ms
 
 
 def measure(wl, binding, args, steps, warmup, module):
@@ -324,6 +339,16 @@ def main():
     del ring
     torch.cuda.empty_cache()
     if not args.no_others:
+        # the same workload hot (two input sets, everything stays in the Infinity Cache) and with the other
+        # set of module terms (agent bias with 7x7 block components and DWC on / off), cold
+        k, w = max(50, args.steps // 3), max(5, args.warmup // 3)
+        other_mode = "pure" if module else "module"
+        line["variants"] = {
+            "%s_hot_us" % args.mode: step_time(wl, binding, 1.0, k, w, module) * 1e3,
+            "%s_cold_us" % other_mode: step_time(wl, binding, args.ring_bytes, k, w, not module) * 1e3,
+            "%s_hot_us" % other_mode: step_time(wl, binding, 1.0, k, w, not module) * 1e3,
+            "module_prepared_bias_cold_us": step_time(wl, binding, args.ring_bytes, k, w, True, True) * 1e3,
+        }
         others = {}
         for name, w in inputs.WORKLOADS.items():
             if name == wl.name:

@@ -91,6 +91,8 @@ typedef struct {
   const float *b2_col, *b2_row, *b2_blk; /* [H,w,n], [H,h,n], [H,h0,w0,n] */
   int32_t blk_h0, blk_w0;
   const float *dwc_w, *dwc_b;            /* [H,d,3,3], [H,d]; dwc_b may be NULL with dwc_w set */
+  const void *bias_tables;               /* NULL, or what agent_attn_bias_tables() built from these very
+                                            bias components for problems of this shape (see there) */
 } aa_params;
 
 /* Bytes of device workspace agent_attn_fwd / agent_aggregate_fwd need for this
@@ -106,6 +108,24 @@ size_t agent_attn_workspace_bytes(const aa_desc *desc, const aa_params *params);
 aa_status agent_attn_fwd(const aa_desc *desc, const void *Q, const void *K, const void *V,
                          const void *A, const aa_params *params, void *workspace,
                          size_t workspace_bytes, void *out, void *hip_stream);
+
+/* Agent bias prepared ahead of the forward calls (Eq. (5), Appendix B).  The bias does not depend
+ * on the batch or on Q, K, V, so the fp16 / bf16 kernels read it from tables (the bias per head, or
+ * its column and block components interpolated along x when n is large) that the forward entry
+ * points otherwise rebuild in the workspace on every call.  A caller whose bias components stay
+ * fixed between calls (inference) builds them once:
+ *   bytes = agent_attn_bias_tables_bytes(desc, params);      0: this problem uses no tables
+ *   agent_attn_bias_tables(desc, params, tables, bytes, stream);
+ * and passes `tables` as params->bias_tables, together with the same component pointers (kernels
+ * that do not use tables still read the components), to agent_attn_fwd, agent_aggregate_fwd or
+ * agent_broadcast_fwd.  The tables belong to (heads, N, n, d, grid, dtype, which bias components
+ * are non-NULL, blk_h0, blk_w0); batch, strides and scales may differ between the calls.  They are
+ * not validated against the components: after changing a component, build them again.
+ * tables: device memory, 256-byte aligned, at least `bytes`; params->bias_tables is ignored here.
+ * Errors: as for the forward (AA_ERR_WORKSPACE for a NULL, misaligned or short buffer). */
+size_t agent_attn_bias_tables_bytes(const aa_desc *desc, const aa_params *params);
+aa_status agent_attn_bias_tables(const aa_desc *desc, const aa_params *params, void *tables,
+                                 size_t tables_bytes, void *hip_stream);
 
 /* A = Pooling(Q), Sec. 4.2: average over the window
  * [floor(i*L/La), ceil((i+1)*L/La)) per axis.  A_out [batch, heads, n, d], desc->dtype. */

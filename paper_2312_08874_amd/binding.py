@@ -36,7 +36,7 @@ class aa_params(ctypes.Structure):
     _fields_ = [("b1_col", ctypes.c_void_p), ("b1_row", ctypes.c_void_p), ("b1_blk", ctypes.c_void_p),
                 ("b2_col", ctypes.c_void_p), ("b2_row", ctypes.c_void_p), ("b2_blk", ctypes.c_void_p),
                 ("blk_h0", ctypes.c_int32), ("blk_w0", ctypes.c_int32),
-                ("dwc_w", ctypes.c_void_p), ("dwc_b", ctypes.c_void_p)]
+                ("dwc_w", ctypes.c_void_p), ("dwc_b", ctypes.c_void_p), ("bias_tables", ctypes.c_void_p)]
 
 
 class aa_param_grads(ctypes.Structure):
@@ -47,7 +47,8 @@ class aa_param_grads(ctypes.Structure):
 
 EXPORTS = ("agent_attn_workspace_bytes", "agent_attn_fwd", "agent_pool_fwd", "agent_aggregate_fwd",
            "agent_broadcast_fwd", "agent_attn_flops", "agent_attn_status_str", "agent_attn_plan_str",
-           "agent_attn_bwd_workspace_bytes", "agent_attn_bwd")
+           "agent_attn_bwd_workspace_bytes", "agent_attn_bwd", "agent_attn_bias_tables_bytes",
+           "agent_attn_bias_tables")
 
 _lib = None
 
@@ -84,6 +85,10 @@ def lib():
         L.agent_attn_bwd.restype = ctypes.c_int
         L.agent_attn_bwd.argtypes = [dp, vp, vp, vp, vp, pp, vp, vp, ctypes.c_size_t, vp, vp, vp, vp,
                                      ctypes.POINTER(aa_param_grads), vp]
+        L.agent_attn_bias_tables_bytes.restype = ctypes.c_size_t
+        L.agent_attn_bias_tables_bytes.argtypes = [dp, pp]
+        L.agent_attn_bias_tables.restype = ctypes.c_int
+        L.agent_attn_bias_tables.argtypes = [dp, pp, vp, ctypes.c_size_t, vp]
         L.agent_attn_plan_str.restype = ctypes.c_size_t
         L.agent_attn_plan_str.argtypes = [dp, ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
         L.agent_attn_status_str.restype = ctypes.c_char_p
@@ -111,10 +116,14 @@ def make_desc(batch, heads, N, n, d, dtype, grid=None, agent_grid=None, scale1=0
 
 
 def make_params(params: dict | None):
-    """dict of torch fp32 device tensors (keys as in aa_params, plus optional 'blk') -> aa_params or None."""
+    """dict of torch fp32 device tensors (keys as in aa_params; 'bias_tables': the uint8 tensor that
+    agent_attn_bias_tables() returned for these components) -> aa_params or None."""
     if not params:
         return None
     p = aa_params()
+    if params.get("bias_tables") is not None:
+        assert params["bias_tables"].is_cuda and str(params["bias_tables"].dtype) == "torch.uint8"
+        p.bias_tables = params["bias_tables"].data_ptr()
     h0 = w0 = 0
     for key in ("b1_col", "b1_row", "b1_blk", "b2_col", "b2_row", "b2_blk", "dwc_w", "dwc_b"):
         t = params.get(key)
@@ -152,6 +161,24 @@ def _check(status, where):
 
 def workspace_bytes(desc: aa_desc, params: aa_params | None = None) -> int:
     return int(lib().agent_attn_workspace_bytes(ctypes.byref(desc), _pp(params)))
+
+
+def agent_attn_bias_tables(params: dict, *, heads, N, n, d, dtype, grid, out=None, stream=None):
+    """Agent-bias tables for problems of this shape (dtype: torch dtype of Q), built once from the bias
+    components in `params`; returns a uint8 device tensor to pass on as params['bias_tables'], or None
+    when such problems use no tables."""
+    import torch
+    code = {torch.float32: AA_F32, torch.float16: AA_F16, torch.bfloat16: AA_BF16}[dtype]
+    desc = make_desc(1, heads, N, n, d, code, grid)
+    p = make_params({k: v for k, v in params.items() if k != "bias_tables"})
+    need = int(lib().agent_attn_bias_tables_bytes(ctypes.byref(desc), _pp(p)))
+    if need == 0:
+        return None
+    if out is None:
+        out = torch.empty(need, dtype=torch.uint8, device="cuda")
+    _check(lib().agent_attn_bias_tables(ctypes.byref(desc), _pp(p), out.data_ptr(), out.numel(), _stream(stream)),
+           "agent_attn_bias_tables")
+    return out
 
 
 def plan_str(desc: aa_desc, agents_given: bool = False) -> str:

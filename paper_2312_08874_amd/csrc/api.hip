@@ -26,6 +26,14 @@ size_t elem_size(int dtype) { return dtype == AA_F32 ? 4 : 2; }
 
 enum Path { PATH_GENERIC = 0, PATH_SMALL_FUSED = 1, PATH_SMALL_SPLIT = 2 };
 
+// Layout of the agent-bias tables (byte offsets into one buffer, kNone = table not used): per bias either
+// the dense form or the half-resized form with its row component.
+constexpr size_t kNone = ~(size_t)0;
+struct BiasPlan {
+  size_t B1d = kNone, B2d = kNone, H1 = kNone, R1 = kNone, H2 = kNone, R2 = kNone;
+  size_t total = 0;
+};
+
 struct Plan {
   int S;               // N-splits of the generic aggregation
   int bcast_waves_large;                              // waves (32 tokens each) per block of the large broadcast
@@ -37,8 +45,8 @@ struct Plan {
   size_t off_A;        // pooled agents, element type of the problem
   size_t off_acc, off_m, off_l;
   size_t off_VA;       // merged V_A, fp32
-  size_t off_B1d, off_B2d;   // dense agent bias (0 = not built)
-  size_t off_H1, off_R1, off_H2, off_R2;   // half-resized agent bias and its row component (0 = not built)
+  BiasPlan bias;       // agent-bias tables, offsets relative to off_bias
+  size_t off_bias;     // where they live in the workspace (unused when the caller brings prepared tables)
   size_t total;
 };
 
@@ -83,6 +91,7 @@ aa_status check_params(const aa_params* p) {
   if (!p) return AA_OK;
   if ((p->b1_blk || p->b2_blk) && (p->blk_h0 <= 0 || p->blk_w0 <= 0)) return AA_ERR_SHAPE;
   if (p->dwc_b && !p->dwc_w) return AA_ERR_NULL;
+  if (((uintptr_t)p->bias_tables % 256) != 0) return AA_ERR_WORKSPACE;
   return AA_OK;
 }
 
@@ -174,6 +183,40 @@ void plan_large(const aa_desc* d, Plan& pl) {
 // (it is read once per batch element; beyond the cap the kernels evaluate the components per score).
 constexpr size_t kBiasDenseCapBytes = (size_t)2 << 30;
 
+BiasPlan plan_bias(const aa_desc* d, const aa_params* params) {
+  BiasPlan bp;
+  size_t off = 0;
+  const bool tables_ok = d->grid_h > 0 && d->dtype != AA_F32;      // the MFMA kernels are the ones that read them
+  // Many agents: n * N bias values per head are too many to write and read back per call, so the
+  // large-agent kernels get the half-resized form (n * blk_h0 * w values) and interpolate along y.
+  const bool half_form = tables_ok && d->n > 64 && d->grid_w % 4 == 0 &&
+                         aa::bias_half_floats(d->heads, d->n, d->grid_w, params ? (params->blk_h0 > 0 ? params->blk_h0 : 1) : 1) *
+                                 sizeof(float) <= kBiasDenseCapBytes;
+  for (int kind = 1; kind <= 2; ++kind) {
+    const bool any = params && (kind == 1 ? (params->b1_col || params->b1_row || params->b1_blk)
+                                          : (params->b2_col || params->b2_row || params->b2_blk));
+    if (!any || !tables_ok) continue;
+    if (half_form) {
+      const bool blk = kind == 1 ? params->b1_blk != nullptr : params->b2_blk != nullptr;
+      const bool row = kind == 1 ? params->b1_row != nullptr : params->b2_row != nullptr;
+      (kind == 1 ? bp.H1 : bp.H2) = off;
+      off += align_up(aa::bias_half_floats(d->heads, d->n, d->grid_w, blk ? params->blk_h0 : 1) * sizeof(float));
+      if (row) {
+        (kind == 1 ? bp.R1 : bp.R2) = off;
+        off += align_up(aa::bias_rows_floats(d->heads, d->n, d->grid_h) * sizeof(float));
+      }
+      continue;
+    }
+    const size_t bytes = aa::bias_dense_floats(kind, d->heads, d->n, d->N) * sizeof(float);
+    if (bytes <= kBiasDenseCapBytes) {
+      (kind == 1 ? bp.B1d : bp.B2d) = off;
+      off += align_up(bytes);
+    }
+  }
+  bp.total = off;
+  return bp;
+}
+
 Plan make_plan(const aa_desc* d, const aa_params* params = nullptr) {
   Plan pl{};
   const size_t units = (size_t)d->batch * d->heads;
@@ -193,32 +236,9 @@ Plan make_plan(const aa_desc* d, const aa_params* params = nullptr) {
   off += align_up(units * Smax * d->n * sizeof(float));
   pl.off_VA = off;
   off += align_up(units * d->n * d->d * sizeof(float));
-  pl.off_B1d = pl.off_B2d = pl.off_H1 = pl.off_R1 = pl.off_H2 = pl.off_R2 = 0;
-  const bool dense_ok = d->grid_h > 0 && d->dtype != AA_F32;      // the MFMA kernels are the ones that read it
-  // Many agents: n * N bias values per head are too many to write and read back per call, so the
-  // large-agent kernels get the half-resized form (n * blk_h0 * w values) and interpolate along y.
-  const bool half_form = dense_ok && d->n > 64 && d->grid_w % 4 == 0;
-  for (int kind = 1; kind <= 2; ++kind) {
-    const bool any = params && (kind == 1 ? (params->b1_col || params->b1_row || params->b1_blk)
-                                          : (params->b2_col || params->b2_row || params->b2_blk));
-    if (!any || !dense_ok) continue;
-    if (half_form) {
-      const bool blk = kind == 1 ? params->b1_blk != nullptr : params->b2_blk != nullptr;
-      const bool row = kind == 1 ? params->b1_row != nullptr : params->b2_row != nullptr;
-      (kind == 1 ? pl.off_H1 : pl.off_H2) = off;
-      off += align_up(aa::bias_half_floats(d->heads, d->n, d->grid_w, blk ? params->blk_h0 : 1) * sizeof(float));
-      if (row) {
-        (kind == 1 ? pl.off_R1 : pl.off_R2) = off;
-        off += align_up(aa::bias_rows_floats(d->heads, d->n, d->grid_h) * sizeof(float));
-      }
-      continue;
-    }
-    const size_t bytes = aa::bias_dense_floats(kind, d->heads, d->n, d->N) * sizeof(float);
-    if (bytes <= kBiasDenseCapBytes) {
-      (kind == 1 ? pl.off_B1d : pl.off_B2d) = off;
-      off += align_up(bytes);
-    }
-  }
+  pl.bias = plan_bias(d, params);
+  pl.off_bias = off;
+  if (!(params && params->bias_tables)) off += pl.bias.total;      // prepared tables need no room here
   pl.total = off;
   return pl;
 }
@@ -368,19 +388,22 @@ aa_status run_broadcast(const Problem& pr, const void* Q, const void* A, const f
   return AA_OK;
 }
 
-// Build the dense agent bias in the workspace (when the plan reserved room for it and the MFMA kernels
-// will run) and point the problem's bias arguments at it.
-aa_status prepare_dense_bias(Problem& pr, const Plan& pl, void* workspace, bool mfma_path, hipStream_t st) {
-  if (!mfma_path) return AA_OK;
-  char* ws = (char*)workspace;
-  float* d1 = (pl.off_B1d && pr.b1.any()) ? (float*)(ws + pl.off_B1d) : nullptr;
-  float* d2 = (pl.off_B2d && pr.b2.any()) ? (float*)(ws + pl.off_B2d) : nullptr;
-  AA_HIP(aa::launch_bias_dense(pr, d1, d2, st));
-  float* h1 = (pl.off_H1 && pr.b1.any()) ? (float*)(ws + pl.off_H1) : nullptr;
-  float* h2 = (pl.off_H2 && pr.b2.any()) ? (float*)(ws + pl.off_H2) : nullptr;
-  float* r1 = (h1 && pl.off_R1) ? (float*)(ws + pl.off_R1) : nullptr;
-  float* r2 = (h2 && pl.off_R2) ? (float*)(ws + pl.off_R2) : nullptr;
-  AA_HIP(aa::launch_bias_half(pr, h1, r1, h2, r2, st));
+// Point the problem's bias arguments at the agent-bias tables in `base` (laid out by `bp`), building them
+// first when `build` is set.  pr.b1 / pr.b2 select the biases: a call that uses only one of them leaves
+// the other's arguments empty and its table alone.
+aa_status prepare_bias_tables(Problem& pr, const BiasPlan& bp, void* base_ptr, bool build, hipStream_t st) {
+  char* base = (char*)base_ptr;
+  auto at = [&](size_t off, bool wanted) { return (off != kNone && wanted) ? (float*)(base + off) : nullptr; };
+  float* d1 = at(bp.B1d, pr.b1.any());
+  float* d2 = at(bp.B2d, pr.b2.any());
+  float* h1 = at(bp.H1, pr.b1.any());
+  float* h2 = at(bp.H2, pr.b2.any());
+  float* r1 = at(bp.R1, h1 != nullptr);
+  float* r2 = at(bp.R2, h2 != nullptr);
+  if (build) {
+    AA_HIP(aa::launch_bias_dense(pr, d1, d2, st));
+    AA_HIP(aa::launch_bias_half(pr, h1, r1, h2, r2, st));
+  }
   if (h1) {
     pr.b1.half = h1;
     pr.b1.rows = r1;
@@ -404,6 +427,16 @@ aa_status prepare_dense_bias(Problem& pr, const Plan& pl, void* workspace, bool 
   return AA_OK;
 }
 
+// The tables of a forward call: the caller's prepared ones, else built in the workspace; none when the
+// MFMA kernels will not run (the other kernels evaluate the components).
+aa_status prepare_dense_bias(Problem& pr, const Plan& pl, const aa_params* params, void* workspace, bool mfma_path,
+                             hipStream_t st) {
+  if (!mfma_path || pl.bias.total == 0) return AA_OK;
+  if (params && params->bias_tables) return prepare_bias_tables(pr, pl.bias, (void*)params->bias_tables, false, st);
+  if (!workspace) return AA_OK;
+  return prepare_bias_tables(pr, pl.bias, (char*)workspace + pl.off_bias, true, st);
+}
+
 aa_status run_pool(const Problem& pr, const void* Q, void* A, hipStream_t st) {
   if (use_small(pr, {Q, A}))
     AA_HIP(aa::launch_small_pool(pr, Q, A, st));
@@ -422,6 +455,30 @@ size_t agent_attn_workspace_bytes(const aa_desc* desc, const aa_params* params) 
   if (check_desc(desc, params_use_grid(params), false) != AA_OK) return 0;
   if (check_params(params) != AA_OK) return 0;
   return make_plan(desc, params).total;
+}
+
+size_t agent_attn_bias_tables_bytes(const aa_desc* desc, const aa_params* params) {
+  if (!params || check_desc(desc, params_use_grid(params), false) != AA_OK) return 0;
+  aa_params own = *params;
+  own.bias_tables = nullptr;
+  if (check_params(&own) != AA_OK) return 0;
+  return plan_bias(desc, &own).total;
+}
+
+aa_status agent_attn_bias_tables(const aa_desc* desc, const aa_params* params, void* tables, size_t tables_bytes,
+                                 void* hip_stream) {
+  if (!params) return AA_ERR_NULL;
+  aa_status st = check_desc(desc, params_use_grid(params), false);
+  if (st != AA_OK) return st;
+  aa_params own = *params;
+  own.bias_tables = nullptr;
+  st = check_params(&own);
+  if (st != AA_OK) return st;
+  const BiasPlan bp = plan_bias(desc, &own);
+  if (bp.total == 0) return AA_OK;
+  if (!tables || ((uintptr_t)tables % kAlign) != 0 || tables_bytes < bp.total) return AA_ERR_WORKSPACE;
+  Problem pr = make_problem(desc, &own);
+  return prepare_bias_tables(pr, bp, tables, true, (hipStream_t)hip_stream);
 }
 
 uint64_t agent_attn_flops(const aa_desc* desc) {
@@ -461,7 +518,7 @@ aa_status agent_aggregate_fwd(const aa_desc* desc, const void* A, const void* K,
     return AA_ERR_ALIAS;
   Problem pr = make_problem(desc, params);
   pr.b2 = aa::BiasArgs{};
-  st = prepare_dense_bias(pr, pl, workspace, use_small(pr, {A, K, V}) || use_large(pr, {A, K, V}),
+  st = prepare_dense_bias(pr, pl, params, workspace, use_small(pr, {A, K, V}) || use_large(pr, {A, K, V}),
                           (hipStream_t)hip_stream);
   if (st != AA_OK) return st;
   return run_aggregate(pr, A, K, V, workspace, pl, VA_out, (hipStream_t)hip_stream);
@@ -485,7 +542,13 @@ aa_status agent_broadcast_fwd(const aa_desc* desc, const void* Q, const void* A,
     return AA_ERR_ALIAS;
   Problem pr = make_problem(desc, params);
   pr.b1 = aa::BiasArgs{};
-  return run_broadcast(pr, Q, A, VA, V, out, make_plan(desc), (hipStream_t)hip_stream);
+  const Plan pl = make_plan(desc, params);
+  if (params && params->bias_tables) {      // no workspace here: tables only when the caller prepared them
+    st = prepare_dense_bias(pr, pl, params, nullptr, use_small(pr, {Q, A, V, out}) || use_large(pr, {Q, A, V, out}),
+                            (hipStream_t)hip_stream);
+    if (st != AA_OK) return st;
+  }
+  return run_broadcast(pr, Q, A, VA, V, out, pl, (hipStream_t)hip_stream);
 }
 
 aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, const void* V, const void* A,
@@ -513,7 +576,8 @@ aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, cons
   Problem pr = make_problem(desc, params);
   hipStream_t stream = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
-  st = prepare_dense_bias(pr, pl, workspace, use_small(pr, {Q, K, V, A, out}) || use_large(pr, {Q, K, V, A, out}), stream);
+  st = prepare_dense_bias(pr, pl, params, workspace, use_small(pr, {Q, K, V, A, out}) || use_large(pr, {Q, K, V, A, out}),
+                          stream);
   if (st != AA_OK) return st;
   if (pl.prefer_fused && aa::small_fused_supported(pr) && use_small(pr, {Q, K, V, A, out})) {
     AA_HIP(aa::launch_small_fused(pr, Q, K, V, A, out, stream));

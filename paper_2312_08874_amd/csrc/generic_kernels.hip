@@ -344,74 +344,117 @@ __global__ __launch_bounds__(256) void bias_dense_kernel(BiasArgs b1, float* __r
 // ---------------------------------------------------------------------------
 // The half-resized tables of BiasArgs (both kinds in one launch; a null output skips a kind).
 // ---------------------------------------------------------------------------
+// One thread per 16 bytes of output (four neighbours in x, or four agents).  The tables are transposes of
+// the parameter layouts, so the 64 lanes of a wave take an 8 x 8 tile of (agent, x) positions: eight lanes
+// along the table's contiguous direction and eight along the parameter's give 128-byte pieces on both
+// sides.  The counts are threads per segment (tiles x 64, ragged tiles included).
 __global__ __launch_bounds__(256) void bias_half_kernel(BiasArgs b1, float* __restrict__ half1, float* __restrict__ rows1,
                                                         BiasArgs b2, float* __restrict__ half2, float* __restrict__ rows2,
-                                                        int n, int gh, int gw, size_t c_half1, size_t c_half2, size_t c_rows) {
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  const int NA = round_up64(n);
-  const size_t seg[4] = {half1 ? c_half1 : 0, rows1 ? c_rows : 0, half2 ? c_half2 : 0, rows2 ? c_rows : 0};
+                                                        int n, int gh, int gw, unsigned q_half1, unsigned q_half2,
+                                                        unsigned q_rows) {
+  unsigned q = blockIdx.x * 256u + threadIdx.x;
+  const unsigned q_rows64 = (q_rows + 63u) & ~63u;      // every segment starts on a wave boundary
+  const unsigned seg[4] = {half1 ? q_half1 : 0u, rows1 ? q_rows64 : 0u, half2 ? q_half2 : 0u, rows2 ? q_rows64 : 0u};
   int which = 0;
-  while (which < 4 && i >= seg[which]) i -= seg[which++];
+  while (which < 4 && q >= seg[which]) q -= seg[which++];
   if (which == 4) return;
   const bool first = which < 2;
   const BiasArgs& b = first ? b1 : b2;
-  const int h0 = b.blk ? b.h0 : 1, w0 = b.blk ? b.w0 : 1, he = h0;
-  const int j = (int)(i & 3);
-  float v = 0.0f;
-  if (which == 0 || which == 2) {
-    const int hd = (int)(i / ((size_t)NA * gw * he)), ii = (int)((i / ((size_t)NA * gw)) % he);
-    int a, x;
-    if (first) {
-      a = (int)((i >> 2) % NA);
-      x = 4 * (int)((i / (4 * (size_t)NA)) % (gw / 4)) + j;
-    } else {
-      x = (int)((i >> 2) % gw);
-      a = 4 * (int)((i / (4 * (size_t)gw)) % (NA / 4)) + j;
-    }
-    if (a < n) {
-      if (b.col) v += first ? b.col[((size_t)hd * n + a) * gw + x] : b.col[((size_t)hd * gw + x) * n + a];
-      if (b.blk) {
-        int x0, x1;
-        float fx;
-        bilinear_coord(x, gw, w0, x0, x1, fx);
-        float v0, v1;
-        if (first) {
-          const float* p = b.blk + (((size_t)hd * n + a) * h0 + ii) * w0;
-          v0 = p[x0];
-          v1 = p[x1];
-        } else {
-          const float* p = b.blk + ((size_t)hd * h0 + ii) * w0 * n + a;
-          v0 = p[(size_t)x0 * n];
-          v1 = p[(size_t)x1 * n];
+  const unsigned NA = (unsigned)round_up64(n), NAq = NA >> 2, gwq = (unsigned)gw >> 2;
+  const int h0 = b.blk ? b.h0 : 1, w0 = b.blk ? b.w0 : 1;
+  const unsigned he = (unsigned)h0;
+  float out[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  float* dst;
+  const unsigned lane = q & 63u, lo = lane & 7u, hi = lane >> 3;
+  q >>= 6;                     // tile index
+  bool live = true;
+  size_t quad = 0;             // index of this thread's 16 bytes in its table
+  if (which == 0) {            // tiles over (x/4, a) for each (hd, i); table index ((hd * he + i) * w/4 + x/4) * NA + a
+    const unsigned ta = NA >> 3, tx = (gwq + 7) >> 3;
+    const unsigned a = 8 * (q % ta) + lo, t = q / ta, xq = 8 * (t % tx) + hi, t2 = t / tx, ii = t2 % he, hd = t2 / he;
+    live = xq < gwq;
+    quad = ((size_t)(hd * he + ii) * gwq + xq) * NA + a;
+    if (live && (int)a < n) {
+      const float* col = b.col ? b.col + ((size_t)hd * n + a) * gw + 4 * xq : nullptr;
+      const float* p = b.blk ? b.blk + (((size_t)hd * n + a) * h0 + ii) * w0 : nullptr;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (col) out[j] = col[j];
+        if (p) {
+          int x0, x1;
+          float fx;
+          bilinear_coord((int)(4 * xq) + j, gw, w0, x0, x1, fx);
+          const float v0 = p[x0], v1 = p[x1];
+          out[j] += v0 + (v1 - v0) * fx;
         }
-        v += v0 + (v1 - v0) * fx;
       }
     }
-    (first ? half1 : half2)[i] = v * kLog2e;
-  } else {
-    const int hd = (int)(i / ((size_t)NA * gh));
-    if (first) {
-      const int a = (int)(i % NA), y = (int)((i / NA) % gh);
-      if (a < n && b.row) v = b.row[((size_t)hd * n + a) * gh + y];
-    } else {
-      const int y = (int)((i >> 2) % gh), a = 4 * (int)((i / (4 * (size_t)gh)) % (NA / 4)) + j;
-      if (a < n && b.row) v = b.row[((size_t)hd * gh + y) * n + a];
+    dst = half1;
+  } else if (which == 2) {     // tiles over (a/4, x) for each (hd, i); table index ((hd * he + i) * NA/4 + a/4) * w + x
+    const unsigned tx = ((unsigned)gw + 7) >> 3, taq = NAq >> 3;
+    const unsigned xr = 8 * (q % tx) + lo, t = q / tx, aq = 8 * (t % taq) + hi, t2 = t / taq, ii = t2 % he, hd = t2 / he;
+    live = xr < (unsigned)gw;
+    const unsigned x = live ? xr : 0u;
+    quad = ((size_t)(hd * he + ii) * NAq + aq) * gw + x;
+    int x0 = 0, x1 = 0;
+    float fx = 0.0f;
+    if (b.blk) bilinear_coord((int)x, gw, w0, x0, x1, fx);
+    const float* col = b.col ? b.col + ((size_t)hd * gw + x) * n : nullptr;
+    const float* p = b.blk ? b.blk + ((size_t)hd * h0 + ii) * w0 * n : nullptr;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int a = (int)(4 * aq) + j;
+      if (a < n) {
+        if (col) out[j] = col[a];
+        if (p) {
+          const float v0 = p[(size_t)x0 * n + a], v1 = p[(size_t)x1 * n + a];
+          out[j] += v0 + (v1 - v0) * fx;
+        }
+      }
     }
-    (first ? rows1 : rows2)[i] = v * kLog2e;
+    dst = half2;
+  } else if (which == 1) {     // table index (hd * h + y) * NA/4 + a/4, 64 of them per tile
+    quad = (size_t)q * 64 + lane;
+    live = quad < q_rows;
+    const unsigned aq = (unsigned)(quad % NAq), t = (unsigned)(quad / NAq), y = t % (unsigned)gh, hd = t / (unsigned)gh;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int a = (int)(4 * aq) + j;
+      if (live && a < n && b.row) out[j] = b.row[((size_t)hd * n + a) * gh + y];
+    }
+    dst = rows1;
+  } else {                     // table index (hd * NA/4 + a/4) * h + y
+    quad = (size_t)q * 64 + lane;
+    live = quad < q_rows;
+    const unsigned y = (unsigned)(quad % (unsigned)gh), t = (unsigned)(quad / (unsigned)gh), aq = t % NAq, hd = t / NAq;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int a = (int)(4 * aq) + j;
+      if (live && a < n && b.row) out[j] = b.row[((size_t)hd * gh + y) * n + a];
+    }
+    dst = rows2;
   }
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  if (live) *(f32x4*)(dst + quad * 4) = f32x4{out[0] * kLog2e, out[1] * kLog2e, out[2] * kLog2e, out[3] * kLog2e};
 }
 
 size_t bias_half_floats(int heads, int n, int gw, int he) { return (size_t)heads * round_up64(n) * he * gw; }
 size_t bias_rows_floats(int heads, int n, int gh) { return (size_t)heads * round_up64(n) * gh; }
 
 hipError_t launch_bias_half(const Problem& p, float* half1, float* rows1, float* half2, float* rows2, hipStream_t st) {
-  const size_t c_half1 = bias_half_floats(p.heads, p.n, p.gw, p.b1.blk ? p.b1.h0 : 1);
-  const size_t c_half2 = bias_half_floats(p.heads, p.n, p.gw, p.b2.blk ? p.b2.h0 : 1);
-  const size_t c_rows = bias_rows_floats(p.heads, p.n, p.gh);
-  const size_t total = (half1 ? c_half1 : 0) + (rows1 ? c_rows : 0) + (half2 ? c_half2 : 0) + (rows2 ? c_rows : 0);
+  // threads per segment: 64 per 8 x 8 tile (ragged tiles along x included); the caller keeps every table
+  // below 2 GiB, so 32-bit counts suffice
+  const unsigned NA = (unsigned)round_up64(p.n), gwq = (unsigned)p.gw >> 2;
+  auto tiles = [&](int he, bool kind1) {
+    return kind1 ? (unsigned)p.heads * he * ((gwq + 7) / 8) * (NA / 8) : (unsigned)p.heads * he * (((unsigned)p.gw + 7) / 8) * (NA / 32);
+  };
+  const unsigned q_half1 = 64u * tiles(p.b1.blk ? p.b1.h0 : 1, true);
+  const unsigned q_half2 = 64u * tiles(p.b2.blk ? p.b2.h0 : 1, false);
+  const unsigned q_rows = (unsigned)(bias_rows_floats(p.heads, p.n, p.gh) / 4), q_rows64 = (q_rows + 63u) & ~63u;
+  const size_t total = (size_t)(half1 ? q_half1 : 0) + (rows1 ? q_rows64 : 0) + (half2 ? q_half2 : 0) + (rows2 ? q_rows64 : 0);
   if (total == 0) return hipSuccess;
   bias_half_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(p.b1, half1, rows1, p.b2, half2, rows2,
-                                                                               p.n, p.gh, p.gw, c_half1, c_half2, c_rows);
+                                                                               p.n, p.gh, p.gw, q_half1, q_half2, q_rows);
   return hipGetLastError();
 }
 

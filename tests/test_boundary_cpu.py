@@ -29,9 +29,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    # int32 x10, float x3, int32, int64 x6 -> 104 bytes; params: 6 ptr, 2 int32, 2 ptr -> 72 bytes
+    # int32 x10, float x3, int32, int64 x6 -> 104 bytes; params: 6 ptr, 2 int32, 3 ptr -> 80 bytes
     assert ctypes.sizeof(binding.aa_desc) == 104
-    assert ctypes.sizeof(binding.aa_params) == 72
+    assert ctypes.sizeof(binding.aa_params) == 80
 
 
 def test_flops_follow_the_cost_model():
@@ -112,6 +112,45 @@ def test_stage_entry_points_reject_bad_arguments():
     assert L.agent_broadcast_fwd(ctypes.byref(d), FAKE, FAKE * 2, FAKE * 3, None, None, FAKE * 9 + (1 << 41),
                                  None) == -1
     assert L.agent_attn_fwd(None, FAKE, FAKE, FAKE, None, None, FAKE, 1, FAKE, None) == -1
+
+
+def test_bias_tables_entry_points_validate_on_the_host():
+    L = binding.lib()
+    d = make_desc(4, 3, 196, 49, 64, binding.AA_BF16, (14, 14), (7, 7))
+    p = aa_params()
+    assert L.agent_attn_bias_tables_bytes(ctypes.byref(d), None) == 0
+    assert L.agent_attn_bias_tables_bytes(ctypes.byref(d), ctypes.byref(p)) == 0          # no bias component
+    p.b1_col = FAKE * 7
+    one = L.agent_attn_bias_tables_bytes(ctypes.byref(d), ctypes.byref(p))
+    assert one >= 3 * 64 * 196 * 4 and one % 256 == 0                                     # dense B1: H * 64 * N floats
+    p.b2_row = FAKE * 8
+    both = L.agent_attn_bias_tables_bytes(ctypes.byref(d), ctypes.byref(p))
+    assert both > one
+    # tables do not depend on the batch; fp32 problems use none
+    assert L.agent_attn_bias_tables_bytes(ctypes.byref(make_desc(1, 3, 196, 49, 64, binding.AA_BF16, (14, 14))),
+                                          ctypes.byref(p)) == both
+    assert L.agent_attn_bias_tables_bytes(ctypes.byref(make_desc(4, 3, 196, 49, 64, binding.AA_F32, (14, 14))),
+                                          ctypes.byref(p)) == 0
+    # many agents: only the x direction is expanded, far below n * N values per head
+    big = make_desc(1, 8, 16384, 1024, 64, binding.AA_BF16, (128, 128), (32, 32))
+    p.b1_blk = FAKE * 9
+    p.blk_h0 = p.blk_w0 = 7
+    half = L.agent_attn_bias_tables_bytes(ctypes.byref(big), ctypes.byref(p))
+    assert 0 < half < 8 * 1024 * 16384 * 4 // 8
+    # prepared tables shrink the workspace by exactly their size
+    w_full = binding.workspace_bytes(d, p)
+    q = aa_params.from_buffer_copy(p)
+    q.bias_tables = FAKE * 11
+    assert w_full - binding.workspace_bytes(d, q) == L.agent_attn_bias_tables_bytes(ctypes.byref(d), ctypes.byref(p))
+    # build: NULL params, bad buffer, misaligned prepared tables in a forward call
+    assert L.agent_attn_bias_tables(ctypes.byref(d), None, FAKE, 1 << 30, None) == -1
+    assert L.agent_attn_bias_tables(ctypes.byref(d), ctypes.byref(p), None, 1 << 30, None) == -5
+    assert L.agent_attn_bias_tables(ctypes.byref(d), ctypes.byref(p), FAKE + 8, 1 << 30, None) == -5
+    assert L.agent_attn_bias_tables(ctypes.byref(d), ctypes.byref(p), FAKE, 64, None) == -5
+    assert L.agent_attn_bias_tables(ctypes.byref(make_desc(4, 3, 196, 49, 64, 2)), ctypes.byref(p), FAKE, 1 << 30,
+                                    None) == -2                                           # bias without a grid
+    q.bias_tables = FAKE * 11 + 8
+    assert call_fwd(d, params=q) == -5
 
 
 def test_plan_string_is_host_only():

@@ -260,6 +260,37 @@ def test_module_terms_many_agents(aa, oracle, which, grid, agrid, blk, dtype, d)
                        max_abs=1e-2 * max(1.0, float(np.abs(ref).max())))
 
 
+@pytest.mark.parametrize("name,batch", [("deit_t", 2), ("swin_t_s1", 1), ("sd_latent", 1)])
+def test_prepared_bias_tables(aa, name, batch):
+    """Bias tables built once by agent_attn_bias_tables() and passed in aa_params give the very bits of the
+    tables the forward pass builds per call (dense tables on the small-agent kernels, half-expanded ones
+    on the large-agent kernels), for another batch size too; the broadcast stage, which has no workspace
+    and otherwise evaluates the components per score, reads them as well."""
+    import torch
+    wl = small(WL[name], batch)
+    t = inputs.make_qkv(wl)
+    params = util.params_to_device(inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, index=wl.index))
+    dv = dev_qkv(wl, t)
+    tables = aa.agent_attn_bias_tables(params, heads=wl.heads, N=wl.N, n=wl.n, d=wl.d, dtype=dv["Q"].dtype,
+                                       grid=wl.grid)
+    assert tables is not None
+    prepared = dict(params, bias_tables=tables)
+    kw = dict(grid=wl.grid, agent_grid=wl.agent_grid)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], params=params, **kw)
+    O2 = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], params=prepared, **kw)
+    assert torch.equal(O, O2)
+    one = {k: v[:1].contiguous() for k, v in dv.items()}          # the tables do not depend on the batch
+    assert torch.equal(aa.agent_attn_fwd(one["Q"], one["K"], one["V"], params=prepared, **kw), O[:1])
+    A = aa.agent_pool_fwd(dv["Q"], **kw)
+    VA = aa.agent_aggregate_fwd(A, dv["K"], dv["V"], grid=wl.grid, params=params)
+    assert torch.equal(VA, aa.agent_aggregate_fwd(A, dv["K"], dv["V"], grid=wl.grid, params=prepared))
+    Oc = aa.agent_broadcast_fwd(dv["Q"], A, VA, dv["V"], grid=wl.grid, params=params).float()
+    Ot = aa.agent_broadcast_fwd(dv["Q"], A, VA, dv["V"], grid=wl.grid, params=prepared).float()
+    # two evaluation orders of the same bias: at most an output rounding step apart
+    assert (Oc - Ot).abs().max().item() <= 2.0 ** -6 * max(1.0, Oc.abs().max().item())
+    assert ((Oc - Ot).norm() / Oc.norm()).item() <= 2e-3
+
+
 def _stored(A, wl):
     """GPU tensor of agents -> numpy array in the storage representation of inputs.to_float64."""
     import torch
