@@ -189,7 +189,7 @@ BiasPlan plan_bias(const aa_desc* d, const aa_params* params) {
   const bool tables_ok = d->grid_h > 0 && d->dtype != AA_F32;      // the MFMA kernels are the ones that read them
   // Many agents: n * N bias values per head are too many to write and read back per call, so the
   // large-agent kernels get the half-resized form (n * blk_h0 * w values) and interpolate along y.
-  const bool half_form = tables_ok && d->n > 64 && d->grid_w % 4 == 0 &&
+  const bool half_form = tables_ok && d->n > 64 && d->grid_w % 4 == 0 && (int64_t)d->N * d->grid_w < ((int64_t)1 << 32) &&
                          aa::bias_half_floats(d->heads, d->n, d->grid_w, params ? (params->blk_h0 > 0 ? params->blk_h0 : 1) : 1) *
                                  sizeof(float) <= kBiasDenseCapBytes;
   for (int kind = 1; kind <= 2; ++kind) {
