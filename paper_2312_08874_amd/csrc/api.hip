@@ -114,10 +114,16 @@ int choose_splits(const aa_desc* d) {
   return S;
 }
 
-// Tuning override for experiments: integer environment variable, 0 / unset = use the built-in choice.
+// Tuning overrides for sweeps: integer environment variables, read only by builds made with
+// -DAA_TUNING_ENV; the library as shipped ignores the environment and always takes the built-in choice.
 int tuning_env(const char* name) {
+#ifdef AA_TUNING_ENV
   const char* v = getenv(name);
   return v ? atoi(v) : 0;
+#else
+  (void)name;
+  return 0;
+#endif
 }
 
 // Splits / chunks of the small-agent path.  An explicit n_splits forces the multi-kernel path

@@ -448,3 +448,54 @@ def test_forward_strided_layouts(aa, name, grid, agrid, d, dtype, heads, module,
     assert torch.equal(VA, aa.agent_aggregate_fwd(A, dense["K"], dense["V"], grid=grid, params=params))
     O = aa.agent_broadcast_fwd(views["Q"], A, VA, views["V"], grid=grid, params=params, out=out_tm)
     assert torch.equal(O, aa.agent_broadcast_fwd(dense["Q"], A, VA, dense["V"], grid=grid, params=params))
+
+
+# --------------------------------------------------------------------------
+# seeded random problems over the whole admissible range of shapes: every kernel family, ragged pooling
+# windows, agent counts off the tile sizes, random subsets of the module terms, the SD-variant scalars
+# --------------------------------------------------------------------------
+def _random_case(seed):
+    import dataclasses
+    rng = np.random.default_rng(1000 + seed)
+    dtype = ["f32", "f16", "bf16"][seed % 3]
+    gh, gw = int(rng.integers(1, 33)), int(rng.integers(1, 33))
+    if seed % 4 == 0:
+        gw = 4 * max(1, gw // 4)                   # widths the many-agent bias tables accept
+    ah, aw = int(rng.integers(1, min(gh, 12) + 1)), int(rng.integers(1, min(gw, 12) + 1))
+    if seed % 5 == 0:                              # many agents: more than one 64-agent chunk
+        gh, gw = max(gh, 12), 4 * max(3, gw // 4)
+        ah, aw = int(rng.integers(8, 13)), int(rng.integers(9, 13))
+    if dtype == "f32":
+        d = int(rng.integers(1, 80)) if seed % 2 else int(rng.choice([8, 32, 64]))
+    else:                                          # half of them the widths of the small-agent kernels
+        d = int(rng.choice([32, 64])) if rng.random() < 0.5 else int(rng.choice([8, 16, 24, 40, 72, 96, 128]))
+    wl = dataclasses.replace(WL["tiny"], batch=int(rng.integers(1, 3)), heads=int(rng.integers(1, 4)), grid=(gh, gw),
+                             agent_grid=(ah, aw), d=d, dtype=dtype, index=20 + seed)
+    keys = [k for k in ("b1_col", "b1_row", "b1_blk", "b2_col", "b2_row", "b2_blk", "dwc_w") if rng.random() < 0.4]
+    if "dwc_w" in keys and rng.random() < 0.5:
+        keys.append("dwc_b")
+    blk = (int(rng.integers(1, 8)), int(rng.integers(1, 8)))
+    kw = {}
+    if rng.random() < 0.3:
+        kw = dict(scale2=float(d) ** -0.15, v_residual_k=0.075)
+    return wl, keys, blk, kw
+
+
+@pytest.mark.parametrize("seed", range(90))
+def test_forward_random_problems(aa, oracle, seed):
+    wl, keys, blk, kw = _random_case(seed)
+    t = inputs.make_qkv(wl)
+    full = inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, blk=blk, index=wl.index)
+    params = {k: full[k] for k in keys} or None
+    dv = dev_qkv(wl, t)
+    A = aa.agent_pool_fwd(dv["Q"], grid=wl.grid, agent_grid=wl.agent_grid)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid,
+                          params=util.params_to_device(params) if params else None, **kw)
+    # both sides take the GPU's pooled agents in the 16-bit types (their rounding is checked by test_pool)
+    ref = util.oracle_forward_units(oracle, wl, t, list(range(wl.units)), params=params,
+                                    A=None if wl.dtype == "f32" else _stored(A, wl), **kw)
+    what = "seed %d: grid %s agents %s d %d %s heads %d terms %s %s" % (seed, wl.grid, wl.agent_grid, wl.d, wl.dtype,
+                                                                       wl.heads, keys, kw)
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, wl.dtype, what,
+                       max_abs=None if wl.dtype == "f32" else 1e-2 * max(1.0, float(np.abs(ref).max())))
+
