@@ -451,6 +451,45 @@ def test_forward_strided_layouts(aa, name, grid, agrid, d, dtype, heads, module,
 
 
 # --------------------------------------------------------------------------
+# HIP graph capture: the library allocates nothing and clears nothing with memsets, so a forward pass
+# can be captured and replayed; every replay must give the bits of the eager call on the current inputs
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("name,batch,module", [("deit_t", 4, False), ("deit_t", 4, True), ("swin_t_s1", 2, True),
+                                               ("sd_latent", 1, True), ("tiny", 1, True)])
+def test_forward_replayed_from_a_graph(aa, name, batch, module):
+    import torch
+    wl = small(WL[name], batch)
+    t = inputs.make_qkv(wl)
+    dv = dev_qkv(wl, t)
+    params = util.params_to_device(inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, index=wl.index)) \
+        if module else None
+    kw = dict(grid=wl.grid, agent_grid=wl.agent_grid, params=params)
+    out = torch.empty_like(dv["Q"])
+    ws = torch.empty(max(256, aa.workspace_bytes(aa._desc_from(dv["Q"], wl.n, wl.grid, wl.agent_grid),
+                                                 aa.make_params(params))), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        call = aa.prepare_fwd(dv["Q"], dv["K"], dv["V"], out=out, workspace=ws, stream=side, **kw)
+        call()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            call()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        # eager work and a change of the inputs between the replays
+        for k in ("Q", "K", "V"):
+            dv[k].copy_(torch.roll(dv[k], shifts=rep + 1, dims=2))
+        ws.fill_(rep)
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], **kw)
+        assert torch.equal(out, eager), "replay %d differs from the eager call" % rep
+
+
+# --------------------------------------------------------------------------
 # seeded random problems over the whole admissible range of shapes: every kernel family, ragged pooling
 # windows, agent counts off the tile sizes, random subsets of the module terms, the SD-variant scalars
 # --------------------------------------------------------------------------
