@@ -39,6 +39,25 @@ __global__ __launch_bounds__(256) void from_f32_kernel(const float* __restrict__
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i < count) dst[i] = E::from_f32(src[i]);
 }
+// The three token gradients at once: src holds dQ, dK, dV back to back (count elements each); four
+// elements per thread.
+template <class E>
+__global__ __launch_bounds__(256) void from_f32_x3_kernel(const float* __restrict__ src, typename E::T* __restrict__ d0,
+                                                          typename E::T* __restrict__ d1, typename E::T* __restrict__ d2,
+                                                          size_t count) {
+  const size_t quads = (count + 3) / 4;
+  size_t q = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= 3 * quads) return;
+  const int which = (int)(q / quads);
+  q -= (size_t)which * quads;
+  typename E::T* dst = which == 0 ? d0 : (which == 1 ? d1 : d2);
+  const float* s = src + (size_t)which * count;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const size_t i = 4 * q + j;
+    if (i < count) dst[i] = E::from_f32(s[i]);
+  }
+}
 
 // ---------------------------------------------------------------------------
 // Batched C[u] = alpha * op(A[u]) op(B[u]) (+ C[u] when ACC), all fp32 row-major.
@@ -226,19 +245,31 @@ __device__ __forceinline__ void mfma_stage_tile(const uint16_t* __restrict__ src
   }
 }
 
+// One product of a batch: pointers, shapes, leading dimensions and per-unit strides.
+struct MatmulArgs {
+  const uint16_t* A;
+  const uint16_t* B;
+  void* C;
+  int M, Nc, Kd, lda, ldb, ldc;
+  size_t strideA, strideB, strideC;
+  float alpha;
+};
+
+// The 64 x 64 tile (tile_row, tile_col) of matrix `z` (unit * ksplit + k-slice) of one product.
 template <class E, bool TA, bool TB, int OUT>
-__global__ __launch_bounds__(256) void mfma_matmul_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
-                                                          void* __restrict__ C, int M, int Nc, int Kd, int lda, int ldb,
-                                                          int ldc, size_t strideA, size_t strideB, size_t strideC,
-                                                          float alpha, int ksplit, int kchunk) {
-  __shared__ __attribute__((aligned(16))) uint16_t As[64][kLdsK];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[64][kLdsK];
-  // blockIdx.z = unit * ksplit + k-slice; with ksplit > 1 every slice writes its own partial result
-  // (C then points at a scratch of [units * ksplit] matrices, strideC = M * ldc) and a second kernel adds
-  // the slices up in order
-  const int u = blockIdx.z / ksplit, ks = blockIdx.z - u * ksplit;
+__device__ __forceinline__ void mfma_matmul_tile(const MatmulArgs& m, int tile_row, int tile_col, int z, int ksplit,
+                                                 int kchunk, uint16_t (&As)[64][kLdsK], uint16_t (&Bs)[64][kLdsK]) {
+  const uint16_t* __restrict__ A = m.A;
+  const uint16_t* __restrict__ B = m.B;
+  void* __restrict__ C = m.C;
+  const int M = m.M, Nc = m.Nc, Kd = m.Kd, lda = m.lda, ldb = m.ldb, ldc = m.ldc;
+  const size_t strideA = m.strideA, strideB = m.strideB, strideC = m.strideC;
+  const float alpha = m.alpha;
+  // with ksplit > 1 every slice writes its own partial result (C then points at a scratch of
+  // [units * ksplit] matrices, strideC = M * ldc) and a second kernel adds the slices up in order
+  const int u = z / ksplit, ks = z - u * ksplit;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int row0 = blockIdx.y * 64, col0 = blockIdx.x * 64;
+  const int row0 = tile_row * 64, col0 = tile_col * 64;
   const uint16_t* Au = A + (size_t)u * strideA;
   const uint16_t* Bu = B + (size_t)u * strideB;
   const int wm = wave >> 1, wn = wave & 1, r = lane & 15, g = lane >> 4;
@@ -270,13 +301,37 @@ __global__ __launch_bounds__(256) void mfma_matmul_kernel(const uint16_t* __rest
       for (int e = 0; e < 4; ++e) {
         const int gm = row0 + 32 * wm + 16 * i + 4 * g + e;
         if (gm >= M) continue;
-        const size_t o = (size_t)blockIdx.z * strideC + (size_t)gm * ldc + gc;
+        const size_t o = (size_t)z * strideC + (size_t)gm * ldc + gc;
         const float v = alpha * acc[i][j][e];
         if constexpr (OUT == 0) ((float*)C)[o] = v;
         if constexpr (OUT == 1) ((float*)C)[o] += v;
         if constexpr (OUT == 2) ((uint16_t*)C)[o] = Half<E>::from_f32(v);
       }
     }
+}
+
+// grid = (column tiles, row tiles, units * ksplit)
+template <class E, bool TA, bool TB, int OUT>
+__global__ __launch_bounds__(256) void mfma_matmul_kernel(MatmulArgs m, int ksplit, int kchunk) {
+  __shared__ __attribute__((aligned(16))) uint16_t As[64][kLdsK];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[64][kLdsK];
+  mfma_matmul_tile<E, TA, TB, OUT>(m, blockIdx.y, blockIdx.x, blockIdx.z, ksplit, kchunk, As, Bs);
+}
+
+// Two independent products of the same kind in one launch (they are latency-bound at the sizes of this
+// path, so sharing a launch is worth more than the idle blocks of the smaller one):
+// grid = (tiles of m0 + tiles of m1, units): the first tiles0 blocks of a unit work on m0.
+template <class E, bool TA, bool TB, int OUT>
+__global__ __launch_bounds__(256) void mfma_matmul_pair_kernel(MatmulArgs m0, MatmulArgs m1, int tiles0) {
+  __shared__ __attribute__((aligned(16))) uint16_t As[64][kLdsK];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[64][kLdsK];
+  const bool second = (int)blockIdx.x >= tiles0;
+  const MatmulArgs& m = second ? m1 : m0;
+  const int t = second ? blockIdx.x - tiles0 : blockIdx.x, ct = (m.Nc + 63) / 64;
+  if (second)
+    mfma_matmul_tile<E, TA, TB, OUT>(m1, t / ct, t % ct, blockIdx.y, 1, (m1.Kd + 31) / 32 * 32, As, Bs);
+  else
+    mfma_matmul_tile<E, TA, TB, OUT>(m0, t / ct, t % ct, blockIdx.y, 1, (m0.Kd + 31) / 32 * 32, As, Bs);
 }
 
 constexpr int kRowCache = 16;      // row elements a lane keeps in registers in the row kernels
@@ -647,15 +702,22 @@ hipError_t mfma_matmul(const uint16_t* A, const uint16_t* B, void* C, int M, int
   const int kchunk = ((Kd + ksplit - 1) / ksplit + 31) / 32 * 32;
   const dim3 grid((Nc + 63) / 64, (M + 63) / 64, units * ksplit);
   if (ksplit == 1) {
-    mfma_matmul_kernel<E, TA, TB, OUT><<<grid, dim3(256), 0, st>>>(A, B, C, M, Nc, Kd, lda, ldb, ldc, strideA, strideB,
-                                                                  strideC, alpha, 1, kchunk);
+    mfma_matmul_kernel<E, TA, TB, OUT><<<grid, dim3(256), 0, st>>>(
+        MatmulArgs{A, B, C, M, Nc, Kd, lda, ldb, ldc, strideA, strideB, strideC, alpha}, 1, kchunk);
     return hipGetLastError();
   }
-  mfma_matmul_kernel<E, TA, TB, 0><<<grid, dim3(256), 0, st>>>(A, B, scratch, M, Nc, Kd, lda, ldb, Nc, strideA, strideB,
-                                                                (size_t)M * Nc, alpha, ksplit, kchunk);
+  mfma_matmul_kernel<E, TA, TB, 0><<<grid, dim3(256), 0, st>>>(
+      MatmulArgs{A, B, scratch, M, Nc, Kd, lda, ldb, Nc, strideA, strideB, (size_t)M * Nc, alpha}, ksplit, kchunk);
   const size_t count = (size_t)units * M * Nc;
   splitk_reduce_kernel<E, OUT><<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(scratch, C, M, Nc, ldc, strideC,
                                                                                              ksplit, count);
+  return hipGetLastError();
+}
+
+template <class E, bool TA, bool TB, int OUT>
+hipError_t mfma_matmul_pair(const MatmulArgs& m0, const MatmulArgs& m1, int units, hipStream_t st) {
+  const int tiles0 = ((m0.Nc + 63) / 64) * ((m0.M + 63) / 64), tiles1 = ((m1.Nc + 63) / 64) * ((m1.M + 63) / 64);
+  mfma_matmul_pair_kernel<E, TA, TB, OUT><<<dim3(tiles0 + tiles1, units), dim3(256), 0, st>>>(m0, m1, tiles0);
   return hipGetLastError();
 }
 
@@ -708,6 +770,16 @@ hipError_t backward_tail(const Problem& p, const float* Vf, const float* dOf, co
                                                                                       p.ah, p.aw, count);
     }
   }
+  if (dKf == dQf + u * Nd && dVf == dKf + u * Nd) {      // both callers lay them out back to back
+    const size_t count = u * Nd;
+    const dim3 grid((unsigned)((3 * ((count + 3) / 4) + 255) / 256));
+    switch (p.dtype) {
+      case 0: from_f32_x3_kernel<ElemF32><<<grid, dim3(256), 0, st>>>(dQf, (float*)dQ, (float*)dK, (float*)dV, count); break;
+      case 1: from_f32_x3_kernel<ElemF16><<<grid, dim3(256), 0, st>>>(dQf, (_Float16*)dQ, (_Float16*)dK, (_Float16*)dV, count); break;
+      default: from_f32_x3_kernel<ElemBF16><<<grid, dim3(256), 0, st>>>(dQf, (uint16_t*)dQ, (uint16_t*)dK, (uint16_t*)dV, count); break;
+    }
+    return hipGetLastError();
+  }
   AA_BWD_CHECK(from_f32(p.dtype, dQf, dQ, u * Nd, st));
   AA_BWD_CHECK(from_f32(p.dtype, dKf, dK, u * Nd, st));
   AA_BWD_CHECK(from_f32(p.dtype, dVf, dV, u * Nd, st));
@@ -743,7 +815,9 @@ hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, 
   const bool want_db1 = pg.db1_col || pg.db1_row || pg.db1_blk, want_db2 = pg.db2_col || pg.db2_row || pg.db2_blk;
 
   // forward recompute
-  AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(Ah, Kh, F1, n, N, d, d, d, ldN, nd, Nd, s1, U, p.scale1, st)));
+  // both score matrices in one launch: S1 = c1 A K^T and S2 = c2 Q A^T
+  AA_BWD_CHECK((mfma_matmul_pair<E, false, true, 0>(MatmulArgs{Ah, Kh, F1, n, N, d, d, d, ldN, nd, Nd, s1, p.scale1},
+                                                    MatmulArgs{Qh, Ah, F2, N, n, d, d, d, ldn, Nd, nd, s2, p.scale2}, U, st)));
   // rows of up to 64 elements get 16 lanes each (four rows per wave)
   auto rows_grid = [&](int rows, int lpr) { return dim3((unsigned)(((size_t)rows * lpr + 63) / 64), U); };
   if (N <= 64)
@@ -751,7 +825,6 @@ hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, 
   else
     softmax_rows16_kernel<E, 1, 64><<<rows_grid(n, 64), dim3(64), 0, st>>>(F1, P1h, n, N, ldN, p.b1, p.heads, n, p.gh, p.gw);
   AA_BWD_CHECK((mfma_matmul<E, false, false, 2>(P1h, Vh, VAh, n, d, N, ldN, d, d, s1, Nd, nd, U, 1.0f, st, dKf, u * Nd)));
-  AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(Qh, Ah, F2, N, n, d, d, d, ldn, Nd, nd, s2, U, p.scale2, st)));
   if (n <= 64)
     softmax_rows16_kernel<E, 2, 16><<<rows_grid(N, 16), dim3(64), 0, st>>>(F2, P2h, N, n, ldn, p.b2, p.heads, n, p.gh, p.gw);
   else
@@ -759,7 +832,9 @@ hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, 
 
   // broadcast stage
   AA_BWD_CHECK((mfma_matmul<E, true, false, 2>(P2h, dOh, dVAh, n, d, N, ldn, d, d, s2, Nd, nd, U, 1.0f, st, dKf, u * Nd)));
-  AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(dOh, VAh, F2, N, n, d, d, d, ldn, Nd, nd, s2, U, 1.0f, st)));
+  // dP2 = dO V_A^T and dP1 = dV_A V^T in one launch (F1's scores are no longer needed: P1 is stored)
+  AA_BWD_CHECK((mfma_matmul_pair<E, false, true, 0>(MatmulArgs{dOh, VAh, F2, N, n, d, d, d, ldn, Nd, nd, s2, 1.0f},
+                                                    MatmulArgs{dVAh, Vh, F1, n, N, d, d, d, ldN, nd, Nd, s1, 1.0f}, U, st)));
   if (n <= 64)
     softmax_grad_rows16_kernel<E, 16><<<rows_grid(N, 16), dim3(64), 0, st>>>(P2h, F2, dS2h, N, n, ldn, want_db2);
   else
@@ -768,14 +843,14 @@ hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, 
   AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(dS2h, Qh, dAf, n, d, N, ldn, d, d, s2, Nd, nd, U, p.scale2, st, dKf, u * Nd)));
 
   // aggregation stage
-  AA_BWD_CHECK((mfma_matmul<E, false, true, 0>(dVAh, Vh, F1, n, N, d, d, d, ldN, nd, Nd, s1, U, 1.0f, st)));
   if (N <= 64)
     softmax_grad_rows16_kernel<E, 16><<<rows_grid(n, 16), dim3(64), 0, st>>>(P1h, F1, dS1h, n, N, ldN, want_db1);
   else
     softmax_grad_rows16_kernel<E, 64><<<rows_grid(n, 64), dim3(64), 0, st>>>(P1h, F1, dS1h, n, N, ldN, want_db1);
   AA_BWD_CHECK((mfma_matmul<E, false, false, 1>(dS1h, Kh, dAf, n, d, N, ldN, d, d, s1, Nd, nd, U, p.scale1, st, dKf, u * Nd)));
-  AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(dS1h, Ah, dKf, N, d, n, ldN, d, d, s1, nd, Nd, U, p.scale1, st)));
-  AA_BWD_CHECK((mfma_matmul<E, true, false, 0>(P1h, dVAh, dVf, N, d, n, ldN, d, d, s1, nd, Nd, U, 1.0f, st)));
+  // dK = c1 dS1^T A and dV = P1^T dV_A in one launch
+  AA_BWD_CHECK((mfma_matmul_pair<E, true, false, 0>(MatmulArgs{dS1h, Ah, dKf, N, d, n, ldN, d, d, s1, nd, Nd, p.scale1},
+                                                    MatmulArgs{P1h, dVAh, dVf, N, d, n, ldN, d, d, s1, nd, Nd, 1.0f}, U, st)));
 
   if (p.dwc_w || p.vk != 0.0f) {      // the gathers of the module terms read fp32 copies
     AA_BWD_CHECK(to_f32(p.dtype, V, Vf, u * Nd, st));
