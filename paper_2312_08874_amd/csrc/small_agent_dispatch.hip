@@ -36,7 +36,9 @@ __global__ __launch_bounds__(64) void small_merge_kernel(const float* __restrict
 
 bool small_supported(const Problem& p) {
   // N bound: the pooling kernel divides window indices by reciprocal multiplication (exact below 2^20)
-  return (p.dtype == 1 || p.dtype == 2) && (p.d == 32 || p.d == 64) && p.n <= 64 && p.N <= (1 << 20);
+  // a unit's rows are addressed with 32-bit byte offsets (buffer loads): its extent stays below 2 GiB
+  return (p.dtype == 1 || p.dtype == 2) && (p.d == 32 || p.d == 64) && p.n <= 64 && p.N <= (1 << 20) &&
+         ((long long)p.N + 64) * p.lay.sn * 2 < (1ll << 31);
 }
 
 // The one-block-per-unit kernel keeps the unit's Q, K and V rows in LDS (160 KB per CU, some of it for
