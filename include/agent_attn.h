@@ -96,8 +96,9 @@ typedef struct {
 } aa_params;
 
 /* Bytes of device workspace agent_attn_fwd / agent_aggregate_fwd need for this
- * problem (holds A when it is pooled, the split partials (m, l, acc), V_A and a
- * few counters).  Returns 0 when the descriptor is invalid. */
+ * problem (holds A when it is pooled, the split partials (m, l, acc), V_A and,
+ * unless params->bias_tables brings prepared ones, the agent-bias tables).
+ * Returns 0 when the descriptor is invalid. */
 size_t agent_attn_workspace_bytes(const aa_desc *desc, const aa_params *params);
 
 /* Whole forward pass, Eq. (3)/(5)/(6).  A == NULL: agents are pooled from Q
