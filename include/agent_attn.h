@@ -172,7 +172,8 @@ size_t agent_attn_bwd_workspace_bytes(const aa_desc *desc, const aa_params *para
  * Q, K, V and are rounded once from fp32.  The pooled agents are rounded to the
  * element type exactly as the forward pass does; that rounding is treated as
  * the identity by the gradient.  Outputs must not overlap inputs or the
- * workspace.  Same stream, error and determinism conventions as the forward. */
+ * workspace.  Same stream, error and determinism conventions as the forward.
+ * params->bias_tables is not used here: the bias is taken from its components. */
 aa_status agent_attn_bwd(const aa_desc *desc, const void *Q, const void *K, const void *V,
                          const void *A, const aa_params *params, const void *dO, void *workspace,
                          size_t workspace_bytes, void *dQ, void *dK, void *dV, void *dA,
