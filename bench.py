@@ -209,6 +209,18 @@ def step_time(wl, binding, ring_bytes, steps, warmup, module, prepared=False):
     return ms
 
 
+def measured_copy_gbs():
+    """What a plain device-to-device copy of 1 GiB reaches on this GPU (bytes read + bytes written per
+    second): the practical ceiling next to the 8 TB/s peak that the roofline fraction is quoted against."""
+    import torch
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    ms = timed(lambda i: dst.copy_(src), 10, 3)
+    del src, dst
+    torch.cuda.empty_cache()
+    return 2.0 * (1 << 30) / (ms * 1e-3) / 1e9
+
+
 def measure(wl, binding, args, steps, warmup, module):
     import torch
     ring = Ring(wl, binding, args.ring_bytes, module)
@@ -341,6 +353,10 @@ def main():
     if not args.no_others:
         # the same workload hot (two input sets, everything stays in the Infinity Cache) and with the other
         # set of module terms (agent bias with 7x7 block components and DWC on / off), cold
+        copy_gbs = measured_copy_gbs()
+        line["measured_copy_gbs"] = copy_gbs
+        if line["roofline"]["bound"] == "hbm":
+            line["roofline"]["frac_of_measured_copy"] = line["roofline"]["achieved"] / copy_gbs
         k, w = max(50, args.steps // 3), max(5, args.warmup // 3)
         other_mode = "pure" if module else "module"
         line["variants"] = {
