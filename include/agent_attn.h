@@ -25,7 +25,7 @@
  *    pointers that are multiples of 16 bytes, anything else takes the reference kernels.  A
  *    [batch, heads, n, d], V_A and the workspace are dense.  Distinct elements of `out` must not
  *    alias.  token t = y*grid_w + x; agent a = ay*agent_w + ax.  The backward entry point
- *    accepts dense tensors only.
+ *    takes the same strides (through dense staging copies in its workspace).
  *    Element type is desc->dtype (fp32, fp16 or bf16); all accumulation is fp32;
  *    `out` is rounded once to nearest-even.
  *  - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
@@ -171,7 +171,9 @@ size_t agent_attn_bwd_workspace_bytes(const aa_desc *desc, const aa_params *para
  * receives their gradient (required).  dQ, dK, dV have the shape and type of
  * Q, K, V and are rounded once from fp32.  The pooled agents are rounded to the
  * element type exactly as the forward pass does; that rounding is treated as
- * the identity by the gradient.  Outputs must not overlap inputs or the
+ * the identity by the gradient.  Strides: Q, K, V, dQ, dK, dV use the
+ * descriptor's input strides, dO its output strides (strided tensors are staged
+ * through dense copies in the workspace).  Outputs must not overlap inputs or the
  * workspace.  Same stream, error and determinism conventions as the forward.
  * params->bias_tables is not used here: the bias is taken from its components. */
 aa_status agent_attn_bwd(const aa_desc *desc, const void *Q, const void *K, const void *V,

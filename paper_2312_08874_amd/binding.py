@@ -242,13 +242,14 @@ def agent_attn_bwd(Q, K, V, dO, A=None, *, grid=None, agent_grid=None, params: d
     fp32 gradient under the parameter's own name prefixed with "d" (db1_col, ..., ddwc_w, ddwc_b)."""
     import torch
     n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
-    assert all(t.is_contiguous() for t in (Q, K, V, dO)), "agent_attn_bwd takes dense tensors"
-    desc = _desc_from(Q, n, grid, agent_grid, scale1=scale1, scale2=scale2, v_residual_k=v_residual_k)
+    # Q, K, V (and their gradients) share one set of strides, dO may have its own (the layout of the output)
+    desc = _desc_from(Q, n, grid, agent_grid, same=(K, V), out=dO, scale1=scale1, scale2=scale2,
+                      v_residual_k=v_residual_k)
     p = make_params(params)
     need = int(lib().agent_attn_bwd_workspace_bytes(ctypes.byref(desc), _pp(p)))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
-    out = {"dQ": torch.empty_like(Q), "dK": torch.empty_like(K), "dV": torch.empty_like(V)}
+    out = {k: torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device) for k in ("dQ", "dK", "dV")}
     if A is not None:
         out["dA"] = torch.empty_like(A)
     g = aa_param_grads()

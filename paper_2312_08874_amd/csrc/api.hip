@@ -608,16 +608,21 @@ aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, cons
   return run_broadcast(pr, Q, agents, VA, V, out, pl, stream);
 }
 
-// Backward workspace: the pooled agents in the element type (256-byte aligned), then the fp32 scratch.
+// Backward workspace: the pooled agents in the element type (256-byte aligned), then the fp32 scratch, then,
+// for strided tensors, seven dense staging copies (Q, K, V, dO in; dQ, dK, dV out).
 static size_t bwd_agents_bytes(const aa_desc* d) {
   return align_up((size_t)d->batch * d->heads * d->n * d->d * elem_size(d->dtype));
+}
+static size_t bwd_stage_bytes(const aa_desc* d) {
+  return align_up((size_t)d->batch * d->heads * d->N * d->d * elem_size(d->dtype));
 }
 
 size_t agent_attn_bwd_workspace_bytes(const aa_desc* desc, const aa_params* params) {
   if (check_desc(desc, params_use_grid(params), false) != AA_OK) return 0;
   if (check_params(params) != AA_OK) return 0;
   const Problem pr = make_problem(desc, params);
-  return bwd_agents_bytes(desc) + align_up(aa::backward_workspace_floats(pr) * sizeof(float));
+  return bwd_agents_bytes(desc) + align_up(aa::backward_workspace_floats(pr) * sizeof(float)) +
+         (dense_layout(desc) ? 0 : 7 * bwd_stage_bytes(desc));
 }
 
 aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, const void* V, const void* A,
@@ -629,7 +634,6 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
   if (st != AA_OK) return st;
   st = check_params(params);
   if (st != AA_OK) return st;
-  if (!dense_layout(desc)) return AA_ERR_UNSUPPORTED;      // the backward takes dense tensors only
   if (!Q || !K || !V || !dO || !dQ || !dK || !dV) return AA_ERR_NULL;
   if (pooling ? dA != nullptr : dA == nullptr) return AA_ERR_NULL;
   aa::BackwardParamGrads pg{};
@@ -647,27 +651,54 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
   const size_t need = agent_attn_bwd_workspace_bytes(desc, params);
   if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < need) return AA_ERR_WORKSPACE;
   const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
-  const size_t big = units * desc->N * desc->d * es, small = units * desc->n * desc->d * es;
+  // Q, K, V and their gradients use the input strides, dO the output strides (it has the layout of out)
+  const size_t big = extent_bytes(desc, false), obig = extent_bytes(desc, true);
+  const size_t small = units * desc->n * desc->d * es;
   const void* ins[] = {Q, K, V, dO};
   void* outs[] = {dQ, dK, dV};
   for (int a = 0; a < 3; ++a) {
     void* o = outs[a];
     for (const void* i : ins)
-      if (overlaps(o, big, i, big)) return AA_ERR_ALIAS;
+      if (overlaps(o, big, i, i == dO ? obig : big)) return AA_ERR_ALIAS;
     if (overlaps(o, big, A, small) || overlaps(o, big, workspace, workspace_bytes) || overlaps(o, big, dA, small))
       return AA_ERR_ALIAS;
     for (int b = a + 1; b < 3; ++b)
       if (overlaps(o, big, outs[b], big)) return AA_ERR_ALIAS;
   }
   for (const void* i : ins)
-    if (overlaps(workspace, workspace_bytes, i, big) || overlaps(dA, small, i, big)) return AA_ERR_ALIAS;
+    if (overlaps(workspace, workspace_bytes, i, i == dO ? obig : big) || overlaps(dA, small, i, i == dO ? obig : big))
+      return AA_ERR_ALIAS;
   if (overlaps(workspace, workspace_bytes, A, small) || overlaps(dA, small, A, small) ||
       overlaps(dA, small, workspace, workspace_bytes))
     return AA_ERR_ALIAS;
 
-  const Problem pr = make_problem(desc, params);
+  Problem pr = make_problem(desc, params);
   hipStream_t stream = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
+  // Strided tensors: the kernels below work on dense copies staged at the end of the workspace
+  void* sdQ = nullptr;
+  void* sdK = nullptr;
+  void* sdV = nullptr;
+  void *udQ = dQ, *udK = dK, *udV = dV;
+  const Problem strided_pr = pr;
+  if (!dense_layout(desc)) {
+    const size_t sb = bwd_stage_bytes(desc);
+    char* stage = ws + need - 7 * sb;
+    AA_HIP(aa::launch_restride(pr, true, false, Q, stage, stream));
+    AA_HIP(aa::launch_restride(pr, true, false, K, stage + sb, stream));
+    AA_HIP(aa::launch_restride(pr, true, false, V, stage + 2 * sb, stream));
+    AA_HIP(aa::launch_restride(pr, true, true, dO, stage + 3 * sb, stream));
+    Q = stage;
+    K = stage + sb;
+    V = stage + 2 * sb;
+    dO = stage + 3 * sb;
+    sdQ = dQ = stage + 4 * sb;
+    sdK = dK = stage + 5 * sb;
+    sdV = dV = stage + 6 * sb;
+    aa_desc dd = *desc;
+    dd.stride_b = dd.stride_h = dd.stride_n = dd.out_stride_b = dd.out_stride_h = dd.out_stride_n = 0;
+    pr.lay = layout_of(&dd);
+  }
   const void* agents = A;
   if (pooling) {
     st = run_pool(pr, Q, ws, stream);
@@ -678,6 +709,11 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
                         aligned16(V) && aligned16(dO) && aligned16(agents);
   AA_HIP(aa::launch_backward(pr, Q, K, V, agents, dO, (float*)(ws + bwd_agents_bytes(desc)), dQ, dK, dV, dA, !pooling,
                              use_mfma, pg, stream));
+  if (sdQ) {
+    AA_HIP(aa::launch_restride(strided_pr, false, false, sdQ, udQ, stream));
+    AA_HIP(aa::launch_restride(strided_pr, false, false, sdK, udK, stream));
+    AA_HIP(aa::launch_restride(strided_pr, false, false, sdV, udV, stream));
+  }
   return AA_OK;
 }
 

@@ -458,6 +458,40 @@ hipError_t launch_bias_half(const Problem& p, float* half1, float* rows1, float*
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Dense <-> strided copies of a [units][N][d] token tensor (the backward pass works on dense copies of
+// strided tensors).  T only carries the element size.  thread = one element.
+// ---------------------------------------------------------------------------
+template <class T, bool TO_DENSE>
+__global__ __launch_bounds__(256) void restride_kernel(const T* __restrict__ src, T* __restrict__ dst, int N, int d,
+                                                       int heads, long long sb, long long sh, int sn, size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  const int c = (int)(i % d);
+  const size_t row = i / d;
+  const int t = (int)(row % N), u = (int)(row / N);
+  const size_t strided = (size_t)(u / heads) * (size_t)sb + (size_t)(u % heads) * (size_t)sh + (size_t)t * sn + c;
+  if (TO_DENSE)
+    dst[i] = src[strided];
+  else
+    dst[strided] = src[i];
+}
+
+hipError_t launch_restride(const Problem& p, bool to_dense, bool out_layout, const void* src, void* dst, hipStream_t st) {
+  const size_t count = (size_t)p.units * p.N * p.d;
+  const long long sb = out_layout ? p.lay.ob : p.lay.sb, sh = out_layout ? p.lay.oh : p.lay.sh;
+  const int sn = out_layout ? p.lay.on : p.lay.sn;
+  const dim3 grid((unsigned)((count + 255) / 256));
+  if (p.dtype == 0) {
+    if (to_dense) restride_kernel<float, true><<<grid, dim3(256), 0, st>>>((const float*)src, (float*)dst, p.N, p.d, p.heads, sb, sh, sn, count);
+    else restride_kernel<float, false><<<grid, dim3(256), 0, st>>>((const float*)src, (float*)dst, p.N, p.d, p.heads, sb, sh, sn, count);
+  } else {
+    if (to_dense) restride_kernel<uint16_t, true><<<grid, dim3(256), 0, st>>>((const uint16_t*)src, (uint16_t*)dst, p.N, p.d, p.heads, sb, sh, sn, count);
+    else restride_kernel<uint16_t, false><<<grid, dim3(256), 0, st>>>((const uint16_t*)src, (uint16_t*)dst, p.N, p.d, p.heads, sb, sh, sn, count);
+  }
+  return hipGetLastError();
+}
+
 size_t bias_dense_floats(int kind, int heads, int n, int N) {
   return kind == 1 ? (size_t)heads * round_up64(n) * round_up64(N) : (size_t)heads * N * round_up64(n);
 }

@@ -38,6 +38,9 @@ hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, hipStream
 // layout of BiasArgs, in one launch; a null output skips that kind
 size_t bias_dense_floats(int kind, int heads, int n, int N);
 hipError_t launch_bias_dense(const Problem& p, float* out1, float* out2, hipStream_t st);
+// dense <-> strided copy of a [units][N][d] token tensor in the problem's element type; the strided side
+// uses the input strides of p.lay, or its output strides (out_layout)
+hipError_t launch_restride(const Problem& p, bool to_dense, bool out_layout, const void* src, void* dst, hipStream_t st);
 // the half-resized tables of BiasArgs (he = table rows per agent: blk_h0, or 1 without block components)
 size_t bias_half_floats(int heads, int n, int gw, int he);
 size_t bias_rows_floats(int heads, int n, int gh);

@@ -200,3 +200,9 @@ def test_bwd_rejects_bad_arguments():
     p = aa_params()
     p.b1_col = 12 * G
     assert call(params=p, grads=g, ws_bytes=need - 1) == -5     # accepted up to the workspace check
+    # strided tensors are staged through dense copies: seven more [units, N, d] buffers in the workspace
+    tm = make_desc(2, 3, 196, 49, 32, binding.AA_BF16, (14, 14), (7, 7), strides=(196 * 96, 32, 96),
+                   out_strides=(196 * 96, 32, 96))
+    need_tm = L.agent_attn_bwd_workspace_bytes(ctypes.byref(tm), None)
+    assert need_tm - need == 7 * 6 * 196 * 32 * 2
+    assert call(desc=tm, ws_bytes=need) == -5 and call(desc=tm, dQ=G + 64) == -6

@@ -186,3 +186,35 @@ def test_backward_random_problems(aa, oracle, seed):
     _run_case(aa, oracle, wl, given=bool(rng.random() < 0.3), module=module,
               blk=(int(rng.integers(1, 6)), int(rng.integers(1, 6))), kw=kw)
 
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("layout", ["token_major", "fused_qkv"])
+def test_backward_strided_layouts(aa, dtype, layout):
+    """Token-major [B,N,H,d] tensors and the q / k / v slices of a fused projection [B,N,3,H,d]: the
+    backward pass stages them through dense copies, so every gradient has the bits of the dense call
+    and lands with the strides of its tensor."""
+    import torch
+    wl = _wl("strided", dtype, (9, 8), (3, 4), 32 if dtype == "bf16" else 20, batch=2, heads=3, index=71)
+    t = inputs.make_qkv(wl)
+    dO = inputs.make_tensor((wl.units, wl.N, wl.d), stream=wl.index * 16 + 12, dtype=wl.dtype)
+    shape = (wl.batch, wl.heads, wl.N, wl.d)
+    dense = {k: util.to_device(v, wl.dtype, shape) for k, v in t.items()}
+    dense["dO"] = util.to_device(dO, wl.dtype, shape)
+    params = util.params_to_device(inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, blk=(3, 2), index=wl.index))
+    kw = dict(grid=wl.grid, agent_grid=wl.agent_grid, params=params)
+    ref = aa.agent_attn_bwd(dense["Q"], dense["K"], dense["V"], dense["dO"], **kw)
+    if layout == "token_major":
+        view = {k: v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for k, v in dense.items()}
+    else:
+        fused = torch.stack([dense[k].permute(0, 2, 1, 3) for k in ("Q", "K", "V")], dim=2).contiguous()   # [B,N,3,H,d]
+        view = {k: fused[:, :, i].permute(0, 2, 1, 3) for i, k in enumerate(("Q", "K", "V"))}
+        view["dO"] = dense["dO"].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    assert not view["Q"].is_contiguous()
+    got = aa.agent_attn_bwd(view["Q"], view["K"], view["V"], view["dO"], **kw)
+    for k in ("dQ", "dK", "dV"):
+        assert got[k].stride() == view["Q"].stride()
+        assert torch.equal(got[k], ref[k]), k
+    for k in ref:
+        if k not in ("dQ", "dK", "dV"):
+            assert torch.equal(got[k], ref[k]), k
+
