@@ -260,14 +260,23 @@ def test_module_terms_many_agents(aa, oracle, which, grid, agrid, blk, dtype, d)
                        max_abs=1e-2 * max(1.0, float(np.abs(ref).max())))
 
 
-@pytest.mark.parametrize("name,batch", [("deit_t", 2), ("swin_t_s1", 1), ("sd_latent", 1)])
+_PREPARED_EXTRA = {"large_dense_many": dict(grid=(15, 15), agent_grid=(10, 13), d=64, dtype="bf16", heads=2),
+                   "large_dense_few": dict(grid=(12, 10), agent_grid=(3, 5), d=40, dtype="f16", heads=2)}
+
+
+@pytest.mark.parametrize("name,batch", [("deit_t", 2), ("swin_t_s1", 1), ("sd_latent", 1), ("large_dense_many", 2),
+                                        ("large_dense_few", 2)])
 def test_prepared_bias_tables(aa, name, batch):
     """Bias tables built once by agent_attn_bias_tables() and passed in aa_params give the very bits of the
     tables the forward pass builds per call (dense tables on the small-agent kernels, half-expanded ones
     on the large-agent kernels), for another batch size too; the broadcast stage, which has no workspace
     and otherwise evaluates the components per score, reads them as well."""
+    import dataclasses
     import torch
-    wl = small(WL[name], batch)
+    if name in _PREPARED_EXTRA:      # dense tables read by the large-agent kernels
+        wl = dataclasses.replace(WL["tiny"], batch=batch, index=31, **_PREPARED_EXTRA[name])
+    else:
+        wl = small(WL[name], batch)
     t = inputs.make_qkv(wl)
     params = util.params_to_device(inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, index=wl.index))
     dv = dev_qkv(wl, t)
