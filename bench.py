@@ -221,6 +221,26 @@ def measured_copy_gbs():
     return 2.0 * (1 << 30) / (ms * 1e-3) / 1e9
 
 
+def single_call_latency_us(wl, binding):
+    """Host-visible latency of one isolated forward call: enqueue + wait, median of 30 (launch-bound
+    problems such as the fp32 parity configuration are priced by this, not by a roofline)."""
+    import statistics
+    import torch
+    ring = Ring(wl, binding, 1.0, False)
+    for i in range(5):
+        ring.forward(i)
+    torch.cuda.synchronize()
+    samples = []
+    for i in range(30):
+        t0 = time.perf_counter()
+        ring.forward(i)
+        torch.cuda.synchronize()
+        samples.append((time.perf_counter() - t0) * 1e6)
+    del ring
+    torch.cuda.empty_cache()
+    return statistics.median(samples)
+
+
 def measure(wl, binding, args, steps, warmup, module):
     import torch
     ring = Ring(wl, binding, args.ring_bytes, module)
@@ -365,6 +385,7 @@ def main():
             "%s_hot_us" % other_mode: step_time(wl, binding, 1.0, k, w, not module) * 1e3,
             "module_prepared_bias_cold_us": step_time(wl, binding, args.ring_bytes, k, w, True, True) * 1e3,
         }
+        line["variants"]["tiny_single_call_latency_us"] = single_call_latency_us(inputs.WORKLOADS["tiny"], binding)
         others = {}
         for name, w in inputs.WORKLOADS.items():
             if name == wl.name:
