@@ -373,8 +373,8 @@ aa_status run_aggregate(const Problem& pr, const void* A, const void* K, const v
     return AA_OK;
   }
   const Partials part = partials_in(ws, pl, pl.S);
-  AA_HIP(aa::launch_aggregate_generic(pr, A, K, V, part, st));
-  AA_HIP(aa::launch_merge_generic(pr, part, VA, st));
+  AA_HIP(aa::launch_aggregate_generic(pr, A, K, V, part, VA, st));
+  if (part.S > 1) AA_HIP(aa::launch_merge_generic(pr, part, VA, st));
   return AA_OK;
 }
 
@@ -736,8 +736,8 @@ size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, siz
                    agents_given ? "" : "pool_chunk + ", pl.S_large, pl.waves_large * pl.nw_large * 16,
                    32 * pl.bcast_waves_large);
   } else {
-    len = snprintf(buf, buf_len, "%saggregate_generic(S=%d) + merge_generic + broadcast_generic",
-                   agents_given ? "" : "pool_generic + ", pl.S);
+    len = snprintf(buf, buf_len, "%saggregate_generic(S=%d) + %sbroadcast_generic", agents_given ? "" : "pool_generic + ",
+                   pl.S, pl.S > 1 ? "merge_generic + " : "");
   }
   if (len < 0) return 0;
   return (size_t)len < buf_len ? (size_t)len : buf_len - 1;

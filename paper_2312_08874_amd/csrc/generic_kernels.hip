@@ -94,7 +94,8 @@ template <class E>
 __global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
     const typename E::T* __restrict__ A, const typename E::T* __restrict__ K,
     const typename E::T* __restrict__ V, BiasArgs b1, float scale, int N, int n, int d, int heads, Layout lay,
-    int gh, int gw, int S, float* __restrict__ part_acc, float* __restrict__ part_m, float* __restrict__ part_l) {
+    int gh, int gw, int S, float* __restrict__ part_acc, float* __restrict__ part_m, float* __restrict__ part_l,
+    float* __restrict__ VA_direct) {
   extern __shared__ float smem[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int a = blockIdx.x * kWaves + wave;
@@ -156,7 +157,14 @@ __global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
     __syncthreads();
   }
 
-  if (active) {
+  if (active && VA_direct) {      // a single split is the whole sum: normalise here, as the merge would
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int k = 0; k < kMaxDPerLane; ++k) {
+      const int c = lane + 64 * k;
+      if (c < d) VA_direct[((size_t)u * n + a) * d + c] = acc[k] * inv;
+    }
+  } else if (active) {
     const size_t row = ((size_t)u * S + s) * n + a;
 #pragma unroll
     for (int k = 0; k < kMaxDPerLane; ++k) {
@@ -526,13 +534,14 @@ hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, hipStream
   return hipGetLastError();
 }
 
+// VA_direct: with one split (part.S == 1) the kernel may write the normalised V_A itself (no merge launch)
 hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* K, const void* V,
-                                    const Partials& part, hipStream_t st) {
+                                    const Partials& part, float* VA_direct, hipStream_t st) {
   dim3 grid((p.n + kWaves - 1) / kWaves, part.S, p.units);
   const size_t lds = (size_t)kWaves * (p.d + 64) * sizeof(float);
   AA_DISPATCH_DTYPE(p.dtype, aggregate_generic_kernel<E><<<grid, dim3(64 * kWaves), lds, st>>>(
       (const typename E::T*)A, (const typename E::T*)K, (const typename E::T*)V, p.b1, p.scale1, p.N, p.n, p.d,
-      p.heads, p.lay, p.gh, p.gw, part.S, part.acc, part.m, part.l));
+      p.heads, p.lay, p.gh, p.gw, part.S, part.acc, part.m, part.l, part.S == 1 ? VA_direct : nullptr));
   return hipGetLastError();
 }
 

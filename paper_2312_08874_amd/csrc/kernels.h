@@ -46,7 +46,7 @@ size_t bias_half_floats(int heads, int n, int gw, int he);
 size_t bias_rows_floats(int heads, int n, int gh);
 hipError_t launch_bias_half(const Problem& p, float* half1, float* rows1, float* half2, float* rows2, hipStream_t st);
 hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* K, const void* V,
-                                    const Partials& part, hipStream_t st);
+                                    const Partials& part, float* VA_direct, hipStream_t st);
 hipError_t launch_merge_generic(const Problem& p, const Partials& part, float* VA, hipStream_t st);
 hipError_t launch_broadcast_generic(const Problem& p, const void* Q, const void* A, const float* VA,
                                     const void* V, void* out, hipStream_t st);
