@@ -131,6 +131,7 @@ __global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
     if (valid) {
       const typename E::T* kr = Ku + (size_t)t * lay.sn;
       float dot = 0.0f;
+#pragma unroll 8
       for (int c = 0; c < d; ++c) dot += a_row[c] * E::to_f32(kr[c]);
       sc = dot * scale;
       if (has_bias) sc += bias1_at(b, a, t / gw, t % gw, gh, gw);
@@ -149,6 +150,7 @@ __global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
         const int c = lane + 64 * k;
         if (c < d) {
           float v = acc[k] * alpha;
+#pragma unroll 8
           for (int j = 0; j < cnt; ++j) v += p_sh[j] * E::to_f32(Vu[(size_t)(tb + j) * lay.sn + c]);
           acc[k] = v;
         }
@@ -242,6 +244,7 @@ __global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
     for (int a = lane; a < n; a += 64) {
       const typename E::T* ar = A + ((size_t)u * n + a) * d;
       float dot = 0.0f;
+#pragma unroll 8
       for (int c = 0; c < d; ++c) dot += q_row[c] * E::to_f32(ar[c]);
       float s = dot * scale;
       if (has_bias) s += bias2_at(b, a, y, x, gh, gw, n);
@@ -264,6 +267,7 @@ __global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
     const float* VAu = VA + (size_t)u * n * d;
     for (int c = lane; c < d; c += 64) {
       float o = 0.0f;
+#pragma unroll 8
       for (int a = 0; a < n; ++a) o += sc[a] * VAu[(size_t)a * d + c];
       o *= inv;
       if (dwc_w) {
