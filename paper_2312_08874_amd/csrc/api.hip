@@ -5,7 +5,6 @@
 
 #include <math.h>
 #include <stdio.h>
-#include <stdlib.h>
 
 #include <initializer_list>
 
@@ -43,6 +42,7 @@ struct Plan {
   int bcast_chunks;    // token chunks per unit of the small-agent broadcast
   bool prefer_fused;   // small-agent regime: one block per unit does the whole pass
   size_t off_A;        // pooled agents, element type of the problem
+  size_t off_Alo;      // what rounding them to the element type left over (fp16 / bf16), same shape
   size_t off_acc, off_m, off_l;
   size_t off_VA;       // merged V_A, fp32
   BiasPlan bias;       // agent-bias tables, offsets relative to off_bias
@@ -114,25 +114,12 @@ int choose_splits(const aa_desc* d) {
   return S;
 }
 
-// Tuning overrides for sweeps: integer environment variables, read only by builds made with
-// -DAA_TUNING_ENV; the library as shipped ignores the environment and always takes the built-in choice.
-int tuning_env(const char* name) {
-#ifdef AA_TUNING_ENV
-  const char* v = getenv(name);
-  return v ? atoi(v) : 0;
-#else
-  (void)name;
-  return 0;
-#endif
-}
-
 // Splits / chunks of the small-agent path.  An explicit n_splits forces the multi-kernel path
 // with that many splits (rounded so that every split is a non-empty multiple of 32 tokens).
 void plan_small(const aa_desc* d, Plan& pl) {
   const int64_t units = (int64_t)d->batch * d->heads;
   int S = d->n_splits;
   pl.prefer_fused = (S <= 0);   // taken when the unit's Q rows fit in LDS, see run time check
-  if (S <= 0 && tuning_env("AA_SMALL_S") > 0) S = tuning_env("AA_SMALL_S");
   if (S <= 0) {
     S = (int)((448 + units - 1) / units);      // a few hundred blocks: one resident round on 256 CUs (swept)
     const int max_by_len = (d->N + 127) / 128;
@@ -143,13 +130,10 @@ void plan_small(const aa_desc* d, Plan& pl) {
   const int chunk = aa::small_split_chunk(d->N, S);
   pl.S_small = (d->N + chunk - 1) / chunk;
   // tokens per broadcast block: about 448 blocks in all as well, 256 to 1024 tokens each (swept)
-  int btok = tuning_env("AA_SMALL_BTOK");
-  if (btok < 32) {
-    const int64_t want = (448 + units - 1) / units;
-    btok = (int)((d->N + want - 1) / want);
-    btok = (btok + 31) / 32 * 32;
-    btok = btok < 256 ? 256 : (btok > 1024 ? 1024 : btok);
-  }
+  const int64_t want = (448 + units - 1) / units;
+  int btok = (int)((d->N + want - 1) / want);
+  btok = (btok + 31) / 32 * 32;
+  btok = btok < 256 ? 256 : (btok > 1024 ? 1024 : btok);
   pl.bcast_chunks = (d->N + btok - 1) / btok;
 }
 
@@ -158,17 +142,13 @@ void plan_small(const aa_desc* d, Plan& pl) {
 void plan_large(const aa_desc* d, Plan& pl) {
   const int64_t units = (int64_t)d->batch * d->heads;
   pl.nw_large = 1;     // one 16-agent tile per wave: 117 VGPRs, two blocks of 8 waves per CU (measured best)
-  if (tuning_env("AA_LARGE_NW") == 1 || tuning_env("AA_LARGE_NW") == 2) pl.nw_large = tuning_env("AA_LARGE_NW");
   int waves = (d->n + 16 * pl.nw_large - 1) / (16 * pl.nw_large);
   if (waves > 8) waves = 8;
-  if (tuning_env("AA_LARGE_WAVES") >= 4 && tuning_env("AA_LARGE_WAVES") <= 8 && waves > tuning_env("AA_LARGE_WAVES"))
-    waves = tuning_env("AA_LARGE_WAVES");
   if (waves < 4) waves = 4;          // the staging copies want at least 256 threads
   pl.waves_large = waves;
   const int apb = waves * pl.nw_large * 16;
   const int64_t nblocks = (d->n + apb - 1) / apb;
   int S = d->n_splits;
-  if (S <= 0 && tuning_env("AA_LARGE_S") > 0) S = tuning_env("AA_LARGE_S");
   if (S <= 0) {
     S = (int)((512 + units * nblocks - 1) / (units * nblocks));
     const int max_by_len = (d->N + 127) / 128;
@@ -181,8 +161,6 @@ void plan_large(const aa_desc* d, Plan& pl) {
   pl.chunk_large = chunk;
   pl.S_large = (d->N + chunk - 1) / chunk;
   pl.bcast_waves_large = 8;
-  if (tuning_env("AA_LARGE_BWAVES") >= 4 && tuning_env("AA_LARGE_BWAVES") <= 8)
-    pl.bcast_waves_large = tuning_env("AA_LARGE_BWAVES");
 }
 
 // The dense form of the agent bias is built in the workspace when it stays below this size per kind
@@ -233,6 +211,8 @@ Plan make_plan(const aa_desc* d, const aa_params* params = nullptr) {
   if (pl.S_large > Smax) Smax = pl.S_large;
   size_t off = 0;
   pl.off_A = off;
+  off += align_up(units * d->n * d->d * elem_size(d->dtype));
+  pl.off_Alo = off;
   off += align_up(units * d->n * d->d * elem_size(d->dtype));
   pl.off_acc = off;
   off += align_up(units * Smax * d->n * d->d * sizeof(float));
@@ -346,11 +326,12 @@ aa_status check_workspace(const void* ws, size_t bytes, const Plan& pl) {
     if ((call) != hipSuccess) return AA_ERR_HIP; \
   } while (0)
 
-aa_status run_aggregate(const Problem& pr, const void* A, const void* K, const void* V, void* ws, const Plan& pl,
-                        float* VA, hipStream_t st) {
+// Alo: residual of pooled agents (see kernels.h), null for agents that were handed in
+aa_status run_aggregate(const Problem& pr, const void* A, const void* Alo, const void* K, const void* V, void* ws,
+                        const Plan& pl, float* VA, hipStream_t st) {
   if (use_small(pr, {A, K, V})) {
     const Partials part = partials_in(ws, pl, pl.S_small);
-    AA_HIP(aa::launch_small_aggregate(pr, A, K, V, part, st));
+    AA_HIP(aa::launch_small_aggregate(pr, A, Alo, K, V, part, st));
     AA_HIP(aa::launch_small_merge(pr, part, VA, st));
     return AA_OK;
   }
@@ -358,38 +339,38 @@ aa_status run_aggregate(const Problem& pr, const void* A, const void* K, const v
     const Partials part = partials_in(ws, pl, pl.S_large);
     switch (padded_width(pr.d)) {
       case 32:
-        AA_HIP(aa::launch_large_aggregate_dp32(pr, A, K, V, part, pl.chunk_large, pl.waves_large, pl.nw_large, st));
+        AA_HIP(aa::launch_large_aggregate_dp32(pr, A, Alo, K, V, part, pl.chunk_large, pl.waves_large, pl.nw_large, st));
         AA_HIP(aa::launch_large_merge_dp32(pr, part, VA, st));
         break;
       case 64:
-        AA_HIP(aa::launch_large_aggregate_dp64(pr, A, K, V, part, pl.chunk_large, pl.waves_large, pl.nw_large, st));
+        AA_HIP(aa::launch_large_aggregate_dp64(pr, A, Alo, K, V, part, pl.chunk_large, pl.waves_large, pl.nw_large, st));
         AA_HIP(aa::launch_large_merge_dp64(pr, part, VA, st));
         break;
       default:
-        AA_HIP(aa::launch_large_aggregate_dp128(pr, A, K, V, part, pl.chunk_large, pl.waves_large, pl.nw_large, st));
+        AA_HIP(aa::launch_large_aggregate_dp128(pr, A, Alo, K, V, part, pl.chunk_large, pl.waves_large, pl.nw_large, st));
         AA_HIP(aa::launch_large_merge_dp128(pr, part, VA, st));
         break;
     }
     return AA_OK;
   }
   const Partials part = partials_in(ws, pl, pl.S);
-  AA_HIP(aa::launch_aggregate_generic(pr, A, K, V, part, VA, st));
+  AA_HIP(aa::launch_aggregate_generic(pr, A, Alo, K, V, part, VA, st));
   if (part.S > 1) AA_HIP(aa::launch_merge_generic(pr, part, VA, st));
   return AA_OK;
 }
 
-aa_status run_broadcast(const Problem& pr, const void* Q, const void* A, const float* VA, const void* V, void* out,
-                        const Plan& pl, hipStream_t st) {
+aa_status run_broadcast(const Problem& pr, const void* Q, const void* A, const void* Alo, const float* VA,
+                        const void* V, void* out, const Plan& pl, hipStream_t st) {
   if (use_small(pr, {Q, A, V, out})) {
-    AA_HIP(aa::launch_small_broadcast(pr, Q, A, VA, nullptr, V, out, pl.bcast_chunks, st));
+    AA_HIP(aa::launch_small_broadcast(pr, Q, A, Alo, VA, nullptr, V, out, pl.bcast_chunks, st));
   } else if (use_large(pr, {Q, A, VA, V, out})) {
     switch (padded_width(pr.d)) {
-      case 32: AA_HIP(aa::launch_large_broadcast_dp32(pr, Q, A, VA, V, out, pl.bcast_waves_large, st)); break;
-      case 64: AA_HIP(aa::launch_large_broadcast_dp64(pr, Q, A, VA, V, out, pl.bcast_waves_large, st)); break;
-      default: AA_HIP(aa::launch_large_broadcast_dp128(pr, Q, A, VA, V, out, pl.bcast_waves_large, st)); break;
+      case 32: AA_HIP(aa::launch_large_broadcast_dp32(pr, Q, A, Alo, VA, V, out, pl.bcast_waves_large, st)); break;
+      case 64: AA_HIP(aa::launch_large_broadcast_dp64(pr, Q, A, Alo, VA, V, out, pl.bcast_waves_large, st)); break;
+      default: AA_HIP(aa::launch_large_broadcast_dp128(pr, Q, A, Alo, VA, V, out, pl.bcast_waves_large, st)); break;
     }
   } else {
-    AA_HIP(aa::launch_broadcast_generic(pr, Q, A, VA, V, out, st));
+    AA_HIP(aa::launch_broadcast_generic(pr, Q, A, Alo, VA, V, out, st));
   }
   return AA_OK;
 }
@@ -443,13 +424,14 @@ aa_status prepare_dense_bias(Problem& pr, const Plan& pl, const aa_params* param
   return prepare_bias_tables(pr, pl.bias, (char*)workspace + pl.off_bias, true, st);
 }
 
-aa_status run_pool(const Problem& pr, const void* Q, void* A, hipStream_t st) {
+// Alo: where to put the residual of the pooled agents (fp16 / bf16; see kernels.h), or null
+aa_status run_pool(const Problem& pr, const void* Q, void* A, void* Alo, hipStream_t st) {
   if (use_small(pr, {Q, A}))
-    AA_HIP(aa::launch_small_pool(pr, Q, A, st));
+    AA_HIP(aa::launch_small_pool(pr, Q, A, Alo, st));
   else if ((pr.dtype == 1 || pr.dtype == 2) && pr.d % 8 == 0 && aligned16(Q) && aligned16(A))
-    AA_HIP(aa::launch_pool_chunk(pr, Q, A, st));
+    AA_HIP(aa::launch_pool_chunk(pr, Q, A, Alo, st));
   else
-    AA_HIP(aa::launch_pool_generic(pr, Q, A, st));
+    AA_HIP(aa::launch_pool_generic(pr, Q, A, Alo, st));
   return AA_OK;
 }
 
@@ -500,7 +482,7 @@ aa_status agent_pool_fwd(const aa_desc* desc, const void* Q, void* A_out, void* 
   const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
   if (overlaps(A_out, units * desc->n * desc->d * es, Q, extent_bytes(desc, false))) return AA_ERR_ALIAS;
   Problem pr = make_problem(desc, nullptr);
-  return run_pool(pr, Q, A_out, (hipStream_t)hip_stream);
+  return run_pool(pr, Q, A_out, nullptr, (hipStream_t)hip_stream);
 }
 
 aa_status agent_aggregate_fwd(const aa_desc* desc, const void* A, const void* K, const void* V,
@@ -527,7 +509,7 @@ aa_status agent_aggregate_fwd(const aa_desc* desc, const void* A, const void* K,
   st = prepare_dense_bias(pr, pl, params, workspace, use_small(pr, {A, K, V}) || use_large(pr, {A, K, V}),
                           (hipStream_t)hip_stream);
   if (st != AA_OK) return st;
-  return run_aggregate(pr, A, K, V, workspace, pl, VA_out, (hipStream_t)hip_stream);
+  return run_aggregate(pr, A, nullptr, K, V, workspace, pl, VA_out, (hipStream_t)hip_stream);
 }
 
 aa_status agent_broadcast_fwd(const aa_desc* desc, const void* Q, const void* A, const float* VA, const void* V,
@@ -554,7 +536,7 @@ aa_status agent_broadcast_fwd(const aa_desc* desc, const void* Q, const void* A,
                             (hipStream_t)hip_stream);
     if (st != AA_OK) return st;
   }
-  return run_broadcast(pr, Q, A, VA, V, out, pl, (hipStream_t)hip_stream);
+  return run_broadcast(pr, Q, A, nullptr, VA, V, out, pl, (hipStream_t)hip_stream);
 }
 
 aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, const void* V, const void* A,
@@ -589,23 +571,28 @@ aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, cons
     AA_HIP(aa::launch_small_fused(pr, Q, K, V, A, out, stream));
     return AA_OK;
   }
+  // Pooled agents are kept in two element-type terms (rounded value + residual) so that the 16-bit rounding of
+  // an average does not enter the scores; agents handed in are exact in the element type.
   const void* agents = A;
+  const void* agents_lo = nullptr;
   if (pooling) {
-    st = run_pool(pr, Q, ws + pl.off_A, stream);
+    void* lo = pr.dtype == AA_F32 ? nullptr : ws + pl.off_Alo;
+    st = run_pool(pr, Q, ws + pl.off_A, lo, stream);
     if (st != AA_OK) return st;
     agents = ws + pl.off_A;
+    agents_lo = lo;
   }
   float* VA = (float*)(ws + pl.off_VA);
   if (use_small(pr, {Q, K, V, agents, out})) {
     // small-agent regime: the broadcast blocks merge the split partials themselves (no merge launch)
     const Partials part = partials_in(workspace, pl, pl.S_small);
-    AA_HIP(aa::launch_small_aggregate(pr, agents, K, V, part, stream));
-    AA_HIP(aa::launch_small_broadcast(pr, Q, agents, nullptr, &part, V, out, pl.bcast_chunks, stream));
+    AA_HIP(aa::launch_small_aggregate(pr, agents, agents_lo, K, V, part, stream));
+    AA_HIP(aa::launch_small_broadcast(pr, Q, agents, agents_lo, nullptr, &part, V, out, pl.bcast_chunks, stream));
     return AA_OK;
   }
-  st = run_aggregate(pr, agents, K, V, workspace, pl, VA, stream);
+  st = run_aggregate(pr, agents, agents_lo, K, V, workspace, pl, VA, stream);
   if (st != AA_OK) return st;
-  return run_broadcast(pr, Q, agents, VA, V, out, pl, stream);
+  return run_broadcast(pr, Q, agents, agents_lo, VA, V, out, pl, stream);
 }
 
 // Backward workspace: the pooled agents in the element type (256-byte aligned), then the fp32 scratch, then,
@@ -701,7 +688,7 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
   }
   const void* agents = A;
   if (pooling) {
-    st = run_pool(pr, Q, ws, stream);
+    st = run_pool(pr, Q, ws, nullptr, stream);
     if (st != AA_OK) return st;
     agents = ws;
   }

@@ -16,7 +16,8 @@ constexpr int kMaxDPerLane = 4;       // d <= 64 * kMaxDPerLane
 // ---------------------------------------------------------------------------
 template <class E>
 __global__ __launch_bounds__(64) void pool_generic_kernel(const typename E::T* __restrict__ Q,
-                                                          typename E::T* __restrict__ A, int N, int n, int d,
+                                                          typename E::T* __restrict__ A,
+                                                          typename E::T* __restrict__ Alo, int N, int n, int d,
                                                           int heads, Layout lay, int gh, int gw, int ah, int aw) {
   const int a = blockIdx.x, u = blockIdx.y;
   const int ay = a / aw, ax = a % aw;
@@ -28,7 +29,10 @@ __global__ __launch_bounds__(64) void pool_generic_kernel(const typename E::T* _
     float acc = 0.0f;
     for (int y = y0; y < y1; ++y)
       for (int x = x0; x < x1; ++x) acc += E::to_f32(q[((size_t)y * gw + x) * lay.sn + c]);
-    A[((size_t)u * n + a) * d + c] = E::from_f32(acc * inv);
+    const float mean = acc * inv;
+    const typename E::T hi = E::from_f32(mean);
+    A[((size_t)u * n + a) * d + c] = hi;
+    if (Alo) Alo[((size_t)u * n + a) * d + c] = E::from_f32(mean - E::to_f32(hi));      // what the rounding left over
   }
 }
 
@@ -39,8 +43,8 @@ __global__ __launch_bounds__(64) void pool_generic_kernel(const typename E::T* _
 // ---------------------------------------------------------------------------
 template <class E>
 __global__ __launch_bounds__(256) void pool_chunk_kernel(const uint16_t* __restrict__ Q, uint16_t* __restrict__ A,
-                                                         int N, int n, int d, int heads, Layout lay, int gh, int gw,
-                                                         int ah, int aw) {
+                                                         uint16_t* __restrict__ Alo, int N, int n, int d, int heads,
+                                                         Layout lay, int gh, int gw, int ah, int aw) {
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   const int cpr = d >> 3, u = blockIdx.y;
   const int item = blockIdx.x * 256 + threadIdx.x;
@@ -73,15 +77,22 @@ __global__ __launch_bounds__(256) void pool_chunk_kernel(const uint16_t* __restr
     for (; x < x1; ++x) add(*(const u32x4*)(row + (size_t)x * lay.sn));
   }
   const float inv = 1.0f / (float)((y1 - y0) * (x1 - x0));
-  u32x4 w;
+  u32x4 w, wlo;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
-    union { uint16_t h[2]; uint32_t w; } t;
-    *(typename E::T*)&t.h[0] = E::from_f32(acc[2 * k] * inv);
-    *(typename E::T*)&t.h[1] = E::from_f32(acc[2 * k + 1] * inv);
+    union { uint16_t h[2]; uint32_t w; } t, tl;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const float mean = acc[2 * k + j] * inv;
+      const typename E::T hi = E::from_f32(mean);
+      *(typename E::T*)&t.h[j] = hi;
+      *(typename E::T*)&tl.h[j] = E::from_f32(mean - E::to_f32(hi));      // what the rounding left over
+    }
     w[k] = t.w;
+    wlo[k] = tl.w;
   }
   *(u32x4*)(A + ((size_t)u * n + a) * d + 8 * chunk) = w;
+  if (Alo) *(u32x4*)(Alo + ((size_t)u * n + a) * d + 8 * chunk) = wlo;
 }
 
 // ---------------------------------------------------------------------------
@@ -92,7 +103,7 @@ __global__ __launch_bounds__(256) void pool_chunk_kernel(const uint16_t* __restr
 // ---------------------------------------------------------------------------
 template <class E>
 __global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
-    const typename E::T* __restrict__ A, const typename E::T* __restrict__ K,
+    const typename E::T* __restrict__ A, const typename E::T* __restrict__ Alo, const typename E::T* __restrict__ K,
     const typename E::T* __restrict__ V, BiasArgs b1, float scale, int N, int n, int d, int heads, Layout lay,
     int gh, int gw, int S, float* __restrict__ part_acc, float* __restrict__ part_m, float* __restrict__ part_l,
     float* __restrict__ VA_direct) {
@@ -118,7 +129,10 @@ __global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
   const bool has_bias = b.any();
 
   if (active)
-    for (int c = lane; c < d; c += 64) a_row[c] = E::to_f32(A[((size_t)u * n + a) * d + c]);
+    for (int c = lane; c < d; c += 64) {
+      const size_t i = ((size_t)u * n + a) * d + c;
+      a_row[c] = E::to_f32(A[i]) + (Alo ? E::to_f32(Alo[i]) : 0.0f);      // pooled agents come in two terms
+    }
   __syncthreads();
 
   float m = -INFINITY, l = 0.0f;
@@ -215,8 +229,8 @@ __global__ __launch_bounds__(64) void merge_generic_kernel(const float* __restri
 // ---------------------------------------------------------------------------
 template <class E>
 __global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
-    const typename E::T* __restrict__ Q, const typename E::T* __restrict__ A, const float* __restrict__ VA,
-    const typename E::T* __restrict__ V, BiasArgs b2, const float* __restrict__ dwc_w,
+    const typename E::T* __restrict__ Q, const typename E::T* __restrict__ A, const typename E::T* __restrict__ Alo,
+    const float* __restrict__ VA, const typename E::T* __restrict__ V, BiasArgs b2, const float* __restrict__ dwc_w,
     const float* __restrict__ dwc_b, float scale, float vk, int N, int n, int d, int heads, Layout lay, int gh,
     int gw, typename E::T* __restrict__ O) {
   extern __shared__ float smem[];
@@ -244,8 +258,14 @@ __global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
     for (int a = lane; a < n; a += 64) {
       const typename E::T* ar = A + ((size_t)u * n + a) * d;
       float dot = 0.0f;
+      if (Alo) {      // pooled agents come in two terms; block-uniform
+        const typename E::T* al = Alo + ((size_t)u * n + a) * d;
 #pragma unroll 8
-      for (int c = 0; c < d; ++c) dot += q_row[c] * E::to_f32(ar[c]);
+        for (int c = 0; c < d; ++c) dot += q_row[c] * (E::to_f32(ar[c]) + E::to_f32(al[c]));
+      } else {
+#pragma unroll 8
+        for (int c = 0; c < d; ++c) dot += q_row[c] * E::to_f32(ar[c]);
+      }
       float s = dot * scale;
       if (has_bias) s += bias2_at(b, a, y, x, gh, gw, n);
       sc[a] = s;
@@ -518,33 +538,35 @@ hipError_t launch_bias_dense(const Problem& p, float* out1, float* out2, hipStre
   return hipGetLastError();
 }
 
-hipError_t launch_pool_generic(const Problem& p, const void* Q, void* A, hipStream_t st) {
+hipError_t launch_pool_generic(const Problem& p, const void* Q, void* A, void* Alo, hipStream_t st) {
   dim3 grid(p.n, p.units);
+  if (p.dtype == 0) Alo = nullptr;      // fp32 agents carry no residual worth keeping
   AA_DISPATCH_DTYPE(p.dtype, pool_generic_kernel<E><<<grid, dim3(64), 0, st>>>(
-      (const typename E::T*)Q, (typename E::T*)A, p.N, p.n, p.d, p.heads, p.lay, p.gh, p.gw, p.ah, p.aw));
+      (const typename E::T*)Q, (typename E::T*)A, (typename E::T*)Alo, p.N, p.n, p.d, p.heads, p.lay, p.gh, p.gw, p.ah, p.aw));
   return hipGetLastError();
 }
 
-hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, hipStream_t st) {
+hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, void* Alo, hipStream_t st) {
   const dim3 grid((p.n * (p.d >> 3) + 255) / 256, p.units);
   if (p.dtype == 2)
-    pool_chunk_kernel<ElemBF16><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, p.N, p.n, p.d, p.heads,
-                                                            p.lay, p.gh, p.gw, p.ah, p.aw);
+    pool_chunk_kernel<ElemBF16><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, (uint16_t*)Alo, p.N, p.n, p.d,
+                                                            p.heads, p.lay, p.gh, p.gw, p.ah, p.aw);
   else if (p.dtype == 1)
-    pool_chunk_kernel<ElemF16><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, p.N, p.n, p.d, p.heads,
-                                                           p.lay, p.gh, p.gw, p.ah, p.aw);
+    pool_chunk_kernel<ElemF16><<<grid, dim3(256), 0, st>>>((const uint16_t*)Q, (uint16_t*)A, (uint16_t*)Alo, p.N, p.n, p.d,
+                                                           p.heads, p.lay, p.gh, p.gw, p.ah, p.aw);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
 // VA_direct: with one split (part.S == 1) the kernel may write the normalised V_A itself (no merge launch)
-hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* K, const void* V,
+hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* Alo, const void* K, const void* V,
                                     const Partials& part, float* VA_direct, hipStream_t st) {
   dim3 grid((p.n + kWaves - 1) / kWaves, part.S, p.units);
   const size_t lds = (size_t)kWaves * (p.d + 64) * sizeof(float);
   AA_DISPATCH_DTYPE(p.dtype, aggregate_generic_kernel<E><<<grid, dim3(64 * kWaves), lds, st>>>(
-      (const typename E::T*)A, (const typename E::T*)K, (const typename E::T*)V, p.b1, p.scale1, p.N, p.n, p.d,
+      (const typename E::T*)A, (const typename E::T*)Alo, (const typename E::T*)K, (const typename E::T*)V, p.b1,
+      p.scale1, p.N, p.n, p.d,
       p.heads, p.lay, p.gh, p.gw, part.S, part.acc, part.m, part.l, part.S == 1 ? VA_direct : nullptr));
   return hipGetLastError();
 }
@@ -557,12 +579,12 @@ hipError_t launch_merge_generic(const Problem& p, const Partials& part, float* V
 
 size_t broadcast_generic_lds_bytes(int n, int d) { return (size_t)kWaves * (n + d) * sizeof(float); }
 
-hipError_t launch_broadcast_generic(const Problem& p, const void* Q, const void* A, const float* VA,
+hipError_t launch_broadcast_generic(const Problem& p, const void* Q, const void* A, const void* Alo, const float* VA,
                                     const void* V, void* out, hipStream_t st) {
   dim3 grid((p.N + kWaves - 1) / kWaves, p.units);
   const size_t lds = broadcast_generic_lds_bytes(p.n, p.d);
   AA_DISPATCH_DTYPE(p.dtype, broadcast_generic_kernel<E><<<grid, dim3(64 * kWaves), lds, st>>>(
-      (const typename E::T*)Q, (const typename E::T*)A, VA, (const typename E::T*)V, p.b2, p.dwc_w, p.dwc_b,
+      (const typename E::T*)Q, (const typename E::T*)A, (const typename E::T*)Alo, VA, (const typename E::T*)V, p.b2, p.dwc_w, p.dwc_b,
       p.scale2, p.vk, p.N, p.n, p.d, p.heads, p.lay, p.gh, p.gw, (typename E::T*)out));
   return hipGetLastError();
 }

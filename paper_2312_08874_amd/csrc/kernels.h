@@ -31,9 +31,14 @@ struct Partials {
 };
 
 // --- reference-quality kernels: any shape (d <= 256), any dtype, VALU fp32 math ---
-hipError_t launch_pool_generic(const Problem& p, const void* Q, void* A, hipStream_t st);
+// Pooled agents are averages of element-type values: for fp16 / bf16 every pooling kernel can also write, next
+// to the agents rounded to the element type (A), what that rounding left over (Alo = rn(mean - A), same layout;
+// null = not wanted).  The attention kernels take the pair and add the residual's score product to the leading
+// one, so a forward pass that pools its own agents does not lose them to a 16-bit rounding.  Agents handed in by
+// the caller are exact in the element type: Alo is null for them.
+hipError_t launch_pool_generic(const Problem& p, const void* Q, void* A, void* Alo, hipStream_t st);
 // fp16 / bf16, d a multiple of 8, Q and A 16-byte aligned: 16-byte loads, thread per (agent, 8 channels)
-hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, hipStream_t st);
+hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, void* Alo, hipStream_t st);
 // agent bias of kind 1 (p.b1 -> out1) and / or 2 (p.b2 -> out2) evaluated for all pairs into the padded dense
 // layout of BiasArgs, in one launch; a null output skips that kind
 size_t bias_dense_floats(int kind, int heads, int n, int N);
@@ -45,10 +50,10 @@ hipError_t launch_restride(const Problem& p, bool to_dense, bool out_layout, con
 size_t bias_half_floats(int heads, int n, int gw, int he);
 size_t bias_rows_floats(int heads, int n, int gh);
 hipError_t launch_bias_half(const Problem& p, float* half1, float* rows1, float* half2, float* rows2, hipStream_t st);
-hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* K, const void* V,
+hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* Alo, const void* K, const void* V,
                                     const Partials& part, float* VA_direct, hipStream_t st);
 hipError_t launch_merge_generic(const Problem& p, const Partials& part, float* VA, hipStream_t st);
-hipError_t launch_broadcast_generic(const Problem& p, const void* Q, const void* A, const float* VA,
+hipError_t launch_broadcast_generic(const Problem& p, const void* Q, const void* A, const void* Alo, const float* VA,
                                     const void* V, void* out, hipStream_t st);
 // dynamic LDS the generic broadcast needs for this problem (bytes)
 size_t broadcast_generic_lds_bytes(int n, int d);
@@ -76,28 +81,28 @@ bool small_fused_supported(const Problem& p);
 // whole forward pass, one block per (batch, head) unit; A == nullptr pools Q
 hipError_t launch_small_fused(const Problem& p, const void* Q, const void* K, const void* V, const void* A,
                               void* out, hipStream_t st);
-hipError_t launch_small_pool(const Problem& p, const void* Q, void* A, hipStream_t st);
+hipError_t launch_small_pool(const Problem& p, const void* Q, void* A, void* Alo, hipStream_t st);
 // tokens per split (multiple of 32) the split-N aggregation uses for S requested splits
 int small_split_chunk(int N, int S);
 // part.S must equal ceil(N / small_split_chunk(N, S_requested)); m is stored in the log2 domain
-hipError_t launch_small_aggregate(const Problem& p, const void* A, const void* K, const void* V,
+hipError_t launch_small_aggregate(const Problem& p, const void* A, const void* Alo, const void* K, const void* V,
                                   const Partials& part, hipStream_t st);
 hipError_t launch_small_merge(const Problem& p, const Partials& part, float* VA, hipStream_t st);
 // V_A either merged (VA, part == nullptr) or as the aggregation's split partials (part, VA unused): the
 // broadcast blocks then do the merge themselves while staging V_A
-hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A, const float* VA,
+hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A, const void* Alo, const float* VA,
                                   const Partials* part, const void* V, void* out, int chunks, hipStream_t st);
 
 // per (element type, head width) units behind the launchers above
 #define AA_DECLARE_SMALL(TAG)                                                                                       \
   hipError_t launch_small_fused_##TAG(const Problem& p, const void* Q, const void* K, const void* V, const void* A, \
                                       void* out, hipStream_t st);                                                   \
-  hipError_t launch_small_pool_##TAG(const Problem& p, const void* Q, void* A, hipStream_t st);                     \
-  hipError_t launch_small_aggregate_##TAG(const Problem& p, const void* A, const void* K, const void* V,            \
-                                          const Partials& part, hipStream_t st);                                    \
-  hipError_t launch_small_broadcast_##TAG(const Problem& p, const void* Q, const void* A, const float* VA,          \
-                                          const Partials* part, const void* V, void* out, int chunks,               \
-                                          hipStream_t st);
+  hipError_t launch_small_pool_##TAG(const Problem& p, const void* Q, void* A, void* Alo, hipStream_t st);          \
+  hipError_t launch_small_aggregate_##TAG(const Problem& p, const void* A, const void* Alo, const void* K,          \
+                                          const void* V, const Partials& part, hipStream_t st);                     \
+  hipError_t launch_small_broadcast_##TAG(const Problem& p, const void* Q, const void* A, const void* Alo,          \
+                                          const float* VA, const Partials* part, const void* V, void* out,          \
+                                          int chunks, hipStream_t st);
 AA_DECLARE_SMALL(bf16_d32)
 AA_DECLARE_SMALL(bf16_d64)
 AA_DECLARE_SMALL(f16_d32)
@@ -106,11 +111,12 @@ AA_DECLARE_SMALL(f16_d64)
 // --- large-agent regime (any n; fp16 / bf16; d a multiple of 8, d <= 128): flash-style MFMA kernels that
 //     stage the streamed operand in LDS; one set per padded head width DP in {32, 64, 128} ---
 #define AA_DECLARE_LARGE(DP)                                                                                        \
-  hipError_t launch_large_aggregate_dp##DP(const Problem& p, const void* A, const void* K, const void* V,           \
-                                           const Partials& part, int chunk, int waves, int nw, hipStream_t st);     \
+  hipError_t launch_large_aggregate_dp##DP(const Problem& p, const void* A, const void* Alo, const void* K,         \
+                                           const void* V, const Partials& part, int chunk, int waves, int nw,       \
+                                           hipStream_t st);                                                         \
   hipError_t launch_large_merge_dp##DP(const Problem& p, const Partials& part, float* VA, hipStream_t st);          \
-  hipError_t launch_large_broadcast_dp##DP(const Problem& p, const void* Q, const void* A, const float* VA,         \
-                                           const void* V, void* out, int waves, hipStream_t st);
+  hipError_t launch_large_broadcast_dp##DP(const Problem& p, const void* Q, const void* A, const void* Alo,         \
+                                           const float* VA, const void* V, void* out, int waves, hipStream_t st);
 AA_DECLARE_LARGE(32)
 AA_DECLARE_LARGE(64)
 AA_DECLARE_LARGE(128)

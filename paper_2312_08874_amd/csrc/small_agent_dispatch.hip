@@ -60,20 +60,20 @@ hipError_t launch_small_fused(const Problem& p, const void* Q, const void* K, co
                               void* out, hipStream_t st) {
   return AA_SMALL_ROUTE(p, launch_small_fused, p, Q, K, V, A, out, st);
 }
-hipError_t launch_small_pool(const Problem& p, const void* Q, void* A, hipStream_t st) {
-  return AA_SMALL_ROUTE(p, launch_small_pool, p, Q, A, st);
+hipError_t launch_small_pool(const Problem& p, const void* Q, void* A, void* Alo, hipStream_t st) {
+  return AA_SMALL_ROUTE(p, launch_small_pool, p, Q, A, Alo, st);
 }
-hipError_t launch_small_aggregate(const Problem& p, const void* A, const void* K, const void* V,
+hipError_t launch_small_aggregate(const Problem& p, const void* A, const void* Alo, const void* K, const void* V,
                                   const Partials& part, hipStream_t st) {
-  return AA_SMALL_ROUTE(p, launch_small_aggregate, p, A, K, V, part, st);
+  return AA_SMALL_ROUTE(p, launch_small_aggregate, p, A, Alo, K, V, part, st);
 }
 hipError_t launch_small_merge(const Problem& p, const Partials& part, float* VA, hipStream_t st) {
   small_merge_kernel<<<dim3(p.n, p.units), dim3(64), 0, st>>>(part.acc, part.m, part.l, part.S, p.n, p.d, VA);
   return hipGetLastError();
 }
-hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A, const float* VA,
+hipError_t launch_small_broadcast(const Problem& p, const void* Q, const void* A, const void* Alo, const float* VA,
                                   const Partials* part, const void* V, void* out, int chunks, hipStream_t st) {
-  return AA_SMALL_ROUTE(p, launch_small_broadcast, p, Q, A, VA, part, V, out, chunks, st);
+  return AA_SMALL_ROUTE(p, launch_small_broadcast, p, Q, A, Alo, VA, part, V, out, chunks, st);
 }
 
 }  // namespace aa
