@@ -11,10 +11,11 @@
  *   O  += DWC(V)                                       Sec. 4.2 Eq. (6), 3x3 depthwise convolution (k = 3, Eq. (7))
  *   O  += v_residual_k * V                             Appendix C.1 (Stable-Diffusion variant)
  *
- * scale defaults to d^-1/2 (Sec. 3.2).  B1 [n,N] and B2 [N,n] are never passed
- * dense: they are evaluated inside the kernels from the three components of
- * Appendix B (column, row and block bias; the block bias is resized bilinearly
- * with half-pixel centres from blk_h0 x blk_w0 to the token grid).
+ * scale defaults to d^-1/2 (Sec. 3.2).  The caller passes B1 [n,N] and B2 [N,n] as the three
+ * components of Appendix B (column, row and block bias; the block bias is resized bilinearly
+ * with half-pixel centres from blk_h0 x blk_w0 to the token grid), never as dense matrices; the
+ * library evaluates them per score or, for fp16 / bf16, once per call into tables of its own
+ * (agent_attn_bias_tables() exposes that step for parameters that stay fixed).
  *
  * General conventions
  *  - Every tensor pointer is a DEVICE pointer owned by the caller; the library
@@ -31,7 +32,10 @@
  *  - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
  *    the null stream) and return without synchronising.  Work of one call is
  *    ordered after earlier work on that stream.
- *  - Errors are return codes.  On any error nothing has been launched.
+ *  - Errors are return codes.  Every error except AA_ERR_HIP comes from host-side validation and
+ *    means that nothing has been launched.  AA_ERR_HIP reports a failing HIP runtime call; kernels
+ *    of the same call enqueued before it may still run, and `out` and the workspace are then
+ *    unspecified.
  *  - Two calls may run concurrently only with distinct workspaces and outputs.
  *  - Results are deterministic: same inputs, same bits.
  */

@@ -201,14 +201,24 @@ BiasPlan plan_bias(const aa_desc* d, const aa_params* params) {
   return bp;
 }
 
+Problem make_problem(const aa_desc* d, const aa_params* p);
+bool large_supported(const Problem& pr);
+
 Plan make_plan(const aa_desc* d, const aa_params* params = nullptr) {
   Plan pl{};
   const size_t units = (size_t)d->batch * d->heads;
   pl.S = choose_splits(d);
   plan_small(d, pl);
   plan_large(d, pl);
-  int Smax = pl.S > pl.S_small ? pl.S : pl.S_small;
-  if (pl.S_large > Smax) Smax = pl.S_large;
+  // room for the partials of the kernel family this shape runs on, and of the reference kernels it falls back
+  // to when a pointer turns out to be unaligned
+  const Problem shape = make_problem(d, nullptr);
+  int Smax = pl.S;
+  if (aa::small_supported(shape)) {
+    if (pl.S_small > Smax) Smax = pl.S_small;
+  } else if (large_supported(shape)) {
+    if (pl.S_large > Smax) Smax = pl.S_large;
+  }
   size_t off = 0;
   pl.off_A = off;
   off += align_up(units * d->n * d->d * elem_size(d->dtype));
