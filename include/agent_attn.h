@@ -114,6 +114,21 @@ aa_status agent_attn_fwd(const aa_desc *desc, const void *Q, const void *K, cons
                          const void *A, const aa_params *params, void *workspace,
                          size_t workspace_bytes, void *out, void *hip_stream);
 
+/* The same forward pass for callers that cannot allocate device memory and have no workspace to hand
+ * over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * workspace is an array of agent_attn_static_scratch_bytes() bytes (64 MiB) that the library holds in
+ * every GPU's memory from the moment it is loaded there until the process ends; the call allocates and
+ * frees nothing (no hipMalloc, no hipFree, no allocating library routine).  Problems whose
+ * agent_attn_workspace_bytes() exceeds that size are rejected with AA_ERR_WORKSPACE before anything is
+ * launched (module mode with many agents fits when params->bias_tables brings prepared tables).
+ * Everything else -- arguments, validation, kernels, results bit for bit -- is agent_attn_fwd's.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams
+ * or threads) race and give unspecified results; calls on one stream are ordered and safe.  The array
+ * keeps the last call's contents; nothing in it has to be cleared between calls. */
+size_t agent_attn_static_scratch_bytes(void);
+aa_status agent_attn_fwd_static(const aa_desc *desc, const void *Q, const void *K, const void *V,
+                                const void *A, const aa_params *params, void *out, void *hip_stream);
+
 /* Agent bias prepared ahead of the forward calls (Eq. (5), Appendix B).  The bias does not depend
  * on the batch or on Q, K, V, so the fp16 / bf16 kernels read it from tables (the bias per head, or
  * its column and block components interpolated along x when n is large) that the forward entry

@@ -48,7 +48,7 @@ class aa_param_grads(ctypes.Structure):
 EXPORTS = ("agent_attn_workspace_bytes", "agent_attn_fwd", "agent_pool_fwd", "agent_aggregate_fwd",
            "agent_broadcast_fwd", "agent_attn_flops", "agent_attn_status_str", "agent_attn_plan_str",
            "agent_attn_bwd_workspace_bytes", "agent_attn_bwd", "agent_attn_bias_tables_bytes",
-           "agent_attn_bias_tables")
+           "agent_attn_bias_tables", "agent_attn_fwd_static", "agent_attn_static_scratch_bytes")
 
 _lib = None
 
@@ -74,6 +74,10 @@ def lib():
         L.agent_attn_flops.argtypes = [dp]
         L.agent_attn_fwd.restype = ctypes.c_int
         L.agent_attn_fwd.argtypes = [dp, vp, vp, vp, vp, pp, vp, ctypes.c_size_t, vp, vp]
+        L.agent_attn_fwd_static.restype = ctypes.c_int
+        L.agent_attn_fwd_static.argtypes = [dp, vp, vp, vp, vp, pp, vp, vp]
+        L.agent_attn_static_scratch_bytes.restype = ctypes.c_size_t
+        L.agent_attn_static_scratch_bytes.argtypes = []
         L.agent_pool_fwd.restype = ctypes.c_int
         L.agent_pool_fwd.argtypes = [dp, vp, vp, vp]
         L.agent_aggregate_fwd.restype = ctypes.c_int
@@ -233,6 +237,23 @@ def agent_attn_fwd(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict 
                               _stream(stream))
     _check(st, "agent_attn_fwd")
     return out
+
+
+def agent_attn_fwd_static(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict | None = None, scale1=0.0,
+                          scale2=0.0, v_residual_k=0.0, n_splits=0, out, stream=None):
+    """agent_attn_fwd on the library's own static workspace: allocates nothing (`out` is the caller's)."""
+    n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
+    desc = _desc_from(Q, n, grid, agent_grid, same=(K, V), out=out, scale1=scale1, scale2=scale2,
+                      v_residual_k=v_residual_k, n_splits=n_splits)
+    p = make_params(params)
+    st = lib().agent_attn_fwd_static(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(A), _pp(p),
+                                     out.data_ptr(), _stream(stream))
+    _check(st, "agent_attn_fwd_static")
+    return out
+
+
+def static_scratch_bytes() -> int:
+    return int(lib().agent_attn_static_scratch_bytes())
 
 
 def agent_attn_bwd(Q, K, V, dO, A=None, *, grid=None, agent_grid=None, params: dict | None = None, scale1=0.0,

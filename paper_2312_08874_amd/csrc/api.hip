@@ -7,8 +7,15 @@
 #include <stdio.h>
 
 #include <initializer_list>
+#include <mutex>
 
 #include "kernels.h"
+
+// Workspace of agent_attn_fwd_static(): one array per GPU, reserved when the library's code object is loaded
+// on that GPU and held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress(); the device address it yields is what kernels and copies are given.
+#define AA_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+static __device__ __align__(256) unsigned char scratch[AA_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -712,6 +719,41 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
     AA_HIP(aa::launch_restride(strided_pr, false, false, sdV, udV, stream));
   }
   return AA_OK;
+}
+
+size_t agent_attn_static_scratch_bytes(void) { return AA_STATIC_SCRATCH_BYTES; }
+
+aa_status agent_attn_fwd_static(const aa_desc* desc, const void* Q, const void* K, const void* V, const void* A,
+                                const aa_params* params, void* out, void* hip_stream) {
+  // host-only validation first (same order as agent_attn_fwd), so that every error but AA_ERR_HIP is decided
+  // before the GPU is touched
+  const bool pooling = (A == nullptr);
+  aa_status st = check_desc(desc, pooling || params_use_grid(params), pooling);
+  if (st == AA_ERR_SHAPE && pooling && desc && desc->grid_h == 0 && desc->grid_w == 0) st = AA_ERR_POOL;
+  if (st != AA_OK) return st;
+  st = check_params(params);
+  if (st != AA_OK) return st;
+  if (!Q || !K || !V || !out) return AA_ERR_NULL;
+  if (make_plan(desc, params).total > AA_STATIC_SCRATCH_BYTES) return AA_ERR_WORKSPACE;
+  // device address of this GPU's copy of the array, looked up once per device
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* base[kMaxDevices] = {};
+  int dev = 0;
+  AA_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return AA_ERR_UNSUPPORTED;
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!base[dev]) {
+      void* p = nullptr;
+      AA_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+      if (!p) return AA_ERR_HIP;
+      base[dev] = p;
+    }
+    ptr = base[dev];
+  }
+  return agent_attn_fwd(desc, Q, K, V, A, params, ptr, AA_STATIC_SCRATCH_BYTES, out, hip_stream);
 }
 
 size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, size_t buf_len) {
