@@ -43,8 +43,11 @@ struct BiasPlan {
 struct Plan {
   int S;               // N-splits of the generic aggregation
   int bcast_waves_large;                              // waves (32 tokens each) per block of the large broadcast
-  int S_large, chunk_large, waves_large, nw_large;   // large-agent MFMA aggregation: splits, tokens per split,
-                                                      // waves per block, 16-agent tiles per wave
+  int S_large, chunk_large, waves_large;   // large-agent MFMA aggregation: splits, tokens per split, waves per block
+                                           // (one tile of 16 agents each)
+  int n_pad, agent_blocks;                 // agents rounded up to whole chunks of 64; blocks of 16 * waves agents
+  // buffers of the large-agent forward (see aa::LargeFwdBuffers)
+  size_t off_A1hi, off_A1lo, off_A2hi, off_A2lo, off_VAop, off_pacc, off_pm, off_pl, off_tickets;
   int S_small;         // N-splits of the small-agent MFMA aggregation
   int bcast_chunks;    // token chunks per unit of the small-agent broadcast
   bool prefer_fused;   // small-agent regime: one block per unit does the whole pass
@@ -144,21 +147,21 @@ void plan_small(const aa_desc* d, Plan& pl) {
   pl.bcast_chunks = (d->N + btok - 1) / btok;
 }
 
-// Large-agent path: agents per block = waves * nw * 16; splits chosen for about 512 blocks, at least
-// 128 tokens per split, split length a multiple of the 64-token K/V tile.
+// Large-agent path: 64 or 128 agents per block (4 or 8 waves of one 16-agent tile; whole chunks of 64 agents,
+// which is the unit the broadcast stages); splits chosen for about 512 blocks, at least 512 tokens per split
+// (the split partials stay small beside K and V), split length a multiple of the 64-token K/V tile.
 void plan_large(const aa_desc* d, Plan& pl) {
   const int64_t units = (int64_t)d->batch * d->heads;
-  pl.nw_large = 1;     // one 16-agent tile per wave: 117 VGPRs, two blocks of 8 waves per CU (measured best)
-  int waves = (d->n + 16 * pl.nw_large - 1) / (16 * pl.nw_large);
-  if (waves > 8) waves = 8;
-  if (waves < 4) waves = 4;          // the staging copies want at least 256 threads
+  const int waves = d->n <= 64 ? 4 : 8;          // the staging copies want at least 256 threads
   pl.waves_large = waves;
-  const int apb = waves * pl.nw_large * 16;
+  const int apb = waves * 16;
   const int64_t nblocks = (d->n + apb - 1) / apb;
+  pl.agent_blocks = (int)nblocks;
+  pl.n_pad = aa::round_up64(d->n);
   int S = d->n_splits;
   if (S <= 0) {
     S = (int)((512 + units * nblocks - 1) / (units * nblocks));
-    const int max_by_len = (d->N + 127) / 128;
+    const int max_by_len = (d->N + 511) / 512;
     if (S > max_by_len) S = max_by_len;
   }
   if (S > d->N) S = d->N;
@@ -210,6 +213,7 @@ BiasPlan plan_bias(const aa_desc* d, const aa_params* params) {
 
 Problem make_problem(const aa_desc* d, const aa_params* p);
 bool large_supported(const Problem& pr);
+int padded_width(int d);
 
 Plan make_plan(const aa_desc* d, const aa_params* params = nullptr) {
   Plan pl{};
@@ -221,11 +225,8 @@ Plan make_plan(const aa_desc* d, const aa_params* params = nullptr) {
   // to when a pointer turns out to be unaligned
   const Problem shape = make_problem(d, nullptr);
   int Smax = pl.S;
-  if (aa::small_supported(shape)) {
-    if (pl.S_small > Smax) Smax = pl.S_small;
-  } else if (large_supported(shape)) {
-    if (pl.S_large > Smax) Smax = pl.S_large;
-  }
+  const bool large = !aa::small_supported(shape) && large_supported(shape);
+  if (aa::small_supported(shape) && pl.S_small > Smax) Smax = pl.S_small;
   size_t off = 0;
   pl.off_A = off;
   off += align_up(units * d->n * d->d * elem_size(d->dtype));
@@ -239,6 +240,19 @@ Plan make_plan(const aa_desc* d, const aa_params* params = nullptr) {
   off += align_up(units * Smax * d->n * sizeof(float));
   pl.off_VA = off;
   off += align_up(units * d->n * d->d * sizeof(float));
+  if (large) {
+    const int dp = padded_width(d->d);
+    const size_t ops = align_up(units * pl.n_pad * dp * 2);
+    pl.off_A1hi = off, off += ops;
+    pl.off_A1lo = off, off += ops;
+    pl.off_A2hi = off, off += ops;
+    pl.off_A2lo = off, off += ops;
+    pl.off_VAop = off, off += ops;
+    pl.off_pacc = off, off += align_up(units * pl.agent_blocks * pl.S_large * pl.waves_large * (dp / 16) * 256 * sizeof(float));
+    pl.off_pm = off, off += align_up(units * pl.agent_blocks * pl.S_large * pl.waves_large * 16 * sizeof(float));
+    pl.off_pl = off, off += align_up(units * pl.agent_blocks * pl.S_large * pl.waves_large * 16 * sizeof(float));
+    pl.off_tickets = off, off += align_up(units * pl.agent_blocks * sizeof(unsigned));
+  }
   pl.bias = plan_bias(d, params);
   pl.off_bias = off;
   if (!(params && params->bias_tables)) off += pl.bias.total;      // prepared tables need no room here
@@ -343,6 +357,51 @@ aa_status check_workspace(const void* ws, size_t bytes, const Plan& pl) {
     if ((call) != hipSuccess) return AA_ERR_HIP; \
   } while (0)
 
+aa::LargeFwdBuffers large_buffers(void* ws, const Plan& pl, const Problem& pr) {
+  char* base = (char*)ws;
+  aa::LargeFwdBuffers b{};
+  b.A1hi = (uint16_t*)(base + pl.off_A1hi);
+  b.A1lo = (uint16_t*)(base + pl.off_A1lo);
+  b.A2hi = (uint16_t*)(base + pl.off_A2hi);
+  b.A2lo = (uint16_t*)(base + pl.off_A2lo);
+  b.VAop = (uint16_t*)(base + pl.off_VAop);
+  b.part_acc = (float*)(base + pl.off_pacc);
+  b.part_m = (float*)(base + pl.off_pm);
+  b.part_l = (float*)(base + pl.off_pl);
+  b.tickets = (unsigned*)(base + pl.off_tickets);
+  b.n_tickets = pr.units * pl.agent_blocks;
+  b.n_pad = pl.n_pad;
+  b.S = pl.S_large;
+  b.chunk = pl.chunk_large;
+  b.W = pl.waves_large;
+  b.agent_blocks = pl.agent_blocks;
+  return b;
+}
+
+// The three launches of the large-agent forward pass.  A == nullptr: agents pooled from Q.
+aa_status run_large_forward(const Problem& pr, const void* Q, const void* K, const void* V, const void* A, void* ws,
+                            const Plan& pl, void* out, hipStream_t st) {
+  const aa::LargeFwdBuffers b = large_buffers(ws, pl, pr);
+  switch (padded_width(pr.d)) {
+    case 32:
+      AA_HIP(aa::launch_large_agents_dp32(pr, Q, A, b, st));
+      AA_HIP(aa::launch_large_aggregate2_dp32(pr, K, V, b, nullptr, st));
+      AA_HIP(aa::launch_large_broadcast2_dp32(pr, Q, V, out, b, pl.bcast_waves_large, st));
+      break;
+    case 64:
+      AA_HIP(aa::launch_large_agents_dp64(pr, Q, A, b, st));
+      AA_HIP(aa::launch_large_aggregate2_dp64(pr, K, V, b, nullptr, st));
+      AA_HIP(aa::launch_large_broadcast2_dp64(pr, Q, V, out, b, pl.bcast_waves_large, st));
+      break;
+    default:
+      AA_HIP(aa::launch_large_agents_dp128(pr, Q, A, b, st));
+      AA_HIP(aa::launch_large_aggregate2_dp128(pr, K, V, b, nullptr, st));
+      AA_HIP(aa::launch_large_broadcast2_dp128(pr, Q, V, out, b, pl.bcast_waves_large, st));
+      break;
+  }
+  return AA_OK;
+}
+
 // Alo: residual of pooled agents (see kernels.h), null for agents that were handed in
 aa_status run_aggregate(const Problem& pr, const void* A, const void* Alo, const void* K, const void* V, void* ws,
                         const Plan& pl, float* VA, hipStream_t st) {
@@ -353,19 +412,21 @@ aa_status run_aggregate(const Problem& pr, const void* A, const void* Alo, const
     return AA_OK;
   }
   if (use_large(pr, {A, K, V})) {
-    const Partials part = partials_in(ws, pl, pl.S_large);
+    // agents handed in: written as scaled two-term operands first, then the split aggregation whose last block
+    // merges, here into fp32 rows
+    const aa::LargeFwdBuffers b = large_buffers(ws, pl, pr);
     switch (padded_width(pr.d)) {
       case 32:
-        AA_HIP(aa::launch_large_aggregate_dp32(pr, A, Alo, K, V, part, pl.chunk_large, pl.waves_large, pl.nw_large, st));
-        AA_HIP(aa::launch_large_merge_dp32(pr, part, VA, st));
+        AA_HIP(aa::launch_large_agents_dp32(pr, nullptr, A, b, st));
+        AA_HIP(aa::launch_large_aggregate2_dp32(pr, K, V, b, VA, st));
         break;
       case 64:
-        AA_HIP(aa::launch_large_aggregate_dp64(pr, A, Alo, K, V, part, pl.chunk_large, pl.waves_large, pl.nw_large, st));
-        AA_HIP(aa::launch_large_merge_dp64(pr, part, VA, st));
+        AA_HIP(aa::launch_large_agents_dp64(pr, nullptr, A, b, st));
+        AA_HIP(aa::launch_large_aggregate2_dp64(pr, K, V, b, VA, st));
         break;
       default:
-        AA_HIP(aa::launch_large_aggregate_dp128(pr, A, Alo, K, V, part, pl.chunk_large, pl.waves_large, pl.nw_large, st));
-        AA_HIP(aa::launch_large_merge_dp128(pr, part, VA, st));
+        AA_HIP(aa::launch_large_agents_dp128(pr, nullptr, A, b, st));
+        AA_HIP(aa::launch_large_aggregate2_dp128(pr, K, V, b, VA, st));
         break;
     }
     return AA_OK;
@@ -588,6 +649,8 @@ aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, cons
     AA_HIP(aa::launch_small_fused(pr, Q, K, V, A, out, stream));
     return AA_OK;
   }
+  if (!aa::small_supported(pr) && use_large(pr, {Q, K, V, A, out}))
+    return run_large_forward(pr, Q, K, V, A, workspace, pl, out, stream);
   // Pooled agents are kept in two element-type terms (rounded value + residual) so that the 16-bit rounding of
   // an average does not enter the scores; agents handed in are exact in the element type.
   const void* agents = A;
@@ -771,9 +834,9 @@ size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, siz
                      agents_given ? "" : "small_pool + ", pl.S_small, pl.bcast_chunks);
   } else if (large_supported(pr)) {
     len = snprintf(buf, buf_len,
-                   "%slarge_aggregate(S=%d, %d agents/block) + large_merge + large_broadcast(%d tokens/block)",
-                   agents_given ? "" : "pool_chunk + ", pl.S_large, pl.waves_large * pl.nw_large * 16,
-                   32 * pl.bcast_waves_large);
+                   "large_agents(%s) + large_aggregate2(S=%d, %d agents/block, last block merges) + "
+                   "large_broadcast2(%d tokens/block)",
+                   agents_given ? "given" : "pooled", pl.S_large, pl.waves_large * 16, 32 * pl.bcast_waves_large);
   } else {
     len = snprintf(buf, buf_len, "%saggregate_generic(S=%d) + %sbroadcast_generic", agents_given ? "" : "pool_generic + ",
                    pl.S, pl.S > 1 ? "merge_generic + " : "");

@@ -2,3 +2,4 @@
 #define AA_DP 64
 #define AA_NS large_dp64
 #include "large_agent_kernels.inc"
+#include "large_fwd_kernels.inc"
