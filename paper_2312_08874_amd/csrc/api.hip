@@ -337,7 +337,9 @@ bool use_small(const Problem& pr, std::initializer_list<const void*> ptrs) {
 
 // Large-agent MFMA kernels: fp16 / bf16, d a multiple of 8 (16-byte chunks) up to 128.
 bool large_supported(const Problem& pr) {
-  return (pr.dtype == AA_F16 || pr.dtype == AA_BF16) && pr.d % 8 == 0 && pr.d <= 128;
+  // a unit's rows are addressed with 32-bit byte offsets (buffer loads): its extent stays below 2 GiB
+  return (pr.dtype == AA_F16 || pr.dtype == AA_BF16) && pr.d % 8 == 0 && pr.d <= 128 &&
+         ((long long)pr.N + 64) * pr.lay.sn * 2 < (1ll << 31);
 }
 bool use_large(const Problem& pr, std::initializer_list<const void*> ptrs) {
   if (!large_supported(pr) || !layout_vectorizable(pr.lay)) return false;
