@@ -47,7 +47,7 @@ struct Plan {
                                            // (one tile of 16 agents each)
   int n_pad, agent_blocks;                 // agents rounded up to whole chunks of 64; blocks of 16 * waves agents
   // buffers of the large-agent forward (see aa::LargeFwdBuffers)
-  size_t off_A1hi, off_A1lo, off_A2hi, off_A2lo, off_VAop, off_pacc, off_pm, off_pl, off_tickets;
+  size_t off_A1hi, off_A1lo, off_A2hi, off_A2lo, off_VAop, off_pacc, off_pm, off_pl;
   int S_small;         // N-splits of the small-agent MFMA aggregation
   int bcast_chunks;    // token chunks per unit of the small-agent broadcast
   bool prefer_fused;   // small-agent regime: one block per unit does the whole pass
@@ -251,7 +251,6 @@ Plan make_plan(const aa_desc* d, const aa_params* params = nullptr) {
     pl.off_pacc = off, off += align_up(units * pl.agent_blocks * pl.S_large * pl.waves_large * (dp / 16) * 256 * sizeof(float));
     pl.off_pm = off, off += align_up(units * pl.agent_blocks * pl.S_large * pl.waves_large * 16 * sizeof(float));
     pl.off_pl = off, off += align_up(units * pl.agent_blocks * pl.S_large * pl.waves_large * 16 * sizeof(float));
-    pl.off_tickets = off, off += align_up(units * pl.agent_blocks * sizeof(unsigned));
   }
   pl.bias = plan_bias(d, params);
   pl.off_bias = off;
@@ -370,8 +369,6 @@ aa::LargeFwdBuffers large_buffers(void* ws, const Plan& pl, const Problem& pr) {
   b.part_acc = (float*)(base + pl.off_pacc);
   b.part_m = (float*)(base + pl.off_pm);
   b.part_l = (float*)(base + pl.off_pl);
-  b.tickets = (unsigned*)(base + pl.off_tickets);
-  b.n_tickets = pr.units * pl.agent_blocks;
   b.n_pad = pl.n_pad;
   b.S = pl.S_large;
   b.chunk = pl.chunk_large;
@@ -836,9 +833,9 @@ size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, siz
                      agents_given ? "" : "small_pool + ", pl.S_small, pl.bcast_chunks);
   } else if (large_supported(pr)) {
     len = snprintf(buf, buf_len,
-                   "large_agents(%s) + large_aggregate2(S=%d, %d agents/block, last block merges) + "
-                   "large_broadcast2(%d tokens/block)",
-                   agents_given ? "given" : "pooled", pl.S_large, pl.waves_large * 16, 32 * pl.bcast_waves_large);
+                   "large_agents(%s) + large_aggregate(S=%d, %d agents/block)%s + large_broadcast(%d tokens/block)",
+                   agents_given ? "given" : "pooled", pl.S_large, pl.waves_large * 16,
+                   pl.S_large > 1 ? " + large_merge" : "", 32 * pl.bcast_waves_large);
   } else {
     len = snprintf(buf, buf_len, "%saggregate_generic(S=%d) + %sbroadcast_generic", agents_given ? "" : "pool_generic + ",
                    pl.S, pl.S > 1 ? "merge_generic + " : "");

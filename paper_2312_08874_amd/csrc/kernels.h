@@ -112,13 +112,12 @@ AA_DECLARE_SMALL(f16_d64)
 //     stage the streamed operand in LDS; one set per padded head width DP in {32, 64, 128} ---
 // Buffers of the large-agent forward pass (all in the caller's workspace): the agents as MFMA operands
 // (scale1 * log2e * A and scale2 * log2e * A, two element-type terms each, [units][n_pad][DP]), V_A in the
-// broadcast's operand order ([units][n_pad / 64][64 * DP] elements), the split partials and merge tickets of
+// broadcast's operand order ([units][n_pad / 64][64 * DP] elements), the split partials of
 // the aggregation, and its launch shape (W waves of 16 agents per block, S splits of `chunk` tokens).
 struct LargeFwdBuffers {
   uint16_t *A1hi, *A1lo, *A2hi, *A2lo, *VAop;
   float *part_acc, *part_m, *part_l;
-  unsigned* tickets;
-  int n_tickets, n_pad, S, chunk, W, agent_blocks;
+  int n_pad, S, chunk, W, agent_blocks;
 };
 
 #define AA_DECLARE_LARGE(DP)                                                                                        \
@@ -128,8 +127,8 @@ AA_DECLARE_LARGE(32)
 AA_DECLARE_LARGE(64)
 AA_DECLARE_LARGE(128)
 #undef AA_DECLARE_LARGE
-// whole-forward kernels of the large-agent regime: agents as operands (pooled from Q, or Agiven) and cleared
-// merge tickets -> split aggregation whose last block merges (V_A in operand order, or fp32 rows for the stage
+// whole-forward kernels of the large-agent regime: agents as operands (pooled from Q, or Agiven) -> split
+// aggregation (+ merge launch when there are several splits; V_A in operand order, or fp32 rows for the stage
 // entry point) -> broadcast
 #define AA_DECLARE_LARGE_FWD(DP)                                                                                    \
   size_t large_fwd_part_floats_dp##DP(int units, int agent_blocks, int S, int W);                                   \
