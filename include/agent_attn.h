@@ -205,6 +205,21 @@ aa_status agent_attn_bwd(const aa_desc *desc, const void *Q, const void *K, cons
  * Returns 0 when the descriptor is invalid. */
 uint64_t agent_attn_flops(const aa_desc *desc);
 
+/* Measurement aid: agent_attn_fwd with every kernel launch of the pass timed.  A HIP event is recorded on
+ * `hip_stream` before the first launch and after each one; the call then waits for the last event (unlike
+ * agent_attn_fwd it blocks) and returns, in launch order, the name of each launcher and the time between its
+ * two events in milliseconds (kernel duration plus launch gap).  At most `max_times` entries are written;
+ * *n_times receives their number.  Creates and destroys its events on every call: not for hot loops.
+ * Other arguments, validation and results as for agent_attn_fwd. */
+typedef struct {
+  char name[48];
+  float ms;
+} aa_kernel_time;
+aa_status agent_attn_fwd_timed(const aa_desc *desc, const void *Q, const void *K, const void *V,
+                               const void *A, const aa_params *params, void *workspace,
+                               size_t workspace_bytes, void *out, void *hip_stream,
+                               aa_kernel_time *times, int max_times, int *n_times);
+
 /* Writes a short, human-readable name of the kernel sequence agent_attn_fwd would run for this
  * problem (pooling when agents_given == 0), e.g. "small_fused" or
  * "small_pool + small_aggregate(S=7) + small_merge + small_broadcast", assuming 16-byte aligned

@@ -39,6 +39,10 @@ class aa_params(ctypes.Structure):
                 ("dwc_w", ctypes.c_void_p), ("dwc_b", ctypes.c_void_p), ("bias_tables", ctypes.c_void_p)]
 
 
+class aa_kernel_time(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 48), ("ms", ctypes.c_float)]
+
+
 class aa_param_grads(ctypes.Structure):
     _fields_ = [("db1_col", ctypes.c_void_p), ("db1_row", ctypes.c_void_p), ("db1_blk", ctypes.c_void_p),
                 ("db2_col", ctypes.c_void_p), ("db2_row", ctypes.c_void_p), ("db2_blk", ctypes.c_void_p),
@@ -48,7 +52,8 @@ class aa_param_grads(ctypes.Structure):
 EXPORTS = ("agent_attn_workspace_bytes", "agent_attn_fwd", "agent_pool_fwd", "agent_aggregate_fwd",
            "agent_broadcast_fwd", "agent_attn_flops", "agent_attn_status_str", "agent_attn_plan_str",
            "agent_attn_bwd_workspace_bytes", "agent_attn_bwd", "agent_attn_bias_tables_bytes",
-           "agent_attn_bias_tables", "agent_attn_fwd_static", "agent_attn_static_scratch_bytes")
+           "agent_attn_bias_tables", "agent_attn_fwd_static", "agent_attn_static_scratch_bytes",
+           "agent_attn_fwd_timed")
 
 _lib = None
 
@@ -78,6 +83,9 @@ def lib():
         L.agent_attn_fwd_static.argtypes = [dp, vp, vp, vp, vp, pp, vp, vp]
         L.agent_attn_static_scratch_bytes.restype = ctypes.c_size_t
         L.agent_attn_static_scratch_bytes.argtypes = []
+        L.agent_attn_fwd_timed.restype = ctypes.c_int
+        L.agent_attn_fwd_timed.argtypes = [dp, vp, vp, vp, vp, pp, vp, ctypes.c_size_t, vp, vp,
+                                           ctypes.POINTER(aa_kernel_time), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
         L.agent_pool_fwd.restype = ctypes.c_int
         L.agent_pool_fwd.argtypes = [dp, vp, vp, vp]
         L.agent_aggregate_fwd.restype = ctypes.c_int
@@ -250,6 +258,23 @@ def agent_attn_fwd_static(Q, K, V, A=None, *, grid=None, agent_grid=None, params
                                      out.data_ptr(), _stream(stream))
     _check(st, "agent_attn_fwd_static")
     return out
+
+
+def agent_attn_fwd_timed(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict | None = None, scale1=0.0,
+                         scale2=0.0, v_residual_k=0.0, n_splits=0, out, workspace, stream=None):
+    """agent_attn_fwd with each kernel launch timed by HIP events on the launch stream; blocks until the
+    pass is done.  Returns [(launcher name, milliseconds), ...] in launch order."""
+    n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
+    desc = _desc_from(Q, n, grid, agent_grid, same=(K, V), out=out, scale1=scale1, scale2=scale2,
+                      v_residual_k=v_residual_k, n_splits=n_splits)
+    p = make_params(params)
+    times = (aa_kernel_time * 16)()
+    count = ctypes.c_int(0)
+    st = lib().agent_attn_fwd_timed(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(A), _pp(p),
+                                    workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                    out.data_ptr(), _stream(stream), times, 16, ctypes.byref(count))
+    _check(st, "agent_attn_fwd_timed")
+    return [(times[i].name.decode(), float(times[i].ms)) for i in range(count.value)]
 
 
 def static_scratch_bytes() -> int:

@@ -5,6 +5,7 @@
 
 #include <math.h>
 #include <stdio.h>
+#include <string.h>
 
 #include <initializer_list>
 #include <mutex>
@@ -353,9 +354,35 @@ aa_status check_workspace(const void* ws, size_t bytes, const Plan& pl) {
   return AA_OK;
 }
 
-#define AA_HIP(call)                       \
-  do {                                     \
+// Launch recorder of agent_attn_fwd_timed(): while one is installed on the calling thread, every kernel launcher
+// that returns through AA_HIP is followed by an event on the recorder's stream, so that the time between
+// consecutive events is the duration of that launcher's kernel.
+struct LaunchRecorder {
+  static constexpr int kMax = 16;
+  hipStream_t stream;
+  int n;
+  const char* names[kMax];      // the launcher's name inside its AA_HIP(...) text, e.g. "large_aggregate2_dp64"
+  int name_len[kMax];
+  hipEvent_t ev[kMax + 1];      // ev[0] before the first launch
+};
+thread_local LaunchRecorder* g_recorder = nullptr;
+
+void note_launch(const char* call_text) {
+  LaunchRecorder* r = g_recorder;
+  static const char kPrefix[] = "aa::launch_";
+  if (!r || r->n >= LaunchRecorder::kMax || strncmp(call_text, kPrefix, sizeof(kPrefix) - 1) != 0) return;
+  const char* name = call_text + sizeof(kPrefix) - 1;
+  const char* end = strchr(name, '(');
+  r->names[r->n] = name;
+  r->name_len[r->n] = end ? (int)(end - name) : (int)strlen(name);
+  (void)hipEventRecord(r->ev[r->n + 1], r->stream);
+  ++r->n;
+}
+
+#define AA_HIP(call)                             \
+  do {                                           \
     if ((call) != hipSuccess) return AA_ERR_HIP; \
+    note_launch(#call);                          \
   } while (0)
 
 aa::LargeFwdBuffers large_buffers(void* ws, const Plan& pl, const Problem& pr) {
@@ -385,16 +412,19 @@ aa_status run_large_forward(const Problem& pr, const void* Q, const void* K, con
     case 32:
       AA_HIP(aa::launch_large_agents_dp32(pr, Q, A, b, st));
       AA_HIP(aa::launch_large_aggregate2_dp32(pr, K, V, b, nullptr, st));
+      if (b.S > 1) AA_HIP(aa::launch_large_merge2_dp32(pr, b, nullptr, st));
       AA_HIP(aa::launch_large_broadcast2_dp32(pr, Q, V, out, b, pl.bcast_waves_large, st));
       break;
     case 64:
       AA_HIP(aa::launch_large_agents_dp64(pr, Q, A, b, st));
       AA_HIP(aa::launch_large_aggregate2_dp64(pr, K, V, b, nullptr, st));
+      if (b.S > 1) AA_HIP(aa::launch_large_merge2_dp64(pr, b, nullptr, st));
       AA_HIP(aa::launch_large_broadcast2_dp64(pr, Q, V, out, b, pl.bcast_waves_large, st));
       break;
     default:
       AA_HIP(aa::launch_large_agents_dp128(pr, Q, A, b, st));
       AA_HIP(aa::launch_large_aggregate2_dp128(pr, K, V, b, nullptr, st));
+      if (b.S > 1) AA_HIP(aa::launch_large_merge2_dp128(pr, b, nullptr, st));
       AA_HIP(aa::launch_large_broadcast2_dp128(pr, Q, V, out, b, pl.bcast_waves_large, st));
       break;
   }
@@ -418,14 +448,17 @@ aa_status run_aggregate(const Problem& pr, const void* A, const void* Alo, const
       case 32:
         AA_HIP(aa::launch_large_agents_dp32(pr, nullptr, A, b, st));
         AA_HIP(aa::launch_large_aggregate2_dp32(pr, K, V, b, VA, st));
+        if (b.S > 1) AA_HIP(aa::launch_large_merge2_dp32(pr, b, VA, st));
         break;
       case 64:
         AA_HIP(aa::launch_large_agents_dp64(pr, nullptr, A, b, st));
         AA_HIP(aa::launch_large_aggregate2_dp64(pr, K, V, b, VA, st));
+        if (b.S > 1) AA_HIP(aa::launch_large_merge2_dp64(pr, b, VA, st));
         break;
       default:
         AA_HIP(aa::launch_large_agents_dp128(pr, nullptr, A, b, st));
         AA_HIP(aa::launch_large_aggregate2_dp128(pr, K, V, b, VA, st));
+        if (b.S > 1) AA_HIP(aa::launch_large_merge2_dp128(pr, b, VA, st));
         break;
     }
     return AA_OK;
@@ -816,6 +849,45 @@ aa_status agent_attn_fwd_static(const aa_desc* desc, const void* Q, const void* 
     ptr = base[dev];
   }
   return agent_attn_fwd(desc, Q, K, V, A, params, ptr, AA_STATIC_SCRATCH_BYTES, out, hip_stream);
+}
+
+aa_status agent_attn_fwd_timed(const aa_desc* desc, const void* Q, const void* K, const void* V, const void* A,
+                               const aa_params* params, void* workspace, size_t workspace_bytes, void* out,
+                               void* hip_stream, aa_kernel_time* times, int max_times, int* n_times) {
+  if (!times || !n_times || max_times <= 0) return AA_ERR_NULL;
+  *n_times = 0;
+  LaunchRecorder rec{};
+  rec.stream = (hipStream_t)hip_stream;
+  int made = 0;
+  aa_status st = AA_OK;
+  for (; made <= LaunchRecorder::kMax; ++made)
+    if (hipEventCreate(&rec.ev[made]) != hipSuccess) {
+      st = AA_ERR_HIP;
+      break;
+    }
+  if (st == AA_OK && hipEventRecord(rec.ev[0], rec.stream) != hipSuccess) st = AA_ERR_HIP;
+  if (st == AA_OK) {
+    g_recorder = &rec;
+    st = agent_attn_fwd(desc, Q, K, V, A, params, workspace, workspace_bytes, out, hip_stream);
+    g_recorder = nullptr;
+  }
+  if (st == AA_OK && rec.n > 0 && hipEventSynchronize(rec.ev[rec.n]) != hipSuccess) st = AA_ERR_HIP;
+  if (st == AA_OK) {
+    for (int i = 0; i < rec.n && i < max_times; ++i) {
+      float ms = 0.0f;
+      if (hipEventElapsedTime(&ms, rec.ev[i], rec.ev[i + 1]) != hipSuccess) {
+        st = AA_ERR_HIP;
+        break;
+      }
+      const int len = rec.name_len[i] < (int)sizeof(times[i].name) - 1 ? rec.name_len[i] : (int)sizeof(times[i].name) - 1;
+      memcpy(times[i].name, rec.names[i], (size_t)len);
+      times[i].name[len] = 0;
+      times[i].ms = ms;
+      *n_times = i + 1;
+    }
+  }
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(rec.ev[i]);
+  return st;
 }
 
 size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, size_t buf_len) {

@@ -136,6 +136,7 @@ AA_DECLARE_LARGE(128)
                                         const LargeFwdBuffers& b, hipStream_t st);                                  \
   hipError_t launch_large_aggregate2_dp##DP(const Problem& p, const void* K, const void* V,                         \
                                             const LargeFwdBuffers& b, float* VA32, hipStream_t st);                 \
+  hipError_t launch_large_merge2_dp##DP(const Problem& p, const LargeFwdBuffers& b, float* VA32, hipStream_t st);   \
   hipError_t launch_large_broadcast2_dp##DP(const Problem& p, const void* Q, const void* V, void* out,              \
                                             const LargeFwdBuffers& b, int waves, hipStream_t st);
 AA_DECLARE_LARGE_FWD(32)
