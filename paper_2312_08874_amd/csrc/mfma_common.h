@@ -42,6 +42,10 @@ struct Mx<ElemBF16> {
     lo = __uint_as_float(w << 16);
     hi = __uint_as_float(w & 0xFFFF0000u);
   }
+  // acc + the two packed elements of w (one v_dot2c against a pair of ones)
+  static __device__ __forceinline__ float add_pair(uint32_t w, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, kOnes2), acc, false);
+  }
 };
 template <>
 struct Mx<ElemF16> {
@@ -59,6 +63,9 @@ struct Mx<ElemF16> {
     const f16x2 h = __builtin_bit_cast(f16x2, w);
     lo = (float)h[0];
     hi = (float)h[1];
+  }
+  static __device__ __forceinline__ float add_pair(uint32_t w, float acc) {
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), __builtin_bit_cast(f16x2, kOnes2), acc, false);
   }
 };
 
