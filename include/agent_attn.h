@@ -147,6 +147,19 @@ size_t agent_attn_bias_tables_bytes(const aa_desc *desc, const aa_params *params
 aa_status agent_attn_bias_tables(const aa_desc *desc, const aa_params *params, void *tables,
                                  size_t tables_bytes, void *hip_stream);
 
+/* Agent bias adapted to another number of agent tokens (Appendix D.1 / D.2, "Numbers of agent tokens": a
+ * model trained with n agents runs with more agents on higher-resolution inputs, its agent bias bilinearly
+ * interpolated).  Every bias component present in `src` (laid out for agent_h x agent_w agents on a
+ * grid_h x grid_w token grid, src->blk_h0 x blk_w0 block components) is interpolated along its agent grid,
+ * with half-pixel centres as for the block bias, into the array of the same name in `dst`, which the caller
+ * sized for new_agent_h x new_agent_w agents: b1_col [H,n',w], b1_row [H,n',h], b1_blk [H,n',h0,w0], b2_col
+ * [H,w,n'], b2_row [H,h,n'], b2_blk [H,h0,w0,n'].  The token grid and the block size stay as they are; DWC
+ * parameters do not depend on the agents and are not touched.  Errors: AA_ERR_NULL when a component of src
+ * has no destination, AA_ERR_ALIAS when source and destination coincide, AA_ERR_SHAPE for non-positive sizes. */
+aa_status agent_attn_resize_bias(int32_t heads, int32_t grid_h, int32_t grid_w, int32_t agent_h,
+                                 int32_t agent_w, int32_t new_agent_h, int32_t new_agent_w,
+                                 const aa_params *src, const aa_params *dst, void *hip_stream);
+
 /* A = Pooling(Q), Sec. 4.2: average over the window
  * [floor(i*L/La), ceil((i+1)*L/La)) per axis.  A_out [batch, heads, n, d], desc->dtype. */
 aa_status agent_pool_fwd(const aa_desc *desc, const void *Q, void *A_out, void *hip_stream);

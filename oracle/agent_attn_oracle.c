@@ -157,6 +157,29 @@ void oracle_resize_bilinear(const double *src, int h0, int w0, size_t stride,
 }
 
 /* ------------------------------------------------------------------------
+ * Agent bias adapted to another number of agent tokens (Appendix D.1 / D.2,
+ * "Numbers of agent tokens": the bias of a model trained with n agents is
+ * bilinearly interpolated to the larger n used on higher-resolution inputs).
+ * A bias component is viewed as [outer, ah, aw, inner] with the agents on an
+ * ah x aw grid (agent a = ay*aw + ax); every [ah, aw] image (one per outer
+ * and inner index) is resized to [ah2, aw2] with the same half-pixel rule as
+ * oracle_resize_bilinear().  dst [outer, ah2, aw2, inner].
+ * ---------------------------------------------------------------------- */
+void oracle_resize_agent_axis(const double *src, int outer, int ah, int aw,
+                              int inner, int ah2, int aw2, double *dst)
+{
+    double *plane = (double *)malloc((size_t)ah2 * aw2 * sizeof(double));
+    for (int o = 0; o < outer; ++o)
+        for (int i = 0; i < inner; ++i) {
+            oracle_resize_bilinear(src + (size_t)o * ah * aw * inner + i, ah, aw,
+                                   (size_t)inner, ah2, aw2, plane);
+            for (int a = 0; a < ah2 * aw2; ++a)
+                dst[((size_t)o * ah2 * aw2 + a) * inner + i] = plane[a];
+        }
+    free(plane);
+}
+
+/* ------------------------------------------------------------------------
  * Agent bias composition, Appendix B, for ONE head.
  *
  *   B1[a, y*w+x] = col1[a,x] + row1[a,y] + resize(blk1[a,:,:])[y,x]

@@ -32,17 +32,20 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def use_library(path: str) -> None:
+    """Load a differently built copy of the oracle instead of oracle/liboracle.so.  For the mutation test
+    only (tests/test_oracle_mutations.py hands the path to its pytest subprocess with --oracle-lib): it
+    checks that the pins notice a mistake planted in a copy of the source."""
+    global _lib
+    _lib = ctypes.CDLL(path)
+    _lib.oracle_num_threads.restype = ctypes.c_int
+
+
 def _load():
     global _lib
     if _lib is None:
-        # AA_ORACLE_LIB: a differently built copy of this library.  Only the mutation test sets it, to check
-        # that the pins notice a planted mistake; nothing else may.
-        alt = os.environ.get("AA_ORACLE_LIB")
-        if alt:
-            _lib = ctypes.CDLL(alt)
-        else:
-            build()
-            _lib = ctypes.CDLL(_LIB)
+        build()
+        _lib = ctypes.CDLL(_LIB)
         _lib.oracle_num_threads.restype = ctypes.c_int
     return _lib
 
@@ -92,6 +95,40 @@ def resize_bilinear(plane, h, w):
     h0, w0 = plane.shape
     out = np.empty((h, w), dtype=np.float64)
     _load().oracle_resize_bilinear(_p(plane), h0, w0, ctypes.c_size_t(1), h, w, _p(out))
+    return out
+
+
+def resize_agent_axis(comp, agent_grid, new_agent_grid, agents_last):
+    """Appendix D.1 / D.2 ("Numbers of agent tokens"): one bias component bilinearly interpolated along
+    its agent grid.  agents_last False: comp [..., n, inner...] with the agents right after the leading
+    (head) axis, e.g. b1_col [H, n, w], b1_blk [H, n, h0, w0]; True: agents on the last axis, e.g.
+    b2_col [H, w, n], b2_blk [H, h0, w0, n].  Returns the component for the new agent grid."""
+    comp = _f64(comp)
+    ah, aw = agent_grid
+    ah2, aw2 = new_agent_grid
+    if agents_last:
+        assert comp.shape[-1] == ah * aw
+        outer, inner = int(np.prod(comp.shape[:-1])), 1
+        new_shape = comp.shape[:-1] + (ah2 * aw2,)
+    else:
+        assert comp.shape[1] == ah * aw
+        outer, inner = comp.shape[0], int(np.prod(comp.shape[2:]))
+        new_shape = (comp.shape[0], ah2 * aw2) + comp.shape[2:]
+    out = np.empty(new_shape, dtype=np.float64)
+    _load().oracle_resize_agent_axis(_p(comp), outer, ah, aw, inner, ah2, aw2, _p(out))
+    return out
+
+
+def resize_bias_agents(params, agent_grid, new_agent_grid):
+    """All bias components of a parameter dict (keys b1_col, b1_row, b1_blk, b2_col, b2_row, b2_blk; each
+    [H, ...]) adapted to a new agent grid; other entries are passed through."""
+    out = dict(params)
+    for key in ("b1_col", "b1_row", "b1_blk"):
+        if params.get(key) is not None:
+            out[key] = resize_agent_axis(params[key], agent_grid, new_agent_grid, agents_last=False)
+    for key in ("b2_col", "b2_row", "b2_blk"):
+        if params.get(key) is not None:
+            out[key] = resize_agent_axis(params[key], agent_grid, new_agent_grid, agents_last=True)
     return out
 
 

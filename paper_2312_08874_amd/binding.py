@@ -53,7 +53,7 @@ EXPORTS = ("agent_attn_workspace_bytes", "agent_attn_fwd", "agent_pool_fwd", "ag
            "agent_broadcast_fwd", "agent_attn_flops", "agent_attn_status_str", "agent_attn_plan_str",
            "agent_attn_bwd_workspace_bytes", "agent_attn_bwd", "agent_attn_bias_tables_bytes",
            "agent_attn_bias_tables", "agent_attn_fwd_static", "agent_attn_static_scratch_bytes",
-           "agent_attn_fwd_timed")
+           "agent_attn_fwd_timed", "agent_attn_resize_bias")
 
 _lib = None
 
@@ -86,6 +86,8 @@ def lib():
         L.agent_attn_fwd_timed.restype = ctypes.c_int
         L.agent_attn_fwd_timed.argtypes = [dp, vp, vp, vp, vp, pp, vp, ctypes.c_size_t, vp, vp,
                                            ctypes.POINTER(aa_kernel_time), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+        L.agent_attn_resize_bias.restype = ctypes.c_int
+        L.agent_attn_resize_bias.argtypes = [ctypes.c_int32] * 7 + [pp, pp, vp]
         L.agent_pool_fwd.restype = ctypes.c_int
         L.agent_pool_fwd.argtypes = [dp, vp, vp, vp]
         L.agent_aggregate_fwd.restype = ctypes.c_int
@@ -275,6 +277,31 @@ def agent_attn_fwd_timed(Q, K, V, A=None, *, grid=None, agent_grid=None, params:
                                     out.data_ptr(), _stream(stream), times, 16, ctypes.byref(count))
     _check(st, "agent_attn_fwd_timed")
     return [(times[i].name.decode(), float(times[i].ms)) for i in range(count.value)]
+
+
+def agent_attn_resize_bias(params: dict, *, heads, grid, agent_grid, new_agent_grid, stream=None) -> dict:
+    """Bias components of `params` adapted to new_agent_grid (Appendix D.1 / D.2); returns a new dict in which
+    they are replaced by freshly allocated tensors and every other entry (DWC) is passed through."""
+    import torch
+    n2 = new_agent_grid[0] * new_agent_grid[1]
+    out = {k: v for k, v in params.items() if k != "bias_tables"}
+    for key in ("b1_col", "b1_row", "b1_blk"):
+        if params.get(key) is not None:
+            t = params[key]
+            out[key] = torch.empty((t.shape[0], n2) + tuple(t.shape[2:]), dtype=torch.float32, device=t.device)
+    for key in ("b2_col", "b2_row", "b2_blk"):
+        if params.get(key) is not None:
+            t = params[key]
+            out[key] = torch.empty(tuple(t.shape[:-1]) + (n2,), dtype=torch.float32, device=t.device)
+    bias_keys = ("b1_col", "b1_row", "b1_blk", "b2_col", "b2_row", "b2_blk")
+    src = make_params({k: params[k] for k in bias_keys if params.get(k) is not None})
+    dst = make_params({k: out[k] for k in bias_keys if params.get(k) is not None})
+    if src is None:
+        return out
+    st = lib().agent_attn_resize_bias(heads, grid[0], grid[1], agent_grid[0], agent_grid[1], new_agent_grid[0],
+                                      new_agent_grid[1], _pp(src), _pp(dst), _stream(stream))
+    _check(st, "agent_attn_resize_bias")
+    return out
 
 
 def static_scratch_bytes() -> int:

@@ -579,6 +579,33 @@ aa_status agent_attn_bias_tables(const aa_desc* desc, const aa_params* params, v
   return prepare_bias_tables(pr, bp, tables, true, (hipStream_t)hip_stream);
 }
 
+aa_status agent_attn_resize_bias(int32_t heads, int32_t grid_h, int32_t grid_w, int32_t agent_h, int32_t agent_w,
+                                 int32_t new_agent_h, int32_t new_agent_w, const aa_params* src, const aa_params* dst,
+                                 void* hip_stream) {
+  if (!src || !dst) return AA_ERR_NULL;
+  if (heads <= 0 || grid_h <= 0 || grid_w <= 0 || agent_h <= 0 || agent_w <= 0 || new_agent_h <= 0 || new_agent_w <= 0)
+    return AA_ERR_SHAPE;
+  if ((src->b1_blk || src->b2_blk) && (src->blk_h0 <= 0 || src->blk_w0 <= 0)) return AA_ERR_SHAPE;
+  if ((int64_t)new_agent_h * new_agent_w * (int64_t)heads * ((int64_t)grid_h + grid_w) >= ((int64_t)1 << 40)) return AA_ERR_UNSUPPORTED;
+  // every component present in src needs a destination (and nothing else is touched)
+  const float* in[6] = {src->b1_col, src->b1_row, src->b1_blk, src->b2_col, src->b2_row, src->b2_blk};
+  float* out[6] = {(float*)dst->b1_col, (float*)dst->b1_row, (float*)dst->b1_blk,
+                   (float*)dst->b2_col, (float*)dst->b2_row, (float*)dst->b2_blk};
+  const int inner_len[3] = {grid_w, grid_h, src->blk_h0 * src->blk_w0};      // per agent: col, row, block
+  for (int k = 0; k < 6; ++k)
+    if (in[k] && (!out[k] || out[k] == in[k])) return out[k] ? AA_ERR_ALIAS : AA_ERR_NULL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  for (int k = 0; k < 6; ++k) {
+    if (!in[k]) continue;
+    const int len = inner_len[k % 3];
+    // kind 1: [H][n][len] (agents before the per-agent values); kind 2: [H][len][n] (agents last)
+    const size_t outer = k < 3 ? (size_t)heads : (size_t)heads * len;
+    const int inner = k < 3 ? len : 1;
+    AA_HIP(aa::launch_resize_agent_axis(in[k], out[k], outer, agent_h, agent_w, inner, new_agent_h, new_agent_w, st));
+  }
+  return AA_OK;
+}
+
 uint64_t agent_attn_flops(const aa_desc* desc) {
   if (check_desc(desc, false, false) != AA_OK) return 0;
   return 8ull * (uint64_t)desc->N * (uint64_t)desc->n * (uint64_t)desc->d * (uint64_t)desc->batch *

@@ -524,6 +524,40 @@ hipError_t launch_restride(const Problem& p, bool to_dense, bool out_layout, con
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Bias component adapted to another agent grid (Appendix D.1 / D.2, "Numbers of agent tokens"): the tensor is
+// viewed as [outer][ah][aw][inner] and every [ah][aw] image is bilinearly interpolated (half-pixel centres, as
+// for the block bias) to [ah2][aw2].  thread = one output element.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void resize_agent_axis_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                                int ah, int aw, int inner, int ah2, int aw2,
+                                                                size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  const int c = (int)(i % inner);
+  const size_t t = i / inner;
+  const int ax = (int)(t % aw2), ay = (int)((t / aw2) % ah2);
+  const size_t o = t / ((size_t)aw2 * ah2);
+  int y0, y1, x0, x1;
+  float fy, fx;
+  bilinear_coord(ay, ah2, ah, y0, y1, fy);
+  bilinear_coord(ax, aw2, aw, x0, x1, fx);
+  const float* p = src + o * ah * aw * inner + c;
+  const float v00 = p[(size_t)(y0 * aw + x0) * inner], v01 = p[(size_t)(y0 * aw + x1) * inner];
+  const float v10 = p[(size_t)(y1 * aw + x0) * inner], v11 = p[(size_t)(y1 * aw + x1) * inner];
+  const float top = v00 + (v01 - v00) * fx, bot = v10 + (v11 - v10) * fx;
+  dst[i] = top + (bot - top) * fy;
+}
+
+hipError_t launch_resize_agent_axis(const float* src, float* dst, size_t outer, int ah, int aw, int inner, int ah2,
+                                    int aw2, hipStream_t st) {
+  const size_t count = outer * ah2 * aw2 * inner;
+  if (count == 0) return hipSuccess;
+  resize_agent_axis_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(src, dst, ah, aw, inner, ah2, aw2,
+                                                                                      count);
+  return hipGetLastError();
+}
+
 size_t bias_dense_floats(int kind, int heads, int n, int N) {
   return kind == 1 ? (size_t)heads * round_up64(n) * round_up64(N) : (size_t)heads * N * round_up64(n);
 }

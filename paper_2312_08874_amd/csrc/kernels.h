@@ -43,6 +43,9 @@ hipError_t launch_pool_chunk(const Problem& p, const void* Q, void* A, void* Alo
 // layout of BiasArgs, in one launch; a null output skips that kind
 size_t bias_dense_floats(int kind, int heads, int n, int N);
 hipError_t launch_bias_dense(const Problem& p, float* out1, float* out2, hipStream_t st);
+// one bias component [outer][ah][aw][inner] bilinearly interpolated along its agent grid to [outer][ah2][aw2][inner]
+hipError_t launch_resize_agent_axis(const float* src, float* dst, size_t outer, int ah, int aw, int inner, int ah2,
+                                    int aw2, hipStream_t st);
 // dense <-> strided copy of a [units][N][d] token tensor in the problem's element type; the strided side
 // uses the input strides of p.lay, or its output strides (out_layout)
 hipError_t launch_restride(const Problem& p, bool to_dense, bool out_layout, const void* src, void* dst, hipStream_t st);

@@ -305,6 +305,31 @@ def _stored(A, wl):
     return a.numpy()
 
 
+@pytest.mark.parametrize("dtype,d", [("f32", 24), ("bf16", 32), ("f16", 40)])
+def test_bias_adapted_to_more_agents(aa, oracle, dtype, d):
+    """Appendix D.1 / D.2 ("Numbers of agent tokens"): bias parameters of a 7 x 7 = 49-agent model interpolated
+    to 14 x 14 = 196 agents on the GPU, against the oracle's interpolation, and the forward pass with the
+    adapted bias against the oracle's."""
+    import dataclasses
+    heads, grid, agrid, agrid2 = 2, (28, 28), (7, 7), (14, 14)
+    trained = inputs.make_module_params(heads, agrid[0] * agrid[1], d, grid, blk=(4, 3), index=7)
+    dev = util.params_to_device(trained)
+    adapted = aa.agent_attn_resize_bias(dev, heads=heads, grid=grid, agent_grid=agrid, new_agent_grid=agrid2)
+    ref_params = oracle.resize_bias_agents({k: np.asarray(v, dtype=np.float64) for k, v in trained.items()}, agrid, agrid2)
+    for key in ("b1_col", "b1_row", "b1_blk", "b2_col", "b2_row", "b2_blk"):
+        got = adapted[key].cpu().numpy().astype(np.float64)
+        assert got.shape == ref_params[key].shape
+        assert np.abs(got - ref_params[key]).max() <= 1e-6 * max(1.0, np.abs(ref_params[key]).max()), key
+    assert adapted["dwc_w"] is dev["dwc_w"]
+    wl = dataclasses.replace(WL["deit_t"], batch=1, heads=heads, grid=grid, agent_grid=agrid2, d=d, dtype=dtype, index=7)
+    t = inputs.make_qkv(wl)
+    dv = dev_qkv(wl, t)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=grid, agent_grid=agrid2, params=adapted)
+    ref = util.oracle_forward_units(oracle, wl, t, list(range(wl.units)), params=ref_params)
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, dtype, "bias adapted to 196 agents",
+                       max_abs=None if dtype == "f32" else 1e-2 * max(1.0, float(np.abs(ref).max())))
+
+
 def test_highres_module_mode_sampled(aa, oracle):
     wl = WL["highres"]
     t = inputs.make_qkv(wl)

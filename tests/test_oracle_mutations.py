@@ -39,6 +39,10 @@ MUTATIONS = [
     ("dA of the two stages not added", "dA_keys[e] += dA_queries[e];", "dA_keys[e] += 0.0;", 0),
     ("bias-block gradient misses one bilinear corner", "gsrc[((size_t)y1 * w0 + x1) * stride] += gv * fy * fx;",
      "gsrc[((size_t)y1 * w0 + x1) * stride] += 0.0;", 0),
+    ("agent-axis resize walks the agent grid transposed", "oracle_resize_bilinear(src + (size_t)o * ah * aw * inner + i, ah, aw,",
+     "oracle_resize_bilinear(src + (size_t)o * ah * aw * inner + i, aw, ah,", 0),
+    ("agent-axis resize scatters with the wrong stride", "dst[((size_t)o * ah2 * aw2 + a) * inner + i] = plane[a];",
+     "dst[((size_t)o * ah2 * aw2 + a) + (size_t)i * ah2 * aw2] = plane[a];", 0),
 ]
 
 
@@ -51,9 +55,9 @@ def _build(tmp_path, name, text):
 
 
 def _pins_pass(lib):
-    env = dict(os.environ, AA_ORACLE_LIB=lib, OMP_NUM_THREADS="2")
+    env = dict(os.environ, OMP_NUM_THREADS="2")
     r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_oracle_pins.py", "tests/test_oracle_bwd_pins.py", "-x",
-                        "-q", "-p", "no:cacheprovider"], cwd=ROOT, env=env, stdout=subprocess.PIPE,
+                        "-q", "-p", "no:cacheprovider", "--oracle-lib", lib], cwd=ROOT, env=env, stdout=subprocess.PIPE,
                        stderr=subprocess.STDOUT, timeout=600)
     return r.returncode == 0, r.stdout.decode()[-400:]
 

@@ -123,6 +123,37 @@ def test_bilinear_vs_brute_and_library(oracle):
     np.testing.assert_allclose(oracle.resize_bilinear(np.full((3, 3), 1.7), 11, 5), 1.7, atol=1e-15)
 
 
+def test_agent_axis_resize_vs_library_and_brute(oracle):
+    """Appendix D.1 / D.2: bias components interpolated to another agent count, both component layouts."""
+    heads, (ah, aw), (ah2, aw2) = 2, (3, 4), (6, 7)
+    for shape_tail in [(5,), (2, 3)]:      # b1_col-like [H, n, w] and b1_blk-like [H, n, h0, w0]
+        comp = rnd((heads, ah * aw) + shape_tail, 34)
+        got = oracle.resize_agent_axis(comp, (ah, aw), (ah2, aw2), agents_last=False)
+        assert got.shape == (heads, ah2 * aw2) + shape_tail
+        img = torch.from_numpy(comp.reshape(heads, ah, aw, -1)).permute(0, 3, 1, 2)      # [H, inner, ah, aw]
+        lib = F.interpolate(img, size=(ah2, aw2), mode="bilinear", align_corners=False)
+        np.testing.assert_allclose(got.reshape(heads, ah2, aw2, -1), lib.permute(0, 2, 3, 1).numpy(), atol=1e-13)
+        plane = comp[1].reshape(ah, aw, -1)[:, :, 0]      # brute force on one image
+        np.testing.assert_allclose(got[1].reshape(ah2, aw2, -1)[:, :, 0],
+                                   np.array(brute.bilinear(plane.tolist(), ah2, aw2)), atol=1e-13)
+    for shape_head in [(5,), (2, 3)]:      # b2_col-like [H, w, n] and b2_blk-like [H, h0, w0, n]
+        comp = rnd((heads,) + shape_head + (ah * aw,), 35)
+        got = oracle.resize_agent_axis(comp, (ah, aw), (ah2, aw2), agents_last=True)
+        assert got.shape == (heads,) + shape_head + (ah2 * aw2,)
+        img = torch.from_numpy(comp.reshape(-1, 1, ah, aw))
+        lib = F.interpolate(img, size=(ah2, aw2), mode="bilinear", align_corners=False)
+        np.testing.assert_allclose(got.reshape(-1, ah2, aw2), lib[:, 0].numpy(), atol=1e-13)
+    comp = rnd((heads, ah * aw, 4), 36)
+    np.testing.assert_array_equal(oracle.resize_agent_axis(comp, (ah, aw), (ah, aw), agents_last=False), comp)
+    const = np.full((heads, 6, ah * aw), -0.3)
+    np.testing.assert_allclose(oracle.resize_agent_axis(const, (ah, aw), (9, 2), agents_last=True), -0.3, atol=1e-15)
+    # whole parameter sets: every bias component is resized, the rest is passed through
+    params = dict(b1_col=rnd((heads, ah * aw, 8), 37), b2_blk=rnd((heads, 2, 2, ah * aw), 38), dwc_w=rnd((heads, 4, 3, 3), 39))
+    out = oracle.resize_bias_agents(params, (ah, aw), (ah2, aw2))
+    assert out["b1_col"].shape == (heads, ah2 * aw2, 8) and out["b2_blk"].shape == (heads, 2, 2, ah2 * aw2)
+    assert out["dwc_w"] is params["dwc_w"]
+
+
 def test_bias_components(oracle):
     n, h, w, h0, w0 = 5, 6, 8, 3, 4
     col1, row1, blk1 = rnd((n, w), 31), rnd((n, h), 32), rnd((n, h0, w0), 33)
