@@ -82,6 +82,21 @@ typedef struct {
                                            N*H*d, stride_h = d, stride_n = H*d; the q / k / v slices of a
                                            fused projection output [B,N,3,H,d] use stride_n = 3*H*d. */
   int64_t out_stride_b, out_stride_h, out_stride_n; /* the same for `out`; all 0 = dense [B,H,N,d] */
+  int32_t image_h, image_w; /* Both 0: no windows.  Otherwise (Sec. 5.5, window-size ablation: agent attention
+                               inside the windows of a Swin-style model) Q, K, V and out are images of
+                               image_h x image_w tokens per (batch, head), row-major, and the attention runs
+                               independently inside every grid_h x grid_w window (image_h % grid_h == 0,
+                               image_w % grid_w == 0; N = grid_h*grid_w stays the tokens of ONE window; pooling,
+                               bias and DWC act within a window, DWC zero-padded at its border).  The windows
+                               are addressed where they lie: image token (Y,X) of (b,h) is at
+                               b*stride_b + h*stride_h + (Y*image_w + X)*stride_n; all strides 0 = dense
+                               [B,H,image_h*image_w,d].  Given agents A are [batch, windows, heads, n, d],
+                               windows in row-major order (dA likewise).  Served by agent_attn_fwd (and its
+                               _static / _timed forms) and agent_attn_bwd; the stage entry points return
+                               AA_ERR_UNSUPPORTED for a windowed descriptor.  fp32 and problems served by
+                               the one-block-per-unit kernel read the windows in place; the other 16-bit
+                               kernel families and the backward pass work on window-major copies that the
+                               call makes in the workspace, and scatter their results back. */
 } aa_desc;
 
 /* Module-mode parameters (host struct of device pointers, fp32).  A NULL pointer

@@ -29,7 +29,8 @@ class aa_desc(ctypes.Structure):
                 ("v_residual_k", ctypes.c_float),
                 ("n_splits", ctypes.c_int32),
                 ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
-                ("out_stride_b", ctypes.c_int64), ("out_stride_h", ctypes.c_int64), ("out_stride_n", ctypes.c_int64)]
+                ("out_stride_b", ctypes.c_int64), ("out_stride_h", ctypes.c_int64), ("out_stride_n", ctypes.c_int64),
+                ("image_h", ctypes.c_int32), ("image_w", ctypes.c_int32)]
 
 
 class aa_params(ctypes.Structure):
@@ -121,12 +122,14 @@ def _dtype_code(t):
 
 
 def make_desc(batch, heads, N, n, d, dtype, grid=None, agent_grid=None, scale1=0.0, scale2=0.0,
-              v_residual_k=0.0, n_splits=0, strides=(0, 0, 0), out_strides=(0, 0, 0)) -> aa_desc:
-    """strides / out_strides: (batch, head, token) element strides of Q, K, V / of out; zeros = dense."""
+              v_residual_k=0.0, n_splits=0, strides=(0, 0, 0), out_strides=(0, 0, 0), image=None) -> aa_desc:
+    """strides / out_strides: (batch, head, token) element strides of Q, K, V / of out; zeros = dense.
+    image: (image_h, image_w) when the tensors are images cut into grid-sized windows (N = one window)."""
     gh, gw = grid if grid is not None else (0, 0)
     ah, aw = agent_grid if agent_grid is not None else (0, 0)
+    ih, iw = image if image is not None else (0, 0)
     return aa_desc(batch, heads, N, n, d, gh, gw, ah, aw, dtype, scale1, scale2, v_residual_k, n_splits,
-                   *[int(x) for x in strides], *[int(x) for x in out_strides])
+                   *[int(x) for x in strides], *[int(x) for x in out_strides], ih, iw)
 
 
 def make_params(params: dict | None):
@@ -220,6 +223,11 @@ def _desc_from(Q, n, grid, agent_grid, same=(), out=None, **kw):
         assert t is None or (tuple(t.shape) == tuple(Q.shape) and _strides_of(t) == st), \
             "Q, K, V must share one shape and one set of strides"
     ost = _strides_of(out) if out is not None else (0, 0, 0)
+    window = kw.pop("window", None)
+    if window is not None:      # Q is the whole image [B,H,grid_h*grid_w,d]; the attention runs per window
+        assert grid is not None and grid[0] * grid[1] == N and grid[0] % window[0] == 0 and grid[1] % window[1] == 0
+        return make_desc(B, H, window[0] * window[1], n, d, _dtype_code(Q), window, agent_grid, strides=st,
+                         out_strides=ost, image=grid, **kw)
     return make_desc(B, H, N, n, d, _dtype_code(Q), grid, agent_grid, strides=st, out_strides=ost, **kw)
 
 
@@ -232,14 +240,17 @@ def _workspace(desc, params, workspace):
 
 
 def agent_attn_fwd(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict | None = None, scale1=0.0,
-                   scale2=0.0, v_residual_k=0.0, n_splits=0, out=None, workspace=None, stream=None):
-    """O = agent attention of Q, K, V [B,H,N,d] (device tensors).  A None: pool Q onto agent_grid."""
+                   scale2=0.0, v_residual_k=0.0, n_splits=0, window=None, out=None, workspace=None, stream=None):
+    """O = agent attention of Q, K, V [B,H,N,d] (device tensors).  A None: pool Q onto agent_grid.
+    window=(wh, ww): the tensors are grid-sized images and the attention (pooling, bias, DWC included) runs
+    inside each wh x ww window on its own; agent_grid and params then describe one window, a given A is
+    [B, windows, H, n, d]."""
     import torch
     n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
     if out is None:
         out = torch.empty_like(Q)      # keeps Q's (possibly permuted) layout
     desc = _desc_from(Q, n, grid, agent_grid, same=(K, V), out=out, scale1=scale1, scale2=scale2,
-                      v_residual_k=v_residual_k, n_splits=n_splits)
+                      v_residual_k=v_residual_k, n_splits=n_splits, window=window)
     p = make_params(params)
     workspace, need = _workspace(desc, p, workspace)
     st = lib().agent_attn_fwd(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(A), _pp(p),
@@ -250,11 +261,11 @@ def agent_attn_fwd(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict 
 
 
 def agent_attn_fwd_static(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict | None = None, scale1=0.0,
-                          scale2=0.0, v_residual_k=0.0, n_splits=0, out, stream=None):
+                          scale2=0.0, v_residual_k=0.0, n_splits=0, window=None, out, stream=None):
     """agent_attn_fwd on the library's own static workspace: allocates nothing (`out` is the caller's)."""
     n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
     desc = _desc_from(Q, n, grid, agent_grid, same=(K, V), out=out, scale1=scale1, scale2=scale2,
-                      v_residual_k=v_residual_k, n_splits=n_splits)
+                      v_residual_k=v_residual_k, n_splits=n_splits, window=window)
     p = make_params(params)
     st = lib().agent_attn_fwd_static(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(A), _pp(p),
                                      out.data_ptr(), _stream(stream))
@@ -263,12 +274,12 @@ def agent_attn_fwd_static(Q, K, V, A=None, *, grid=None, agent_grid=None, params
 
 
 def agent_attn_fwd_timed(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict | None = None, scale1=0.0,
-                         scale2=0.0, v_residual_k=0.0, n_splits=0, out, workspace, stream=None):
+                         scale2=0.0, v_residual_k=0.0, n_splits=0, window=None, out, workspace, stream=None):
     """agent_attn_fwd with each kernel launch timed by HIP events on the launch stream; blocks until the
     pass is done.  Returns [(launcher name, milliseconds), ...] in launch order."""
     n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
     desc = _desc_from(Q, n, grid, agent_grid, same=(K, V), out=out, scale1=scale1, scale2=scale2,
-                      v_residual_k=v_residual_k, n_splits=n_splits)
+                      v_residual_k=v_residual_k, n_splits=n_splits, window=window)
     p = make_params(params)
     times = (aa_kernel_time * 16)()
     count = ctypes.c_int(0)
@@ -309,7 +320,7 @@ def static_scratch_bytes() -> int:
 
 
 def agent_attn_bwd(Q, K, V, dO, A=None, *, grid=None, agent_grid=None, params: dict | None = None, scale1=0.0,
-                   scale2=0.0, v_residual_k=0.0, want_param_grads=True, workspace=None, stream=None):
+                   scale2=0.0, v_residual_k=0.0, want_param_grads=True, window=None, workspace=None, stream=None):
     """Gradients of agent_attn_fwd for upstream dO.  Returns a dict: dQ, dK, dV (shape and type of Q),
     dA when A is given, and, for every module parameter present in `params` (want_param_grads), its
     fp32 gradient under the parameter's own name prefixed with "d" (db1_col, ..., ddwc_w, ddwc_b)."""
@@ -317,7 +328,7 @@ def agent_attn_bwd(Q, K, V, dO, A=None, *, grid=None, agent_grid=None, params: d
     n = A.shape[2] if A is not None else agent_grid[0] * agent_grid[1]
     # Q, K, V (and their gradients) share one set of strides, dO may have its own (the layout of the output)
     desc = _desc_from(Q, n, grid, agent_grid, same=(K, V), out=dO, scale1=scale1, scale2=scale2,
-                      v_residual_k=v_residual_k)
+                      v_residual_k=v_residual_k, window=window)
     p = make_params(params)
     need = int(lib().agent_attn_bwd_workspace_bytes(ctypes.byref(desc), _pp(p)))
     if workspace is None:

@@ -57,13 +57,26 @@ struct Plan {
   size_t off_acc, off_m, off_l;
   size_t off_VA;       // merged V_A, fp32
   BiasPlan bias;       // agent-bias tables, offsets relative to off_bias
+  size_t off_stage;    // window mode: window-major copies of Q, K, V and of the output (kNoStage: not needed)
+  size_t stage_bytes;  // size of one of the four
   size_t off_bias;     // where they live in the workspace (unused when the caller brings prepared tables)
   size_t total;
 };
 
 // Shape checks common to every entry point.  need_grid / need_agent_grid say
 // whether the call uses the 2-D structure of tokens / agents.
-aa_status check_desc(const aa_desc* d, bool need_grid, bool need_agent_grid) {
+bool windowed(const aa_desc* d) {
+  return (d->image_h > 0 || d->image_w > 0) && !(d->image_h == d->grid_h && d->image_w == d->grid_w);
+}
+int64_t windows_of(const aa_desc* d) {
+  return windowed(d) ? (int64_t)(d->image_h / d->grid_h) * (d->image_w / d->grid_w) : 1;
+}
+// independent (batch, window, head) problems
+int64_t units_of(const aa_desc* d) { return (int64_t)d->batch * d->heads * windows_of(d); }
+// tokens per (batch, head) in memory
+int64_t image_tokens(const aa_desc* d) { return windowed(d) ? (int64_t)d->image_h * d->image_w : (int64_t)d->N; }
+
+aa_status check_desc(const aa_desc* d, bool need_grid, bool need_agent_grid, bool windows_ok = true) {
   if (!d) return AA_ERR_NULL;
   if (d->dtype != AA_F32 && d->dtype != AA_F16 && d->dtype != AA_BF16) return AA_ERR_DTYPE;
   if (d->batch <= 0 || d->heads <= 0 || d->N <= 0 || d->n <= 0 || d->d <= 0) return AA_ERR_SHAPE;
@@ -74,9 +87,16 @@ aa_status check_desc(const aa_desc* d, bool need_grid, bool need_agent_grid) {
   if (has_grid && (int64_t)d->grid_h * d->grid_w != d->N) return AA_ERR_SHAPE;
   if (has_agrid && (int64_t)d->agent_h * d->agent_w != d->n) return AA_ERR_SHAPE;
   if (need_grid && !has_grid) return AA_ERR_SHAPE;
+  if (d->image_h < 0 || d->image_w < 0) return AA_ERR_SHAPE;
+  if (d->image_h > 0 || d->image_w > 0) {      // windows: the grid is one window of the image
+    if (!has_grid || d->image_h <= 0 || d->image_w <= 0) return AA_ERR_SHAPE;
+    if (d->image_h % d->grid_h != 0 || d->image_w % d->grid_w != 0) return AA_ERR_SHAPE;
+    if (d->image_h > 65535 || d->image_w > 65535) return AA_ERR_UNSUPPORTED;
+    if (windowed(d) && !windows_ok) return AA_ERR_UNSUPPORTED;
+  }
   if (need_agent_grid && !has_agrid) return AA_ERR_POOL;
   if (need_agent_grid && has_grid && (d->agent_h > d->grid_h || d->agent_w > d->grid_w)) return AA_ERR_POOL;
-  const int64_t units = (int64_t)d->batch * d->heads;
+  const int64_t units = units_of(d);
   if (units > 65535) return AA_ERR_UNSUPPORTED;
   if (d->d > kMaxD) return AA_ERR_UNSUPPORTED;
   if (d->grid_h > 65535 || d->grid_w > 65535) return AA_ERR_UNSUPPORTED;   // 32-bit window arithmetic
@@ -107,7 +127,7 @@ aa_status check_params(const aa_params* p) {
 }
 
 int choose_splits(const aa_desc* d) {
-  const int64_t units = (int64_t)d->batch * d->heads;
+  const int64_t units = units_of(d);
   int S = d->n_splits;
   if (S <= 0) {
     // generic path: one wave per (unit, agent, split); aim for a few thousand waves
@@ -128,7 +148,7 @@ int choose_splits(const aa_desc* d) {
 // Splits / chunks of the small-agent path.  An explicit n_splits forces the multi-kernel path
 // with that many splits (rounded so that every split is a non-empty multiple of 32 tokens).
 void plan_small(const aa_desc* d, Plan& pl) {
-  const int64_t units = (int64_t)d->batch * d->heads;
+  const int64_t units = units_of(d);
   int S = d->n_splits;
   pl.prefer_fused = (S <= 0);   // taken when the unit's Q rows fit in LDS, see run time check
   if (S <= 0) {
@@ -152,7 +172,7 @@ void plan_small(const aa_desc* d, Plan& pl) {
 // which is the unit the broadcast stages); splits chosen for about 512 blocks, at least 512 tokens per split
 // (the split partials stay small beside K and V), split length a multiple of the 64-token K/V tile.
 void plan_large(const aa_desc* d, Plan& pl) {
-  const int64_t units = (int64_t)d->batch * d->heads;
+  const int64_t units = units_of(d);
   const int waves = d->n <= 64 ? 4 : 8;          // the staging copies want at least 256 threads
   pl.waves_large = waves;
   const int apb = waves * 16;
@@ -216,9 +236,11 @@ Problem make_problem(const aa_desc* d, const aa_params* p);
 bool large_supported(const Problem& pr);
 int padded_width(int d);
 
+constexpr size_t kNoStage = ~(size_t)0;
+
 Plan make_plan(const aa_desc* d, const aa_params* params = nullptr) {
   Plan pl{};
-  const size_t units = (size_t)d->batch * d->heads;
+  const size_t units = (size_t)units_of(d);
   pl.S = choose_splits(d);
   plan_small(d, pl);
   plan_large(d, pl);
@@ -253,6 +275,13 @@ Plan make_plan(const aa_desc* d, const aa_params* params = nullptr) {
     pl.off_pm = off, off += align_up(units * pl.agent_blocks * pl.S_large * pl.waves_large * 16 * sizeof(float));
     pl.off_pl = off, off += align_up(units * pl.agent_blocks * pl.S_large * pl.waves_large * 16 * sizeof(float));
   }
+  // windows that the kernel family of this shape does not address in place (see agent_attn_fwd)
+  pl.off_stage = kNoStage;
+  if (windowed(d) && d->dtype != AA_F32 && !(pl.prefer_fused && aa::small_fused_supported(shape))) {
+    pl.stage_bytes = align_up(units * d->N * d->d * elem_size(d->dtype));
+    pl.off_stage = off;
+    off += 4 * pl.stage_bytes;
+  }
   pl.bias = plan_bias(d, params);
   pl.off_bias = off;
   if (!(params && params->bias_tables)) off += pl.bias.total;      // prepared tables need no room here
@@ -264,23 +293,31 @@ aa::Layout layout_of(const aa_desc* d) {
   aa::Layout L;
   const bool dense_in = d->stride_b == 0 && d->stride_h == 0 && d->stride_n == 0;
   const bool dense_out = d->out_stride_b == 0 && d->out_stride_h == 0 && d->out_stride_n == 0;
+  const long long tokens = image_tokens(d);
   L.sn = dense_in ? d->d : (int)d->stride_n;
-  L.sh = dense_in ? (long long)d->N * d->d : d->stride_h;
-  L.sb = dense_in ? (long long)d->N * d->d * d->heads : d->stride_b;
+  L.sh = dense_in ? tokens * d->d : d->stride_h;
+  L.sb = dense_in ? tokens * d->d * d->heads : d->stride_b;
   L.on = dense_out ? d->d : (int)d->out_stride_n;
-  L.oh = dense_out ? (long long)d->N * d->d : d->out_stride_h;
-  L.ob = dense_out ? (long long)d->N * d->d * d->heads : d->out_stride_b;
+  L.oh = dense_out ? tokens * d->d : d->out_stride_h;
+  L.ob = dense_out ? tokens * d->d * d->heads : d->out_stride_b;
+  if (windowed(d)) {
+    L.line = d->image_w;
+    L.wh = d->grid_h;
+    L.ww = d->grid_w;
+    L.wxn = d->image_w / d->grid_w;
+    L.nwin = (int)windows_of(d);
+  }
   return L;
 }
 bool dense_layout(const aa_desc* d) {
-  return d->stride_b == 0 && d->stride_h == 0 && d->stride_n == 0 && d->out_stride_b == 0 && d->out_stride_h == 0 &&
+  return !windowed(d) && d->stride_b == 0 && d->stride_h == 0 && d->stride_n == 0 && d->out_stride_b == 0 && d->out_stride_h == 0 &&
          d->out_stride_n == 0;
 }
 // bytes from the base pointer to one past the last element of a token tensor
 size_t extent_bytes(const aa_desc* d, bool out) {
   const aa::Layout L = layout_of(d);
   const size_t sb = out ? L.ob : L.sb, sh = out ? L.oh : L.sh, sn = out ? L.on : L.sn;
-  return ((size_t)(d->batch - 1) * sb + (size_t)(d->heads - 1) * sh + (size_t)(d->N - 1) * sn + (size_t)d->d) *
+  return ((size_t)(d->batch - 1) * sb + (size_t)(d->heads - 1) * sh + (size_t)(image_tokens(d) - 1) * sn + (size_t)d->d) *
          elem_size(d->dtype);
 }
 // the 16-byte vector accesses of the MFMA kernels need every stride to be a multiple of 8 elements
@@ -290,7 +327,7 @@ bool layout_vectorizable(const aa::Layout& L) {
 
 Problem make_problem(const aa_desc* d, const aa_params* p) {
   Problem pr{};
-  pr.units = d->batch * d->heads;
+  pr.units = (int)units_of(d);
   pr.heads = d->heads;
   pr.N = d->N;
   pr.n = d->n;
@@ -608,12 +645,11 @@ aa_status agent_attn_resize_bias(int32_t heads, int32_t grid_h, int32_t grid_w, 
 
 uint64_t agent_attn_flops(const aa_desc* desc) {
   if (check_desc(desc, false, false) != AA_OK) return 0;
-  return 8ull * (uint64_t)desc->N * (uint64_t)desc->n * (uint64_t)desc->d * (uint64_t)desc->batch *
-         (uint64_t)desc->heads;
+  return 8ull * (uint64_t)desc->N * (uint64_t)desc->n * (uint64_t)desc->d * (uint64_t)units_of(desc);
 }
 
 aa_status agent_pool_fwd(const aa_desc* desc, const void* Q, void* A_out, void* hip_stream) {
-  aa_status st = check_desc(desc, true, true);
+  aa_status st = check_desc(desc, true, true, false);
   if (st != AA_OK) return st;
   if (!Q || !A_out) return AA_ERR_NULL;
   const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
@@ -626,7 +662,7 @@ aa_status agent_aggregate_fwd(const aa_desc* desc, const void* A, const void* K,
                               const aa_params* params, void* workspace, size_t workspace_bytes, float* VA_out,
                               void* hip_stream) {
   const bool bias1 = params && (params->b1_col || params->b1_row || params->b1_blk);
-  aa_status st = check_desc(desc, bias1, false);
+  aa_status st = check_desc(desc, bias1, false, false);
   if (st != AA_OK) return st;
   st = check_params(params);
   if (st != AA_OK) return st;
@@ -653,7 +689,7 @@ aa_status agent_broadcast_fwd(const aa_desc* desc, const void* Q, const void* A,
                               const aa_params* params, void* out, void* hip_stream) {
   const bool bias2 = params && (params->b2_col || params->b2_row || params->b2_blk);
   const bool dwc = params && params->dwc_w;
-  aa_status st = check_desc(desc, bias2 || dwc, false);
+  aa_status st = check_desc(desc, bias2 || dwc, false, false);
   if (st != AA_OK) return st;
   st = check_params(params);
   if (st != AA_OK) return st;
@@ -676,31 +712,12 @@ aa_status agent_broadcast_fwd(const aa_desc* desc, const void* Q, const void* A,
   return run_broadcast(pr, Q, A, nullptr, VA, V, out, pl, (hipStream_t)hip_stream);
 }
 
-aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, const void* V, const void* A,
-                         const aa_params* params, void* workspace, size_t workspace_bytes, void* out,
-                         void* hip_stream) {
-  const bool pooling = (A == nullptr);
-  aa_status st = check_desc(desc, pooling || params_use_grid(params), pooling);
-  if (st == AA_ERR_SHAPE && pooling && desc && desc->grid_h == 0 && desc->grid_w == 0) st = AA_ERR_POOL;
-  if (st != AA_OK) return st;
-  st = check_params(params);
-  if (st != AA_OK) return st;
-  if (!Q || !K || !V || !out) return AA_ERR_NULL;
-  const Plan pl = make_plan(desc, params);
-  st = check_workspace(workspace, workspace_bytes, pl);
-  if (st != AA_OK) return st;
-  const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
-  const size_t big = extent_bytes(desc, false), obig = extent_bytes(desc, true);
-  if (overlaps(out, obig, Q, big) || overlaps(out, obig, K, big) || overlaps(out, obig, V, big) ||
-      overlaps(out, obig, A, units * desc->n * desc->d * es) || overlaps(out, obig, workspace, workspace_bytes) ||
-      overlaps(workspace, workspace_bytes, Q, big) || overlaps(workspace, workspace_bytes, K, big) ||
-      overlaps(workspace, workspace_bytes, V, big) ||
-      overlaps(workspace, workspace_bytes, A, units * desc->n * desc->d * es))
-    return AA_ERR_ALIAS;
-
-  Problem pr = make_problem(desc, params);
-  hipStream_t stream = (hipStream_t)hip_stream;
+// The forward pass proper on validated arguments: picks the kernel family and launches it.
+static aa_status forward_core(Problem pr, const Plan& pl, const aa_params* params, const void* Q, const void* K,
+                              const void* V, const void* A, void* workspace, void* out, hipStream_t stream) {
   char* ws = (char*)workspace;
+  const bool pooling = (A == nullptr);
+  aa_status st;
   st = prepare_dense_bias(pr, pl, params, workspace, use_small(pr, {Q, K, V, A, out}) || use_large(pr, {Q, K, V, A, out}),
                           stream);
   if (st != AA_OK) return st;
@@ -734,13 +751,63 @@ aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, cons
   return run_broadcast(pr, Q, agents, agents_lo, VA, V, out, pl, stream);
 }
 
+aa_status agent_attn_fwd(const aa_desc* desc, const void* Q, const void* K, const void* V, const void* A,
+                         const aa_params* params, void* workspace, size_t workspace_bytes, void* out,
+                         void* hip_stream) {
+  const bool pooling = (A == nullptr);
+  aa_status st = check_desc(desc, pooling || params_use_grid(params), pooling);
+  if (st == AA_ERR_SHAPE && pooling && desc && desc->grid_h == 0 && desc->grid_w == 0) st = AA_ERR_POOL;
+  if (st != AA_OK) return st;
+  st = check_params(params);
+  if (st != AA_OK) return st;
+  if (!Q || !K || !V || !out) return AA_ERR_NULL;
+  const Plan pl = make_plan(desc, params);
+  st = check_workspace(workspace, workspace_bytes, pl);
+  if (st != AA_OK) return st;
+  const size_t es = elem_size(desc->dtype), units = (size_t)units_of(desc);
+  const size_t big = extent_bytes(desc, false), obig = extent_bytes(desc, true);
+  if (overlaps(out, obig, Q, big) || overlaps(out, obig, K, big) || overlaps(out, obig, V, big) ||
+      overlaps(out, obig, A, units * desc->n * desc->d * es) || overlaps(out, obig, workspace, workspace_bytes) ||
+      overlaps(workspace, workspace_bytes, Q, big) || overlaps(workspace, workspace_bytes, K, big) ||
+      overlaps(workspace, workspace_bytes, V, big) ||
+      overlaps(workspace, workspace_bytes, A, units * desc->n * desc->d * es))
+    return AA_ERR_ALIAS;
+
+  Problem pr = make_problem(desc, params);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (pr.lay.line != 0) {
+    // Windows (Sec. 5.5).  The fp32 / fallback kernels and the one-block-per-unit kernel address them in place;
+    // the other 16-bit families run on window-major copies made here and their result is scattered back.
+    const bool mfma = use_small(pr, {Q, K, V, A, out}) || use_large(pr, {Q, K, V, A, out});
+    const bool fused = pl.prefer_fused && aa::small_fused_supported(pr) && use_small(pr, {Q, K, V, A, out});
+    if (mfma && !fused) {
+      if (pl.off_stage == kNoStage) return AA_ERR_UNSUPPORTED;      // cannot happen: the plan saw the same shape
+      char* stage = (char*)workspace + pl.off_stage;
+      const size_t sb = pl.stage_bytes;
+      AA_HIP(aa::launch_restride(pr, true, false, Q, stage, stream));
+      AA_HIP(aa::launch_restride(pr, true, false, K, stage + sb, stream));
+      AA_HIP(aa::launch_restride(pr, true, false, V, stage + 2 * sb, stream));
+      Problem inner = pr;
+      inner.lay = aa::Layout{};
+      inner.lay.sn = inner.lay.on = pr.d;
+      inner.lay.sh = inner.lay.oh = (long long)pr.N * pr.d;
+      inner.lay.sb = inner.lay.ob = (long long)pr.N * pr.d * pr.heads;
+      st = forward_core(inner, pl, params, stage, stage + sb, stage + 2 * sb, A, workspace, stage + 3 * sb, stream);
+      if (st != AA_OK) return st;
+      AA_HIP(aa::launch_restride(pr, false, true, stage + 3 * sb, out, stream));
+      return AA_OK;
+    }
+  }
+  return forward_core(pr, pl, params, Q, K, V, A, workspace, out, stream);
+}
+
 // Backward workspace: the pooled agents in the element type (256-byte aligned), then the fp32 scratch, then,
 // for strided tensors, seven dense staging copies (Q, K, V, dO in; dQ, dK, dV out).
 static size_t bwd_agents_bytes(const aa_desc* d) {
-  return align_up((size_t)d->batch * d->heads * d->n * d->d * elem_size(d->dtype));
+  return align_up((size_t)units_of(d) * d->n * d->d * elem_size(d->dtype));
 }
 static size_t bwd_stage_bytes(const aa_desc* d) {
-  return align_up((size_t)d->batch * d->heads * d->N * d->d * elem_size(d->dtype));
+  return align_up((size_t)units_of(d) * d->N * d->d * elem_size(d->dtype));
 }
 
 size_t agent_attn_bwd_workspace_bytes(const aa_desc* desc, const aa_params* params) {
@@ -776,7 +843,7 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
   }
   const size_t need = agent_attn_bwd_workspace_bytes(desc, params);
   if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < need) return AA_ERR_WORKSPACE;
-  const size_t es = elem_size(desc->dtype), units = (size_t)desc->batch * desc->heads;
+  const size_t es = elem_size(desc->dtype), units = (size_t)units_of(desc);
   // Q, K, V and their gradients use the input strides, dO the output strides (it has the layout of out)
   const size_t big = extent_bytes(desc, false), obig = extent_bytes(desc, true);
   const size_t small = units * desc->n * desc->d * es;
@@ -823,6 +890,8 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
     sdV = dV = stage + 6 * sb;
     aa_desc dd = *desc;
     dd.stride_b = dd.stride_h = dd.stride_n = dd.out_stride_b = dd.out_stride_h = dd.out_stride_n = 0;
+    dd.batch = (int32_t)(units_of(desc) / desc->heads);      // windows become batch entries of the dense copies
+    dd.image_h = dd.image_w = 0;
     pr.lay = layout_of(&dd);
   }
   const void* agents = A;
@@ -938,6 +1007,11 @@ size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, siz
   } else {
     len = snprintf(buf, buf_len, "%saggregate_generic(S=%d) + %sbroadcast_generic", agents_given ? "" : "pool_generic + ",
                    pl.S, pl.S > 1 ? "merge_generic + " : "");
+  }
+  if (len >= 0 && (size_t)len < buf_len && windowed(desc)) {
+    const int more = snprintf(buf + len, buf_len - (size_t)len, "; %d windows per image, %s", (int)windows_of(desc),
+                              pl.off_stage == kNoStage ? "read in place" : "staged as window-major copies");
+    if (more > 0) len += more;
   }
   if (len < 0) return 0;
   return (size_t)len < buf_len ? (size_t)len : buf_len - 1;

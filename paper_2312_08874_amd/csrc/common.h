@@ -37,16 +37,27 @@ struct ElemBF16 {
 // The channel stride is always 1.  A, V_A and the workspace are dense.
 // ---------------------------------------------------------------------------
 struct Layout {
-  long long sb, sh;      // batch and head strides of Q, K, V
-  int sn;                // token (row) stride of Q, K, V
-  long long ob, oh;      // the same for out
-  int on;
-  __host__ __device__ size_t in_unit(int u, int heads) const {
-    return (size_t)(u / heads) * (size_t)sb + (size_t)(u % heads) * (size_t)sh;
+  long long sb = 0, sh = 0;      // batch and head strides of Q, K, V
+  int sn = 0;                    // token (row) stride of Q, K, V
+  long long ob = 0, oh = 0;      // the same for out
+  int on = 0;
+  // Window mode (Sec. 5.5, window-size ablation: agent attention inside the windows of a Swin-style model): the tensors are
+  // images of `line` tokens per image row, cut into nwin = (rows of windows) * wxn windows of wh x ww
+  // tokens.  A unit is then one (batch, window, head), u = (b * nwin + window) * heads + head, and token t
+  // of the unit is pixel (t / ww, t % ww) of its window.  line == 0: no windows, tokens are consecutive rows.
+  int line = 0, nwin = 1, wxn = 1, wh = 0, ww = 0;
+  __host__ __device__ size_t unit_base(int u, int heads, long long b_stride, long long h_stride, int n_stride) const {
+    const int bw = u / heads, hd = u - bw * heads;
+    if (line == 0) return (size_t)bw * (size_t)b_stride + (size_t)hd * (size_t)h_stride;
+    const int b = bw / nwin, win = bw - b * nwin, wy = win / wxn, wx = win - wy * wxn;
+    return (size_t)b * (size_t)b_stride + (size_t)hd * (size_t)h_stride +
+           ((size_t)wy * wh * line + (size_t)wx * ww) * (size_t)n_stride;
   }
-  __host__ __device__ size_t out_unit(int u, int heads) const {
-    return (size_t)(u / heads) * (size_t)ob + (size_t)(u % heads) * (size_t)oh;
-  }
+  __host__ __device__ size_t in_unit(int u, int heads) const { return unit_base(u, heads, sb, sh, sn); }
+  __host__ __device__ size_t out_unit(int u, int heads) const { return unit_base(u, heads, ob, oh, on); }
+  // row index (in units of the token stride) of token t of a unit, and of pixel (y, x) of its gw-wide grid
+  __host__ __device__ size_t tok(int t) const { return line == 0 ? (size_t)t : (size_t)(t / ww) * line + (size_t)(t % ww); }
+  __host__ __device__ int pitch(int gw) const { return line == 0 ? gw : line; }
 };
 
 // ---------------------------------------------------------------------------

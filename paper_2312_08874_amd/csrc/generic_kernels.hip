@@ -28,7 +28,7 @@ __global__ __launch_bounds__(64) void pool_generic_kernel(const typename E::T* _
   for (int c = threadIdx.x; c < d; c += 64) {
     float acc = 0.0f;
     for (int y = y0; y < y1; ++y)
-      for (int x = x0; x < x1; ++x) acc += E::to_f32(q[((size_t)y * gw + x) * lay.sn + c]);
+      for (int x = x0; x < x1; ++x) acc += E::to_f32(q[((size_t)y * lay.pitch(gw) + x) * lay.sn + c]);
     const float mean = acc * inv;
     const typename E::T hi = E::from_f32(mean);
     A[((size_t)u * n + a) * d + c] = hi;
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void pool_chunk_kernel(const uint16_t* __restr
     }
   };
   for (int y = y0; y < y1; ++y) {
-    const uint16_t* row = q + (size_t)y * gw * lay.sn;
+    const uint16_t* row = q + (size_t)y * lay.pitch(gw) * lay.sn;
     int x = x0;
     for (; x + 4 <= x1; x += 4) {
       u32x4 v[4];
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
     const bool valid = active && t < t1;
     float sc = -INFINITY;
     if (valid) {
-      const typename E::T* kr = Ku + (size_t)t * lay.sn;
+      const typename E::T* kr = Ku + lay.tok(t) * lay.sn;
       float dot = 0.0f;
 #pragma unroll 8
       for (int c = 0; c < d; ++c) dot += a_row[c] * E::to_f32(kr[c]);
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(64 * kWaves) void aggregate_generic_kernel(
         if (c < d) {
           float v = acc[k] * alpha;
 #pragma unroll 8
-          for (int j = 0; j < cnt; ++j) v += p_sh[j] * E::to_f32(Vu[(size_t)(tb + j) * lay.sn + c]);
+          for (int j = 0; j < cnt; ++j) v += p_sh[j] * E::to_f32(Vu[lay.tok(tb + j) * lay.sn + c]);
           acc[k] = v;
         }
       }
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
   const int y = gw > 0 ? i / gw : 0, x = gw > 0 ? i % gw : 0;
 
   if (active)
-    for (int c = lane; c < d; c += 64) q_row[c] = E::to_f32(Q[lay.in_unit(u, heads) + (size_t)i * lay.sn + c]);
+    for (int c = lane; c < d; c += 64) q_row[c] = E::to_f32(Q[lay.in_unit(u, heads) + lay.tok(i) * lay.sn + c]);
   __syncthreads();
 
   float mx = -INFINITY;
@@ -297,12 +297,12 @@ __global__ __launch_bounds__(64 * kWaves) void broadcast_generic_kernel(
           for (int kx = -1; kx <= 1; ++kx) {
             const int yy = y + ky, xx = x + kx;
             if (yy >= 0 && yy < gh && xx >= 0 && xx < gw)
-              conv += w9[(ky + 1) * 3 + (kx + 1)] * E::to_f32(V[lay.in_unit(u, heads) + ((size_t)yy * gw + xx) * lay.sn + c]);
+              conv += w9[(ky + 1) * 3 + (kx + 1)] * E::to_f32(V[lay.in_unit(u, heads) + ((size_t)yy * lay.pitch(gw) + xx) * lay.sn + c]);
           }
         o += conv;
       }
-      if (vk != 0.0f) o += vk * E::to_f32(V[lay.in_unit(u, heads) + (size_t)i * lay.sn + c]);
-      O[lay.out_unit(u, heads) + (size_t)i * lay.on + c] = E::from_f32(o);
+      if (vk != 0.0f) o += vk * E::to_f32(V[lay.in_unit(u, heads) + lay.tok(i) * lay.sn + c]);
+      O[lay.out_unit(u, heads) + lay.tok(i) * lay.on + c] = E::from_f32(o);
     }
   }
 }
@@ -492,17 +492,24 @@ hipError_t launch_bias_half(const Problem& p, float* half1, float* rows1, float*
 
 // ---------------------------------------------------------------------------
 // Dense <-> strided copies of a [units][N][d] token tensor (the backward pass works on dense copies of
-// strided tensors).  T only carries the element size.  thread = one element.
+// strided tensors; the forward pass on dense copies of the windows of an image when the kernel family that
+// serves the shape does not address windows in place).  T only carries the size of what a thread moves:
+// one element, or a 16-byte piece of 8 16-bit elements (d and every stride a multiple of 8 then).
 // ---------------------------------------------------------------------------
-template <class T, bool TO_DENSE>
+typedef uint32_t piece16_t __attribute__((ext_vector_type(4)));
+
+template <class T, int EPT, bool TO_DENSE>
 __global__ __launch_bounds__(256) void restride_kernel(const T* __restrict__ src, T* __restrict__ dst, int N, int d,
-                                                       int heads, long long sb, long long sh, int sn, size_t count) {
+                                                       int heads, Layout lay, bool out_layout, size_t count) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= count) return;
-  const int c = (int)(i % d);
-  const size_t row = i / d;
+  const int dp = d / EPT;                      // pieces per row
+  const int c = (int)(i % dp);
+  const size_t row = i / dp;
   const int t = (int)(row % N), u = (int)(row / N);
-  const size_t strided = (size_t)(u / heads) * (size_t)sb + (size_t)(u % heads) * (size_t)sh + (size_t)t * sn + c;
+  const size_t strided_elems = out_layout ? lay.out_unit(u, heads) + lay.tok(t) * lay.on
+                                          : lay.in_unit(u, heads) + lay.tok(t) * lay.sn;
+  const size_t strided = strided_elems / EPT + c;
   if (TO_DENSE)
     dst[i] = src[strided];
   else
@@ -510,17 +517,22 @@ __global__ __launch_bounds__(256) void restride_kernel(const T* __restrict__ src
 }
 
 hipError_t launch_restride(const Problem& p, bool to_dense, bool out_layout, const void* src, void* dst, hipStream_t st) {
-  const size_t count = (size_t)p.units * p.N * p.d;
-  const long long sb = out_layout ? p.lay.ob : p.lay.sb, sh = out_layout ? p.lay.oh : p.lay.sh;
-  const int sn = out_layout ? p.lay.on : p.lay.sn;
+  const Layout& L = p.lay;
+  const bool wide = p.dtype != 0 && p.d % 8 == 0 && L.sb % 8 == 0 && L.sh % 8 == 0 && L.sn % 8 == 0 && L.ob % 8 == 0 &&
+                    L.oh % 8 == 0 && L.on % 8 == 0 && ((uintptr_t)src & 15) == 0 && ((uintptr_t)dst & 15) == 0;
+  const size_t count = (size_t)p.units * p.N * p.d / (wide ? 8 : 1);
   const dim3 grid((unsigned)((count + 255) / 256));
-  if (p.dtype == 0) {
-    if (to_dense) restride_kernel<float, true><<<grid, dim3(256), 0, st>>>((const float*)src, (float*)dst, p.N, p.d, p.heads, sb, sh, sn, count);
-    else restride_kernel<float, false><<<grid, dim3(256), 0, st>>>((const float*)src, (float*)dst, p.N, p.d, p.heads, sb, sh, sn, count);
-  } else {
-    if (to_dense) restride_kernel<uint16_t, true><<<grid, dim3(256), 0, st>>>((const uint16_t*)src, (uint16_t*)dst, p.N, p.d, p.heads, sb, sh, sn, count);
-    else restride_kernel<uint16_t, false><<<grid, dim3(256), 0, st>>>((const uint16_t*)src, (uint16_t*)dst, p.N, p.d, p.heads, sb, sh, sn, count);
-  }
+#define AA_RESTRIDE(T, EPT)                                                                                              \
+  do {                                                                                                                   \
+    if (to_dense)                                                                                                        \
+      restride_kernel<T, EPT, true><<<grid, dim3(256), 0, st>>>((const T*)src, (T*)dst, p.N, p.d, p.heads, L, out_layout, count); \
+    else                                                                                                                 \
+      restride_kernel<T, EPT, false><<<grid, dim3(256), 0, st>>>((const T*)src, (T*)dst, p.N, p.d, p.heads, L, out_layout, count); \
+  } while (0)
+  if (p.dtype == 0) AA_RESTRIDE(float, 1);
+  else if (wide) AA_RESTRIDE(piece16_t, 8);
+  else AA_RESTRIDE(uint16_t, 1);
+#undef AA_RESTRIDE
   return hipGetLastError();
 }
 

@@ -29,8 +29,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    # int32 x10, float x3, int32, int64 x6 -> 104 bytes; params: 6 ptr, 2 int32, 3 ptr -> 80 bytes
-    assert ctypes.sizeof(binding.aa_desc) == 104
+    # int32 x10, float x3, int32, int64 x6, int32 x2 -> 112 bytes; params: 6 ptr, 2 int32, 3 ptr -> 80 bytes
+    assert ctypes.sizeof(binding.aa_desc) == 112
+    assert binding.aa_desc.image_h.offset == 104 and binding.aa_desc.image_w.offset == 108
     assert ctypes.sizeof(binding.aa_params) == 80
 
 
@@ -41,6 +42,22 @@ def test_flops_follow_the_cost_model():
         macs = 2 * n * N * C + 2 * N * n * C
         assert binding.flops(make_desc(B, H, N, n, d, binding.AA_BF16)) == 2 * macs * B
     assert binding.flops(make_desc(1, 1, 0, 4, 4, binding.AA_F32)) == 0
+
+
+def test_windows_in_the_descriptor_are_validated_on_the_host():
+    """image_h x image_w cut into grid-sized windows: units and workspace scale with the number of windows."""
+    one = make_desc(2, 3, 49, 9, 32, binding.AA_BF16, (7, 7), (3, 3))
+    win = make_desc(2, 3, 49, 9, 32, binding.AA_BF16, (7, 7), (3, 3), image=(56, 56))
+    assert binding.flops(win) == 64 * binding.flops(one)
+    assert binding.workspace_bytes(win) > binding.workspace_bytes(one) > 0
+    assert "64 windows per image" in binding.plan_str(win)
+    same = make_desc(2, 3, 49, 9, 32, binding.AA_BF16, (7, 7), (3, 3), image=(7, 7))      # one window = no windows
+    assert binding.workspace_bytes(same) == binding.workspace_bytes(one)
+    for image in ((56, 55), (50, 56), (56, 0), (-7, 7), (70000 * 7, 7)):
+        assert binding.workspace_bytes(make_desc(2, 3, 49, 9, 32, binding.AA_BF16, (7, 7), (3, 3), image=image)) == 0
+    assert binding.workspace_bytes(make_desc(2, 3, 49, 9, 32, binding.AA_BF16, None, None, image=(56, 56))) == 0
+    # too many (batch, window, head) units for the launch grid
+    assert binding.workspace_bytes(make_desc(64, 8, 49, 9, 32, binding.AA_BF16, (7, 7), (3, 3), image=(112, 112))) == 0
 
 
 def test_workspace_query():

@@ -166,6 +166,36 @@ def test_backward_is_deterministic_and_ignores_workspace(aa):
         assert torch.equal(a[k], b[k])
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_windows_in_descriptor(aa, dtype):
+    """Windows named in the descriptor (Sec. 5.5): the gradients of the image tensors are, bit for bit, those
+    of the same windows handed over as a batch (a case the tests above hold against the oracle)."""
+    import torch
+    batch, heads, image, window, agrid, d = 2, 2, (12, 18), (6, 6), (3, 3), 24 if dtype == "f32" else 32
+    (Y, X), (wh, ww) = image, window
+    nwin = (Y // wh) * (X // ww)
+    params = util.params_to_device(inputs.make_module_params(heads, 9, d, window, blk=(3, 2), index=21))
+
+    def part(x):      # [B,H,Y*X,d] -> [B*windows,H,wh*ww,d]
+        v = x.reshape(batch, heads, Y // wh, wh, X // ww, ww, d)
+        return v.permute(0, 2, 4, 1, 3, 5, 6).reshape(batch * nwin, heads, wh * ww, d).contiguous()
+
+    def unpart(x):
+        v = x.reshape(batch, Y // wh, X // ww, heads, wh, ww, d)
+        return v.permute(0, 3, 1, 4, 2, 5, 6).reshape(batch, heads, Y * X, d).contiguous()
+
+    img = [util.to_device(inputs.make_tensor((batch * heads, Y * X, d), stream=700 + i, dtype=dtype), dtype,
+                          (batch, heads, Y * X, d)) for i in range(4)]
+    a = aa.agent_attn_bwd(*img, grid=image, window=window, agent_grid=agrid, params=params, v_residual_k=0.05)
+    b = aa.agent_attn_bwd(*[part(x) for x in img], grid=window, agent_grid=agrid, params=params, v_residual_k=0.05)
+    for k in ("dQ", "dK", "dV"):
+        assert torch.equal(a[k], unpart(b[k])), k
+    for k in a:
+        if k not in ("dQ", "dK", "dV"):
+            assert torch.equal(a[k], b[k]), k
+    assert float(a["dQ"].float().abs().max()) > 0
+
+
 @pytest.mark.parametrize("seed", range(36))
 def test_backward_random_problems(aa, oracle, seed):
     """Seeded random shapes: both product paths (fp32 vector and MFMA, with padded score rows and ragged

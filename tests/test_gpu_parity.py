@@ -431,6 +431,103 @@ def test_forward_one_block_per_unit(aa, oracle, grid, agrid, d, dtype, module):
 
 
 # --------------------------------------------------------------------------
+# windows in the descriptor (Sec. 5.5, window-size ablation of Agent-Swin): the image tensors are handed over
+# as they are; the reference is the oracle on an explicitly partitioned copy, window by window
+# --------------------------------------------------------------------------
+def _partition(x, heads, image, window):
+    """[B*H, Y*X, d] image tensor -> [B*windows*H, wh*ww, d], units ordered (batch, window row-major, head)."""
+    (Y, X), (wh, ww) = image, window
+    BH, _, d = x.shape
+    v = x.reshape(BH // heads, heads, Y // wh, wh, X // ww, ww, d)
+    return np.ascontiguousarray(v.transpose(0, 2, 4, 1, 3, 5, 6)).reshape(-1, wh * ww, d)
+
+
+def _unpartition(o, batch, heads, image, window):
+    (Y, X), (wh, ww) = image, window
+    v = o.reshape(batch, Y // wh, X // ww, heads, wh, ww, o.shape[-1])
+    return np.ascontiguousarray(v.transpose(0, 3, 1, 4, 2, 5, 6)).reshape(batch * heads, Y * X, o.shape[-1])
+
+
+WINDOW_CASES = [
+    # name, image, window, agents, d, dtype, n_splits, token-major layout, kernel family the windows run on
+    ("7x7 one block", (56, 56), (7, 7), (3, 3), 32, "bf16", 0, False, "small_fused"),
+    ("14x14 one block", (56, 56), (14, 14), (7, 7), 32, "f16", 0, False, "small_fused"),
+    ("14x14 one block, token-major", (56, 56), (14, 14), (7, 7), 64, "bf16", 0, True, "small_fused"),
+    ("14x14 split", (56, 56), (14, 14), (7, 7), 32, "bf16", 2, False, "small_aggregate"),
+    ("28x28 many agents", (56, 56), (28, 28), (9, 9), 32, "f16", 0, False, "large_aggregate"),
+    ("28x28 many agents, token-major", (56, 28), (28, 28), (9, 9), 40, "bf16", 0, True, "large_aggregate"),
+    ("14x14 fp32", (28, 42), (14, 14), (7, 7), 24, "f32", 0, False, "generic"),
+    ("ragged windows fp32", (15, 20), (5, 4), (2, 3), 20, "f32", 0, True, "generic"),
+    ("whole image as one window", (14, 14), (14, 14), (7, 7), 32, "bf16", 0, False, "small_fused"),
+]
+
+
+@pytest.mark.parametrize("module", [False, True])
+@pytest.mark.parametrize("name,image,window,agrid,d,dtype,n_splits,token_major,family", WINDOW_CASES,
+                         ids=[c[0] for c in WINDOW_CASES])
+def test_forward_windows_in_descriptor(aa, oracle, name, image, window, agrid, d, dtype, n_splits, token_major, family,
+                                       module):
+    import dataclasses
+    import torch
+    batch, heads = 2, 3
+    (Y, X), (wh, ww) = image, window
+    nwin = (Y // wh) * (X // ww)
+    wl = dataclasses.replace(WL["tiny"], batch=batch * nwin, heads=heads, grid=window, agent_grid=agrid, d=d, dtype=dtype,
+                             index=13)
+    desc = aa.make_desc(batch, heads, wl.N, wl.n, d, {"f32": 0, "f16": 1, "bf16": 2}[dtype], window, agrid,
+                        n_splits=n_splits, image=image)
+    plan = aa.plan_str(desc)
+    assert family in plan, plan
+    img = {k: inputs.make_tensor((batch * heads, Y * X, d), stream=13 * 16 + 40 + i, dtype=dtype)
+           for i, k in enumerate(("Q", "K", "V"))}
+    t = {k: _partition(v, heads, image, window) for k, v in img.items()}
+    params = inputs.make_module_params(heads, wl.n, d, window, blk=(3, 2), index=13) if module else None
+    dev = {}
+    for k, v in img.items():
+        x = util.to_device(v, dtype, (batch, heads, Y * X, d))
+        if token_major:      # [B, Y*X, H, d] in memory, handed over as a [B, H, Y*X, d] view
+            x = x.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+            assert not x.is_contiguous()
+        dev[k] = x
+    out = torch.full_like(dev["Q"], float("nan"))
+    O = aa.agent_attn_fwd(dev["Q"], dev["K"], dev["V"], grid=image, window=window, agent_grid=agrid, n_splits=n_splits,
+                          params=util.params_to_device(params) if module else None, out=out)
+    ref = _unpartition(util.oracle_forward_units(oracle, wl, t, list(range(wl.units)), params=params), batch, heads,
+                       image, window)
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, dtype, "windows " + name,
+                       max_abs=None if dtype == "f32" else 1e-2 * max(1.0, float(np.abs(ref).max())))
+    # and what the same library gives for the partitioned copy handed over as a batch of windows (bit for bit
+    # where the windows run through the very same kernels)
+    part = {k: util.to_device(v, dtype, (batch * nwin, heads, wl.N, d)) for k, v in t.items()}
+    O2 = aa.agent_attn_fwd(part["Q"], part["K"], part["V"], grid=window, agent_grid=agrid, n_splits=n_splits,
+                           params=util.params_to_device(params) if module else None)
+    got2 = _unpartition(util.to_host64(O2).reshape(-1, wl.N, d), batch, heads, image, window)
+    got = util.to_host64(O).reshape(got2.shape)
+    if family == "small_fused":      # the in-place kernel may cut the tokens into fewer slices: same bar, other rounding
+        util.assert_parity(got, got2, dtype, "windows in place against a batch of windows",
+                           max_abs=1e-2 * max(1.0, float(np.abs(ref).max())))
+    else:
+        assert np.array_equal(got, got2)
+
+
+def test_windows_descriptor_errors(aa):
+    import ctypes
+    lib = aa.lib()
+    ok = aa.make_desc(1, 2, 49, 9, 32, 2, (7, 7), (3, 3), image=(56, 56))
+    assert lib.agent_attn_workspace_bytes(ctypes.byref(ok), None) > 0
+    for image in ((56, 55), (50, 56), (56, 0), (-7, 7)):      # not a whole number of windows, half given, negative
+        bad = aa.make_desc(1, 2, 49, 9, 32, 2, (7, 7), (3, 3), image=image)
+        assert lib.agent_attn_workspace_bytes(ctypes.byref(bad), None) == 0
+    nogrid = aa.make_desc(1, 2, 49, 9, 32, 2, None, None, image=(56, 56))
+    assert lib.agent_attn_workspace_bytes(ctypes.byref(nogrid), None) == 0
+    # the stage entry points do not serve windows
+    import torch
+    Q = torch.zeros(1, 2, 56 * 56, 32, dtype=torch.bfloat16, device="cuda")
+    A = torch.zeros(64, 2, 9, 32, dtype=torch.bfloat16, device="cuda")
+    assert lib.agent_pool_fwd(ctypes.byref(ok), Q.data_ptr(), A.data_ptr(), None) == -7      # AA_ERR_UNSUPPORTED
+
+
+# --------------------------------------------------------------------------
 # strided Q, K, V, out: views of token-major [B,N,H,d] tensors and of a fused [B,N,3,H,d] projection
 # output must give exactly the bits of the dense call, on every kernel family
 # --------------------------------------------------------------------------
