@@ -222,6 +222,10 @@ def _desc_from(Q, n, grid, agent_grid, same=(), out=None, **kw):
     for t in same:
         assert t is None or (tuple(t.shape) == tuple(Q.shape) and _strides_of(t) == st), \
             "Q, K, V must share one shape and one set of strides"
+        assert t is None or (t.dtype == Q.dtype and t.device == Q.device), "Q, K, V must share one dtype and one device"
+    if out is not None:
+        assert tuple(out.shape) == tuple(Q.shape) and out.dtype == Q.dtype and out.device == Q.device, \
+            "out / dO must have the shape, dtype and device of Q"
     ost = _strides_of(out) if out is not None else (0, 0, 0)
     window = kw.pop("window", None)
     if window is not None:      # Q is the whole image [B,H,grid_h*grid_w,d]; the attention runs per window
@@ -231,12 +235,35 @@ def _desc_from(Q, n, grid, agent_grid, same=(), out=None, **kw):
     return make_desc(B, H, N, n, d, _dtype_code(Q), grid, agent_grid, strides=st, out_strides=ost, **kw)
 
 
-def _workspace(desc, params, workspace):
+def _workspace(desc, params, workspace, stream=None, device=None):
+    """The caller's workspace, or a temporary one.  A temporary is allocated on the stream the kernels run on, so
+    that the caching allocator does not hand its memory to other work before they are done with it."""
     import torch
     need = workspace_bytes(desc, params)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        workspace = _alloc_bytes(max(need, 256), stream, device)
+    else:
+        assert workspace.is_cuda and workspace.is_contiguous() and (device is None or workspace.device == device)
     return workspace, need
+
+
+def _alloc_bytes(nbytes, stream, device):
+    import torch
+    device = "cuda" if device is None else device
+    if stream is None:
+        return torch.empty(nbytes, dtype=torch.uint8, device=device)
+    with torch.cuda.stream(stream):
+        return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def _check_agents(A, Q, n, what="A", dtype=None):
+    """A / VA: dense [B', H, n, d] (B' = batch, or batch * windows) in Q's dtype (or `dtype`) on Q's device."""
+    if A is None:
+        return
+    assert A.is_cuda and A.device == Q.device and A.dtype == (Q.dtype if dtype is None else dtype), \
+        what + " must be on Q's device in the expected dtype"
+    assert A.dim() == 4 and A.is_contiguous() and A.shape[1] == Q.shape[1] and A.shape[2] == n and \
+        A.shape[3] == Q.shape[3], what + " must be a dense [B,H,n,d] tensor"
 
 
 def agent_attn_fwd(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict | None = None, scale1=0.0,
@@ -252,7 +279,8 @@ def agent_attn_fwd(Q, K, V, A=None, *, grid=None, agent_grid=None, params: dict 
     desc = _desc_from(Q, n, grid, agent_grid, same=(K, V), out=out, scale1=scale1, scale2=scale2,
                       v_residual_k=v_residual_k, n_splits=n_splits, window=window)
     p = make_params(params)
-    workspace, need = _workspace(desc, p, workspace)
+    _check_agents(A, Q, n)
+    workspace, need = _workspace(desc, p, workspace, stream, Q.device)
     st = lib().agent_attn_fwd(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(A), _pp(p),
                               workspace.data_ptr(), workspace.numel() * workspace.element_size(), out.data_ptr(),
                               _stream(stream))
@@ -267,6 +295,7 @@ def agent_attn_fwd_static(Q, K, V, A=None, *, grid=None, agent_grid=None, params
     desc = _desc_from(Q, n, grid, agent_grid, same=(K, V), out=out, scale1=scale1, scale2=scale2,
                       v_residual_k=v_residual_k, n_splits=n_splits, window=window)
     p = make_params(params)
+    _check_agents(A, Q, n)
     st = lib().agent_attn_fwd_static(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(A), _pp(p),
                                      out.data_ptr(), _stream(stream))
     _check(st, "agent_attn_fwd_static")
@@ -281,6 +310,7 @@ def agent_attn_fwd_timed(Q, K, V, A=None, *, grid=None, agent_grid=None, params:
     desc = _desc_from(Q, n, grid, agent_grid, same=(K, V), out=out, scale1=scale1, scale2=scale2,
                       v_residual_k=v_residual_k, n_splits=n_splits, window=window)
     p = make_params(params)
+    _check_agents(A, Q, n)
     times = (aa_kernel_time * 16)()
     count = ctypes.c_int(0)
     st = lib().agent_attn_fwd_timed(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(A), _pp(p),
@@ -331,8 +361,9 @@ def agent_attn_bwd(Q, K, V, dO, A=None, *, grid=None, agent_grid=None, params: d
                       v_residual_k=v_residual_k, window=window)
     p = make_params(params)
     need = int(lib().agent_attn_bwd_workspace_bytes(ctypes.byref(desc), _pp(p)))
+    _check_agents(A, Q, n)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        workspace = _alloc_bytes(max(need, 256), stream, Q.device)
     out = {k: torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device) for k in ("dQ", "dK", "dV")}
     if A is not None:
         out["dA"] = torch.empty_like(A)
@@ -417,6 +448,7 @@ def agent_pool_fwd(Q, *, grid, agent_grid, out=None, stream=None):
     desc = _desc_from(Q, n, grid, agent_grid)
     if out is None:
         out = torch.empty((B, H, n, d), dtype=Q.dtype, device=Q.device)
+    _check_agents(out, Q, n, "A_out")
     _check(lib().agent_pool_fwd(ctypes.byref(desc), Q.data_ptr(), out.data_ptr(), _stream(stream)),
            "agent_pool_fwd")
     return out
@@ -429,9 +461,11 @@ def agent_aggregate_fwd(A, K, V, *, grid=None, params: dict | None = None, scale
     n = A.shape[2]
     desc = _desc_from(K, n, grid, None, same=(V,), scale1=scale1, n_splits=n_splits)
     p = make_params(params)
-    workspace, need = _workspace(desc, p, workspace)
+    _check_agents(A, K, n)
+    workspace, need = _workspace(desc, p, workspace, stream, K.device)
     if out is None:
         out = torch.empty((B, H, n, d), dtype=torch.float32, device=K.device)
+    _check_agents(out, K, n, "VA_out", torch.float32)
     st = lib().agent_aggregate_fwd(ctypes.byref(desc), A.data_ptr(), K.data_ptr(), V.data_ptr(), _pp(p),
                                    workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                    out.data_ptr(), _stream(stream))
@@ -446,6 +480,8 @@ def agent_broadcast_fwd(Q, A, VA, V=None, *, grid=None, params: dict | None = No
     if out is None:
         out = torch.empty_like(Q)
     desc = _desc_from(Q, n, grid, None, same=(V,), out=out, scale2=scale2, v_residual_k=v_residual_k)
+    _check_agents(A, Q, n)
+    _check_agents(VA, Q, n, "VA", torch.float32)
     p = make_params(params)
     st = lib().agent_broadcast_fwd(ctypes.byref(desc), Q.data_ptr(), A.data_ptr(), VA.data_ptr(), _ptr(V), _pp(p),
                                    out.data_ptr(), _stream(stream))

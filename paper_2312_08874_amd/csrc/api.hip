@@ -385,6 +385,15 @@ bool use_large(const Problem& pr, std::initializer_list<const void*> ptrs) {
   return true;
 }
 int padded_width(int d) { return d <= 32 ? 32 : (d <= 64 ? 64 : 128); }
+// One-launch fp32 kernel: 16-byte accesses on every tensor
+bool use_fused_f32(const Problem& pr, std::initializer_list<const void*> ptrs) {
+  const aa::Layout& L = pr.lay;
+  if (!aa::fused_f32_supported(pr)) return false;
+  if (L.sb % 4 || L.sh % 4 || L.sn % 4 || L.ob % 4 || L.oh % 4 || L.on % 4) return false;
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return false;
+  return true;
+}
 
 aa_status check_workspace(const void* ws, size_t bytes, const Plan& pl) {
   if (!ws || ((uintptr_t)ws % kAlign) != 0 || bytes < pl.total) return AA_ERR_WORKSPACE;
@@ -727,6 +736,10 @@ static aa_status forward_core(Problem pr, const Plan& pl, const aa_params* param
   }
   if (!aa::small_supported(pr) && use_large(pr, {Q, K, V, A, out}))
     return run_large_forward(pr, Q, K, V, A, workspace, pl, out, stream);
+  if (pl.prefer_fused && use_fused_f32(pr, {Q, K, V, A, out, pr.dwc_b})) {
+    AA_HIP(aa::launch_fused_f32(pr, Q, K, V, A, out, stream));
+    return AA_OK;
+  }
   // Pooled agents are kept in two element-type terms (rounded value + residual) so that the 16-bit rounding of
   // an average does not enter the scores; agents handed in are exact in the element type.
   const void* agents = A;
@@ -1004,6 +1017,8 @@ size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, siz
                    "large_agents(%s) + large_aggregate(S=%d, %d agents/block)%s + large_broadcast(%d tokens/block)",
                    agents_given ? "given" : "pooled", pl.S_large, pl.waves_large * 16,
                    pl.S_large > 1 ? " + large_merge" : "", 32 * pl.bcast_waves_large);
+  } else if (pl.prefer_fused && aa::fused_f32_supported(pr)) {
+    len = snprintf(buf, buf_len, "fused_f32");
   } else {
     len = snprintf(buf, buf_len, "%saggregate_generic(S=%d) + %sbroadcast_generic", agents_given ? "" : "pool_generic + ",
                    pl.S, pl.S > 1 ? "merge_generic + " : "");

@@ -48,6 +48,11 @@ hipError_t launch_resize_agent_axis(const float* src, float* dst, size_t outer, 
                                     int aw2, hipStream_t st);
 // dense <-> strided copy of a [units][N][d] token tensor in the problem's element type; the strided side
 // uses the input strides of p.lay, or its output strides (out_layout)
+// Whole fp32 forward pass in one launch, one block per unit, everything out of LDS (fp32 MFMA); for units that fit
+// (see fused_f32_supported).  Needs 16-byte aligned pointers and strides that are multiples of 4 elements.
+bool fused_f32_supported(const Problem& p);
+hipError_t launch_fused_f32(const Problem& p, const void* Q, const void* K, const void* V, const void* A, void* out,
+                            hipStream_t st);
 hipError_t launch_restride(const Problem& p, bool to_dense, bool out_layout, const void* src, void* dst, hipStream_t st);
 // the half-resized tables of BiasArgs (he = table rows per agent: blk_h0, or 1 without block components)
 size_t bias_half_floats(int heads, int n, int gw, int he);

@@ -173,7 +173,9 @@ def test_bias_tables_entry_points_validate_on_the_host():
 def test_plan_string_is_host_only():
     assert binding.plan_str(make_desc(64, 3, 196, 49, 64, binding.AA_BF16, (14, 14), (7, 7))) == "small_fused"
     assert "small_aggregate" in binding.plan_str(make_desc(32, 3, 3136, 49, 32, binding.AA_BF16, (56, 56), (7, 7)))
-    assert "generic" in binding.plan_str(make_desc(1, 1, 196, 49, 32, binding.AA_F32, (14, 14), (7, 7)))
+    assert binding.plan_str(make_desc(1, 1, 196, 49, 32, binding.AA_F32, (14, 14), (7, 7))) == "fused_f32"
+    assert "generic" in binding.plan_str(make_desc(1, 1, 196, 49, 32, binding.AA_F32, (14, 14), (7, 7), n_splits=2))
+    assert "generic" in binding.plan_str(make_desc(1, 1, 3136, 49, 32, binding.AA_F32, (56, 56), (7, 7)))
     assert binding.plan_str(make_desc(1, 1, 0, 49, 32, binding.AA_F32)) == ""
 
 

@@ -170,6 +170,23 @@ def test_forward_is_deterministic(aa):
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
+@pytest.mark.parametrize("grid,agrid,d", [((9, 11), (3, 4), 24), ((14, 14), (7, 7), 32), ((20, 20), (5, 5), 64)])
+def test_one_launch_fp32_kernel_is_deterministic(aa, grid, agrid, d):
+    """The one-launch fp32 kernel with several MFMA waves per SIMD: same bits on every run, pooled or given agents
+    (the softmax shift once depended on when a wave read its score registers)."""
+    import dataclasses
+    import torch
+    wl = dataclasses.replace(WL["tiny"], batch=2, heads=2, grid=grid, agent_grid=agrid, d=d, index=12)
+    assert aa.plan_str(aa.make_desc(wl.batch, wl.heads, wl.N, wl.n, d, 0, grid, agrid)) == "fused_f32"
+    dv = dev_qkv(wl, inputs.make_qkv(wl))
+    A = aa.agent_pool_fwd(dv["Q"], grid=grid, agent_grid=agrid)
+    first = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=grid, agent_grid=agrid)
+    first_given = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], A)
+    for _ in range(12):
+        assert torch.equal(first, aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=grid, agent_grid=agrid))
+        assert torch.equal(first_given, aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], A))
+
+
 def test_forward_ignores_workspace_contents(aa):
     import torch
     wl = small(WL["deit_t"], 2)
@@ -456,8 +473,10 @@ WINDOW_CASES = [
     ("14x14 split", (56, 56), (14, 14), (7, 7), 32, "bf16", 2, False, "small_aggregate"),
     ("28x28 many agents", (56, 56), (28, 28), (9, 9), 32, "f16", 0, False, "large_aggregate"),
     ("28x28 many agents, token-major", (56, 28), (28, 28), (9, 9), 40, "bf16", 0, True, "large_aggregate"),
-    ("14x14 fp32", (28, 42), (14, 14), (7, 7), 24, "f32", 0, False, "generic"),
-    ("ragged windows fp32", (15, 20), (5, 4), (2, 3), 20, "f32", 0, True, "generic"),
+    ("14x14 fp32", (28, 42), (14, 14), (7, 7), 24, "f32", 0, False, "fused_f32"),
+    ("14x14 fp32 split", (28, 42), (14, 14), (7, 7), 24, "f32", 2, False, "generic"),
+    ("ragged windows fp32", (15, 20), (5, 4), (2, 3), 20, "f32", 0, True, "fused_f32"),
+    ("ragged windows fp32, odd width", (15, 20), (5, 4), (2, 3), 18, "f32", 0, True, "generic"),
     ("whole image as one window", (14, 14), (14, 14), (7, 7), 32, "bf16", 0, False, "small_fused"),
 ]
 
@@ -503,7 +522,7 @@ def test_forward_windows_in_descriptor(aa, oracle, name, image, window, agrid, d
                            params=util.params_to_device(params) if module else None)
     got2 = _unpartition(util.to_host64(O2).reshape(-1, wl.N, d), batch, heads, image, window)
     got = util.to_host64(O).reshape(got2.shape)
-    if family == "small_fused":      # the in-place kernel may cut the tokens into fewer slices: same bar, other rounding
+    if family in ("small_fused", "fused_f32"):      # the in-place kernel may cut the tokens into fewer slices: same bar, other rounding
         util.assert_parity(got, got2, dtype, "windows in place against a batch of windows",
                            max_abs=1e-2 * max(1.0, float(np.abs(ref).max())))
     else:
@@ -525,6 +544,33 @@ def test_windows_descriptor_errors(aa):
     Q = torch.zeros(1, 2, 56 * 56, 32, dtype=torch.bfloat16, device="cuda")
     A = torch.zeros(64, 2, 9, 32, dtype=torch.bfloat16, device="cuda")
     assert lib.agent_pool_fwd(ctypes.byref(ok), Q.data_ptr(), A.data_ptr(), None) == -7      # AA_ERR_UNSUPPORTED
+
+
+def test_binding_rejects_mismatched_tensors(aa):
+    """The Python layer refuses tensors whose dtype, device, shape or density differ from what the descriptor
+    will say (the C ABI sees only pointers), before anything is launched."""
+    import torch
+    Q = torch.zeros(1, 2, 64, 32, dtype=torch.bfloat16, device="cuda")
+    A = torch.zeros(1, 2, 8, 32, dtype=torch.bfloat16, device="cuda")
+    VA = torch.zeros(1, 2, 8, 32, dtype=torch.float32, device="cuda")
+    with pytest.raises(AssertionError):
+        aa.agent_attn_fwd(Q, Q.float(), Q, A)                                  # K in another dtype
+    with pytest.raises(AssertionError):
+        aa.agent_attn_fwd(Q, Q, Q, A.float())                                  # A in another dtype
+    with pytest.raises(AssertionError):
+        aa.agent_attn_fwd(Q, Q, Q, torch.zeros(1, 2, 16, 32, dtype=torch.bfloat16, device="cuda")[:, :, ::2])   # A not dense
+    with pytest.raises(AssertionError):
+        aa.agent_attn_fwd(Q, Q, Q, A, out=torch.zeros(1, 2, 32, 32, dtype=torch.bfloat16, device="cuda"))
+    with pytest.raises(AssertionError):
+        aa.agent_broadcast_fwd(Q, A, VA.to(torch.bfloat16))                    # V_A must be fp32
+    with pytest.raises(AssertionError):
+        aa.agent_attn_bwd(Q, Q, Q, Q.float(), A)                               # dO in another dtype
+    # a temporary workspace for a call on a side stream is allocated on that stream
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    O = aa.agent_attn_fwd(Q, Q, Q, A, stream=side)
+    side.synchronize()
+    assert torch.equal(O, aa.agent_attn_fwd(Q, Q, Q, A))
 
 
 # --------------------------------------------------------------------------
