@@ -73,24 +73,49 @@ __global__ __launch_bounds__(64 * kF32Waves) void fused_f32_kernel(
   float* Ou = O + lay.out_unit(u, heads);
 
   // ---- Q, K, V rows -> LDS, zero padded to 16-token tiles and 16*DT channels (plus the 4 pad floats) ----
-  const int per = rows * C4;
-  for (int base = tid; base < 3 * per; base += 4 * blockDim.x) {
-    f32x4 v[4];
+  // Pooling with small uniform windows (Sec. 4.2): one thread per (agent, 4 channels) fetches the window's pieces
+  // itself, next to the bulk loads, so the agents are in LDS at the first barrier and no pooling pass follows.
+  constexpr int kEarlyWin = 4;
+  const int wh_u = gh / max(ah, 1), ww_u = gw / max(aw, 1);
+  const bool early_pool = !Agiven && gh == wh_u * ah && gw == ww_u * aw && wh_u * ww_u <= kEarlyWin &&
+                          16 * NAT * C4 <= (int)blockDim.x;
+  f32x4 pw[kEarlyWin];
+  if (early_pool && tid < 16 * NAT * C4) {
+    const int a = tid / C4, c4 = tid - a * C4;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int idx = base + k * blockDim.x;
-      v[k] = f32x4{0, 0, 0, 0};
-      if (idx < 3 * per) {
-        const int which = idx / per, rem = idx - which * per, row = rem / C4, c4 = rem - row * C4;
-        const float* src = which == 0 ? Qu : (which == 1 ? Ku : Vu);
-        if (row < N && 4 * c4 < d) v[k] = *(const f32x4*)(src + lay.tok(row) * lay.sn + 4 * c4);
+    for (int i = 0; i < kEarlyWin; ++i) pw[i] = f32x4{0, 0, 0, 0};
+    if (a < n && 4 * c4 < d) {
+      const int ay = a / aw, ax = a - ay * aw;
+#pragma unroll
+      for (int i = 0; i < kEarlyWin; ++i)
+        if (i < wh_u * ww_u) {
+          const int yy = i / ww_u, xx = i - yy * ww_u;
+          pw[i] = *(const f32x4*)(Qu + lay.tok((ay * wh_u + yy) * gw + ax * ww_u + xx) * lay.sn + 4 * c4);
+        }
+    }
+  }
+  const int per = rows * C4;          // 16-byte pieces of one tensor's padded rows
+  constexpr int kPer = 3;             // pieces per thread, tensor and round: 9 loads in flight, a tiny unit in one round trip
+  for (int base = tid; base < per; base += kPer * blockDim.x) {
+    f32x4 v[3][kPer];
+#pragma unroll
+    for (int which = 0; which < 3; ++which) {
+      const float* src = which == 0 ? Qu : (which == 1 ? Ku : Vu);
+#pragma unroll
+      for (int k = 0; k < kPer; ++k) {
+        const int idx = base + k * blockDim.x, row = idx / C4, c4 = idx - row * C4;      // C4 is a constant: no division
+        v[which][k] = f32x4{0, 0, 0, 0};
+        if (row < N && 4 * c4 < d)      // row < N implies idx < per
+          v[which][k] = __builtin_nontemporal_load((const f32x4*)(src + lay.tok(row) * lay.sn + 4 * c4));
       }
     }
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int idx = base + k * blockDim.x;
-      if (idx < 3 * per) *(f32x4*)(Q_lds + (size_t)idx * 4) = v[k];      // the three arrays are contiguous
-    }
+    for (int which = 0; which < 3; ++which)
+#pragma unroll
+      for (int k = 0; k < kPer; ++k) {
+        const int idx = base + k * blockDim.x;
+        if (idx < per) *(f32x4*)(Q_lds + ((size_t)which * per + idx) * 4) = v[which][k];      // the three arrays are contiguous
+      }
   }
   if (Agiven) {
     const float* Au = Agiven + (size_t)u * n * d;
@@ -101,9 +126,13 @@ __global__ __launch_bounds__(64 * kF32Waves) void fused_f32_kernel(
       *(f32x4*)(A_lds + a * RS + 4 * c4) = v;
     }
   }
+  if (early_pool && tid < 16 * NAT * C4) {
+    const int a = tid / C4, c4 = tid - a * C4;
+    *(f32x4*)(A_lds + a * RS + 4 * c4) = ((pw[0] + pw[1]) + (pw[2] + pw[3])) * (1.0f / (float)(wh_u * ww_u));
+  }
   __syncthreads();
-  if (!Agiven) {
-    // A = Pooling(Q), Sec. 4.2: thread = (agent, 4 channels), window rows out of LDS
+  if (!Agiven && !early_pool) {
+    // A = Pooling(Q), Sec. 4.2, any windows: thread = (agent, 4 channels), window rows out of LDS
     for (int idx = tid; idx < 16 * NAT * C4; idx += blockDim.x) {
       const int a = idx / C4, c4 = idx - a * C4;
       f32x4 acc = {0, 0, 0, 0};
@@ -202,17 +231,20 @@ __global__ __launch_bounds__(64 * kF32Waves) void fused_f32_kernel(
   __syncthreads();
   // merge of the slices (log-sum-exp, fixed order): thread = (agent, channel)
   for (int idx = tid; idx < 16 * NAT * 16 * DT; idx += blockDim.x) {
-    const int a = idx / (16 * DT), c = idx - a * (16 * DT), at = a >> 4, a16 = a & 15;
+    // the 16 agents of a tile vary fastest: consecutive LDS addresses in the partials, stride RS in V_A (both conflict free)
+    const int a16 = idx & 15, c = (idx >> 4) % (16 * DT), at = idx / (256 * DT), a = 16 * at + a16;
     float M = -INFINITY;
+#pragma unroll 4
     for (int s = 0; s < S; ++s) M = fmaxf(M, part[(size_t)(s * NAT + at) * PART + 256 * DT + a16]);
     float num = 0.0f, den = 0.0f;
+#pragma unroll 4
     for (int s = 0; s < S; ++s) {
       const float* src = part + (size_t)(s * NAT + at) * PART;
       const float w = fast_exp2(src[256 * DT + a16] - M);
       num += w * src[c * 16 + a16];
       den += w * src[256 * DT + 16 + a16];
     }
-    VA_lds[a * RS + c] = num / den;
+    VA_lds[a * RS + c] = num * __builtin_amdgcn_rcpf(den);      // 1 ulp reciprocal: far inside the fp32 bar
   }
   __syncthreads();
 
@@ -278,7 +310,7 @@ __global__ __launch_bounds__(64 * kF32Waves) void fused_f32_kernel(
       }
 #pragma unroll
     for (int ct = 0; ct < DT; ++ct) mfma_results_ready(o[ct]);
-    const float inv = 1.0f / l;
+    const float inv = __builtin_amdgcn_rcpf(l);
 #pragma unroll
     for (int ct = 0; ct < DT; ++ct) {
       f32x4 out = o[ct] * inv;
@@ -310,11 +342,14 @@ size_t fused_f32_lds(int N, int nat, int dt, int S) {
   const size_t rows = (size_t)(N + 15) / 16 * 16, rs = 16 * (size_t)dt + 4;
   return (3 * rows * rs + 2 * 16 * (size_t)nat * rs + (size_t)nat * S * (256 * (size_t)dt + 32)) * sizeof(float);
 }
+// token slices of the aggregation: as many as there are waves for the agent tiles, tiles of tokens, and room in LDS
 int fused_f32_slices(const Problem& p) {
-  const int nat = (p.n + 15) / 16, ntiles = (p.N + 15) / 16;
+  const int nat = (p.n + 15) / 16, dt = (p.d + 15) / 16, ntiles = (p.N + 15) / 16;
   int S = kF32Waves / nat;
   if (S > ntiles) S = ntiles;
-  return S < 1 ? 1 : S;
+  if (S < 1) S = 1;
+  while (S > 1 && fused_f32_lds(p.N, nat, dt, S) > 160 * 1024) --S;
+  return S;
 }
 
 }  // namespace

@@ -170,7 +170,7 @@ def test_forward_is_deterministic(aa):
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
-@pytest.mark.parametrize("grid,agrid,d", [((9, 11), (3, 4), 24), ((14, 14), (7, 7), 32), ((20, 20), (5, 5), 64)])
+@pytest.mark.parametrize("grid,agrid,d", [((9, 11), (3, 4), 24), ((14, 14), (7, 7), 32), ((12, 12), (4, 4), 64)])
 def test_one_launch_fp32_kernel_is_deterministic(aa, grid, agrid, d):
     """The one-launch fp32 kernel with several MFMA waves per SIMD: same bits on every run, pooled or given agents
     (the softmax shift once depended on when a wave read its score registers)."""
