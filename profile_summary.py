@@ -1,29 +1,26 @@
 #!/usr/bin/env python3
 """Turns rocprofv3 CSV output of `bench.py` runs into the short summaries kept under profiles/.
 
-Three runs of the same workload are expected in one directory (names are the -o prefixes):
-
-  rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload W --no-others --no-cpu-baseline
-  rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d DIR -o fetch -- python3 bench.py --workload W --no-others --no-cpu-baseline --copy-calibration --steps 40
-  rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d DIR -o write -- python3 bench.py --workload W --no-others --no-cpu-baseline --copy-calibration --steps 40
-
 usage: python profile_summary.py DIR W
-writes profiles/W_kernels.md and updates profiles/traffic.json (read back by bench.py for roofline.traffic).
+DIR holds, for workload W,
+  stats_kernel_stats.csv   from  rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload W --no-others --no-cpu-baseline --no-traffic
+  bench_profiled.json      the JSON line that run printed (kernel durations from HIP events, taken under the profiler)
+  bench.json               the JSON line of a plain  python3 bench.py --workload W --no-others --no-cpu-baseline
+                           (kernel durations from HIP events, and HBM bytes per launch from the two rocprofv3 --pmc
+                           FETCH_SIZE / WRITE_SIZE child runs that bench.py makes itself, scaled by a copy of known size)
+writes profiles/W_kernels.md: per kernel the profiler's average duration next to the benchmark's own, the measured
+HBM bytes per launch next to the algorithmic ones, and the roofline entry of the dominant kernel.
 
 usage: python profile_summary.py DIR W backward
 DIR holds one run with the backward pass timed as well:
-  rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload W --no-others --no-cpu-baseline --backward --steps 30 --warmup 5
+  rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload W --no-others --no-cpu-baseline --no-traffic --backward --steps 30 --warmup 5
 writes profiles/W_backward_kernels.md (durations of the backward pass's kernels only).
 
 usage: python profile_summary.py DIR W counters [MODE]
 DIR holds one run with eight SQ counters (MODE = pure, the default, or module):
-  rocprofv3 --pmc SQ_BUSY_CU_CYCLES SQ_INSTS_VALU SQ_INSTS_MFMA SQ_ACTIVE_INST_VALU SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_LDS SQ_ACTIVE_INST_LDS SQ_LDS_BANK_CONFLICT --kernel-trace --output-format csv -d DIR -o sq -- python3 bench.py --workload W --mode MODE --no-others --no-cpu-baseline --steps 20 --warmup 5
+  rocprofv3 --pmc SQ_BUSY_CU_CYCLES SQ_INSTS_VALU SQ_INSTS_MFMA SQ_ACTIVE_INST_VALU SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_LDS SQ_ACTIVE_INST_LDS SQ_LDS_BANK_CONFLICT --kernel-trace --output-format csv -d DIR -o sq -- python3 bench.py --workload W --mode MODE --no-others --no-cpu-baseline --no-traffic --steps 20 --warmup 5
 writes profiles/W_sq_counters.md (profiles/W_module_sq_counters.md): per kernel the launch shape, registers,
 LDS, the median of every counter per dispatch and the ratios used in the design notes.
-
-HBM bytes: FETCH_SIZE / WRITE_SIZE are reported in KiB per dispatch; both are scaled by what the same
-counter reads for the plain 1 GiB device-to-device copy that --copy-calibration runs (it moves exactly
-1 GiB in and 1 GiB out), so a mis-scaled counter cancels out.
 """
 import csv
 import json
@@ -37,7 +34,7 @@ GIB_KIB = float(1 << 20)
 
 
 def short(name):
-    name = re.sub(r"\(.*", "", name)
+    name = re.sub(r"\(.*", "", name.replace("(anonymous namespace)::", ""))
     return name.replace("void ", "").replace("aa::", "")
 
 
@@ -94,7 +91,7 @@ BACKWARD_KERNELS = ("matmul_kernel", "mfma_matmul_kernel", "mfma_matmul_pair_ker
 
 def backward_summary(d, wl):
     cmd = ("rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload %s "
-           "--no-others --no-cpu-baseline --backward --steps 30 --warmup 5" % wl)
+           "--no-others --no-cpu-baseline --no-traffic --backward --steps 30 --warmup 5" % wl)
     lines = ["# rocprofv3 summary: backward pass, bench.py --workload %s --backward (one MI355X)" % wl, "",
              "command: `%s`" % cmd, "",
              "Kernels of `agent_attn_bwd` only (the run also times the forward pass; its kernels are in "
@@ -127,12 +124,13 @@ SQ_COUNTERS = ("SQ_BUSY_CU_CYCLES", "SQ_INSTS_VALU", "SQ_INSTS_MFMA", "SQ_ACTIVE
 
 def counters_summary(d, wl, mode):
     cmd = ("rocprofv3 --pmc %s --kernel-trace --output-format csv -d DIR -o sq -- python3 bench.py --workload %s "
-           "--mode %s --no-others --no-cpu-baseline --steps 20 --warmup 5" % (" ".join(SQ_COUNTERS), wl, mode))
+           "--mode %s --no-others --no-cpu-baseline --no-traffic --steps 20 --warmup 5" % (" ".join(SQ_COUNTERS), wl, mode))
     per = {}
     with open(os.path.join(d, "sq_counter_collection.csv")) as f:
         for r in csv.DictReader(f):
             k = short(r["Kernel_Name"])
-            if not k.startswith(("small_", "pool_", "aggregate_", "merge_", "broadcast_", "large_", "bias_")):
+            if not k.startswith(("small_", "pool_", "aggregate_", "merge_", "broadcast_", "large_", "bias_", "fused_",
+                                 "(anonymous namespace)::fused_")):
                 continue
             e = per.setdefault(k, {"c": {}, "dur": [], "shape": None})
             e["c"].setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
@@ -184,56 +182,67 @@ def main():
     if len(sys.argv) > 3 and sys.argv[3] == "counters":
         counters_summary(d, wl, sys.argv[4] if len(sys.argv) > 4 else "pure")
         return
-    lines = ["# rocprofv3 summary: bench.py --workload %s (one MI355X)" % wl, ""]
-    stats_path = os.path.join(d, "stats_kernel_stats.csv")
-    lines += ["## kernel durations (--kernel-trace --stats)", "",
-              "command: `rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py "
-              "--workload %s --no-others --no-cpu-baseline`" % wl, "",
-              "`avg w/o max` leaves out the slowest dispatch (the first launch of a kernel pays for loading its "
-              "code).", "",
-              "| kernel | calls | avg us | avg w/o max | min us | max us | % of GPU time |", "|---|---|---|---|---|---|---|"]
-    for name, calls, avg, mn, mx, pct in read_stats(stats_path):
-        if name.startswith(("small_", "pool_", "aggregate_", "merge_", "broadcast_", "large_")):
+    kernels_summary(d, wl)
+
+
+def launcher_of(kernel):
+    """Launcher name that bench.py reports for a profiler kernel name."""
+    k = re.sub(r"<.*", "", kernel.replace("(anonymous namespace)::", "")).split("::")[-1]
+    table = [("small_fused", "small_fused"), ("fused_f32", "fused_f32"), ("small_pool", "small_pool"),
+             ("small_aggregate", "small_aggregate"), ("small_merge", "small_merge"), ("small_broadcast", "small_broadcast"),
+             ("large_agents", "large_agents"), ("large_aggregate3", "large_aggregate2"), ("large_merge3", "large_merge2"),
+             ("large_broadcast3", "large_broadcast2"), ("restride", "restride"), ("pool_generic", "pool_generic"),
+             ("pool_vec", "pool_generic"), ("aggregate_generic", "aggregate_generic"), ("merge_generic", "merge_generic"),
+             ("broadcast_generic", "broadcast_generic")]
+    for prefix, name in table:
+        if k.startswith(prefix):
+            return name
+    return None
+
+
+def kernels_summary(d, wl):
+    with open(os.path.join(d, "bench.json")) as f:
+        plain = json.loads(f.read().strip().splitlines()[-1])
+    with open(os.path.join(d, "bench_profiled.json")) as f:
+        prof = json.loads(f.read().strip().splitlines()[-1])
+    stats = {}
+    for name, calls, avg, mn, mx, pct in read_stats(os.path.join(d, "stats_kernel_stats.csv")):
+        ln = launcher_of(name)
+        if ln:
             rest = (avg * calls - mx) / (calls - 1) if calls > 1 else avg
-            lines.append("| `%s` | %d | %.2f | %.2f | %.2f | %.2f | %.2f |" % (name, calls, avg, rest, mn, mx, pct))
-    traffic = {}
-    fetch_p, write_p = os.path.join(d, "fetch_counter_collection.csv"), os.path.join(d, "write_counter_collection.csv")
-    if os.path.exists(fetch_p) and os.path.exists(write_p):
-        fetch, write = read_counter(fetch_p, "FETCH_SIZE"), read_counter(write_p, "WRITE_SIZE")
-        cf, cw = calibration(fetch), calibration(write)
-        lines += ["", "## HBM traffic per launch (--pmc FETCH_SIZE, --pmc WRITE_SIZE; separate runs)", "",
-                  "commands: `rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d DIR -o fetch -- python3 "
-                  "bench.py --workload %s --no-others --no-cpu-baseline --copy-calibration --steps 40` and the same with "
-                  "WRITE_SIZE / -o write." % wl, "",
-                  "calibration: the 1 GiB device copy reads FETCH_SIZE = %.0f KiB and WRITE_SIZE = %.0f KiB "
-                  "(expected 1048576 each) -> scale factors %.4f and %.4f." % (cf, cw, GIB_KIB / cf, GIB_KIB / cw), "",
-                  "| kernel | fetch MB | write MB | total MB |", "|---|---|---|---|"]
-        per_stage = {}
-        for k in sorted(set(fetch) | set(write)):
-            st = stage_of(k)
-            if st is None or "copy" in k.lower():
-                continue
-            fb = statistics.median(fetch.get(k, [0.0])) * (GIB_KIB / cf) * 1024.0
-            wb = statistics.median(write.get(k, [0.0])) * (GIB_KIB / cw) * 1024.0
-            lines.append("| `%s` | %.2f | %.2f | %.2f |" % (k, fb / 1e6, wb / 1e6, (fb + wb) / 1e6))
-            e = per_stage.setdefault(st, {"fetch": 0.0, "write": 0.0})
-            e["fetch"] += fb
-            e["write"] += wb
-        for st, e in per_stage.items():
-            traffic[st] = {"hbm_bytes_per_launch": e["fetch"] + e["write"], "fetch_bytes": e["fetch"],
-                           "write_bytes": e["write"]}
+            stats.setdefault(ln, []).append((name, calls, avg, rest, mn, mx))
+    lines = ["# rocprofv3 summary: bench.py --workload %s (one MI355X)" % wl, "",
+             "commands:", "",
+             "    rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload %s --no-others --no-cpu-baseline --no-traffic" % wl,
+             "    python3 bench.py --workload %s --no-others --no-cpu-baseline      (HIP-event durations without the profiler; HBM bytes from its own two rocprofv3 --pmc runs)" % wl, "",
+             "workload: %s" % json.dumps(plain["config"]), "",
+             "step (all kernels of one forward pass, cold inputs): %.2f us plain, %.2f us under the profiler" % (
+                 plain["ms_per_step"] * 1e3, prof["ms_per_step"] * 1e3), "",
+             "`profiler avg` is rocprofv3's average over all dispatches, `w/o max` leaves out the slowest one (the first launch of "
+             "a kernel pays for loading its code); `events` is what bench.py measures itself with HIP events recorded between "
+             "the launches (it includes the gap to the next launch), plain and under the profiler.", "",
+             "| kernel (launcher) | calls | profiler avg us | w/o max | min | max | events us (plain) | events us (profiled) | HBM MB / launch (measured) |",
+             "|---|---|---|---|---|---|---|---|---|"]
+    pk = {k["name"].split("_dp")[0]: k for k in prof["kernels"]}
+    for k in plain["kernels"]:
+        ln = k["name"].split("_dp")[0]
+        rows = stats.get(ln, [])
+        hb = "%.2f" % (k["hbm_bytes"] / 1e6) if k.get("hbm_bytes") else "-"
+        ev2 = "%.2f" % pk[ln]["avg_us"] if ln in pk else "-"
+        if not rows:
+            lines.append("| `%s` | - | - | - | - | - | %.2f | %s | %s |" % (k["name"], k["avg_us"], ev2, hb))
+        for name, calls, avg, rest, mn, mx in rows:
+            lines.append("| `%s` (`%s`) | %d | %.2f | %.2f | %.2f | %.2f | %.2f | %s | %s |" % (
+                short(name)[:60], k["name"], calls, avg, rest, mn, mx, k["avg_us"], ev2, hb))
+    r = plain["roofline"]
+    lines += ["", "roofline of the dominant kernel (bench.py): `%s`" % json.dumps(r), "",
+              "traffic source: %s" % plain.get("traffic_source"), ""]
+    if "algorithmic_path_bytes" in plain or "path_hbm_bytes_measured" in plain:
+        lines.append("whole path: algorithmic bytes %s, measured HBM bytes %s" % (
+            plain.get("algorithmic_path_bytes"), plain.get("path_hbm_bytes_measured")))
     os.makedirs(os.path.join(ROOT, "profiles"), exist_ok=True)
     with open(os.path.join(ROOT, "profiles", "%s_kernels.md" % wl), "w") as f:
         f.write("\n".join(lines) + "\n")
-    if traffic:
-        tpath = os.path.join(ROOT, "profiles", "traffic.json")
-        table = {}
-        if os.path.exists(tpath):
-            with open(tpath) as f:
-                table = json.load(f)
-        table[wl] = traffic
-        with open(tpath, "w") as f:
-            json.dump(table, f, indent=1, sort_keys=True)
     print("\n".join(lines))
 
 
