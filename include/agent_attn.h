@@ -251,7 +251,9 @@ aa_status agent_attn_fwd_timed(const aa_desc *desc, const void *Q, const void *K
 /* Writes a short, human-readable name of the kernel sequence agent_attn_fwd would run for this
  * problem (pooling when agents_given == 0), e.g. "small_fused" or
  * "small_pool + small_aggregate(S=7) + small_merge + small_broadcast", assuming 16-byte aligned
- * tensors.  Host only.  Returns the length written (excluding the terminator), 0 on an invalid
+ * tensors and no module parameters ("fused_f32", the one-launch fp32 kernel, is replaced by the
+ * pool_generic + ... sequence when an agent bias is given).  With windows the text ends in their
+ * number and in whether they are read in place or staged.  Host only.  Returns the length written (excluding the terminator), 0 on an invalid
  * descriptor or a NULL / zero-length buffer. */
 size_t agent_attn_plan_str(const aa_desc *desc, int agents_given, char *buf, size_t buf_len);
 

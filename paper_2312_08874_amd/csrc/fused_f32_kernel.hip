@@ -51,7 +51,7 @@ struct F32Geo {
 template <int NAT, int DT, bool MODULE>
 __global__ __launch_bounds__(64 * kF32Waves) void fused_f32_kernel(
     const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
-    const float* __restrict__ Agiven, float* __restrict__ O, BiasArgs b1, BiasArgs b2, const float* __restrict__ dwc_w,
+    const float* __restrict__ Agiven, float* __restrict__ O, const float* __restrict__ dwc_w,
     const float* __restrict__ dwc_b, float sc1, float sc2, float vk, int N, int n, int d, int heads, Layout lay, int gh,
     int gw, int ah, int aw, int S) {
   extern __shared__ __attribute__((aligned(16))) float smem_f32[];
@@ -63,6 +63,7 @@ __global__ __launch_bounds__(64 * kF32Waves) void fused_f32_kernel(
   float* A_lds = V_lds + (size_t)rows * RS;
   float* VA_lds = A_lds + 16 * NAT * RS;
   float* part = VA_lds + 16 * NAT * RS;      // [NAT * S][PART]: acc[channel][agent], then m[16], l[16]
+  float* dwc_lds = part + (size_t)NAT * S * PART;      // module mode: [9 taps + bias][16 * DT] floats of the head
 
   const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 15, g = lane >> 4;
@@ -117,6 +118,15 @@ __global__ __launch_bounds__(64 * kF32Waves) void fused_f32_kernel(
         if (idx < per) *(f32x4*)(Q_lds + ((size_t)which * per + idx) * 4) = v[which][k];      // the three arrays are contiguous
       }
   }
+  if constexpr (MODULE) {
+    if (dwc_w)      // the head's 3x3 weights transposed to [tap][channel] (row 9: bias), zero beyond d
+      for (int idx = tid; idx < 10 * 16 * DT; idx += blockDim.x) {
+        const int tap = idx / (16 * DT), ch = idx - tap * (16 * DT);
+        float v = 0.0f;
+        if (ch < d) v = tap < 9 ? dwc_w[((size_t)hd * d + ch) * 9 + tap] : (dwc_b ? dwc_b[(size_t)hd * d + ch] : 0.0f);
+        dwc_lds[idx] = v;
+      }
+  }
   if (Agiven) {
     const float* Au = Agiven + (size_t)u * n * d;
     for (int idx = tid; idx < 16 * NAT * C4; idx += blockDim.x) {
@@ -150,15 +160,6 @@ __global__ __launch_bounds__(64 * kF32Waves) void fused_f32_kernel(
   }
 
   // ---- agent aggregation V_A = softmax(s1 A K^T + B1) V: work item = (agent tile, token slice) ----
-  BiasArgs hb1 = b1, hb2 = b2;
-  if constexpr (MODULE) {
-    if (hb1.col) hb1.col += (size_t)hd * n * gw;
-    if (hb1.row) hb1.row += (size_t)hd * n * gh;
-    if (hb1.blk) hb1.blk += (size_t)hd * n * hb1.h0 * hb1.w0;
-    if (hb2.col) hb2.col += (size_t)hd * gw * n;
-    if (hb2.row) hb2.row += (size_t)hd * gh * n;
-    if (hb2.blk) hb2.blk += (size_t)hd * hb2.h0 * hb2.w0 * n;
-  }
   const int tps = (ntiles + S - 1) / S;      // token tiles per slice
   for (int item = wave; item < NAT * S; item += kF32Waves) {
     const int at = item % NAT, s = item / NAT;
@@ -183,15 +184,6 @@ __global__ __launch_bounds__(64 * kF32Waves) void fused_f32_kernel(
         for (int j = 0; j < 4; ++j) c = mma4(kreg[j], areg[kc][j], c);
       }
       mfma_results_ready(c);
-      if constexpr (MODULE) {
-        if (hb1.any() && agent < n) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int t = min(t0 + 4 * g + i, N - 1), y = t / gw, x = t - y * gw;
-            c[i] += kLog2eF * bias1_at(hb1, agent, y, x, gh, gw);
-          }
-        }
-      }
       if (t0 + 16 > N) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -278,9 +270,6 @@ __global__ __launch_bounds__(64 * kF32Waves) void fused_f32_kernel(
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int a = 16 * at + 4 * g + i;
-        if constexpr (MODULE) {
-          if (hb2.any() && a < n) c[i] += kLog2eF * bias2_at(hb2, a, y, x, gh, gw, n);
-        }
         if (a >= n) c[i] = -INFINITY;
         mx = fmaxf(mx, c[i]);
       }
@@ -318,16 +307,15 @@ __global__ __launch_bounds__(64 * kF32Waves) void fused_f32_kernel(
       if constexpr (MODULE) {
         if (ch < d) {
           if (dwc_w) {      // Eq. (6): 3x3 depthwise convolution of V, zero padded at the border of the grid
-            const float* w = dwc_w + ((size_t)hd * d + ch) * 9;
-            if (dwc_b) out += *(const f32x4*)(dwc_b + (size_t)hd * d + ch);
+            out += *(const f32x4*)(dwc_lds + 9 * 16 * DT + ch);
+#pragma unroll
             for (int ky = -1; ky <= 1; ++ky)
+#pragma unroll
               for (int kx = -1; kx <= 1; ++kx) {
                 const int yy = y + ky, xx = x + kx;
-                if (yy >= 0 && yy < gh && xx >= 0 && xx < gw) {
-                  const f32x4 v = *(const f32x4*)(V_lds + (size_t)(yy * gw + xx) * RS + ch);
-                  const int tap = (ky + 1) * 3 + kx + 1;
-                  out += f32x4{w[tap], w[9 + tap], w[18 + tap], w[27 + tap]} * v;
-                }
+                if (yy >= 0 && yy < gh && xx >= 0 && xx < gw)
+                  out += *(const f32x4*)(dwc_lds + ((ky + 1) * 3 + kx + 1) * 16 * DT + ch) *
+                         *(const f32x4*)(V_lds + (size_t)(yy * gw + xx) * RS + ch);
               }
           }
           if (vk != 0.0f) out += vk * *(const f32x4*)(V_lds + (size_t)tokc * RS + ch);      // Appendix C.1
@@ -340,7 +328,7 @@ __global__ __launch_bounds__(64 * kF32Waves) void fused_f32_kernel(
 
 size_t fused_f32_lds(int N, int nat, int dt, int S) {
   const size_t rows = (size_t)(N + 15) / 16 * 16, rs = 16 * (size_t)dt + 4;
-  return (3 * rows * rs + 2 * 16 * (size_t)nat * rs + (size_t)nat * S * (256 * (size_t)dt + 32)) * sizeof(float);
+  return (3 * rows * rs + 2 * 16 * (size_t)nat * rs + (size_t)nat * S * (256 * (size_t)dt + 32) + 160 * (size_t)dt) * sizeof(float);
 }
 // token slices of the aggregation: as many as there are waves for the agent tiles, tiles of tokens, and room in LDS
 int fused_f32_slices(const Problem& p) {
@@ -354,10 +342,13 @@ int fused_f32_slices(const Problem& p) {
 
 }  // namespace
 
-// fp32, d a multiple of 4 up to 64, at most 64 agents, and the unit's padded rows, agents and slice partials
-// within the 160 KB of LDS.  (Alignment of the pointers and strides is the caller's check.)
+// fp32, d a multiple of 4 up to 64, at most 64 agents, no agent bias (on the single CU a unit gets here, evaluating
+// the bias components per score from memory measured slower than the reference kernels' four launches across the
+// chip: 42 against 31 us on the 14x14 shape), and the unit's padded rows, agents and slice partials within the
+// 160 KB of LDS.  (Alignment of the pointers and strides is the caller's check.)
 bool fused_f32_supported(const Problem& p) {
   if (p.dtype != 0 || p.d % 4 != 0 || p.d > 64 || p.n > 64 || p.N > (1 << 16)) return false;
+  if (p.b1.any() || p.b2.any()) return false;
   return fused_f32_lds(p.N, (p.n + 15) / 16, (p.d + 15) / 16, fused_f32_slices(p)) <= 160 * 1024;
 }
 
@@ -366,13 +357,13 @@ hipError_t launch_fused_f32(const Problem& p, const void* Q, const void* K, cons
   const int nat = (p.n + 15) / 16, dt = (p.d + 15) / 16;
   const int S = fused_f32_slices(p);
   const size_t lds = fused_f32_lds(p.N, nat, dt, S);
-  const bool mod = p.b1.any() || p.b2.any() || p.dwc_w != nullptr || p.vk != 0.0f;
+  const bool mod = p.dwc_w != nullptr || p.vk != 0.0f;
   hipError_t err = hipErrorInvalidValue;
   auto launch = [&](auto kernel) {
     err = allow_lds(kernel, lds);
     if (err == hipSuccess)
       kernel<<<dim3(p.units), dim3(64 * kF32Waves), lds, st>>>((const float*)Q, (const float*)K, (const float*)V,
-                                                               (const float*)A, (float*)out, p.b1, p.b2, p.dwc_w, p.dwc_b,
+                                                               (const float*)A, (float*)out, p.dwc_w, p.dwc_b,
                                                                p.scale1, p.scale2, p.vk, p.N, p.n, p.d, p.heads, p.lay,
                                                                p.gh, p.gw, p.ah, p.aw, S);
   };
