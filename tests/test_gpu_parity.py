@@ -397,6 +397,43 @@ def test_forward_stress_distributions(aa, oracle, scale_qk, v_mean):
                        max_abs=1e-2 * max(1.0, float(np.abs(ref2).max())))
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f16", 40)])
+@pytest.mark.parametrize("kind", ["scaled x4", "scaled x8", "rising along tokens and agents"])
+def test_large_agent_kernels_growing_maxima(aa, oracle, kind, dtype, d):
+    """Many agents (the large-agent kernels) with scores that keep outgrowing the running maximum: those kernels
+    compute a tile's weights with the old maximum first and fall back to a slow path (scores taken again, maximum
+    raised, accumulators rescaled) only when a weight comes out too large.  Peaky inputs and inputs whose scores
+    rise along the token axis (aggregation) and along the agent axis (broadcast) take that path again and again."""
+    import dataclasses
+    wl = dataclasses.replace(WL["sd_latent"], batch=1, heads=2, grid=(48, 32), agent_grid=(16, 16), d=d, dtype=dtype,
+                             index=14)
+    assert "large_aggregate" in aa.plan_str(aa.make_desc(wl.batch, wl.heads, wl.N, wl.n, d, 1 if dtype == "f16" else 2,
+                                                         wl.grid, wl.agent_grid))
+    scale = {"scaled x4": 4.0, "scaled x8": 8.0}.get(kind, 1.0)
+    t = inputs.make_qkv(wl, scale_qk=scale)
+    f = {k: inputs.to_float64(v, dtype) for k, v in t.items()}
+    A64 = None
+    if kind.startswith("rising"):
+        ramp_t = (1.0 + 5.0 * np.arange(wl.N) / wl.N)[None, :, None]
+        f["K"] = f["K"] * ramp_t
+        f["Q"] = f["Q"] * 2.0
+        t = {k: inputs.to_storage(v, dtype) for k, v in f.items()}
+        f = {k: inputs.to_float64(v, dtype) for k, v in t.items()}
+        # agents handed in, growing with their index: later agent chunks of the broadcast carry the larger scores
+        pooled = oracle.pool(f["Q"], *wl.grid, *wl.agent_grid)
+        A_st = inputs.to_storage(pooled * (0.5 + 3.0 * np.arange(wl.n) / wl.n)[None, :, None], dtype)
+        A64 = inputs.to_float64(A_st, dtype)
+    dv = dev_qkv(wl, t)
+    if A64 is None:
+        O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid)
+        ref = oracle.agent_attn_fwd(f["Q"], f["K"], f["V"], heads=wl.heads, grid=wl.grid, agent_grid=wl.agent_grid)
+    else:
+        O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], util.to_device(A_st, dtype, (wl.batch, wl.heads, wl.n, d)))
+        ref = oracle.agent_attn_fwd(f["Q"], f["K"], f["V"], heads=wl.heads, A=A64)
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, dtype, "large agents, " + kind,
+                       max_abs=1e-2 * max(1.0, float(np.abs(ref).max())))
+
+
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("grid,agrid,d", [((1, 1), (1, 1), 8), ((3, 5), (3, 3), 8), ((1, 197), (1, 16), 40),
                                           ((10, 20), (9, 9), 72), ((25, 8), (4, 4), 128), ((56, 56), (3, 3), 32),
