@@ -173,7 +173,7 @@ void plan_small(const aa_desc* d, Plan& pl) {
 // (the split partials stay small beside K and V), split length a multiple of the 64-token K/V tile.
 void plan_large(const aa_desc* d, Plan& pl) {
   const int64_t units = units_of(d);
-  const int waves = d->n <= 64 ? 4 : 8;          // the staging copies want at least 256 threads
+  const int waves = d->n <= 256 ? 4 : 8;          // 64 or 128 agents per block; the staging copies want at least 256 threads
   pl.waves_large = waves;
   const int apb = waves * 16;
   const int64_t nblocks = (d->n + apb - 1) / apb;
@@ -181,7 +181,10 @@ void plan_large(const aa_desc* d, Plan& pl) {
   pl.n_pad = aa::round_up64(d->n);
   int S = d->n_splits;
   if (S <= 0) {
-    S = (int)((512 + units * nblocks - 1) / (units * nblocks));
+    // about 512 blocks of 8 waves, or 256 blocks of 4 (measured as fast as 512 on the 256-agent latent shape, with
+    // half the partials to write and merge)
+    const int64_t target = waves == 8 ? 512 : 256;
+    S = (int)((target + units * nblocks - 1) / (units * nblocks));
     const int max_by_len = (d->N + 511) / 512;
     if (S > max_by_len) S = max_by_len;
   }
