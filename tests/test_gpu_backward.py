@@ -149,6 +149,14 @@ def test_backward_deit_shape(aa, oracle):
     _run_case(aa, oracle, wl)
 
 
+@pytest.mark.parametrize("name,batch,heads", [("swin_t_s1", 1, 3), ("sd_latent", 1, 2), ("highres", 1, 1)])
+def test_backward_workload_shapes(aa, oracle, name, batch, heads):
+    """The other benchmark shapes at their real N, n and d (fewer units, so that the oracle's dense n x N matrices
+    stay within seconds): every gradient element against the oracle."""
+    wl = dataclasses.replace(WL[name], batch=batch, heads=heads)
+    _run_case(aa, oracle, wl)
+
+
 def test_backward_is_deterministic_and_ignores_workspace(aa):
     import torch
     wl = _wl("det", "bf16", (12, 12), (4, 4), 32)

@@ -140,7 +140,7 @@ def test_forward_pure_elementwise(aa, oracle, name, batch):
 
 
 @pytest.mark.parametrize("name,n_units,n_rows", [("deit_t", 24, None), ("swin_t_s1", 6, 512), ("sd_latent", 4, 1024),
-                                                 ("highres", 2, 1024)])
+                                                 ("highres", 8, 4096)])
 def test_forward_pure_full_size_sampled(aa, oracle, name, n_units, n_rows):
     """Full workload on the GPU (the launch configuration bench.py times); oracle on sampled units and rows."""
     wl = WL[name]
