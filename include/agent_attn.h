@@ -175,6 +175,32 @@ aa_status agent_attn_resize_bias(int32_t heads, int32_t grid_h, int32_t grid_w, 
                                  int32_t agent_w, int32_t new_agent_h, int32_t new_agent_w,
                                  const aa_params *src, const aa_params *dst, void *hip_stream);
 
+/* The agent attention module with its linear projections (Sec. 4.2; Eq. (7) counts them as 4NC^2 of the module's
+ * cost).  With C = heads*d and T the tokens per (batch) image (N, or image_h*image_w with windows):
+ *   [q | k | v] = x Wqkv^T + bqkv     x [batch, T, C];  Wqkv [3C, C], output rows ordered q, k, v and head-major
+ *                                     inside each (row s*C + h*d + c is channel c of head h of q / k / v for s = 0 / 1 / 2)
+ *   o = agent attention of q, k, v    agent_attn_fwd with agents pooled from q; q, k, v are read where the projection
+ *                                     wrote them ([batch, T, 3, heads, d], i.e. through the descriptor strides), o is
+ *                                     written token-major [batch, T, heads, d] = [batch, T, C]
+ *   y = o Wout^T + bout               Wout [C, C];  y [batch, T, C]
+ * q, k, v and o are stored in desc->dtype (one rounding each from the fp32 accumulator), as the activations of a
+ * model in that type are.  The two products are plain GEMMs and go to the platform's BLAS library (rocBLAS, fp32
+ * accumulation), loaded on first use; everything else is this library's kernels.  All pointers device memory; weights
+ * and biases in desc->dtype, row-major; bqkv / bout may be NULL.
+ * desc: batch, heads, N, n, d, grids (both needed: the agents are pooled), dtype, scales, v_residual_k, n_splits and
+ * image_h / image_w as for agent_attn_fwd; the stride fields must be 0 (the module fixes the layouts).
+ * workspace: agent_attn_module_workspace_bytes(), 256-byte aligned (holds q|k|v, o and the attention's workspace).
+ * Errors: as agent_attn_fwd; AA_ERR_SHAPE for non-zero strides; AA_ERR_UNSUPPORTED when the BLAS library cannot be
+ * loaded; AA_ERR_HIP when one of its calls fails. */
+typedef struct {
+  const void *w_qkv, *b_qkv; /* [3C, C], [3C] or NULL */
+  const void *w_out, *b_out; /* [C, C], [C] or NULL */
+} aa_projections;
+size_t agent_attn_module_workspace_bytes(const aa_desc *desc, const aa_params *params);
+aa_status agent_attn_module_fwd(const aa_desc *desc, const void *x, const aa_projections *proj,
+                                const aa_params *params, void *workspace, size_t workspace_bytes, void *y,
+                                void *hip_stream);
+
 /* A = Pooling(Q), Sec. 4.2: average over the window
  * [floor(i*L/La), ceil((i+1)*L/La)) per axis.  A_out [batch, heads, n, d], desc->dtype. */
 aa_status agent_pool_fwd(const aa_desc *desc, const void *Q, void *A_out, void *hip_stream);

@@ -22,6 +22,8 @@
  * itself: the half-pixel bilinear rule in oracle_resize_bilinear() and the
  * zero padding / cross-correlation orientation in oracle_dwc().  Both are
  * pinned only against library routines that implement the same stated rule.
+ * The same holds for the agent-axis interpolation of the bias
+ * (oracle_resize_agent_axis(), Appendix D gives no rule).
  */
 #include <math.h>
 #include <stddef.h>
@@ -154,6 +156,25 @@ void oracle_resize_bilinear(const double *src, int h0, int w0, size_t stride,
             dst[(size_t)y * w + x] = top + (bot - top) * fy;
         }
     }
+}
+
+/* ------------------------------------------------------------------------
+ * Linear projection of the module (Sec. 4.2; the 4NC^2 term of Eq. (7)):
+ *   Y[r, o] = sum_k X[r, k] * W[o, k] + b[o]
+ * X [rows, K], W [O, K] (one row per output channel), b [O] or NULL, Y [rows, O].
+ * ---------------------------------------------------------------------- */
+void oracle_linear(const double *X, const double *W, const double *b, int rows,
+                   int K, int O, double *Y)
+{
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < rows; ++r)
+        for (int o = 0; o < O; ++o) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k)
+                acc += X[(size_t)r * K + k] * W[(size_t)o * K + k];
+            if (b) acc += b[o];
+            Y[(size_t)r * O + o] = acc;
+        }
 }
 
 /* ------------------------------------------------------------------------

@@ -90,6 +90,18 @@ def pool(Q, gh, gw, ah, aw):
     return A
 
 
+def linear(X, W, b=None):
+    """Sec. 4.2 projections: Y = X W^T + b.  X [..., K], W [O, K], b [O] or None -> [..., O]."""
+    X, W = _f64(X), _f64(W)
+    b = None if b is None else _f64(b)
+    K, O = X.shape[-1], W.shape[0]
+    assert W.shape[1] == K and (b is None or b.shape == (O,))
+    rows = int(np.prod(X.shape[:-1]))
+    out = np.empty(X.shape[:-1] + (O,), dtype=np.float64)
+    _load().oracle_linear(_p(X), _p(W), _p(b), rows, K, O, _p(out))
+    return out
+
+
 def resize_bilinear(plane, h, w):
     plane = _f64(plane)
     h0, w0 = plane.shape

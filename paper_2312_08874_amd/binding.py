@@ -40,6 +40,11 @@ class aa_params(ctypes.Structure):
                 ("dwc_w", ctypes.c_void_p), ("dwc_b", ctypes.c_void_p), ("bias_tables", ctypes.c_void_p)]
 
 
+class aa_projections(ctypes.Structure):
+    _fields_ = [("w_qkv", ctypes.c_void_p), ("b_qkv", ctypes.c_void_p), ("w_out", ctypes.c_void_p),
+                ("b_out", ctypes.c_void_p)]
+
+
 class aa_kernel_time(ctypes.Structure):
     _fields_ = [("name", ctypes.c_char * 48), ("ms", ctypes.c_float)]
 
@@ -54,7 +59,8 @@ EXPORTS = ("agent_attn_workspace_bytes", "agent_attn_fwd", "agent_pool_fwd", "ag
            "agent_broadcast_fwd", "agent_attn_flops", "agent_attn_status_str", "agent_attn_plan_str",
            "agent_attn_bwd_workspace_bytes", "agent_attn_bwd", "agent_attn_bias_tables_bytes",
            "agent_attn_bias_tables", "agent_attn_fwd_static", "agent_attn_static_scratch_bytes",
-           "agent_attn_fwd_timed", "agent_attn_resize_bias")
+           "agent_attn_fwd_timed", "agent_attn_resize_bias", "agent_attn_module_workspace_bytes",
+           "agent_attn_module_fwd")
 
 _lib = None
 
@@ -89,6 +95,10 @@ def lib():
                                            ctypes.POINTER(aa_kernel_time), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
         L.agent_attn_resize_bias.restype = ctypes.c_int
         L.agent_attn_resize_bias.argtypes = [ctypes.c_int32] * 7 + [pp, pp, vp]
+        L.agent_attn_module_workspace_bytes.restype = ctypes.c_size_t
+        L.agent_attn_module_workspace_bytes.argtypes = [dp, pp]
+        L.agent_attn_module_fwd.restype = ctypes.c_int
+        L.agent_attn_module_fwd.argtypes = [dp, vp, ctypes.POINTER(aa_projections), pp, vp, ctypes.c_size_t, vp, vp]
         L.agent_pool_fwd.restype = ctypes.c_int
         L.agent_pool_fwd.argtypes = [dp, vp, vp, vp]
         L.agent_aggregate_fwd.restype = ctypes.c_int
@@ -342,6 +352,41 @@ def agent_attn_resize_bias(params: dict, *, heads, grid, agent_grid, new_agent_g
     st = lib().agent_attn_resize_bias(heads, grid[0], grid[1], agent_grid[0], agent_grid[1], new_agent_grid[0],
                                       new_agent_grid[1], _pp(src), _pp(dst), _stream(stream))
     _check(st, "agent_attn_resize_bias")
+    return out
+
+
+def agent_attn_module_fwd(x, w_qkv, b_qkv, w_out, b_out, *, heads, grid, agent_grid, window=None,
+                          params: dict | None = None, scale1=0.0, scale2=0.0, v_residual_k=0.0, n_splits=0, out=None,
+                          workspace=None, stream=None):
+    """The module with its projections (Sec. 4.2): y = (agent attention of the q, k, v slices of x Wqkv^T + bqkv)
+    Wout^T + bout.  x [B, T, C] with C = heads * d and T = grid_h * grid_w tokens; weights [3C, C] and [C, C], biases
+    [3C], [C] or None, all in x's dtype on x's device.  window=(wh, ww): attention per window of the grid."""
+    import torch
+    B, T, C = x.shape
+    assert x.is_cuda and x.is_contiguous() and C % heads == 0 and grid[0] * grid[1] == T
+    d = C // heads
+    for t, shape in ((w_qkv, (3 * C, C)), (b_qkv, (3 * C,)), (w_out, (C, C)), (b_out, (C,))):
+        assert t is None or (t.is_cuda and t.device == x.device and t.dtype == x.dtype and t.is_contiguous() and
+                             tuple(t.shape) == shape), "projection parameters must be dense, in x's dtype, on x's device"
+    assert w_qkv is not None and w_out is not None
+    if out is None:
+        out = torch.empty_like(x)
+    assert tuple(out.shape) == tuple(x.shape) and out.dtype == x.dtype and out.device == x.device and out.is_contiguous()
+    n = agent_grid[0] * agent_grid[1]
+    if window is not None:
+        assert grid[0] % window[0] == 0 and grid[1] % window[1] == 0
+        desc = make_desc(B, heads, window[0] * window[1], n, d, _dtype_code(x), window, agent_grid, scale1, scale2,
+                         v_residual_k, n_splits, image=grid)
+    else:
+        desc = make_desc(B, heads, T, n, d, _dtype_code(x), grid, agent_grid, scale1, scale2, v_residual_k, n_splits)
+    p = make_params(params)
+    need = int(lib().agent_attn_module_workspace_bytes(ctypes.byref(desc), _pp(p)))
+    if workspace is None:
+        workspace = _alloc_bytes(max(need, 256), stream, x.device)
+    proj = aa_projections(w_qkv.data_ptr(), _ptr(b_qkv), w_out.data_ptr(), _ptr(b_out))
+    st = lib().agent_attn_module_fwd(ctypes.byref(desc), x.data_ptr(), ctypes.byref(proj), _pp(p), workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), out.data_ptr(), _stream(stream))
+    _check(st, "agent_attn_module_fwd")
     return out
 
 

@@ -7,6 +7,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <dlfcn.h>
+
 #include <initializer_list>
 #include <mutex>
 
@@ -1000,6 +1002,134 @@ aa_status agent_attn_fwd_timed(const aa_desc* desc, const void* Q, const void* K
   }
   for (int i = 0; i < made; ++i) (void)hipEventDestroy(rec.ev[i]);
   return st;
+}
+
+// ---------------------------------------------------------------------------
+// Module with projections: two plain GEMMs through rocBLAS (loaded on first use) around agent_attn_fwd.
+// ---------------------------------------------------------------------------
+extern "C++" {
+namespace {
+
+// The few rocBLAS entry points used, by their C ABI (enums are ints there): operation none / transpose = 111 / 112,
+// datatype f16 / f32 / bf16 = 150 / 151 / 168, algorithm standard = 0.
+struct Blas {
+  int (*create_handle)(void**) = nullptr;
+  int (*set_stream)(void*, hipStream_t) = nullptr;
+  int (*gemm_ex)(void*, int, int, int, int, int, const void*, const void*, int, int, const void*, int, int, const void*,
+                 const void*, int, int, void*, int, int, int, int, int32_t, uint32_t) = nullptr;
+  void* handle[64] = {};
+  std::mutex mu;
+  bool tried = false, ok = false;
+};
+Blas& blas() {
+  static Blas b;
+  return b;
+}
+bool blas_load(Blas& b) {
+  if (b.tried) return b.ok;
+  b.tried = true;
+  void* lib = dlopen("librocblas.so", RTLD_NOW | RTLD_LOCAL);
+  if (!lib) lib = dlopen("/opt/rocm/lib/librocblas.so", RTLD_NOW | RTLD_LOCAL);
+  if (!lib) return false;
+  b.create_handle = (decltype(b.create_handle))dlsym(lib, "rocblas_create_handle");
+  b.set_stream = (decltype(b.set_stream))dlsym(lib, "rocblas_set_stream");
+  b.gemm_ex = (decltype(b.gemm_ex))dlsym(lib, "rocblas_gemm_ex");
+  b.ok = b.create_handle && b.set_stream && b.gemm_ex;
+  return b.ok;
+}
+
+// Y [M, O] = X [M, K] W^T (W [O, K]), all row-major in `dtype`, fp32 accumulation.  In the library's column-major
+// terms: Y^T (O x M, ld O) = W (as K x O, ld K)^T * X (as K x M, ld K).
+aa_status linear_rows(int dtype, int M, int O, int K, const void* X, int ldx, const void* W, void* Y, int ldy,
+                      hipStream_t st) {
+  Blas& b = blas();
+  std::lock_guard<std::mutex> lock(b.mu);
+  if (!blas_load(b)) return AA_ERR_UNSUPPORTED;
+  int dev = 0;
+  AA_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return AA_ERR_UNSUPPORTED;
+  if (!b.handle[dev] && b.create_handle(&b.handle[dev]) != 0) return AA_ERR_HIP;
+  if (b.set_stream(b.handle[dev], st) != 0) return AA_ERR_HIP;
+  const int type = dtype == AA_F32 ? 151 : (dtype == AA_F16 ? 150 : 168);
+  const float one = 1.0f, zero = 0.0f;
+  const int rc = b.gemm_ex(b.handle[dev], 112, 111, O, M, K, &one, W, type, K, X, type, ldx, &zero, Y, type, ldy, Y, type,
+                           ldy, 151, 0, 0, 0);
+  return rc == 0 ? AA_OK : AA_ERR_HIP;
+}
+
+struct ModulePlan {
+  size_t off_qkv, off_o, off_inner, inner_bytes, total;
+  int64_t tokens;      // per batch element
+  int C;
+};
+ModulePlan module_plan(const aa_desc* d, const aa_desc* inner, const aa_params* params) {
+  ModulePlan mp{};
+  mp.tokens = image_tokens(d);
+  mp.C = d->heads * d->d;
+  const size_t es = elem_size(d->dtype), rows = (size_t)d->batch * (size_t)mp.tokens;
+  size_t off = 0;
+  mp.off_qkv = off, off += align_up(rows * 3 * mp.C * es);
+  mp.off_o = off, off += align_up(rows * mp.C * es);
+  mp.off_inner = off;
+  mp.inner_bytes = make_plan(inner, params).total;
+  mp.total = off + align_up(mp.inner_bytes);
+  return mp;
+}
+// the attention's descriptor inside the module: q, k, v are slices of [batch, T, 3, heads, d], o is [batch, T, heads, d]
+aa_status module_inner_desc(const aa_desc* d, aa_desc* inner) {
+  if (!d) return AA_ERR_NULL;
+  if (d->stride_b || d->stride_h || d->stride_n || d->out_stride_b || d->out_stride_h || d->out_stride_n) return AA_ERR_SHAPE;
+  if (d->heads <= 0 || d->d <= 0 || d->batch <= 0) return AA_ERR_SHAPE;
+  *inner = *d;
+  const int64_t C = (int64_t)d->heads * d->d;
+  const int64_t T = (d->image_h > 0 && d->image_w > 0) ? (int64_t)d->image_h * d->image_w : (int64_t)d->N;
+  inner->stride_b = T * 3 * C, inner->stride_h = d->d, inner->stride_n = 3 * C;
+  inner->out_stride_b = T * C, inner->out_stride_h = d->d, inner->out_stride_n = C;
+  if (C > (1 << 20) || T * 3 * C >= ((int64_t)1 << 31)) return AA_ERR_UNSUPPORTED;      // 32-bit GEMM sizes
+  return check_desc(inner, true, true);
+}
+
+}  // namespace
+}  // extern "C++"
+
+size_t agent_attn_module_workspace_bytes(const aa_desc* desc, const aa_params* params) {
+  aa_desc inner;
+  if (module_inner_desc(desc, &inner) != AA_OK || check_params(params) != AA_OK) return 0;
+  return module_plan(desc, &inner, params).total;
+}
+
+aa_status agent_attn_module_fwd(const aa_desc* desc, const void* x, const aa_projections* proj, const aa_params* params,
+                                void* workspace, size_t workspace_bytes, void* y, void* hip_stream) {
+  aa_desc inner;
+  aa_status st = module_inner_desc(desc, &inner);
+  if (st == AA_ERR_SHAPE && desc && desc->grid_h == 0 && desc->grid_w == 0) st = AA_ERR_POOL;
+  if (st != AA_OK) return st;
+  st = check_params(params);
+  if (st != AA_OK) return st;
+  if (!x || !y || !proj || !proj->w_qkv || !proj->w_out) return AA_ERR_NULL;
+  const ModulePlan mp = module_plan(desc, &inner, params);
+  if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < mp.total) return AA_ERR_WORKSPACE;
+  const size_t es = elem_size(desc->dtype), rows = (size_t)desc->batch * (size_t)mp.tokens;
+  const size_t act = rows * mp.C * es;
+  if (overlaps(y, act, x, act) || overlaps(y, act, workspace, workspace_bytes) || overlaps(workspace, workspace_bytes, x, act) ||
+      overlaps(y, act, proj->w_qkv, (size_t)3 * mp.C * mp.C * es) || overlaps(y, act, proj->w_out, (size_t)mp.C * mp.C * es))
+    return AA_ERR_ALIAS;
+  if (rows >= ((size_t)1 << 31)) return AA_ERR_UNSUPPORTED;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  char* qkv = ws + mp.off_qkv;
+  char* o = ws + mp.off_o;
+  const int C = mp.C;
+  st = linear_rows(desc->dtype, (int)rows, 3 * C, C, x, C, proj->w_qkv, qkv, 3 * C, stream);
+  if (st != AA_OK) return st;
+  if (proj->b_qkv) AA_HIP(aa::launch_add_row_bias(desc->dtype, qkv, proj->b_qkv, rows, 3 * C, stream));
+  st = agent_attn_fwd(&inner, qkv, qkv + (size_t)C * es, qkv + (size_t)2 * C * es, nullptr, params, ws + mp.off_inner,
+                      align_up(mp.inner_bytes), o, hip_stream);
+  if (st != AA_OK) return st;
+  st = linear_rows(desc->dtype, (int)rows, C, C, o, C, proj->w_out, y, C, stream);
+  if (st != AA_OK) return st;
+  if (proj->b_out) AA_HIP(aa::launch_add_row_bias(desc->dtype, y, proj->b_out, rows, C, stream));
+  return AA_OK;
 }
 
 size_t agent_attn_plan_str(const aa_desc* desc, int agents_given, char* buf, size_t buf_len) {

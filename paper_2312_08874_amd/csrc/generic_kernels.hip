@@ -537,6 +537,24 @@ hipError_t launch_restride(const Problem& p, bool to_dense, bool out_layout, con
 }
 
 // ---------------------------------------------------------------------------
+// Bias of a linear projection: Y[r][c] += bias[c].  thread = one element.
+// ---------------------------------------------------------------------------
+template <class E>
+__global__ __launch_bounds__(256) void add_row_bias_kernel(typename E::T* __restrict__ Y, const typename E::T* __restrict__ bias,
+                                                           size_t count, int cols) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  Y[i] = E::from_f32(E::to_f32(Y[i]) + E::to_f32(bias[i % cols]));
+}
+
+hipError_t launch_add_row_bias(int dtype, void* Y, const void* bias, size_t rows, int cols, hipStream_t st) {
+  const size_t count = rows * (size_t)cols;
+  const dim3 grid((unsigned)((count + 255) / 256));
+  AA_DISPATCH_DTYPE(dtype, add_row_bias_kernel<E><<<grid, dim3(256), 0, st>>>((typename E::T*)Y, (const typename E::T*)bias, count, cols));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Bias component adapted to another agent grid (Appendix D.1 / D.2, "Numbers of agent tokens"): the tensor is
 // viewed as [outer][ah][aw][inner] and every [ah][aw] image is bilinearly interpolated (half-pixel centres, as
 // for the block bias) to [ah2][aw2].  thread = one output element.

@@ -53,6 +53,8 @@ hipError_t launch_resize_agent_axis(const float* src, float* dst, size_t outer, 
 bool fused_f32_supported(const Problem& p);
 hipError_t launch_fused_f32(const Problem& p, const void* Q, const void* K, const void* V, const void* A, void* out,
                             hipStream_t st);
+// Y[r][c] += bias[c] for a row-major [rows][cols] matrix of `dtype` (the bias of a linear projection), rounded once
+hipError_t launch_add_row_bias(int dtype, void* Y, const void* bias, size_t rows, int cols, hipStream_t st);
 hipError_t launch_restride(const Problem& p, bool to_dense, bool out_layout, const void* src, void* dst, hipStream_t st);
 // the half-resized tables of BiasArgs (he = table rows per agent: blk_h0, or 1 without block components)
 size_t bias_half_floats(int heads, int n, int gw, int he);

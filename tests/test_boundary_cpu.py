@@ -115,6 +115,30 @@ def test_fwd_rejects_bad_arguments():
     assert call_fwd(make_desc(1, 1, 196, 49, 32, 0, **ok), params=p) == -1
 
 
+def test_module_entry_point_rejects_bad_arguments():
+    """agent_attn_module_fwd validates on the host before it loads the BLAS library or launches anything."""
+    L = binding.lib()
+    proj = binding.aa_projections(FAKE * 6, None, FAKE * 7, None)
+    d = make_desc(2, 3, 196, 49, 64, binding.AA_BF16, (14, 14), (7, 7))
+    need = L.agent_attn_module_workspace_bytes(ctypes.byref(d), None)
+    plain = binding.workspace_bytes(make_desc(2, 3, 196, 49, 64, binding.AA_BF16, (14, 14), (7, 7),
+                                              strides=(196 * 576, 64, 576), out_strides=(196 * 192, 64, 192)))
+    assert need >= plain + 4 * 2 * 196 * 192 * 2      # q | k | v and o on top of the attention's workspace
+
+    def call(desc, x=FAKE, p=proj, ws=FAKE * 4, ws_bytes=1 << 40, y=FAKE * 5 + (1 << 41)):
+        return L.agent_attn_module_fwd(ctypes.byref(desc), x, None if p is None else ctypes.byref(p), None, ws, ws_bytes,
+                                       y, None)
+
+    assert call(d, x=None) == -1 and call(d, p=None) == -1 and call(d, y=None) == -1
+    assert call(d, p=binding.aa_projections(None, None, FAKE * 7, None)) == -1
+    assert call(d, ws=None) == -5 and call(d, ws_bytes=need - 1) == -5
+    assert call(d, y=FAKE + 64) == -6                                                   # y overlaps x
+    assert call(make_desc(2, 3, 196, 49, 64, binding.AA_BF16, (14, 14), (7, 7), strides=(196 * 192, 64, 192))) == -2
+    assert call(make_desc(2, 3, 196, 49, 64, binding.AA_BF16, None, (7, 7))) == -4      # the module pools: grids needed
+    assert call(make_desc(2, 3, 196, 49, 64, 9, (14, 14), (7, 7))) == -3
+    assert L.agent_attn_module_workspace_bytes(ctypes.byref(make_desc(2, 3, 195, 49, 64, 2, (14, 14), (7, 7))), None) == 0
+
+
 def test_stage_entry_points_reject_bad_arguments():
     L = binding.lib()
     d = make_desc(1, 1, 196, 49, 32, 0, (14, 14), (7, 7))

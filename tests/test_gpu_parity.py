@@ -583,6 +583,46 @@ def test_windows_descriptor_errors(aa):
     assert lib.agent_pool_fwd(ctypes.byref(ok), Q.data_ptr(), A.data_ptr(), None) == -7      # AA_ERR_UNSUPPORTED
 
 
+# --------------------------------------------------------------------------
+# the module with its projections (Sec. 4.2; the 4NC^2 of Eq. (7)): x -> q | k | v -> agent attention -> y
+# --------------------------------------------------------------------------
+MODULE_CASES = [
+    # name, batch, heads, d, grid, window, agent grid, dtype, module terms
+    ("deit-like", 2, 3, 64, (14, 14), None, (7, 7), "bf16", True),
+    ("swin windows 7x7", 1, 3, 32, (28, 28), (7, 7), (3, 3), "bf16", True),
+    ("latent-like, many agents", 1, 4, 40, (32, 32), None, (16, 16), "f16", False),
+    ("fp32", 2, 2, 24, (10, 12), None, (5, 4), "f32", True),
+    ("fp32 windows, one launch per window", 1, 2, 16, (12, 12), (6, 6), (3, 3), "f32", False),
+]
+
+
+@pytest.mark.parametrize("name,batch,heads,d,grid,window,agrid,dtype,module", MODULE_CASES, ids=[c[0] for c in MODULE_CASES])
+def test_module_with_projections(aa, oracle, name, batch, heads, d, grid, window, agrid, dtype, module):
+    C, T = heads * d, grid[0] * grid[1]
+    n = agrid[0] * agrid[1]
+    mk = lambda shape, stream, std: inputs.make_tensor(shape, stream=900 + stream, std=std, dtype=dtype)
+    x = mk((batch, T, C), 0, 1.0)
+    w_qkv, b_qkv = mk((3 * C, C), 1, C ** -0.5), mk((3 * C,), 2, 0.1)
+    w_out, b_out = mk((C, C), 3, C ** -0.5), mk((C,), 4, 0.1)
+    params = inputs.make_module_params(heads, n, d, window or grid, blk=(3, 2), index=15) if module else None
+    dev = lambda a: util.to_device(a, dtype)
+    y = aa.agent_attn_module_fwd(dev(x), dev(w_qkv), dev(b_qkv), dev(w_out), dev(b_out), heads=heads, grid=grid,
+                                 agent_grid=agrid, window=window, params=util.params_to_device(params) if module else None)
+    ref = util.oracle_module_forward(oracle, x, w_qkv, b_qkv, w_out, b_out, dtype, heads=heads, grid=grid,
+                                     agent_grid=agrid, window=window, params=params)
+    scale = max(1.0, float(np.abs(ref).max()))
+    util.assert_parity(util.to_host64(y).reshape(ref.shape), ref, dtype, "module " + name,
+                       max_abs=util.TOL[dtype]["max_abs"] * scale)
+    # without the biases of the projections
+    y2 = aa.agent_attn_module_fwd(dev(x), dev(w_qkv), None, dev(w_out), None, heads=heads, grid=grid, agent_grid=agrid,
+                                  window=window, params=util.params_to_device(params) if module else None)
+    ref2 = util.oracle_module_forward(oracle, x, w_qkv, None, w_out, None, dtype, heads=heads, grid=grid,
+                                      agent_grid=agrid, window=window, params=params)
+    util.assert_parity(util.to_host64(y2).reshape(ref2.shape), ref2, dtype, "module without projection biases " + name,
+                       max_abs=util.TOL[dtype]["max_abs"] * max(1.0, float(np.abs(ref2).max())))
+    assert np.abs(ref - ref2).max() > 1e-3
+
+
 def test_binding_rejects_mismatched_tensors(aa):
     """The Python layer refuses tensors whose dtype, device, shape or density differ from what the descriptor
     will say (the C ABI sees only pointers), before anything is launched."""

@@ -39,6 +39,9 @@ MUTATIONS = [
     ("dA of the two stages not added", "dA_keys[e] += dA_queries[e];", "dA_keys[e] += 0.0;", 0),
     ("bias-block gradient misses one bilinear corner", "gsrc[((size_t)y1 * w0 + x1) * stride] += gv * fy * fx;",
      "gsrc[((size_t)y1 * w0 + x1) * stride] += 0.0;", 0),
+    ("projection reads its weight transposed", "acc += X[(size_t)r * K + k] * W[(size_t)o * K + k];",
+     "acc += X[(size_t)r * K + k] * W[(size_t)k * O + o];", 0),
+    ("projection bias dropped", "if (b) acc += b[o];", "if (b) acc += 0.0 * b[o];", 0),
     ("agent-axis resize walks the agent grid transposed", "oracle_resize_bilinear(src + (size_t)o * ah * aw * inner + i, ah, aw,",
      "oracle_resize_bilinear(src + (size_t)o * ah * aw * inner + i, aw, ah,", 0),
     ("agent-axis resize scatters with the wrong stride", "dst[((size_t)o * ah2 * aw2 + a) * inner + i] = plane[a];",

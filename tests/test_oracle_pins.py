@@ -123,6 +123,29 @@ def test_bilinear_vs_brute_and_library(oracle):
     np.testing.assert_allclose(oracle.resize_bilinear(np.full((3, 3), 1.7), 11, 5), 1.7, atol=1e-15)
 
 
+def test_linear_projection_vs_library_brute_and_closed_forms(oracle):
+    """Sec. 4.2 projections, Y = X W^T + b: a library matmul, pure-Python loops, and cases with known answers."""
+    X, W, b = rnd((2, 5, 7), 60), rnd((4, 7), 61), rnd((4,), 62)
+    got = oracle.linear(X, W, b)
+    np.testing.assert_allclose(got, X @ W.T + b, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(got, F.linear(torch.from_numpy(X), torch.from_numpy(W), torch.from_numpy(b)).numpy(),
+                               rtol=0, atol=1e-13)
+    for r in range(5):
+        for o in range(4):
+            acc = b[o]
+            for k in range(7):
+                acc += X[1, r, k] * W[o, k]
+            assert abs(got[1, r, o] - acc) < 1e-13
+    # a non-square weight with one non-zero entry picks one input channel for one output channel, no bias
+    W1 = np.zeros((4, 7))
+    W1[2, 5] = 3.0
+    sel = oracle.linear(X, W1)
+    assert np.array_equal(sel[..., 2], 3.0 * X[..., 5]) and not sel[..., [0, 1, 3]].any()
+    # identity weight returns the input; the bias alone comes out for a zero input
+    assert np.array_equal(oracle.linear(X, np.eye(7)), X)
+    assert np.array_equal(oracle.linear(np.zeros((3, 7)), W, b), np.tile(b, (3, 1)))
+
+
 def test_agent_axis_resize_vs_library_and_brute(oracle):
     """Appendix D.1 / D.2: bias components interpolated to another agent count, both component layouts."""
     heads, (ah, aw), (ah2, aw2) = 2, (3, 4), (6, 7)

@@ -110,3 +110,40 @@ def oracle_forward_units(oracle, wl, t, unit_ids, *, rows=None, params=None, A=N
                 O = O + kw["v_residual_k"] * V[0][rows]
         outs.append(O)
     return np.stack(outs)
+
+
+def oracle_module_forward(oracle, x_st, w_qkv_st, b_qkv_st, w_out_st, b_out_st, dtype, *, heads, grid, agent_grid,
+                          window=None, params=None, **kw):
+    """The module with its projections from oracle pieces (Sec. 4.2): q | k | v = x Wqkv^T + b stored in the I/O
+    type, agent attention per head (per window when `window` is given: the image is partitioned explicitly), its
+    output stored in the I/O type, y = o Wout^T + b.  Inputs are storage arrays; returns float64 [B, T, C]."""
+    f = lambda a: None if a is None else inputs.to_float64(a, dtype)
+    x = f(x_st)
+    B, T, C = x.shape
+    d = C // heads
+    store = lambda a: inputs.to_float64(inputs.to_storage(a, dtype), dtype)
+    qkv = store(oracle.linear(x, f(w_qkv_st), f(b_qkv_st))).reshape(B, T, 3, heads, d)
+    q, k, v = (np.ascontiguousarray(qkv[:, :, i].transpose(0, 2, 1, 3)).reshape(B * heads, T, d) for i in range(3))
+    B1 = B2 = None
+    sel = {}
+    g = window if window is not None else grid
+    n = agent_grid[0] * agent_grid[1]
+    if params:
+        B1, B2 = dense_biases(oracle, params, heads, n, g)
+        if params.get("dwc_w") is not None:
+            sel["dwc_w"], sel["dwc_b"] = params["dwc_w"], params.get("dwc_b")
+    if window is None:
+        o = oracle.agent_attn_fwd(q, k, v, heads=heads, grid=grid, agent_grid=agent_grid, B1=B1, B2=B2, **sel, **kw)
+    else:
+        (Y, X), (wh, ww) = grid, window
+
+        def part(t):      # [B*H, Y*X, d] -> [B*windows*H, wh*ww, d], units ordered (batch, window, head)
+            u = t.reshape(B, heads, Y // wh, wh, X // ww, ww, d)
+            return np.ascontiguousarray(u.transpose(0, 2, 4, 1, 3, 5, 6)).reshape(-1, wh * ww, d)
+
+        ow = oracle.agent_attn_fwd(part(q), part(k), part(v), heads=heads, grid=window, agent_grid=agent_grid, B1=B1, B2=B2,
+                                   **sel, **kw)
+        u = ow.reshape(B, Y // wh, X // ww, heads, wh, ww, d)
+        o = np.ascontiguousarray(u.transpose(0, 3, 1, 4, 2, 5, 6)).reshape(B * heads, T, d)
+    o = store(np.ascontiguousarray(o.reshape(B, heads, T, d).transpose(0, 2, 1, 3)).reshape(B, T, C))
+    return oracle.linear(o, f(w_out_st), f(b_out_st))
