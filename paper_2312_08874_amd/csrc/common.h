@@ -61,6 +61,34 @@ struct Layout {
 };
 
 // ---------------------------------------------------------------------------
+// XCD-aware block numbering.  The 256 CUs sit in eight XCDs, each with an L2 of its own, and the blocks of a
+// 1-D grid are handed to the XCDs in turn (block L to XCD L % 8).  Blocks that read the same data ("members" of a
+// "group": the agent blocks of one (unit, split), the token chunks of one unit) are therefore numbered so that a
+// group stays on one XCD: block L is member (L / 8) % members of group ((L / 8) / members) * 8 + L % 8, the grid
+// being rounded up to whole rounds of eight groups (blocks of groups that do not exist leave at once).  Only when
+// the groups spread evenly over the XCDs (a multiple of eight, or many); otherwise plain numbering.
+// ---------------------------------------------------------------------------
+struct XcdGrid {
+  int groups, members, grouped;
+  __host__ static XcdGrid make(int groups, int members) {
+    return XcdGrid{groups, members, (groups % 8 == 0 || groups >= 64) ? 1 : 0};
+  }
+  __host__ long long blocks() const { return grouped ? (long long)(groups + 7) / 8 * 8 * members : (long long)groups * members; }
+  // false: this block has no work
+  __device__ __forceinline__ bool decode(unsigned L, int& group, int& member) const {
+    if (grouped) {
+      const unsigned slot = L >> 3;
+      member = (int)(slot % (unsigned)members);
+      group = (int)(slot / (unsigned)members) * 8 + (int)(L & 7u);
+    } else {
+      member = (int)(L % (unsigned)members);
+      group = (int)(L / (unsigned)members);
+    }
+    return group < groups;
+  }
+};
+
+// ---------------------------------------------------------------------------
 // Agent bias (Appendix B), evaluated on the fly from its three components.
 // Pointers are already offset to the head; any may be null.
 //   kind 1: B1[a,(y,x)] = col[a*w+x] + row[a*h+y] + resize(blk[a,:,:])[y,x]
