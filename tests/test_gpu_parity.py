@@ -566,6 +566,33 @@ def test_forward_windows_in_descriptor(aa, oracle, name, image, window, agrid, d
         assert np.array_equal(got, got2)
 
 
+@pytest.mark.parametrize("window,agrid,n_splits,dtype", [((7, 7), (3, 3), 0, "bf16"), ((14, 14), (7, 7), 2, "f16"),
+                                                         ((14, 14), (9, 9), 0, "bf16"), ((7, 7), (2, 2), 0, "f32")])
+def test_windows_with_given_agents_and_static_workspace(aa, oracle, window, agrid, n_splits, dtype):
+    """Windows with agents handed in per (batch, window, head) -- [B, windows, H, n, d] -- on every kernel family,
+    through the ordinary entry point and through the one that allocates nothing."""
+    import dataclasses
+    import torch
+    batch, heads, image, d = 2, 2, (28, 28), 32
+    (Y, X), (wh, ww) = image, window
+    nwin = (Y // wh) * (X // ww)
+    wl = dataclasses.replace(WL["tiny"], batch=batch * nwin, heads=heads, grid=window, agent_grid=agrid, d=d, dtype=dtype,
+                             index=16)
+    img = {k: inputs.make_tensor((batch * heads, Y * X, d), stream=16 * 16 + 40 + i, dtype=dtype)
+           for i, k in enumerate(("Q", "K", "V"))}
+    t = {k: _partition(v, heads, image, window) for k, v in img.items()}
+    A_st = inputs.make_tensor((wl.units, wl.n, d), stream=16 * 16 + 11, std=0.5, dtype=dtype)      # unit order (b, window, head)
+    dev = {k: util.to_device(v, dtype, (batch, heads, Y * X, d)) for k, v in img.items()}
+    Ad = util.to_device(A_st, dtype, (batch * nwin, heads, wl.n, d))
+    O = aa.agent_attn_fwd(dev["Q"], dev["K"], dev["V"], Ad, grid=image, window=window, n_splits=n_splits)
+    ref = _unpartition(util.oracle_forward_units(oracle, wl, t, list(range(wl.units)), A=A_st), batch, heads, image, window)
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, dtype, "windows, agents given",
+                       max_abs=None if dtype == "f32" else 1e-2 * max(1.0, float(np.abs(ref).max())))
+    out = torch.full_like(dev["Q"], float("nan"))
+    O2 = aa.agent_attn_fwd_static(dev["Q"], dev["K"], dev["V"], Ad, grid=image, window=window, n_splits=n_splits, out=out)
+    assert torch.equal(O, O2)
+
+
 def test_windows_descriptor_errors(aa):
     import ctypes
     lib = aa.lib()
