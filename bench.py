@@ -268,6 +268,38 @@ def single_call_latency_us(wl, binding):
     return statistics.median(samples)
 
 
+def module_with_projections_us(wl, binding, steps=30, warmup=5):
+    """The module with its projections (agent_attn_module_fwd: q | k | v GEMM, agent attention, output GEMM) on the
+    workload's shape, x [B, N, heads * d] resident in HBM, same inputs every call (hot); microseconds per call."""
+    import torch
+    C = wl.heads * wl.d
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[wl.dtype]
+    g = torch.Generator(device="cuda").manual_seed(20231214)
+    x = torch.randn((wl.batch, wl.N, C), generator=g, device="cuda", dtype=torch.float32).to(tdt)
+    w_qkv = (torch.randn((3 * C, C), generator=g, device="cuda", dtype=torch.float32) * C ** -0.5).to(tdt)
+    w_out = (torch.randn((C, C), generator=g, device="cuda", dtype=torch.float32) * C ** -0.5).to(tdt)
+    y = torch.empty_like(x)
+    desc = binding.make_desc(wl.batch, wl.heads, wl.N, wl.n, wl.d, {"f32": 0, "f16": 1, "bf16": 2}[wl.dtype], wl.grid,
+                             wl.agent_grid)
+    import ctypes
+    need = int(binding.lib().agent_attn_module_workspace_bytes(ctypes.byref(desc), None))
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    call = lambda: binding.agent_attn_module_fwd(x, w_qkv, None, w_out, None, heads=wl.heads, grid=wl.grid,
+                                                 agent_grid=wl.agent_grid, out=y, workspace=ws)
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    del x, w_qkv, w_out, y, ws
+    torch.cuda.empty_cache()
+    return e0.elapsed_time(e1) / steps * 1e3
+
+
 def measure(wl, binding, args, steps, warmup, module, traffic):
     ring = Ring(wl, binding, args.ring_bytes, module)
     ms = timed_graph(ring, steps, warmup) if args.graph else timed(ring.forward, steps, warmup)
@@ -521,6 +553,11 @@ def main():
             "module_prepared_bias_cold_us": step_time(wl, binding, args.ring_bytes, k, w, True, True) * 1e3,
         }
         line["variants"]["tiny_single_call_latency_us"] = single_call_latency_us(inputs.WORKLOADS["tiny"], binding)
+        try:      # two library GEMMs around the operator; not part of the headline figure
+            line["variants"]["with_projections_hot_us"] = module_with_projections_us(wl, binding)
+        except Exception as e:      # the BLAS library is an optional dependency of that entry point alone
+            line["variants"]["with_projections_hot_us"] = None
+            line["variants"]["with_projections_note"] = repr(e)[:120]
         others = {}
         for name in names[1:]:
             w2 = inputs.WORKLOADS[name]
