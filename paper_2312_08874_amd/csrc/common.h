@@ -60,6 +60,8 @@ struct Layout {
   __host__ __device__ int pitch(int gw) const { return line == 0 ? gw : line; }
 };
 
+constexpr int kComputeUnits = 256;      // MI355X
+
 // ---------------------------------------------------------------------------
 // XCD-aware block numbering.  The 256 CUs sit in eight XCDs, each with an L2 of its own, and the blocks of a
 // 1-D grid are handed to the XCDs in turn (block L to XCD L % 8).  Blocks that read the same data ("members" of a
