@@ -399,14 +399,17 @@ def test_forward_stress_distributions(aa, oracle, scale_qk, v_mean):
 
 @pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f16", 40)])
 @pytest.mark.parametrize("kind", ["scaled x4", "scaled x8", "rising along tokens and agents"])
-def test_large_agent_kernels_growing_maxima(aa, oracle, kind, dtype, d):
+@pytest.mark.parametrize("units,grid", [((1, 2), (48, 32)), ((3, 12), (64, 32))], ids=["few blocks", "more blocks than CUs"])
+def test_large_agent_kernels_growing_maxima(aa, oracle, kind, dtype, d, units, grid):
     """Many agents (the large-agent kernels) with scores that keep outgrowing the running maximum: those kernels
     compute a tile's weights with the old maximum first and fall back to a slow path (scores taken again, maximum
     raised, accumulators rescaled) only when a weight comes out too large.  Peaky inputs and inputs whose scores
-    rise along the token axis (aggregation) and along the agent axis (broadcast) take that path again and again."""
+    rise along the token axis (aggregation) and along the agent axis (broadcast) take that path again and again.
+    The broadcast has two builds of its chunk loop: with more 256-token blocks than the chip has CUs (the second
+    shape: 36 units x 8 blocks) it runs the one that fits two blocks on a CU, whose slow path is a pass of its own."""
     import dataclasses
-    wl = dataclasses.replace(WL["sd_latent"], batch=1, heads=2, grid=(48, 32), agent_grid=(16, 16), d=d, dtype=dtype,
-                             index=14)
+    wl = dataclasses.replace(WL["sd_latent"], batch=units[0], heads=units[1], grid=grid, agent_grid=(16, 16), d=d,
+                             dtype=dtype, index=14)
     assert "large_aggregate" in aa.plan_str(aa.make_desc(wl.batch, wl.heads, wl.N, wl.n, d, 1 if dtype == "f16" else 2,
                                                          wl.grid, wl.agent_grid))
     scale = {"scaled x4": 4.0, "scaled x8": 8.0}.get(kind, 1.0)
