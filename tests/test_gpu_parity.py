@@ -397,7 +397,7 @@ def test_forward_stress_distributions(aa, oracle, scale_qk, v_mean):
                        max_abs=1e-2 * max(1.0, float(np.abs(ref2).max())))
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f16", 40)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f16", 40), ("bf16", 32)])
 @pytest.mark.parametrize("kind", ["scaled x4", "scaled x8", "rising along tokens and agents"])
 @pytest.mark.parametrize("units,grid", [((1, 2), (48, 32)), ((3, 12), (64, 32))], ids=["few blocks", "more blocks than CUs"])
 def test_large_agent_kernels_growing_maxima(aa, oracle, kind, dtype, d, units, grid):
