@@ -40,6 +40,7 @@ enum Path { PATH_GENERIC = 0, PATH_SMALL_FUSED = 1, PATH_SMALL_SPLIT = 2 };
 constexpr size_t kNone = ~(size_t)0;
 struct BiasPlan {
   size_t B1d = kNone, B2d = kNone, H1 = kNone, R1 = kNone, H2 = kNone, R2 = kNone;
+  size_t WT = kNone, K1 = kNone, K2 = kNone;      // matrix form of the block component (BiasArgs::wt / blkop)
   size_t total = 0;
 };
 
@@ -203,6 +204,8 @@ void plan_large(const aa_desc* d, Plan& pl) {
 // (it is read once per batch element; beyond the cap the kernels evaluate the components per score).
 constexpr size_t kBiasDenseCapBytes = (size_t)2 << 30;
 
+int padded_width(int d);
+
 BiasPlan plan_bias(const aa_desc* d, const aa_params* params) {
   BiasPlan bp;
   size_t off = 0;
@@ -219,8 +222,19 @@ BiasPlan plan_bias(const aa_desc* d, const aa_params* params) {
     if (half_form) {
       const bool blk = kind == 1 ? params->b1_blk != nullptr : params->b2_blk != nullptr;
       const bool row = kind == 1 ? params->b1_row != nullptr : params->b2_row != nullptr;
+      // block component through the matrix pipe (two more k-steps of the score products) when its grid has at
+      // most 64 cells and the head width pads to 64; the half-resized table then holds the column component only
+      const bool matrix = kind == 1 && blk && params->blk_h0 * params->blk_w0 <= 64 && padded_width(d->d) == 64;
+      if (matrix) {
+        if (bp.WT == kNone) {
+          bp.WT = off;
+          off += align_up(aa::bias_wt_bytes(d->N));
+        }
+        (kind == 1 ? bp.K1 : bp.K2) = off;
+        off += align_up(aa::bias_blkop_bytes(d->heads, d->n));
+      }
       (kind == 1 ? bp.H1 : bp.H2) = off;
-      off += align_up(aa::bias_half_floats(d->heads, d->n, d->grid_w, blk ? params->blk_h0 : 1) * sizeof(float));
+      off += align_up(aa::bias_half_floats(d->heads, d->n, d->grid_w, blk && !matrix ? params->blk_h0 : 1) * sizeof(float));
       if (row) {
         (kind == 1 ? bp.R1 : bp.R2) = off;
         off += align_up(aa::bias_rows_floats(d->heads, d->n, d->grid_h) * sizeof(float));
@@ -548,21 +562,32 @@ aa_status prepare_bias_tables(Problem& pr, const BiasPlan& bp, void* base_ptr, b
   float* h2 = at(bp.H2, pr.b2.any());
   float* r1 = at(bp.R1, h1 != nullptr);
   float* r2 = at(bp.R2, h2 != nullptr);
+  uint16_t* k1 = (uint16_t*)at(bp.K1, pr.b1.any());
+  uint16_t* k2 = (uint16_t*)at(bp.K2, pr.b2.any());
+  uint16_t* wt = (uint16_t*)at(bp.WT, k1 != nullptr || k2 != nullptr);
   if (build) {
     AA_HIP(aa::launch_bias_dense(pr, d1, d2, st));
-    AA_HIP(aa::launch_bias_half(pr, h1, r1, h2, r2, st));
+    Problem colrow = pr;      // a kind in matrix form keeps its block component out of the half-resized table
+    if (k1) colrow.b1.blk = nullptr;
+    if (k2) colrow.b2.blk = nullptr;
+    AA_HIP(aa::launch_bias_half(colrow, h1, r1, h2, r2, st));
+    AA_HIP(aa::launch_bias_matrix(pr, wt, k1, k2, st));
   }
   if (h1) {
     pr.b1.half = h1;
     pr.b1.rows = r1;
-    pr.b1.he = pr.b1.blk ? pr.b1.h0 : 1;
+    pr.b1.he = (pr.b1.blk && !k1) ? pr.b1.h0 : 1;
     pr.b1.ld = aa::round_up64(pr.n);
+    pr.b1.wt = k1 ? wt : nullptr;
+    pr.b1.blkop = k1;
   }
   if (h2) {
     pr.b2.half = h2;
     pr.b2.rows = r2;
-    pr.b2.he = pr.b2.blk ? pr.b2.h0 : 1;
+    pr.b2.he = (pr.b2.blk && !k2) ? pr.b2.h0 : 1;
     pr.b2.ld = aa::round_up64(pr.n);
+    pr.b2.wt = k2 ? wt : nullptr;
+    pr.b2.blkop = k2;
   }
   if (d1) {
     pr.b1.dense = d1;
