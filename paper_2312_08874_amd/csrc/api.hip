@@ -40,7 +40,7 @@ enum Path { PATH_GENERIC = 0, PATH_SMALL_FUSED = 1, PATH_SMALL_SPLIT = 2 };
 constexpr size_t kNone = ~(size_t)0;
 struct BiasPlan {
   size_t B1d = kNone, B2d = kNone, H1 = kNone, R1 = kNone, H2 = kNone, R2 = kNone;
-  size_t WT = kNone, K1 = kNone, K2 = kNone;      // matrix form of the block component (BiasArgs::wt / blkop)
+  size_t WT = kNone, K1 = kNone;      // matrix form of the block component of B1 (BiasArgs::wt / blkop)
   size_t total = 0;
 };
 
@@ -222,15 +222,15 @@ BiasPlan plan_bias(const aa_desc* d, const aa_params* params) {
     if (half_form) {
       const bool blk = kind == 1 ? params->b1_blk != nullptr : params->b2_blk != nullptr;
       const bool row = kind == 1 ? params->b1_row != nullptr : params->b2_row != nullptr;
-      // block component through the matrix pipe (two more k-steps of the score products) when its grid has at
-      // most 64 cells and the head width pads to 64; the half-resized table then holds the column component only
+      // B1's block component goes through the matrix pipe (two more k-steps of the aggregation's score products)
+      // when its grid has at most 64 cells and the head width pads to 64; the half-resized table then holds the
+      // column component only.  (Not B2: in the broadcast's orientation a lane owns a token, the column and row
+      // pieces it needs per agent tile stay the same 16-byte loads, and the same change measured no gain there.)
       const bool matrix = kind == 1 && blk && params->blk_h0 * params->blk_w0 <= 64 && padded_width(d->d) == 64;
       if (matrix) {
-        if (bp.WT == kNone) {
-          bp.WT = off;
-          off += align_up(aa::bias_wt_bytes(d->N));
-        }
-        (kind == 1 ? bp.K1 : bp.K2) = off;
+        bp.WT = off;
+        off += align_up(aa::bias_wt_bytes(d->N));
+        bp.K1 = off;
         off += align_up(aa::bias_blkop_bytes(d->heads, d->n));
       }
       (kind == 1 ? bp.H1 : bp.H2) = off;
@@ -563,15 +563,13 @@ aa_status prepare_bias_tables(Problem& pr, const BiasPlan& bp, void* base_ptr, b
   float* r1 = at(bp.R1, h1 != nullptr);
   float* r2 = at(bp.R2, h2 != nullptr);
   uint16_t* k1 = (uint16_t*)at(bp.K1, pr.b1.any());
-  uint16_t* k2 = (uint16_t*)at(bp.K2, pr.b2.any());
-  uint16_t* wt = (uint16_t*)at(bp.WT, k1 != nullptr || k2 != nullptr);
+  uint16_t* wt = (uint16_t*)at(bp.WT, k1 != nullptr);
   if (build) {
     AA_HIP(aa::launch_bias_dense(pr, d1, d2, st));
     Problem colrow = pr;      // a kind in matrix form keeps its block component out of the half-resized table
     if (k1) colrow.b1.blk = nullptr;
-    if (k2) colrow.b2.blk = nullptr;
     AA_HIP(aa::launch_bias_half(colrow, h1, r1, h2, r2, st));
-    AA_HIP(aa::launch_bias_matrix(pr, wt, k1, k2, st));
+    AA_HIP(aa::launch_bias_matrix(pr, wt, k1, st));
   }
   if (h1) {
     pr.b1.half = h1;
@@ -584,10 +582,8 @@ aa_status prepare_bias_tables(Problem& pr, const BiasPlan& bp, void* base_ptr, b
   if (h2) {
     pr.b2.half = h2;
     pr.b2.rows = r2;
-    pr.b2.he = (pr.b2.blk && !k2) ? pr.b2.h0 : 1;
+    pr.b2.he = pr.b2.blk ? pr.b2.h0 : 1;
     pr.b2.ld = aa::round_up64(pr.n);
-    pr.b2.wt = k2 ? wt : nullptr;
-    pr.b2.blkop = k2;
   }
   if (d1) {
     pr.b1.dense = d1;

@@ -125,11 +125,11 @@ struct BiasArgs {
   const float* half;
   const float* rows;
   int he;
-  // matrix form of the block component (large-agent kernels, head width padded to 64): the bilinear resize is a
+  // matrix form of B1's block component (large aggregation, head width padded to 64): the bilinear resize is a
   // product  W[token][k] * blk[agent][k]  over the k = h0 * w0 <= 64 cells of the block grid, so it rides the score
   // MFMAs as two more k-steps.  wt: [N][64] fp16 interpolation weights (at most four non-zero per token);
-  // blkop: [heads][n_pad][64] fp16 block values times log2 e (kind 1: plain rows; kind 2: 16-byte pieces permuted
-  // as the broadcast's agent rows are).  half / rows then carry the column and row components only (he = 1).
+  // blkop: [heads][n_pad][64] fp16 block values times log2 e.  half / rows then carry the column and row
+  // components only (he = 1).
   const uint16_t* wt = nullptr;
   const uint16_t* blkop = nullptr;
   __host__ __device__ bool any() const { return col || row || blk; }

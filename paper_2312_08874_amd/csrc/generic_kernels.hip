@@ -491,29 +491,26 @@ hipError_t launch_bias_half(const Problem& p, float* half1, float* rows1, float*
 }
 
 // ---------------------------------------------------------------------------
-// Matrix form of the block component (see BiasArgs::wt / blkop): one thread per 16 bytes (eight fp16 values).
-// Segments: the token weights [N][64]; the kind-1 block operand [heads][n_pad][64]; the kind-2 block operand, whose
-// rows are stored the way the large broadcast stores its agent rows (16-byte piece p of row a in slot
-// p ^ ((a & 15) >> 1), the LDS permutation of 128-byte rows).  A null output skips a segment.
+// Matrix form of B1's block component (see BiasArgs::wt / blkop): one thread per 16 bytes (eight fp16 values).
+// Segments: the token weights [N][64], then the block operand [heads][n_pad][64] (times log2 e).
 // ---------------------------------------------------------------------------
 constexpr int kBiasK = 64;      // k-slots of the matrix form
 __device__ __forceinline__ uint16_t f16_bits(float v) {
   const _Float16 h = (_Float16)v;
   return __builtin_bit_cast(uint16_t, h);
 }
-__global__ __launch_bounds__(256) void bias_matrix_kernel(uint16_t* __restrict__ wt, uint16_t* __restrict__ k1,
-                                                          uint16_t* __restrict__ k2, BiasArgs b1, BiasArgs b2, int heads,
-                                                          int n, int N, int gh, int gw, int h0, int w0, unsigned q_wt,
-                                                          unsigned q_k) {
+__global__ __launch_bounds__(256) void bias_matrix_kernel(uint16_t* __restrict__ wt, uint16_t* __restrict__ k1, BiasArgs b1,
+                                                          int n, int gh, int gw, unsigned q_wt, unsigned q_k) {
   unsigned q = blockIdx.x * 256u + threadIdx.x;
-  const unsigned seg[3] = {wt ? q_wt : 0u, k1 ? q_k : 0u, k2 ? q_k : 0u};
-  int which = 0;
-  while (which < 3 && q >= seg[which]) q -= seg[which++];
-  if (which == 3) return;
+  const bool weights = q < q_wt;
+  if (!weights) {
+    q -= q_wt;
+    if (q >= q_k) return;
+  }
   const unsigned piece = q & 7u, row = q >> 3;
+  const int h0 = b1.h0, w0 = b1.w0;
   uint16_t out[8];
-  uint16_t* dst;
-  if (which == 0) {      // row = token
+  if (weights) {      // row = token
     const int y = (int)row / gw, x = (int)row - y * gw;
     int i0, i1, j0, j1;
     float fy, fx;
@@ -530,36 +527,30 @@ __global__ __launch_bounds__(256) void bias_matrix_kernel(uint16_t* __restrict__
       }
       out[e] = f16_bits(v);
     }
-    dst = wt + (size_t)row * kBiasK + 8 * piece;
-  } else {               // row = (head, padded agent)
+  } else {            // row = (head, padded agent)
     const unsigned NA = (unsigned)round_up64(n), a = row % NA, hd = row / NA;
-    const bool first = which == 1;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int k = 8 * (int)piece + e;
       float v = 0.0f;
-      if ((int)a < n && k < h0 * w0)
-        v = first ? b1.blk[((size_t)hd * n + a) * h0 * w0 + k] : b2.blk[((size_t)hd * h0 * w0 + k) * n + a];
+      if ((int)a < n && k < h0 * w0) v = b1.blk[((size_t)hd * n + a) * h0 * w0 + k];
       out[e] = f16_bits(v * kLog2e);
     }
-    const unsigned slot = first ? piece : (piece ^ ((a & 15u) >> 1));
-    dst = (first ? k1 : k2) + (size_t)row * kBiasK + 8 * slot;
   }
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  *(u32x4*)dst = u32x4{(uint32_t)out[0] | ((uint32_t)out[1] << 16), (uint32_t)out[2] | ((uint32_t)out[3] << 16),
-                       (uint32_t)out[4] | ((uint32_t)out[5] << 16), (uint32_t)out[6] | ((uint32_t)out[7] << 16)};
+  *(u32x4*)((weights ? wt : k1) + (size_t)row * kBiasK + 8 * piece) =
+      u32x4{(uint32_t)out[0] | ((uint32_t)out[1] << 16), (uint32_t)out[2] | ((uint32_t)out[3] << 16),
+            (uint32_t)out[4] | ((uint32_t)out[5] << 16), (uint32_t)out[6] | ((uint32_t)out[7] << 16)};
 }
 
 size_t bias_wt_bytes(int N) { return (size_t)N * kBiasK * 2; }
 size_t bias_blkop_bytes(int heads, int n) { return (size_t)heads * round_up64(n) * kBiasK * 2; }
 
-hipError_t launch_bias_matrix(const Problem& p, uint16_t* wt, uint16_t* k1, uint16_t* k2, hipStream_t st) {
+hipError_t launch_bias_matrix(const Problem& p, uint16_t* wt, uint16_t* k1, hipStream_t st) {
+  if (!wt || !k1) return hipSuccess;
   const unsigned q_wt = (unsigned)p.N * 8u, q_k = (unsigned)p.heads * (unsigned)round_up64(p.n) * 8u;
-  const size_t total = (size_t)(wt ? q_wt : 0) + (k1 ? q_k : 0) + (k2 ? q_k : 0);
-  if (total == 0) return hipSuccess;
-  const int h0 = p.b1.blk ? p.b1.h0 : p.b2.h0, w0 = p.b1.blk ? p.b1.w0 : p.b2.w0;
-  bias_matrix_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(wt, k1, k2, p.b1, p.b2, p.heads, p.n, p.N,
-                                                                                 p.gh, p.gw, h0, w0, q_wt, q_k);
+  const size_t total = (size_t)q_wt + q_k;
+  bias_matrix_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(wt, k1, p.b1, p.n, p.gh, p.gw, q_wt, q_k);
   return hipGetLastError();
 }
 

@@ -60,10 +60,10 @@ hipError_t launch_restride(const Problem& p, bool to_dense, bool out_layout, con
 size_t bias_half_floats(int heads, int n, int gw, int he);
 size_t bias_rows_floats(int heads, int n, int gh);
 hipError_t launch_bias_half(const Problem& p, float* half1, float* rows1, float* half2, float* rows2, hipStream_t st);
-// matrix form of the block component (BiasArgs::wt / blkop): token weights, kind-1 and kind-2 block operands
+// matrix form of B1's block component (BiasArgs::wt / blkop): token weights and block operand
 size_t bias_wt_bytes(int N);
 size_t bias_blkop_bytes(int heads, int n);
-hipError_t launch_bias_matrix(const Problem& p, uint16_t* wt, uint16_t* k1, uint16_t* k2, hipStream_t st);
+hipError_t launch_bias_matrix(const Problem& p, uint16_t* wt, uint16_t* k1, hipStream_t st);
 hipError_t launch_aggregate_generic(const Problem& p, const void* A, const void* Alo, const void* K, const void* V,
                                     const Partials& part, float* VA_direct, hipStream_t st);
 hipError_t launch_merge_generic(const Problem& p, const Partials& part, float* VA, hipStream_t st);

@@ -253,13 +253,17 @@ def test_module_terms_one_at_a_time(aa, oracle, which, dtype, d):
 
 @pytest.mark.parametrize("dtype,d", [("f16", 32), ("bf16", 64), ("bf16", 40)])
 @pytest.mark.parametrize("grid,agrid,blk", [((13, 12), (9, 9), (4, 3)), ((20, 16), (10, 13), (7, 7)),
-                                            ((9, 24), (5, 13), (1, 1)), ((15, 15), (10, 13), (4, 3))])
+                                            ((9, 24), (5, 13), (1, 1)), ((15, 15), (10, 13), (4, 3)),
+                                            ((16, 16), (9, 9), (8, 8)), ((16, 16), (9, 9), (9, 9))])
 @pytest.mark.parametrize("which", ["b1_col", "b1_row", "b1_blk", "b2_col", "b2_row", "b2_blk", "all"])
 def test_module_terms_many_agents(aa, oracle, which, grid, agrid, blk, dtype, d):
     """Agent bias with more than 64 agents: the kernels read tables of the column and block components
     interpolated along x and interpolate along y themselves (grids whose width is a multiple of four;
-    the last grid takes the other route).  Token counts off the 64-token tile, agent counts off the
-    16-agent tile and beyond the last 64-agent boundary, a 1 x 1 block."""
+    the (15, 15) grid takes the other route).  Token counts off the 64-token tile, agent counts off the
+    16-agent tile and beyond the last 64-agent boundary, a 1 x 1 block.  Where the head width pads to 64 and the
+    block grid has at most 64 cells, the aggregation takes B1's block component as two more k-steps of its score
+    products (fp16 interpolation weights times fp16 block values): an 8 x 8 block fills those k-steps exactly, a
+    9 x 9 block does not fit and stays on the tables."""
     import dataclasses
     wl = dataclasses.replace(WL["deit_t"], batch=1, heads=2, grid=grid, agent_grid=agrid, d=d, dtype=dtype)
     t = inputs.make_qkv(wl)
