@@ -441,6 +441,22 @@ def test_large_agent_kernels_growing_maxima(aa, oracle, kind, dtype, d, units, g
                        max_abs=1e-2 * max(1.0, float(np.abs(ref).max())))
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f16", 40), ("f16", 24)])
+def test_large_broadcast_two_blocks_per_cu_ragged(aa, oracle, dtype, d):
+    """The broadcast build that shares a CU between two blocks (more 256-token blocks than CUs: 36 units x 8) on a
+    shape off every tile: 2000 tokens (the last block and its last wave are partial), 130 agents (the last chunk
+    of 64 holds two agents, the rest is padding that must be masked), ragged pooling windows."""
+    import dataclasses
+    wl = dataclasses.replace(WL["sd_latent"], batch=3, heads=12, grid=(50, 40), agent_grid=(13, 10), d=d, dtype=dtype,
+                             index=21)
+    t = inputs.make_qkv(wl)
+    dv = dev_qkv(wl, t)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], grid=wl.grid, agent_grid=wl.agent_grid)
+    ref = oracle.agent_attn_fwd(*(inputs.to_float64(t[k], wl.dtype) for k in ("Q", "K", "V")), heads=wl.heads,
+                                grid=wl.grid, agent_grid=wl.agent_grid)
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, dtype, "ragged, two blocks per CU")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("grid,agrid,d", [((1, 1), (1, 1), 8), ((3, 5), (3, 3), 8), ((1, 197), (1, 16), 40),
                                           ((10, 20), (9, 9), 72), ((25, 8), (4, 4), 128), ((56, 56), (3, 3), 32),
