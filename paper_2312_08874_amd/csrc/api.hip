@@ -941,6 +941,9 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
   }
   const bool use_mfma = (pr.dtype == AA_F16 || pr.dtype == AA_BF16) && pr.d % 8 == 0 && aligned16(Q) && aligned16(K) &&
                         aligned16(V) && aligned16(dO) && aligned16(agents);
+  // the path that keeps no attention matrix in memory has the smaller workspace and needs aligned tensors
+  if (aa::backward_fused_supported(pr) && !(use_mfma && aligned16(dQ) && aligned16(dK) && aligned16(dV) && aligned16(dA)))
+    return AA_ERR_UNSUPPORTED;
   AA_HIP(aa::launch_backward(pr, Q, K, V, agents, dO, (float*)(ws + bwd_agents_bytes(desc)), dQ, dK, dV, dA, !pooling,
                              use_mfma, pg, stream));
   if (sdQ) {

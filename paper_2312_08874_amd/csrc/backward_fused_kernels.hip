@@ -1,0 +1,650 @@
+// Backward pass of agent attention without the attention matrices in memory (fp16 / bf16, d a multiple of 8 up
+// to 128, n <= 256, no agent bias, no DWC, no V residual): every score tile is recomputed where it is used.
+//
+// Both stages of agent attention (Sec. 4.1 Eq. (3)) are softmax attentions between the N tokens and the n agents:
+//   aggregation   S1 = c1 A K^T (n x N), P1 = softmax over tokens,  V_A = P1 V
+//   broadcast     S2 = c2 Q A^T (N x n), P2 = softmax over agents,  O   = P2 V_A
+// and the gradient of a softmax attention needs, per score, only  P  and  dS = P o (dP - D)  with D the row sum
+// of P o dP.  For the aggregation D1 = rowsum(dV_A o V_A); for the broadcast D2 is taken with the row's scores.
+// A gradient that is a sum over agents (per token: dQ, dK, dV) is built by a kernel whose waves own 16 tokens
+// and walk over all agents, kept in LDS ("token kernel", tiles agents x tokens); a gradient that is a sum over
+// tokens (per agent: V_A itself, dV_A, dA) by a kernel whose waves own 16 agents and walk over a range of tokens
+// streamed through LDS ("agent kernel", tiles tokens x agents), the ranges' partial sums being added in a
+// fixed order afterwards.  In both the 16 x 16 accumulator tile of a score product already has the lane layout
+// of an MFMA operand whose contraction index runs over the tile's rows, so P and dS go from one product into
+// the next without leaving the registers; the other operand is read from LDS with the transpose read.
+//
+// Launches:  agent<FWD> + merge   V_A, lse1                 (recomputes the forward aggregation)
+//            token<BC>            dQ (without the pooling term), lse2, D2
+//            agent<BC> + reduce   dV_A, D1, dA (broadcast part)
+//            token<AGG>           dK, dV
+//            agent<AGG> + reduce  dA (aggregation part)
+//            pooling adjoint      dQ += Pooling^T(dA)         (Sec. 4.2), when the agents were pooled
+// Scores are taken in the log2 domain (scale * log2 e folded into one multiplication, exp2 for the weights).
+// No atomics: results are bitwise repeatable.
+#include "kernels.h"
+#include "mfma_common.h"
+
+namespace aa {
+
+namespace {
+
+constexpr int kThreads = 256;       // four waves per block
+constexpr float kMasked = 3.0e38f;  // a log-sum-exp that turns every weight of its row into exp2(-huge) = 0
+
+template <int DP>
+struct Geo {
+  static constexpr int LST = DP + 16;      // LDS row stride in elements (16-byte reads of 16 rows and transpose
+                                           // reads of 4 rows x 32 bytes are free of bank conflicts at this stride)
+  static constexpr int KS = DP / 32;       // k-steps of a product over the channels
+  static constexpr int CC = DP / 16;       // 16-channel output tiles
+  static constexpr int CPR = DP / 8;       // 16-byte pieces per row
+};
+
+__device__ __forceinline__ u32x4 load16(const uint16_t* p, bool ok) {
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (ok) v = *reinterpret_cast<const u32x4*>(p);
+  return v;
+}
+
+// rows [row0, row0 + rows) of a dense [rows_total][d] matrix into an LDS image [rows][LST], zeros elsewhere
+template <int DP>
+__device__ __forceinline__ void stage_rows(uint16_t* lds, const uint16_t* src, int row0, int rows, int rows_total, int d,
+                                           int tid) {
+  using G = Geo<DP>;
+  for (int i = tid; i < rows * G::CPR; i += kThreads) {
+    const int r = i / G::CPR, c = i - r * G::CPR;
+    const bool ok = row0 + r < rows_total && c * 8 < d;
+    *reinterpret_cast<u32x4*>(lds + r * G::LST + c * 8) = load16(src + (size_t)(row0 + r) * d + c * 8, ok);
+  }
+}
+
+// MFMA operand of rows [16 * tile, +16) for k-step ks (lane r, g: row r, channels 32 ks + 8 g ...)
+template <int DP>
+__device__ __forceinline__ u32x4 row_operand(const uint16_t* lds, int tile, int ks, int r, int g) {
+  return *reinterpret_cast<const u32x4*>(lds + (16 * tile + r) * Geo<DP>::LST + (4 * ks + g) * 8);
+}
+// Transposed operand: rows of the product = channels [16 cc, +16), contraction slots of lane group g = rows
+// 16 ta + 4 g .. + 3 and 16 tb + 4 g .. + 3 of the LDS image (the rows an accumulator tile pair holds per lane)
+template <int DP>
+__device__ __forceinline__ u32x4 col_operand(const uint16_t* lds, int ta, int tb, int cc, int r, int g) {
+  const int sub = 4 * g + (r >> 2), col = cc * 16 + 4 * (r & 3);
+  const u32x2 lo = lds_read_tr(lds + (16 * ta + sub) * Geo<DP>::LST + col);
+  const u32x2 hi = lds_read_tr(lds + (16 * tb + sub) * Geo<DP>::LST + col);
+  return u32x4{lo[0], lo[1], hi[0], hi[1]};
+}
+template <class E>
+__device__ __forceinline__ u32x2 pack4(float a, float b, float c, float d) {
+  return u32x2{Mx<E>::pack2(a, b), Mx<E>::pack2(c, d)};
+}
+
+enum { kFwd = 0, kBc = 1, kAgg = 2 };
+
+// ---------------------------------------------------------------------------
+// Token kernel.  Block: all agents of a unit in LDS (M1 = A, M2 = V_A for the broadcast, dV_A for the
+// aggregation), four waves of 16 tokens each per 64-token tile, tiles_per_block tiles in turn.
+//   kBc :  X = Q, Y = dO  ->  O1 = c2 dS2 A (fp32 or element type), st1 = lse2, st2 = D2
+//   kAgg:  X = K, Y = V, rs1 = lse1, rs2 = D1  ->  O1 = dK = c1 dS1^T A,  O2 = dV = P1^T dV_A
+// ---------------------------------------------------------------------------
+struct TokenArgs {
+  const uint16_t *X, *Y, *M1, *M2;
+  const float *rs1, *rs2;
+  float *st1, *st2;
+  void *O1, *O2;
+  int N, n, d, nt, tiles_per_block, o1_f32;
+  float sc, oscale;
+};
+
+template <class E, int DP>
+__device__ __forceinline__ void store_token_tile(void* out, bool f32, size_t row, int d, int cc, int g, f32x4 v, bool ok) {
+  const int c = cc * 16 + 4 * g;
+  if (!ok || c >= d) return;
+  if (f32) {
+    *reinterpret_cast<f32x4*>((float*)out + row * d + c) = v;
+  } else {
+    *reinterpret_cast<u32x2*>((uint16_t*)out + row * d + c) = pack4<E>(v[0], v[1], v[2], v[3]);
+  }
+}
+
+template <class E, int DP, int PROB>
+__global__ __launch_bounds__(kThreads) void fused_token_kernel(TokenArgs a) {
+  using G = Geo<DP>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int rows = a.nt * 16;
+  uint16_t* m1 = reinterpret_cast<uint16_t*>(smem);
+  uint16_t* m2 = m1 + rows * G::LST;
+  float* rs = reinterpret_cast<float*>(m2 + rows * G::LST);      // kAgg: lse1[rows], D1[rows]
+  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 15, g = lane >> 4;
+  const size_t ubN = (size_t)u * a.N, ubn = (size_t)u * a.n;
+
+  stage_rows<DP>(m1, a.M1 + ubn * a.d, 0, rows, a.n, a.d, tid);
+  stage_rows<DP>(m2, a.M2 + ubn * a.d, 0, rows, a.n, a.d, tid);
+  if constexpr (PROB == kAgg) {
+    for (int i = tid; i < rows; i += kThreads) {
+      rs[i] = i < a.n ? a.rs1[ubn + i] : kMasked;
+      rs[rows + i] = i < a.n ? a.rs2[ubn + i] : 0.0f;
+    }
+  }
+  __syncthreads();
+
+  const int tile0 = blockIdx.x * a.tiles_per_block;
+  for (int tl = tile0; tl < tile0 + a.tiles_per_block && tl * 64 < a.N; ++tl) {
+    const int t = tl * 64 + w * 16 + r;      // this lane's token (column of every tile below)
+    const bool tok_ok = t < a.N;
+    u32x4 xq[G::KS], yq[G::KS];
+#pragma unroll
+    for (int ks = 0; ks < G::KS; ++ks) {
+      const int c8 = (4 * ks + g) * 8;
+      const bool ok = tok_ok && c8 < a.d;
+      xq[ks] = load16(a.X + (ubN + t) * a.d + c8, ok);
+      yq[ks] = load16(a.Y + (ubN + t) * a.d + c8, ok);
+    }
+
+    if constexpr (PROB == kBc) {
+      f32x4 S[16], dP[16];
+#pragma unroll
+      for (int T = 0; T < 16; ++T) {
+        S[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+        dP[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (T < a.nt) {
+#pragma unroll
+          for (int ks = 0; ks < G::KS; ++ks) {
+            S[T] = Mx<E>::mma(row_operand<DP>(m1, T, ks, r, g), xq[ks], S[T]);
+            dP[T] = Mx<E>::mma(row_operand<DP>(m2, T, ks, r, g), yq[ks], dP[T]);
+          }
+        }
+      }
+      // softmax over the agents of this lane's token: rows 16 T + 4 g + i, spread over the four lane groups
+      float m = -INFINITY;
+#pragma unroll
+      for (int T = 0; T < 16; ++T)
+        if (T < a.nt) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float s = (16 * T + 4 * g + i < a.n) ? S[T][i] * a.sc : -INFINITY;
+            S[T][i] = s;
+            m = fmaxf(m, s);
+          }
+        }
+      m = xor16_32_max(m);
+      float l = 0.f, dn = 0.f;
+#pragma unroll
+      for (int T = 0; T < 16; ++T)
+        if (T < a.nt) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float p = fast_exp2(S[T][i] - m);
+            S[T][i] = p;
+            l += p;
+            dn += p * dP[T][i];
+          }
+        }
+      l = xor16_32_sum(l);
+      dn = xor16_32_sum(dn);
+      const float inv = 1.0f / l, D = dn * inv;
+      if (g == 0 && tok_ok) {
+        a.st1[ubN + t] = m + __builtin_amdgcn_logf(l);      // v_log_f32: log2
+        a.st2[ubN + t] = D;
+      }
+      u32x2 ds[16];
+#pragma unroll
+      for (int T = 0; T < 16; ++T) {
+        ds[T] = u32x2{0u, 0u};
+        if (T < a.nt) {
+          const f32x4 p = S[T] * inv, q = dP[T];
+          ds[T] = pack4<E>(p[0] * (q[0] - D), p[1] * (q[1] - D), p[2] * (q[2] - D), p[3] * (q[3] - D));
+        }
+      }
+#pragma unroll
+      for (int cc = 0; cc < G::CC; ++cc) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int T = 0; T < 16; T += 2)
+          if (T < a.nt)
+            acc = Mx<E>::mma(col_operand<DP>(m1, T, T + 1, cc, r, g), u32x4{ds[T][0], ds[T][1], ds[T + 1][0], ds[T + 1][1]},
+                             acc);
+        store_token_tile<E, DP>(a.O1, a.o1_f32 != 0, ubN + t, a.d, cc, g, acc * a.oscale, tok_ok);
+      }
+    } else {
+      f32x4 accK[G::CC], accV[G::CC];
+#pragma unroll
+      for (int cc = 0; cc < G::CC; ++cc) accK[cc] = accV[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int T = 0; T < a.nt; T += 2) {
+        u32x2 pp[2], dd[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          f32x4 s = {0.f, 0.f, 0.f, 0.f}, q = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < G::KS; ++ks) {
+            s = Mx<E>::mma(row_operand<DP>(m1, T + h, ks, r, g), xq[ks], s);
+            q = Mx<E>::mma(row_operand<DP>(m2, T + h, ks, r, g), yq[ks], q);
+          }
+          const f32x4 lse = *reinterpret_cast<const f32x4*>(rs + 16 * (T + h) + 4 * g);
+          const f32x4 d1 = *reinterpret_cast<const f32x4*>(rs + rows + 16 * (T + h) + 4 * g);
+          float p[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) p[i] = fast_exp2(s[i] * a.sc - lse[i]);
+          pp[h] = pack4<E>(p[0], p[1], p[2], p[3]);
+          dd[h] = pack4<E>(p[0] * (q[0] - d1[0]), p[1] * (q[1] - d1[1]), p[2] * (q[2] - d1[2]), p[3] * (q[3] - d1[3]));
+        }
+        const u32x4 pop = {pp[0][0], pp[0][1], pp[1][0], pp[1][1]}, dop = {dd[0][0], dd[0][1], dd[1][0], dd[1][1]};
+#pragma unroll
+        for (int cc = 0; cc < G::CC; ++cc) {
+          accK[cc] = Mx<E>::mma(col_operand<DP>(m1, T, T + 1, cc, r, g), dop, accK[cc]);
+          accV[cc] = Mx<E>::mma(col_operand<DP>(m2, T, T + 1, cc, r, g), pop, accV[cc]);
+        }
+      }
+#pragma unroll
+      for (int cc = 0; cc < G::CC; ++cc) {
+        store_token_tile<E, DP>(a.O1, false, ubN + t, a.d, cc, g, accK[cc] * a.oscale, tok_ok);
+        store_token_tile<E, DP>(a.O2, false, ubN + t, a.d, cc, g, accV[cc], tok_ok);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Agent kernel.  Grid (token ranges, blocks of 64 agents, units); each wave keeps its 16 agents' rows of M1
+// (and M2) in registers as operands and walks over its range in tiles of 32 tokens staged through LDS
+// (two buffers, one barrier per tile).
+//   kFwd:  X = K, Y = V            ->  P1 = sum_t w V (unnormalised, running maximum pm, weight sum pl)
+//   kBc :  X = Q, Y = dO, M2 = V_A, ts1 = lse2, ts2 = D2  ->  P1 = sum_t P2 dO,  P2 = sum_t dS2 Q
+//   kAgg:  X = K, Y = V,  M2 = dV_A, rs1 = lse1, rs2 = D1 ->  P1 = sum_t dS1 K
+// Partial sums are rows [unit][range][agent][d] of fp32.
+// ---------------------------------------------------------------------------
+struct AgentArgs {
+  const uint16_t *X, *Y, *M1, *M2;
+  const float *ts1, *ts2, *rs1, *rs2;
+  float *P1, *P2, *pm, *pl;
+  int N, n, d, chunk, S;
+  float sc;
+};
+
+template <class E, int DP, int PROB>
+__global__ __launch_bounds__(kThreads) void fused_agent_kernel(AgentArgs a) {
+  using G = Geo<DP>;
+  constexpr int kTileRows = 32;
+  constexpr int kPieces = kTileRows * G::CPR;
+  constexpr int NLD = (kPieces + kThreads - 1) / kThreads;
+  constexpr int kImage = kTileRows * G::LST;      // elements per staged tile
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint16_t* xt = reinterpret_cast<uint16_t*>(smem);              // [2][32][LST]
+  uint16_t* yt = xt + 2 * kImage;                                  // [2][32][LST]
+  float* ts = reinterpret_cast<float*>(yt + 2 * kImage);          // kBc: [2][2][32]
+  const int s = blockIdx.x, ab = blockIdx.y, u = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 15, g = lane >> 4;
+  const size_t ubN = (size_t)u * a.N, ubn = (size_t)u * a.n;
+  const int agent = ab * 64 + w * 16 + r;
+  const bool ag_ok = agent < a.n;
+  const int t_beg = s * a.chunk, t_end = min(a.N, t_beg + a.chunk);
+  const int ntile = (t_end - t_beg + kTileRows - 1) / kTileRows;
+
+  u32x4 a1[G::KS], a2[G::KS];
+#pragma unroll
+  for (int ks = 0; ks < G::KS; ++ks) {
+    const int c8 = (4 * ks + g) * 8;
+    const bool ok = ag_ok && c8 < a.d;
+    a1[ks] = load16(a.M1 + (ubn + agent) * a.d + c8, ok);
+    a2[ks] = u32x4{0u, 0u, 0u, 0u};
+    if constexpr (PROB != kFwd) a2[ks] = load16(a.M2 + (ubn + agent) * a.d + c8, ok);
+  }
+  float lse_a = kMasked, d_a = 0.f;
+  if constexpr (PROB == kAgg) {
+    if (ag_ok) {
+      lse_a = a.rs1[ubn + agent];
+      d_a = a.rs2[ubn + agent];
+    }
+  }
+
+  u32x4 xr[NLD], yr[NLD];
+  float sr = 0.f;
+  auto fetch = [&](int it) {
+    const int t0 = t_beg + it * kTileRows;
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+      const int i = tid + j * kThreads;
+      const int row = i / G::CPR, c = i - row * G::CPR;
+      const bool ok = i < kPieces && t0 + row < t_end && c * 8 < a.d;
+      xr[j] = load16(a.X + (ubN + t0 + row) * a.d + c * 8, ok);
+      yr[j] = load16(a.Y + (ubN + t0 + row) * a.d + c * 8, ok);
+    }
+    if constexpr (PROB == kBc) {
+      if (tid < 64) {
+        const int tt = t0 + (tid & 31);
+        sr = tid < 32 ? kMasked : 0.f;
+        if (tt < t_end) sr = (tid < 32 ? a.ts1 : a.ts2)[ubN + tt];
+      }
+    }
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+      const int i = tid + j * kThreads;
+      if (i < kPieces) {
+        const int row = i / G::CPR, c = i - row * G::CPR;
+        *reinterpret_cast<u32x4*>(xt + buf * kImage + row * G::LST + c * 8) = xr[j];
+        *reinterpret_cast<u32x4*>(yt + buf * kImage + row * G::LST + c * 8) = yr[j];
+      }
+    }
+    if constexpr (PROB == kBc) {
+      if (tid < 64) ts[buf * 64 + tid] = sr;
+    }
+  };
+
+  f32x4 acc1[G::CC], acc2[G::CC];
+#pragma unroll
+  for (int cc = 0; cc < G::CC; ++cc) acc1[cc] = acc2[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;
+
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int it = 0; it < ntile; ++it) {
+    const int buf = it & 1;
+    if (it + 1 < ntile) fetch(it + 1);
+    const uint16_t* xb = xt + buf * kImage;
+    const uint16_t* yb = yt + buf * kImage;
+    const int t0 = t_beg + it * kTileRows;
+    f32x4 sv[2], qv[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      sv[j] = qv[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < G::KS; ++ks) {
+        sv[j] = Mx<E>::mma(row_operand<DP>(xb, j, ks, r, g), a1[ks], sv[j]);
+        if constexpr (PROB != kFwd) qv[j] = Mx<E>::mma(row_operand<DP>(yb, j, ks, r, g), a2[ks], qv[j]);
+      }
+    }
+    // this lane: agent `agent`, tokens t0 + 16 j + 4 g + i
+    u32x4 pop, dop = {0u, 0u, 0u, 0u};
+    if constexpr (PROB == kFwd) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float sc = (t0 + 16 * j + 4 * g + i < t_end) ? sv[j][i] * a.sc : -INFINITY;
+          sv[j][i] = sc;
+          mx = fmaxf(mx, sc);
+        }
+      mx = xor16_32_max(mx);
+      const float m_new = fmaxf(m_run, mx);      // finite: the tile holds at least one token of the range
+      const float alpha = fast_exp2(m_run - m_new);
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          sv[j][i] = fast_exp2(sv[j][i] - m_new);
+          sum += sv[j][i];
+        }
+      l_run = l_run * alpha + sum;      // per lane group; the groups are added at the end
+      m_run = m_new;
+#pragma unroll
+      for (int cc = 0; cc < G::CC; ++cc) acc1[cc] *= alpha;
+      const u32x2 p0 = pack4<E>(sv[0][0], sv[0][1], sv[0][2], sv[0][3]), p1 = pack4<E>(sv[1][0], sv[1][1], sv[1][2], sv[1][3]);
+      pop = u32x4{p0[0], p0[1], p1[0], p1[1]};
+    } else {
+      u32x2 pp[2], dd[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        float p[4], e[4];
+        if constexpr (PROB == kBc) {
+          const f32x4 lse = *reinterpret_cast<const f32x4*>(ts + buf * 64 + 16 * j + 4 * g);
+          const f32x4 d2 = *reinterpret_cast<const f32x4*>(ts + buf * 64 + 32 + 16 * j + 4 * g);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            p[i] = fast_exp2(sv[j][i] * a.sc - lse[i]);
+            e[i] = p[i] * (qv[j][i] - d2[i]);
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            p[i] = (t0 + 16 * j + 4 * g + i < t_end) ? fast_exp2(sv[j][i] * a.sc - lse_a) : 0.f;
+            e[i] = p[i] * (qv[j][i] - d_a);
+          }
+        }
+        pp[j] = pack4<E>(p[0], p[1], p[2], p[3]);
+        dd[j] = pack4<E>(e[0], e[1], e[2], e[3]);
+      }
+      pop = u32x4{pp[0][0], pp[0][1], pp[1][0], pp[1][1]};
+      dop = u32x4{dd[0][0], dd[0][1], dd[1][0], dd[1][1]};
+    }
+#pragma unroll
+    for (int cc = 0; cc < G::CC; ++cc) {
+      if constexpr (PROB == kFwd) acc1[cc] = Mx<E>::mma(col_operand<DP>(yb, 0, 1, cc, r, g), pop, acc1[cc]);
+      if constexpr (PROB == kBc) {
+        acc1[cc] = Mx<E>::mma(col_operand<DP>(yb, 0, 1, cc, r, g), pop, acc1[cc]);
+        acc2[cc] = Mx<E>::mma(col_operand<DP>(xb, 0, 1, cc, r, g), dop, acc2[cc]);
+      }
+      if constexpr (PROB == kAgg) acc1[cc] = Mx<E>::mma(col_operand<DP>(xb, 0, 1, cc, r, g), dop, acc1[cc]);
+    }
+    if (it + 1 < ntile) stash(buf ^ 1);
+    __syncthreads();
+  }
+
+  // lane (r, g): agent `agent`, channels 16 cc + 4 g .. + 3
+  const size_t prow = ((size_t)u * a.S + s) * a.n + agent;
+  if constexpr (PROB == kFwd) {
+    l_run = xor16_32_sum(l_run);
+    if (g == 0 && ag_ok) {
+      a.pm[prow] = m_run;
+      a.pl[prow] = l_run;
+    }
+  }
+#pragma unroll
+  for (int cc = 0; cc < G::CC; ++cc) {
+    const int c = cc * 16 + 4 * g;
+    if (ag_ok && c < a.d) {
+      *reinterpret_cast<f32x4*>(a.P1 + prow * a.d + c) = acc1[cc];
+      if constexpr (PROB == kBc) *reinterpret_cast<f32x4*>(a.P2 + prow * a.d + c) = acc2[cc];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Sums over the token ranges, one 64-lane block per (agent, unit), lane = channel (and channel + 64), ranges
+// in order.
+// ---------------------------------------------------------------------------
+// log-sum-exp merge of the recomputed aggregation: V_A (fp32 and element type) and lse1 (log2 domain)
+template <class E>
+__global__ __launch_bounds__(64) void fused_merge_kernel(const float* __restrict__ acc, const float* __restrict__ pm,
+                                                         const float* __restrict__ pl, int S, int n, int d,
+                                                         float* __restrict__ VAf, uint16_t* __restrict__ VAe,
+                                                         float* __restrict__ lse1) {
+  const int ag = blockIdx.x, u = blockIdx.y, lane = threadIdx.x;
+  float M = -INFINITY;
+  for (int s = 0; s < S; ++s) M = fmaxf(M, pm[((size_t)u * S + s) * n + ag]);
+  float L = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const size_t row = ((size_t)u * S + s) * n + ag;
+    L += pl[row] * fast_exp2(pm[row] - M);
+  }
+  const float inv = 1.0f / L;
+  for (int c = lane; c < d; c += 64) {
+    float v = 0.f;
+    for (int s = 0; s < S; ++s) {
+      const size_t row = ((size_t)u * S + s) * n + ag;
+      v += acc[row * d + c] * fast_exp2(pm[row] - M);
+    }
+    v *= inv;
+    const size_t o = ((size_t)u * n + ag) * d + c;
+    VAf[o] = v;
+    const typename E::T e = E::from_f32(v);
+    VAe[o] = __builtin_bit_cast(uint16_t, e);
+  }
+  if (lane == 0) lse1[(size_t)u * n + ag] = M + __builtin_amdgcn_logf(L);
+}
+
+// dV_A = sum of the ranges (element type), D1 = rowsum(dV_A o V_A), dA = c2 * sum of the ranges
+template <class E>
+__global__ __launch_bounds__(64) void fused_reduce_bc_kernel(const float* __restrict__ pva, const float* __restrict__ pa,
+                                                             int S, int n, int d, const float* __restrict__ VAf,
+                                                             uint16_t* __restrict__ dVAe, float* __restrict__ D1,
+                                                             float* __restrict__ dAf, float c2) {
+  const int ag = blockIdx.x, u = blockIdx.y, lane = threadIdx.x;
+  float dot = 0.f;
+  for (int c = lane; c < d; c += 64) {
+    float v = 0.f, q = 0.f;
+    for (int s = 0; s < S; ++s) {
+      const size_t i = (((size_t)u * S + s) * n + ag) * d + c;
+      v += pva[i];
+      q += pa[i];
+    }
+    const size_t o = ((size_t)u * n + ag) * d + c;
+    const typename E::T e = E::from_f32(v);
+    dVAe[o] = __builtin_bit_cast(uint16_t, e);
+    dot += E::to_f32(e) * VAf[o];
+    dAf[o] = c2 * q;
+  }
+  dot = wave_sum(dot);
+  if (lane == 0) D1[(size_t)u * n + ag] = dot;
+}
+
+// dA += c1 * sum of the ranges; written in the element type too when the agents were handed in
+template <class E>
+__global__ __launch_bounds__(64) void fused_reduce_agg_kernel(const float* __restrict__ pa, int S, int n, int d,
+                                                              float* __restrict__ dAf, uint16_t* __restrict__ dAe, float c1) {
+  const int ag = blockIdx.x, u = blockIdx.y, lane = threadIdx.x;
+  for (int c = lane; c < d; c += 64) {
+    float q = 0.f;
+    for (int s = 0; s < S; ++s) q += pa[(((size_t)u * S + s) * n + ag) * d + c];
+    const size_t o = ((size_t)u * n + ag) * d + c;
+    const float v = dAf[o] + c1 * q;
+    dAf[o] = v;
+    if (dAe) {
+      const typename E::T e = E::from_f32(v);
+      dAe[o] = __builtin_bit_cast(uint16_t, e);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+struct FusedPlan {
+  int DP, nt, n64, S, chunk, tiles_per_block, token_blocks;
+  // workspace offsets in floats (every region a multiple of 64 floats)
+  size_t VAf, VAe, dVAe, lse1, D1, lse2, D2, dAf, dQf, part, total;
+};
+
+size_t up64(size_t v) { return (v + 63) / 64 * 64; }
+
+FusedPlan fused_plan(const Problem& p, bool pooled) {
+  FusedPlan f{};
+  f.DP = p.d <= 32 ? 32 : (p.d <= 64 ? 64 : 128);
+  f.nt = (p.n + 31) / 32 * 2;      // agent tiles of the token kernel: pairs
+  f.n64 = (p.n + 63) / 64;
+  const int groups = f.n64 * p.units;
+  int S = (2 * kComputeUnits + groups - 1) / groups;      // about two blocks per CU
+  S = min(S, (p.N + 127) / 128);
+  S = max(S, 1);
+  f.chunk = ((p.N + S - 1) / S + 31) / 32 * 32;
+  f.S = (p.N + f.chunk - 1) / f.chunk;
+  const int tiles = (p.N + 63) / 64;
+  f.tiles_per_block = max(1, min(8, (int)((long long)tiles * p.units / (2 * kComputeUnits))));
+  f.token_blocks = (tiles + f.tiles_per_block - 1) / f.tiles_per_block;
+  const size_t u = (size_t)p.units, nd = up64((size_t)p.n * p.d), un = up64(u * p.n), uN = up64(u * p.N);
+  size_t o = 0;
+  f.VAf = o, o += u * nd;
+  f.VAe = o, o += u * nd / 2;
+  f.dVAe = o, o += u * nd / 2;
+  f.lse1 = o, o += un;
+  f.D1 = o, o += un;
+  f.lse2 = o, o += uN;
+  f.D2 = o, o += uN;
+  f.dAf = o, o += u * nd;
+  f.dQf = o, o += pooled ? up64(u * p.N * p.d) : 0;
+  f.part = o, o += up64(u * f.S * p.n * (size_t)(2 * p.d + 2));
+  f.total = o;
+  return f;
+}
+
+template <class E, int DP>
+hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
+                     const uint16_t* A, const uint16_t* dO, float* ws, void* dQ, void* dK, void* dV, void* dA,
+                     bool agents_given, hipStream_t st) {
+  using G = Geo<DP>;
+  const int U = p.units, N = p.N, n = p.n, d = p.d;
+  float* VAf = ws + f.VAf;
+  uint16_t* VAe = reinterpret_cast<uint16_t*>(ws + f.VAe);
+  uint16_t* dVAe = reinterpret_cast<uint16_t*>(ws + f.dVAe);
+  float *lse1 = ws + f.lse1, *D1 = ws + f.D1, *lse2 = ws + f.lse2, *D2 = ws + f.D2, *dAf = ws + f.dAf, *dQf = ws + f.dQf;
+  const size_t part_rows = (size_t)U * f.S * n;
+  float* part1 = ws + f.part;
+  float* part2 = part1 + part_rows * d;
+  float* pm = part1 + part_rows * d;      // kFwd only (part2 is kBc only)
+  float* pl = pm + part_rows;
+  const float sc1 = p.scale1 * kLog2e, sc2 = p.scale2 * kLog2e;
+
+  const size_t agent_lds = (size_t)4 * 32 * G::LST * 2 + 2 * 64 * sizeof(float);
+  const size_t token_lds = (size_t)2 * f.nt * 16 * G::LST * 2 + (size_t)2 * f.nt * 16 * sizeof(float);
+  const dim3 agrid(f.S, f.n64, U), tgrid(f.token_blocks, U), rgrid(n, U);
+  hipError_t e;
+  if ((e = allow_lds(fused_token_kernel<E, DP, kBc>, token_lds)) != hipSuccess) return e;
+  if ((e = allow_lds(fused_token_kernel<E, DP, kAgg>, token_lds)) != hipSuccess) return e;
+
+  AgentArgs ag{};
+  ag.N = N, ag.n = n, ag.d = d, ag.chunk = f.chunk, ag.S = f.S;
+  // the aggregation again: V_A and the log-sum-exp of its rows
+  ag.X = K, ag.Y = V, ag.M1 = A, ag.M2 = nullptr, ag.P1 = part1, ag.pm = pm, ag.pl = pl, ag.sc = sc1;
+  fused_agent_kernel<E, DP, kFwd><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
+  fused_merge_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, pm, pl, f.S, n, d, VAf, VAe, lse1);
+
+  // broadcast: per-token gradient and row statistics, then the per-agent sums
+  TokenArgs tk{};
+  tk.N = N, tk.n = n, tk.d = d, tk.nt = f.nt, tk.tiles_per_block = f.tiles_per_block;
+  tk.X = Q, tk.Y = dO, tk.M1 = A, tk.M2 = VAe, tk.st1 = lse2, tk.st2 = D2, tk.sc = sc2, tk.oscale = p.scale2;
+  tk.O1 = agents_given ? dQ : (void*)dQf, tk.o1_f32 = agents_given ? 0 : 1;
+  fused_token_kernel<E, DP, kBc><<<tgrid, dim3(kThreads), token_lds, st>>>(tk);
+  ag.X = Q, ag.Y = dO, ag.M2 = VAe, ag.ts1 = lse2, ag.ts2 = D2, ag.P1 = part1, ag.P2 = part2, ag.sc = sc2;
+  fused_agent_kernel<E, DP, kBc><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
+  fused_reduce_bc_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, part2, f.S, n, d, VAf, dVAe, D1, dAf, p.scale2);
+
+  // aggregation
+  tk.X = K, tk.Y = V, tk.M2 = dVAe, tk.rs1 = lse1, tk.rs2 = D1, tk.sc = sc1, tk.oscale = p.scale1;
+  tk.O1 = dK, tk.O2 = dV, tk.o1_f32 = 0;
+  fused_token_kernel<E, DP, kAgg><<<tgrid, dim3(kThreads), token_lds, st>>>(tk);
+  ag.X = K, ag.Y = V, ag.M2 = dVAe, ag.rs1 = lse1, ag.rs2 = D1, ag.P1 = part1, ag.sc = sc1;
+  fused_agent_kernel<E, DP, kAgg><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
+  fused_reduce_agg_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, f.S, n, d, dAf, agents_given ? (uint16_t*)dA : nullptr,
+                                                         p.scale1);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (!agents_given) {
+    if ((e = backward_pool_adjoint(p, dQf, dAf, st)) != hipSuccess) return e;
+    if ((e = backward_from_f32(p.dtype, dQf, dQ, (size_t)U * N * d, st)) != hipSuccess) return e;
+  }
+  return hipGetLastError();
+}
+
+template <class E>
+hipError_t run_fused_dp(const Problem& p, const FusedPlan& f, const void* Q, const void* K, const void* V, const void* A,
+                        const void* dO, float* ws, void* dQ, void* dK, void* dV, void* dA, bool agents_given,
+                        hipStream_t st) {
+  const uint16_t *q = (const uint16_t*)Q, *k = (const uint16_t*)K, *v = (const uint16_t*)V, *a = (const uint16_t*)A,
+                 *g = (const uint16_t*)dO;
+  switch (f.DP) {
+    case 32: return run_fused<E, 32>(p, f, q, k, v, a, g, ws, dQ, dK, dV, dA, agents_given, st);
+    case 64: return run_fused<E, 64>(p, f, q, k, v, a, g, ws, dQ, dK, dV, dA, agents_given, st);
+    default: return run_fused<E, 128>(p, f, q, k, v, a, g, ws, dQ, dK, dV, dA, agents_given, st);
+  }
+}
+
+}  // namespace
+
+bool backward_fused_supported(const Problem& p) {
+  return (p.dtype == 1 || p.dtype == 2) && p.d % 8 == 0 && p.d <= 128 && p.n <= 256 && !p.b1.any() && !p.b2.any() &&
+         !p.dwc_w && p.vk == 0.0f;
+}
+
+size_t backward_fused_workspace_floats(const Problem& p, bool pooled) { return fused_plan(p, pooled).total; }
+
+hipError_t launch_backward_fused(const Problem& p, const void* Q, const void* K, const void* V, const void* A_elem,
+                                 const void* dO, float* ws, void* dQ, void* dK, void* dV, void* dA, bool agents_given,
+                                 hipStream_t st) {
+  const FusedPlan f = fused_plan(p, !agents_given);
+  if (p.dtype == 2) return run_fused_dp<ElemBF16>(p, f, Q, K, V, A_elem, dO, ws, dQ, dK, dV, dA, agents_given, st);
+  return run_fused_dp<ElemF16>(p, f, Q, K, V, A_elem, dO, ws, dQ, dK, dV, dA, agents_given, st);
+}
+
+}  // namespace aa
