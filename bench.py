@@ -327,10 +327,9 @@ def measure(wl, binding, args, steps, warmup, module, traffic):
 
 
 def measure_backward(wl, binding, ring, steps, warmup):
-    """agent_attn_bwd on the first input set (same buffers every call: the dense attention matrices in its
-    workspace dwarf the inputs, so a cold ring would add nothing).  20*N*n*d FLOPs per unit in ten matrix
-    products: on MFMA for fp16 / bf16 (priced against the dense MFMA peak), as fp32 vector FMAs for fp32
-    (priced against the fp32 vector peak)."""
+    """agent_attn_bwd on the first input set (same buffers every call).  20*N*n*d FLOPs per unit in ten matrix
+    products (the score tiles a 16-bit pure-mode problem recomputes are not counted): on MFMA for fp16 / bf16
+    (priced against the dense MFMA peak), as fp32 vector FMAs for fp32 (priced against the fp32 vector peak)."""
     import ctypes
     import torch
     s = ring.sets[0]
@@ -343,14 +342,18 @@ def measure_backward(wl, binding, ring, steps, warmup):
         binding.agent_attn_bwd(s["Q"], s["K"], s["V"], dO, grid=wl.grid, agent_grid=wl.agent_grid, params=ring.params,
                                workspace=ws)
     ms = timed(call, steps, warmup)
+    fused = wl.dtype != "f32" and ring.params is None and wl.d % 8 == 0 and wl.d <= 128 and wl.n <= 256
     flops = 20.0 * wl.N * wl.n * wl.d * wl.units
     tf = flops / (ms * 1e-3) / 1e12
     peak = VALU_F32_PEAK_TFLOPS if wl.dtype == "f32" else MFMA_PEAK_TFLOPS
     return {"ms_per_step": ms, "tokens_per_s": wl.batch * wl.N / (ms * 1e-3), "tflops": tf,
             "workspace_bytes": need, "cache": "hot (one input set)",
-            "kernels": "reference-quality: 10 batched matrix products + row softmax / gradient kernels, attention "
-                       "matrices materialised in the workspace",
-            "roofline": {"kernel": "matmul_kernel" if wl.dtype == "f32" else "mfma_matmul_kernel",
+            "kernels": ("token kernels (dQ, dK, dV) + agent kernels (V_A, dV_A, dA) that recompute their score tiles, "
+                        "no attention matrix in memory") if fused else
+                       ("reference-quality: 10 batched matrix products + row softmax / gradient kernels, attention "
+                        "matrices materialised in the workspace"),
+            "roofline": {"kernel": "fused_token_kernel + fused_agent_kernel" if fused else
+                         ("matmul_kernel" if wl.dtype == "f32" else "mfma_matmul_kernel"),
                          "bound": "alu" if wl.dtype == "f32" else "mfma", "achieved": tf, "peak": peak,
                          "unit": "TFLOP/s", "frac": tf / peak, "traffic": None}}
 

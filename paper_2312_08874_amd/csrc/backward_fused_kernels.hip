@@ -1,5 +1,5 @@
 // Backward pass of agent attention without the attention matrices in memory (fp16 / bf16, d a multiple of 8 up
-// to 128, n <= 256, no agent bias, no DWC, no V residual): every score tile is recomputed where it is used.
+// to 128, no agent bias, no DWC, no V residual): every score tile is recomputed where it is used.
 //
 // Both stages of agent attention (Sec. 4.1 Eq. (3)) are softmax attentions between the N tokens and the n agents:
 //   aggregation   S1 = c1 A K^T (n x N), P1 = softmax over tokens,  V_A = P1 V
@@ -7,7 +7,7 @@
 // and the gradient of a softmax attention needs, per score, only  P  and  dS = P o (dP - D)  with D the row sum
 // of P o dP.  For the aggregation D1 = rowsum(dV_A o V_A); for the broadcast D2 is taken with the row's scores.
 // A gradient that is a sum over agents (per token: dQ, dK, dV) is built by a kernel whose waves own 16 tokens
-// and walk over all agents, kept in LDS ("token kernel", tiles agents x tokens); a gradient that is a sum over
+// and walk over all agents, staged through LDS ("token kernel", tiles agents x tokens); a gradient that is a sum over
 // tokens (per agent: V_A itself, dV_A, dA) by a kernel whose waves own 16 agents and walk over a range of tokens
 // streamed through LDS ("agent kernel", tiles tokens x agents), the ranges' partial sums being added in a
 // fixed order afterwards.  In both the 16 x 16 accumulator tile of a score product already has the lane layout
@@ -81,9 +81,10 @@ __device__ __forceinline__ u32x2 pack4(float a, float b, float c, float d) {
 enum { kFwd = 0, kBc = 1, kAgg = 2 };
 
 // ---------------------------------------------------------------------------
-// Token kernel.  Block: all agents of a unit in LDS (M1 = A, M2 = V_A for the broadcast, dV_A for the
-// aggregation), four waves of 16 tokens each per 64-token tile, tiles_per_block tiles in turn.
-//   kBc :  X = Q, Y = dO  ->  O1 = c2 dS2 A (fp32 or element type), st1 = lse2, st2 = D2
+// Token kernel.  Block: 128 tokens of a unit, 32 per wave, held in registers as operands; the unit's agents
+// pass through LDS ch_rows at a time (M1 = A, M2 = V_A for the broadcast, dV_A for the aggregation).
+//   kBc :  X = Q, Y = dO  ->  O1 = c2 dS2 A (fp32 or element type), st1 = lse2, st2 = D2; two passes over the
+//          agents: the rows' statistics first, then dS2
 //   kAgg:  X = K, Y = V, rs1 = lse1, rs2 = D1  ->  O1 = dK = c1 dS1^T A,  O2 = dV = P1^T dV_A
 // ---------------------------------------------------------------------------
 struct TokenArgs {
@@ -91,11 +92,11 @@ struct TokenArgs {
   const float *rs1, *rs2;
   float *st1, *st2;
   void *O1, *O2;
-  int N, n, d, nt, tiles_per_block, o1_f32;
+  int N, n, d, n_rows, ch_rows, o1_f32;      // n_rows: n rounded up to 32; ch_rows: agents staged at a time (x32)
   float sc, oscale;
 };
 
-template <class E, int DP>
+template <class E>
 __device__ __forceinline__ void store_token_tile(void* out, bool f32, size_t row, int d, int cc, int g, f32x4 v, bool ok) {
   const int c = cc * 16 + 4 * g;
   if (!ok || c >= d) return;
@@ -106,140 +107,198 @@ __device__ __forceinline__ void store_token_tile(void* out, bool f32, size_t row
   }
 }
 
+constexpr int kTokCols = 2;                      // 16-token columns per wave: every LDS operand feeds two products
+constexpr int kTokBlock = 4 * 16 * kTokCols;     // tokens per block
+
 template <class E, int DP, int PROB>
 __global__ __launch_bounds__(kThreads) void fused_token_kernel(TokenArgs a) {
   using G = Geo<DP>;
+  constexpr int NK = kTokCols;
   extern __shared__ __align__(16) unsigned char smem[];
-  const int rows = a.nt * 16;
   uint16_t* m1 = reinterpret_cast<uint16_t*>(smem);
-  uint16_t* m2 = m1 + rows * G::LST;
-  float* rs = reinterpret_cast<float*>(m2 + rows * G::LST);      // kAgg: lse1[rows], D1[rows]
+  uint16_t* m2 = m1 + a.ch_rows * G::LST;
+  float* rs = reinterpret_cast<float*>(m2 + a.ch_rows * G::LST);      // kAgg: lse1[ch_rows], D1[ch_rows]
   const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 15, g = lane >> 4;
   const size_t ubN = (size_t)u * a.N, ubn = (size_t)u * a.n;
 
-  stage_rows<DP>(m1, a.M1 + ubn * a.d, 0, rows, a.n, a.d, tid);
-  stage_rows<DP>(m2, a.M2 + ubn * a.d, 0, rows, a.n, a.d, tid);
-  if constexpr (PROB == kAgg) {
-    for (int i = tid; i < rows; i += kThreads) {
-      rs[i] = i < a.n ? a.rs1[ubn + i] : kMasked;
-      rs[rows + i] = i < a.n ? a.rs2[ubn + i] : 0.0f;
-    }
-  }
-  __syncthreads();
-
-  const int tile0 = blockIdx.x * a.tiles_per_block;
-  for (int tl = tile0; tl < tile0 + a.tiles_per_block && tl * 64 < a.N; ++tl) {
-    const int t = tl * 64 + w * 16 + r;      // this lane's token (column of every tile below)
-    const bool tok_ok = t < a.N;
-    u32x4 xq[G::KS], yq[G::KS];
+  // this lane's tokens (the column it holds of every tile below), one per 16-token column of the wave
+  int t[NK];
+  bool tok_ok[NK];
+  u32x4 xq[NK][G::KS], yq[NK][G::KS];
+#pragma unroll
+  for (int k = 0; k < NK; ++k) {
+    t[k] = blockIdx.x * kTokBlock + (w * NK + k) * 16 + r;
+    tok_ok[k] = t[k] < a.N;
 #pragma unroll
     for (int ks = 0; ks < G::KS; ++ks) {
       const int c8 = (4 * ks + g) * 8;
-      const bool ok = tok_ok && c8 < a.d;
-      xq[ks] = load16(a.X + (ubN + t) * a.d + c8, ok);
-      yq[ks] = load16(a.Y + (ubN + t) * a.d + c8, ok);
+      const bool ok = tok_ok[k] && c8 < a.d;
+      xq[k][ks] = load16(a.X + (ubN + t[k]) * a.d + c8, ok);
+      yq[k][ks] = load16(a.Y + (ubN + t[k]) * a.d + c8, ok);
     }
+  }
+  // agents [row0, row0 + ch_rows) into LDS; returns the number of 16-agent tiles staged (even)
+  auto stage = [&](int row0) {
+    __syncthreads();      // the previous chunk has been read by every wave
+    stage_rows<DP>(m1, a.M1 + ubn * a.d, row0, a.ch_rows, a.n, a.d, tid);
+    stage_rows<DP>(m2, a.M2 + ubn * a.d, row0, a.ch_rows, a.n, a.d, tid);
+    if constexpr (PROB == kAgg) {
+      for (int i = tid; i < a.ch_rows; i += kThreads) {
+        rs[i] = row0 + i < a.n ? a.rs1[ubn + row0 + i] : kMasked;
+        rs[a.ch_rows + i] = row0 + i < a.n ? a.rs2[ubn + row0 + i] : 0.0f;
+      }
+    }
+    __syncthreads();
+    return min(a.ch_rows, a.n_rows - row0) / 16;
+  };
+  // both score-side products of agent tile T for the wave's token columns
+  auto products = [&](int T, f32x4 (&s)[NK], f32x4 (&q)[NK]) {
+    u32x4 o1[G::KS], o2[G::KS];
+#pragma unroll
+    for (int ks = 0; ks < G::KS; ++ks) {
+      o1[ks] = row_operand<DP>(m1, T, ks, r, g);
+      o2[ks] = row_operand<DP>(m2, T, ks, r, g);
+    }
+#pragma unroll
+    for (int k = 0; k < NK; ++k) {
+      s[k] = q[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < G::KS; ++ks) {
+        s[k] = Mx<E>::mma(o1[ks], xq[k][ks], s[k]);
+        q[k] = Mx<E>::mma(o2[ks], yq[k][ks], q[k]);
+      }
+    }
+  };
 
-    if constexpr (PROB == kBc) {
-      f32x4 S[16], dP[16];
+  if constexpr (PROB == kBc) {
+    // pass 1: log-sum-exp and D2 of every token's row, taken per lane over the rows it holds (agents
+    // 16 T + 4 g + i) with a running maximum, the four lane groups combined afterwards
+    float m_l[NK], l_l[NK], dn_l[NK];
 #pragma unroll
-      for (int T = 0; T < 16; ++T) {
-        S[T] = f32x4{0.f, 0.f, 0.f, 0.f};
-        dP[T] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (T < a.nt) {
+    for (int k = 0; k < NK; ++k) m_l[k] = -1.0e30f, l_l[k] = 0.f, dn_l[k] = 0.f;
+    for (int row0 = 0; row0 < a.n_rows; row0 += a.ch_rows) {
+      const int tiles = stage(row0);
+      for (int T = 0; T < tiles; ++T) {
+        f32x4 s[NK], q[NK];
+        products(T, s, q);
+        const int a0 = row0 + 16 * T + 4 * g;
 #pragma unroll
-          for (int ks = 0; ks < G::KS; ++ks) {
-            S[T] = Mx<E>::mma(row_operand<DP>(m1, T, ks, r, g), xq[ks], S[T]);
-            dP[T] = Mx<E>::mma(row_operand<DP>(m2, T, ks, r, g), yq[ks], dP[T]);
-          }
-        }
-      }
-      // softmax over the agents of this lane's token: rows 16 T + 4 g + i, spread over the four lane groups
-      float m = -INFINITY;
-#pragma unroll
-      for (int T = 0; T < 16; ++T)
-        if (T < a.nt) {
+        for (int k = 0; k < NK; ++k) {
+          float sv[4], mx = -INFINITY;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float s = (16 * T + 4 * g + i < a.n) ? S[T][i] * a.sc : -INFINITY;
-            S[T][i] = s;
-            m = fmaxf(m, s);
+            sv[i] = (a0 + i < a.n) ? s[k][i] * a.sc : -INFINITY;
+            mx = fmaxf(mx, sv[i]);
           }
-        }
-      m = xor16_32_max(m);
-      float l = 0.f, dn = 0.f;
-#pragma unroll
-      for (int T = 0; T < 16; ++T)
-        if (T < a.nt) {
+          const float m_new = fmaxf(m_l[k], mx);      // finite: m_l starts at -1e30
+          const float alpha = fast_exp2(m_l[k] - m_new);
+          float sum = 0.f, dsum = 0.f;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float p = fast_exp2(S[T][i] - m);
-            S[T][i] = p;
-            l += p;
-            dn += p * dP[T][i];
+            const float p = fast_exp2(sv[i] - m_new);
+            sum += p;
+            dsum += p * q[k][i];
           }
-        }
-      l = xor16_32_sum(l);
-      dn = xor16_32_sum(dn);
-      const float inv = 1.0f / l, D = dn * inv;
-      if (g == 0 && tok_ok) {
-        a.st1[ubN + t] = m + __builtin_amdgcn_logf(l);      // v_log_f32: log2
-        a.st2[ubN + t] = D;
-      }
-      u32x2 ds[16];
-#pragma unroll
-      for (int T = 0; T < 16; ++T) {
-        ds[T] = u32x2{0u, 0u};
-        if (T < a.nt) {
-          const f32x4 p = S[T] * inv, q = dP[T];
-          ds[T] = pack4<E>(p[0] * (q[0] - D), p[1] * (q[1] - D), p[2] * (q[2] - D), p[3] * (q[3] - D));
+          l_l[k] = l_l[k] * alpha + sum;
+          dn_l[k] = dn_l[k] * alpha + dsum;
+          m_l[k] = m_new;
         }
       }
+    }
+    float lse[NK], D[NK];
 #pragma unroll
-      for (int cc = 0; cc < G::CC; ++cc) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int T = 0; T < 16; T += 2)
-          if (T < a.nt)
-            acc = Mx<E>::mma(col_operand<DP>(m1, T, T + 1, cc, r, g), u32x4{ds[T][0], ds[T][1], ds[T + 1][0], ds[T + 1][1]},
-                             acc);
-        store_token_tile<E, DP>(a.O1, a.o1_f32 != 0, ubN + t, a.d, cc, g, acc * a.oscale, tok_ok);
+    for (int k = 0; k < NK; ++k) {
+      const float M = xor16_32_max(m_l[k]);
+      const float f = fast_exp2(m_l[k] - M);
+      const float l = xor16_32_sum(l_l[k] * f), dn = xor16_32_sum(dn_l[k] * f);
+      lse[k] = M + __builtin_amdgcn_logf(l);      // v_log_f32: log2
+      D[k] = dn / l;
+      if (g == 0 && tok_ok[k]) {
+        a.st1[ubN + t[k]] = lse[k];
+        a.st2[ubN + t[k]] = D[k];
       }
-    } else {
-      f32x4 accK[G::CC], accV[G::CC];
+    }
+    // pass 2: dS2 tile by tile into the product with A.  Rows past n need no mask here: their dS meets zero
+    // rows of A.
+    f32x4 acc[NK][G::CC];
 #pragma unroll
-      for (int cc = 0; cc < G::CC; ++cc) accK[cc] = accV[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
-      for (int T = 0; T < a.nt; T += 2) {
-        u32x2 pp[2], dd[2];
+    for (int k = 0; k < NK; ++k)
+#pragma unroll
+      for (int cc = 0; cc < G::CC; ++cc) acc[k][cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int row0 = 0; row0 < a.n_rows; row0 += a.ch_rows) {
+      const int tiles = stage(row0);
+      for (int T = 0; T < tiles; T += 2) {
+        u32x2 dd[NK][2];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-          f32x4 s = {0.f, 0.f, 0.f, 0.f}, q = {0.f, 0.f, 0.f, 0.f};
+          f32x4 s[NK], q[NK];
+          products(T + h, s, q);
 #pragma unroll
-          for (int ks = 0; ks < G::KS; ++ks) {
-            s = Mx<E>::mma(row_operand<DP>(m1, T + h, ks, r, g), xq[ks], s);
-            q = Mx<E>::mma(row_operand<DP>(m2, T + h, ks, r, g), yq[ks], q);
+          for (int k = 0; k < NK; ++k) {
+            float e[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) e[i] = fast_exp2(s[k][i] * a.sc - lse[k]) * (q[k][i] - D[k]);
+            dd[k][h] = pack4<E>(e[0], e[1], e[2], e[3]);
           }
-          const f32x4 lse = *reinterpret_cast<const f32x4*>(rs + 16 * (T + h) + 4 * g);
-          const f32x4 d1 = *reinterpret_cast<const f32x4*>(rs + rows + 16 * (T + h) + 4 * g);
-          float p[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) p[i] = fast_exp2(s[i] * a.sc - lse[i]);
-          pp[h] = pack4<E>(p[0], p[1], p[2], p[3]);
-          dd[h] = pack4<E>(p[0] * (q[0] - d1[0]), p[1] * (q[1] - d1[1]), p[2] * (q[2] - d1[2]), p[3] * (q[3] - d1[3]));
         }
-        const u32x4 pop = {pp[0][0], pp[0][1], pp[1][0], pp[1][1]}, dop = {dd[0][0], dd[0][1], dd[1][0], dd[1][1]};
 #pragma unroll
         for (int cc = 0; cc < G::CC; ++cc) {
-          accK[cc] = Mx<E>::mma(col_operand<DP>(m1, T, T + 1, cc, r, g), dop, accK[cc]);
-          accV[cc] = Mx<E>::mma(col_operand<DP>(m2, T, T + 1, cc, r, g), pop, accV[cc]);
+          const u32x4 co = col_operand<DP>(m1, T, T + 1, cc, r, g);
+#pragma unroll
+          for (int k = 0; k < NK; ++k)
+            acc[k][cc] = Mx<E>::mma(co, u32x4{dd[k][0][0], dd[k][0][1], dd[k][1][0], dd[k][1][1]}, acc[k][cc]);
         }
       }
+    }
 #pragma unroll
-      for (int cc = 0; cc < G::CC; ++cc) {
-        store_token_tile<E, DP>(a.O1, false, ubN + t, a.d, cc, g, accK[cc] * a.oscale, tok_ok);
-        store_token_tile<E, DP>(a.O2, false, ubN + t, a.d, cc, g, accV[cc], tok_ok);
+    for (int k = 0; k < NK; ++k)
+#pragma unroll
+      for (int cc = 0; cc < G::CC; ++cc)
+        store_token_tile<E>(a.O1, a.o1_f32 != 0, ubN + t[k], a.d, cc, g, acc[k][cc] * a.oscale, tok_ok[k]);
+  } else {
+    f32x4 accK[NK][G::CC], accV[NK][G::CC];
+#pragma unroll
+    for (int k = 0; k < NK; ++k)
+#pragma unroll
+      for (int cc = 0; cc < G::CC; ++cc) accK[k][cc] = accV[k][cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int row0 = 0; row0 < a.n_rows; row0 += a.ch_rows) {
+      const int tiles = stage(row0);
+      for (int T = 0; T < tiles; T += 2) {
+        u32x2 pp[NK][2], dd[NK][2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          f32x4 s[NK], q[NK];
+          products(T + h, s, q);
+          const f32x4 lse = *reinterpret_cast<const f32x4*>(rs + 16 * (T + h) + 4 * g);
+          const f32x4 d1 = *reinterpret_cast<const f32x4*>(rs + a.ch_rows + 16 * (T + h) + 4 * g);
+#pragma unroll
+          for (int k = 0; k < NK; ++k) {
+            float p[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) p[i] = fast_exp2(s[k][i] * a.sc - lse[i]);
+            pp[k][h] = pack4<E>(p[0], p[1], p[2], p[3]);
+            dd[k][h] = pack4<E>(p[0] * (q[k][0] - d1[0]), p[1] * (q[k][1] - d1[1]), p[2] * (q[k][2] - d1[2]),
+                                p[3] * (q[k][3] - d1[3]));
+          }
+        }
+#pragma unroll
+        for (int cc = 0; cc < G::CC; ++cc) {
+          const u32x4 c1 = col_operand<DP>(m1, T, T + 1, cc, r, g), c2 = col_operand<DP>(m2, T, T + 1, cc, r, g);
+#pragma unroll
+          for (int k = 0; k < NK; ++k) {
+            accK[k][cc] = Mx<E>::mma(c1, u32x4{dd[k][0][0], dd[k][0][1], dd[k][1][0], dd[k][1][1]}, accK[k][cc]);
+            accV[k][cc] = Mx<E>::mma(c2, u32x4{pp[k][0][0], pp[k][0][1], pp[k][1][0], pp[k][1][1]}, accV[k][cc]);
+          }
+        }
       }
     }
+#pragma unroll
+    for (int k = 0; k < NK; ++k)
+#pragma unroll
+      for (int cc = 0; cc < G::CC; ++cc) {
+        store_token_tile<E>(a.O1, false, ubN + t[k], a.d, cc, g, accK[k][cc] * a.oscale, tok_ok[k]);
+        store_token_tile<E>(a.O2, false, ubN + t[k], a.d, cc, g, accV[k][cc], tok_ok[k]);
+      }
   }
 }
 
@@ -523,7 +582,7 @@ __global__ __launch_bounds__(64) void fused_reduce_agg_kernel(const float* __res
 // host side
 // ---------------------------------------------------------------------------
 struct FusedPlan {
-  int DP, nt, n64, S, chunk, tiles_per_block, token_blocks;
+  int DP, n_rows, ch_rows, n64, S, chunk, token_blocks;
   // workspace offsets in floats (every region a multiple of 64 floats)
   size_t VAf, VAe, dVAe, lse1, D1, lse2, D2, dAf, dQf, part, total;
 };
@@ -533,7 +592,8 @@ size_t up64(size_t v) { return (v + 63) / 64 * 64; }
 FusedPlan fused_plan(const Problem& p, bool pooled) {
   FusedPlan f{};
   f.DP = p.d <= 32 ? 32 : (p.d <= 64 ? 64 : 128);
-  f.nt = (p.n + 31) / 32 * 2;      // agent tiles of the token kernel: pairs
+  f.n_rows = (p.n + 31) / 32 * 32;      // the token kernels take agent tiles in pairs
+  f.ch_rows = min(f.n_rows, 128);
   f.n64 = (p.n + 63) / 64;
   const int groups = f.n64 * p.units;
   int S = (2 * kComputeUnits + groups - 1) / groups;      // about two blocks per CU
@@ -541,9 +601,7 @@ FusedPlan fused_plan(const Problem& p, bool pooled) {
   S = max(S, 1);
   f.chunk = ((p.N + S - 1) / S + 31) / 32 * 32;
   f.S = (p.N + f.chunk - 1) / f.chunk;
-  const int tiles = (p.N + 63) / 64;
-  f.tiles_per_block = max(1, min(8, (int)((long long)tiles * p.units / (2 * kComputeUnits))));
-  f.token_blocks = (tiles + f.tiles_per_block - 1) / f.tiles_per_block;
+  f.token_blocks = (p.N + kTokBlock - 1) / kTokBlock;
   const size_t u = (size_t)p.units, nd = up64((size_t)p.n * p.d), un = up64(u * p.n), uN = up64(u * p.N);
   size_t o = 0;
   f.VAf = o, o += u * nd;
@@ -578,7 +636,7 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
   const float sc1 = p.scale1 * kLog2e, sc2 = p.scale2 * kLog2e;
 
   const size_t agent_lds = (size_t)4 * 32 * G::LST * 2 + 2 * 64 * sizeof(float);
-  const size_t token_lds = (size_t)2 * f.nt * 16 * G::LST * 2 + (size_t)2 * f.nt * 16 * sizeof(float);
+  const size_t token_lds = (size_t)2 * f.ch_rows * G::LST * 2 + (size_t)2 * f.ch_rows * sizeof(float);
   const dim3 agrid(f.S, f.n64, U), tgrid(f.token_blocks, U), rgrid(n, U);
   hipError_t e;
   if ((e = allow_lds(fused_token_kernel<E, DP, kBc>, token_lds)) != hipSuccess) return e;
@@ -593,7 +651,7 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
 
   // broadcast: per-token gradient and row statistics, then the per-agent sums
   TokenArgs tk{};
-  tk.N = N, tk.n = n, tk.d = d, tk.nt = f.nt, tk.tiles_per_block = f.tiles_per_block;
+  tk.N = N, tk.n = n, tk.d = d, tk.n_rows = f.n_rows, tk.ch_rows = f.ch_rows;
   tk.X = Q, tk.Y = dO, tk.M1 = A, tk.M2 = VAe, tk.st1 = lse2, tk.st2 = D2, tk.sc = sc2, tk.oscale = p.scale2;
   tk.O1 = agents_given ? dQ : (void*)dQf, tk.o1_f32 = agents_given ? 0 : 1;
   fused_token_kernel<E, DP, kBc><<<tgrid, dim3(kThreads), token_lds, st>>>(tk);
@@ -633,8 +691,8 @@ hipError_t run_fused_dp(const Problem& p, const FusedPlan& f, const void* Q, con
 }  // namespace
 
 bool backward_fused_supported(const Problem& p) {
-  return (p.dtype == 1 || p.dtype == 2) && p.d % 8 == 0 && p.d <= 128 && p.n <= 256 && !p.b1.any() && !p.b2.any() &&
-         !p.dwc_w && p.vk == 0.0f;
+  return (p.dtype == 1 || p.dtype == 2) && p.d % 8 == 0 && p.d <= 128 && p.units <= 65535 && !p.b1.any() &&
+         !p.b2.any() && !p.dwc_w && p.vk == 0.0f;
 }
 
 size_t backward_fused_workspace_floats(const Problem& p, bool pooled) { return fused_plan(p, pooled).total; }
