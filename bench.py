@@ -342,7 +342,7 @@ def measure_backward(wl, binding, ring, steps, warmup):
         binding.agent_attn_bwd(s["Q"], s["K"], s["V"], dO, grid=wl.grid, agent_grid=wl.agent_grid, params=ring.params,
                                workspace=ws)
     ms = timed(call, steps, warmup)
-    fused = wl.dtype != "f32" and ring.params is None and wl.d % 8 == 0 and wl.d <= 128 and wl.n <= 256
+    fused = wl.dtype != "f32" and ring.params is None and wl.d % 8 == 0 and wl.d <= 128
     flops = 20.0 * wl.N * wl.n * wl.d * wl.units
     tf = flops / (ms * 1e-3) / 1e12
     peak = VALU_F32_PEAK_TFLOPS if wl.dtype == "f32" else MFMA_PEAK_TFLOPS

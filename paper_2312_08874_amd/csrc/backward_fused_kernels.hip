@@ -303,9 +303,9 @@ __global__ __launch_bounds__(kThreads) void fused_token_kernel(TokenArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// Agent kernel.  Grid (token ranges, blocks of 64 agents, units); each wave keeps its 16 agents' rows of M1
-// (and M2) in registers as operands and walks over its range in tiles of 32 tokens staged through LDS
-// (two buffers, one barrier per tile).
+// Agent kernel.  Grid (token ranges, blocks of 64 or 128 agents, units); each wave keeps the rows of M1 (and
+// M2) of its 16 or 32 agents in registers as operands and walks over its range in tiles of 32 tokens staged
+// through LDS (two buffers, one barrier per tile).
 //   kFwd:  X = K, Y = V            ->  P1 = sum_t w V (unnormalised, running maximum pm, weight sum pl)
 //   kBc :  X = Q, Y = dO, M2 = V_A, ts1 = lse2, ts2 = D2  ->  P1 = sum_t P2 dO,  P2 = sum_t dS2 Q
 //   kAgg:  X = K, Y = V,  M2 = dV_A, rs1 = lse1, rs2 = D1 ->  P1 = sum_t dS1 K
@@ -319,9 +319,13 @@ struct AgentArgs {
   float sc;
 };
 
+template <int DP>
+constexpr int agent_cols() { return DP == 128 ? 1 : 2; }      // 16-agent columns per wave (registers allowing)
+
 template <class E, int DP, int PROB>
 __global__ __launch_bounds__(kThreads) void fused_agent_kernel(AgentArgs a) {
   using G = Geo<DP>;
+  constexpr int NA = agent_cols<DP>();
   constexpr int kTileRows = 32;
   constexpr int kPieces = kTileRows * G::CPR;
   constexpr int NLD = (kPieces + kThreads - 1) / kThreads;
@@ -333,25 +337,32 @@ __global__ __launch_bounds__(kThreads) void fused_agent_kernel(AgentArgs a) {
   const int s = blockIdx.x, ab = blockIdx.y, u = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 15, g = lane >> 4;
   const size_t ubN = (size_t)u * a.N, ubn = (size_t)u * a.n;
-  const int agent = ab * 64 + w * 16 + r;
-  const bool ag_ok = agent < a.n;
   const int t_beg = s * a.chunk, t_end = min(a.N, t_beg + a.chunk);
   const int ntile = (t_end - t_beg + kTileRows - 1) / kTileRows;
 
-  u32x4 a1[G::KS], a2[G::KS];
+  // this lane's agents (the column it holds of every tile below), one per 16-agent column of the wave
+  int agent[NA];
+  bool ag_ok[NA];
+  u32x4 a1[NA][G::KS], a2[NA][G::KS];
+  float lse_a[NA], d_a[NA];
 #pragma unroll
-  for (int ks = 0; ks < G::KS; ++ks) {
-    const int c8 = (4 * ks + g) * 8;
-    const bool ok = ag_ok && c8 < a.d;
-    a1[ks] = load16(a.M1 + (ubn + agent) * a.d + c8, ok);
-    a2[ks] = u32x4{0u, 0u, 0u, 0u};
-    if constexpr (PROB != kFwd) a2[ks] = load16(a.M2 + (ubn + agent) * a.d + c8, ok);
-  }
-  float lse_a = kMasked, d_a = 0.f;
-  if constexpr (PROB == kAgg) {
-    if (ag_ok) {
-      lse_a = a.rs1[ubn + agent];
-      d_a = a.rs2[ubn + agent];
+  for (int k = 0; k < NA; ++k) {
+    agent[k] = (ab * 4 + w) * 16 * NA + k * 16 + r;
+    ag_ok[k] = agent[k] < a.n;
+#pragma unroll
+    for (int ks = 0; ks < G::KS; ++ks) {
+      const int c8 = (4 * ks + g) * 8;
+      const bool ok = ag_ok[k] && c8 < a.d;
+      a1[k][ks] = load16(a.M1 + (ubn + agent[k]) * a.d + c8, ok);
+      a2[k][ks] = u32x4{0u, 0u, 0u, 0u};
+      if constexpr (PROB != kFwd) a2[k][ks] = load16(a.M2 + (ubn + agent[k]) * a.d + c8, ok);
+    }
+    lse_a[k] = kMasked, d_a[k] = 0.f;
+    if constexpr (PROB == kAgg) {
+      if (ag_ok[k]) {
+        lse_a[k] = a.rs1[ubn + agent[k]];
+        d_a[k] = a.rs2[ubn + agent[k]];
+      }
     }
   }
 
@@ -390,10 +401,14 @@ __global__ __launch_bounds__(kThreads) void fused_agent_kernel(AgentArgs a) {
     }
   };
 
-  f32x4 acc1[G::CC], acc2[G::CC];
+  f32x4 acc1[NA][G::CC], acc2[NA][G::CC];
+  float m_run[NA], l_run[NA];
 #pragma unroll
-  for (int cc = 0; cc < G::CC; ++cc) acc1[cc] = acc2[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;
+  for (int k = 0; k < NA; ++k) {
+    m_run[k] = -INFINITY, l_run[k] = 0.f;
+#pragma unroll
+    for (int cc = 0; cc < G::CC; ++cc) acc1[k][cc] = acc2[k][cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
 
   fetch(0);
   stash(0);
@@ -404,99 +419,124 @@ __global__ __launch_bounds__(kThreads) void fused_agent_kernel(AgentArgs a) {
     const uint16_t* xb = xt + buf * kImage;
     const uint16_t* yb = yt + buf * kImage;
     const int t0 = t_beg + it * kTileRows;
-    f32x4 sv[2], qv[2];
+    // score-side products: token subtile j (rows of the tiles), agent column k
+    f32x4 sv[NA][2], qv[NA][2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      sv[j] = qv[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+      u32x4 xo[G::KS], yo[G::KS];
 #pragma unroll
       for (int ks = 0; ks < G::KS; ++ks) {
-        sv[j] = Mx<E>::mma(row_operand<DP>(xb, j, ks, r, g), a1[ks], sv[j]);
-        if constexpr (PROB != kFwd) qv[j] = Mx<E>::mma(row_operand<DP>(yb, j, ks, r, g), a2[ks], qv[j]);
+        xo[ks] = row_operand<DP>(xb, j, ks, r, g);
+        if constexpr (PROB != kFwd) yo[ks] = row_operand<DP>(yb, j, ks, r, g);
+      }
+#pragma unroll
+      for (int k = 0; k < NA; ++k) {
+        sv[k][j] = qv[k][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < G::KS; ++ks) {
+          sv[k][j] = Mx<E>::mma(xo[ks], a1[k][ks], sv[k][j]);
+          if constexpr (PROB != kFwd) qv[k][j] = Mx<E>::mma(yo[ks], a2[k][ks], qv[k][j]);
+        }
       }
     }
-    // this lane: agent `agent`, tokens t0 + 16 j + 4 g + i
-    u32x4 pop, dop = {0u, 0u, 0u, 0u};
-    if constexpr (PROB == kFwd) {
-      float mx = -INFINITY;
+    // this lane: agents agent[k], tokens t0 + 16 j + 4 g + i
+    u32x4 pop[NA], dop[NA];
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+    for (int k = 0; k < NA; ++k) {
+      dop[k] = u32x4{0u, 0u, 0u, 0u};
+      if constexpr (PROB == kFwd) {
+        float mx = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float sc = (t0 + 16 * j + 4 * g + i < t_end) ? sv[j][i] * a.sc : -INFINITY;
-          sv[j][i] = sc;
-          mx = fmaxf(mx, sc);
-        }
-      mx = xor16_32_max(mx);
-      const float m_new = fmaxf(m_run, mx);      // finite: the tile holds at least one token of the range
-      const float alpha = fast_exp2(m_run - m_new);
-      float sum = 0.f;
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          sv[j][i] = fast_exp2(sv[j][i] - m_new);
-          sum += sv[j][i];
-        }
-      l_run = l_run * alpha + sum;      // per lane group; the groups are added at the end
-      m_run = m_new;
-#pragma unroll
-      for (int cc = 0; cc < G::CC; ++cc) acc1[cc] *= alpha;
-      const u32x2 p0 = pack4<E>(sv[0][0], sv[0][1], sv[0][2], sv[0][3]), p1 = pack4<E>(sv[1][0], sv[1][1], sv[1][2], sv[1][3]);
-      pop = u32x4{p0[0], p0[1], p1[0], p1[1]};
-    } else {
-      u32x2 pp[2], dd[2];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        float p[4], e[4];
-        if constexpr (PROB == kBc) {
-          const f32x4 lse = *reinterpret_cast<const f32x4*>(ts + buf * 64 + 16 * j + 4 * g);
-          const f32x4 d2 = *reinterpret_cast<const f32x4*>(ts + buf * 64 + 32 + 16 * j + 4 * g);
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            p[i] = fast_exp2(sv[j][i] * a.sc - lse[i]);
-            e[i] = p[i] * (qv[j][i] - d2[i]);
+            const float sc = (t0 + 16 * j + 4 * g + i < t_end) ? sv[k][j][i] * a.sc : -INFINITY;
+            sv[k][j][i] = sc;
+            mx = fmaxf(mx, sc);
           }
-        } else {
+        mx = xor16_32_max(mx);
+        const float m_new = fmaxf(m_run[k], mx);      // finite: the tile holds at least one token of the range
+        const float alpha = fast_exp2(m_run[k] - m_new);
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            p[i] = (t0 + 16 * j + 4 * g + i < t_end) ? fast_exp2(sv[j][i] * a.sc - lse_a) : 0.f;
-            e[i] = p[i] * (qv[j][i] - d_a);
+            sv[k][j][i] = fast_exp2(sv[k][j][i] - m_new);
+            sum += sv[k][j][i];
           }
+        l_run[k] = l_run[k] * alpha + sum;      // per lane group; the groups are added at the end
+        m_run[k] = m_new;
+#pragma unroll
+        for (int cc = 0; cc < G::CC; ++cc) acc1[k][cc] *= alpha;
+        const u32x2 p0 = pack4<E>(sv[k][0][0], sv[k][0][1], sv[k][0][2], sv[k][0][3]),
+                    p1 = pack4<E>(sv[k][1][0], sv[k][1][1], sv[k][1][2], sv[k][1][3]);
+        pop[k] = u32x4{p0[0], p0[1], p1[0], p1[1]};
+      } else {
+        u32x2 pp[2], dd[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          float p[4], e[4];
+          if constexpr (PROB == kBc) {
+            const f32x4 lse = *reinterpret_cast<const f32x4*>(ts + buf * 64 + 16 * j + 4 * g);
+            const f32x4 d2 = *reinterpret_cast<const f32x4*>(ts + buf * 64 + 32 + 16 * j + 4 * g);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              p[i] = fast_exp2(sv[k][j][i] * a.sc - lse[i]);
+              e[i] = p[i] * (qv[k][j][i] - d2[i]);
+            }
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              p[i] = (t0 + 16 * j + 4 * g + i < t_end) ? fast_exp2(sv[k][j][i] * a.sc - lse_a[k]) : 0.f;
+              e[i] = p[i] * (qv[k][j][i] - d_a[k]);
+            }
+          }
+          pp[j] = pack4<E>(p[0], p[1], p[2], p[3]);
+          dd[j] = pack4<E>(e[0], e[1], e[2], e[3]);
         }
-        pp[j] = pack4<E>(p[0], p[1], p[2], p[3]);
-        dd[j] = pack4<E>(e[0], e[1], e[2], e[3]);
+        pop[k] = u32x4{pp[0][0], pp[0][1], pp[1][0], pp[1][1]};
+        dop[k] = u32x4{dd[0][0], dd[0][1], dd[1][0], dd[1][1]};
       }
-      pop = u32x4{pp[0][0], pp[0][1], pp[1][0], pp[1][1]};
-      dop = u32x4{dd[0][0], dd[0][1], dd[1][0], dd[1][1]};
     }
 #pragma unroll
     for (int cc = 0; cc < G::CC; ++cc) {
-      if constexpr (PROB == kFwd) acc1[cc] = Mx<E>::mma(col_operand<DP>(yb, 0, 1, cc, r, g), pop, acc1[cc]);
-      if constexpr (PROB == kBc) {
-        acc1[cc] = Mx<E>::mma(col_operand<DP>(yb, 0, 1, cc, r, g), pop, acc1[cc]);
-        acc2[cc] = Mx<E>::mma(col_operand<DP>(xb, 0, 1, cc, r, g), dop, acc2[cc]);
+      if constexpr (PROB != kAgg) {
+        const u32x4 cy = col_operand<DP>(yb, 0, 1, cc, r, g);
+#pragma unroll
+        for (int k = 0; k < NA; ++k) acc1[k][cc] = Mx<E>::mma(cy, pop[k], acc1[k][cc]);
       }
-      if constexpr (PROB == kAgg) acc1[cc] = Mx<E>::mma(col_operand<DP>(xb, 0, 1, cc, r, g), dop, acc1[cc]);
+      if constexpr (PROB != kFwd) {
+        const u32x4 cx = col_operand<DP>(xb, 0, 1, cc, r, g);
+#pragma unroll
+        for (int k = 0; k < NA; ++k) {
+          if constexpr (PROB == kBc) acc2[k][cc] = Mx<E>::mma(cx, dop[k], acc2[k][cc]);
+          if constexpr (PROB == kAgg) acc1[k][cc] = Mx<E>::mma(cx, dop[k], acc1[k][cc]);
+        }
+      }
     }
     if (it + 1 < ntile) stash(buf ^ 1);
     __syncthreads();
   }
 
-  // lane (r, g): agent `agent`, channels 16 cc + 4 g .. + 3
-  const size_t prow = ((size_t)u * a.S + s) * a.n + agent;
-  if constexpr (PROB == kFwd) {
-    l_run = xor16_32_sum(l_run);
-    if (g == 0 && ag_ok) {
-      a.pm[prow] = m_run;
-      a.pl[prow] = l_run;
-    }
-  }
+  // lane (r, g): agents agent[k], channels 16 cc + 4 g .. + 3
 #pragma unroll
-  for (int cc = 0; cc < G::CC; ++cc) {
-    const int c = cc * 16 + 4 * g;
-    if (ag_ok && c < a.d) {
-      *reinterpret_cast<f32x4*>(a.P1 + prow * a.d + c) = acc1[cc];
-      if constexpr (PROB == kBc) *reinterpret_cast<f32x4*>(a.P2 + prow * a.d + c) = acc2[cc];
+  for (int k = 0; k < NA; ++k) {
+    const size_t prow = ((size_t)u * a.S + s) * a.n + agent[k];
+    if constexpr (PROB == kFwd) {
+      const float l = xor16_32_sum(l_run[k]);
+      if (g == 0 && ag_ok[k]) {
+        a.pm[prow] = m_run[k];
+        a.pl[prow] = l;
+      }
+    }
+#pragma unroll
+    for (int cc = 0; cc < G::CC; ++cc) {
+      const int c = cc * 16 + 4 * g;
+      if (ag_ok[k] && c < a.d) {
+        *reinterpret_cast<f32x4*>(a.P1 + prow * a.d + c) = acc1[k][cc];
+        if constexpr (PROB == kBc) *reinterpret_cast<f32x4*>(a.P2 + prow * a.d + c) = acc2[k][cc];
+      }
     }
   }
 }
@@ -582,7 +622,7 @@ __global__ __launch_bounds__(64) void fused_reduce_agg_kernel(const float* __res
 // host side
 // ---------------------------------------------------------------------------
 struct FusedPlan {
-  int DP, n_rows, ch_rows, n64, S, chunk, token_blocks;
+  int DP, n_rows, ch_rows, agent_blocks, S, chunk, token_blocks;
   // workspace offsets in floats (every region a multiple of 64 floats)
   size_t VAf, VAe, dVAe, lse1, D1, lse2, D2, dAf, dQf, part, total;
 };
@@ -594,8 +634,9 @@ FusedPlan fused_plan(const Problem& p, bool pooled) {
   f.DP = p.d <= 32 ? 32 : (p.d <= 64 ? 64 : 128);
   f.n_rows = (p.n + 31) / 32 * 32;      // the token kernels take agent tiles in pairs
   f.ch_rows = min(f.n_rows, 128);
-  f.n64 = (p.n + 63) / 64;
-  const int groups = f.n64 * p.units;
+  const int per_block = 64 * (f.DP == 128 ? 1 : 2);      // agents per block of the agent kernels (agent_cols)
+  f.agent_blocks = (p.n + per_block - 1) / per_block;
+  const int groups = f.agent_blocks * p.units;
   int S = (2 * kComputeUnits + groups - 1) / groups;      // about two blocks per CU
   S = min(S, (p.N + 127) / 128);
   S = max(S, 1);
@@ -637,7 +678,7 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
 
   const size_t agent_lds = (size_t)4 * 32 * G::LST * 2 + 2 * 64 * sizeof(float);
   const size_t token_lds = (size_t)2 * f.ch_rows * G::LST * 2 + (size_t)2 * f.ch_rows * sizeof(float);
-  const dim3 agrid(f.S, f.n64, U), tgrid(f.token_blocks, U), rgrid(n, U);
+  const dim3 agrid(f.S, f.agent_blocks, U), tgrid(f.token_blocks, U), rgrid(n, U);
   hipError_t e;
   if ((e = allow_lds(fused_token_kernel<E, DP, kBc>, token_lds)) != hipSuccess) return e;
   if ((e = allow_lds(fused_token_kernel<E, DP, kAgg>, token_lds)) != hipSuccess) return e;
