@@ -1,5 +1,5 @@
 // Backward pass of agent attention without the attention matrices in memory (fp16 / bf16, d a multiple of 8 up
-// to 128, no agent bias, no DWC, no V residual): every score tile is recomputed where it is used.
+// to 128, no agent bias, no DWC): every score tile is recomputed where it is used.
 //
 // Both stages of agent attention (Sec. 4.1 Eq. (3)) are softmax attentions between the N tokens and the n agents:
 //   aggregation   S1 = c1 A K^T (n x N), P1 = softmax over tokens,  V_A = P1 V
@@ -17,7 +17,7 @@
 // Launches:  agent<FWD> + merge   V_A, lse1                 (recomputes the forward aggregation)
 //            token<BC>            dQ (without the pooling term), lse2, D2
 //            agent<BC> + reduce   dV_A, D1, dA (broadcast part)
-//            token<AGG>           dK, dV
+//            token<AGG>           dK, dV (with the k dO that comes through the V residual, Appendix C.1)
 //            agent<AGG> + reduce  dA (aggregation part)
 //            pooling adjoint      dQ += Pooling^T(dA)         (Sec. 4.2), when the agents were pooled
 // Scores are taken in the log2 domain (scale * log2 e folded into one multiplication, exp2 for the weights).
@@ -94,6 +94,8 @@ struct TokenArgs {
   void *O1, *O2;
   int N, n, d, n_rows, ch_rows, o1_f32;      // n_rows: n rounded up to 32; ch_rows: agents staged at a time (x32)
   float sc, oscale;
+  const uint16_t* G;      // kAgg: dO, for the share of dV that comes through the V residual (Appendix C.1: O += k V)
+  float vk;
 };
 
 template <class E>
@@ -297,7 +299,16 @@ __global__ __launch_bounds__(kThreads) void fused_token_kernel(TokenArgs a) {
 #pragma unroll
       for (int cc = 0; cc < G::CC; ++cc) {
         store_token_tile<E>(a.O1, false, ubN + t[k], a.d, cc, g, accK[k][cc] * a.oscale, tok_ok[k]);
-        store_token_tile<E>(a.O2, false, ubN + t[k], a.d, cc, g, accV[k][cc], tok_ok[k]);
+        f32x4 dv = accV[k][cc];
+        const int c = cc * 16 + 4 * g;
+        if (a.vk != 0.0f && tok_ok[k] && c < a.d) {      // dV += k dO
+          const u32x2 go = *reinterpret_cast<const u32x2*>(a.G + (ubN + t[k]) * a.d + c);
+          float g0, g1, g2, g3;
+          Mx<E>::unpack2(go[0], g0, g1);
+          Mx<E>::unpack2(go[1], g2, g3);
+          dv += f32x4{g0, g1, g2, g3} * a.vk;
+        }
+        store_token_tile<E>(a.O2, false, ubN + t[k], a.d, cc, g, dv, tok_ok[k]);
       }
   }
 }
@@ -702,7 +713,7 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
 
   // aggregation
   tk.X = K, tk.Y = V, tk.M2 = dVAe, tk.rs1 = lse1, tk.rs2 = D1, tk.sc = sc1, tk.oscale = p.scale1;
-  tk.O1 = dK, tk.O2 = dV, tk.o1_f32 = 0;
+  tk.O1 = dK, tk.O2 = dV, tk.o1_f32 = 0, tk.G = dO, tk.vk = p.vk;
   fused_token_kernel<E, DP, kAgg><<<tgrid, dim3(kThreads), token_lds, st>>>(tk);
   ag.X = K, ag.Y = V, ag.M2 = dVAe, ag.rs1 = lse1, ag.rs2 = D1, ag.P1 = part1, ag.sc = sc1;
   fused_agent_kernel<E, DP, kAgg><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
@@ -733,7 +744,7 @@ hipError_t run_fused_dp(const Problem& p, const FusedPlan& f, const void* Q, con
 
 bool backward_fused_supported(const Problem& p) {
   return (p.dtype == 1 || p.dtype == 2) && p.d % 8 == 0 && p.d <= 128 && p.units <= 65535 && !p.b1.any() &&
-         !p.b2.any() && !p.dwc_w && p.vk == 0.0f;
+         !p.b2.any() && !p.dwc_w;
 }
 
 size_t backward_fused_workspace_floats(const Problem& p, bool pooled) { return fused_plan(p, pooled).total; }

@@ -88,7 +88,7 @@ hipError_t launch_backward(const Problem& p, const void* Q, const void* K, const
                            bool use_mfma, const BackwardParamGrads& pg, hipStream_t st);
 
 // Backward without the attention matrices in memory (score tiles recomputed in the kernels that use them):
-// fp16 / bf16, d a multiple of 8 up to 128, pure mode (no agent bias, DWC or V residual); every tensor
+// fp16 / bf16, d a multiple of 8 up to 128, no agent bias and no DWC (the V residual is handled); every tensor
 // 16-byte aligned.  launch_backward takes this path whenever the problem allows it, and the workspace figure
 // above is then this path's (a few n x d and N-long arrays, split partial sums, an fp32 dQ when the agents are
 // pooled).

@@ -102,7 +102,7 @@ def _run_case(aa, oracle, wl, *, given=False, module=False, blk=(3, 2), kw=None)
         ref["dQ"] = ref["dQ"] + oracle.pool_bwd(ref.pop("dA"), *wl.grid, *wl.agent_grid)
     for k in ("dQ", "dK", "dV") + (("dA",) if given else ()):
         _check(got[k], ref[k], wl.dtype, "%s %s" % (wl.name, k),
-               pure=not module and not kw.get("v_residual_k") and wl.d % 8 == 0 and wl.d <= 128)
+               pure=not module and wl.d % 8 == 0 and wl.d <= 128)
     if module:
         h0, w0 = blk
         gh, gw = wl.grid
