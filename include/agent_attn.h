@@ -220,9 +220,13 @@ aa_status agent_broadcast_fwd(const aa_desc *desc, const void *Q, const void *A,
 /* ------------------------------------------------------------------------
  * Backward pass (the paper trains its models end to end, Sec. 5; the gradients
  * follow from Eq. (3), (5), (6) and Appendix B / C.1 by the chain rule).
- * First implementation: reference-quality kernels that materialise both
- * attention matrices in the workspace (fp32), so the workspace is large:
- * about 4*n*N + 7*N*d + 4*n*d floats per (batch, head) unit.
+ * Two implementations.  fp16 / bf16 problems without agent bias and DWC
+ * (d a multiple of 8 up to 128; the V residual is allowed) run kernels that
+ * recompute every score tile where it is used and keep no attention matrix in
+ * memory: the workspace is a few n*d and N-long arrays per unit, the partial
+ * sums of the split token ranges and, with pooled agents, one fp32 dQ.  Every
+ * other problem runs reference-quality kernels that materialise both attention
+ * matrices in the workspace: about 4*n*N + 7*N*d + 4*n*d floats per unit.
  * ---------------------------------------------------------------------- */
 
 /* Gradients of the module parameters (host struct of device pointers, fp32,
@@ -248,7 +252,10 @@ size_t agent_attn_bwd_workspace_bytes(const aa_desc *desc, const aa_params *para
  * descriptor's input strides, dO its output strides (strided tensors are staged
  * through dense copies in the workspace).  Outputs must not overlap inputs or the
  * workspace.  Same stream, error and determinism conventions as the forward.
- * params->bias_tables is not used here: the bias is taken from its components. */
+ * params->bias_tables is not used here: the bias is taken from its components.
+ * The recomputing kernels read 16 bytes at a time: for a problem they serve
+ * (see above), Q, K, V, A, dO and the gradient tensors must be 16-byte aligned
+ * (AA_ERR_UNSUPPORTED otherwise); strided tensors are staged and need not be. */
 aa_status agent_attn_bwd(const aa_desc *desc, const void *Q, const void *K, const void *V,
                          const void *A, const aa_params *params, const void *dO, void *workspace,
                          size_t workspace_bytes, void *dQ, void *dK, void *dV, void *dA,

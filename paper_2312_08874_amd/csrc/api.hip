@@ -905,6 +905,12 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
     return AA_ERR_ALIAS;
 
   Problem pr = make_problem(desc, params);
+  // the kernels that keep no attention matrix in memory have the smaller workspace, so there is no falling back
+  // from them: they need aligned tensors (strided ones are staged into aligned copies)
+  if (aa::backward_fused_supported(pr) && !(aligned16(A) && aligned16(dA))) return AA_ERR_UNSUPPORTED;
+  if (aa::backward_fused_supported(pr) && dense_layout(desc) &&
+      !(aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(dO) && aligned16(dQ) && aligned16(dK) && aligned16(dV)))
+    return AA_ERR_UNSUPPORTED;
   hipStream_t stream = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
   // Strided tensors: the kernels below work on dense copies staged at the end of the workspace
@@ -941,9 +947,6 @@ aa_status agent_attn_bwd(const aa_desc* desc, const void* Q, const void* K, cons
   }
   const bool use_mfma = (pr.dtype == AA_F16 || pr.dtype == AA_BF16) && pr.d % 8 == 0 && aligned16(Q) && aligned16(K) &&
                         aligned16(V) && aligned16(dO) && aligned16(agents);
-  // the path that keeps no attention matrix in memory has the smaller workspace and needs aligned tensors
-  if (aa::backward_fused_supported(pr) && !(use_mfma && aligned16(dQ) && aligned16(dK) && aligned16(dV) && aligned16(dA)))
-    return AA_ERR_UNSUPPORTED;
   AA_HIP(aa::launch_backward(pr, Q, K, V, agents, dO, (float*)(ws + bwd_agents_bytes(desc)), dQ, dK, dV, dA, !pooling,
                              use_mfma, pg, stream));
   if (sdQ) {

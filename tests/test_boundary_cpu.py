@@ -248,6 +248,9 @@ def test_bwd_rejects_bad_arguments():
     p = aa_params()
     p.b1_col = 12 * G
     assert call(params=p, grads=g, ws_bytes=need - 1) == -5     # accepted up to the workspace check
+    # the kernels a pure 16-bit problem runs read 16 bytes at a time; with a module term the other path runs
+    assert call(Q=G + 2) == -7 and call(dK=8 * G + 8) == -7                              # AA_ERR_UNSUPPORTED
+    assert call(Q=G + 2, params=p, ws_bytes=need - 1) == -5
     # strided tensors are staged through dense copies: seven more [units, N, d] buffers in the workspace
     tm = make_desc(2, 3, 196, 49, 32, binding.AA_BF16, (14, 14), (7, 7), strides=(196 * 96, 32, 96),
                    out_strides=(196 * 96, 32, 96))
