@@ -563,21 +563,18 @@ __global__ __launch_bounds__(64) void fused_merge_kernel(const float* __restrict
                                                          float* __restrict__ VAf, uint16_t* __restrict__ VAe,
                                                          float* __restrict__ lse1) {
   const int ag = blockIdx.x, u = blockIdx.y, lane = threadIdx.x;
-  float M = -INFINITY;
-  for (int s = 0; s < S; ++s) M = fmaxf(M, pm[((size_t)u * S + s) * n + ag]);
-  float L = 0.f;
-  for (int s = 0; s < S; ++s) {
-    const size_t row = ((size_t)u * S + s) * n + ag;
-    L += pl[row] * fast_exp2(pm[row] - M);
-  }
-  const float inv = 1.0f / L;
+  __shared__ float wgt[64];
+  // lane s holds range s (S <= 64)
+  const size_t my = ((size_t)u * S + min(lane, S - 1)) * n + ag;
+  const float pm_s = lane < S ? pm[my] : -INFINITY, pl_s = lane < S ? pl[my] : 0.f;
+  const float M = wave_max(pm_s);
+  const float w_s = fast_exp2(pm_s - M);
+  const float L = wave_sum(pl_s * w_s);
+  wgt[lane] = w_s / L;
+  __syncthreads();
   for (int c = lane; c < d; c += 64) {
     float v = 0.f;
-    for (int s = 0; s < S; ++s) {
-      const size_t row = ((size_t)u * S + s) * n + ag;
-      v += acc[row * d + c] * fast_exp2(pm[row] - M);
-    }
-    v *= inv;
+    for (int s = 0; s < S; ++s) v += acc[(((size_t)u * S + s) * n + ag) * d + c] * wgt[s];
     const size_t o = ((size_t)u * n + ag) * d + c;
     VAf[o] = v;
     const typename E::T e = E::from_f32(v);
@@ -648,8 +645,8 @@ FusedPlan fused_plan(const Problem& p, bool pooled) {
   const int per_block = 64 * (f.DP == 128 ? 1 : 2);      // agents per block of the agent kernels (agent_cols)
   f.agent_blocks = (p.n + per_block - 1) / per_block;
   const int groups = f.agent_blocks * p.units;
-  int S = (2 * kComputeUnits + groups - 1) / groups;      // about two blocks per CU
-  S = min(S, (p.N + 127) / 128);
+  int S = (2 * kComputeUnits + groups - 1) / groups;      // about two blocks per CU (four measured no faster)
+  S = min(min(S, 64), (p.N + 127) / 128);                 // at most 64: the merge gives every range a lane
   S = max(S, 1);
   f.chunk = ((p.N + S - 1) / S + 31) / 32 * 32;
   f.S = (p.N + f.chunk - 1) / f.chunk;
