@@ -15,11 +15,12 @@
 // the next without leaving the registers; the other operand is read from LDS with the transpose read.
 //
 // Launches:  agent<FWD> + merge   V_A, lse1                 (recomputes the forward aggregation)
-//            token<BC>            dQ (without the pooling term), lse2, D2
+//            token<BCSTAT>        lse2, D2
 //            agent<BC> + reduce   dV_A, D1, dA (broadcast part)
 //            token<AGG>           dK, dV (with the k dO that comes through the V residual, Appendix C.1)
 //            agent<AGG> + reduce  dA (aggregation part)
-//            pooling adjoint      dQ += Pooling^T(dA)         (Sec. 4.2), when the agents were pooled
+//            token<BC>            dQ = c2 dS2 A + Pooling^T(dA)   (the pooling term, Sec. 4.2, when the agents were
+//                                 pooled: dA is complete by now)
 // Scores are taken in the log2 domain (scale * log2 e folded into one multiplication, exp2 for the weights).
 // No atomics: results are bitwise repeatable.
 #include "kernels.h"
@@ -78,13 +79,13 @@ __device__ __forceinline__ u32x2 pack4(float a, float b, float c, float d) {
   return u32x2{Mx<E>::pack2(a, b), Mx<E>::pack2(c, d)};
 }
 
-enum { kFwd = 0, kBc = 1, kAgg = 2 };
+enum { kFwd = 0, kBc = 1, kAgg = 2, kBcStat = 3 };
 
 // ---------------------------------------------------------------------------
 // Token kernel.  Block: 128 tokens of a unit, 32 per wave, held in registers as operands; the unit's agents
 // pass through LDS ch_rows at a time (M1 = A, M2 = V_A for the broadcast, dV_A for the aggregation).
-//   kBc :  X = Q, Y = dO  ->  O1 = c2 dS2 A (fp32 or element type), st1 = lse2, st2 = D2; two passes over the
-//          agents: the rows' statistics first, then dS2
+//   kBcStat:  X = Q, Y = dO  ->  st1 = lse2, st2 = D2 of every token's row
+//   kBc :  X = Q, Y = dO, st1, st2  ->  O1 = dQ = c2 dS2 A + Pooling^T(dA)
 //   kAgg:  X = K, Y = V, rs1 = lse1, rs2 = D1  ->  O1 = dK = c1 dS1^T A,  O2 = dV = P1^T dV_A
 // ---------------------------------------------------------------------------
 struct TokenArgs {
@@ -92,30 +93,50 @@ struct TokenArgs {
   const float *rs1, *rs2;
   float *st1, *st2;
   void *O1, *O2;
-  int N, n, d, n_rows, ch_rows, o1_f32;      // n_rows: n rounded up to 32; ch_rows: agents staged at a time (x32)
+  int N, n, d, n_rows, ch_rows;      // n_rows: n rounded up to 32; ch_rows: agents staged at a time (x32)
+  const float* dA;                   // kBc: the finished dA [units][n][d] when the agents were pooled (else null)
+  int gh, gw, ah, aw;                // the pooling's grids
   float sc, oscale;
   const uint16_t* G;      // kAgg: dO, for the share of dV that comes through the V residual (Appendix C.1: O += k V)
   float vk;
 };
 
 template <class E>
-__device__ __forceinline__ void store_token_tile(void* out, bool f32, size_t row, int d, int cc, int g, f32x4 v, bool ok) {
+__device__ __forceinline__ void store_token_tile(void* out, size_t row, int d, int cc, int g, f32x4 v, bool ok) {
   const int c = cc * 16 + 4 * g;
   if (!ok || c >= d) return;
-  if (f32) {
-    *reinterpret_cast<f32x4*>((float*)out + row * d + c) = v;
-  } else {
-    *reinterpret_cast<u32x2*>((uint16_t*)out + row * d + c) = pack4<E>(v[0], v[1], v[2], v[3]);
-  }
+  *reinterpret_cast<u32x2*>((uint16_t*)out + row * d + c) = pack4<E>(v[0], v[1], v[2], v[3]);
 }
 
-constexpr int kTokCols = 2;                      // 16-token columns per wave: every LDS operand feeds two products
-constexpr int kTokBlock = 4 * 16 * kTokCols;     // tokens per block
+// Pooling^T(dA) (Sec. 4.2: the agents are window averages of Q) for channels c .. c + 3 of token t: every agent
+// whose window holds the token hands it 1 / (window size) of its gradient.  dA: the unit's [n][d] fp32 rows.
+__device__ __forceinline__ f32x4 pool_adjoint4(const float* dA, int t, int c, int d, int gh, int gw, int ah, int aw) {
+  const int y = t / gw, x = t - y * gw;
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (gh % ah == 0 && gw % aw == 0) {      // disjoint equal windows: one agent per token
+    const int wh = gh / ah, ww = gw / aw;
+    v = *reinterpret_cast<const f32x4*>(dA + (size_t)((y / wh) * aw + x / ww) * d + c) * (1.0f / (float)(wh * ww));
+  } else {
+    const int ayc = (int)(((unsigned)y * (unsigned)ah) / (unsigned)gh), axc = (int)(((unsigned)x * (unsigned)aw) / (unsigned)gw);
+    for (int ay = max(0, ayc - 1); ay <= min(ah - 1, ayc + 1); ++ay) {
+      const int y0 = pool_win_lo(ay, gh, ah), y1 = pool_win_hi(ay, gh, ah);
+      if (y < y0 || y >= y1) continue;
+      for (int ax = max(0, axc - 1); ax <= min(aw - 1, axc + 1); ++ax) {
+        const int x0 = pool_win_lo(ax, gw, aw), x1 = pool_win_hi(ax, gw, aw);
+        if (x < x0 || x >= x1) continue;
+        v += *reinterpret_cast<const f32x4*>(dA + (size_t)(ay * aw + ax) * d + c) * (1.0f / (float)((y1 - y0) * (x1 - x0)));
+      }
+    }
+  }
+  return v;
+}
 
-template <class E, int DP, int PROB>
+// NK: 16-token columns per wave of the token kernels (every LDS operand feeds that many products); a block
+// holds 64 NK tokens
+
+template <class E, int DP, int PROB, int NK>
 __global__ __launch_bounds__(kThreads) void fused_token_kernel(TokenArgs a) {
   using G = Geo<DP>;
-  constexpr int NK = kTokCols;
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* m1 = reinterpret_cast<uint16_t*>(smem);
   uint16_t* m2 = m1 + a.ch_rows * G::LST;
@@ -129,7 +150,7 @@ __global__ __launch_bounds__(kThreads) void fused_token_kernel(TokenArgs a) {
   u32x4 xq[NK][G::KS], yq[NK][G::KS];
 #pragma unroll
   for (int k = 0; k < NK; ++k) {
-    t[k] = blockIdx.x * kTokBlock + (w * NK + k) * 16 + r;
+    t[k] = blockIdx.x * (64 * NK) + (w * NK + k) * 16 + r;
     tok_ok[k] = t[k] < a.N;
 #pragma unroll
     for (int ks = 0; ks < G::KS; ++ks) {
@@ -172,8 +193,8 @@ __global__ __launch_bounds__(kThreads) void fused_token_kernel(TokenArgs a) {
     }
   };
 
-  if constexpr (PROB == kBc) {
-    // pass 1: log-sum-exp and D2 of every token's row, taken per lane over the rows it holds (agents
+  if constexpr (PROB == kBcStat) {
+    // log-sum-exp and D2 of every token's row, taken per lane over the rows it holds (agents
     // 16 T + 4 g + i) with a running maximum, the four lane groups combined afterwards
     float m_l[NK], l_l[NK], dn_l[NK];
 #pragma unroll
@@ -184,44 +205,51 @@ __global__ __launch_bounds__(kThreads) void fused_token_kernel(TokenArgs a) {
         f32x4 s[NK], q[NK];
         products(T, s, q);
         const int a0 = row0 + 16 * T + 4 * g;
+        const bool ragged = row0 + 16 * T + 16 > a.n;      // only the last tile can hold rows past n
 #pragma unroll
         for (int k = 0; k < NK; ++k) {
-          float sv[4], mx = -INFINITY;
+          float sv[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) sv[i] = s[k][i] * a.sc;
+          if (ragged) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sv[i] = (a0 + i < a.n) ? sv[i] : -INFINITY;
+          }
+          const float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+          if (__builtin_amdgcn_ballot_w64(mx > m_l[k]) != 0) {      // some lane's maximum moves: rare after the first tiles
+            const float m_new = fmaxf(m_l[k], mx);      // finite: m_l starts at -1e30
+            const float alpha = fast_exp2(m_l[k] - m_new);
+            l_l[k] *= alpha;
+            dn_l[k] *= alpha;
+            m_l[k] = m_new;
+          }
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            sv[i] = (a0 + i < a.n) ? s[k][i] * a.sc : -INFINITY;
-            mx = fmaxf(mx, sv[i]);
+            const float p = fast_exp2(sv[i] - m_l[k]);
+            l_l[k] += p;
+            dn_l[k] += p * q[k][i];
           }
-          const float m_new = fmaxf(m_l[k], mx);      // finite: m_l starts at -1e30
-          const float alpha = fast_exp2(m_l[k] - m_new);
-          float sum = 0.f, dsum = 0.f;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float p = fast_exp2(sv[i] - m_new);
-            sum += p;
-            dsum += p * q[k][i];
-          }
-          l_l[k] = l_l[k] * alpha + sum;
-          dn_l[k] = dn_l[k] * alpha + dsum;
-          m_l[k] = m_new;
         }
       }
     }
-    float lse[NK], D[NK];
 #pragma unroll
     for (int k = 0; k < NK; ++k) {
       const float M = xor16_32_max(m_l[k]);
       const float f = fast_exp2(m_l[k] - M);
       const float l = xor16_32_sum(l_l[k] * f), dn = xor16_32_sum(dn_l[k] * f);
-      lse[k] = M + __builtin_amdgcn_logf(l);      // v_log_f32: log2
-      D[k] = dn / l;
       if (g == 0 && tok_ok[k]) {
-        a.st1[ubN + t[k]] = lse[k];
-        a.st2[ubN + t[k]] = D[k];
+        a.st1[ubN + t[k]] = M + __builtin_amdgcn_logf(l);      // v_log_f32: log2
+        a.st2[ubN + t[k]] = dn / l;
       }
     }
-    // pass 2: dS2 tile by tile into the product with A.  Rows past n need no mask here: their dS meets zero
-    // rows of A.
+  } else if constexpr (PROB == kBc) {
+    // dS2 tile by tile into the product with A.  Rows past n need no mask here: their dS meets zero rows of A.
+    float lse[NK], D[NK];
+#pragma unroll
+    for (int k = 0; k < NK; ++k) {
+      lse[k] = tok_ok[k] ? a.st1[ubN + t[k]] : 0.f;
+      D[k] = tok_ok[k] ? a.st2[ubN + t[k]] : 0.f;
+    }
     f32x4 acc[NK][G::CC];
 #pragma unroll
     for (int k = 0; k < NK; ++k)
@@ -255,8 +283,12 @@ __global__ __launch_bounds__(kThreads) void fused_token_kernel(TokenArgs a) {
 #pragma unroll
     for (int k = 0; k < NK; ++k)
 #pragma unroll
-      for (int cc = 0; cc < G::CC; ++cc)
-        store_token_tile<E>(a.O1, a.o1_f32 != 0, ubN + t[k], a.d, cc, g, acc[k][cc] * a.oscale, tok_ok[k]);
+      for (int cc = 0; cc < G::CC; ++cc) {
+        f32x4 v = acc[k][cc] * a.oscale;
+        const int c = cc * 16 + 4 * g;
+        if (a.dA && tok_ok[k] && c < a.d) v += pool_adjoint4(a.dA + ubn * a.d, t[k], c, a.d, a.gh, a.gw, a.ah, a.aw);
+        store_token_tile<E>(a.O1, ubN + t[k], a.d, cc, g, v, tok_ok[k]);
+      }
   } else {
     f32x4 accK[NK][G::CC], accV[NK][G::CC];
 #pragma unroll
@@ -298,7 +330,7 @@ __global__ __launch_bounds__(kThreads) void fused_token_kernel(TokenArgs a) {
     for (int k = 0; k < NK; ++k)
 #pragma unroll
       for (int cc = 0; cc < G::CC; ++cc) {
-        store_token_tile<E>(a.O1, false, ubN + t[k], a.d, cc, g, accK[k][cc] * a.oscale, tok_ok[k]);
+        store_token_tile<E>(a.O1, ubN + t[k], a.d, cc, g, accK[k][cc] * a.oscale, tok_ok[k]);
         f32x4 dv = accV[k][cc];
         const int c = cc * 16 + 4 * g;
         if (a.vk != 0.0f && tok_ok[k] && c < a.d) {      // dV += k dO
@@ -308,7 +340,7 @@ __global__ __launch_bounds__(kThreads) void fused_token_kernel(TokenArgs a) {
           Mx<E>::unpack2(go[1], g2, g3);
           dv += f32x4{g0, g1, g2, g3} * a.vk;
         }
-        store_token_tile<E>(a.O2, false, ubN + t[k], a.d, cc, g, dv, tok_ok[k]);
+        store_token_tile<E>(a.O2, ubN + t[k], a.d, cc, g, dv, tok_ok[k]);
       }
   }
 }
@@ -456,30 +488,37 @@ __global__ __launch_bounds__(kThreads) void fused_agent_kernel(AgentArgs a) {
     for (int k = 0; k < NA; ++k) {
       dop[k] = u32x4{0u, 0u, 0u, 0u};
       if constexpr (PROB == kFwd) {
+        const bool ragged = t0 + kTileRows > t_end;      // only the range's last tile can hold rows past its end
         float mx = -INFINITY;
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float sc = (t0 + 16 * j + 4 * g + i < t_end) ? sv[k][j][i] * a.sc : -INFINITY;
+            float sc = sv[k][j][i] * a.sc;
+            if (ragged) sc = (t0 + 16 * j + 4 * g + i < t_end) ? sc : -INFINITY;
             sv[k][j][i] = sc;
             mx = fmaxf(mx, sc);
           }
-        mx = xor16_32_max(mx);
-        const float m_new = fmaxf(m_run[k], mx);      // finite: the tile holds at least one token of the range
-        const float alpha = fast_exp2(m_run[k] - m_new);
+        // The running maximum is per lane group here (rows 4 g + i of the tiles) and shared by the four groups
+        // only when it moves: then every group takes the agent's maximum over the whole tile, so the groups'
+        // accumulators keep one common scale.
+        if (__builtin_amdgcn_ballot_w64(mx > m_run[k]) != 0) {
+          const float m_new = fmaxf(m_run[k], xor16_32_max(mx));      // finite: the tile holds a token of the range
+          const float alpha = fast_exp2(m_run[k] - m_new);
+          l_run[k] *= alpha;
+          m_run[k] = m_new;
+#pragma unroll
+          for (int cc = 0; cc < G::CC; ++cc) acc1[k][cc] *= alpha;
+        }
         float sum = 0.f;
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            sv[k][j][i] = fast_exp2(sv[k][j][i] - m_new);
+            sv[k][j][i] = fast_exp2(sv[k][j][i] - m_run[k]);
             sum += sv[k][j][i];
           }
-        l_run[k] = l_run[k] * alpha + sum;      // per lane group; the groups are added at the end
-        m_run[k] = m_new;
-#pragma unroll
-        for (int cc = 0; cc < G::CC; ++cc) acc1[k][cc] *= alpha;
+        l_run[k] += sum;      // per lane group; the groups are added at the end
         const u32x2 p0 = pack4<E>(sv[k][0][0], sv[k][0][1], sv[k][0][2], sv[k][0][3]),
                     p1 = pack4<E>(sv[k][1][0], sv[k][1][1], sv[k][1][2], sv[k][1][3]);
         pop[k] = u32x4{p0[0], p0[1], p1[0], p1[1]};
@@ -630,14 +669,15 @@ __global__ __launch_bounds__(64) void fused_reduce_agg_kernel(const float* __res
 // host side
 // ---------------------------------------------------------------------------
 struct FusedPlan {
-  int DP, n_rows, ch_rows, agent_blocks, S, chunk, token_blocks;
+  int DP, n_rows, ch_rows, agent_blocks, S, chunk;
+  bool wide;
   // workspace offsets in floats (every region a multiple of 64 floats)
-  size_t VAf, VAe, dVAe, lse1, D1, lse2, D2, dAf, dQf, part, total;
+  size_t VAf, VAe, dVAe, lse1, D1, lse2, D2, dAf, part, total;
 };
 
 size_t up64(size_t v) { return (v + 63) / 64 * 64; }
 
-FusedPlan fused_plan(const Problem& p, bool pooled) {
+FusedPlan fused_plan(const Problem& p) {
   FusedPlan f{};
   f.DP = p.d <= 32 ? 32 : (p.d <= 64 ? 64 : 128);
   f.n_rows = (p.n + 31) / 32 * 32;      // the token kernels take agent tiles in pairs
@@ -650,7 +690,8 @@ FusedPlan fused_plan(const Problem& p, bool pooled) {
   S = max(S, 1);
   f.chunk = ((p.N + S - 1) / S + 31) / 32 * 32;
   f.S = (p.N + f.chunk - 1) / f.chunk;
-  f.token_blocks = (p.N + kTokBlock - 1) / kTokBlock;
+  // four token columns per wave in the broadcast's token kernels when that still leaves two blocks per CU
+  f.wide = f.DP <= 64 && (long long)((p.N + 255) / 256) * p.units >= 2 * kComputeUnits;
   const size_t u = (size_t)p.units, nd = up64((size_t)p.n * p.d), un = up64(u * p.n), uN = up64(u * p.N);
   size_t o = 0;
   f.VAf = o, o += u * nd;
@@ -661,7 +702,6 @@ FusedPlan fused_plan(const Problem& p, bool pooled) {
   f.lse2 = o, o += uN;
   f.D2 = o, o += uN;
   f.dAf = o, o += u * nd;
-  f.dQf = o, o += pooled ? up64(u * p.N * p.d) : 0;
   f.part = o, o += up64(u * f.S * p.n * (size_t)(2 * p.d + 2));
   f.total = o;
   return f;
@@ -676,7 +716,7 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
   float* VAf = ws + f.VAf;
   uint16_t* VAe = reinterpret_cast<uint16_t*>(ws + f.VAe);
   uint16_t* dVAe = reinterpret_cast<uint16_t*>(ws + f.dVAe);
-  float *lse1 = ws + f.lse1, *D1 = ws + f.D1, *lse2 = ws + f.lse2, *D2 = ws + f.D2, *dAf = ws + f.dAf, *dQf = ws + f.dQf;
+  float *lse1 = ws + f.lse1, *D1 = ws + f.D1, *lse2 = ws + f.lse2, *D2 = ws + f.D2, *dAf = ws + f.dAf;
   const size_t part_rows = (size_t)U * f.S * n;
   float* part1 = ws + f.part;
   float* part2 = part1 + part_rows * d;
@@ -686,10 +726,15 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
 
   const size_t agent_lds = (size_t)4 * 32 * G::LST * 2 + 2 * 64 * sizeof(float);
   const size_t token_lds = (size_t)2 * f.ch_rows * G::LST * 2 + (size_t)2 * f.ch_rows * sizeof(float);
-  const dim3 agrid(f.S, f.agent_blocks, U), tgrid(f.token_blocks, U), rgrid(n, U);
+  const dim3 agrid(f.S, f.agent_blocks, U), rgrid(n, U);
+  const dim3 tgrid2((N + 127) / 128, U), tgrid4((N + 255) / 256, U);
+  constexpr int NW = DP <= 64 ? 4 : 2;      // the wide form is never chosen at DP = 128
   hipError_t e;
-  if ((e = allow_lds(fused_token_kernel<E, DP, kBc>, token_lds)) != hipSuccess) return e;
-  if ((e = allow_lds(fused_token_kernel<E, DP, kAgg>, token_lds)) != hipSuccess) return e;
+  if ((e = allow_lds(fused_token_kernel<E, DP, kBc, 2>, token_lds)) != hipSuccess) return e;
+  if ((e = allow_lds(fused_token_kernel<E, DP, kBcStat, 2>, token_lds)) != hipSuccess) return e;
+  if ((e = allow_lds(fused_token_kernel<E, DP, kBc, NW>, token_lds)) != hipSuccess) return e;
+  if ((e = allow_lds(fused_token_kernel<E, DP, kBcStat, NW>, token_lds)) != hipSuccess) return e;
+  if ((e = allow_lds(fused_token_kernel<E, DP, kAgg, 2>, token_lds)) != hipSuccess) return e;
 
   AgentArgs ag{};
   ag.N = N, ag.n = n, ag.d = d, ag.chunk = f.chunk, ag.S = f.S;
@@ -701,26 +746,30 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
   // broadcast: per-token gradient and row statistics, then the per-agent sums
   TokenArgs tk{};
   tk.N = N, tk.n = n, tk.d = d, tk.n_rows = f.n_rows, tk.ch_rows = f.ch_rows;
+  tk.gh = p.gh, tk.gw = p.gw, tk.ah = p.ah, tk.aw = p.aw;
   tk.X = Q, tk.Y = dO, tk.M1 = A, tk.M2 = VAe, tk.st1 = lse2, tk.st2 = D2, tk.sc = sc2, tk.oscale = p.scale2;
-  tk.O1 = agents_given ? dQ : (void*)dQf, tk.o1_f32 = agents_given ? 0 : 1;
-  fused_token_kernel<E, DP, kBc><<<tgrid, dim3(kThreads), token_lds, st>>>(tk);
+  if (f.wide)
+    fused_token_kernel<E, DP, kBcStat, NW><<<tgrid4, dim3(kThreads), token_lds, st>>>(tk);
+  else
+    fused_token_kernel<E, DP, kBcStat, 2><<<tgrid2, dim3(kThreads), token_lds, st>>>(tk);
   ag.X = Q, ag.Y = dO, ag.M2 = VAe, ag.ts1 = lse2, ag.ts2 = D2, ag.P1 = part1, ag.P2 = part2, ag.sc = sc2;
   fused_agent_kernel<E, DP, kBc><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
   fused_reduce_bc_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, part2, f.S, n, d, VAf, dVAe, D1, dAf, p.scale2);
 
   // aggregation
   tk.X = K, tk.Y = V, tk.M2 = dVAe, tk.rs1 = lse1, tk.rs2 = D1, tk.sc = sc1, tk.oscale = p.scale1;
-  tk.O1 = dK, tk.O2 = dV, tk.o1_f32 = 0, tk.G = dO, tk.vk = p.vk;
-  fused_token_kernel<E, DP, kAgg><<<tgrid, dim3(kThreads), token_lds, st>>>(tk);
+  tk.O1 = dK, tk.O2 = dV, tk.G = dO, tk.vk = p.vk;
+  fused_token_kernel<E, DP, kAgg, 2><<<tgrid2, dim3(kThreads), token_lds, st>>>(tk);
   ag.X = K, ag.Y = V, ag.M2 = dVAe, ag.rs1 = lse1, ag.rs2 = D1, ag.P1 = part1, ag.sc = sc1;
   fused_agent_kernel<E, DP, kAgg><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
   fused_reduce_agg_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, f.S, n, d, dAf, agents_given ? (uint16_t*)dA : nullptr,
                                                          p.scale1);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (!agents_given) {
-    if ((e = backward_pool_adjoint(p, dQf, dAf, st)) != hipSuccess) return e;
-    if ((e = backward_from_f32(p.dtype, dQf, dQ, (size_t)U * N * d, st)) != hipSuccess) return e;
-  }
+  // dQ last: the pooling term needs the finished dA
+  tk.X = Q, tk.Y = dO, tk.M2 = VAe, tk.sc = sc2, tk.oscale = p.scale2, tk.O1 = dQ, tk.dA = agents_given ? nullptr : dAf;
+  if (f.wide)
+    fused_token_kernel<E, DP, kBc, NW><<<tgrid4, dim3(kThreads), token_lds, st>>>(tk);
+  else
+    fused_token_kernel<E, DP, kBc, 2><<<tgrid2, dim3(kThreads), token_lds, st>>>(tk);
   return hipGetLastError();
 }
 
@@ -744,12 +793,12 @@ bool backward_fused_supported(const Problem& p) {
          !p.b2.any() && !p.dwc_w;
 }
 
-size_t backward_fused_workspace_floats(const Problem& p, bool pooled) { return fused_plan(p, pooled).total; }
+size_t backward_fused_workspace_floats(const Problem& p) { return fused_plan(p).total; }
 
 hipError_t launch_backward_fused(const Problem& p, const void* Q, const void* K, const void* V, const void* A_elem,
                                  const void* dO, float* ws, void* dQ, void* dK, void* dV, void* dA, bool agents_given,
                                  hipStream_t st) {
-  const FusedPlan f = fused_plan(p, !agents_given);
+  const FusedPlan f = fused_plan(p);
   if (p.dtype == 2) return run_fused_dp<ElemBF16>(p, f, Q, K, V, A_elem, dO, ws, dQ, dK, dV, dA, agents_given, st);
   return run_fused_dp<ElemF16>(p, f, Q, K, V, A_elem, dO, ws, dQ, dK, dV, dA, agents_given, st);
 }

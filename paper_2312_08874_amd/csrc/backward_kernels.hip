@@ -862,25 +862,8 @@ hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, 
 
 }  // namespace
 
-hipError_t backward_pool_adjoint(const Problem& p, float* dQf, const float* dAf, hipStream_t st) {
-  const size_t all = (size_t)p.units * p.N * p.d;
-  if (p.d % 4 == 0) {
-    const size_t count = all / 4;
-    pool_grad_kernel<4><<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(dQf, dAf, p.N, p.n, p.d, p.gh, p.gw,
-                                                                                    p.ah, p.aw, count);
-  } else {
-    pool_grad_kernel<1><<<dim3((unsigned)((all + 255) / 256)), dim3(256), 0, st>>>(dQf, dAf, p.N, p.n, p.d, p.gh, p.gw, p.ah,
-                                                                                  p.aw, all);
-  }
-  return hipGetLastError();
-}
-
-hipError_t backward_from_f32(int dtype, const float* src, void* dst, size_t count, hipStream_t st) {
-  return from_f32(dtype, src, dst, count, st);
-}
-
 size_t backward_workspace_floats(const Problem& p) {
-  if (backward_fused_supported(p)) return backward_fused_workspace_floats(p, true);
+  if (backward_fused_supported(p)) return backward_fused_workspace_floats(p);
   const size_t u = (size_t)p.units, Nd = (size_t)p.N * p.d, nd = (size_t)p.n * p.d;
   // fp32 path: Q, K, V, dO, dQ, dK, dV (7 x N*d), A, V_A, dV_A, dA (4 x n*d), P1, dS1, P2, dS2 (4 x n*N).
   // 16-bit path: 5 x N*d + n*d fp32, the two score matrices in fp32 and four 16-bit copies (rows padded

@@ -90,17 +90,12 @@ hipError_t launch_backward(const Problem& p, const void* Q, const void* K, const
 // Backward without the attention matrices in memory (score tiles recomputed in the kernels that use them):
 // fp16 / bf16, d a multiple of 8 up to 128, no agent bias and no DWC (the V residual is handled); every tensor
 // 16-byte aligned.  launch_backward takes this path whenever the problem allows it, and the workspace figure
-// above is then this path's (a few n x d and N-long arrays, split partial sums, an fp32 dQ when the agents are
-// pooled).
+// above is then this path's (a few n x d and N-long arrays, split partial sums).
 bool backward_fused_supported(const Problem& p);
-size_t backward_fused_workspace_floats(const Problem& p, bool pooled);
+size_t backward_fused_workspace_floats(const Problem& p);
 hipError_t launch_backward_fused(const Problem& p, const void* Q, const void* K, const void* V, const void* A_elem,
                                  const void* dO, float* ws, void* dQ, void* dK, void* dV, void* dA, bool agents_given,
                                  hipStream_t st);
-// pieces of the reference backward the fused one reuses: dQf += Pooling^T(dAf) on dense fp32 arrays, and the
-// rounding of an fp32 array to the element type
-hipError_t backward_pool_adjoint(const Problem& p, float* dQf, const float* dAf, hipStream_t st);
-hipError_t backward_from_f32(int dtype, const float* src, void* dst, size_t count, hipStream_t st);
 
 // --- small-agent regime (n <= 64, d in {32, 64}, fp16 / bf16): MFMA kernels that keep A and V_A in
 //     registers and stream tokens straight from global memory ---

@@ -105,9 +105,9 @@ def backward_summary(d, wl):
             name = re.sub(r"\(.*", "", name)
             if name.startswith(BACKWARD_KERNELS):
                 rows.append((name, int(r["Calls"]), float(r["AverageNs"]) / 1e3))
-    ncalls = min(c for n, c, a in rows if n.startswith("pool_grad_kernel") or n.startswith("from_f32_kernel")) if rows else 1
-    pg = [c for n, c, a in rows if n.startswith("pool_grad_kernel")]
-    ncalls = pg[0] if pg else ncalls
+    # kernels that run once per backward call
+    once = [c for n, c, a in rows if n.startswith(("fused_merge_kernel", "pool_grad_kernel", "from_f32_x3_kernel"))]
+    ncalls = min(once) if once else 1
     total = 0.0
     for name, calls, avg in rows:
         per = calls * avg / ncalls
