@@ -134,8 +134,10 @@ __device__ __forceinline__ f32x4 pool_adjoint4(const float* dA, int t, int c, in
 // NK: 16-token columns per wave of the token kernels (every LDS operand feeds that many products); a block
 // holds 64 NK tokens
 
+// Two blocks per CU asked for wherever the registers allow: with at most 256 registers per lane the compiler keeps
+// the MFMA accumulators in ordinary registers instead of copying them in and out of the accumulator file.
 template <class E, int DP, int PROB, int NK>
-__global__ __launch_bounds__(kThreads) void fused_token_kernel(TokenArgs a) {
+__global__ __launch_bounds__(kThreads, (DP == 128 && PROB == kAgg) ? 1 : 2) void fused_token_kernel(TokenArgs a) {
   using G = Geo<DP>;
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* m1 = reinterpret_cast<uint16_t*>(smem);
@@ -366,7 +368,7 @@ template <int DP>
 constexpr int agent_cols() { return DP == 128 ? 1 : 2; }      // 16-agent columns per wave (registers allowing)
 
 template <class E, int DP, int PROB>
-__global__ __launch_bounds__(kThreads) void fused_agent_kernel(AgentArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void fused_agent_kernel(AgentArgs a) {
   using G = Geo<DP>;
   constexpr int NA = agent_cols<DP>();
   constexpr int kTileRows = 32;

@@ -17,7 +17,8 @@ DIR holds one run with the backward pass timed as well:
 writes profiles/W_backward_kernels.md (durations of the backward pass's kernels only).
 
 usage: python profile_summary.py DIR W counters [MODE]
-DIR holds one run with eight SQ counters (MODE = pure, the default, or module):
+DIR holds one run with eight SQ counters (MODE = pure, the default, module, or backward = pure with --backward
+added to the bench.py command: then only the backward pass's kernels are listed):
   rocprofv3 --pmc SQ_BUSY_CU_CYCLES SQ_INSTS_VALU SQ_INSTS_MFMA SQ_ACTIVE_INST_VALU SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_LDS SQ_ACTIVE_INST_LDS SQ_LDS_BANK_CONFLICT --kernel-trace --output-format csv -d DIR -o sq -- python3 bench.py --workload W --mode MODE --no-others --no-cpu-baseline --no-traffic --steps 20 --warmup 5
 writes profiles/W_sq_counters.md (profiles/W_module_sq_counters.md): per kernel the launch shape, registers,
 LDS, the median of every counter per dispatch and the ratios used in the design notes.
@@ -123,9 +124,13 @@ SQ_COUNTERS = ("SQ_BUSY_CU_CYCLES", "SQ_INSTS_VALU", "SQ_INSTS_MFMA", "SQ_ACTIVE
                "SQ_INSTS_LDS", "SQ_ACTIVE_INST_LDS", "SQ_LDS_BANK_CONFLICT")
 
 
+BACKWARD_FUSED = ("fused_token_kernel", "fused_agent_kernel", "fused_merge_kernel", "fused_reduce_")
+
+
 def counters_summary(d, wl, mode):
+    bench_mode = "pure --backward" if mode == "backward" else mode
     cmd = ("rocprofv3 --pmc %s --kernel-trace --output-format csv -d DIR -o sq -- python3 bench.py --workload %s "
-           "--mode %s --no-others --no-cpu-baseline --no-traffic --steps 20 --warmup 5" % (" ".join(SQ_COUNTERS), wl, mode))
+           "--mode %s --no-others --no-cpu-baseline --no-traffic --steps 20 --warmup 5" % (" ".join(SQ_COUNTERS), wl, bench_mode))
     per = {}
     with open(os.path.join(d, "sq_counter_collection.csv")) as f:
         for r in csv.DictReader(f):
@@ -133,12 +138,14 @@ def counters_summary(d, wl, mode):
             if not k.startswith(("small_", "pool_", "aggregate_", "merge_", "broadcast_", "large_", "bias_", "fused_",
                                  "(anonymous namespace)::fused_")):
                 continue
+            if (mode == "backward") != k.startswith(BACKWARD_FUSED):      # the backward's kernels, or all the others
+                continue
             e = per.setdefault(k, {"c": {}, "dur": [], "shape": None})
             e["c"].setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
             e["dur"].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
             e["shape"] = (int(r["Grid_Size"]), int(r["Workgroup_Size"]), int(r["VGPR_Count"]), int(r["Accum_VGPR_Count"]),
                           int(r["LDS_Block_Size"]), int(r["Scratch_Size"]))
-    lines = ["# SQ counters: bench.py --workload %s --mode %s (one MI355X)" % (wl, mode), "", "command: `%s`" % cmd, "",
+    lines = ["# SQ counters: bench.py --workload %s --mode %s (one MI355X)" % (wl, bench_mode), "", "command: `%s`" % cmd, "",
              "Medians over the dispatches of each kernel; counter values are sums over the chip as rocprofv3 reports "
              "them.  Kernel durations under counter collection are longer than in the timing runs.", "",
              "| kernel | grid threads | block | VGPRs (+acc) | LDS B | scratch B | us under collection |",
