@@ -48,18 +48,6 @@ __device__ __forceinline__ u32x4 load16(const uint16_t* p, bool ok) {
   return v;
 }
 
-// rows [row0, row0 + rows) of a dense [rows_total][d] matrix into an LDS image [rows][LST], zeros elsewhere
-template <int DP>
-__device__ __forceinline__ void stage_rows(uint16_t* lds, const uint16_t* src, int row0, int rows, int rows_total, int d,
-                                           int tid) {
-  using G = Geo<DP>;
-  for (int i = tid; i < rows * G::CPR; i += kThreads) {
-    const int r = i / G::CPR, c = i - r * G::CPR;
-    const bool ok = row0 + r < rows_total && c * 8 < d;
-    *reinterpret_cast<u32x4*>(lds + r * G::LST + c * 8) = load16(src + (size_t)(row0 + r) * d + c * 8, ok);
-  }
-}
-
 // MFMA operand of rows [16 * tile, +16) for k-step ks (lane r, g: row r, channels 32 ks + 8 g ...)
 template <int DP>
 __device__ __forceinline__ u32x4 row_operand(const uint16_t* lds, int tile, int ks, int r, int g) {
@@ -162,11 +150,36 @@ __global__ __launch_bounds__(kThreads, (DP == 128 && PROB == kAgg) ? 1 : 2) void
       yq[k][ks] = load16(a.Y + (ubN + t[k]) * a.d + c8, ok);
     }
   }
-  // agents [row0, row0 + ch_rows) into LDS; returns the number of 16-agent tiles staged (even)
+  // agents [row0, row0 + ch_rows) into LDS; returns the number of 16-agent tiles staged (even).  A chunk has at
+  // most 128 rows, i.e. NPC 16-byte pieces per thread and matrix, whose places are worked out once.
+  constexpr int NPC = 128 * G::CPR / kThreads;
+  int goff[NPC], loff[NPC], prow[NPC];
+#pragma unroll
+  for (int j = 0; j < NPC; ++j) {
+    const int i = tid + j * kThreads, c = i % G::CPR;
+    prow[j] = i / G::CPR;
+    goff[j] = prow[j] * a.d + c * 8;
+    loff[j] = prow[j] * G::LST + c * 8;
+    if (c * 8 >= a.d) prow[j] |= 1 << 20;      // a column past d: reads as a row past n, still written (as zeros)
+  }
   auto stage = [&](int row0) {
     __syncthreads();      // the previous chunk has been read by every wave
-    stage_rows<DP>(m1, a.M1 + ubn * a.d, row0, a.ch_rows, a.n, a.d, tid);
-    stage_rows<DP>(m2, a.M2 + ubn * a.d, row0, a.ch_rows, a.n, a.d, tid);
+    const uint16_t* b1 = a.M1 + (ubn + row0) * a.d;
+    const uint16_t* b2 = a.M2 + (ubn + row0) * a.d;
+    u32x4 v1[NPC], v2[NPC];
+#pragma unroll
+    for (int j = 0; j < NPC; ++j) {
+      const bool ok = row0 + prow[j] < a.n;
+      v1[j] = load16(b1 + goff[j], ok);
+      v2[j] = load16(b2 + goff[j], ok);
+    }
+#pragma unroll
+    for (int j = 0; j < NPC; ++j) {
+      if ((prow[j] & 0xFFFFF) < a.ch_rows) {
+        *reinterpret_cast<u32x4*>(m1 + loff[j]) = v1[j];
+        *reinterpret_cast<u32x4*>(m2 + loff[j]) = v2[j];
+      }
+    }
     if constexpr (PROB == kAgg) {
       for (int i = tid; i < a.ch_rows; i += kThreads) {
         rs[i] = row0 + i < a.n ? a.rs1[ubn + row0 + i] : kMasked;

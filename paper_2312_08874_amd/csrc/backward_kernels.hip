@@ -312,7 +312,7 @@ __device__ __forceinline__ void mfma_matmul_tile(const MatmulArgs& m, int tile_r
 
 // grid = (column tiles, row tiles, units * ksplit)
 template <class E, bool TA, bool TB, int OUT>
-__global__ __launch_bounds__(256) void mfma_matmul_kernel(MatmulArgs m, int ksplit, int kchunk) {
+__global__ __launch_bounds__(256, 2) void mfma_matmul_kernel(MatmulArgs m, int ksplit, int kchunk) {
   __shared__ __attribute__((aligned(16))) uint16_t As[64][kLdsK];
   __shared__ __attribute__((aligned(16))) uint16_t Bs[64][kLdsK];
   mfma_matmul_tile<E, TA, TB, OUT>(m, blockIdx.y, blockIdx.x, blockIdx.z, ksplit, kchunk, As, Bs);
@@ -322,7 +322,7 @@ __global__ __launch_bounds__(256) void mfma_matmul_kernel(MatmulArgs m, int kspl
 // path, so sharing a launch is worth more than the idle blocks of the smaller one):
 // grid = (tiles of m0 + tiles of m1, units): the first tiles0 blocks of a unit work on m0.
 template <class E, bool TA, bool TB, int OUT>
-__global__ __launch_bounds__(256) void mfma_matmul_pair_kernel(MatmulArgs m0, MatmulArgs m1, int tiles0) {
+__global__ __launch_bounds__(256, 2) void mfma_matmul_pair_kernel(MatmulArgs m0, MatmulArgs m1, int tiles0) {
   __shared__ __attribute__((aligned(16))) uint16_t As[64][kLdsK];
   __shared__ __attribute__((aligned(16))) uint16_t Bs[64][kLdsK];
   const bool second = (int)blockIdx.x >= tiles0;
