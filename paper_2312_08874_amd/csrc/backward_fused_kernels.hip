@@ -381,7 +381,7 @@ template <int DP>
 constexpr int agent_cols() { return DP == 128 ? 1 : 2; }      // 16-agent columns per wave (registers allowing)
 
 template <class E, int DP, int PROB>
-__global__ __launch_bounds__(kThreads, 2) void fused_agent_kernel(AgentArgs a) {
+__global__ __launch_bounds__(kThreads, PROB == kBc ? 2 : 3) void fused_agent_kernel(AgentArgs a) {
   using G = Geo<DP>;
   constexpr int NA = agent_cols<DP>();
   constexpr int kTileRows = 32;
@@ -684,7 +684,7 @@ __global__ __launch_bounds__(64) void fused_reduce_agg_kernel(const float* __res
 // host side
 // ---------------------------------------------------------------------------
 struct FusedPlan {
-  int DP, n_rows, ch_rows, agent_blocks, S, chunk;
+  int DP, n_rows, ch_rows, agent_blocks, S[2], chunk[2];      // [0]: agent kBc, [1]: agent kFwd / kAgg
   bool wide;
   // workspace offsets in floats (every region a multiple of 64 floats)
   size_t VAf, VAe, dVAe, lse1, D1, lse2, D2, dAf, part, total;
@@ -700,11 +700,14 @@ FusedPlan fused_plan(const Problem& p) {
   const int per_block = 64 * (f.DP == 128 ? 1 : 2);      // agents per block of the agent kernels (agent_cols)
   f.agent_blocks = (p.n + per_block - 1) / per_block;
   const int groups = f.agent_blocks * p.units;
-  int S = (2 * kComputeUnits + groups - 1) / groups;      // about two blocks per CU (four measured no faster)
-  S = min(min(S, 64), (p.N + 127) / 128);                 // at most 64: the merge gives every range a lane
-  S = max(S, 1);
-  f.chunk = ((p.N + S - 1) / S + 31) / 32 * 32;
-  f.S = (p.N + f.chunk - 1) / f.chunk;
+  // token ranges: about two blocks per CU for the broadcast's agent kernel (192 registers), three for the other
+  // two (which fit three blocks; four measured no faster).  At most 64: the merge gives every range a lane.
+  for (int k = 0; k < 2; ++k) {
+    int S = ((2 + k) * kComputeUnits + groups - 1) / groups;
+    S = max(min(min(S, 64), (p.N + 127) / 128), 1);
+    f.chunk[k] = ((p.N + S - 1) / S + 31) / 32 * 32;
+    f.S[k] = (p.N + f.chunk[k] - 1) / f.chunk[k];
+  }
   // four token columns per wave in the broadcast's token kernels when that still leaves two blocks per CU
   f.wide = f.DP <= 64 && (long long)((p.N + 255) / 256) * p.units >= 2 * kComputeUnits;
   const size_t u = (size_t)p.units, nd = up64((size_t)p.n * p.d), un = up64(u * p.n), uN = up64(u * p.N);
@@ -717,7 +720,7 @@ FusedPlan fused_plan(const Problem& p) {
   f.lse2 = o, o += uN;
   f.D2 = o, o += uN;
   f.dAf = o, o += u * nd;
-  f.part = o, o += up64(u * f.S * p.n * (size_t)(2 * p.d + 2));
+  f.part = o, o += up64(u * max(f.S[0], f.S[1]) * p.n * (size_t)(2 * p.d + 2));
   f.total = o;
   return f;
 }
@@ -732,16 +735,15 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
   uint16_t* VAe = reinterpret_cast<uint16_t*>(ws + f.VAe);
   uint16_t* dVAe = reinterpret_cast<uint16_t*>(ws + f.dVAe);
   float *lse1 = ws + f.lse1, *D1 = ws + f.D1, *lse2 = ws + f.lse2, *D2 = ws + f.D2, *dAf = ws + f.dAf;
-  const size_t part_rows = (size_t)U * f.S * n;
   float* part1 = ws + f.part;
-  float* part2 = part1 + part_rows * d;
-  float* pm = part1 + part_rows * d;      // kFwd only (part2 is kBc only)
-  float* pl = pm + part_rows;
+  float* part2 = part1 + (size_t)U * f.S[0] * n * d;      // kBc only
+  float* pm = part1 + (size_t)U * f.S[1] * n * d;         // kFwd only
+  float* pl = pm + (size_t)U * f.S[1] * n;
   const float sc1 = p.scale1 * kLog2e, sc2 = p.scale2 * kLog2e;
 
   const size_t agent_lds = (size_t)4 * 32 * G::LST * 2 + 2 * 64 * sizeof(float);
   const size_t token_lds = (size_t)2 * f.ch_rows * G::LST * 2 + (size_t)2 * f.ch_rows * sizeof(float);
-  const dim3 agrid(f.S, f.agent_blocks, U), rgrid(n, U);
+  const dim3 agrid_bc(f.S[0], f.agent_blocks, U), agrid(f.S[1], f.agent_blocks, U), rgrid(n, U);
   const dim3 tgrid2((N + 127) / 128, U), tgrid4((N + 255) / 256, U);
   constexpr int NW = DP <= 64 ? 4 : 2;      // the wide form is never chosen at DP = 128
   hipError_t e;
@@ -752,11 +754,11 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
   if ((e = allow_lds(fused_token_kernel<E, DP, kAgg, 2>, token_lds)) != hipSuccess) return e;
 
   AgentArgs ag{};
-  ag.N = N, ag.n = n, ag.d = d, ag.chunk = f.chunk, ag.S = f.S;
+  ag.N = N, ag.n = n, ag.d = d, ag.chunk = f.chunk[1], ag.S = f.S[1];
   // the aggregation again: V_A and the log-sum-exp of its rows
   ag.X = K, ag.Y = V, ag.M1 = A, ag.M2 = nullptr, ag.P1 = part1, ag.pm = pm, ag.pl = pl, ag.sc = sc1;
   fused_agent_kernel<E, DP, kFwd><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
-  fused_merge_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, pm, pl, f.S, n, d, VAf, VAe, lse1);
+  fused_merge_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, pm, pl, f.S[1], n, d, VAf, VAe, lse1);
 
   // broadcast: per-token gradient and row statistics, then the per-agent sums
   TokenArgs tk{};
@@ -768,16 +770,18 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
   else
     fused_token_kernel<E, DP, kBcStat, 2><<<tgrid2, dim3(kThreads), token_lds, st>>>(tk);
   ag.X = Q, ag.Y = dO, ag.M2 = VAe, ag.ts1 = lse2, ag.ts2 = D2, ag.P1 = part1, ag.P2 = part2, ag.sc = sc2;
-  fused_agent_kernel<E, DP, kBc><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
-  fused_reduce_bc_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, part2, f.S, n, d, VAf, dVAe, D1, dAf, p.scale2);
+  ag.chunk = f.chunk[0], ag.S = f.S[0];
+  fused_agent_kernel<E, DP, kBc><<<agrid_bc, dim3(kThreads), agent_lds, st>>>(ag);
+  fused_reduce_bc_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, part2, f.S[0], n, d, VAf, dVAe, D1, dAf, p.scale2);
 
   // aggregation
   tk.X = K, tk.Y = V, tk.M2 = dVAe, tk.rs1 = lse1, tk.rs2 = D1, tk.sc = sc1, tk.oscale = p.scale1;
   tk.O1 = dK, tk.O2 = dV, tk.G = dO, tk.vk = p.vk;
   fused_token_kernel<E, DP, kAgg, 2><<<tgrid2, dim3(kThreads), token_lds, st>>>(tk);
   ag.X = K, ag.Y = V, ag.M2 = dVAe, ag.rs1 = lse1, ag.rs2 = D1, ag.P1 = part1, ag.sc = sc1;
+  ag.chunk = f.chunk[1], ag.S = f.S[1];
   fused_agent_kernel<E, DP, kAgg><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
-  fused_reduce_agg_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, f.S, n, d, dAf, agents_given ? (uint16_t*)dA : nullptr,
+  fused_reduce_agg_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, f.S[1], n, d, dAf, agents_given ? (uint16_t*)dA : nullptr,
                                                          p.scale1);
   // dQ last: the pooling term needs the finished dA
   tk.X = Q, tk.Y = dO, tk.M2 = VAe, tk.sc = sc2, tk.oscale = p.scale2, tk.O1 = dQ, tk.dA = agents_given ? nullptr : dAf;
