@@ -23,6 +23,8 @@
 //                                 pooled: dA is complete by now)
 // Scores are taken in the log2 domain (scale * log2 e folded into one multiplication, exp2 for the weights).
 // No atomics: results are bitwise repeatable.
+#include <type_traits>
+
 #include "kernels.h"
 #include "mfma_common.h"
 
@@ -214,37 +216,44 @@ __global__ __launch_bounds__(kThreads, (DP == 128 && PROB == kAgg) ? 1 : 2) void
     float m_l[NK], l_l[NK], dn_l[NK];
 #pragma unroll
     for (int k = 0; k < NK; ++k) m_l[k] = -1.0e30f, l_l[k] = 0.f, dn_l[k] = 0.f;
+    // one agent tile; RAGGED: it may hold rows past n (only the last tiles can).  The scale is positive, so the
+    // maximum is taken on the raw products and the scale rides the exponent's multiply-add.
+    auto stat_tile = [&](int T, int row0, auto ragged_c) {
+      constexpr bool RAGGED = decltype(ragged_c)::value;
+      f32x4 s[NK], q[NK];
+      products(T, s, q);
+      const int a0 = row0 + 16 * T + 4 * g;
+#pragma unroll
+      for (int k = 0; k < NK; ++k) {
+        float sv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          sv[i] = s[k][i];
+          if constexpr (RAGGED) sv[i] = (a0 + i < a.n) ? sv[i] : -INFINITY;
+        }
+        const float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])) * a.sc;
+        if (__builtin_amdgcn_ballot_w64(mx > m_l[k]) != 0) {      // some lane's maximum moves: rare after the first tiles
+          const float m_new = fmaxf(m_l[k], mx);      // finite: m_l starts at -1e30
+          const float alpha = fast_exp2(m_l[k] - m_new);
+          l_l[k] *= alpha;
+          dn_l[k] *= alpha;
+          m_l[k] = m_new;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float p = fast_exp2(fmaf(sv[i], a.sc, -m_l[k]));
+          l_l[k] += p;
+          dn_l[k] = fmaf(p, q[k][i], dn_l[k]);
+        }
+      }
+    };
     for (int row0 = 0; row0 < a.n_rows; row0 += a.ch_rows) {
       const int tiles = stage(row0);
       for (int T = 0; T < tiles; ++T) {
-        f32x4 s[NK], q[NK];
-        products(T, s, q);
-        const int a0 = row0 + 16 * T + 4 * g;
-        const bool ragged = row0 + 16 * T + 16 > a.n;      // only the last tile can hold rows past n
-#pragma unroll
-        for (int k = 0; k < NK; ++k) {
-          float sv[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) sv[i] = s[k][i] * a.sc;
-          if (ragged) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) sv[i] = (a0 + i < a.n) ? sv[i] : -INFINITY;
-          }
-          const float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-          if (__builtin_amdgcn_ballot_w64(mx > m_l[k]) != 0) {      // some lane's maximum moves: rare after the first tiles
-            const float m_new = fmaxf(m_l[k], mx);      // finite: m_l starts at -1e30
-            const float alpha = fast_exp2(m_l[k] - m_new);
-            l_l[k] *= alpha;
-            dn_l[k] *= alpha;
-            m_l[k] = m_new;
-          }
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float p = fast_exp2(sv[i] - m_l[k]);
-            l_l[k] += p;
-            dn_l[k] += p * q[k][i];
-          }
-        }
+        if (row0 + 16 * T + 16 > a.n)
+          stat_tile(T, row0, std::true_type{});
+        else
+          stat_tile(T, row0, std::false_type{});
       }
     }
 #pragma unroll
@@ -471,7 +480,9 @@ __global__ __launch_bounds__(kThreads, PROB == kBc ? 2 : 3) void fused_agent_ker
   fetch(0);
   stash(0);
   __syncthreads();
-  for (int it = 0; it < ntile; ++it) {
+  // one tile of 32 tokens; RAGGED: it may hold rows past the range's end (only the last tile can)
+  auto tile = [&](int it, auto ragged_c) {
+    constexpr bool RAGGED = decltype(ragged_c)::value;
     const int buf = it & 1;
     if (it + 1 < ntile) fetch(it + 1);
     const uint16_t* xb = xt + buf * kImage;
@@ -503,17 +514,17 @@ __global__ __launch_bounds__(kThreads, PROB == kBc ? 2 : 3) void fused_agent_ker
     for (int k = 0; k < NA; ++k) {
       dop[k] = u32x4{0u, 0u, 0u, 0u};
       if constexpr (PROB == kFwd) {
-        const bool ragged = t0 + kTileRows > t_end;      // only the range's last tile can hold rows past its end
+        // the scale is positive: the maximum is taken on the raw products, the scale rides the exponent's
+        // multiply-add
         float mx = -INFINITY;
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            float sc = sv[k][j][i] * a.sc;
-            if (ragged) sc = (t0 + 16 * j + 4 * g + i < t_end) ? sc : -INFINITY;
-            sv[k][j][i] = sc;
-            mx = fmaxf(mx, sc);
+            if constexpr (RAGGED) sv[k][j][i] = (t0 + 16 * j + 4 * g + i < t_end) ? sv[k][j][i] : -INFINITY;
+            mx = fmaxf(mx, sv[k][j][i]);
           }
+        mx *= a.sc;
         // The running maximum is per lane group here (rows 4 g + i of the tiles) and shared by the four groups
         // only when it moves: then every group takes the agent's maximum over the whole tile, so the groups'
         // accumulators keep one common scale.
@@ -530,7 +541,7 @@ __global__ __launch_bounds__(kThreads, PROB == kBc ? 2 : 3) void fused_agent_ker
         for (int j = 0; j < 2; ++j)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            sv[k][j][i] = fast_exp2(sv[k][j][i] - m_run[k]);
+            sv[k][j][i] = fast_exp2(fmaf(sv[k][j][i], a.sc, -m_run[k]));
             sum += sv[k][j][i];
           }
         l_run[k] += sum;      // per lane group; the groups are added at the end
@@ -553,7 +564,8 @@ __global__ __launch_bounds__(kThreads, PROB == kBc ? 2 : 3) void fused_agent_ker
           } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              p[i] = (t0 + 16 * j + 4 * g + i < t_end) ? fast_exp2(sv[k][j][i] * a.sc - lse_a[k]) : 0.f;
+              p[i] = fast_exp2(sv[k][j][i] * a.sc - lse_a[k]);
+              if constexpr (RAGGED) p[i] = (t0 + 16 * j + 4 * g + i < t_end) ? p[i] : 0.f;
               e[i] = p[i] * (qv[k][j][i] - d_a[k]);
             }
           }
@@ -582,7 +594,9 @@ __global__ __launch_bounds__(kThreads, PROB == kBc ? 2 : 3) void fused_agent_ker
     }
     if (it + 1 < ntile) stash(buf ^ 1);
     __syncthreads();
-  }
+  };
+  for (int it = 0; it + 1 < ntile; ++it) tile(it, std::false_type{});
+  tile(ntile - 1, std::true_type{});
 
   // lane (r, g): agents agent[k], channels 16 cc + 4 g .. + 3
 #pragma unroll
