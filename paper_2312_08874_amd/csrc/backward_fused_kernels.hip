@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kThreads, (DP == 128 && PROB == kAgg) ? 1 : 2) void
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* m1 = reinterpret_cast<uint16_t*>(smem);
   uint16_t* m2 = m1 + a.ch_rows * G::LST;
-  float* rs = reinterpret_cast<float*>(m2 + a.ch_rows * G::LST);      // kAgg: lse1[ch_rows], D1[ch_rows]
+  float* rs = reinterpret_cast<float*>(m2 + a.ch_rows * G::LST);      // kAgg: lse1[ch_rows], -D1[ch_rows]
   const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 15, g = lane >> 4;
   const size_t ubN = (size_t)u * a.N, ubn = (size_t)u * a.n;
 
@@ -185,13 +185,14 @@ __global__ __launch_bounds__(kThreads, (DP == 128 && PROB == kAgg) ? 1 : 2) void
     if constexpr (PROB == kAgg) {
       for (int i = tid; i < a.ch_rows; i += kThreads) {
         rs[i] = row0 + i < a.n ? a.rs1[ubn + row0 + i] : kMasked;
-        rs[a.ch_rows + i] = row0 + i < a.n ? a.rs2[ubn + row0 + i] : 0.0f;
+        rs[a.ch_rows + i] = row0 + i < a.n ? -a.rs2[ubn + row0 + i] : 0.0f;
       }
     }
     __syncthreads();
     return min(a.ch_rows, a.n_rows - row0) / 16;
   };
-  // both score-side products of agent tile T for the wave's token columns
+  // Both score-side products of agent tile T for the wave's token columns.  q enters holding -D, the row's
+  // sum of P o dP, so that the product returns dP - D (the accumulator input of the MFMA does the subtraction).
   auto products = [&](int T, f32x4 (&s)[NK], f32x4 (&q)[NK]) {
     u32x4 o1[G::KS], o2[G::KS];
 #pragma unroll
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(kThreads, (DP == 128 && PROB == kAgg) ? 1 : 2) void
     }
 #pragma unroll
     for (int k = 0; k < NK; ++k) {
-      s[k] = q[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+      s[k] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < G::KS; ++ks) {
         s[k] = Mx<E>::mma(o1[ks], xq[k][ks], s[k]);
@@ -221,6 +222,8 @@ __global__ __launch_bounds__(kThreads, (DP == 128 && PROB == kAgg) ? 1 : 2) void
     auto stat_tile = [&](int T, int row0, auto ragged_c) {
       constexpr bool RAGGED = decltype(ragged_c)::value;
       f32x4 s[NK], q[NK];
+#pragma unroll
+      for (int k = 0; k < NK; ++k) q[k] = f32x4{0.f, 0.f, 0.f, 0.f};
       products(T, s, q);
       const int a0 = row0 + 16 * T + 4 * g;
 #pragma unroll
@@ -286,12 +289,14 @@ __global__ __launch_bounds__(kThreads, (DP == 128 && PROB == kAgg) ? 1 : 2) void
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
           f32x4 s[NK], q[NK];
+#pragma unroll
+          for (int k = 0; k < NK; ++k) q[k] = f32x4{-D[k], -D[k], -D[k], -D[k]};
           products(T + h, s, q);
 #pragma unroll
           for (int k = 0; k < NK; ++k) {
             float e[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) e[i] = fast_exp2(s[k][i] * a.sc - lse[k]) * (q[k][i] - D[k]);
+            for (int i = 0; i < 4; ++i) e[i] = fast_exp2(s[k][i] * a.sc - lse[k]) * q[k][i];
             dd[k][h] = pack4<E>(e[0], e[1], e[2], e[3]);
           }
         }
@@ -326,17 +331,18 @@ __global__ __launch_bounds__(kThreads, (DP == 128 && PROB == kAgg) ? 1 : 2) void
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
           f32x4 s[NK], q[NK];
-          products(T + h, s, q);
           const f32x4 lse = *reinterpret_cast<const f32x4*>(rs + 16 * (T + h) + 4 * g);
-          const f32x4 d1 = *reinterpret_cast<const f32x4*>(rs + a.ch_rows + 16 * (T + h) + 4 * g);
+          const f32x4 nd1 = *reinterpret_cast<const f32x4*>(rs + a.ch_rows + 16 * (T + h) + 4 * g);      // -D1
+#pragma unroll
+          for (int k = 0; k < NK; ++k) q[k] = nd1;
+          products(T + h, s, q);
 #pragma unroll
           for (int k = 0; k < NK; ++k) {
             float p[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) p[i] = fast_exp2(s[k][i] * a.sc - lse[i]);
             pp[k][h] = pack4<E>(p[0], p[1], p[2], p[3]);
-            dd[k][h] = pack4<E>(p[0] * (q[k][0] - d1[0]), p[1] * (q[k][1] - d1[1]), p[2] * (q[k][2] - d1[2]),
-                                p[3] * (q[k][3] - d1[3]));
+            dd[k][h] = pack4<E>(p[0] * q[k][0], p[1] * q[k][1], p[2] * q[k][2], p[3] * q[k][3]);
           }
         }
 #pragma unroll
@@ -400,7 +406,7 @@ __global__ __launch_bounds__(kThreads, PROB == kBc ? 2 : 3) void fused_agent_ker
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* xt = reinterpret_cast<uint16_t*>(smem);              // [2][32][LST]
   uint16_t* yt = xt + 2 * kImage;                                  // [2][32][LST]
-  float* ts = reinterpret_cast<float*>(yt + 2 * kImage);          // kBc: [2][2][32]
+  float* ts = reinterpret_cast<float*>(yt + 2 * kImage);          // kBc: [2][2][32]: lse2 and -D2 of the tile's tokens
   const int s = blockIdx.x, ab = blockIdx.y, u = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 15, g = lane >> 4;
   const size_t ubN = (size_t)u * a.N, ubn = (size_t)u * a.n;
@@ -428,7 +434,7 @@ __global__ __launch_bounds__(kThreads, PROB == kBc ? 2 : 3) void fused_agent_ker
     if constexpr (PROB == kAgg) {
       if (ag_ok[k]) {
         lse_a[k] = a.rs1[ubn + agent[k]];
-        d_a[k] = a.rs2[ubn + agent[k]];
+        d_a[k] = -a.rs2[ubn + agent[k]];      // kept negated (see the dP product)
       }
     }
   }
@@ -449,7 +455,7 @@ __global__ __launch_bounds__(kThreads, PROB == kBc ? 2 : 3) void fused_agent_ker
       if (tid < 64) {
         const int tt = t0 + (tid & 31);
         sr = tid < 32 ? kMasked : 0.f;
-        if (tt < t_end) sr = (tid < 32 ? a.ts1 : a.ts2)[ubN + tt];
+        if (tt < t_end) sr = tid < 32 ? a.ts1[ubN + tt] : -a.ts2[ubN + tt];      // lse2 and -D2
       }
     }
   };
@@ -501,6 +507,9 @@ __global__ __launch_bounds__(kThreads, PROB == kBc ? 2 : 3) void fused_agent_ker
 #pragma unroll
       for (int k = 0; k < NA; ++k) {
         sv[k][j] = qv[k][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // the dP product starts from -D (of the tile's rows, or of the lane's agent): it returns dP - D
+        if constexpr (PROB == kBc) qv[k][j] = *reinterpret_cast<const f32x4*>(ts + buf * 64 + 32 + 16 * j + 4 * g);
+        if constexpr (PROB == kAgg) qv[k][j] = f32x4{d_a[k], d_a[k], d_a[k], d_a[k]};
 #pragma unroll
         for (int ks = 0; ks < G::KS; ++ks) {
           sv[k][j] = Mx<E>::mma(xo[ks], a1[k][ks], sv[k][j]);
@@ -555,18 +564,17 @@ __global__ __launch_bounds__(kThreads, PROB == kBc ? 2 : 3) void fused_agent_ker
           float p[4], e[4];
           if constexpr (PROB == kBc) {
             const f32x4 lse = *reinterpret_cast<const f32x4*>(ts + buf * 64 + 16 * j + 4 * g);
-            const f32x4 d2 = *reinterpret_cast<const f32x4*>(ts + buf * 64 + 32 + 16 * j + 4 * g);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               p[i] = fast_exp2(sv[k][j][i] * a.sc - lse[i]);
-              e[i] = p[i] * (qv[k][j][i] - d2[i]);
+              e[i] = p[i] * qv[k][j][i];
             }
           } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               p[i] = fast_exp2(sv[k][j][i] * a.sc - lse_a[k]);
               if constexpr (RAGGED) p[i] = (t0 + 16 * j + 4 * g + i < t_end) ? p[i] : 0.f;
-              e[i] = p[i] * (qv[k][j][i] - d_a[k]);
+              e[i] = p[i] * qv[k][j][i];
             }
           }
           pp[j] = pack4<E>(p[0], p[1], p[2], p[3]);
