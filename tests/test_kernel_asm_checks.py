@@ -92,3 +92,32 @@ def test_no_instruction_touches_a_register_with_a_hand_issued_read_in_flight(tmp
         issued, bad = scan_in_flight(open(out).read())
         assert issued > 100, "%s: the hand-issued reads were not found (%d)" % (u, issued)
         assert not bad, "\n".join(bad[:10])
+
+
+def test_backward_product_kernels_keep_their_accumulators_in_ordinary_registers(tmp_path):
+    """The MFMA kernels of the backward pass ask for two blocks per CU, i.e. at most 256 registers per lane: then
+    the compiler has no reason to place MFMA accumulators in the accumulator file, and every copy in or out of it
+    (`v_accvgpr_read` / `_write`) would be a vector instruction spent on nothing.  The recomputing kernels are
+    bound by their vector arithmetic, so the copies cost a tenth of their time when they were there."""
+    units = ["backward_fused_kernels.hip", "backward_kernels.hip"]
+    flags = [f for f in entry.HIPCC_FLAGS if f not in ("-shared", "-Wall")] + ["-S", "--cuda-device-only"]
+    procs = []
+    for u in units:
+        out = str(tmp_path / (u + ".s"))
+        procs.append((u, out, subprocess.Popen(["hipcc"] + flags + [os.path.join(entry.CSRC, u), "-o", out],
+                                               stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    for u, out, p in procs:
+        log, _ = p.communicate()
+        assert p.returncode == 0, log
+        text = open(out).read()
+        assert text.count("v_mfma_f32_16x16x32") > 50, u
+        # per kernel; the aggregation's token kernel at head width 128 needs more than 256 registers and is left
+        # at one block per CU (template arguments <E, 128, kAgg = 2, 2>)
+        kernel, counts = "", {}
+        for line in text.split("\n"):
+            if re.match(r"^_Z\w+:", line):
+                kernel = line.split(":")[0]
+            elif "v_accvgpr" in line:
+                counts[kernel] = counts.get(kernel, 0) + 1
+        counts = {k: c for k, c in counts.items() if not ("fused_token_kernel" in k and "ELi128ELi2ELi2E" in k)}
+        assert not counts, "%s: accumulator-file copies in %s" % (u, sorted(counts.items())[:4])
