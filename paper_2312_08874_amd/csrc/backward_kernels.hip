@@ -15,6 +15,8 @@
 //   pooling             dQ += Pooling^T(dA) (Sec. 4.2), or dA is returned when the agents were given
 //
 // Every reduction runs in a fixed order (no atomics): results are bitwise repeatable.
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace aa {
@@ -501,35 +503,70 @@ __global__ __launch_bounds__(256) void value_extras_kernel(float* __restrict__ d
   dV[i] = v;
 }
 
-// DWC parameter gradients, summed over the batch in a fixed order.  thread = (head, channel, tap) for
-// the weights (tap 9 = the bias).  grid = ceil(heads*d*10 / 64), 64 threads.
-__global__ __launch_bounds__(64) void dwc_param_grad_kernel(const float* __restrict__ V, const float* __restrict__ dO,
-                                                            float* __restrict__ dw, float* __restrict__ db, int batch,
-                                                            int heads, int N, int d, int gh, int gw) {
+// DWC parameter gradients (weights [H][d][3][3], bias [H][d]), summed over the batch and all tokens in a fixed
+// order, in two stages.  Stage 1: grid (slices, heads), 256 threads = 4 token lanes x 64 channels; a block takes
+// a slice of the head's batch * N tokens, every thread the ten sums (nine taps and the bias) of its channel over
+// the tokens of its lane; the four lanes are added in order through LDS.  Stage 2 adds the slices in order.
+__global__ __launch_bounds__(256) void dwc_param_partial_kernel(const float* __restrict__ V, const float* __restrict__ dO,
+                                                               float* __restrict__ part, int batch, int heads, int N,
+                                                               int d, int gh, int gw, int slice_len) {
+  __shared__ float red[4][64][10];
+  const int s = blockIdx.x, hd = blockIdx.y, slices = gridDim.x;
+  const int tl = threadIdx.x >> 6, cl = threadIdx.x & 63;
+  const int total = batch * N, j0 = s * slice_len, j1 = min(total, j0 + slice_len);
+  for (int c0 = 0; c0 < d; c0 += 64) {
+    const int c = c0 + cl;
+    float acc[10];
+#pragma unroll
+    for (int k = 0; k < 10; ++k) acc[k] = 0.0f;
+    if (c < d) {
+      for (int j = j0 + tl; j < j1; j += 4) {
+        const int bt = j / N, t = j - bt * N, y = t / gw, x = t - y * gw;
+        const size_t base = ((size_t)bt * heads + hd) * N;
+        const float g = dO[(base + t) * d + c];
+        acc[9] += g;
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) {
+          const int yy = y + tap / 3 - 1, xx = x + tap % 3 - 1;
+          if (yy >= 0 && yy < gh && xx >= 0 && xx < gw) acc[tap] += g * V[(base + (size_t)yy * gw + xx) * d + c];
+        }
+      }
+    }
+    __syncthreads();      // the previous channel group's sums have been read
+#pragma unroll
+    for (int k = 0; k < 10; ++k) red[tl][cl][k] = acc[k];
+    __syncthreads();
+    if (tl == 0 && c < d) {
+#pragma unroll
+      for (int k = 0; k < 10; ++k)
+        part[(((size_t)hd * slices + s) * d + c) * 10 + k] = ((red[0][cl][k] + red[1][cl][k]) + red[2][cl][k]) + red[3][cl][k];
+    }
+  }
+}
+__global__ __launch_bounds__(64) void dwc_param_sum_kernel(const float* __restrict__ part, float* __restrict__ dw,
+                                                          float* __restrict__ db, int heads, int d, int slices) {
   const int item = blockIdx.x * 64 + threadIdx.x;
   if (item >= heads * d * 10) return;
   const int tap = item % 10, c = (item / 10) % d, hd = item / (10 * d);
   if (tap == 9 && !db) return;
-  const int a = tap / 3 - 1, b = tap % 3 - 1;
   float acc = 0.0f;
-  for (int bt = 0; bt < batch; ++bt) {
-    const size_t base = ((size_t)bt * heads + hd) * N;
-    for (int y = 0; y < gh; ++y)
-      for (int x = 0; x < gw; ++x) {
-        const float g = dO[(base + (size_t)y * gw + x) * d + c];
-        if (tap == 9) {
-          acc += g;
-        } else {
-          const int yy = y + a, xx = x + b;
-          if (yy < 0 || yy >= gh || xx < 0 || xx >= gw) continue;
-          acc += g * V[(base + (size_t)yy * gw + xx) * d + c];
-        }
-      }
-  }
+  for (int s = 0; s < slices; ++s) acc += part[(((size_t)hd * slices + s) * d + c) * 10 + tap];
   if (tap == 9)
     db[(size_t)hd * d + c] = acc;
   else
     dw[((size_t)hd * d + c) * 9 + tap] = acc;
+}
+
+// dst[hd][i] = sum over the batch, in order, of src[(bt * heads + hd)][i]  (i < per_unit): the score gradients of
+// a head added over the batch before the bias components are taken from them
+__global__ __launch_bounds__(256) void batch_sum_kernel(const float* __restrict__ src, float* __restrict__ dst, int batch,
+                                                        int heads, size_t per_unit) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const int hd = blockIdx.y;
+  if (i >= per_unit) return;
+  float acc = 0.0f;
+  for (int bt = 0; bt < batch; ++bt) acc += src[((size_t)bt * heads + hd) * per_unit + i];
+  dst[(size_t)hd * per_unit + i] = acc;
 }
 
 // ---------------------------------------------------------------------------
@@ -725,9 +762,15 @@ inline int round8(int v) { return (v + 7) / 8 * 8; }
 
 // Module terms, pooling adjoint and the final rounding: shared tail of both paths.  dS1 / dS2 are the
 // unrounded fp32 gradients of the scores, rows of length ld1 / ld2.
+constexpr int kDwcSlices = 64;      // token slices of the DWC parameter gradients
+size_t dwc_part_floats(const Problem& p) { return ((size_t)p.heads * p.d * 10 * kDwcSlices + 63) / 64 * 64; }
+
+// scratch1 / scratch2: free workspace of at least heads * n * ld1 and heads * N * ld2 floats (the batch sums of
+// the score gradients); dwc_part: dwc_part_floats() floats (the slice sums of the DWC parameter gradients)
 hipError_t backward_tail(const Problem& p, const float* Vf, const float* dOf, const float* dS1, int ld1,
                          const float* dS2, int ld2, float* dQf, float* dKf, float* dVf, float* dAf, void* dQ, void* dK,
-                         void* dV, void* dA, bool agents_given, const BackwardParamGrads& pg, hipStream_t st) {
+                         void* dV, void* dA, bool agents_given, const BackwardParamGrads& pg, float* scratch1,
+                         float* scratch2, float* dwc_part, hipStream_t st) {
   const size_t u = (size_t)p.units, Nd = (size_t)p.N * p.d, nd = (size_t)p.n * p.d;
   const int N = p.N, n = p.n, d = p.d, U = p.units, batch = U / p.heads;
   if (p.dwc_w || p.vk != 0.0f) {
@@ -736,20 +779,36 @@ hipError_t backward_tail(const Problem& p, const float* Vf, const float* dOf, co
                                                                                     d, p.gh, p.gw, count);
   }
   if (p.dwc_w && pg.ddwc_w) {
+    // slices of about 256 tokens, at most kDwcSlices
+    const long long total = (long long)batch * N;
+    const int slices = (int)std::max<long long>(1, std::min<long long>((total + 255) / 256, kDwcSlices));
+    const int slice_len = (int)((total + slices - 1) / slices);
+    dwc_param_partial_kernel<<<dim3(slices, p.heads), dim3(256), 0, st>>>(Vf, dOf, dwc_part, batch, p.heads, N, d, p.gh,
+                                                                          p.gw, slice_len);
     const int items = p.heads * d * 10;
-    dwc_param_grad_kernel<<<dim3((items + 63) / 64), dim3(64), 0, st>>>(Vf, dOf, pg.ddwc_w, pg.ddwc_b, batch, p.heads, N,
-                                                                        d, p.gh, p.gw);
+    dwc_param_sum_kernel<<<dim3((items + 63) / 64), dim3(64), 0, st>>>(dwc_part, pg.ddwc_w, pg.ddwc_b, p.heads, d, slices);
+  }
+  // the score gradients of a head summed over the batch first (one coalesced pass), the components from the sums
+  const float *sum1 = dS1, *sum2 = dS2;
+  if (batch > 1) {
+    const size_t per1 = (size_t)n * ld1, per2 = (size_t)N * ld2;
+    if (pg.db1_col || pg.db1_row || pg.db1_blk) {
+      batch_sum_kernel<<<dim3((unsigned)((per1 + 255) / 256), p.heads), dim3(256), 0, st>>>(dS1, scratch1, batch, p.heads, per1);
+      sum1 = scratch1;
+    }
+    if (pg.db2_col || pg.db2_row || pg.db2_blk) {
+      batch_sum_kernel<<<dim3((unsigned)((per2 + 255) / 256), p.heads), dim3(256), 0, st>>>(dS2, scratch2, batch, p.heads, per2);
+      sum2 = scratch2;
+    }
   }
   auto bias_grad = [&](int kind, float* out, int which) {
     if (!out) return;
     const int per_head = which == 0 ? n * p.gw : (which == 1 ? n * p.gh : n * pg.h0 * pg.w0);
     const dim3 grid((p.heads * per_head + 63) / 64);
     if (kind == 1)
-      bias_grad_kernel<1><<<grid, dim3(64), 0, st>>>(dS1, ld1, out, which, batch, p.heads, n, p.gh, p.gw, pg.h0,
-                                                              pg.w0);
+      bias_grad_kernel<1><<<grid, dim3(64), 0, st>>>(sum1, ld1, out, which, 1, p.heads, n, p.gh, p.gw, pg.h0, pg.w0);
     else
-      bias_grad_kernel<2><<<grid, dim3(64), 0, st>>>(dS2, ld2, out, which, batch, p.heads, n, p.gh, p.gw, pg.h0,
-                                                              pg.w0);
+      bias_grad_kernel<2><<<grid, dim3(64), 0, st>>>(sum2, ld2, out, which, 1, p.heads, n, p.gh, p.gw, pg.h0, pg.w0);
   };
   bias_grad(1, pg.db1_col, 0);
   bias_grad(1, pg.db1_row, 1);
@@ -857,7 +916,10 @@ hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, 
     AA_BWD_CHECK(to_f32(p.dtype, dO, dOf, u * Nd, st));
   }
   // F1 / F2 now hold the unrounded dS1 / dS2 (when their bias gradients are wanted)
-  return backward_tail(p, Vf, dOf, F1, ldN, F2, ldn, dQf, dKf, dVf, dAf, dQ, dK, dV, dA, agents_given, pg, st);
+  // the four 16-bit matrices are no longer needed: P1 | dS1 and P2 | dS2 are the tail's scratch
+  return backward_tail(p, Vf, dOf, F1, ldN, F2, ldn, dQf, dKf, dVf, dAf, dQ, dK, dV, dA, agents_given, pg,
+                       reinterpret_cast<float*>(P1h), reinterpret_cast<float*>(P2h),
+                       ws + backward_workspace_floats(p) - dwc_part_floats(p), st);
 }
 
 }  // namespace
@@ -869,7 +931,7 @@ size_t backward_workspace_floats(const Problem& p) {
   // 16-bit path: 5 x N*d + n*d fp32, the two score matrices in fp32 and four 16-bit copies (rows padded
   // to a multiple of 8), V_A and dV_A in 16 bits: never more than the figure below.
   const size_t nN = (size_t)p.n * ((p.N + 7) / 8 * 8), Nn = (size_t)p.N * ((p.n + 7) / 8 * 8);
-  return u * (7 * Nd + 4 * nd + 2 * nN + 2 * Nn);
+  return u * (7 * Nd + 4 * nd + 2 * nN + 2 * Nn) + dwc_part_floats(p);      // the slice sums at the very end
 }
 
 hipError_t launch_backward(const Problem& p, const void* Q, const void* K, const void* V, const void* A_elem,
@@ -928,8 +990,9 @@ hipError_t launch_backward(const Problem& p, const void* Q, const void* K, const
   AA_BWD_CHECK((matmul<true, false, false>(T1, Af, dKf, N, d, n, U, p.scale1, st)));
   AA_BWD_CHECK((matmul<true, false, false>(P1, dVAf, dVf, N, d, n, U, 1.0f, st)));
 
-  return backward_tail(p, Vf, dOf, T1, N, T2, n, dQf, dKf, dVf, dAf, dQ, dK, dV, dA, agents_given, pg,
-                                       st);
+  // P1 and P2 are no longer needed: the tail's scratch
+  return backward_tail(p, Vf, dOf, T1, N, T2, n, dQf, dKf, dVf, dAf, dQ, dK, dV, dA, agents_given, pg, P1, P2,
+                       ws + backward_workspace_floats(p) - dwc_part_floats(p), st);
 }
 
 }  // namespace aa
