@@ -18,6 +18,7 @@
 #include <algorithm>
 
 #include "kernels.h"
+#include "lds_optin.h"
 
 namespace aa {
 
@@ -627,6 +628,71 @@ __global__ __launch_bounds__(64) void bias_grad_kernel(const float* __restrict__
   out[item] = acc;
 }
 
+// KIND 1, all three components in one pass: one block per (agent, head) stages the agent's row of dS1 (already
+// summed over the batch) in LDS with coalesced loads, then takes its column sums (thread per x), its row sums
+// (wave per y, lanes over x, fixed reduction tree) and its block-cell sums (through the separable bilinear weights).
+// Dynamic LDS: N + gh * w0 + w0 * gw + h0 * gh floats.
+__global__ __launch_bounds__(256) void bias_grad1_row_kernel(const float* __restrict__ S, int ld, float* __restrict__ col,
+                                                            float* __restrict__ row, float* __restrict__ blk, int n,
+                                                            int gh, int gw, int h0, int w0) {
+  extern __shared__ float rowbuf[];
+  const int a = blockIdx.x, hd = blockIdx.y, tid = threadIdx.x, N = gh * gw;
+  const size_t ra = (size_t)hd * n + a;
+  const float* src = S + ra * ld;
+  for (int t = tid; t < N; t += 256) rowbuf[t] = src[t];
+  __syncthreads();
+  if (col) {
+    for (int x = tid; x < gw; x += 256) {
+      float acc = 0.0f;
+      for (int y = 0; y < gh; ++y) acc += rowbuf[y * gw + x];
+      col[ra * gw + x] = acc;
+    }
+  }
+  if (row) {
+    const int w = tid >> 6, lane = tid & 63;
+    for (int y = w; y < gh; y += 4) {
+      float acc = 0.0f;
+      for (int x = lane; x < gw; x += 64) acc += rowbuf[y * gw + x];
+      acc = wave_sum(acc);
+      if (lane == 0) row[ra * gh + y] = acc;
+    }
+  }
+  if (blk) {
+    // the bilinear weights are separable: T[y][q] = sum_x wx(x, q) S[y][x], then blk[p][q] = sum_y wy(y, p) T[y][q]
+    float* T = rowbuf + N;           // [gh][w0]
+    float* wxt = T + gh * w0;        // [w0][gw]
+    float* wyt = wxt + w0 * gw;      // [h0][gh]
+    for (int i = tid; i < w0 * gw; i += 256) {
+      const int q = i / gw, x = i - q * gw;
+      int x0, x1;
+      float fx;
+      bilinear_coord(x, gw, w0, x0, x1, fx);
+      wxt[i] = (x0 == q ? 1.0f - fx : 0.0f) + (x1 == q ? fx : 0.0f);
+    }
+    for (int i = tid; i < h0 * gh; i += 256) {
+      const int p = i / gh, y = i - p * gh;
+      int y0, y1;
+      float fy;
+      bilinear_coord(y, gh, h0, y0, y1, fy);
+      wyt[i] = (y0 == p ? 1.0f - fy : 0.0f) + (y1 == p ? fy : 0.0f);
+    }
+    __syncthreads();
+    for (int i = tid; i < gh * w0; i += 256) {
+      const int y = i / w0, q = i - y * w0;
+      float acc = 0.0f;
+      for (int x = 0; x < gw; ++x) acc += wxt[q * gw + x] * rowbuf[y * gw + x];
+      T[i] = acc;
+    }
+    __syncthreads();
+    for (int cell = tid; cell < h0 * w0; cell += 256) {
+      const int p = cell / w0, q = cell - p * w0;
+      float acc = 0.0f;
+      for (int y = 0; y < gh; ++y) acc += wyt[p * gh + y] * T[y * w0 + q];
+      blk[ra * h0 * w0 + cell] = acc;
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
 // dQ += Pooling^T(dA): token (y, x) gathers dA[a] / |window(a)| from every agent whose window holds
 // it (adaptive windows may overlap by one row / column).  thread = element of dQ.
@@ -810,9 +876,24 @@ hipError_t backward_tail(const Problem& p, const float* Vf, const float* dOf, co
     else
       bias_grad_kernel<2><<<grid, dim3(64), 0, st>>>(sum2, ld2, out, which, 1, p.heads, n, p.gh, p.gw, pg.h0, pg.w0);
   };
-  bias_grad(1, pg.db1_col, 0);
-  bias_grad(1, pg.db1_row, 1);
-  bias_grad(1, pg.db1_blk, 2);
+  const size_t row_lds = ((size_t)N + (size_t)p.gh * pg.w0 + (size_t)pg.w0 * p.gw + (size_t)pg.h0 * p.gh) * sizeof(float);
+  if ((pg.db1_col || pg.db1_row || pg.db1_blk) && row_lds <= 160 * 1024) {      // an agent's row fits in LDS
+    if (row_lds > 64 * 1024) {      // opt-in for more than 64 KB of dynamic LDS, once per device
+      int dev = 0;
+      AA_BWD_CHECK(hipGetDevice(&dev));
+      if (lds_optin_registry().needs((const void*)bias_grad1_row_kernel, dev)) {
+        AA_BWD_CHECK(hipFuncSetAttribute((const void*)bias_grad1_row_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         160 * 1024));
+        lds_optin_registry().done((const void*)bias_grad1_row_kernel, dev);
+      }
+    }
+    bias_grad1_row_kernel<<<dim3(n, p.heads), dim3(256), row_lds, st>>>(sum1, ld1, pg.db1_col, pg.db1_row, pg.db1_blk, n,
+                                                                       p.gh, p.gw, pg.h0, pg.w0);
+  } else {
+    bias_grad(1, pg.db1_col, 0);
+    bias_grad(1, pg.db1_row, 1);
+    bias_grad(1, pg.db1_blk, 2);
+  }
   bias_grad(2, pg.db2_col, 0);
   bias_grad(2, pg.db2_row, 1);
   bias_grad(2, pg.db2_blk, 2);
