@@ -505,23 +505,25 @@ __global__ __launch_bounds__(256) void value_extras_kernel(float* __restrict__ d
 }
 
 // DWC parameter gradients (weights [H][d][3][3], bias [H][d]), summed over the batch and all tokens in a fixed
-// order, in two stages.  Stage 1: grid (slices, heads), 256 threads = 4 token lanes x 64 channels; a block takes
-// a slice of the head's batch * N tokens, every thread the ten sums (nine taps and the bias) of its channel over
-// the tokens of its lane; the four lanes are added in order through LDS.  Stage 2 adds the slices in order.
+// order, in two stages.  Stage 1: grid (slices, heads), 256 threads = TL token lanes x CL channels (CL = 32 or 64);
+// a block takes a slice of the head's batch * N tokens, every thread the ten sums (nine taps and the bias) of its
+// channel over the tokens of its lane; the lanes are added in order through LDS.  Stage 2 adds the slices in order.
+template <int CL>
 __global__ __launch_bounds__(256) void dwc_param_partial_kernel(const float* __restrict__ V, const float* __restrict__ dO,
                                                                float* __restrict__ part, int batch, int heads, int N,
                                                                int d, int gh, int gw, int slice_len) {
-  __shared__ float red[4][64][10];
+  constexpr int TL = 256 / CL;
+  __shared__ float red[TL][CL][10];
   const int s = blockIdx.x, hd = blockIdx.y, slices = gridDim.x;
-  const int tl = threadIdx.x >> 6, cl = threadIdx.x & 63;
+  const int tl = threadIdx.x / CL, cl = threadIdx.x % CL;
   const int total = batch * N, j0 = s * slice_len, j1 = min(total, j0 + slice_len);
-  for (int c0 = 0; c0 < d; c0 += 64) {
+  for (int c0 = 0; c0 < d; c0 += CL) {
     const int c = c0 + cl;
     float acc[10];
 #pragma unroll
     for (int k = 0; k < 10; ++k) acc[k] = 0.0f;
     if (c < d) {
-      for (int j = j0 + tl; j < j1; j += 4) {
+      for (int j = j0 + tl; j < j1; j += TL) {
         const int bt = j / N, t = j - bt * N, y = t / gw, x = t - y * gw;
         const size_t base = ((size_t)bt * heads + hd) * N;
         const float g = dO[(base + t) * d + c];
@@ -539,8 +541,12 @@ __global__ __launch_bounds__(256) void dwc_param_partial_kernel(const float* __r
     __syncthreads();
     if (tl == 0 && c < d) {
 #pragma unroll
-      for (int k = 0; k < 10; ++k)
-        part[(((size_t)hd * slices + s) * d + c) * 10 + k] = ((red[0][cl][k] + red[1][cl][k]) + red[2][cl][k]) + red[3][cl][k];
+      for (int k = 0; k < 10; ++k) {
+        float v = red[0][cl][k];
+#pragma unroll
+        for (int l = 1; l < TL; ++l) v += red[l][cl][k];
+        part[(((size_t)hd * slices + s) * d + c) * 10 + k] = v;
+      }
     }
   }
 }
@@ -828,8 +834,12 @@ inline int round8(int v) { return (v + 7) / 8 * 8; }
 
 // Module terms, pooling adjoint and the final rounding: shared tail of both paths.  dS1 / dS2 are the
 // unrounded fp32 gradients of the scores, rows of length ld1 / ld2.
-constexpr int kDwcSlices = 64;      // token slices of the DWC parameter gradients
-size_t dwc_part_floats(const Problem& p) { return ((size_t)p.heads * p.d * 10 * kDwcSlices + 63) / 64 * 64; }
+// token slices of the DWC parameter gradients: about 256 tokens each, at most 1024 and at most 4M floats of sums
+int dwc_slices(const Problem& p) {
+  const long long total = (long long)(p.units / p.heads) * p.N, per = (long long)p.heads * p.d * 10;
+  return (int)std::max<long long>(1, std::min<long long>({(total + 255) / 256, 1024LL, (4LL << 20) / per}));
+}
+size_t dwc_part_floats(const Problem& p) { return ((size_t)p.heads * p.d * 10 * dwc_slices(p) + 63) / 64 * 64; }
 
 // scratch1 / scratch2: free workspace of at least heads * n * ld1 and heads * N * ld2 floats (the batch sums of
 // the score gradients); dwc_part: dwc_part_floats() floats (the slice sums of the DWC parameter gradients)
@@ -845,12 +855,15 @@ hipError_t backward_tail(const Problem& p, const float* Vf, const float* dOf, co
                                                                                     d, p.gh, p.gw, count);
   }
   if (p.dwc_w && pg.ddwc_w) {
-    // slices of about 256 tokens, at most kDwcSlices
     const long long total = (long long)batch * N;
-    const int slices = (int)std::max<long long>(1, std::min<long long>((total + 255) / 256, kDwcSlices));
+    const int slices = dwc_slices(p);
     const int slice_len = (int)((total + slices - 1) / slices);
-    dwc_param_partial_kernel<<<dim3(slices, p.heads), dim3(256), 0, st>>>(Vf, dOf, dwc_part, batch, p.heads, N, d, p.gh,
-                                                                          p.gw, slice_len);
+    if (d <= 32)
+      dwc_param_partial_kernel<32><<<dim3(slices, p.heads), dim3(256), 0, st>>>(Vf, dOf, dwc_part, batch, p.heads, N, d,
+                                                                                p.gh, p.gw, slice_len);
+    else
+      dwc_param_partial_kernel<64><<<dim3(slices, p.heads), dim3(256), 0, st>>>(Vf, dOf, dwc_part, batch, p.heads, N, d,
+                                                                                p.gh, p.gw, slice_len);
     const int items = p.heads * d * 10;
     dwc_param_sum_kernel<<<dim3((items + 63) / 64), dim3(64), 0, st>>>(dwc_part, pg.ddwc_w, pg.ddwc_b, p.heads, d, slices);
   }
