@@ -11,10 +11,11 @@ DIR holds, for workload W,
 writes profiles/W_kernels.md: per kernel the profiler's average duration next to the benchmark's own, the measured
 HBM bytes per launch next to the algorithmic ones, and the roofline entry of the dominant kernel.
 
-usage: python profile_summary.py DIR W backward
-DIR holds one run with the backward pass timed as well:
-  rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload W --no-others --no-cpu-baseline --no-traffic --backward --steps 30 --warmup 5
-writes profiles/W_backward_kernels.md (durations of the backward pass's kernels only).
+usage: python profile_summary.py DIR W backward [MODE]
+DIR holds one run with the backward pass timed as well (MODE = pure, the default, or module):
+  rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload W --mode MODE --no-others --no-cpu-baseline --no-traffic --backward --steps 30 --warmup 5
+writes profiles/W_backward_kernels.md (profiles/W_module_backward_kernels.md): durations of the backward pass's
+kernels only.
 
 usage: python profile_summary.py DIR W counters [MODE]
 DIR holds one run with eight SQ counters (MODE = pure, the default, module, or backward = pure with --backward
@@ -86,15 +87,16 @@ def calibration(values_by_kernel):
 
 BACKWARD_KERNELS = ("matmul_kernel", "mfma_matmul_kernel", "mfma_matmul_pair_kernel", "from_f32_x3_kernel",
                     "splitk_reduce_kernel", "softmax_rows", "softmax_grad_rows",
-                    "value_extras_kernel", "dwc_param_grad_kernel", "bias_grad_kernel", "pool_grad_kernel", "to_f32_kernel",
+                    "value_extras_kernel", "dwc_param_partial_kernel", "dwc_param_sum_kernel", "batch_sum_kernel",
+                    "bias_grad_kernel", "bias_grad1_row_kernel", "pool_grad_kernel", "to_f32_kernel",
                     "from_f32_kernel", "fused_token_kernel", "fused_agent_kernel", "fused_merge_kernel",
                     "fused_reduce_bc_kernel", "fused_reduce_agg_kernel")
 
 
-def backward_summary(d, wl):
+def backward_summary(d, wl, mode="pure"):
     cmd = ("rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o stats -- python3 bench.py --workload %s "
-           "--no-others --no-cpu-baseline --no-traffic --backward --steps 30 --warmup 5" % wl)
-    lines = ["# rocprofv3 summary: backward pass, bench.py --workload %s --backward (one MI355X)" % wl, "",
+           "--mode %s --no-others --no-cpu-baseline --no-traffic --backward --steps 30 --warmup 5" % (wl, mode))
+    lines = ["# rocprofv3 summary: backward pass, bench.py --workload %s --mode %s --backward (one MI355X)" % (wl, mode), "",
              "command: `%s`" % cmd, "",
              "Kernels of `agent_attn_bwd` only (the run also times the forward pass; its kernels are in "
              "`%s_kernels.md`).  `us per backward` = calls x avg / number of backward calls." % wl, "",
@@ -115,7 +117,8 @@ def backward_summary(d, wl):
         total += per
         lines.append("| `%s` | %d | %.1f | %.1f |" % (name, calls, avg, per))
     lines += ["", "sum over the kernels: %.1f us per backward call (%d calls)" % (total, ncalls)]
-    with open(os.path.join(ROOT, "profiles", "%s_backward_kernels.md" % wl), "w") as f:
+    name = "%s_backward_kernels.md" % wl if mode == "pure" else "%s_%s_backward_kernels.md" % (wl, mode)
+    with open(os.path.join(ROOT, "profiles", name), "w") as f:
         f.write("\n".join(lines) + "\n")
     print("\n".join(lines))
 
@@ -185,7 +188,7 @@ def counters_summary(d, wl, mode):
 def main():
     d, wl = sys.argv[1], sys.argv[2]
     if len(sys.argv) > 3 and sys.argv[3] == "backward":
-        backward_summary(d, wl)
+        backward_summary(d, wl, sys.argv[4] if len(sys.argv) > 4 else "pure")
         return
     if len(sys.argv) > 3 and sys.argv[3] == "counters":
         counters_summary(d, wl, sys.argv[4] if len(sys.argv) > 4 else "pure")
