@@ -550,18 +550,25 @@ __global__ __launch_bounds__(256) void dwc_param_partial_kernel(const float* __r
     }
   }
 }
+// one wave per (head, channel): lane l adds the slices l, l + 64, ... in order, the lanes are added by a fixed tree
 __global__ __launch_bounds__(64) void dwc_param_sum_kernel(const float* __restrict__ part, float* __restrict__ dw,
                                                           float* __restrict__ db, int heads, int d, int slices) {
-  const int item = blockIdx.x * 64 + threadIdx.x;
-  if (item >= heads * d * 10) return;
-  const int tap = item % 10, c = (item / 10) % d, hd = item / (10 * d);
-  if (tap == 9 && !db) return;
-  float acc = 0.0f;
-  for (int s = 0; s < slices; ++s) acc += part[(((size_t)hd * slices + s) * d + c) * 10 + tap];
-  if (tap == 9)
-    db[(size_t)hd * d + c] = acc;
-  else
-    dw[((size_t)hd * d + c) * 9 + tap] = acc;
+  const int c = blockIdx.x, hd = blockIdx.y, lane = threadIdx.x;
+  float acc[10];
+#pragma unroll
+  for (int k = 0; k < 10; ++k) acc[k] = 0.0f;
+  for (int s = lane; s < slices; s += 64) {
+    const float* q = part + (((size_t)hd * slices + s) * d + c) * 10;
+#pragma unroll
+    for (int k = 0; k < 10; ++k) acc[k] += q[k];
+  }
+#pragma unroll
+  for (int k = 0; k < 10; ++k) acc[k] = wave_sum(acc[k]);
+  if (lane == 0) {
+#pragma unroll
+    for (int k = 0; k < 9; ++k) dw[((size_t)hd * d + c) * 9 + k] = acc[k];
+    if (db) db[(size_t)hd * d + c] = acc[9];
+  }
 }
 
 // dst[hd][i] = sum over the batch, in order, of src[(bt * heads + hd)][i]  (i < per_unit): the score gradients of
@@ -834,10 +841,10 @@ inline int round8(int v) { return (v + 7) / 8 * 8; }
 
 // Module terms, pooling adjoint and the final rounding: shared tail of both paths.  dS1 / dS2 are the
 // unrounded fp32 gradients of the scores, rows of length ld1 / ld2.
-// token slices of the DWC parameter gradients: about 256 tokens each, at most 1024 and at most 4M floats of sums
+// token slices of the DWC parameter gradients: about 64 tokens each, at most 4096 and at most 8M floats of sums
 int dwc_slices(const Problem& p) {
   const long long total = (long long)(p.units / p.heads) * p.N, per = (long long)p.heads * p.d * 10;
-  return (int)std::max<long long>(1, std::min<long long>({(total + 255) / 256, 1024LL, (4LL << 20) / per}));
+  return (int)std::max<long long>(1, std::min<long long>({(total + 63) / 64, 4096LL, (8LL << 20) / per}));
 }
 size_t dwc_part_floats(const Problem& p) { return ((size_t)p.heads * p.d * 10 * dwc_slices(p) + 63) / 64 * 64; }
 
@@ -864,8 +871,7 @@ hipError_t backward_tail(const Problem& p, const float* Vf, const float* dOf, co
     else
       dwc_param_partial_kernel<64><<<dim3(slices, p.heads), dim3(256), 0, st>>>(Vf, dOf, dwc_part, batch, p.heads, N, d,
                                                                                 p.gh, p.gw, slice_len);
-    const int items = p.heads * d * 10;
-    dwc_param_sum_kernel<<<dim3((items + 63) / 64), dim3(64), 0, st>>>(dwc_part, pg.ddwc_w, pg.ddwc_b, p.heads, d, slices);
+    dwc_param_sum_kernel<<<dim3(d, p.heads), dim3(64), 0, st>>>(dwc_part, pg.ddwc_w, pg.ddwc_b, p.heads, d, slices);
   }
   // the score gradients of a head summed over the batch first (one coalesced pass), the components from the sums
   const float *sum1 = dS1, *sum2 = dS2;
