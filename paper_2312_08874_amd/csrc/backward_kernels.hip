@@ -641,24 +641,36 @@ __global__ __launch_bounds__(64) void bias_grad_kernel(const float* __restrict__
   out[item] = acc;
 }
 
-// KIND 1, all three components in one pass: one block per (agent, head) stages the agent's row of dS1 (already
+// All three components in one pass.  KIND 1: one block per (agent, head) stages the agent's row of dS1 (already
 // summed over the batch) in LDS with coalesced loads, then takes its column sums (thread per x), its row sums
 // (wave per y, lanes over x, fixed reduction tree) and its block-cell sums (through the separable bilinear weights).
 // Dynamic LDS: N + gh * w0 + w0 * gw + h0 * gh floats.
-__global__ __launch_bounds__(256) void bias_grad1_row_kernel(const float* __restrict__ S, int ld, float* __restrict__ col,
-                                                            float* __restrict__ row, float* __restrict__ blk, int n,
-                                                            int gh, int gw, int h0, int w0) {
+// KIND 2 (dS2 [H][N][ld], the agent's scores a column of stride ld; outputs agent-minor): the same block, its
+// staging loads gathered; used while the head's matrix is small enough to sit in L2.
+template <int KIND>
+__global__ __launch_bounds__(256) void bias_grad_row_kernel(const float* __restrict__ S, int ld, float* __restrict__ col,
+                                                           float* __restrict__ row, float* __restrict__ blk, int n,
+                                                           int gh, int gw, int h0, int w0) {
   extern __shared__ float rowbuf[];
   const int a = blockIdx.x, hd = blockIdx.y, tid = threadIdx.x, N = gh * gw;
   const size_t ra = (size_t)hd * n + a;
-  const float* src = S + ra * ld;
-  for (int t = tid; t < N; t += 256) rowbuf[t] = src[t];
+  if (KIND == 1) {
+    const float* src = S + ra * ld;
+    for (int t = tid; t < N; t += 256) rowbuf[t] = src[t];
+  } else {
+    const float* src = S + (size_t)hd * N * ld + a;
+    for (int t = tid; t < N; t += 256) rowbuf[t] = src[(size_t)t * ld];
+  }
+  // output places of column x, row y, cell (p, q) of this agent
+  auto col_at = [&](int x) { return KIND == 1 ? ra * gw + x : ((size_t)hd * gw + x) * n + a; };
+  auto row_at = [&](int y) { return KIND == 1 ? ra * gh + y : ((size_t)hd * gh + y) * n + a; };
+  auto blk_at = [&](int cell) { return KIND == 1 ? ra * h0 * w0 + cell : ((size_t)hd * h0 * w0 + cell) * n + a; };
   __syncthreads();
   if (col) {
     for (int x = tid; x < gw; x += 256) {
       float acc = 0.0f;
       for (int y = 0; y < gh; ++y) acc += rowbuf[y * gw + x];
-      col[ra * gw + x] = acc;
+      col[col_at(x)] = acc;
     }
   }
   if (row) {
@@ -667,7 +679,7 @@ __global__ __launch_bounds__(256) void bias_grad1_row_kernel(const float* __rest
       float acc = 0.0f;
       for (int x = lane; x < gw; x += 64) acc += rowbuf[y * gw + x];
       acc = wave_sum(acc);
-      if (lane == 0) row[ra * gh + y] = acc;
+      if (lane == 0) row[row_at(y)] = acc;
     }
   }
   if (blk) {
@@ -701,7 +713,7 @@ __global__ __launch_bounds__(256) void bias_grad1_row_kernel(const float* __rest
       const int p = cell / w0, q = cell - p * w0;
       float acc = 0.0f;
       for (int y = 0; y < gh; ++y) acc += wyt[p * gh + y] * T[y * w0 + q];
-      blk[ra * h0 * w0 + cell] = acc;
+      blk[blk_at(cell)] = acc;
     }
   }
 }
@@ -896,26 +908,35 @@ hipError_t backward_tail(const Problem& p, const float* Vf, const float* dOf, co
       bias_grad_kernel<2><<<grid, dim3(64), 0, st>>>(sum2, ld2, out, which, 1, p.heads, n, p.gh, p.gw, pg.h0, pg.w0);
   };
   const size_t row_lds = ((size_t)N + (size_t)p.gh * pg.w0 + (size_t)pg.w0 * p.gw + (size_t)pg.h0 * p.gh) * sizeof(float);
-  if ((pg.db1_col || pg.db1_row || pg.db1_blk) && row_lds <= 160 * 1024) {      // an agent's row fits in LDS
-    if (row_lds > 64 * 1024) {      // opt-in for more than 64 KB of dynamic LDS, once per device
-      int dev = 0;
-      AA_BWD_CHECK(hipGetDevice(&dev));
-      if (lds_optin_registry().needs((const void*)bias_grad1_row_kernel, dev)) {
-        AA_BWD_CHECK(hipFuncSetAttribute((const void*)bias_grad1_row_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         160 * 1024));
-        lds_optin_registry().done((const void*)bias_grad1_row_kernel, dev);
-      }
+  auto row_optin = [&](const void* fn) -> hipError_t {      // more than 64 KB of dynamic LDS: once per device
+    if (row_lds <= 64 * 1024) return hipSuccess;
+    int dev = 0;
+    AA_BWD_CHECK(hipGetDevice(&dev));
+    if (lds_optin_registry().needs(fn, dev)) {
+      AA_BWD_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      lds_optin_registry().done(fn, dev);
     }
-    bias_grad1_row_kernel<<<dim3(n, p.heads), dim3(256), row_lds, st>>>(sum1, ld1, pg.db1_col, pg.db1_row, pg.db1_blk, n,
-                                                                       p.gh, p.gw, pg.h0, pg.w0);
+    return hipSuccess;
+  };
+  if ((pg.db1_col || pg.db1_row || pg.db1_blk) && row_lds <= 160 * 1024) {      // an agent's row fits in LDS
+    AA_BWD_CHECK(row_optin((const void*)bias_grad_row_kernel<1>));
+    bias_grad_row_kernel<1><<<dim3(n, p.heads), dim3(256), row_lds, st>>>(sum1, ld1, pg.db1_col, pg.db1_row, pg.db1_blk, n,
+                                                                         p.gh, p.gw, pg.h0, pg.w0);
   } else {
     bias_grad(1, pg.db1_col, 0);
     bias_grad(1, pg.db1_row, 1);
     bias_grad(1, pg.db1_blk, 2);
   }
-  bias_grad(2, pg.db2_col, 0);
-  bias_grad(2, pg.db2_row, 1);
-  bias_grad(2, pg.db2_blk, 2);
+  // the broadcast's: the gathered form while a head's matrix is at most 16 MB, else a coalesced pass per component
+  if ((pg.db2_col || pg.db2_row || pg.db2_blk) && row_lds <= 160 * 1024 && (size_t)N * ld2 * sizeof(float) <= (16u << 20)) {
+    AA_BWD_CHECK(row_optin((const void*)bias_grad_row_kernel<2>));
+    bias_grad_row_kernel<2><<<dim3(n, p.heads), dim3(256), row_lds, st>>>(sum2, ld2, pg.db2_col, pg.db2_row, pg.db2_blk, n,
+                                                                         p.gh, p.gw, pg.h0, pg.w0);
+  } else {
+    bias_grad(2, pg.db2_col, 0);
+    bias_grad(2, pg.db2_row, 1);
+    bias_grad(2, pg.db2_blk, 2);
+  }
   if (agents_given) {
     AA_BWD_CHECK(from_f32(p.dtype, dAf, dA, u * nd, st));
   } else {

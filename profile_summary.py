@@ -88,7 +88,7 @@ def calibration(values_by_kernel):
 BACKWARD_KERNELS = ("matmul_kernel", "mfma_matmul_kernel", "mfma_matmul_pair_kernel", "from_f32_x3_kernel",
                     "splitk_reduce_kernel", "softmax_rows", "softmax_grad_rows",
                     "value_extras_kernel", "dwc_param_partial_kernel", "dwc_param_sum_kernel", "batch_sum_kernel",
-                    "bias_grad_kernel", "bias_grad1_row_kernel", "pool_grad_kernel", "to_f32_kernel",
+                    "bias_grad_kernel", "bias_grad_row_kernel", "pool_grad_kernel", "to_f32_kernel",
                     "from_f32_kernel", "fused_token_kernel", "fused_agent_kernel", "fused_merge_kernel",
                     "fused_reduce_bc_kernel", "fused_reduce_agg_kernel")
 
