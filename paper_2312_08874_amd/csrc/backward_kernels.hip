@@ -656,7 +656,14 @@ __global__ __launch_bounds__(256) void bias_grad_row_kernel(const float* __restr
   const size_t ra = (size_t)hd * n + a;
   if (KIND == 1) {
     const float* src = S + ra * ld;
-    for (int t = tid; t < N; t += 256) rowbuf[t] = src[t];
+    int done = 0;
+    if ((reinterpret_cast<uintptr_t>(src) & 15) == 0) {      // the row starts 16-byte aligned: four floats per load
+      const float4* s4 = reinterpret_cast<const float4*>(src);
+      float4* r4 = reinterpret_cast<float4*>(rowbuf);
+      for (int t = tid; t < N / 4; t += 256) r4[t] = s4[t];
+      done = N / 4 * 4;
+    }
+    for (int t = done + tid; t < N; t += 256) rowbuf[t] = src[t];
   } else {
     const float* src = S + (size_t)hd * N * ld + a;
     for (int t = tid; t < N; t += 256) rowbuf[t] = src[(size_t)t * ld];
