@@ -392,13 +392,11 @@ struct AgentArgs {
   float sc;
 };
 
-template <int DP>
-constexpr int agent_cols() { return DP == 128 ? 1 : 2; }      // 16-agent columns per wave (registers allowing)
-
-template <class E, int DP, int PROB>
+// NA: 16-agent columns per wave (every LDS operand feeds that many products); a block holds 64 NA agents.  Two where
+// the registers allow it (d <= 64) and the unit has more than 64 agents, else one.
+template <class E, int DP, int PROB, int NA>
 __global__ __launch_bounds__(kThreads, PROB == kBc ? 2 : 3) void fused_agent_kernel(AgentArgs a) {
   using G = Geo<DP>;
-  constexpr int NA = agent_cols<DP>();
   constexpr int kTileRows = 32;
   constexpr int kPieces = kTileRows * G::CPR;
   constexpr int NLD = (kPieces + kThreads - 1) / kThreads;
@@ -706,7 +704,7 @@ __global__ __launch_bounds__(64) void fused_reduce_agg_kernel(const float* __res
 // host side
 // ---------------------------------------------------------------------------
 struct FusedPlan {
-  int DP, n_rows, ch_rows, agent_blocks, S[2], chunk[2];      // [0]: agent kBc, [1]: agent kFwd / kAgg
+  int DP, n_rows, ch_rows, agent_cols, agent_blocks, S[2], chunk[2];      // [0]: agent kBc, [1]: agent kFwd / kAgg
   bool wide;
   // workspace offsets in floats (every region a multiple of 64 floats)
   size_t VAf, VAe, dVAe, lse1, D1, lse2, D2, dAf, part, total;
@@ -719,7 +717,8 @@ FusedPlan fused_plan(const Problem& p) {
   f.DP = p.d <= 32 ? 32 : (p.d <= 64 ? 64 : 128);
   f.n_rows = (p.n + 31) / 32 * 32;      // the token kernels take agent tiles in pairs
   f.ch_rows = min(f.n_rows, 128);
-  const int per_block = 64 * (f.DP == 128 ? 1 : 2);      // agents per block of the agent kernels (agent_cols)
+  f.agent_cols = (f.DP == 128 || p.n <= 64) ? 1 : 2;
+  const int per_block = 64 * f.agent_cols;      // agents per block of the agent kernels
   f.agent_blocks = (p.n + per_block - 1) / per_block;
   const int groups = f.agent_blocks * p.units;
   // token ranges: about two blocks per CU for the broadcast's agent kernel (192 registers), three for the other
@@ -779,7 +778,10 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
   ag.N = N, ag.n = n, ag.d = d, ag.chunk = f.chunk[1], ag.S = f.S[1];
   // the aggregation again: V_A and the log-sum-exp of its rows
   ag.X = K, ag.Y = V, ag.M1 = A, ag.M2 = nullptr, ag.P1 = part1, ag.pm = pm, ag.pl = pl, ag.sc = sc1;
-  fused_agent_kernel<E, DP, kFwd><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
+  if (f.agent_cols == 2)
+    fused_agent_kernel<E, DP, kFwd, DP <= 64 ? 2 : 1><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
+  else
+    fused_agent_kernel<E, DP, kFwd, 1><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
   fused_merge_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, pm, pl, f.S[1], n, d, VAf, VAe, lse1);
 
   // broadcast: per-token gradient and row statistics, then the per-agent sums
@@ -793,7 +795,10 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
     fused_token_kernel<E, DP, kBcStat, 2><<<tgrid2, dim3(kThreads), token_lds, st>>>(tk);
   ag.X = Q, ag.Y = dO, ag.M2 = VAe, ag.ts1 = lse2, ag.ts2 = D2, ag.P1 = part1, ag.P2 = part2, ag.sc = sc2;
   ag.chunk = f.chunk[0], ag.S = f.S[0];
-  fused_agent_kernel<E, DP, kBc><<<agrid_bc, dim3(kThreads), agent_lds, st>>>(ag);
+  if (f.agent_cols == 2)
+    fused_agent_kernel<E, DP, kBc, DP <= 64 ? 2 : 1><<<agrid_bc, dim3(kThreads), agent_lds, st>>>(ag);
+  else
+    fused_agent_kernel<E, DP, kBc, 1><<<agrid_bc, dim3(kThreads), agent_lds, st>>>(ag);
   fused_reduce_bc_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, part2, f.S[0], n, d, VAf, dVAe, D1, dAf, p.scale2);
 
   // aggregation
@@ -802,7 +807,10 @@ hipError_t run_fused(const Problem& p, const FusedPlan& f, const uint16_t* Q, co
   fused_token_kernel<E, DP, kAgg, 2><<<tgrid2, dim3(kThreads), token_lds, st>>>(tk);
   ag.X = K, ag.Y = V, ag.M2 = dVAe, ag.rs1 = lse1, ag.rs2 = D1, ag.P1 = part1, ag.sc = sc1;
   ag.chunk = f.chunk[1], ag.S = f.S[1];
-  fused_agent_kernel<E, DP, kAgg><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
+  if (f.agent_cols == 2)
+    fused_agent_kernel<E, DP, kAgg, DP <= 64 ? 2 : 1><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
+  else
+    fused_agent_kernel<E, DP, kAgg, 1><<<agrid, dim3(kThreads), agent_lds, st>>>(ag);
   fused_reduce_agg_kernel<E><<<rgrid, dim3(64), 0, st>>>(part1, f.S[1], n, d, dAf, agents_given ? (uint16_t*)dA : nullptr,
                                                          p.scale1);
   // dQ last: the pooling term needs the finished dA
