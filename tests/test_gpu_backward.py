@@ -144,6 +144,17 @@ def test_backward_module_mode(aa, oracle, grid, agrid, d, dtype):
     _run_case(aa, oracle, _wl("module", dtype, grid, agrid, d), module=True)
 
 
+@pytest.mark.parametrize("agrid,dtype,batch,heads", [((6, 5), "f32", 2, 1), ((6, 5), "bf16", 2, 1),
+                                                     ((16, 16), "f16", 1, 2)])
+def test_backward_module_mode_many_tokens(aa, oracle, agrid, dtype, batch, heads):
+    """Module terms on a 132 x 128 token grid: an agent's row of score gradients takes more than 64 KB of LDS in
+    the kernel that sums the bias components (opt-in path), with a batch to add up first (and, for fp32, rows that
+    start off the 16-byte grid); with 256 agents a head's broadcast score gradients exceed the size up to which
+    that kernel gathers them, so its three components take the one-pass-per-component kernels."""
+    _run_case(aa, oracle, _wl("many_tokens", dtype, (132, 128), agrid, 16, batch=batch, heads=heads, index=33),
+              module=True, blk=(4, 3))
+
+
 def test_backward_module_given_agents_and_residual(aa, oracle):
     wl = _wl("module-given", "f32", (8, 8), (2, 8), 24)
     _run_case(aa, oracle, wl, given=True, module=True, kw=dict(v_residual_k=0.075, scale2=24 ** -0.15))
