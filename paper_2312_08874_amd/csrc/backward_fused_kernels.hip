@@ -6,11 +6,11 @@
 //   broadcast     S2 = c2 Q A^T (N x n), P2 = softmax over agents,  O   = P2 V_A
 // and the gradient of a softmax attention needs, per score, only  P  and  dS = P o (dP - D)  with D the row sum
 // of P o dP.  For the aggregation D1 = rowsum(dV_A o V_A); for the broadcast D2 is taken with the row's scores.
-// A gradient that is a sum over agents (per token: dQ, dK, dV) is built by a kernel whose waves own 16 tokens
-// and walk over all agents, staged through LDS ("token kernel", tiles agents x tokens); a gradient that is a sum over
-// tokens (per agent: V_A itself, dV_A, dA) by a kernel whose waves own 16 agents and walk over a range of tokens
-// streamed through LDS ("agent kernel", tiles tokens x agents), the ranges' partial sums being added in a
-// fixed order afterwards.  In both the 16 x 16 accumulator tile of a score product already has the lane layout
+// A gradient that is a sum over agents (per token: dQ, dK, dV) is built by a kernel whose waves own a few 16-token
+// columns and walk over all agents, staged through LDS ("token kernel", tiles agents x tokens); a gradient that is
+// a sum over tokens (per agent: V_A itself, dV_A, dA) by a kernel whose waves own one or two 16-agent columns and
+// walk over a range of tokens streamed through LDS ("agent kernel", tiles tokens x agents), the ranges' partial
+// sums being added in a fixed order afterwards.  In both the 16 x 16 accumulator tile of a score product already has the lane layout
 // of an MFMA operand whose contraction index runs over the tile's rows, so P and dS go from one product into
 // the next without leaving the registers; the other operand is read from LDS with the transpose read.
 //
