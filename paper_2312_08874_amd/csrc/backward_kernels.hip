@@ -617,10 +617,22 @@ __global__ __launch_bounds__(64) void bias_grad_kernel(const float* __restrict__
   float acc = 0.0f;
   for (int bt = 0; bt < batch; ++bt) {
     const int u = bt * heads + hd;
-    if (which == 0) {
-      for (int y = 0; y < gh; ++y) acc += ds_at<KIND>(dS, u, a, y * gw + p, n, N);
+    if (which == 0) {      // four loads in flight, added in index order
+      int y = 0;
+      for (; y + 4 <= gh; y += 4) {
+        const float v0 = ds_at<KIND>(dS, u, a, y * gw + p, n, N), v1 = ds_at<KIND>(dS, u, a, (y + 1) * gw + p, n, N),
+                    v2 = ds_at<KIND>(dS, u, a, (y + 2) * gw + p, n, N), v3 = ds_at<KIND>(dS, u, a, (y + 3) * gw + p, n, N);
+        acc = (((acc + v0) + v1) + v2) + v3;
+      }
+      for (; y < gh; ++y) acc += ds_at<KIND>(dS, u, a, y * gw + p, n, N);
     } else if (which == 1) {
-      for (int x = 0; x < gw; ++x) acc += ds_at<KIND>(dS, u, a, p * gw + x, n, N);
+      int x = 0;
+      for (; x + 4 <= gw; x += 4) {
+        const float v0 = ds_at<KIND>(dS, u, a, p * gw + x, n, N), v1 = ds_at<KIND>(dS, u, a, p * gw + x + 1, n, N),
+                    v2 = ds_at<KIND>(dS, u, a, p * gw + x + 2, n, N), v3 = ds_at<KIND>(dS, u, a, p * gw + x + 3, n, N);
+        acc = (((acc + v0) + v1) + v2) + v3;
+      }
+      for (; x < gw; ++x) acc += ds_at<KIND>(dS, u, a, p * gw + x, n, N);
     } else {
       for (int y = 0; y < gh; ++y) {
         int y0, y1;
