@@ -215,6 +215,21 @@ def test_binding_has_no_fallback():
     assert "oracle" not in src.replace("no CPU or eager fallback", "")
 
 
+def test_bwd_workspace_of_the_largest_workload():
+    """The recomputing backward keeps no attention matrix: for the 16384-token, 1024-agent workload its workspace
+    stays below 200 MB, where the path that a module term selects needs the two n x N matrices several times over."""
+    L = binding.lib()
+    desc = make_desc(1, 8, 16384, 1024, 64, binding.AA_BF16, (128, 128), (32, 32))
+    pure = L.agent_attn_bwd_workspace_bytes(ctypes.byref(desc), None)
+    p = aa_params()
+    p.b1_col = 1 << 42
+    with_bias = L.agent_attn_bwd_workspace_bytes(ctypes.byref(desc), ctypes.byref(p))
+    assert 0 < pure < 200e6 and with_bias > 2e9
+    # fp32 problems take the other path as well
+    assert L.agent_attn_bwd_workspace_bytes(ctypes.byref(make_desc(1, 8, 16384, 1024, 64, binding.AA_F32, (128, 128),
+                                                                   (32, 32))), None) > 2e9
+
+
 def test_bwd_rejects_bad_arguments():
     """agent_attn_bwd validates on the host before anything is launched."""
     L = binding.lib()
