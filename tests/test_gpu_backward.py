@@ -66,9 +66,9 @@ def _check_param(got, ref, dtype, what, floor=0.0):
     assert rel <= {"f32": 1e-4, "f16": 5e-3, "bf16": 1e-2}[dtype], "%s: rel_l2 %.3e" % (what, rel)
 
 
-def _run_case(aa, oracle, wl, *, given=False, module=False, blk=(3, 2), kw=None):
+def _run_case(aa, oracle, wl, *, given=False, module=False, blk=(3, 2), kw=None, scale_qk=1.0):
     kw = kw or {}
-    t = inputs.make_qkv(wl)
+    t = inputs.make_qkv(wl, scale_qk=scale_qk)
     dO = inputs.make_tensor((wl.units, wl.N, wl.d), stream=wl.index * 16 + 12, dtype=wl.dtype)
     shape = (wl.batch, wl.heads, wl.N, wl.d)
     dv = {k: util.to_device(v, wl.dtype, shape) for k, v in t.items()}
@@ -184,6 +184,15 @@ def test_backward_many_agents_ragged(aa, oracle, grid, agrid, d, dtype, given):
     (128) with a ragged last chunk and a ragged last block of agents, token counts that end inside a tile
     and are cut into several ranges, head widths 16 .. 128, pooled (ragged windows) and given agents."""
     _run_case(aa, oracle, _wl("ragged", dtype, grid, agrid, d, batch=1, heads=2, index=29), given=given)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("scale_qk,given", [(4.0, True), (4.0, False), (8.0, True)])
+def test_backward_peaky_softmaxes(aa, oracle, scale_qk, given, dtype):
+    """Q and K four and eight times larger: both softmaxes close to one-hot, weights spread over many orders of
+    magnitude, score gradients dominated by a few pairs.  Same bars."""
+    _run_case(aa, oracle, _wl("peaky", dtype, (20, 18), (6, 5), 32, batch=1, heads=2, index=37), given=given,
+              scale_qk=scale_qk)
 
 
 @pytest.mark.parametrize("grid,agrid,d", [((12, 12), (4, 4), 32), ((40, 40), (12, 12), 64)])
