@@ -264,6 +264,45 @@ def test_backward_random_problems(aa, oracle, seed):
               blk=(int(rng.integers(1, 6)), int(rng.integers(1, 6))), kw=kw)
 
 
+@pytest.mark.parametrize("module", [False, True])
+def test_backward_replayed_from_a_graph(aa, module):
+    """The backward pass allocates nothing and clears nothing with memsets: captured once, every replay gives the
+    bits of the eager call on the inputs of the moment (pure: the recomputing kernels; module terms: the kernels
+    that keep the matrices in memory, with their parameter gradients)."""
+    import ctypes
+    import torch
+    wl = _wl("graph", "bf16", (24, 20), (6, 5), 32, batch=2, heads=2, index=41)
+    shape = (wl.batch, wl.heads, wl.N, wl.d)
+    t = [util.to_device(inputs.make_tensor((wl.units, wl.N, wl.d), stream=900 + i, dtype=wl.dtype), wl.dtype, shape)
+         for i in range(4)]
+    params = util.params_to_device(inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, blk=(3, 2), index=wl.index)) \
+        if module else None
+    kw = dict(grid=wl.grid, agent_grid=wl.agent_grid, params=params)
+    desc = aa.make_desc(wl.batch, wl.heads, wl.N, wl.n, wl.d, 2, wl.grid, wl.agent_grid)
+    need = int(aa.lib().agent_attn_bwd_workspace_bytes(ctypes.byref(desc), aa._pp(aa.make_params(params))))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        aa.agent_attn_bwd(*t, workspace=ws, stream=side, **kw)      # first call outside the capture (one-time set-up)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            got = aa.agent_attn_bwd(*t, workspace=ws, stream=side, **kw)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for x in t:
+            x.copy_(torch.roll(x, shifts=rep + 1, dims=2))
+        ws.fill_(rep)
+        for v in got.values():
+            v.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = aa.agent_attn_bwd(*t, **kw)
+        for k in eager:
+            assert torch.equal(got[k], eager[k]), "replay %d: %s differs from the eager call" % (rep, k)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("layout", ["token_major", "fused_qkv"])
 def test_backward_strided_layouts(aa, dtype, layout):
