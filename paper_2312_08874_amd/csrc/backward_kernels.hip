@@ -523,6 +523,7 @@ __global__ __launch_bounds__(256) void dwc_param_partial_kernel(const float* __r
 #pragma unroll
     for (int k = 0; k < 10; ++k) acc[k] = 0.0f;
     if (c < d) {
+#pragma unroll 4
       for (int j = j0 + tl; j < j1; j += TL) {
         const int bt = j / N, t = j - bt * N, y = t / gw, x = t - y * gw;
         const size_t base = ((size_t)bt * heads + hd) * N;
@@ -579,7 +580,15 @@ __global__ __launch_bounds__(256) void batch_sum_kernel(const float* __restrict_
   const int hd = blockIdx.y;
   if (i >= per_unit) return;
   float acc = 0.0f;
-  for (int bt = 0; bt < batch; ++bt) acc += src[((size_t)bt * heads + hd) * per_unit + i];
+  int bt = 0;
+  for (; bt + 8 <= batch; bt += 8) {      // eight loads in flight, added in batch order
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = src[((size_t)(bt + k) * heads + hd) * per_unit + i];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc += v[k];
+  }
+  for (; bt < batch; ++bt) acc += src[((size_t)bt * heads + hd) * per_unit + i];
   dst[(size_t)hd * per_unit + i] = acc;
 }
 
