@@ -78,6 +78,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError("HIP library %s not built; run `python -c 'import __graft_entry__ as g; g.build()'`"
                               % LIB_PATH)
+        # torch ships a HIP runtime of its own: with torch loaded first the library binds to that instance, the one
+        # whose allocator hands out the tensors.  Loaded the other way round the process holds two runtimes, and
+        # pointers of one mean nothing to the other (every launch fails with AA_ERR_HIP).
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, dp, pp = ctypes.c_void_p, ctypes.POINTER(aa_desc), ctypes.POINTER(aa_params)
         L.agent_attn_workspace_bytes.restype = ctypes.c_size_t

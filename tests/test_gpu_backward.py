@@ -2,8 +2,8 @@
 gradients on the same seeded inputs.
 
 Bar, per gradient tensor g with reference r: fp32 path max-abs <= 1e-4 * max(1, max|r|); fp16 / bf16
-paths max-abs <= 1e-2 * max(1, max|r|) and relative L2 <= 5e-3, except bf16 problems with module terms:
-1e-2 (they run the kernels that keep the attention matrices in memory, where the probabilities and the
+paths max-abs <= 1e-2 * max(1, max|r|) and relative L2 <= 5e-3, except bf16 problems with module terms or
+the enlarged second scale of Appendix C.1 (see _check): 1e-2 (the former run the kernels that keep the attention matrices in memory, where the probabilities and the
 score gradients are stored in bf16 before the products that give dQ, dK, dV, so a gradient chains three
 operands of relative error up to 2^-9; five unit roundoffs, as for the parameter gradients below; a near
 one-hot broadcast softmax - the SD variant's scale d^-0.15 together with a bias - reaches 7e-3).  Pure
@@ -49,8 +49,12 @@ def _stored(t, dtype, shape):
 
 
 def _check(got, ref, dtype, what, pure=False):
-    """pure: a problem without module terms, served by the kernels that keep P and dS in fp32 up to the one
-    rounding that makes them matrix operands: the bf16 bar is the forward's 5e-3 there."""
+    """pure: a problem without module terms and with the default scales, served by the kernels that keep P and dS
+    in fp32 up to the one rounding that makes them matrix operands: the bf16 bar is the forward's 5e-3 there.
+    With the enlarged second scale of Appendix C.1 (d^-0.15 instead of d^-0.5: scores four times larger at d = 64)
+    the broadcast softmax is peaked, dS2 = P2 o (dP2 - D2) is a small difference of larger terms, and the 2^-9
+    rounding of the bf16 operands behind dP2 (V_A) shows: dQ reaches 7.4e-3 on seeded random problems (two-term
+    dS2 operands did not move it), so those keep the 1e-2 of the problems with module terms."""
     scale = max(1.0, float(np.abs(ref).max()))
     util.assert_parity(util.to_host64(got).reshape(ref.shape), ref, dtype, what,
                        max_abs=util.TOL[dtype]["max_abs"] * scale,
@@ -102,7 +106,7 @@ def _run_case(aa, oracle, wl, *, given=False, module=False, blk=(3, 2), kw=None,
         ref["dQ"] = ref["dQ"] + oracle.pool_bwd(ref.pop("dA"), *wl.grid, *wl.agent_grid)
     for k in ("dQ", "dK", "dV") + (("dA",) if given else ()):
         _check(got[k], ref[k], wl.dtype, "%s %s" % (wl.name, k),
-               pure=not module and wl.d % 8 == 0 and wl.d <= 128)
+               pure=not module and not kw.get("scale2") and wl.d % 8 == 0 and wl.d <= 128)
     if module:
         h0, w0 = blk
         gh, gw = wl.grid
