@@ -53,8 +53,10 @@ def _check(got, ref, dtype, what, pure=False):
     in fp32 up to the one rounding that makes them matrix operands: the bf16 bar is the forward's 5e-3 there.
     With the enlarged second scale of Appendix C.1 (d^-0.15 instead of d^-0.5: scores four times larger at d = 64)
     the broadcast softmax is peaked, dS2 = P2 o (dP2 - D2) is a small difference of larger terms, and the 2^-9
-    rounding of the bf16 operands behind dP2 (V_A) shows: dQ reaches 7.4e-3 on seeded random problems (two-term
-    dS2 operands did not move it), so those keep the 1e-2 of the problems with module terms."""
+    roundings behind dP2 = dO V_A^T show (V_A as an operand, P1 as the operand of the product that gives V_A:
+    6e-3 .. 7e-3 each in an fp64 emulation with one rounding switched on at a time): dQ reaches 7.4e-3 on seeded
+    random problems (two-term dS2 operands did not move it), so those keep the 1e-2 of the problems with module
+    terms."""
     scale = max(1.0, float(np.abs(ref).max()))
     util.assert_parity(util.to_host64(got).reshape(ref.shape), ref, dtype, what,
                        max_abs=util.TOL[dtype]["max_abs"] * scale,
