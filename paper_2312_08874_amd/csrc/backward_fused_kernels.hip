@@ -729,8 +729,9 @@ FusedPlan fused_plan(const Problem& p) {
     f.chunk[k] = ((p.N + S - 1) / S + 31) / 32 * 32;
     f.S[k] = (p.N + f.chunk[k] - 1) / f.chunk[k];
   }
-  // four token columns per wave in the broadcast's token kernels when that still leaves two blocks per CU
-  f.wide = f.DP <= 64 && (long long)((p.N + 255) / 256) * p.units >= 2 * kComputeUnits;
+  // four token columns per wave in the broadcast's token kernels when the unit has more than one 64-agent chunk to
+  // reuse them on and that still leaves two blocks per CU
+  f.wide = f.DP <= 64 && p.n > 64 && (long long)((p.N + 255) / 256) * p.units >= 2 * kComputeUnits;
   const size_t u = (size_t)p.units, nd = up64((size_t)p.n * p.d), un = up64(u * p.n), uN = up64(u * p.N);
   size_t o = 0;
   f.VAf = o, o += u * nd;
