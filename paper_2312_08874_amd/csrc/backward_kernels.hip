@@ -338,6 +338,11 @@ __global__ __launch_bounds__(256, 2) void mfma_matmul_pair_kernel(MatmulArgs m0,
 }
 
 constexpr int kRowCache = 16;      // row elements a lane keeps in registers in the row kernels
+// dynamic LDS of softmax_rows16_bias1_kernel
+size_t bias1_row_lds(const Problem& p) {
+  const int h0 = p.b1.blk ? p.b1.h0 : 0;
+  return ((size_t)p.gw + p.gh + (size_t)h0 * p.gw + 3 * (size_t)p.gh) * sizeof(float);
+}
 
 // reductions over groups of LPR consecutive lanes (LPR a power of two)
 template <int LPR>
@@ -431,6 +436,76 @@ __global__ __launch_bounds__(64) void softmax_rows16_kernel(const float* __restr
   const float inv = 1.0f / sum;
   if (live)
     for (int j = lane; j < ld; j += LPR) prow[j] = j < cols ? Half<E>::from_f32(__expf(score(j) - gmx) * inv) : (uint16_t)0;
+}
+
+// The same for the aggregation's rows (one wave per agent row) when there is an agent bias and the row is long:
+// the agent's bias is laid out in LDS first -- its column and row components, the block component interpolated
+// along x (h0 rows of gw values), the y interpolation of every token row -- so that a score costs three LDS reads
+// and an interpolation instead of six global reads and two coordinate computations, twice per score.  The
+// arithmetic of a bias value is that of bias1_at, term by term.  Dynamic LDS: gw + gh + h0 * gw + 3 * gh floats.
+template <class E>
+__global__ __launch_bounds__(64) void softmax_rows16_bias1_kernel(const float* __restrict__ S, uint16_t* __restrict__ P,
+                                                                  int rows, int ld, BiasArgs b, int heads, int gh, int gw) {
+  extern __shared__ float sm[];
+  float* colv = sm;                     // [gw]
+  float* rowv = colv + gw;              // [gh]
+  float* U = rowv + gh;                 // [h0][gw]
+  const int h0 = b.blk ? b.h0 : 0, w0 = b.w0;
+  float* fyv = U + h0 * gw;             // [gh]
+  int* y0v = reinterpret_cast<int*>(fyv + gh);      // [gh]
+  int* y1v = y0v + gh;                  // [gh]
+  const int r = blockIdx.x, u = blockIdx.y, lane = threadIdx.x, hd = u % heads, n = rows;
+  const float* row = S + ((size_t)u * rows + r) * ld;
+  uint16_t* prow = P + ((size_t)u * rows + r) * ld;
+  const size_t ra = (size_t)hd * n + r;
+  for (int x = lane; x < gw; x += 64) colv[x] = b.col ? b.col[ra * gw + x] : 0.0f;
+  for (int y = lane; y < gh; y += 64) {
+    rowv[y] = b.row ? b.row[ra * gh + y] : 0.0f;
+    int y0 = 0, y1 = 0;
+    float fy = 0.0f;
+    if (b.blk) bilinear_coord(y, gh, h0, y0, y1, fy);
+    y0v[y] = y0, y1v[y] = y1, fyv[y] = fy;
+  }
+  if (b.blk) {
+    const float* cells = b.blk + ra * h0 * w0;
+    for (int i = lane; i < h0 * gw; i += 64) {
+      const int p = i / gw, x = i - p * gw;
+      int x0, x1;
+      float fx;
+      bilinear_coord(x, gw, w0, x0, x1, fx);
+      const float v0 = cells[p * w0 + x0], v1 = cells[p * w0 + x1];
+      U[i] = v0 + (v1 - v0) * fx;
+    }
+  }
+  __syncthreads();
+  auto score = [&](int y, int x) -> float {
+    float v = 0.0f;
+    if (b.col) v += colv[x];
+    if (b.row) v += rowv[y];
+    if (b.blk) {
+      const float top = U[y0v[y] * gw + x], bot = U[y1v[y] * gw + x];
+      v += top + (bot - top) * fyv[y];
+    }
+    return row[y * gw + x] + v;
+  };
+  // one pass for the maximum and the sum together (running maximum per lane, rescaled sum), a second to write
+  float mx = -INFINITY, sum = 0.0f;
+  for (int y = 0; y < gh; ++y)
+    for (int x = lane; x < gw; x += 64) {
+      const float v = score(y, x);
+      if (v > mx) {
+        sum = sum * __expf(mx - v) + 1.0f;      // exp(-inf) = 0 on the first element
+        mx = v;
+      } else {
+        sum += __expf(v - mx);
+      }
+    }
+  const float gmx = group_max<64>(mx);
+  sum = group_sum<64>(mx == -INFINITY ? 0.0f : sum * __expf(mx - gmx));
+  const float inv = 1.0f / sum;
+  for (int y = 0; y < gh; ++y)
+    for (int x = lane; x < gw; x += 64) prow[y * gw + x] = Half<E>::from_f32(__expf(score(y, x) - gmx) * inv);
+  for (int j = gh * gw + lane; j < ld; j += 64) prow[j] = (uint16_t)0;      // the padding columns
 }
 
 // dS = P o (dP - rowsum(P o dP)) with P in the element type, dP fp32, dS rounded to the element type
@@ -1030,6 +1105,8 @@ hipError_t launch_backward_mfma(const Problem& p, const void* Q, const void* K, 
   auto rows_grid = [&](int rows, int lpr) { return dim3((unsigned)(((size_t)rows * lpr + 63) / 64), U); };
   if (N <= 64)
     softmax_rows16_kernel<E, 1, 16><<<rows_grid(n, 16), dim3(64), 0, st>>>(F1, P1h, n, N, ldN, p.b1, p.heads, n, p.gh, p.gw);
+  else if (p.b1.any() && N > 64 * kRowCache && bias1_row_lds(p) <= 64 * 1024)      // rows too long for registers
+    softmax_rows16_bias1_kernel<E><<<dim3(n, U), dim3(64), bias1_row_lds(p), st>>>(F1, P1h, n, ldN, p.b1, p.heads, p.gh, p.gw);
   else
     softmax_rows16_kernel<E, 1, 64><<<rows_grid(n, 64), dim3(64), 0, st>>>(F1, P1h, n, N, ldN, p.b1, p.heads, n, p.gh, p.gw);
   AA_BWD_CHECK((mfma_matmul<E, false, false, 2>(P1h, Vh, VAh, n, d, N, ldN, d, d, s1, Nd, nd, U, 1.0f, st, dKf, u * Nd)));
