@@ -441,6 +441,35 @@ def test_large_agent_kernels_growing_maxima(aa, oracle, kind, dtype, d, units, g
                        max_abs=1e-2 * max(1.0, float(np.abs(ref).max())))
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f16", 40)])
+@pytest.mark.parametrize("step", [0.25, 8.0, 40.0], ids=["inside the slack", "around the slack", "past the slack"])
+def test_large_broadcast_module_mode_rising_agent_chunks(aa, oracle, step, dtype, d):
+    """The broadcast kernel of the paths with module terms walks the agents in chunks of 128 and moves the
+    reference of its running softmax only when a chunk's largest score passes it by more than 2^8.  Agents
+    handed in whose size grows from chunk to chunk by a small, a middling and a large step take both sides of
+    that test (weights above 1 kept as they are; reference raised and the accumulators rescaled)."""
+    import dataclasses
+    wl = dataclasses.replace(WL["sd_latent"], batch=1, heads=2, grid=(40, 32), agent_grid=(16, 32), d=d, dtype=dtype,
+                             index=15)
+    t = inputs.make_qkv(wl)
+    f = {k: inputs.to_float64(v, dtype) for k, v in t.items()}
+    pooled = oracle.pool(f["Q"], *wl.grid, *wl.agent_grid)
+    pooled = pooled / np.linalg.norm(pooled, axis=-1, keepdims=True)
+    qn = float(np.linalg.norm(f["Q"], axis=-1).mean())
+    # the largest base-2 exponent a token sees in chunk c is about 0.4 * (1 + step * c); over the first chunk's
+    # it rises by at most 1.2, by 3 to 10 at the median (up to 24), and by 14 to 50 at the median for the three steps
+    grow = (1.0 + step * (np.arange(wl.n) // 128)) * np.sqrt(d) / (qn * np.log2(np.e))
+    A_st = inputs.to_storage(pooled * grow[None, :, None], dtype)
+    full = inputs.make_module_params(wl.heads, wl.n, wl.d, wl.grid, blk=(5, 4), index=wl.index)
+    params = {k: full[k] for k in ("b2_col", "b2_row", "b2_blk", "dwc_w", "dwc_b")}
+    dv = dev_qkv(wl, t)
+    O = aa.agent_attn_fwd(dv["Q"], dv["K"], dv["V"], util.to_device(A_st, dtype, (wl.batch, wl.heads, wl.n, d)),
+                          grid=wl.grid, params=util.params_to_device(params))
+    ref = util.oracle_forward_units(oracle, wl, t, list(range(wl.units)), params=params, A=A_st)
+    util.assert_parity(util.to_host64(O).reshape(ref.shape), ref, dtype, "module broadcast, step %g" % step,
+                       max_abs=1e-2 * max(1.0, float(np.abs(ref).max())))
+
+
 @pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f16", 40), ("f16", 24)])
 def test_large_broadcast_two_blocks_per_cu_ragged(aa, oracle, dtype, d):
     """The broadcast build that shares a CU between two blocks (more 256-token blocks than CUs: 36 units x 8) on a
